@@ -1,0 +1,492 @@
+/*
+ * CPU oracle for the cached embedding-bag training path.  TEST INFRASTRUCTURE ONLY:
+ * it exists to check the HIP library and to be timed as the CPU baseline; nothing on
+ * the product path may call it, and it shares no code with the HIP sources.
+ *
+ * What it computes (paper sections in brackets):
+ *   - pooled lookup: for every (table, sample) bag, the sum of the looked-up rows
+ *     [Section 2.1.1, "embedding table operators ... pool the result using sum"];
+ *   - sparse backward with row-wise Adagrad: every distinct row of a batch receives the
+ *     sum of the output gradients of the bags that looked it up (once per lookup), one
+ *     accumulator per row [Section 2.1.2: optimizers with few states per row, Adagrad;
+ *     Section 5.9: the GPU aggregates, runs the optimizer and updates the weights in the
+ *     memory they live in during backward];
+ *   - a one-level software cache of raw rows with tags and per-entry timestamps
+ *     [Section 5.3.1], managed per batch in the order the paper lists [Section 5.5.2]:
+ *     1) stamp the hits, 2) choose slots for the misses, 3) evict when no slot is free;
+ *     a missed row is inserted into the cache from the lower tier and the least recently
+ *     used row is written back to it [Section 5.5.4]; rows fetched for a batch stay in
+ *     the cache until that batch has trained [Section 5.7].
+ *
+ * Readings where the paper is silent (the HIP path follows the same ones):
+ *   - organisation: each table has its own W-way set-associative cache, set(r) = r mod S;
+ *   - time = batch id k = 1, 2, ... given at prefetch; free entries carry timestamp -1;
+ *   - inside one batch the distinct rows of a table are handled in two phases: all hits
+ *     are stamped k first, then the misses in ascending row order; the victim of a miss
+ *     is the way with the smallest timestamp < k, the lowest way among equals;
+ *   - when every way of the set already carries timestamp k the row is not inserted
+ *     ("bypass"): it is read from and updated in the lower tier directly;
+ *   - every evicted row is written back (rows are trained on after insertion, so all
+ *     lines are dirty); flush writes back every valid line and keeps the tags;
+ *   - row-wise Adagrad: m += mean_d(g_d^2); w_d -= lr * g_d / (sqrt(m) + eps), m starts
+ *     wherever the caller's state array starts (0 in the tests), eps outside the root;
+ *   - fp16 storage: rows are widened exactly, results are rounded to nearest even.
+ * All floating-point work is done in fp64 from the stored values and rounded once when
+ * stored (fp32 state, fp32 or fp16 weights, fp32 pooled output).
+ *
+ * Plain C, no blocking or fusion: each function is the definition written out.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_OK 0
+#define ORC_EINVAL (-1)
+#define ORC_ERANGE (-2)
+#define ORC_EORDER (-3)
+#define ORC_ENOMEM (-4)
+
+typedef struct {
+  int64_t rows;        /* H_t */
+  int32_t dim;         /* D_t */
+  int32_t dtype;       /* 0 = fp32, 1 = fp16 storage */
+  void *weights;       /* caller-owned backing tier [rows, dim] */
+  float *state;        /* caller-owned backing tier accumulator [rows] */
+  int64_t cache_slots; /* S_t = cache_slots / ways (floor) */
+} orc_table_spec;
+
+typedef struct {
+  int64_t lookups, uniques, hits, inserts, bypasses, evictions, hit_lookups;
+} orc_stats;
+
+typedef struct {
+  int64_t rows;
+  int32_t dim, dtype;
+  void *weights;
+  float *state;
+  int64_t sets;
+  int64_t *tag;     /* [sets*ways], -1 = free */
+  int32_t *ts;      /* [sets*ways], -1 = free */
+  void *lines;      /* [sets*ways, dim] in the storage type */
+  float *line_state;/* [sets*ways] */
+  /* last prefetched batch */
+  int64_t n_uniq;
+  int64_t *uniq;    /* sorted distinct rows */
+  int64_t *mult;    /* lookups per distinct row */
+  /* events of the last prefetch */
+  int64_t n_hit, n_ins, n_byp;
+  int64_t *hit_row;
+  int64_t *ins_row, *ins_slot, *ins_old;
+  int64_t *byp_row;
+  int64_t cap;
+  orc_stats st;
+} orc_table;
+
+typedef struct {
+  int32_t T, ways;
+  orc_table *tab;
+  int32_t k;           /* batch id of the last prefetch */
+  int32_t B;
+  int64_t N;
+  int64_t *indices;
+  int64_t *offsets;
+  int64_t cap_idx, cap_off;
+  int forwarded, prefetched;
+  int threads;
+  orc_stats last, total;
+} orc;
+
+/* ---------------- fp16 <-> fp64 ---------------- */
+
+static double half_to_double(uint16_t h) {
+  int s = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+  double v;
+  if (e == 0) v = ldexp((double)m, -24);
+  else if (e == 31) v = m ? NAN : INFINITY;
+  else v = ldexp((double)(m | 1024), e - 25);
+  return s ? -v : v;
+}
+
+/* round to nearest, ties to even, straight from fp64 (no intermediate fp32) */
+static uint16_t double_to_half(double x) {
+  uint64_t b;
+  memcpy(&b, &x, 8);
+  uint16_t sign = (uint16_t)((b >> 48) & 0x8000u);
+  int64_t e = (int64_t)((b >> 52) & 0x7ff);
+  uint64_t m = b & ((1ull << 52) - 1);
+  if (e == 0x7ff) return (uint16_t)(sign | 0x7c00u | (m ? 0x200u : 0));
+  if (e == 0) return sign;
+  int64_t he = e - 1023 + 15;
+  if (he >= 31) return (uint16_t)(sign | 0x7c00u);
+  if (he >= 1) {
+    uint32_t r = (uint32_t)((he << 10) | (int64_t)(m >> 42));
+    uint64_t rem = m & ((1ull << 42) - 1), half = 1ull << 41;
+    if (rem > half || (rem == half && (r & 1))) r++;
+    return (uint16_t)(sign | r);
+  }
+  uint64_t M = m | (1ull << 52);
+  int64_t shift = 1051 - e; /* result in units of 2^-24 */
+  if (shift >= 64) return sign;
+  uint64_t q = M >> shift, rem = M & ((1ull << shift) - 1), half = 1ull << (shift - 1);
+  if (rem > half || (rem == half && (q & 1))) q++;
+  return (uint16_t)(sign | (uint16_t)q);
+}
+
+uint16_t orc_double_to_half(double x) { return double_to_half(x); }
+double orc_half_to_double(uint16_t h) { return half_to_double(h); }
+
+static double load_elem(const void *base, int dtype, int64_t i) {
+  return dtype == 0 ? (double)((const float *)base)[i] : half_to_double(((const uint16_t *)base)[i]);
+}
+static void store_elem(void *base, int dtype, int64_t i, double v) {
+  if (dtype == 0) ((float *)base)[i] = (float)v;
+  else ((uint16_t *)base)[i] = double_to_half(v);
+}
+static size_t esize(int dtype) { return dtype == 0 ? 4 : 2; }
+
+/* ---------------- life cycle ---------------- */
+
+static void free_table(orc_table *t) {
+  free(t->tag); free(t->ts); free(t->lines); free(t->line_state);
+  free(t->uniq); free(t->mult); free(t->hit_row); free(t->ins_row);
+  free(t->ins_slot); free(t->ins_old); free(t->byp_row);
+}
+
+void orc_destroy(void *hp) {
+  orc *h = (orc *)hp;
+  if (!h) return;
+  for (int t = 0; t < h->T; t++) free_table(&h->tab[t]);
+  free(h->tab); free(h->indices); free(h->offsets); free(h);
+}
+
+void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
+  if (!specs || T <= 0 || ways <= 0) return NULL;
+  orc *h = (orc *)calloc(1, sizeof(orc));
+  if (!h) return NULL;
+  h->T = T; h->ways = ways; h->threads = 1;
+  h->tab = (orc_table *)calloc((size_t)T, sizeof(orc_table));
+  for (int t = 0; t < T; t++) {
+    orc_table *tb = &h->tab[t];
+    const orc_table_spec *s = &specs[t];
+    if (s->rows <= 0 || s->dim <= 0 || (s->dtype != 0 && s->dtype != 1) || !s->weights || !s->state ||
+        s->cache_slots < 0) { orc_destroy(h); return NULL; }
+    tb->rows = s->rows; tb->dim = s->dim; tb->dtype = s->dtype;
+    tb->weights = s->weights; tb->state = s->state;
+    tb->sets = s->cache_slots / ways;
+    int64_t slots = tb->sets * ways;
+    if (slots > 0) {
+      tb->tag = (int64_t *)malloc(sizeof(int64_t) * (size_t)slots);
+      tb->ts = (int32_t *)malloc(sizeof(int32_t) * (size_t)slots);
+      tb->lines = calloc((size_t)slots * (size_t)s->dim, esize(s->dtype));
+      tb->line_state = (float *)calloc((size_t)slots, sizeof(float));
+      if (!tb->tag || !tb->ts || !tb->lines || !tb->line_state) { orc_destroy(h); return NULL; }
+      for (int64_t i = 0; i < slots; i++) { tb->tag[i] = -1; tb->ts[i] = -1; }
+    }
+  }
+  return h;
+}
+
+void orc_set_threads(void *hp, int n) { ((orc *)hp)->threads = n > 0 ? n : 1; }
+
+/* ---------------- cache primitives ---------------- */
+
+/* slot of row r in table tb's cache, or -1 when it is not cached */
+static int64_t find_slot(const orc_table *tb, int ways, int64_t r) {
+  if (tb->sets == 0) return -1;
+  int64_t s = r % tb->sets;
+  for (int w = 0; w < ways; w++)
+    if (tb->tag[s * ways + w] == r) return s * ways + w;
+  return -1;
+}
+
+static void line_to_backing(orc_table *tb, int64_t slot, int64_t r) {
+  size_t rb = (size_t)tb->dim * esize(tb->dtype);
+  memcpy((char *)tb->weights + (size_t)r * rb, (char *)tb->lines + (size_t)slot * rb, rb);
+  tb->state[r] = tb->line_state[slot];
+}
+static void backing_to_line(orc_table *tb, int64_t slot, int64_t r) {
+  size_t rb = (size_t)tb->dim * esize(tb->dtype);
+  memcpy((char *)tb->lines + (size_t)slot * rb, (char *)tb->weights + (size_t)r * rb, rb);
+  tb->line_state[slot] = tb->state[r];
+}
+
+static int cmp_i64(const void *a, const void *b) {
+  int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+  return x < y ? -1 : x > y;
+}
+
+static int grow(orc_table *tb, int64_t n) {
+  if (n <= tb->cap) return 0;
+  int64_t c = n + n / 2 + 16;
+  int64_t **ptrs[] = {&tb->uniq, &tb->mult, &tb->hit_row, &tb->ins_row, &tb->ins_slot, &tb->ins_old, &tb->byp_row};
+  for (unsigned i = 0; i < sizeof(ptrs) / sizeof(ptrs[0]); i++) {
+    int64_t *p = (int64_t *)realloc(*ptrs[i], sizeof(int64_t) * (size_t)c);
+    if (!p) return -1;
+    *ptrs[i] = p;
+  }
+  tb->cap = c;
+  return 0;
+}
+
+/* One table, one batch: distinct rows, then the two-phase LRU pass. */
+static int prefetch_table(orc *h, int t) {
+  orc_table *tb = &h->tab[t];
+  const int W = h->ways;
+  const int32_t k = h->k;
+  int64_t lo = h->offsets[(int64_t)t * h->B], hi = h->offsets[(int64_t)(t + 1) * h->B];
+  int64_t n = hi - lo;
+  memset(&tb->st, 0, sizeof(tb->st));
+  tb->n_uniq = tb->n_hit = tb->n_ins = tb->n_byp = 0;
+  tb->st.lookups = n;
+  if (n == 0) return 0;
+  if (grow(tb, n)) return ORC_ENOMEM;
+  /* distinct rows in ascending order with their multiplicities */
+  int64_t *tmp = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+  if (!tmp) return ORC_ENOMEM;
+  memcpy(tmp, h->indices + lo, sizeof(int64_t) * (size_t)n);
+  qsort(tmp, (size_t)n, sizeof(int64_t), cmp_i64);
+  int64_t u = 0;
+  for (int64_t i = 0; i < n; i++) {
+    if (i == 0 || tmp[i] != tmp[i - 1]) { tb->uniq[u] = tmp[i]; tb->mult[u] = 1; u++; }
+    else tb->mult[u - 1]++;
+  }
+  free(tmp);
+  tb->n_uniq = u;
+  tb->st.uniques = u;
+  /* phase 1: hits get the time of access */
+  char *is_hit = (char *)calloc((size_t)u, 1);
+  if (!is_hit) return ORC_ENOMEM;
+  for (int64_t i = 0; i < u; i++) {
+    int64_t slot = find_slot(tb, W, tb->uniq[i]);
+    if (slot >= 0) {
+      tb->ts[slot] = k;
+      is_hit[i] = 1;
+      tb->hit_row[tb->n_hit++] = tb->uniq[i];
+      tb->st.hits++;
+      tb->st.hit_lookups += tb->mult[i];
+    }
+  }
+  /* phase 2: misses in ascending row order pick a slot, evicting if it is occupied */
+  for (int64_t i = 0; i < u; i++) {
+    if (is_hit[i]) continue;
+    int64_t r = tb->uniq[i];
+    int victim = -1;
+    int64_t s = 0;
+    if (tb->sets > 0) {
+      s = r % tb->sets;
+      for (int w = 0; w < W; w++) {
+        int32_t tw = tb->ts[s * W + w];
+        if (tw < k && (victim < 0 || tw < tb->ts[s * W + victim])) victim = w;
+      }
+    }
+    if (victim < 0) {
+      tb->byp_row[tb->n_byp++] = r;
+      tb->st.bypasses++;
+      continue;
+    }
+    int64_t slot = s * W + victim;
+    int64_t old = tb->tag[slot];
+    if (old >= 0) { line_to_backing(tb, slot, old); tb->st.evictions++; }
+    backing_to_line(tb, slot, r);
+    tb->tag[slot] = r;
+    tb->ts[slot] = k;
+    tb->ins_row[tb->n_ins] = r; tb->ins_slot[tb->n_ins] = slot; tb->ins_old[tb->n_ins] = old;
+    tb->n_ins++;
+    tb->st.inserts++;
+  }
+  free(is_hit);
+  return 0;
+}
+
+static void add_stats(orc_stats *a, const orc_stats *b) {
+  a->lookups += b->lookups; a->uniques += b->uniques; a->hits += b->hits; a->inserts += b->inserts;
+  a->bypasses += b->bypasses; a->evictions += b->evictions; a->hit_lookups += b->hit_lookups;
+}
+
+int orc_prefetch(void *hp, const int64_t *indices, const int64_t *offsets, int32_t B, int64_t N) {
+  orc *h = (orc *)hp;
+  if (!h || !offsets || B < 0 || N < 0 || (N > 0 && !indices)) return ORC_EINVAL;
+  int64_t nb = (int64_t)h->T * B;
+  if (offsets[0] != 0 || offsets[nb] != N) return ORC_EINVAL;
+  for (int64_t i = 0; i < nb; i++) if (offsets[i + 1] < offsets[i]) return ORC_EINVAL;
+  for (int t = 0; t < h->T; t++)
+    for (int64_t j = offsets[(int64_t)t * B]; j < offsets[(int64_t)(t + 1) * B]; j++)
+      if (indices[j] < 0 || indices[j] >= h->tab[t].rows) return ORC_ERANGE;
+  if (N > h->cap_idx) { free(h->indices); h->indices = (int64_t *)malloc(sizeof(int64_t) * (size_t)N); h->cap_idx = N; }
+  if (nb + 1 > h->cap_off) { free(h->offsets); h->offsets = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb + 1)); h->cap_off = nb + 1; }
+  if ((N > 0 && !h->indices) || !h->offsets) return ORC_ENOMEM;
+  if (N > 0) memcpy(h->indices, indices, sizeof(int64_t) * (size_t)N);
+  memcpy(h->offsets, offsets, sizeof(int64_t) * (size_t)(nb + 1));
+  h->B = B; h->N = N;
+  h->k += 1;
+  int rc = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(h->threads)
+  for (int t = 0; t < h->T; t++) {
+    int r = prefetch_table(h, t);
+    if (r) {
+#pragma omp critical
+      rc = r;
+    }
+  }
+  if (rc) return rc;
+  memset(&h->last, 0, sizeof(h->last));
+  for (int t = 0; t < h->T; t++) add_stats(&h->last, &h->tab[t].st);
+  add_stats(&h->total, &h->last);
+  h->prefetched = 1; h->forwarded = 0;
+  return ORC_OK;
+}
+
+/* out[b, col_t + d] = sum over the lookups of bag (t, b) of the row, read where it lives */
+int orc_forward(void *hp, float *out) {
+  orc *h = (orc *)hp;
+  if (!h || !out) return ORC_EINVAL;
+  if (!h->prefetched) return ORC_EORDER;
+  int64_t sumD = 0;
+  for (int t = 0; t < h->T; t++) sumD += h->tab[t].dim;
+  int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(h->threads)
+  for (int t = 0; t < h->T; t++) {
+    orc_table *tb = &h->tab[t];
+    int64_t col = 0;
+    for (int q = 0; q < t; q++) col += h->tab[q].dim;
+    double *acc = (double *)malloc(sizeof(double) * (size_t)tb->dim);
+    if (!acc) { failed = 1; continue; }
+    for (int32_t b = 0; b < h->B; b++) {
+      for (int d = 0; d < tb->dim; d++) acc[d] = 0.0;
+      for (int64_t j = h->offsets[(int64_t)t * h->B + b]; j < h->offsets[(int64_t)t * h->B + b + 1]; j++) {
+        int64_t r = h->indices[j];
+        int64_t slot = find_slot(tb, h->ways, r);
+        const void *src = slot >= 0 ? tb->lines : tb->weights;
+        int64_t base = (slot >= 0 ? slot : r) * tb->dim;
+        for (int d = 0; d < tb->dim; d++) acc[d] += load_elem(src, tb->dtype, base + d);
+      }
+      for (int d = 0; d < tb->dim; d++) out[(int64_t)b * sumD + col + d] = (float)acc[d];
+    }
+    free(acc);
+  }
+  if (failed) return ORC_ENOMEM;
+  h->forwarded = 1;
+  return ORC_OK;
+}
+
+static int64_t lower_bound(const int64_t *a, int64_t n, int64_t v) {
+  int64_t lo = 0, hi = n;
+  while (lo < hi) { int64_t mid = (lo + hi) / 2; if (a[mid] < v) lo = mid + 1; else hi = mid; }
+  return lo;
+}
+
+/* g_r = sum over lookups of r of grad_out[bag]; m_r += mean(g^2); w_r -= lr*g/(sqrt(m_r)+eps) */
+int orc_backward_update(void *hp, const float *grad_out, float lr, float eps) {
+  orc *h = (orc *)hp;
+  if (!h || !grad_out) return ORC_EINVAL;
+  if (!h->forwarded) return ORC_EORDER;
+  int64_t sumD = 0;
+  for (int t = 0; t < h->T; t++) sumD += h->tab[t].dim;
+  int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(h->threads)
+  for (int t = 0; t < h->T; t++) {
+    orc_table *tb = &h->tab[t];
+    int64_t col = 0;
+    for (int q = 0; q < t; q++) col += h->tab[q].dim;
+    int64_t U = tb->n_uniq;
+    if (U == 0) continue;
+    double *g = (double *)calloc((size_t)U * (size_t)tb->dim, sizeof(double));
+    if (!g) { failed = 1; continue; }
+    for (int32_t b = 0; b < h->B; b++)
+      for (int64_t j = h->offsets[(int64_t)t * h->B + b]; j < h->offsets[(int64_t)t * h->B + b + 1]; j++) {
+        int64_t u = lower_bound(tb->uniq, U, h->indices[j]);
+        for (int d = 0; d < tb->dim; d++) g[u * tb->dim + d] += (double)grad_out[(int64_t)b * sumD + col + d];
+      }
+    for (int64_t u = 0; u < U; u++) {
+      int64_t r = tb->uniq[u];
+      int64_t slot = find_slot(tb, h->ways, r);
+      void *wbase = slot >= 0 ? tb->lines : tb->weights;
+      float *mptr = slot >= 0 ? &tb->line_state[slot] : &tb->state[r];
+      int64_t base = (slot >= 0 ? slot : r) * tb->dim;
+      double sq = 0.0;
+      for (int d = 0; d < tb->dim; d++) sq += g[u * tb->dim + d] * g[u * tb->dim + d];
+      double m = (double)*mptr + sq / (double)tb->dim;
+      double denom = sqrt(m) + (double)eps;
+      for (int d = 0; d < tb->dim; d++) {
+        double w = load_elem(wbase, tb->dtype, base + d);
+        store_elem(wbase, tb->dtype, base + d, w - (double)lr * g[u * tb->dim + d] / denom);
+      }
+      *mptr = (float)m;
+    }
+    free(g);
+  }
+  if (failed) return ORC_ENOMEM;
+  h->forwarded = 0; h->prefetched = 0;
+  return ORC_OK;
+}
+
+/* every valid line (row and accumulator) goes to the lower tier; tags stay */
+int orc_flush(void *hp) {
+  orc *h = (orc *)hp;
+  if (!h) return ORC_EINVAL;
+  for (int t = 0; t < h->T; t++) {
+    orc_table *tb = &h->tab[t];
+    for (int64_t s = 0; s < tb->sets * h->ways; s++)
+      if (tb->tag[s] >= 0) line_to_backing(tb, s, tb->tag[s]);
+  }
+  return ORC_OK;
+}
+
+/* ---------------- observation ---------------- */
+
+int64_t orc_num_sets(void *hp, int32_t t) { return ((orc *)hp)->tab[t].sets; }
+int32_t orc_batch_id(void *hp) { return ((orc *)hp)->k; }
+
+int orc_export_cache_state(void *hp, int32_t t, int64_t *tags, int32_t *ts) {
+  orc *h = (orc *)hp;
+  if (!h || t < 0 || t >= h->T) return ORC_EINVAL;
+  orc_table *tb = &h->tab[t];
+  int64_t n = tb->sets * h->ways;
+  if (n) { memcpy(tags, tb->tag, sizeof(int64_t) * (size_t)n); memcpy(ts, tb->ts, sizeof(int32_t) * (size_t)n); }
+  return ORC_OK;
+}
+
+int orc_get_stats(void *hp, orc_stats *last, orc_stats *total) {
+  orc *h = (orc *)hp;
+  if (!h) return ORC_EINVAL;
+  if (last) *last = h->last;
+  if (total) *total = h->total;
+  return ORC_OK;
+}
+
+/* events of the last prefetch: kind 0 = hits, 1 = inserts, 2 = bypasses.  With null
+ * arrays returns the count; otherwise fills table[], row[] and, for inserts, slot[]
+ * (table-local, set*ways + way) and old[] (row evicted from it, -1 if it was free). */
+int64_t orc_events(void *hp, int kind, int64_t *table, int64_t *row, int64_t *slot, int64_t *old) {
+  orc *h = (orc *)hp;
+  int64_t n = 0;
+  for (int t = 0; t < h->T; t++) {
+    orc_table *tb = &h->tab[t];
+    int64_t c = kind == 0 ? tb->n_hit : kind == 1 ? tb->n_ins : tb->n_byp;
+    const int64_t *src = kind == 0 ? tb->hit_row : kind == 1 ? tb->ins_row : tb->byp_row;
+    if (table && row)
+      for (int64_t i = 0; i < c; i++) {
+        table[n + i] = t; row[n + i] = src[i];
+        if (kind == 1 && slot && old) { slot[n + i] = tb->ins_slot[i]; old[n + i] = tb->ins_old[i]; }
+      }
+    n += c;
+  }
+  return n;
+}
+
+/* current value of a row and its accumulator, wherever they live */
+int orc_read_row(void *hp, int32_t t, int64_t r, double *w, float *m) {
+  orc *h = (orc *)hp;
+  if (!h || t < 0 || t >= h->T || r < 0 || r >= h->tab[t].rows) return ORC_EINVAL;
+  orc_table *tb = &h->tab[t];
+  int64_t slot = find_slot(tb, h->ways, r);
+  const void *src = slot >= 0 ? tb->lines : tb->weights;
+  int64_t base = (slot >= 0 ? slot : r) * tb->dim;
+  for (int d = 0; d < tb->dim; d++) w[d] = load_elem(src, tb->dtype, base + d);
+  *m = slot >= 0 ? tb->line_state[slot] : tb->state[r];
+  return ORC_OK;
+}
