@@ -1,0 +1,200 @@
+/*
+ * tbe.h -- C ABI of the cached embedding-bag training path for AMD MI355X (gfx950).
+ *
+ * One handle owns a software cache of hot embedding rows in HBM in front of a larger
+ * backing tier in pinned host memory, for a set of embedding tables, and runs the
+ * per-batch path of DLRM embedding training through it:
+ *
+ *   prefetch  : decide, for the distinct rows of a batch, hit / insert / bypass, pick the
+ *               LRU victims, write the victims back and fetch the missed rows
+ *               (paper Section 5.5: tag/state lookup, cache algorithm, data
+ *               lookup/update, data movement; Section 5.7: prefetch stage "4a");
+ *   forward   : pooled (sum) embedding-bag lookup (Section 2.1.1);
+ *   backward  : per-row gradient aggregation + row-wise Adagrad applied where the row
+ *               lives (Section 2.1.2 Eq. 2, Section 5.9);
+ *   flush     : write every cached row back to the backing tier (write-back rule of
+ *               Section 5.5.4).
+ *
+ * Conventions
+ *   - every function returns 0 on success or a negative TBE_E* code; no exception
+ *     crosses the boundary; tbe_last_error() gives a text for the last failure;
+ *   - pointers named d_* are DEVICE pointers, h_* are HOST pointers;
+ *   - the caller owns every buffer it passes in; the library owns the cache lines, tags,
+ *     timestamps and all scratch memory, allocated once in tbe_create;
+ *   - work is enqueued on the two HIP streams given at creation and the calls return
+ *     without waiting for the GPU, except tbe_flush, tbe_get_stats and the tbe_export_*
+ *     calls, which synchronise both streams;
+ *   - a handle must be driven from one host thread at a time.
+ *
+ * Cache semantics (deterministic; they define the expected tags and timestamps bit for
+ * bit).  Each table t has S_t = cache_slots / ways sets of `ways` entries;
+ * row r maps to set r mod S_t.  Batch ids k = 1, 2, ... are assigned by tbe_prefetch.
+ * For batch k the distinct rows of each table are handled in two phases (Section 5.5.2
+ * lists the steps in this order): 1) every row found in its set is a hit and its entry is
+ * stamped k; 2) the remaining rows, in ascending row order, take the entry of their set
+ * with the smallest timestamp below k (free entries carry -1; the lowest way wins a
+ * tie); the row that was there is evicted and written back, the new row is fetched.  A
+ * row whose set has no entry older than k is not cached for this batch ("bypass"): it
+ * is read and updated directly in the backing tier.  No row needed by a batch that has not
+ * trained is ever evicted (Section 5.7).
+ */
+#ifndef TBE_H
+#define TBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TBE_OK 0
+#define TBE_EINVAL (-1)    /* bad argument: null pointer, bad dim / dtype / ways, bad offsets */
+#define TBE_ERANGE (-2)    /* an index is outside [0, rows) of its table                      */
+#define TBE_EORDER (-3)    /* call order violated (see the functions)                         */
+#define TBE_ENOMEM (-4)    /* device or host allocation failed                                */
+#define TBE_ELIMIT (-5)    /* batch / lookup count / key space above what create sized        */
+#define TBE_EMISMATCH (-6) /* tbe_forward given other buffers than the pending tbe_prefetch   */
+#define TBE_EHIP (-7)      /* a HIP runtime call failed                                       */
+
+#define TBE_FP32 0
+#define TBE_FP16 1 /* rows stored as IEEE binary16, all arithmetic in fp32, stores round to nearest even */
+
+typedef struct tbe_ctx *tbe_handle;
+
+/* One embedding table (Section 5.2: a two-dimensional tensor in byte-addressable memory). */
+typedef struct {
+  int64_t rows;        /* H_t >= 1, below 2^31                                                   */
+  int32_t dim;         /* D_t: multiple of 4 (fp32) or 8 (fp16), at most 256 (fp32) / 512 (fp16) */
+  int32_t dtype;       /* TBE_FP32 or TBE_FP16                                                   */
+  void *host_weights;  /* HOST, pinned (hipHostMalloc / tbe_host_alloc), [rows, dim] row-major:  */
+                       /* the backing tier; read and written by GPU kernels over the host link   */
+  float *host_state;   /* HOST, pinned, [rows]: row-wise Adagrad accumulator of the backing tier */
+  int64_t cache_slots; /* HBM slots for this table; S_t = cache_slots / ways (floor); 0 = none   */
+} tbe_table_spec;
+
+typedef struct {
+  int64_t lookups;     /* N of the batch                                         */
+  int64_t uniques;     /* distinct (table, row) pairs                            */
+  int64_t hits;        /* distinct rows found in the cache                       */
+  int64_t inserts;     /* distinct rows fetched into the cache                   */
+  int64_t bypasses;    /* distinct rows served from the backing tier directly    */
+  int64_t evictions;   /* rows written back to make room (subset of inserts)     */
+  int64_t hit_lookups; /* lookups whose row was a hit (lookup-weighted hit count) */
+} tbe_batch_stats;
+
+typedef struct {
+  tbe_batch_stats last;  /* last prefetched batch                                   */
+  tbe_batch_stats total; /* sum over all batches since create                       */
+  int64_t h2d_bytes;     /* backing tier -> cache, rows + accumulators, since create */
+  int64_t d2h_bytes;     /* cache -> backing tier (evictions and flushes)           */
+  int32_t batch_id;      /* k of the last prefetch                                  */
+  int32_t reserved;
+} tbe_stats;
+
+/*
+ * Create a handle (the problem statement of Sections 5.3 and 5.5: a cache class with cache
+ * memory, tags and timestamp states per table, managed by GPU kernels).
+ *   specs, num_tables : HOST array of table descriptions (copied).
+ *   ways              : associativity W, 1..64 (one 64-lane wavefront handles one set).
+ *   max_batch         : largest `batch` (samples) of any later call.
+ *   max_lookups       : largest `num_lookups` of any later call (< 2^31).
+ *   compute_stream    : hipStream_t on which forward / backward run (NULL = default stream).
+ *   aux_stream        : hipStream_t on which prefetch work runs; may equal compute_stream
+ *                       (then nothing overlaps).  Both must have the default priority.
+ * The sum over tables of the key spans (about the row counts, rounded up to whole sets)
+ * must stay below 2^32 (TBE_ELIMIT).  All device memory is allocated here (TBE_ENOMEM).
+ */
+int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables, int32_t ways,
+               int32_t max_batch, int64_t max_lookups, void *compute_stream, void *aux_stream);
+
+/*
+ * Prefetch stage (Section 5.7 "4a", Section 5.5.1-5.5.4) for one batch; assigns it the next
+ * batch id.
+ *   d_indices : DEVICE int64[num_lookups], table-local row ids; the lookups of bag
+ *               (t, b) are d_indices[d_offsets[t*batch+b] .. d_offsets[t*batch+b+1]).
+ *   d_offsets : DEVICE int64[num_tables*batch + 1], non-decreasing, first 0, last
+ *               num_lookups.
+ * Both buffers must stay valid and unchanged until the matching tbe_backward_update has
+ * completed on the compute stream.  They must have been produced on (or be ordered
+ * before) the compute stream at the time of this call.
+ * At most ONE batch may be ahead of training: allowed while no more than one batch is
+ * prefetched-or-forwarded and not yet updated (else TBE_EORDER).  When such a batch is
+ * still in flight, the cache decisions of the new batch are taken as if it had
+ * already trained, and the copies that would touch its rows wait for its update.
+ * Bad offsets / out-of-range indices are detected on the device: the batch then does
+ * nothing and the error is reported by the next synchronising call (and by later calls).
+ */
+int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch,
+                 int64_t num_lookups);
+
+/*
+ * Pooled lookup (Section 2.1.1, sum pooling): for every table t, sample b and d < D_t
+ *   d_out[b * sum_dim + col_t + d] = sum over the bag's lookups j of W_t[d_indices[j]][d]
+ * with col_t the sum of the dims of the tables before t; an empty bag gives zeros; fp32
+ * accumulation.  d_out: DEVICE float[batch * sum_dim].
+ * Consumes the oldest prefetched batch, which must have been prefetched with these same
+ * buffers (TBE_EMISMATCH); when nothing is pending it runs the prefetch stage itself
+ * first.  TBE_EORDER if the previous forwarded batch has not been updated yet.
+ */
+int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch,
+                int64_t num_lookups, float *d_out);
+
+/*
+ * Sparse backward fused with row-wise Adagrad (Section 2.1.2, Section 5.9) for the batch
+ * last forwarded: for every distinct row r of table t in it
+ *   g[d]  = sum over its lookups j of d_grad_out[bag(j) * sum_dim + col_t + d]
+ *   m_r  += (1 / D_t) * sum_d g[d]^2
+ *   w_r[d] -= lr * g[d] / (sqrt(m_r) + eps)           (with the new m_r)
+ * applied in place to the cache line, or to the backing tier for bypassed rows.
+ * d_grad_out: DEVICE float[batch * sum_dim], ready on the compute stream.
+ * TBE_EORDER without a forwarded batch.
+ */
+int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float eps);
+
+/*
+ * Write every valid cache line and its accumulator to the backing tier (Section 5.5.4,
+ * write-back) and wait for both streams: afterwards the host arrays hold the current model.
+ * Tags and timestamps stay.  TBE_EORDER while a batch is prefetched or forwarded but not
+ * updated.  Also reports errors the device found earlier.
+ */
+int tbe_flush(tbe_handle h);
+
+/* Waits for outstanding work and releases everything the library allocated. */
+int tbe_destroy(tbe_handle h);
+
+/* Counters (synchronises).  Hit rate per distinct row = hits / uniques; per lookup =
+ * hit_lookups / lookups; requests reaching the backing tier = (1 - hit rate) * requests
+ * (Section 4.2, Eq. 4 with alpha the miss ratio). */
+int tbe_get_stats(tbe_handle h, tbe_stats *out);
+
+/* Sets and slots of a table's cache: S_t (and S_t * ways slots). */
+int64_t tbe_num_sets(tbe_handle h, int32_t table);
+
+/* Copy a table's tags (row id, -1 = free) and timestamps (batch id, -1 = free) to
+ * HOST arrays of S_t * ways entries, index set * ways + way.  Synchronises. */
+int tbe_export_cache_state(tbe_handle h, int32_t table, int64_t *h_tags, int32_t *h_ts);
+
+/*
+ * Events of the last prefetched batch.  kind 0 = hits, 1 = inserts, 2 = bypasses.
+ * Returns the number of events (or a negative error).  With non-null HOST arrays (each at
+ * least `capacity` long) fills h_table / h_row, and for inserts h_slot (table-local,
+ * set * ways + way) and h_old (row evicted from that slot, -1 if it was free); h_slot and
+ * h_old may be null.  Order: ascending (table, set, row).  Synchronises.
+ */
+int64_t tbe_export_batch_events(tbe_handle h, int32_t kind, int64_t capacity, int64_t *h_table,
+                                int64_t *h_row, int64_t *h_slot, int64_t *h_old);
+
+/* Text describing the last error on this handle (static storage; h may be NULL for
+ * errors of tbe_create). */
+const char *tbe_last_error(tbe_handle h);
+
+/* Pinned, device-visible host memory for the backing tier (existing memory cannot be
+ * registered after the fact on every system).  Contents are uninitialised. */
+int tbe_host_alloc(void **h_ptr, size_t bytes);
+int tbe_host_free(void *h_ptr);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TBE_H */

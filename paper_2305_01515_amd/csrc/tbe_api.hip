@@ -1,0 +1,512 @@
+// C ABI of libtbe: handle life cycle, the two-stream batch pipeline, observation calls.
+// Declarations and the contract of every call are in include/tbe.h.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/tbe.h"
+#include "tbe_internal.h"
+
+using namespace tbe;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+struct DevAlloc {  // everything hipMalloc'ed, freed together
+  std::vector<void *> ptrs;
+  template <class P>
+  hipError_t get(P **p, size_t bytes) {
+    void *v = nullptr;
+    hipError_t e = hipMalloc(&v, bytes ? bytes : 16);
+    if (e == hipSuccess) ptrs.push_back(v);
+    *p = (P *)v;
+    return e;
+  }
+  void release() {
+    for (void *p : ptrs) (void)hipFree(p);
+    ptrs.clear();
+  }
+};
+
+}  // namespace
+
+struct tbe_ctx {
+  Geometry g{};
+  std::vector<TableMeta> tm;  // host copy
+  TableMeta *d_tm = nullptr;
+  ClassInfo ci{};
+  DevAlloc mem;
+  int32_t *tags = nullptr, *ts = nullptr;
+  float *cache_m = nullptr;
+  char *lines = nullptr;
+  BatchBuf buf[2]{};
+  SortScratch ss{};
+  BatchCounters *d_total = nullptr;       // running totals of the per-batch counters
+  unsigned long long *d_bytes = nullptr;  // [0] backing->cache, [1] cache->backing
+  hipStream_t cs = nullptr, as = nullptr;
+  hipEvent_t ev_inputs = nullptr, ev_ready[2] = {nullptr, nullptr}, ev_trained[2] = {nullptr, nullptr};
+  bool trained_recorded[2] = {false, false};
+  int32_t max_batch = 0;
+  int64_t max_lookups = 0;
+  int32_t k = 0;
+  // pipeline: buffers prefetched and waiting for forward (oldest first), the buffer that
+  // was forwarded and waits for its update, and a buffer whose copies wait for that update
+  int pend[2] = {-1, -1};
+  int n_pend = 0;
+  int current = -1;
+  int deferred = -1;
+  int last_buf = -1;
+  int64_t total_lookups = 0;
+  int sticky = 0;
+  std::string err;
+};
+
+namespace {
+
+int fail(tbe_ctx *h, int code, const std::string &msg) {
+  if (h) h->err = msg; else g_create_error = msg;
+  return code;
+}
+
+int hipfail(tbe_ctx *h, hipError_t e, const char *what) {
+  return fail(h, e == hipErrorOutOfMemory ? TBE_ENOMEM : TBE_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define HIP_TRY(h, call)                                  \
+  do {                                                    \
+    hipError_t e__ = (call);                              \
+    if (e__ != hipSuccess) return hipfail(h, e__, #call); \
+  } while (0)
+
+int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
+
+__global__ void add_totals_kernel(const BatchCounters *c, BatchCounters *tot) {
+  if (threadIdx.x == 0 && c->err == 0) {
+    tot->hits += c->hits;
+    tot->evictions += c->evictions;
+    tot->hit_lookups += c->hit_lookups;
+  }
+}
+
+// 64-bit totals: [0] uniques [1] inserts [2] bypasses
+__global__ void add_totals64_kernel(const BatchCounters *c, unsigned long long *t64) {
+  if (threadIdx.x == 0 && c->err == 0) {
+    t64[0] += (unsigned long long)c->n_uniq;
+    t64[1] += (unsigned long long)c->n_ins;
+    t64[2] += (unsigned long long)c->n_byp;
+  }
+}
+
+int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
+  const size_t N = (size_t)std::max<int64_t>(n, 1);
+  HIP_TRY(h, h->mem.get(&b.loc, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.sorted_bag, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.bag_of_pos, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.uid_sorted, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.uniq_key, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.run_off, 4 * (N + 1)));
+  HIP_TRY(h, h->mem.get(&b.uniq_sid, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.loc_u, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.status, N));
+  HIP_TRY(h, h->mem.get(&b.old_tag, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.old_ts, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.touched, 8 * N));
+  HIP_TRY(h, h->mem.get(&b.ins_idx, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.byp_idx, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.long_idx, 4 * (N / kLongRun + 2)));
+  HIP_TRY(h, h->mem.get(&b.cnt, sizeof(BatchCounters)));
+  HIP_TRY(h, hipMemset(b.cnt, 0, sizeof(BatchCounters)));
+  return TBE_OK;
+}
+
+int device_error_code(int e) { return e == 0 ? 0 : e == 1 ? TBE_EINVAL : TBE_ERANGE; }
+
+// After a synchronisation: pick up errors the device recorded.
+int collect_device_errors(tbe_ctx *h) {
+  for (int i = 0; i < 2; i++) {
+    BatchCounters c;
+    HIP_TRY(h, hipMemcpy(&c, h->buf[i].cnt, sizeof(c), hipMemcpyDeviceToHost));
+    if (c.err && !h->sticky) {
+      h->sticky = device_error_code(c.err);
+      h->err = c.err == 1 ? "offsets are not a non-decreasing partition of [0, num_lookups]"
+                          : "an index is outside its table";
+    }
+  }
+  return h->sticky;
+}
+
+int sync_all(tbe_ctx *h) {
+  HIP_TRY(h, hipStreamSynchronize(h->as));
+  HIP_TRY(h, hipStreamSynchronize(h->cs));
+  return TBE_OK;
+}
+
+// Cache -> cache copies for buffer `bi`, then mark the batch ready for forward.
+int enqueue_fill(tbe_ctx *h, int bi) {
+  BatchBuf &b = h->buf[bi];
+  HIP_TRY(h, launch_fill(h->d_tm, h->g, b, h->cache_m, h->d_bytes, h->d_bytes + 1, h->as));
+  HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->as));
+  return TBE_OK;
+}
+
+int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch, int64_t n) {
+  if (!d_offsets || batch < 0 || n < 0 || (n > 0 && !d_indices)) return fail(h, TBE_EINVAL, "prefetch: bad argument");
+  if (batch > h->max_batch || n > h->max_lookups) return fail(h, TBE_ELIMIT, "prefetch: batch or lookups above the sizes given to tbe_create");
+  if (h->n_pend + (h->current >= 0 ? 1 : 0) > 1) return fail(h, TBE_EORDER, "prefetch: more than one batch would be ahead of training");
+  // a free buffer: not pending, not current
+  int bi = 0;
+  while (bi < 2 && (bi == h->current || (h->n_pend > 0 && h->pend[0] == bi))) bi++;
+  BatchBuf &b = h->buf[bi];
+  const bool in_flight = h->n_pend > 0 || h->current >= 0;
+  b.d_indices = d_indices; b.d_offsets = d_offsets; b.batch = batch; b.n = n; b.k = ++h->k;
+  h->total_lookups += n;
+  h->last_buf = bi;
+  if (h->as != h->cs) {
+    // inputs produced on the compute stream so far, and the last training step that read
+    // this buffer's arrays, come first
+    HIP_TRY(h, hipEventRecord(h->ev_inputs, h->cs));
+    HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_inputs, 0));
+  }
+  HIP_TRY(h, launch_keygen(h->d_tm, h->g, b, h->ss.keys[0], h->ss.vals[0], h->as));
+  int res = 0;
+  HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
+  HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->as));
+  hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total);
+  hipLaunchKernelGGL(add_totals64_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_bytes + 2);
+  HIP_TRY(h, hipGetLastError());
+  h->pend[h->n_pend++] = bi;
+  if (in_flight) {
+    h->deferred = bi;  // its copies must not touch rows the batch in flight still uses
+    return TBE_OK;
+  }
+  return enqueue_fill(h, bi);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *tbe_last_error(tbe_handle h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+int tbe_host_alloc(void **h_ptr, size_t bytes) {
+  if (!h_ptr) return TBE_EINVAL;
+  hipError_t e = hipHostMalloc(h_ptr, bytes ? bytes : 16, hipHostMallocDefault);
+  if (e != hipSuccess) { *h_ptr = nullptr; (void)hipGetLastError(); return TBE_ENOMEM; }
+  return TBE_OK;
+}
+
+int tbe_host_free(void *h_ptr) { return hipHostFree(h_ptr) == hipSuccess ? TBE_OK : TBE_EHIP; }
+
+int tbe_destroy(tbe_handle h) {
+  if (!h) return TBE_EINVAL;
+  (void)hipStreamSynchronize(h->as);
+  (void)hipStreamSynchronize(h->cs);
+  h->mem.release();
+  if (h->ev_inputs) (void)hipEventDestroy(h->ev_inputs);
+  for (int i = 0; i < 2; i++) {
+    if (h->ev_ready[i]) (void)hipEventDestroy(h->ev_ready[i]);
+    if (h->ev_trained[i]) (void)hipEventDestroy(h->ev_trained[i]);
+  }
+  delete h;
+  return TBE_OK;
+}
+
+int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables, int32_t ways, int32_t max_batch,
+               int64_t max_lookups, void *compute_stream, void *aux_stream) {
+  if (!out) return fail(nullptr, TBE_EINVAL, "create: null output handle");
+  *out = nullptr;
+  if (!specs || num_tables <= 0) return fail(nullptr, TBE_EINVAL, "create: no tables");
+  if (ways < 1 || ways > kWave) return fail(nullptr, TBE_EINVAL, "create: ways must be 1..64");
+  if (max_batch < 1 || max_lookups < 1 || max_lookups > (1ll << 30))
+    return fail(nullptr, TBE_EINVAL, "create: max_batch >= 1 and 1 <= max_lookups <= 2^30 required");
+  if ((int64_t)num_tables * max_batch >= (1ll << 31)) return fail(nullptr, TBE_ELIMIT, "create: tables x batch too large");
+  tbe_ctx *h = new (std::nothrow) tbe_ctx();
+  if (!h) return fail(nullptr, TBE_ENOMEM, "create: host allocation failed");
+  h->cs = (hipStream_t)compute_stream;
+  h->as = (hipStream_t)aux_stream;
+  h->max_batch = max_batch;
+  h->max_lookups = max_lookups;
+  h->g.T = num_tables;
+  h->g.ways = ways;
+  h->tm.resize(num_tables);
+  uint64_t key = 0, sets = 0;
+  int64_t col = 0;
+  size_t line_bytes = 0;
+  std::vector<size_t> line_off(num_tables);
+  std::vector<int> tclass(num_tables);
+  for (int t = 0; t < num_tables; t++) {
+    const tbe_table_spec &s = specs[t];
+    TableMeta &m = h->tm[t];
+    const int epl = s.dtype == TBE_FP32 ? 4 : 8;
+    if ((s.dtype != TBE_FP32 && s.dtype != TBE_FP16) || s.rows < 1 || s.rows >= (1ll << 31) || s.dim < epl ||
+        s.dim % epl || s.dim > 64 * epl || !s.host_weights || !s.host_state || s.cache_slots < 0) {
+      delete h;
+      return fail(nullptr, TBE_EINVAL, "create: bad table spec " + std::to_string(t));
+    }
+    m.rows = s.rows;
+    m.dim = s.dim;
+    m.dtype = s.dtype;
+    m.row_bytes = (uint32_t)(s.dim * (s.dtype == TBE_FP32 ? 4 : 2));
+    m.lanes = next_pow2(s.dim / epl);
+    m.col = (int32_t)col;
+    m.sets = (uint32_t)std::min<int64_t>(s.cache_slots / ways, (1ll << 31) / ways);
+    m.rows_per_set = m.sets ? (uint32_t)((s.rows + m.sets - 1) / m.sets) : 0;
+    m.key_base = (uint32_t)key;
+    m.set_base = (uint32_t)sets;
+    m.slot_base = (int32_t)(sets * ways);
+    m.host_w = (char *)s.host_weights;
+    m.host_m = s.host_state;
+    key += m.sets ? (uint64_t)m.sets * m.rows_per_set : (uint64_t)s.rows;
+    sets += m.sets;
+    col += s.dim;
+    line_off[t] = line_bytes;
+    line_bytes += ((size_t)m.sets * ways * m.row_bytes + 255) & ~(size_t)255;
+    if (key > (1ull << 32) || sets * ways >= (1ull << 31) || col >= (1ll << 30)) {
+      delete h;
+      return fail(nullptr, TBE_ELIMIT, "create: key space, slot count or output width too large");
+    }
+    // class of the table
+    int c = 0;
+    for (; c < h->ci.n_classes; c++)
+      if (h->ci.cls_dtype[c] == m.dtype && h->ci.cls_lanes[c] == m.lanes) break;
+    if (c == h->ci.n_classes) {
+      h->ci.cls_dtype[c] = m.dtype;
+      h->ci.cls_lanes[c] = m.lanes;
+      h->ci.cls_count[c] = 0;
+      h->ci.n_classes++;
+    }
+    h->ci.cls_count[c]++;
+    tclass[t] = c;
+  }
+  h->g.sum_dim = (int32_t)col;
+  h->g.total_sets = (uint32_t)sets;
+  h->g.total_slots = (int64_t)sets * ways;
+  h->g.key_bits = 1;
+  while (h->g.key_bits < 32 && (1ull << h->g.key_bits) < key) h->g.key_bits++;
+
+  auto bail = [&](int code) { tbe_destroy(h); return code; };
+  auto hipbail = [&](hipError_t e, const char *what) {
+    int code = hipfail(nullptr, e, what);
+    tbe_destroy(h);
+    return code;
+  };
+#define CREATE_TRY(call)                                  \
+  do {                                                    \
+    hipError_t e__ = (call);                              \
+    if (e__ != hipSuccess) return hipbail(e__, #call);    \
+  } while (0)
+
+  const size_t slots = (size_t)h->g.total_slots;
+  CREATE_TRY(h->mem.get(&h->lines, line_bytes));
+  CREATE_TRY(h->mem.get(&h->tags, 4 * slots));
+  CREATE_TRY(h->mem.get(&h->ts, 4 * slots));
+  CREATE_TRY(h->mem.get(&h->cache_m, 4 * slots));
+  if (slots) {
+    CREATE_TRY(hipMemset(h->tags, 0xFF, 4 * slots));  // -1 = free
+    CREATE_TRY(hipMemset(h->ts, 0xFF, 4 * slots));
+    CREATE_TRY(hipMemset(h->cache_m, 0, 4 * slots));
+  }
+  for (int t = 0; t < num_tables; t++) h->tm[t].lines = h->lines + line_off[t];
+  CREATE_TRY(h->mem.get(&h->d_tm, sizeof(TableMeta) * num_tables));
+  CREATE_TRY(hipMemcpy(h->d_tm, h->tm.data(), sizeof(TableMeta) * num_tables, hipMemcpyHostToDevice));
+  {  // class tables
+    int32_t *d_tc = nullptr;
+    CREATE_TRY(h->mem.get(&d_tc, 4 * (size_t)num_tables));
+    CREATE_TRY(hipMemcpy(d_tc, tclass.data(), 4 * (size_t)num_tables, hipMemcpyHostToDevice));
+    h->ci.table_class = d_tc;
+    for (int c = 0; c < h->ci.n_classes; c++) {
+      std::vector<int32_t> ids;
+      for (int t = 0; t < num_tables; t++)
+        if (tclass[t] == c) ids.push_back(t);
+      int32_t *d_ids = nullptr;
+      CREATE_TRY(h->mem.get(&d_ids, 4 * ids.size()));
+      CREATE_TRY(hipMemcpy(d_ids, ids.data(), 4 * ids.size(), hipMemcpyHostToDevice));
+      h->ci.cls_tables[c] = d_ids;
+    }
+  }
+  for (int i = 0; i < 2; i++) {
+    int rc = alloc_batchbuf(h, h->buf[i], max_lookups);
+    if (rc) { g_create_error = h->err; return bail(rc); }
+    CREATE_TRY(hipEventCreateWithFlags(&h->ev_ready[i], hipEventDisableTiming));
+    CREATE_TRY(hipEventCreateWithFlags(&h->ev_trained[i], hipEventDisableTiming));
+  }
+  CREATE_TRY(hipEventCreateWithFlags(&h->ev_inputs, hipEventDisableTiming));
+  const size_t N = (size_t)max_lookups;
+  for (int i = 0; i < 2; i++) {
+    CREATE_TRY(h->mem.get(&h->ss.keys[i], 4 * N));
+    CREATE_TRY(h->mem.get(&h->ss.vals[i], 4 * N));
+  }
+  CREATE_TRY(h->mem.get(&h->ss.hist, 4 * 256 * 1024));
+  CREATE_TRY(h->mem.get(&h->ss.blk, 8 * 1024));
+  CREATE_TRY(h->mem.get(&h->d_total, sizeof(BatchCounters)));
+  CREATE_TRY(hipMemset(h->d_total, 0, sizeof(BatchCounters)));
+  CREATE_TRY(h->mem.get(&h->d_bytes, 8 * 8));
+  CREATE_TRY(hipMemset(h->d_bytes, 0, 8 * 8));
+  CREATE_TRY(hipDeviceSynchronize());
+#undef CREATE_TRY
+  *out = h;
+  return TBE_OK;
+}
+
+int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch, int64_t num_lookups) {
+  if (!h) return TBE_EINVAL;
+  if (h->sticky) return h->sticky;
+  return do_prefetch(h, d_indices, d_offsets, batch, num_lookups);
+}
+
+int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch, int64_t num_lookups,
+                float *d_out) {
+  if (!h) return TBE_EINVAL;
+  if (h->sticky) return h->sticky;
+  if (!d_out) return fail(h, TBE_EINVAL, "forward: null output");
+  if (h->current >= 0) return fail(h, TBE_EORDER, "forward: the previous batch has not been updated");
+  if (h->n_pend == 0) {
+    int rc = do_prefetch(h, d_indices, d_offsets, batch, num_lookups);
+    if (rc) return rc;
+  }
+  const int bi = h->pend[0];
+  BatchBuf &b = h->buf[bi];
+  if (b.d_indices != d_indices || b.d_offsets != d_offsets || b.batch != batch || b.n != num_lookups)
+    return fail(h, TBE_EMISMATCH, "forward: buffers differ from the pending prefetch");
+  if (h->deferred == bi) return fail(h, TBE_EORDER, "forward: the batch before this one has not been updated");
+  h->pend[0] = h->pend[1];
+  h->n_pend--;
+  if (h->as != h->cs) HIP_TRY(h, hipStreamWaitEvent(h->cs, h->ev_ready[bi], 0));
+  HIP_TRY(h, launch_forward_classes(h->d_tm, h->ci, h->g, b, d_out, h->cs));
+  h->current = bi;
+  return TBE_OK;
+}
+
+int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float eps) {
+  if (!h) return TBE_EINVAL;
+  if (h->sticky) return h->sticky;
+  if (!d_grad_out) return fail(h, TBE_EINVAL, "backward_update: null gradient");
+  if (h->current < 0) return fail(h, TBE_EORDER, "backward_update: no forwarded batch");
+  const int bi = h->current;
+  HIP_TRY(h, launch_backward_classes(h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, lr, eps, h->cs));
+  h->current = -1;
+  if (h->as != h->cs) {
+    HIP_TRY(h, hipEventRecord(h->ev_trained[bi], h->cs));
+    // later prefetch work (which may reuse this buffer or move rows this batch used) follows it
+    HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_trained[bi], 0));
+  }
+  if (h->deferred >= 0) {
+    const int d = h->deferred;
+    h->deferred = -1;
+    return enqueue_fill(h, d);
+  }
+  return TBE_OK;
+}
+
+int tbe_flush(tbe_handle h) {
+  if (!h) return TBE_EINVAL;
+  if (h->n_pend > 0 || h->current >= 0) return fail(h, TBE_EORDER, "flush: a batch is still in flight");
+  int rc = sync_all(h);
+  if (rc) return rc;
+  HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->cache_m, h->d_bytes + 1, h->cs));
+  rc = sync_all(h);
+  if (rc) return rc;
+  return collect_device_errors(h);
+}
+
+int64_t tbe_num_sets(tbe_handle h, int32_t table) {
+  if (!h || table < 0 || table >= h->g.T) return TBE_EINVAL;
+  return h->tm[table].sets;
+}
+
+int tbe_get_stats(tbe_handle h, tbe_stats *out) {
+  if (!h || !out) return TBE_EINVAL;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  memset(out, 0, sizeof(*out));
+  BatchCounters tot;
+  unsigned long long b64[8];
+  HIP_TRY(h, hipMemcpy(&tot, h->d_total, sizeof(tot), hipMemcpyDeviceToHost));
+  HIP_TRY(h, hipMemcpy(b64, h->d_bytes, sizeof(b64), hipMemcpyDeviceToHost));
+  if (h->last_buf >= 0) {
+    BatchCounters c;
+    HIP_TRY(h, hipMemcpy(&c, h->buf[h->last_buf].cnt, sizeof(c), hipMemcpyDeviceToHost));
+    out->last.lookups = h->buf[h->last_buf].n;
+    out->last.uniques = c.n_uniq;
+    out->last.hits = (int64_t)c.hits;
+    out->last.inserts = c.n_ins;
+    out->last.bypasses = c.n_byp;
+    out->last.evictions = (int64_t)c.evictions;
+    out->last.hit_lookups = (int64_t)c.hit_lookups;
+  }
+  out->total.lookups = h->total_lookups;
+  out->total.uniques = (int64_t)b64[2];
+  out->total.inserts = (int64_t)b64[3];
+  out->total.bypasses = (int64_t)b64[4];
+  out->total.hits = (int64_t)tot.hits;
+  out->total.evictions = (int64_t)tot.evictions;
+  out->total.hit_lookups = (int64_t)tot.hit_lookups;
+  out->h2d_bytes = (int64_t)b64[0];
+  out->d2h_bytes = (int64_t)b64[1];
+  out->batch_id = h->k;
+  return collect_device_errors(h);
+}
+
+int tbe_export_cache_state(tbe_handle h, int32_t table, int64_t *h_tags, int32_t *h_ts) {
+  if (!h || table < 0 || table >= h->g.T || !h_tags || !h_ts) return TBE_EINVAL;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  const TableMeta &m = h->tm[table];
+  const size_t n = (size_t)m.sets * h->g.ways;
+  if (n == 0) return TBE_OK;
+  std::vector<int32_t> tmp(n);
+  HIP_TRY(h, hipMemcpy(tmp.data(), h->tags + m.slot_base, 4 * n, hipMemcpyDeviceToHost));
+  for (size_t i = 0; i < n; i++) h_tags[i] = tmp[i];
+  HIP_TRY(h, hipMemcpy(h_ts, h->ts + m.slot_base, 4 * n, hipMemcpyDeviceToHost));
+  return TBE_OK;
+}
+
+int64_t tbe_export_batch_events(tbe_handle h, int32_t kind, int64_t capacity, int64_t *h_table, int64_t *h_row,
+                                int64_t *h_slot, int64_t *h_old) {
+  if (!h || kind < 0 || kind > 2) return TBE_EINVAL;
+  if (h->last_buf < 0) return 0;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  const BatchBuf &b = h->buf[h->last_buf];
+  BatchCounters c;
+  HIP_TRY(h, hipMemcpy(&c, b.cnt, sizeof(c), hipMemcpyDeviceToHost));
+  if (c.err) return device_error_code(c.err);
+  const int64_t count = kind == 0 ? (int64_t)c.hits : kind == 1 ? c.n_ins : c.n_byp;
+  if (!h_table || !h_row) return count;
+  if (capacity < count) return fail(h, TBE_ELIMIT, "export_batch_events: capacity too small");
+  const size_t U = (size_t)c.n_uniq;
+  if (U == 0) return 0;
+  std::vector<uint32_t> key(U);
+  std::vector<uint8_t> st(U);
+  std::vector<int32_t> loc(U), old(U);
+  HIP_TRY(h, hipMemcpy(key.data(), b.uniq_key, 4 * U, hipMemcpyDeviceToHost));
+  HIP_TRY(h, hipMemcpy(st.data(), b.status, U, hipMemcpyDeviceToHost));
+  HIP_TRY(h, hipMemcpy(loc.data(), b.loc_u, 4 * U, hipMemcpyDeviceToHost));
+  HIP_TRY(h, hipMemcpy(old.data(), b.old_tag, 4 * U, hipMemcpyDeviceToHost));
+  const uint8_t want = kind == 0 ? ST_HIT : kind == 1 ? ST_INSERT : ST_BYPASS;
+  int64_t n = 0;
+  int t = 0;
+  for (size_t u = 0; u < U; u++) {
+    if (st[u] != want) continue;
+    while (t + 1 < h->g.T && h->tm[t + 1].key_base <= key[u]) t++;
+    const TableMeta &m = h->tm[t];
+    const uint32_t local = key[u] - m.key_base;
+    int64_t row = local;
+    if (m.sets) {
+      const uint32_t s = local / m.rows_per_set;
+      row = (int64_t)(local - s * m.rows_per_set) * m.sets + s;
+    }
+    h_table[n] = t;
+    h_row[n] = row;
+    if (kind == 1 && h_slot) h_slot[n] = loc[u] - m.slot_base;
+    if (kind == 1 && h_old) h_old[n] = old[u];
+    n++;
+  }
+  return n;
+}
+
+}  // extern "C"

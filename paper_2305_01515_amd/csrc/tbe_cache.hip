@@ -1,0 +1,451 @@
+// Index dedup part 2 (run-length encoding of the sorted keys), the set-associative probe
+// with LRU victim choice, miss-list compaction, and the copies between cache and backing
+// tier.  Paper Section 5.5: tag/state lookup (5.5.1), cache algorithm (5.5.2), data
+// lookup/update (5.5.3) and data movement (5.5.4), one-level cache.
+#include "tbe_internal.h"
+
+namespace tbe {
+
+// --------------------------------------------------------------------------------------
+// Generic flag -> exclusive prefix -> emit skeleton over n elements (n may live on the
+// device).  Two 32-bit counters are scanned at once, packed into one 64-bit word.
+//   count kernel : block sums of op.flag(i) over the block's contiguous chunk
+//   block scan   : exclusive scan of the block sums (single block), total at [nblocks]
+//   emit kernel  : op.emit(i, exclusive prefix, flag) for every element, in order
+// --------------------------------------------------------------------------------------
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 4;
+constexpr int kScanTile = kScanThreads * kScanItems;
+constexpr int kScanBlocks = 512;
+
+typedef unsigned long long u64;
+
+__device__ inline u64 wave_incl_scan(u64 v, int lane) {
+  for (int d = 1; d < 64; d <<= 1) {
+    u64 o = __shfl_up(v, d);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+__device__ inline int scan_chunk(int n, int nblocks) {
+  const int tiles = (n + kScanTile - 1) / kScanTile;
+  const int tpb = (tiles + nblocks - 1) / nblocks;
+  return tpb * kScanTile;
+}
+
+template <class Op>
+__global__ __launch_bounds__(kScanThreads) void compact_count_kernel(Op op, const int32_t *n_ptr, int n_fixed,
+                                                                     u64 *blk, const BatchCounters *cnt) {
+  __shared__ u64 wsum[4];
+  if (cnt->err) return;
+  const int n = n_ptr ? *n_ptr : n_fixed;
+  const int chunk = scan_chunk(n, gridDim.x);
+  const int base = blockIdx.x * chunk, end = min(n, base + chunk);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  u64 s = 0;
+  for (int tile = base; tile < end; tile += kScanTile) {
+    const int i0 = tile + tid * kScanItems;
+#pragma unroll
+    for (int q = 0; q < kScanItems; q++)
+      if (i0 + q < end) s += op.flag(i0 + q, n);
+  }
+  for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d);
+  if (lane == 0) wsum[wave] = s;
+  __syncthreads();
+  if (tid == 0) blk[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+__global__ __launch_bounds__(kScanBlocks) void compact_blockscan_kernel(u64 *blk, int nb, const BatchCounters *cnt) {
+  __shared__ u64 wsum[kScanBlocks / 64];
+  if (cnt->err) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const u64 v = tid < nb ? blk[tid] : 0;
+  const u64 incl = wave_incl_scan(v, lane);
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  u64 wb = 0;
+  for (int w = 0; w < wave; w++) wb += wsum[w];
+  if (tid < nb) blk[tid] = wb + incl - v;
+  if (tid == nb - 1) blk[nb] = wb + incl;
+}
+
+template <class Op>
+__global__ __launch_bounds__(kScanThreads) void compact_emit_kernel(Op op, const int32_t *n_ptr, int n_fixed,
+                                                                    const u64 *blk, BatchCounters *cnt) {
+  __shared__ u64 wsum[4];
+  if (cnt->err) return;
+  const int n = n_ptr ? *n_ptr : n_fixed;
+  const int chunk = scan_chunk(n, gridDim.x);
+  const int base = blockIdx.x * chunk, end = min(n, base + chunk);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  u64 carry = blk[blockIdx.x];
+  for (int tile = base; tile < end; tile += kScanTile) {
+    const int i0 = tile + tid * kScanItems;
+    u64 f[kScanItems];
+    u64 tsum = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; q++) {
+      f[q] = (i0 + q < end) ? op.flag(i0 + q, n) : 0;
+      tsum += f[q];
+    }
+    const u64 incl = wave_incl_scan(tsum, lane);
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    u64 wb = 0, all = 0;
+    for (int w = 0; w < 4; w++) {
+      if (w < wave) wb += wsum[w];
+      all += wsum[w];
+    }
+    u64 pre = carry + wb + incl - tsum;
+#pragma unroll
+    for (int q = 0; q < kScanItems; q++) {
+      if (i0 + q < end) op.emit(i0 + q, n, pre, f[q]);
+      pre += f[q];
+    }
+    carry += all;
+    __syncthreads();
+  }
+  op.thread_done(cnt, lane);
+  if (blockIdx.x == 0 && tid == 0) op.finish(cnt, n, blk[gridDim.x]);
+}
+
+template <class Op>
+static void run_compaction(Op op, const int32_t *n_ptr, int n_fixed, int n_bound, u64 *blk, BatchCounters *cnt,
+                           hipStream_t s) {
+  int nb = (n_bound + kScanTile - 1) / kScanTile;
+  if (nb > kScanBlocks) nb = kScanBlocks;
+  if (nb < 1) nb = 1;
+  hipLaunchKernelGGL(compact_count_kernel<Op>, dim3(nb), dim3(kScanThreads), 0, s, op, n_ptr, n_fixed, blk, cnt);
+  hipLaunchKernelGGL(compact_blockscan_kernel, dim3(1), dim3(kScanBlocks), 0, s, blk, nb, cnt);
+  hipLaunchKernelGGL(compact_emit_kernel<Op>, dim3(nb), dim3(kScanThreads), 0, s, op, n_ptr, n_fixed, blk, cnt);
+}
+
+// ---- pass 1 over the N sorted lookups: distinct rows, run starts, set ids ----
+struct DedupOp {
+  const TableMeta *tm;
+  int T;
+  const uint32_t *key;      // sorted
+  const uint32_t *pos;      // lookup position of each sorted element
+  const int32_t *bag_of_pos;
+  uint32_t *uid_sorted;
+  int32_t *sorted_bag;
+  uint32_t *uniq_key;
+  int32_t *run_off;
+  uint32_t *uniq_sid;
+  __device__ u64 flag(int i, int) const { return (i == 0 || key[i] != key[i - 1]) ? 1ull : 0ull; }
+  __device__ void emit(int i, int, u64 pre, u64 f) const {
+    const uint32_t u = (uint32_t)(pre & 0xFFFFFFFFull) + (uint32_t)f - 1u;
+    uid_sorted[i] = u;
+    sorted_bag[i] = bag_of_pos[pos[i]];
+    if (f) {
+      const uint32_t k = key[i];
+      uniq_key[u] = k;
+      run_off[u] = i;
+      const TableMeta &m = tm[find_table(tm, T, k)];
+      uniq_sid[u] = m.sets ? m.set_base + (k - m.key_base) / m.rows_per_set : kNoSet;
+    }
+  }
+  __device__ void thread_done(BatchCounters *, int) const {}
+  __device__ void finish(BatchCounters *cnt, int n, u64 total) const {
+    cnt->n_uniq = (int32_t)(total & 0xFFFFFFFFull);
+    run_off[total & 0xFFFFFFFFull] = n;
+  }
+};
+
+// ---- pass 2 over the distinct rows: first row of every touched set; long runs ----
+struct SetHeadOp {
+  const uint32_t *uniq_sid;
+  const int32_t *run_off;
+  uint2 *touched;
+  int32_t *long_idx;
+  __device__ u64 flag(int u, int) const { return (u == 0 || uniq_sid[u] != uniq_sid[u - 1]) ? 1ull : 0ull; }
+  __device__ void emit(int u, int, u64 pre, u64 f) const {
+    if (f) touched[pre & 0xFFFFFFFFull] = make_uint2(uniq_sid[u], (uint32_t)u);
+  }
+  __device__ void thread_done(BatchCounters *, int) const {}
+  __device__ void finish(BatchCounters *cnt, int, u64 total) const { cnt->n_touched = (int32_t)(total & 0xFFFFFFFFull); }
+};
+
+__global__ __launch_bounds__(256) void long_runs_kernel(const int32_t *__restrict__ run_off, int32_t *long_idx,
+                                                        BatchCounters *cnt) {
+  if (cnt->err) return;
+  const int n = cnt->n_uniq;
+  for (int u = blockIdx.x * blockDim.x + threadIdx.x; u < n; u += gridDim.x * blockDim.x)
+    if (run_off[u + 1] - run_off[u] > kLongRun) long_idx[atomicAdd(&cnt->n_long, 1)] = u;
+}
+
+// ---- pass 3 over the distinct rows after the probe: insert and bypass lists, counters ----
+struct StatusOp {
+  const uint8_t *status;
+  const int32_t *run_off;
+  const int32_t *old_tag;
+  int32_t *ins_idx;
+  int32_t *byp_idx;
+  // per-thread tallies (the emit kernel keeps one Op copy per thread in registers)
+  mutable unsigned int hits, evs;
+  mutable u64 hit_lookups;
+  __device__ u64 flag(int u, int) const {
+    const uint8_t s = status[u];
+    return s == ST_INSERT ? 1ull : s == ST_BYPASS ? (1ull << 32) : 0ull;
+  }
+  __device__ void emit(int u, int, u64 pre, u64 f) const {
+    if (f == 1ull) {
+      ins_idx[pre & 0xFFFFFFFFull] = u;
+      if (old_tag[u] >= 0) evs++;
+    } else if (f) {
+      byp_idx[pre >> 32] = u;
+    } else if (status[u] == ST_HIT) {
+      hits++;
+      hit_lookups += (u64)(run_off[u + 1] - run_off[u]);
+    }
+  }
+  __device__ void thread_done(BatchCounters *cnt, int lane) const {
+    u64 h = hits, e = evs, l = hit_lookups;
+    for (int d = 32; d >= 1; d >>= 1) {
+      h += __shfl_xor(h, d);
+      e += __shfl_xor(e, d);
+      l += __shfl_xor(l, d);
+    }
+    if (lane == 0) {
+      if (h) atomicAdd(&cnt->hits, h);
+      if (e) atomicAdd(&cnt->evictions, e);
+      if (l) atomicAdd(&cnt->hit_lookups, l);
+    }
+  }
+  __device__ void finish(BatchCounters *cnt, int, u64 total) const {
+    cnt->n_ins = (int32_t)(total & 0xFFFFFFFFull);
+    cnt->n_byp = (int32_t)(total >> 32);
+  }
+};
+
+// --------------------------------------------------------------------------------------
+// Probe + LRU: one wavefront per touched set; lane w holds way w.
+//   phase 1: every distinct row of the set that is found is a hit, its way is stamped k;
+//   phase 2: the ways still older than k are ranked by (timestamp, way); the j-th miss in
+//            ascending row order takes the way of rank j (evicting what it held); misses
+//            beyond the number of such ways bypass the cache.
+// Rows of a set arrive in ascending order because the sort key is (set, row div S).
+// --------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restrict__ tm, int T, int W, int32_t k,
+                                                      const uint32_t *__restrict__ uniq_key,
+                                                      const uint2 *__restrict__ touched, int32_t *__restrict__ tags,
+                                                      int32_t *__restrict__ ts, int32_t *__restrict__ loc_u,
+                                                      uint8_t *__restrict__ status, int32_t *__restrict__ old_tag,
+                                                      int32_t *__restrict__ old_ts, const BatchCounters *cnt) {
+  __shared__ int32_t l_tag[kWave];
+  __shared__ int32_t l_ts[kWave];
+  __shared__ int32_t l_way[kWave];
+  if (cnt->err) return;
+  const int lane = threadIdx.x;
+  const int n_touched = cnt->n_touched, n_uniq = cnt->n_uniq;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  for (int v = blockIdx.x; v < n_touched; v += gridDim.x) {
+    const uint2 head = touched[v];
+    const int u0 = (int)head.y;
+    const int u1 = (v + 1 < n_touched) ? (int)touched[v + 1].y : n_uniq;
+    if (head.x == kNoSet) {  // rows of tables without a cache
+      for (int u = u0 + lane; u < u1; u += kWave) {
+        loc_u[u] = -1;
+        status[u] = ST_BYPASS;
+      }
+      continue;
+    }
+    const TableMeta &m = tm[find_table(tm, T, uniq_key[u0])];
+    const uint32_t set = head.x - m.set_base;
+    const int slot0 = (int)head.x * W;  // global slot id of way 0 (set_base * W == slot_base)
+    const uint32_t key0 = m.key_base + set * m.rows_per_set;
+    __syncthreads();
+    l_tag[lane] = lane < W ? tags[slot0 + lane] : -2;
+    l_ts[lane] = lane < W ? ts[slot0 + lane] : 0x7FFFFFFF;
+    __syncthreads();
+    // phase 1: hits
+    for (int c = u0; c < u1; c += kWave) {
+      const int u = c + lane;
+      const bool valid = u < u1;
+      const int32_t row = valid ? (int32_t)((uniq_key[u] - key0) * m.sets + set) : -3;
+      int hit = -1;
+      for (int w = 0; w < W; w++)
+        if (l_tag[w] == row) hit = w;
+      if (valid) {
+        if (hit >= 0) {
+          l_ts[hit] = k;
+          loc_u[u] = slot0 + hit;
+          status[u] = ST_HIT;
+        } else {
+          status[u] = ST_MISS;
+        }
+      }
+    }
+    __syncthreads();
+    // phase 2: rank the evictable ways
+    const int32_t my_ts = l_ts[lane];
+    const bool cand = lane < W && my_ts < k;
+    int rank = 0;
+    for (int w = 0; w < W; w++) {
+      const int32_t tw = l_ts[w];
+      if (tw < k && (tw < my_ts || (tw == my_ts && w < lane))) rank++;
+    }
+    const int n_cand = __popcll(__ballot(cand));
+    if (cand) l_way[rank] = lane;
+    __syncthreads();
+    int before = 0;
+    for (int c = u0; c < u1; c += kWave) {
+      const int u = c + lane;
+      const bool miss = u < u1 && status[u] == ST_MISS;
+      const uint64_t mb = __ballot(miss);
+      if (miss) {
+        const int j = before + __popcll(mb & lt_mask);
+        if (j < n_cand) {
+          const int way = l_way[j];
+          old_tag[u] = l_tag[way];
+          old_ts[u] = l_ts[way];
+          l_tag[way] = (int32_t)((uniq_key[u] - key0) * m.sets + set);
+          l_ts[way] = k;
+          loc_u[u] = slot0 + way;
+          status[u] = ST_INSERT;
+        } else {
+          loc_u[u] = -1;
+          status[u] = ST_BYPASS;
+        }
+      }
+      before += __popcll(mb);
+    }
+    __syncthreads();
+    if (lane < W) {
+      tags[slot0 + lane] = l_tag[lane];
+      ts[slot0 + lane] = l_ts[lane];
+    }
+  }
+}
+
+// per-lookup location, in input order
+__global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__restrict__ pos,
+                                                       const uint32_t *__restrict__ uid_sorted,
+                                                       const int32_t *__restrict__ loc_u, int32_t *__restrict__ loc,
+                                                       const BatchCounters *cnt) {
+  if (cnt->err) return;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x)
+    loc[pos[i]] = loc_u[uid_sorted[i]];
+}
+
+hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
+                              const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
+                              hipStream_t s) {
+  const int n = (int)b.n;
+  if (n == 0) return hipSuccess;
+  DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid};
+  run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
+  SetHeadOp h{b.uniq_sid, b.run_off, b.touched, b.long_idx};
+  run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
+  hipLaunchKernelGGL(long_runs_kernel, dim3(512), dim3(256), 0, s, b.run_off, b.long_idx, b.cnt);
+  int64_t max_touched = (int64_t)g.total_sets + g.T;
+  if (max_touched > n) max_touched = n;
+  const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
+  hipLaunchKernelGGL(probe_kernel, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key, b.touched,
+                     tags, ts, b.loc_u, b.status, b.old_tag, b.old_ts, b.cnt);
+  StatusOp st{b.status, b.run_off, b.old_tag, b.ins_idx, b.byp_idx, 0u, 0u, 0ull};
+  run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
+  const int fin_blocks = (n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096;
+  hipLaunchKernelGGL(finalize_kernel, dim3(fin_blocks), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.loc,
+                     b.cnt);
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------
+// Data movement: 16 lanes per row, 16 bytes per lane and step; the row and its
+// accumulator travel together.  Host rows are reached through the pinned mapping.
+// --------------------------------------------------------------------------------------
+constexpr int kMoveLanes = 16;
+
+__global__ __launch_bounds__(256) void fill_kernel(const TableMeta *__restrict__ tm, int T,
+                                                   const uint32_t *__restrict__ uniq_key,
+                                                   const int32_t *__restrict__ ins_idx,
+                                                   const int32_t *__restrict__ loc_u,
+                                                   const int32_t *__restrict__ old_tag, float *__restrict__ cache_m,
+                                                   const BatchCounters *cnt, u64 *bytes_h2d, u64 *bytes_d2h) {
+  if (cnt->err) return;
+  const int n_ins = cnt->n_ins;
+  const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
+  const int lig = threadIdx.x % kMoveLanes;
+  const int n_groups = gridDim.x * blockDim.x / kMoveLanes;
+  u64 in_b = 0, out_b = 0;
+  for (int i = group; i < n_ins; i += n_groups) {
+    const int u = ins_idx[i];
+    const uint32_t key = uniq_key[u];
+    const TableMeta &m = tm[find_table(tm, T, key)];
+    const uint32_t row = row_of_key(m, key);
+    const int slot = loc_u[u];
+    const int32_t old = old_tag[u];
+    char *line = m.lines + (size_t)(slot - m.slot_base) * m.row_bytes;
+    const char *src = m.host_w + (size_t)row * m.row_bytes;
+    char *dst = m.host_w + (size_t)(old < 0 ? 0 : old) * m.row_bytes;
+    for (uint32_t c = lig * 16; c < m.row_bytes; c += kMoveLanes * 16) {
+      const uint4 fresh = *(const uint4 *)(src + c);
+      if (old >= 0) *(uint4 *)(dst + c) = *(const uint4 *)(line + c);
+      *(uint4 *)(line + c) = fresh;
+    }
+    if (lig == 0) {
+      const float fresh_m = m.host_m[row];
+      if (old >= 0) {
+        m.host_m[old] = cache_m[slot];
+        out_b += m.row_bytes + 4;
+      }
+      cache_m[slot] = fresh_m;
+      in_b += m.row_bytes + 4;
+    }
+  }
+  for (int d = 32; d >= 1; d >>= 1) {
+    in_b += __shfl_xor(in_b, d);
+    out_b += __shfl_xor(out_b, d);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (in_b) atomicAdd(bytes_h2d, in_b);
+    if (out_b) atomicAdd(bytes_d2h, out_b);
+  }
+}
+
+hipError_t launch_fill(const TableMeta *tm, const Geometry &g, const BatchBuf &b, float *cache_m, u64 *bytes_h2d,
+                       u64 *bytes_d2h, hipStream_t s) {
+  if (b.n == 0 || g.total_slots == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_kernel, dim3(2048), dim3(256), 0, s, tm, g.T, b.uniq_key, b.ins_idx, b.loc_u, b.old_tag,
+                     cache_m, b.cnt, bytes_h2d, bytes_d2h);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void flush_kernel(const TableMeta *__restrict__ tm, int T, int64_t total_slots,
+                                                    const int32_t *__restrict__ tags,
+                                                    const float *__restrict__ cache_m, u64 *bytes_d2h) {
+  const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
+  const int lig = threadIdx.x % kMoveLanes;
+  const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / kMoveLanes;
+  u64 out_b = 0;
+  for (int64_t slot = group; slot < total_slots; slot += n_groups) {
+    const int32_t row = tags[slot];
+    if (row < 0) continue;
+    int lo = 0, hi = T - 1;  // table owning this slot: last t with slot_base <= slot
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if ((int64_t)tm[mid].slot_base <= slot) lo = mid; else hi = mid - 1;
+    }
+    const TableMeta &m = tm[lo];
+    const char *line = m.lines + (size_t)(slot - m.slot_base) * m.row_bytes;
+    char *dst = m.host_w + (size_t)row * m.row_bytes;
+    for (uint32_t c = lig * 16; c < m.row_bytes; c += kMoveLanes * 16) *(uint4 *)(dst + c) = *(const uint4 *)(line + c);
+    if (lig == 0) {
+      m.host_m[row] = cache_m[slot];
+      out_b += m.row_bytes + 4;
+    }
+  }
+  for (int d = 32; d >= 1; d >>= 1) out_b += __shfl_xor(out_b, d);
+  if ((threadIdx.x & 63) == 0 && out_b) atomicAdd(bytes_d2h, out_b);
+}
+
+hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, float *cache_m, u64 *bytes_d2h,
+                        hipStream_t s) {
+  if (g.total_slots == 0) return hipSuccess;
+  hipLaunchKernelGGL(flush_kernel, dim3(2048), dim3(256), 0, s, tm, g.T, g.total_slots, tags, cache_m, bytes_d2h);
+  return hipGetLastError();
+}
+
+}  // namespace tbe

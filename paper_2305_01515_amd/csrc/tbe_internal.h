@@ -1,0 +1,147 @@
+// Internal declarations shared by the HIP translation units of libtbe (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tbe {
+
+constexpr int kWave = 64;                 // CDNA wavefront width
+constexpr uint32_t kNoSet = 0xFFFFFFFFu;  // global set id of rows of a table without cache
+constexpr int kLongRun = 64;              // rows with more lookups than this take the block-wide backward
+
+enum Status : uint8_t { ST_MISS = 0, ST_HIT = 1, ST_INSERT = 2, ST_BYPASS = 3 };
+
+// Per-table constants, resident in device memory (array of T).
+//
+// Sort key of (table t, row r): key_base + (r mod S) * rows_per_set + r div S when the table
+// has S > 0 sets, key_base + r otherwise.  It is a bijection of (t, r), ascending in
+// (table, set, row), so one radix sort groups the lookups by table, set and row at once.
+struct TableMeta {
+  int64_t rows;
+  uint32_t key_base;      // first sort key of this table
+  uint32_t rows_per_set;  // ceil(rows / sets); 0 when sets == 0
+  uint32_t sets;          // S_t
+  uint32_t set_base;      // global id of set 0
+  int32_t slot_base;      // global id of slot 0 (= set_base * ways)
+  int32_t dim;
+  int32_t dtype;          // 0 fp32, 1 fp16
+  int32_t col;            // first output column
+  int32_t lanes;          // lanes per row: 16 bytes of the row per lane
+  uint32_t row_bytes;
+  char *lines;            // device: cache lines of this table [sets*ways, row_bytes]
+  char *host_w;           // pinned host rows [rows, row_bytes]
+  float *host_m;          // pinned host accumulators [rows]
+};
+
+// Device-side scalars of one batch (one per batch buffer).
+struct BatchCounters {
+  int32_t n_uniq;     // distinct (table,row) of the batch
+  int32_t n_touched;  // sets with at least one distinct row (+ pseudo sets of cacheless tables)
+  int32_t n_ins;
+  int32_t n_byp;
+  int32_t n_long;     // distinct rows with more than kLongRun lookups
+  int32_t err;        // TBE_E* found on the device, 0 = none
+  int32_t pad0, pad1;
+  unsigned long long hits, evictions, hit_lookups;
+};
+
+// Arrays of one batch; two of these exist so that batch k+1 can be prepared while
+// batch k is still being trained on.
+struct BatchBuf {
+  // per lookup
+  int32_t *loc;         // [N] location of the lookup's row: global slot id, or -1 = backing tier
+  int32_t *sorted_bag;  // [N] global bag id (t*B + b) of the i-th lookup in sorted order
+  int32_t *bag_of_pos;  // [N] global bag id of lookup j (input order)
+  uint32_t *uid_sorted; // [N] index of the distinct row of the i-th sorted lookup
+  // per distinct row (ascending key)
+  uint32_t *uniq_key;   // [N]
+  int32_t *run_off;     // [N+1] first sorted position of each distinct row; run_off[U] = N
+  uint32_t *uniq_sid;   // [N] global set id or kNoSet
+  int32_t *loc_u;       // [N] global slot id or -1
+  uint8_t *status;      // [N] Status
+  int32_t *old_tag;     // [N] for inserts: row that was evicted, -1 if the entry was free
+  int32_t *old_ts;      // [N] for inserts: timestamp the entry carried
+  uint2 *touched;       // [N] (global set id, first distinct row) of every touched set
+  int32_t *ins_idx;     // [N] distinct-row indices of the inserts, ascending
+  int32_t *byp_idx;     // [N] distinct-row indices of the bypasses, ascending
+  int32_t *long_idx;    // [N / kLongRun + 1] distinct rows with long runs (any order)
+  BatchCounters *cnt;   // device
+  // host-side description
+  const int64_t *d_indices;
+  const int64_t *d_offsets;
+  int32_t batch;
+  int64_t n;
+  int32_t k;
+};
+
+// Scratch shared by all batches (only used inside the prefetch stage, which is serial).
+struct SortScratch {
+  uint32_t *keys[2];
+  uint32_t *vals[2];
+  uint32_t *hist;          // [256 * max sort blocks]
+  unsigned long long *blk; // [scan blocks + 1] block sums of the compaction passes
+};
+
+struct Geometry {
+  int32_t T, ways;
+  int32_t sum_dim;
+  int32_t key_bits;     // bits of the largest sort key
+  uint32_t total_sets;
+  int64_t total_slots;
+};
+
+// Tables grouped by (storage type, lanes per row); forward and backward are launched once
+// per class.  lanes = dim / elements-per-16-bytes rounded up to a power of two.
+constexpr int kMaxClasses = 14;
+struct ClassInfo {
+  int n_classes;
+  int cls_dtype[kMaxClasses];
+  int cls_lanes[kMaxClasses];
+  int cls_count[kMaxClasses];
+  const int32_t *cls_tables[kMaxClasses];  // device: table ids of the class
+  const int32_t *table_class;              // device: class of every table
+};
+
+// ---- launchers (each enqueues on `s` and returns the HIP status of the launch) ----
+
+hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf &b, uint32_t *keys, uint32_t *vals,
+                         hipStream_t s);
+hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *result_buf, hipStream_t s);
+hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
+                              const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
+                              hipStream_t s);
+hipError_t launch_fill(const TableMeta *tm, const Geometry &g, const BatchBuf &b, float *cache_m,
+                       unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
+hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, float *cache_m,
+                        unsigned long long *bytes_d2h, hipStream_t s);
+hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
+                                  float *out, hipStream_t s);
+hipError_t launch_backward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
+                                   const float *grad_out, float *cache_m, float lr, float eps, hipStream_t s);
+
+// ---- small device helpers ----
+
+// table that owns sort key `key`: last t with key_base[t] <= key
+__device__ inline int find_table(const TableMeta *tm, int T, uint32_t key) {
+  int lo = 0, hi = T - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (tm[mid].key_base <= key) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+__device__ inline uint32_t key_of_row(const TableMeta &m, uint32_t row) {
+  if (m.sets == 0) return m.key_base + row;
+  uint32_t q = row / m.sets;
+  return m.key_base + (row - q * m.sets) * m.rows_per_set + q;
+}
+
+__device__ inline uint32_t row_of_key(const TableMeta &m, uint32_t key) {
+  uint32_t local = key - m.key_base;
+  if (m.sets == 0) return local;
+  uint32_t s = local / m.rows_per_set;
+  return (local - s * m.rows_per_set) * m.sets + s;
+}
+
+}  // namespace tbe

@@ -1,0 +1,233 @@
+// Index dedup, part 1: sort keys for every lookup of a batch and a stable LSD radix sort
+// of (key, position) pairs.  The paper does not describe this step; it serves the
+// "group the indices" part of the tag/state lookup (Section 5.5.1) on a 64-wide machine.
+#include "tbe_internal.h"
+
+namespace tbe {
+
+// --------------------------------------------------------------------------------------
+// key generation: 8 lanes per bag, 64-byte coalesced reads of the bag's indices
+// --------------------------------------------------------------------------------------
+constexpr int kKeygenLanes = 8;
+
+__global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict__ tm, int T, int B, int64_t N,
+                                                     const int64_t *__restrict__ indices,
+                                                     const int64_t *__restrict__ offsets, uint32_t *__restrict__ keys,
+                                                     uint32_t *__restrict__ vals, int32_t *__restrict__ bag_of_pos,
+                                                     BatchCounters *cnt) {
+  const int64_t nb = (int64_t)T * B;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t bag = gid / kKeygenLanes;
+  const int sub = (int)(gid % kKeygenLanes);
+  if (bag >= nb) return;
+  int64_t lo = offsets[bag], hi = offsets[bag + 1];
+  bool bad = lo < 0 || hi > N || lo > hi;
+  if (bag == 0 && lo != 0) bad = true;
+  if (bag == nb - 1 && hi != N) bad = true;
+  if (bad) {
+    if (sub == 0) atomicMax(&cnt->err, 1 /* -TBE_EINVAL */);
+    return;
+  }
+  const int t = (int)(bag / B);
+  const TableMeta m = tm[t];
+  for (int64_t j = lo + sub; j < hi; j += kKeygenLanes) {
+    int64_t r = indices[j];
+    if (r < 0 || r >= m.rows) {
+      atomicMax(&cnt->err, 2 /* -TBE_ERANGE */);
+      r = 0;
+    }
+    keys[j] = key_of_row(m, (uint32_t)r);
+    vals[j] = (uint32_t)j;
+    bag_of_pos[j] = (int32_t)bag;
+  }
+}
+
+__global__ void reset_counters_kernel(BatchCounters *cnt) {
+  if (threadIdx.x == 0) {
+    cnt->n_uniq = cnt->n_touched = cnt->n_ins = cnt->n_byp = cnt->n_long = cnt->err = 0;
+    cnt->hits = cnt->evictions = cnt->hit_lookups = 0;
+  }
+}
+
+hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf &b, uint32_t *keys, uint32_t *vals,
+                         hipStream_t s) {
+  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, s, b.cnt);
+  const int64_t threads = (int64_t)g.T * b.batch * kKeygenLanes;
+  if (threads > 0) {
+    const int64_t blocks = (threads + 255) / 256;
+    hipLaunchKernelGGL(keygen_kernel, dim3((unsigned)blocks), dim3(256), 0, s, tm, g.T, b.batch, b.n, b.d_indices,
+                       b.d_offsets, keys, vals, b.bag_of_pos, b.cnt);
+  }
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------
+// LSD radix sort, 8-bit digits, three kernels per pass:
+//   upsweep   : per-block digit histogram of the block's contiguous chunk
+//   scan      : exclusive scan of the [digit][block] table (one block)
+//   downsweep : the block walks its chunk tile by tile; inside a tile every wave ranks
+//               its keys with ballot matching (stable), the tile is ordered by digit in
+//               LDS and written out so that neighbouring lanes hit neighbouring addresses
+// --------------------------------------------------------------------------------------
+constexpr int kSortThreads = 256;
+constexpr int kSortItems = 16;
+constexpr int kSortTile = kSortThreads * kSortItems;  // 4096 keys
+constexpr int kRadix = 256;
+constexpr int kMaxSortBlocks = 1024;
+
+__global__ __launch_bounds__(kSortThreads) void sort_upsweep_kernel(const uint32_t *__restrict__ keys, int n, int shift,
+                                                                    uint32_t mask, int chunk,
+                                                                    uint32_t *__restrict__ hist) {
+  __shared__ uint32_t h[kRadix];
+  const int tid = threadIdx.x;
+  h[tid] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * chunk;
+  const int end = min(n, base + chunk);
+  for (int i = base + tid; i < end; i += kSortThreads) atomicAdd(&h[(keys[i] >> shift) & mask], 1u);
+  __syncthreads();
+  hist[tid * gridDim.x + blockIdx.x] = h[tid];
+}
+
+// exclusive scan of `total` uint32 values in place, one block of 1024 threads
+__global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *data, int total) {
+  __shared__ uint32_t wsum[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (total + 1023) / 1024;
+  const int b = tid * per, e = min(total, b + per);
+  uint32_t s = 0;
+  for (int i = b; i < e; i++) s += data[i];
+  uint32_t incl = s;
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_up(incl, d);
+    if (lane >= d) incl += o;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  uint32_t wbase = 0;
+  for (int w = 0; w < wave; w++) wbase += wsum[w];
+  uint32_t run = wbase + incl - s;
+  for (int i = b; i < e; i++) {
+    uint32_t v = data[i];
+    data[i] = run;
+    run += v;
+  }
+}
+
+__global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
+    const uint32_t *__restrict__ keys_in, const uint32_t *__restrict__ vals_in, uint32_t *__restrict__ keys_out,
+    uint32_t *__restrict__ vals_out, int n, int shift, uint32_t mask, int chunk, const uint32_t *__restrict__ hist) {
+  __shared__ uint32_t s_keys[kSortTile];
+  __shared__ uint32_t s_vals[kSortTile];
+  __shared__ uint32_t s_cnt[4][kRadix];  // per wave and digit: count, later exclusive prefix over waves
+  __shared__ uint32_t s_dstart[kRadix];  // first tile-sorted position of each digit
+  __shared__ uint32_t s_gbase[kRadix];   // next global output position of each digit for this block
+  __shared__ uint32_t s_wtot[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const int block_base = blockIdx.x * chunk;
+  const int block_end = min(n, block_base + chunk);
+  s_gbase[tid] = hist[tid * gridDim.x + blockIdx.x];
+
+  for (int tile = block_base; tile < block_end; tile += kSortTile) {
+    for (int w = 0; w < 4; w++) s_cnt[w][tid] = 0;
+    __syncthreads();
+    uint32_t key[kSortItems], val[kSortItems], rank[kSortItems];
+    const int seg = tile + wave * (kWave * kSortItems);
+#pragma unroll
+    for (int q = 0; q < kSortItems; q++) {
+      const int i = seg + q * kWave + lane;
+      const bool valid = i < block_end;
+      key[q] = valid ? keys_in[i] : 0xFFFFFFFFu;
+      val[q] = valid ? vals_in[i] : 0u;
+    }
+#pragma unroll
+    for (int q = 0; q < kSortItems; q++) {
+      const int i = seg + q * kWave + lane;
+      const bool valid = i < block_end;
+      const uint32_t d = (key[q] >> shift) & mask;
+      uint64_t peers = __ballot(valid);
+#pragma unroll
+      for (int bit = 0; bit < 8; bit++) {
+        const bool on = (d >> bit) & 1u;
+        const uint64_t bal = __ballot(on);
+        peers &= on ? bal : ~bal;
+      }
+      const uint32_t below = __popcll(peers & lt_mask);
+      uint32_t prev = 0;
+      if (valid && below == 0) prev = atomicAdd(&s_cnt[wave][d], (uint32_t)__popcll(peers));
+      const int leader = valid ? (__ffsll((unsigned long long)peers) - 1) : lane;
+      prev = __shfl(prev, leader);
+      rank[q] = prev + below;
+    }
+    __syncthreads();
+    // thread tid owns digit tid: totals, prefix over waves, start of the digit in the tile
+    uint32_t c0 = s_cnt[0][tid], c1 = s_cnt[1][tid], c2 = s_cnt[2][tid], c3 = s_cnt[3][tid];
+    const uint32_t total = c0 + c1 + c2 + c3;
+    s_cnt[0][tid] = 0; s_cnt[1][tid] = c0; s_cnt[2][tid] = c0 + c1; s_cnt[3][tid] = c0 + c1 + c2;
+    uint32_t incl = total;
+    for (int dd = 1; dd < 64; dd <<= 1) {
+      uint32_t o = __shfl_up(incl, dd);
+      if (lane >= dd) incl += o;
+    }
+    if (lane == 63) s_wtot[wave] = incl;
+    __syncthreads();
+    uint32_t wb = 0;
+    for (int w = 0; w < wave; w++) wb += s_wtot[w];
+    const uint32_t dstart = wb + incl - total;
+    s_dstart[tid] = dstart;
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kSortItems; q++) {
+      const int i = seg + q * kWave + lane;
+      if (i < block_end) {
+        const uint32_t d = (key[q] >> shift) & mask;
+        const uint32_t p = s_dstart[d] + s_cnt[wave][d] + rank[q];
+        s_keys[p] = key[q];
+        s_vals[p] = val[q];
+      }
+    }
+    __syncthreads();
+    const int tile_n = min(kSortTile, block_end - tile);
+    for (int p = tid; p < tile_n; p += kSortThreads) {
+      const uint32_t k = s_keys[p];
+      const uint32_t d = (k >> shift) & mask;
+      const uint32_t gpos = s_gbase[d] + ((uint32_t)p - s_dstart[d]);
+      keys_out[gpos] = k;
+      vals_out[gpos] = s_vals[p];
+    }
+    __syncthreads();
+    s_gbase[tid] += total;
+    __syncthreads();
+  }
+}
+
+// Sorts ss.keys[0]/vals[0] (n pairs) by the low g.key_bits bits; *result_buf tells which of
+// the two buffers holds the result.
+hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *result_buf, hipStream_t s) {
+  *result_buf = 0;
+  if (n <= 1) return hipSuccess;
+  const int passes = (g.key_bits + 7) / 8;
+  const int bits = (g.key_bits + passes - 1) / passes;  // balanced digit width <= 8
+  const int64_t tiles = (n + kSortTile - 1) / kSortTile;
+  const int blocks = (int)(tiles < kMaxSortBlocks ? tiles : kMaxSortBlocks);
+  const int64_t tiles_per_block = (tiles + blocks - 1) / blocks;
+  const int chunk = (int)(tiles_per_block * kSortTile);
+  const int used_blocks = (int)((n + chunk - 1) / chunk);
+  int cur = 0;
+  for (int p = 0; p < passes; p++) {
+    const int shift = p * bits;
+    const int w = (g.key_bits - shift) < bits ? (g.key_bits - shift) : bits;
+    const uint32_t mask = (1u << w) - 1u;
+    hipLaunchKernelGGL(sort_upsweep_kernel, dim3(used_blocks), dim3(kSortThreads), 0, s, ss.keys[cur], (int)n, shift,
+                       mask, chunk, ss.hist);
+    hipLaunchKernelGGL(sort_scan_kernel, dim3(1), dim3(1024), 0, s, ss.hist, kRadix * used_blocks);
+    hipLaunchKernelGGL(sort_downsweep_kernel, dim3(used_blocks), dim3(kSortThreads), 0, s, ss.keys[cur], ss.vals[cur],
+                       ss.keys[cur ^ 1], ss.vals[cur ^ 1], (int)n, shift, mask, chunk, ss.hist);
+    cur ^= 1;
+  }
+  *result_buf = cur;
+  return hipGetLastError();
+}
+
+}  // namespace tbe

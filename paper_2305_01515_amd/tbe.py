@@ -1,0 +1,189 @@
+"""Python binding of libtbe (include/tbe.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels of the library; torch is used to
+hold device memory and streams.  There is no fallback: if the library cannot be
+loaded the import of this module's `lib()` fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtbe.so")
+
+FP32, FP16 = 0, 1
+ERRORS = {0: "TBE_OK", -1: "TBE_EINVAL", -2: "TBE_ERANGE", -3: "TBE_EORDER", -4: "TBE_ENOMEM", -5: "TBE_ELIMIT",
+          -6: "TBE_EMISMATCH", -7: "TBE_EHIP"}
+EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "tbe_flush", "tbe_destroy",
+           "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
+           "tbe_host_alloc", "tbe_host_free"]
+
+
+class TableSpec(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("dim", C.c_int32), ("dtype", C.c_int32), ("host_weights", C.c_void_p),
+                ("host_state", C.c_void_p), ("cache_slots", C.c_int64)]
+
+
+class BatchStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in
+                ("lookups", "uniques", "hits", "inserts", "bypasses", "evictions", "hit_lookups")]
+
+    def as_dict(self) -> Dict[str, int]:
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class Stats(C.Structure):
+    _fields_ = [("last", BatchStats), ("total", BatchStats), ("h2d_bytes", C.c_int64), ("d2h_bytes", C.c_int64),
+                ("batch_id", C.c_int32), ("reserved", C.c_int32)]
+
+
+class TbeError(RuntimeError):
+    def __init__(self, code: int, what: str, detail: str = ""):
+        super().__init__(f"{what}: {ERRORS.get(code, code)} {detail}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libtbe.so (building it first only when it does not exist)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        l = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        l.tbe_create.argtypes = [C.POINTER(vp), C.POINTER(TableSpec), i32, i32, i32, i64, vp, vp]
+        l.tbe_prefetch.argtypes = [vp, vp, vp, i32, i64]
+        l.tbe_forward.argtypes = [vp, vp, vp, i32, i64, vp]
+        l.tbe_backward_update.argtypes = [vp, vp, C.c_float, C.c_float]
+        l.tbe_flush.argtypes = [vp]
+        l.tbe_destroy.argtypes = [vp]
+        l.tbe_get_stats.argtypes = [vp, C.POINTER(Stats)]
+        l.tbe_num_sets.argtypes = [vp, i32]
+        l.tbe_num_sets.restype = i64
+        l.tbe_export_cache_state.argtypes = [vp, i32, vp, vp]
+        l.tbe_export_batch_events.argtypes = [vp, i32, i64, vp, vp, vp, vp]
+        l.tbe_export_batch_events.restype = i64
+        l.tbe_last_error.argtypes = [vp]
+        l.tbe_last_error.restype = C.c_char_p
+        l.tbe_host_alloc.argtypes = [C.POINTER(vp), C.c_size_t]
+        l.tbe_host_free.argtypes = [vp]
+        _lib = l
+    return _lib
+
+
+def pinned_empty(shape, dtype: torch.dtype) -> torch.Tensor:
+    """A new pinned (device-visible) host tensor for the backing tier."""
+    return torch.empty(shape, dtype=dtype, pin_memory=True)
+
+
+class TBE:
+    """One handle of the library.  weights[t]: pinned host tensor [rows, dim] fp32 or
+    fp16; state[t]: pinned host float32 [rows].  Both are the backing tier and are
+    read and written by the GPU."""
+
+    def __init__(self, weights: Sequence[torch.Tensor], state: Sequence[torch.Tensor], cache_slots: Sequence[int],
+                 ways: int, max_batch: int, max_lookups: int, overlap: bool = True):
+        self._h = C.c_void_p()
+        T = len(weights)
+        self.T, self.ways = T, ways
+        self.weights, self.state = list(weights), list(state)
+        specs = (TableSpec * T)()
+        self.dims: List[int] = []
+        for t, (w, m) in enumerate(zip(weights, state)):
+            if w.device.type != "cpu" or m.device.type != "cpu" or not w.is_pinned() or not m.is_pinned():
+                raise ValueError("backing tier tensors must be pinned host tensors")
+            if not (w.is_contiguous() and m.is_contiguous() and m.dtype == torch.float32):
+                raise ValueError("backing tier tensors must be contiguous; state must be float32")
+            dt = {torch.float32: FP32, torch.float16: FP16}[w.dtype]
+            specs[t] = TableSpec(w.shape[0], w.shape[1], dt, w.data_ptr(), m.data_ptr(), int(cache_slots[t]))
+            self.dims.append(int(w.shape[1]))
+        self.sum_dim = sum(self.dims)
+        self.compute_stream = torch.cuda.current_stream()
+        self.aux_stream = torch.cuda.Stream() if overlap else self.compute_stream
+        rc = lib().tbe_create(C.byref(self._h), specs, T, ways, max_batch, max_lookups,
+                              C.c_void_p(self.compute_stream.cuda_stream), C.c_void_p(self.aux_stream.cuda_stream))
+        if rc:
+            raise TbeError(rc, "tbe_create", lib().tbe_last_error(None).decode())
+        self._keep: List[Tuple[torch.Tensor, ...]] = []
+
+    def _check(self, rc: int, what: str):
+        if rc:
+            raise TbeError(rc, what, lib().tbe_last_error(self._h).decode())
+
+    def close(self):
+        if self._h:
+            lib().tbe_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _batch_of(offsets: torch.Tensor, T: int) -> int:
+        return (offsets.numel() - 1) // T
+
+    def prefetch(self, indices: torch.Tensor, offsets: torch.Tensor):
+        assert indices.is_cuda and offsets.is_cuda and indices.dtype == torch.int64 and offsets.dtype == torch.int64
+        self._keep.append((indices, offsets))
+        self._keep = self._keep[-4:]
+        self._check(lib().tbe_prefetch(self._h, indices.data_ptr(), offsets.data_ptr(),
+                                       self._batch_of(offsets, self.T), indices.numel()), "tbe_prefetch")
+
+    def forward(self, indices: torch.Tensor, offsets: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        B = self._batch_of(offsets, self.T)
+        if out is None:
+            out = torch.empty(B, self.sum_dim, dtype=torch.float32, device=indices.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == B * self.sum_dim
+        self._keep.append((indices, offsets, out))
+        self._keep = self._keep[-4:]
+        self._check(lib().tbe_forward(self._h, indices.data_ptr(), offsets.data_ptr(), B, indices.numel(),
+                                      out.data_ptr()), "tbe_forward")
+        return out
+
+    def backward_update(self, grad_out: torch.Tensor, lr: float, eps: float):
+        assert grad_out.is_cuda and grad_out.dtype == torch.float32 and grad_out.is_contiguous()
+        self._keep.append((grad_out,))
+        self._check(lib().tbe_backward_update(self._h, grad_out.data_ptr(), lr, eps), "tbe_backward_update")
+
+    def flush(self):
+        self._check(lib().tbe_flush(self._h), "tbe_flush")
+
+    def stats(self) -> Dict[str, object]:
+        s = Stats()
+        self._check(lib().tbe_get_stats(self._h, C.byref(s)), "tbe_get_stats")
+        return {"last": s.last.as_dict(), "total": s.total.as_dict(), "h2d_bytes": int(s.h2d_bytes),
+                "d2h_bytes": int(s.d2h_bytes), "batch_id": int(s.batch_id)}
+
+    def num_sets(self, t: int) -> int:
+        return int(lib().tbe_num_sets(self._h, t))
+
+    def cache_state(self, t: int) -> Tuple[np.ndarray, np.ndarray]:
+        n = self.num_sets(t) * self.ways
+        tags = np.empty(n, dtype=np.int64)
+        ts = np.empty(n, dtype=np.int32)
+        self._check(lib().tbe_export_cache_state(self._h, t, tags.ctypes.data, ts.ctypes.data), "tbe_export_cache_state")
+        return tags, ts
+
+    def events(self, kind: str):
+        """kind 'hit' / 'bypass': (table, row); 'insert': (table, row, slot, old)."""
+        kid = {"hit": 0, "insert": 1, "bypass": 2}[kind]
+        n = int(lib().tbe_export_batch_events(self._h, kid, 0, None, None, None, None))
+        if n < 0:
+            self._check(n, "tbe_export_batch_events")
+        arrs = [np.empty(n, dtype=np.int64) for _ in range(4)]
+        got = int(lib().tbe_export_batch_events(self._h, kid, n, *[a.ctypes.data for a in arrs]))
+        if got < 0:
+            self._check(got, "tbe_export_batch_events")
+        return tuple(arrs) if kid == 1 else (arrs[0], arrs[1])

@@ -1,0 +1,54 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI (ctypes)."""
+import pytest
+import torch
+
+from paper_2305_01515_amd import synth
+from parity_util import run_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def small_cfg(dtype, ways, seed, batch=96):
+    """Mixed little model: dims from 4/8 up to the largest supported, set counts that are
+    not powers of two, one table without cache, one fully cached, empty bags, a table
+    whose batch overflows its sets (bypass), long runs (hot rows)."""
+    epl = 4 if dtype == synth.FP32 else 8
+    T = synth.TableCfg
+    tabs = [
+        T(5000, epl, dtype, 1.05, "poisson", 6, 0, 40, cache_slots=7 * ways),
+        T(3001, 64, dtype, 1.2, "poisson", 20, 1, 100, cache_slots=13 * ways),
+        T(777, 128, dtype, None, "fixed", 3, cache_slots=0),
+        T(4 * ways, 8 * epl, dtype, 0.9, "poisson", 1, 0, 8, cache_slots=4 * ways),
+        T(20000, 64 * epl, dtype, 1.3, "poisson", 30, 0, 200, cache_slots=2 * ways),
+        T(100000, 24 * epl, dtype, 1.1, "fixed", 11, cache_slots=ways * 301 + 5),
+    ]
+    return synth.WorkloadCfg("small", tabs, batch=batch, ways=ways, steps=6, seed=seed, init_std=0.05, lr=0.05)
+
+
+@pytest.mark.parametrize("dtype", [synth.FP32, synth.FP16])
+@pytest.mark.parametrize("ways", [1, 8, 32, 64])
+def test_small_mixed_model_serial(dtype, ways):
+    run_parity(small_cfg(dtype, ways, seed=10 + ways), steps=6, order="serial")
+
+
+@pytest.mark.parametrize("order", ["inline", "ahead", "early"])
+@pytest.mark.parametrize("overlap", [True, False])
+def test_small_mixed_model_call_orders(order, overlap):
+    run_parity(small_cfg(synth.FP16, 16, seed=77), steps=7, order=order, overlap=overlap)
+
+
+def test_ragged_sizes_span_tiles():
+    # more lookups than one sort tile per block and a ragged tail; batch not a multiple of anything
+    cfg = small_cfg(synth.FP32, 32, seed=5, batch=1531)
+    run_parity(cfg, steps=3, order="serial")
+
+
+def test_tiny_config_full():
+    cfg = synth.config_tiny()
+    st = run_parity(cfg, steps=cfg.steps, order="serial")
+    assert st["total"]["lookups"] == 20 * 4 * 512 * 20
+
+
+def test_tiny_config_prefetch_ahead():
+    cfg = synth.config_tiny()
+    run_parity(cfg, steps=cfg.steps, order="ahead")
