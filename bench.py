@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the cached embedding-bag training path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: prefetch (dedup, probe/LRU,
+compaction, write-back + fill), pooled forward, backward with fused row-wise Adagrad.
+The workload is the 32-table configuration (32 x 1M rows x dim 128 fp16, batch 8192,
+pooling Poisson(30), Zipf 1.1, 64-way cache holding 5 % of the rows, backing tier in
+pinned host memory, next-batch prefetch issued ahead of training).  All inputs of the
+timed steps are generated beforehand and resident in HBM.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+HOST_LINK_PEAK_GBS = 64.0  # PCIe Gen5 x16, per direction
+
+
+def algorithmic_bytes(cfg, lookups_per_table, uniques_per_table, batch):
+    """Bytes the method itself must move per step, per kernel ('algorithmic bytes')."""
+    from paper_2305_01515_amd import synth
+    fwd = bwd = 0
+    for t, tc in enumerate(cfg.tables):
+        rb = tc.dim * (4 if tc.dtype == synth.FP32 else 2)
+        fwd += lookups_per_table[t] * rb + 4 * lookups_per_table[t]          # rows + locations
+        bwd += uniques_per_table[t] * (2 * rb + 8)                           # row read-modify-write + state
+    fwd += 4 * batch * cfg.sum_dim                                           # pooled output
+    bwd += 4 * batch * cfg.sum_dim                                           # grad_out, read at least once
+    return fwd, bwd
+
+
+def cpu_baseline(cfg, W0, batches, grads, threads):
+    """The oracle as it stands, timed on this machine's host cores on the first batches."""
+    import numpy as np
+    from oracle import Oracle
+    Wn = [w.numpy().copy() for w in W0]
+    Mn = [np.zeros(w.shape[0], dtype=np.float32) for w in W0]
+    o = Oracle(Wn, Mn, [t.cache_slots for t in cfg.tables], cfg.ways, threads=threads)
+    n = 0
+    t0 = time.perf_counter()
+    for (idx, off), g in zip(batches, grads):
+        o.prefetch(idx, off)
+        o.forward()
+        o.backward_update(g, cfg.lr, cfg.eps)
+        n += idx.size
+        if time.perf_counter() - t0 > 20.0:
+            break
+    dt = time.perf_counter() - t0
+    o.close()
+    return n / dt, n
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--tables", type=int, default=32, help="(debug) fewer tables than the named workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="run everything on one stream")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2305_01515_amd import synth
+    from paper_2305_01515_amd.tbe import TBE
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda"
+    K, Wm = args.steps, args.warmup
+    cfg = synth.config_main(tables=args.tables)
+    T = cfg.num_tables
+
+    # backing tier: pinned host tables, initialised on the GPU and copied over
+    Wp, Mp = [], []
+    for t, tc in enumerate(cfg.tables):
+        w = torch.empty(tc.rows, tc.dim, dtype=torch.float16, pin_memory=True)
+        synth.init_table(cfg, t, device=dev, out=w)
+        Wp.append(w)
+        Mp.append(torch.zeros(tc.rows, dtype=torch.float32, pin_memory=True))
+    torch.cuda.synchronize()
+
+    # inputs of all steps, resident in HBM before anything is timed
+    stream = synth.BatchStream(cfg, device=dev)
+    batches = [stream.next() for _ in range(K + Wm + 1)]
+    grads = [synth.grad_out(cfg, s + 1, device=dev) for s in range(min(K + Wm, 6))]
+    max_n = max(int(b[0].numel()) for b in batches)
+    out = torch.empty(cfg.batch, cfg.sum_dim, dtype=torch.float32, device=dev)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        nb = 3
+        v, n = cpu_baseline(cfg, Wp, [(b[0].cpu().numpy(), b[1].cpu().numpy()) for b in batches[:nb]],
+                            [g.cpu().numpy() for g in grads[:nb]], threads)
+        cpu = {"value": v, "unit": "lookups/s", "cores": threads, "kind": "oracle",
+               "sample": f"first batches of the same stream from a cold cache ({n} lookups), oracle -O2, OpenMP over tables"}
+
+    g = TBE(Wp, Mp, [tc.cache_slots for tc in cfg.tables], cfg.ways, cfg.batch, max_n + 1, overlap=not args.no_overlap)
+
+    def run(lo, hi):
+        # next-batch prefetch is issued ahead of the current batch's training
+        for s in range(lo, hi):
+            g.prefetch(*batches[s + 1])
+            g.forward(batches[s][0], batches[s][1], out)
+            g.backward_update(grads[s % len(grads)], cfg.lr, cfg.eps)
+
+    g.prefetch(*batches[0])
+    run(0, Wm)
+    torch.cuda.synchronize()
+    s0 = g.stats()
+    g.set_profiling(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(Wm, Wm + K)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    s1 = g.stats()
+    times = {k: g.stage_times(k) for k in ("prefetch", "fill", "forward", "backward_long", "backward_short")}
+
+    # the timed region trained batches Wm..Wm+K-1; it prefetched batches Wm+1..Wm+K (one ahead)
+    lookups = sum(int(batches[s][0].numel()) for s in range(Wm, Wm + K))
+    tot = {k: s1["total"][k] - s0["total"][k] for k in s1["total"]}
+    npf = K  # one prefetch per timed step
+    h2d = (s1["h2d_bytes"] - s0["h2d_bytes"]) / npf
+    d2h = (s1["d2h_bytes"] - s0["d2h_bytes"]) / npf
+
+    # per-table counts for the algorithmic bytes (from the offsets; uniques from the library's counters)
+    off = batches[Wm][1].cpu()
+    per_table = [int(off[(t + 1) * cfg.batch] - off[t * cfg.batch]) for t in range(T)]
+    scale = (lookups / K) / max(1, sum(per_table))
+    per_table = [p * scale for p in per_table]
+    uniq_per_table = [tot["uniques"] / npf / T] * T
+    fwd_b, bwd_b = algorithmic_bytes(cfg, per_table, uniq_per_table, cfg.batch)
+
+    ms = {k: float(np.mean(v)) if v.size else 0.0 for k, v in times.items()}
+    fwd_gbs = fwd_b / (ms["forward"] * 1e-3) / 1e9 if ms["forward"] else 0.0
+    bwd_ms = ms["backward_long"] + ms["backward_short"]
+    bwd_gbs = bwd_b / (bwd_ms * 1e-3) / 1e9 if bwd_ms else 0.0
+    fill_ms = ms["fill"]
+    res = {
+        "metric": "pooled lookups/s (fwd+bwd+update), achieved HBM GB/s, cache hit rate",
+        "value": lookups / dt,
+        "unit": "lookups/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": dt / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 storage / f32 accumulate", "data": "synthetic",
+        "config": {"workload": "32 tables x 1M rows x dim 128 fp16, batch 8192, pooling Poisson(30) in [1,200], "
+                               "Zipf 1.1, 64-way LRU cache 5% of rows in HBM, backing tier in pinned host memory, "
+                               "next-batch prefetch ahead of training",
+                   "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
+                   "overlap": not args.no_overlap},
+        "roofline": {"kernel": "forward_kernel<fp16, 16 lanes/row> (pooled gather, hit path)",
+                     "bound": "hbm", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": fwd_b, "ms_per_launch": ms["forward"]},
+        "backward": {"kernels": "backward_long_kernel + backward_short_kernel (gradient reduction + row-wise Adagrad)",
+                     "achieved": bwd_gbs, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
+                     "bytes_per_step": bwd_b, "ms_long": ms["backward_long"], "ms_short": ms["backward_short"]},
+        "hit_path": {"ms_fwd_bwd": ms["forward"] + bwd_ms,
+                     "lookups_per_s": (lookups / K) / ((ms["forward"] + bwd_ms) * 1e-3) if bwd_ms else 0.0,
+                     "hbm_frac": (fwd_b + bwd_b) / ((ms["forward"] + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS if bwd_ms else 0.0},
+        "prefetch_stage_ms": ms["prefetch"],
+        "host_link": {"ms_fill": fill_ms, "h2d_bytes_per_step": h2d, "d2h_bytes_per_step": d2h,
+                      "h2d_GBps": h2d / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0,
+                      "d2h_GBps": d2h / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0,
+                      "peak_GBps_per_direction": HOST_LINK_PEAK_GBS,
+                      "frac": max(h2d, d2h) / (fill_ms * 1e-3) / 1e9 / HOST_LINK_PEAK_GBS if fill_ms else 0.0},
+        "cache": {"hit_rate_unique": tot["hits"] / max(1, tot["uniques"]),
+                  "hit_rate_lookup": tot["hit_lookups"] / max(1, tot["lookups"]),
+                  "bypass_frac_unique": tot["bypasses"] / max(1, tot["uniques"]),
+                  "uniques_per_step": tot["uniques"] / npf},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(res))
+    g.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -98,7 +98,7 @@ typedef struct {
  *   specs, num_tables : HOST array of table descriptions (copied).
  *   ways              : associativity W, 1..64 (one 64-lane wavefront handles one set).
  *   max_batch         : largest `batch` (samples) of any later call.
- *   max_lookups       : largest `num_lookups` of any later call (< 2^31).
+ *   max_lookups       : largest `num_lookups` of any later call (at most 2^30).
  *   compute_stream    : hipStream_t on which forward / backward run (NULL = default stream).
  *   aux_stream        : hipStream_t on which prefetch work runs; may equal compute_stream
  *                       (then nothing overlaps).  Both must have the default priority.
@@ -167,6 +167,23 @@ int tbe_destroy(tbe_handle h);
  * hit_lookups / lookups; requests reaching the backing tier = (1 - hit rate) * requests
  * (Section 4.2, Eq. 4 with alpha the miss ratio). */
 int tbe_get_stats(tbe_handle h, tbe_stats *out);
+
+/*
+ * Stage timing for measurement (not described by the paper).  While enabled, every call
+ * brackets the kernels of each stage with HIP timing events on the stream they are
+ * launched on; tbe_get_stage_times returns the elapsed milliseconds of every bracket
+ * recorded since profiling was switched on, in call order (at most 16384 per stage).
+ * Both calls synchronise; tbe_set_profiling discards earlier records.
+ * With h_ms NULL, tbe_get_stage_times returns the number of records.
+ */
+#define TBE_STAGE_PREFETCH 0       /* key generation, sort, dedup, probe, compaction (aux stream) */
+#define TBE_STAGE_FILL 1           /* write-back of victims and fetch of missed rows (aux stream) */
+#define TBE_STAGE_FORWARD 2        /* pooled lookup (compute stream)                              */
+#define TBE_STAGE_BACKWARD_LONG 3  /* backward of rows with many lookups (compute stream)         */
+#define TBE_STAGE_BACKWARD_SHORT 4 /* backward of all other rows (compute stream)                 */
+#define TBE_NUM_STAGES 5
+int tbe_set_profiling(tbe_handle h, int32_t enable);
+int64_t tbe_get_stage_times(tbe_handle h, int32_t stage, int64_t capacity, float *h_ms);
 
 /* Sets and slots of a table's cache: S_t (and S_t * ways slots). */
 int64_t tbe_num_sets(tbe_handle h, int32_t table);

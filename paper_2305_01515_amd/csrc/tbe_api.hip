@@ -63,6 +63,9 @@ struct tbe_ctx {
   int64_t total_lookups = 0;
   int sticky = 0;
   std::string err;
+  // optional stage timing: (start, stop) event pairs per stage, in call order
+  bool profiling = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[TBE_NUM_STAGES];
 };
 
 namespace {
@@ -81,6 +84,31 @@ int hipfail(tbe_ctx *h, hipError_t e, const char *what) {
     hipError_t e__ = (call);                              \
     if (e__ != hipSuccess) return hipfail(h, e__, #call); \
   } while (0)
+
+constexpr size_t kMaxProfiledCalls = 16384;
+
+// Brackets the launches of one stage with timing events on the stream they go to.
+struct StageTimer {
+  tbe_ctx *h;
+  hipStream_t s;
+  hipEvent_t stop = nullptr;
+  StageTimer(tbe_ctx *h_, int stage, hipStream_t s_) : h(h_), s(s_) {
+    if (!h->profiling || h->prof[stage].size() >= kMaxProfiledCalls) return;
+    hipEvent_t a = nullptr, b = nullptr;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { if (a) (void)hipEventDestroy(a); return; }
+    (void)hipEventRecord(a, s);
+    h->prof[stage].emplace_back(a, b);
+    stop = b;
+  }
+  ~StageTimer() { if (stop) (void)hipEventRecord(stop, s); }
+};
+
+void drop_profile(tbe_ctx *h) {
+  for (auto &v : h->prof) {
+    for (auto &p : v) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+    v.clear();
+  }
+}
 
 int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 
@@ -148,7 +176,10 @@ int sync_all(tbe_ctx *h) {
 // Cache -> cache copies for buffer `bi`, then mark the batch ready for forward.
 int enqueue_fill(tbe_ctx *h, int bi) {
   BatchBuf &b = h->buf[bi];
-  HIP_TRY(h, launch_fill(h->d_tm, h->g, b, h->cache_m, h->d_bytes, h->d_bytes + 1, h->as));
+  {
+    StageTimer tm_(h, TBE_STAGE_FILL, h->as);
+    HIP_TRY(h, launch_fill(h->d_tm, h->g, b, h->cache_m, h->d_bytes, h->d_bytes + 1, h->as));
+  }
   HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->as));
   return TBE_OK;
 }
@@ -171,13 +202,16 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     HIP_TRY(h, hipEventRecord(h->ev_inputs, h->cs));
     HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_inputs, 0));
   }
-  HIP_TRY(h, launch_keygen(h->d_tm, h->g, b, h->ss.keys[0], h->ss.vals[0], h->as));
-  int res = 0;
-  HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
-  HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->as));
-  hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total);
-  hipLaunchKernelGGL(add_totals64_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_bytes + 2);
-  HIP_TRY(h, hipGetLastError());
+  {
+    StageTimer tm_(h, TBE_STAGE_PREFETCH, h->as);
+    HIP_TRY(h, launch_keygen(h->d_tm, h->g, b, h->ss.keys[0], h->ss.vals[0], h->as));
+    int res = 0;
+    HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
+    HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->as));
+    hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total);
+    hipLaunchKernelGGL(add_totals64_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_bytes + 2);
+    HIP_TRY(h, hipGetLastError());
+  }
   h->pend[h->n_pend++] = bi;
   if (in_flight) {
     h->deferred = bi;  // its copies must not touch rows the batch in flight still uses
@@ -206,6 +240,7 @@ int tbe_destroy(tbe_handle h) {
   (void)hipStreamSynchronize(h->as);
   (void)hipStreamSynchronize(h->cs);
   h->mem.release();
+  drop_profile(h);
   if (h->ev_inputs) (void)hipEventDestroy(h->ev_inputs);
   for (int i = 0; i < 2; i++) {
     if (h->ev_ready[i]) (void)hipEventDestroy(h->ev_ready[i]);
@@ -376,7 +411,10 @@ int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets
   h->pend[0] = h->pend[1];
   h->n_pend--;
   if (h->as != h->cs) HIP_TRY(h, hipStreamWaitEvent(h->cs, h->ev_ready[bi], 0));
-  HIP_TRY(h, launch_forward_classes(h->d_tm, h->ci, h->g, b, d_out, h->cs));
+  {
+    StageTimer tm_(h, TBE_STAGE_FORWARD, h->cs);
+    HIP_TRY(h, launch_forward_classes(h->d_tm, h->ci, h->g, b, d_out, h->cs));
+  }
   h->current = bi;
   return TBE_OK;
 }
@@ -387,7 +425,14 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   if (!d_grad_out) return fail(h, TBE_EINVAL, "backward_update: null gradient");
   if (h->current < 0) return fail(h, TBE_EORDER, "backward_update: no forwarded batch");
   const int bi = h->current;
-  HIP_TRY(h, launch_backward_classes(h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, lr, eps, h->cs));
+  {
+    StageTimer tm_(h, TBE_STAGE_BACKWARD_LONG, h->cs);
+    HIP_TRY(h, launch_backward_classes(true, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, lr, eps, h->cs));
+  }
+  {
+    StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
+    HIP_TRY(h, launch_backward_classes(false, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, lr, eps, h->cs));
+  }
   h->current = -1;
   if (h->as != h->cs) {
     HIP_TRY(h, hipEventRecord(h->ev_trained[bi], h->cs));
@@ -411,6 +456,26 @@ int tbe_flush(tbe_handle h) {
   rc = sync_all(h);
   if (rc) return rc;
   return collect_device_errors(h);
+}
+
+int tbe_set_profiling(tbe_handle h, int32_t enable) {
+  if (!h) return TBE_EINVAL;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  drop_profile(h);
+  h->profiling = enable != 0;
+  return TBE_OK;
+}
+
+int64_t tbe_get_stage_times(tbe_handle h, int32_t stage, int64_t capacity, float *h_ms) {
+  if (!h || stage < 0 || stage >= TBE_NUM_STAGES) return TBE_EINVAL;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  const auto &v = h->prof[stage];
+  if (!h_ms) return (int64_t)v.size();
+  if (capacity < (int64_t)v.size()) return fail(h, TBE_ELIMIT, "get_stage_times: capacity too small");
+  for (size_t i = 0; i < v.size(); i++) HIP_TRY(h, hipEventElapsedTime(&h_ms[i], v[i].first, v[i].second));
+  return (int64_t)v.size();
 }
 
 int64_t tbe_num_sets(tbe_handle h, int32_t table) {

@@ -250,13 +250,15 @@ static void fwd_one(const TableMeta *tm, const int32_t *tables, int count, const
 }
 
 template <int DT, int G>
-static void bwd_one(const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g, const BatchBuf &b,
-                    const float *grad_out, float *cache_m, float lr, float eps, hipStream_t s) {
-  hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(1024), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                     b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, b.long_idx, grad_out, cache_m, lr, eps, table_class,
-                     b.cnt);
-  hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                     b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, grad_out, cache_m, lr, eps, table_class, b.cnt);
+static void bwd_one(bool long_rows, const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g,
+                    const BatchBuf &b, const float *grad_out, float *cache_m, float lr, float eps, hipStream_t s) {
+  if (long_rows)
+    hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(1024), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
+                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, b.long_idx, grad_out, cache_m, lr, eps,
+                       table_class, b.cnt);
+  else
+    hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
+                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, grad_out, cache_m, lr, eps, table_class, b.cnt);
 }
 
 #define TBE_DISPATCH(DT, LANES, CALL)                         \
@@ -292,12 +294,15 @@ hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, cons
   return hipGetLastError();
 }
 
-hipError_t launch_backward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
-                                   const float *grad_out, float *cache_m, float lr, float eps, hipStream_t s) {
+// long_rows selects the block-per-row kernel (rows with more than kLongRun lookups) or the
+// group-per-row kernel (all other rows); a step runs both, they touch disjoint rows.
+hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
+                                   const BatchBuf &b, const float *grad_out, float *cache_m, float lr, float eps,
+                                   hipStream_t s) {
   if (b.n == 0) return hipSuccess;
   for (int c = 0; c < ci.n_classes; c++)
     TBE_DISPATCH(ci.cls_dtype[c], ci.cls_lanes[c],
-                 (bwd_one<d, l>(tm, c, ci.table_class, g, b, grad_out, cache_m, lr, eps, s)));
+                 (bwd_one<d, l>(long_rows, tm, c, ci.table_class, g, b, grad_out, cache_m, lr, eps, s)));
   return hipGetLastError();
 }
 

@@ -116,8 +116,9 @@ hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *t
                         unsigned long long *bytes_d2h, hipStream_t s);
 hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
                                   float *out, hipStream_t s);
-hipError_t launch_backward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
-                                   const float *grad_out, float *cache_m, float lr, float eps, hipStream_t s);
+hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
+                                   const BatchBuf &b, const float *grad_out, float *cache_m, float lr, float eps,
+                                   hipStream_t s);
 
 // ---- small device helpers ----
 

@@ -21,7 +21,8 @@ ERRORS = {0: "TBE_OK", -1: "TBE_EINVAL", -2: "TBE_ERANGE", -3: "TBE_EORDER", -4:
           -6: "TBE_EMISMATCH", -7: "TBE_EHIP"}
 EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "tbe_flush", "tbe_destroy",
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
-           "tbe_host_alloc", "tbe_host_free"]
+           "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times"]
+STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4}
 
 
 class TableSpec(C.Structure):
@@ -76,6 +77,9 @@ def lib() -> C.CDLL:
         l.tbe_last_error.restype = C.c_char_p
         l.tbe_host_alloc.argtypes = [C.POINTER(vp), C.c_size_t]
         l.tbe_host_free.argtypes = [vp]
+        l.tbe_set_profiling.argtypes = [vp, i32]
+        l.tbe_get_stage_times.argtypes = [vp, i32, i64, vp]
+        l.tbe_get_stage_times.restype = i64
         _lib = l
     return _lib
 
@@ -155,6 +159,7 @@ class TBE:
     def backward_update(self, grad_out: torch.Tensor, lr: float, eps: float):
         assert grad_out.is_cuda and grad_out.dtype == torch.float32 and grad_out.is_contiguous()
         self._keep.append((grad_out,))
+        self._keep = self._keep[-6:]
         self._check(lib().tbe_backward_update(self._h, grad_out.data_ptr(), lr, eps), "tbe_backward_update")
 
     def flush(self):
@@ -165,6 +170,21 @@ class TBE:
         self._check(lib().tbe_get_stats(self._h, C.byref(s)), "tbe_get_stats")
         return {"last": s.last.as_dict(), "total": s.total.as_dict(), "h2d_bytes": int(s.h2d_bytes),
                 "d2h_bytes": int(s.d2h_bytes), "batch_id": int(s.batch_id)}
+
+    def set_profiling(self, enable: bool):
+        self._check(lib().tbe_set_profiling(self._h, 1 if enable else 0), "tbe_set_profiling")
+
+    def stage_times(self, stage: str) -> np.ndarray:
+        """milliseconds of every recorded bracket of a stage (see STAGES)"""
+        sid = STAGES[stage]
+        n = int(lib().tbe_get_stage_times(self._h, sid, 0, None))
+        if n < 0:
+            self._check(n, "tbe_get_stage_times")
+        ms = np.empty(n, dtype=np.float32)
+        got = int(lib().tbe_get_stage_times(self._h, sid, n, ms.ctypes.data))
+        if got < 0:
+            self._check(got, "tbe_get_stage_times")
+        return ms
 
     def num_sets(self, t: int) -> int:
         return int(lib().tbe_num_sets(self._h, t))

@@ -42,17 +42,28 @@ def make_backing(cfg, device="cpu"):
     return Wn, Mn, Wp, Mp
 
 
-def compare_cache_step(o: Oracle, g, T: int, ctx: str):
-    so, sg = o.stats()[0], g.stats()["last"]
+def _canon(arrs):
+    """event arrays -> rows sorted lexicographically (events are compared as sets)"""
+    m = np.stack([np.asarray(a, dtype=np.int64) for a in arrs], axis=1) if len(arrs[0]) else np.zeros((0, len(arrs)), np.int64)
+    return m[np.lexsort(m.T[::-1])] if m.shape[0] else m
+
+
+def gpu_snapshot(g, T: int):
+    """counters, event sets and cache state of the library right after a prefetch"""
+    return {"stats": g.stats()["last"],
+            "events": {k: _canon(g.events(k)) for k in ("hit", "insert", "bypass")},
+            "state": [g.cache_state(t) for t in range(T)]}
+
+
+def compare_cache_step(o: Oracle, snap, T: int, ctx: str):
+    so, sg = o.stats()[0], snap["stats"]
     assert so == sg, f"{ctx}: counters differ: oracle {so} gpu {sg}"
     for kind in ("hit", "insert", "bypass"):
-        eo, eg = o.events(kind), g.events(kind)
-        so_ = sorted(zip(*[a.tolist() for a in eo]))
-        sg_ = sorted(zip(*[a.tolist() for a in eg]))
-        assert so_ == sg_, f"{ctx}: {kind} events differ ({len(so_)} vs {len(sg_)})"
+        eo, eg = _canon(o.events(kind)), snap["events"][kind]
+        assert eo.shape == eg.shape and np.array_equal(eo, eg), f"{ctx}: {kind} events differ ({len(eo)} vs {len(eg)})"
     for t in range(T):
         to, tso = o.cache_state(t)
-        tg, tsg = g.cache_state(t)
+        tg, tsg = snap["state"][t]
         assert np.array_equal(to, tg), f"{ctx}: tags of table {t} differ"
         assert np.array_equal(tso, tsg), f"{ctx}: timestamps of table {t} differ"
 
@@ -74,15 +85,18 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str):
 
 
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
-               oracle_threads: int = 8, max_lookups: int = None):
+               oracle_threads: int = 8, max_lookups: int = None, init_device="cpu"):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
-              'early'    prefetch(k+1) is issued before forward(k)"""
+              'early'    prefetch(k+1) is issued before forward(k)
+    Cache state, counters and event sets are compared after every `check_every`-th
+    prefetch (the library's snapshot is taken right after its prefetch call, the oracle,
+    which is strictly sequential, is compared when it reaches that batch)."""
     from paper_2305_01515_amd.tbe import TBE
 
     T = cfg.num_tables
-    Wn, Mn, Wp, Mp = make_backing(cfg)
+    Wn, Mn, Wp, Mp = make_backing(cfg, device=init_device)
     slots = [tc.cache_slots for tc in cfg.tables]
     o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads)
     stream = synth.BatchStream(cfg, device="cpu")
@@ -91,12 +105,19 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         max_lookups = max(int(b[0].numel()) for b in batches) + 1
     g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, max_lookups, overlap=overlap)
     dev = [(i.to(device), f.to(device)) for i, f in batches]
+    snaps = {}
 
-    def oracle_step(s, out_g, cache_checked):
+    def gpu_prefetch(s, explicit=True):
+        if explicit:
+            g.prefetch(*dev[s])
+        if s % check_every == 0 or s == steps - 1:
+            snaps[s] = gpu_snapshot(g, T)
+
+    def oracle_step(s, out_g):
         idx, off = batches[s]
         o.prefetch(idx.numpy(), off.numpy())
-        if cache_checked:
-            compare_cache_step(o, g, T, f"step {s + 1}")
+        if s in snaps:
+            compare_cache_step(o, snaps.pop(s), T, f"step {s + 1}")
         out_o = o.forward()
         compare_forward(cfg, out_o, out_g.cpu().numpy(), f"step {s + 1}")
         o.backward_update(synth.grad_out(cfg, s + 1).numpy(), cfg.lr, cfg.eps)
@@ -104,38 +125,32 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     for s in range(steps):
         go = synth.grad_out(cfg, s + 1).to(device)
         idx, off = dev[s]
-        check = (s % check_every == 0) or s == steps - 1
         if order == "serial":
-            g.prefetch(idx, off)
+            gpu_prefetch(s)
             out = g.forward(idx, off)
             g.backward_update(go, cfg.lr, cfg.eps)
-            oracle_step(s, out, check)
         elif order == "inline":
             out = g.forward(idx, off)
+            gpu_prefetch(s, explicit=False)
             g.backward_update(go, cfg.lr, cfg.eps)
-            oracle_step(s, out, check)
         elif order == "ahead":
             if s == 0:
-                g.prefetch(idx, off)
+                gpu_prefetch(0)
             out = g.forward(idx, off)
             if s + 1 < steps:
-                g.prefetch(*dev[s + 1])
+                gpu_prefetch(s + 1)
             g.backward_update(go, cfg.lr, cfg.eps)
-            # the library's last prefetched batch is s+1: cache state is compared one step late
-            oracle_step(s, out, False)
-            if s + 1 < steps and check:
-                # oracle catches up with prefetch(s+1) at the next iteration; compare there
-                pass
         elif order == "early":
             if s == 0:
-                g.prefetch(idx, off)
+                gpu_prefetch(0)
             if s + 1 < steps:
-                g.prefetch(*dev[s + 1])
+                gpu_prefetch(s + 1)
             out = g.forward(idx, off)
             g.backward_update(go, cfg.lr, cfg.eps)
-            oracle_step(s, out, False)
         else:
             raise ValueError(order)
+        oracle_step(s, out)
+    assert not snaps
     # final cache state must agree whatever the call order was
     for t in range(T):
         to, tso = o.cache_state(t)

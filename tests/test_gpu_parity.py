@@ -52,3 +52,19 @@ def test_tiny_config_full():
 def test_tiny_config_prefetch_ahead():
     cfg = synth.config_tiny()
     run_parity(cfg, steps=cfg.steps, order="ahead")
+
+
+def test_small_model_exercises_every_path():
+    """the mixed model must actually produce hits, evictions, bypasses and long runs"""
+    st = run_parity(small_cfg(synth.FP16, 8, seed=3), steps=6, order="ahead", check_every=2)
+    tot = st["total"]
+    assert tot["hits"] > 0 and tot["evictions"] > 0 and tot["bypasses"] > 0 and tot["inserts"] > tot["evictions"]
+    assert st["h2d_bytes"] > 0 and st["d2h_bytes"] > 0
+
+
+def test_main_config_full_size():
+    """The benchmark's workload at full size (32 tables x 1M rows x dim 128 fp16, batch
+    8192), prefetch issued ahead as bench.py does; every prefetch is compared."""
+    cfg = synth.config_main()
+    st = run_parity(cfg, steps=3, order="ahead", oracle_threads=16, init_device="cuda")
+    assert st["total"]["bypasses"] > 0
