@@ -42,6 +42,7 @@ struct tbe_ctx {
   DevAlloc mem;
   int32_t *tags = nullptr, *ts = nullptr;
   float *cache_m = nullptr;
+  float *partials = nullptr;  // segment sums of the backward's longest rows
   char *lines = nullptr;
   BatchBuf buf[2]{};
   SortScratch ss{};
@@ -145,7 +146,8 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.touched, 8 * N));
   HIP_TRY(h, h->mem.get(&b.ins_idx, 4 * N));
   HIP_TRY(h, h->mem.get(&b.byp_idx, 4 * N));
-  HIP_TRY(h, h->mem.get(&b.long_idx, 4 * (N / kLongRun + 2)));
+  HIP_TRY(h, h->mem.get(&b.items, 16 * (N / kLongRun + N / kSegment + 2)));
+  HIP_TRY(h, h->mem.get(&b.huge, 16 * (N / kSegment + 2)));
   HIP_TRY(h, h->mem.get(&b.cnt, sizeof(BatchCounters)));
   HIP_TRY(h, hipMemset(b.cnt, 0, sizeof(BatchCounters)));
   return TBE_OK;
@@ -375,7 +377,13 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     CREATE_TRY(h->mem.get(&h->ss.keys[i], 4 * N));
     CREATE_TRY(h->mem.get(&h->ss.vals[i], 4 * N));
   }
-  CREATE_TRY(h->mem.get(&h->ss.hist, 4 * 256 * 1024));
+  {
+    int widest = 0;
+    for (const TableMeta &m : h->tm) widest = std::max(widest, m.lanes * (m.dtype == TBE_FP32 ? 4 : 8));
+    h->g.partial_stride = widest;
+    CREATE_TRY(h->mem.get(&h->partials, 4 * (size_t)widest * (2 * (N / kSegment) + 2)));
+  }
+  CREATE_TRY(h->mem.get(&h->ss.hist, 4 * (256 * 1024 + 256)));
   CREATE_TRY(h->mem.get(&h->ss.blk, 8 * 1024));
   CREATE_TRY(h->mem.get(&h->d_total, sizeof(BatchCounters)));
   CREATE_TRY(hipMemset(h->d_total, 0, sizeof(BatchCounters)));
@@ -427,11 +435,11 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   const int bi = h->current;
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_LONG, h->cs);
-    HIP_TRY(h, launch_backward_classes(true, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(true, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, h->partials, lr, eps, h->cs));
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
-    HIP_TRY(h, launch_backward_classes(false, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(false, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, h->partials, lr, eps, h->cs));
   }
   h->current = -1;
   if (h->as != h->cs) {

@@ -158,7 +158,6 @@ struct SetHeadOp {
   const uint32_t *uniq_sid;
   const int32_t *run_off;
   uint2 *touched;
-  int32_t *long_idx;
   __device__ u64 flag(int u, int) const { return (u == 0 || uniq_sid[u] != uniq_sid[u - 1]) ? 1ull : 0ull; }
   __device__ void emit(int u, int, u64 pre, u64 f) const {
     if (f) touched[pre & 0xFFFFFFFFull] = make_uint2(uniq_sid[u], (uint32_t)u);
@@ -167,12 +166,42 @@ struct SetHeadOp {
   __device__ void finish(BatchCounters *cnt, int, u64 total) const { cnt->n_touched = (int32_t)(total & 0xFFFFFFFFull); }
 };
 
-__global__ __launch_bounds__(256) void long_runs_kernel(const int32_t *__restrict__ run_off, int32_t *long_idx,
+// Work list of the backward for rows with more than kLongRun lookups: one item per
+// segment of kSegment lookups; rows of several segments also get partial-sum slots and an
+// entry in the `huge` list.  List positions are handed out with one atomic per wavefront.
+__global__ __launch_bounds__(256) void long_runs_kernel(const int32_t *__restrict__ run_off, uint4 *items, uint4 *huge,
                                                         BatchCounters *cnt) {
   if (cnt->err) return;
   const int n = cnt->n_uniq;
-  for (int u = blockIdx.x * blockDim.x + threadIdx.x; u < n; u += gridDim.x * blockDim.x)
-    if (run_off[u + 1] - run_off[u] > kLongRun) long_idx[atomicAdd(&cnt->n_long, 1)] = u;
+  const int lane = threadIdx.x & 63;
+  const int stride = gridDim.x * blockDim.x;
+  const int rounds = (n + stride - 1) / stride;
+  for (int r = 0; r < rounds; r++) {
+    const int u = r * stride + blockIdx.x * blockDim.x + threadIdx.x;
+    int len = 0;
+    if (u < n) len = run_off[u + 1] - run_off[u];
+    const int nseg = len > kLongRun ? (len + kSegment - 1) / kSegment : 0;
+    const int multi = nseg > 1 ? nseg : 0;
+    const int is_huge = nseg > 1 ? 1 : 0;
+    // exclusive prefix sums over the wavefront
+    int a = nseg, b = multi, c = is_huge;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int oa = __shfl_up(a, d), ob = __shfl_up(b, d), oc = __shfl_up(c, d);
+      if (lane >= d) { a += oa; b += ob; c += oc; }
+    }
+    const int ta = __shfl(a, 63), tb = __shfl(b, 63), tc = __shfl(c, 63);
+    int ba = 0, bb = 0, bc = 0;
+    if (lane == 63) {
+      if (ta) ba = atomicAdd(&cnt->n_items, ta);
+      if (tb) bb = atomicAdd(&cnt->n_partials, tb);
+      if (tc) bc = atomicAdd(&cnt->n_huge, tc);
+    }
+    ba = __shfl(ba, 63); bb = __shfl(bb, 63); bc = __shfl(bc, 63);
+    const int pbase = bb + b - multi;
+    for (int sgm = 0; sgm < nseg; sgm++)
+      items[ba + a - nseg + sgm] = make_uint4((uint32_t)u, (uint32_t)sgm, (uint32_t)nseg, (uint32_t)pbase);
+    if (is_huge) huge[bc + c - 1] = make_uint4((uint32_t)u, (uint32_t)pbase, (uint32_t)nseg, 0u);
+  }
 }
 
 // ---- pass 3 over the distinct rows after the probe: insert and bypass lists, counters ----
@@ -336,9 +365,9 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   if (n == 0) return hipSuccess;
   DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid};
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
-  SetHeadOp h{b.uniq_sid, b.run_off, b.touched, b.long_idx};
+  SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
   run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
-  hipLaunchKernelGGL(long_runs_kernel, dim3(512), dim3(256), 0, s, b.run_off, b.long_idx, b.cnt);
+  hipLaunchKernelGGL(long_runs_kernel, dim3(512), dim3(256), 0, s, b.run_off, b.items, b.huge, b.cnt);
   int64_t max_touched = (int64_t)g.total_sets + g.T;
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);

@@ -137,6 +137,53 @@ __device__ inline RowRef locate(const TableMeta &m, uint32_t key, int slot, floa
   return r;
 }
 
+// Sum of the output gradients of the lookups [i0, i1) of one row, as seen by one group of G
+// lanes: the bag ids are read G at a time (coalesced) and handed round by shuffles, four
+// gradient rows are in flight per lane.  `stride_chunks` > 1 lets several groups share a
+// range chunk-wise (group `first_chunk` of `stride_chunks`).  Summation order is fixed.
+template <int DT, int G>
+__device__ inline void reduce_grads(float (&g)[Elems<DT>::n], const float *gbase, const int32_t *sorted_bag, int bag0,
+                                    int sum_dim, int i0, int i1, int first_chunk, int stride_chunks, int lig,
+                                    bool active) {
+  constexpr int EPL = Elems<DT>::n;
+  for (int base = i0 + first_chunk * G; base < i1; base += stride_chunks * G) {
+    const int nq = (i1 - base) < G ? (i1 - base) : G;
+    const int my_bag = lig < nq ? sorted_bag[base + lig] - bag0 : 0;
+    for (int q = 0; q < nq; q += 4) {
+      float4 v[4][EPL / 4];
+#pragma unroll
+      for (int x = 0; x < 4; x++) {
+        const int bq = __shfl(my_bag, (q + x) & (G - 1), G);
+        const float *p = gbase + (size_t)bq * sum_dim;
+        const bool ok = active && (q + x < nq);
+#pragma unroll
+        for (int e = 0; e < EPL / 4; e++) v[x][e] = ok ? *(const float4 *)(p + 4 * e) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int x = 0; x < 4; x++)
+#pragma unroll
+        for (int e = 0; e < EPL / 4; e++) {
+          g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
+        }
+    }
+  }
+}
+
+// row-wise Adagrad on the row of distinct index u, gradient g spread over the group
+template <int DT, int G>
+__device__ inline void update_row(const TableMeta &m, uint32_t key, int slot, float *cache_m,
+                                  const float (&g)[Elems<DT>::n], float lr, float eps, int lig, bool active) {
+  constexpr int EPL = Elems<DT>::n;
+  float sq = 0.f;
+#pragma unroll
+  for (int e = 0; e < EPL; e++) sq += g[e] * g[e];
+  for (int d = G / 2; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, G);
+  const RowRef r = locate(m, key, slot, cache_m);
+  const float m_new = *r.m + sq / (float)m.dim;
+  if (active) adagrad_apply<DT>(r.w + lig * 16, g, m_new, lr, eps);
+  if (lig == 0) *r.m = m_new;
+}
+
 // Rows with at most kLongRun lookups: one group of G lanes per distinct row, gradients
 // summed in sorted (= ascending bag) order.
 template <int DT, int G>
@@ -162,58 +209,50 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
     if (table_class[t] != cls) continue;
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
-    const float *gbase = grad_out + m.col + lig * EPL;
-    const int bag0 = t * B;
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    if (active)
-      for (int i = i0; i < i1; i++) load_grad<DT>(g, gbase + (size_t)(sorted_bag[i] - bag0) * sum_dim);
-    float sq = 0.f;
-#pragma unroll
-    for (int e = 0; e < EPL; e++) sq += g[e] * g[e];
-    for (int d = G / 2; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, G);
-    const RowRef r = locate(m, key, loc_u[u], cache_m);
-    const float m_new = *r.m + sq / (float)m.dim;
-    if (active) adagrad_apply<DT>(r.w + lig * 16, g, m_new, lr, eps);
-    if (lig == 0) *r.m = m_new;
+    reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, 0, 1, lig, active);
+    update_row<DT, G>(m, key, loc_u[u], cache_m, g, lr, eps, lig, active);
   }
 }
 
-// Rows with more lookups: one block per row, its 256/G groups take the lookups round
-// robin, partial sums are added in group order through LDS (fixed order: reproducible).
+// Rows with more lookups are cut into segments of kSegment lookups; one block per segment,
+// its 256/G groups take chunks of G lookups round robin and their partial sums are added in
+// group order through LDS.  A row of one segment is updated at once; otherwise the segment
+// sum goes to the row's slots in `partials` and backward_combine_kernel finishes the row.
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__restrict__ tm, int T, int cls, int B,
                                                             int sum_dim, const uint32_t *__restrict__ uniq_key,
                                                             const int32_t *__restrict__ run_off,
                                                             const int32_t *__restrict__ loc_u,
                                                             const int32_t *__restrict__ sorted_bag,
-                                                            const int32_t *__restrict__ long_idx,
+                                                            const uint4 *__restrict__ items,
                                                             const float *__restrict__ grad_out,
-                                                            float *__restrict__ cache_m, float lr, float eps,
+                                                            float *__restrict__ cache_m, float *__restrict__ partials,
+                                                            int pstride, float lr, float eps,
                                                             const int32_t *__restrict__ table_class,
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int NG = 256 / G;
   __shared__ float part[NG][G * EPL + 1];
   if (cnt->err) return;
-  const int n_long = cnt->n_long;
+  const int n_items = cnt->n_items;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
-  for (int li = blockIdx.x; li < n_long; li += gridDim.x) {
-    const int u = long_idx[li];
+  for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+    const uint4 item = items[it];  // (distinct row, segment, segments of the row, first partial slot)
+    const int u = (int)item.x;
     const uint32_t key = uniq_key[u];
     const int t = find_table(tm, T, key);
     if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
-    const int i0 = run_off[u], i1 = run_off[u + 1];
-    const float *gbase = grad_out + m.col + lig * EPL;
-    const int bag0 = t * B;
+    const int i0 = run_off[u] + (int)item.y * kSegment;
+    const int i1 = min(run_off[u + 1], i0 + kSegment);
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    if (active)
-      for (int i = i0 + grp; i < i1; i += NG) load_grad<DT>(g, gbase + (size_t)(sorted_bag[i] - bag0) * sum_dim);
+    reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, grp, NG, lig, active);
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < EPL; e++) part[grp][lig * EPL + e] = g[e];
@@ -225,15 +264,51 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
         for (int q = 0; q < NG; q++) s += part[q][lig * EPL + e];
         g[e] = s;
       }
-      float sq = 0.f;
+      if (item.z == 1u) {
+        update_row<DT, G>(m, key, loc_u[u], cache_m, g, lr, eps, lig, active);
+      } else if (active) {
+        float *p = partials + (size_t)(item.w + item.y) * pstride + lig * EPL;
 #pragma unroll
-      for (int e = 0; e < EPL; e++) sq += g[e] * g[e];
-      for (int d = G / 2; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, G);
-      const RowRef r = locate(m, key, loc_u[u], cache_m);
-      const float m_new = *r.m + sq / (float)m.dim;
-      if (active) adagrad_apply<DT>(r.w + lig * 16, g, m_new, lr, eps);
-      if (lig == 0) *r.m = m_new;
+        for (int e = 0; e < EPL; e++) p[e] = g[e];
+      }
     }
+  }
+}
+
+// Rows of several segments: add the segment sums in segment order, then update the row.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int T, int cls,
+                                                               const uint32_t *__restrict__ uniq_key,
+                                                               const int32_t *__restrict__ loc_u,
+                                                               const uint4 *__restrict__ huge,
+                                                               float *__restrict__ cache_m,
+                                                               const float *__restrict__ partials, int pstride,
+                                                               float lr, float eps,
+                                                               const int32_t *__restrict__ table_class,
+                                                               const BatchCounters *cnt) {
+  constexpr int EPL = Elems<DT>::n;
+  if (cnt->err) return;
+  const int n_huge = cnt->n_huge;
+  const int lig = threadIdx.x % G;
+  const int n_groups = gridDim.x * (256 / G);
+  for (int hi = blockIdx.x * (256 / G) + threadIdx.x / G; hi < n_huge; hi += n_groups) {
+    const uint4 row = huge[hi];  // (distinct row, first partial slot, segments, -)
+    const int u = (int)row.x;
+    const uint32_t key = uniq_key[u];
+    const int t = find_table(tm, T, key);
+    if (table_class[t] != cls) continue;
+    const TableMeta &m = tm[t];
+    const bool active = lig * EPL < m.dim;
+    float g[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; e++) g[e] = 0.f;
+    if (active)
+      for (uint32_t sgm = 0; sgm < row.z; sgm++) {
+        const float *p = partials + (size_t)(row.y + sgm) * pstride + lig * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; e++) g[e] += p[e];
+      }
+    update_row<DT, G>(m, key, loc_u[u], cache_m, g, lr, eps, lig, active);
   }
 }
 
@@ -250,15 +325,19 @@ static void fwd_one(const TableMeta *tm, const int32_t *tables, int count, const
 }
 
 template <int DT, int G>
-static void bwd_one(bool long_rows, const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g,
-                    const BatchBuf &b, const float *grad_out, float *cache_m, float lr, float eps, hipStream_t s) {
-  if (long_rows)
-    hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(1024), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, b.long_idx, grad_out, cache_m, lr, eps,
-                       table_class, b.cnt);
-  else
+static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g,
+                    const BatchBuf &b, const float *grad_out, float *cache_m, float *partials, float lr, float eps,
+                    hipStream_t s) {
+  if (which == 0) {
+    hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
+                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, b.items, grad_out, cache_m, partials,
+                       g.partial_stride, lr, eps, table_class, b.cnt);
+    hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, g.T, cls, b.uniq_key, b.loc_u,
+                       b.huge, cache_m, partials, g.partial_stride, lr, eps, table_class, b.cnt);
+  } else {
     hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
                        b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, grad_out, cache_m, lr, eps, table_class, b.cnt);
+  }
 }
 
 #define TBE_DISPATCH(DT, LANES, CALL)                         \
@@ -294,15 +373,15 @@ hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, cons
   return hipGetLastError();
 }
 
-// long_rows selects the block-per-row kernel (rows with more than kLongRun lookups) or the
+// long_rows selects the segment kernels (rows with more than kLongRun lookups) or the
 // group-per-row kernel (all other rows); a step runs both, they touch disjoint rows.
 hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
-                                   const BatchBuf &b, const float *grad_out, float *cache_m, float lr, float eps,
-                                   hipStream_t s) {
+                                   const BatchBuf &b, const float *grad_out, float *cache_m, float *partials,
+                                   float lr, float eps, hipStream_t s) {
   if (b.n == 0) return hipSuccess;
   for (int c = 0; c < ci.n_classes; c++)
     TBE_DISPATCH(ci.cls_dtype[c], ci.cls_lanes[c],
-                 (bwd_one<d, l>(long_rows, tm, c, ci.table_class, g, b, grad_out, cache_m, lr, eps, s)));
+                 (bwd_one<d, l>(long_rows ? 0 : 1, tm, c, ci.table_class, g, b, grad_out, cache_m, partials, lr, eps, s)));
   return hipGetLastError();
 }
 

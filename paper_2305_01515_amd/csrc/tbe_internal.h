@@ -8,6 +8,7 @@ namespace tbe {
 constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr uint32_t kNoSet = 0xFFFFFFFFu;  // global set id of rows of a table without cache
 constexpr int kLongRun = 64;              // rows with more lookups than this take the block-wide backward
+constexpr int kSegment = 1024;            // ... in segments of this many lookups, one block each
 
 enum Status : uint8_t { ST_MISS = 0, ST_HIT = 1, ST_INSERT = 2, ST_BYPASS = 3 };
 
@@ -39,9 +40,10 @@ struct BatchCounters {
   int32_t n_touched;  // sets with at least one distinct row (+ pseudo sets of cacheless tables)
   int32_t n_ins;
   int32_t n_byp;
-  int32_t n_long;     // distinct rows with more than kLongRun lookups
-  int32_t err;        // TBE_E* found on the device, 0 = none
-  int32_t pad0, pad1;
+  int32_t n_items;    // segments of rows with more than kLongRun lookups
+  int32_t err;        // 1 = bad offsets, 2 = index out of range, 0 = none
+  int32_t n_huge;     // rows of more than one segment
+  int32_t n_partials; // partial-sum slots handed to those rows
   unsigned long long hits, evictions, hit_lookups;
 };
 
@@ -64,7 +66,8 @@ struct BatchBuf {
   uint2 *touched;       // [N] (global set id, first distinct row) of every touched set
   int32_t *ins_idx;     // [N] distinct-row indices of the inserts, ascending
   int32_t *byp_idx;     // [N] distinct-row indices of the bypasses, ascending
-  int32_t *long_idx;    // [N / kLongRun + 1] distinct rows with long runs (any order)
+  uint4 *items;         // [N/kLongRun + N/kSegment + 2] (row, segment, segments, first partial slot)
+  uint4 *huge;          // [N/kSegment + 2] rows of several segments: (row, first partial slot, segments, -)
   BatchCounters *cnt;   // device
   // host-side description
   const int64_t *d_indices;
@@ -78,7 +81,7 @@ struct BatchBuf {
 struct SortScratch {
   uint32_t *keys[2];
   uint32_t *vals[2];
-  uint32_t *hist;          // [256 * max sort blocks]
+  uint32_t *hist;          // [256 * max sort blocks] block histograms, then [256] digit totals
   unsigned long long *blk; // [scan blocks + 1] block sums of the compaction passes
 };
 
@@ -86,6 +89,7 @@ struct Geometry {
   int32_t T, ways;
   int32_t sum_dim;
   int32_t key_bits;     // bits of the largest sort key
+  int32_t partial_stride;  // floats per partial-sum slot (widest row, padded to whole lanes)
   uint32_t total_sets;
   int64_t total_slots;
 };
@@ -117,8 +121,8 @@ hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *t
 hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
                                   float *out, hipStream_t s);
 hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
-                                   const BatchBuf &b, const float *grad_out, float *cache_m, float lr, float eps,
-                                   hipStream_t s);
+                                   const BatchBuf &b, const float *grad_out, float *cache_m, float *partials,
+                                   float lr, float eps, hipStream_t s);
 
 // ---- small device helpers ----
 

@@ -44,7 +44,8 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
 
 __global__ void reset_counters_kernel(BatchCounters *cnt) {
   if (threadIdx.x == 0) {
-    cnt->n_uniq = cnt->n_touched = cnt->n_ins = cnt->n_byp = cnt->n_long = cnt->err = 0;
+    cnt->n_uniq = cnt->n_touched = cnt->n_ins = cnt->n_byp = cnt->n_items = cnt->err = 0;
+    cnt->n_huge = cnt->n_partials = 0;
     cnt->hits = cnt->evictions = cnt->hit_lookups = 0;
   }
 }
@@ -64,7 +65,7 @@ hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf 
 // --------------------------------------------------------------------------------------
 // LSD radix sort, 8-bit digits, three kernels per pass:
 //   upsweep   : per-block digit histogram of the block's contiguous chunk
-//   scan      : exclusive scan of the [digit][block] table (one block)
+//   scan      : per digit, exclusive scan of its counts over the blocks, and digit totals
 //   downsweep : the block walks its chunk tile by tile; inside a tile every wave ranks
 //               its keys with ballot matching (stable), the tile is ordered by digit in
 //               LDS and written out so that neighbouring lanes hit neighbouring addresses
@@ -89,34 +90,30 @@ __global__ __launch_bounds__(kSortThreads) void sort_upsweep_kernel(const uint32
   hist[tid * gridDim.x + blockIdx.x] = h[tid];
 }
 
-// exclusive scan of `total` uint32 values in place, one block of 1024 threads
-__global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *data, int total) {
-  __shared__ uint32_t wsum[16];
+// One block per digit: exclusive scan, over the sort blocks, of that digit's counts (in
+// place) and the digit's total.  nb <= kMaxSortBlocks = block size.
+__global__ __launch_bounds__(kMaxSortBlocks) void sort_scan_kernel(uint32_t *hist, int nb, uint32_t *digit_total) {
+  __shared__ uint32_t wsum[kMaxSortBlocks / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int per = (total + 1023) / 1024;
-  const int b = tid * per, e = min(total, b + per);
-  uint32_t s = 0;
-  for (int i = b; i < e; i++) s += data[i];
-  uint32_t incl = s;
+  uint32_t *row = hist + (size_t)blockIdx.x * nb;
+  const uint32_t v = tid < nb ? row[tid] : 0u;
+  uint32_t incl = v;
   for (int d = 1; d < 64; d <<= 1) {
     uint32_t o = __shfl_up(incl, d);
     if (lane >= d) incl += o;
   }
   if (lane == 63) wsum[wave] = incl;
   __syncthreads();
-  uint32_t wbase = 0;
-  for (int w = 0; w < wave; w++) wbase += wsum[w];
-  uint32_t run = wbase + incl - s;
-  for (int i = b; i < e; i++) {
-    uint32_t v = data[i];
-    data[i] = run;
-    run += v;
-  }
+  uint32_t wb = 0;
+  for (int w = 0; w < wave; w++) wb += wsum[w];
+  if (tid < nb) row[tid] = wb + incl - v;
+  if (tid == kMaxSortBlocks - 1) digit_total[blockIdx.x] = wb + incl;
 }
 
 __global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
     const uint32_t *__restrict__ keys_in, const uint32_t *__restrict__ vals_in, uint32_t *__restrict__ keys_out,
-    uint32_t *__restrict__ vals_out, int n, int shift, uint32_t mask, int chunk, const uint32_t *__restrict__ hist) {
+    uint32_t *__restrict__ vals_out, int n, int shift, uint32_t mask, int chunk, const uint32_t *__restrict__ hist,
+    const uint32_t *__restrict__ digit_total) {
   __shared__ uint32_t s_keys[kSortTile];
   __shared__ uint32_t s_vals[kSortTile];
   __shared__ uint32_t s_cnt[4][kRadix];  // per wave and digit: count, later exclusive prefix over waves
@@ -127,7 +124,20 @@ __global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   const int block_base = blockIdx.x * chunk;
   const int block_end = min(n, block_base + chunk);
-  s_gbase[tid] = hist[tid * gridDim.x + blockIdx.x];
+  {  // first output position of digit tid for this block: digits before it + blocks before this one
+    const uint32_t tot = digit_total[tid];
+    uint32_t incl = tot;
+    for (int dd = 1; dd < 64; dd <<= 1) {
+      uint32_t o = __shfl_up(incl, dd);
+      if (lane >= dd) incl += o;
+    }
+    if (lane == 63) s_wtot[wave] = incl;
+    __syncthreads();
+    uint32_t wb = 0;
+    for (int w = 0; w < wave; w++) wb += s_wtot[w];
+    s_gbase[tid] = wb + incl - tot + hist[tid * gridDim.x + blockIdx.x];
+    __syncthreads();
+  }
 
   for (int tile = block_base; tile < block_end; tile += kSortTile) {
     for (int w = 0; w < 4; w++) s_cnt[w][tid] = 0;
@@ -221,9 +231,11 @@ hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *resul
     const uint32_t mask = (1u << w) - 1u;
     hipLaunchKernelGGL(sort_upsweep_kernel, dim3(used_blocks), dim3(kSortThreads), 0, s, ss.keys[cur], (int)n, shift,
                        mask, chunk, ss.hist);
-    hipLaunchKernelGGL(sort_scan_kernel, dim3(1), dim3(1024), 0, s, ss.hist, kRadix * used_blocks);
+    hipLaunchKernelGGL(sort_scan_kernel, dim3(kRadix), dim3(kMaxSortBlocks), 0, s, ss.hist, used_blocks,
+                       ss.hist + kRadix * kMaxSortBlocks);
     hipLaunchKernelGGL(sort_downsweep_kernel, dim3(used_blocks), dim3(kSortThreads), 0, s, ss.keys[cur], ss.vals[cur],
-                       ss.keys[cur ^ 1], ss.vals[cur ^ 1], (int)n, shift, mask, chunk, ss.hist);
+                       ss.keys[cur ^ 1], ss.vals[cur ^ 1], (int)n, shift, mask, chunk, ss.hist,
+                       ss.hist + kRadix * kMaxSortBlocks);
     cur ^= 1;
   }
   *result_buf = cur;
