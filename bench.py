@@ -128,7 +128,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     s1 = g.stats()
-    times = {k: g.stage_times(k) for k in ("prefetch", "fill", "forward", "backward_long", "backward_short")}
+    times = {k: g.stage_times(k) for k in ("prefetch", "fill", "commit", "forward", "backward_long", "backward_short")}
 
     # the timed region trained batches Wm..Wm+K-1; it prefetched batches Wm+1..Wm+K (one ahead)
     lookups = sum(int(batches[s][0].numel()) for s in range(Wm, Wm + K))
@@ -173,7 +173,7 @@ def main():
         "hit_path": {"ms_fwd_bwd": ms["forward"] + bwd_ms,
                      "lookups_per_s": (lookups / K) / ((ms["forward"] + bwd_ms) * 1e-3) if bwd_ms else 0.0,
                      "hbm_frac": (fwd_b + bwd_b) / ((ms["forward"] + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS if bwd_ms else 0.0},
-        "prefetch_stage_ms": ms["prefetch"],
+        "prefetch_stage_ms": ms["prefetch"], "commit_stage_ms": ms["commit"],
         "host_link": {"ms_fill": fill_ms, "h2d_bytes_per_step": h2d, "d2h_bytes_per_step": d2h,
                       "h2d_GBps": h2d / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0,
                       "d2h_GBps": d2h / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0,
@@ -182,7 +182,8 @@ def main():
         "cache": {"hit_rate_unique": tot["hits"] / max(1, tot["uniques"]),
                   "hit_rate_lookup": tot["hit_lookups"] / max(1, tot["lookups"]),
                   "bypass_frac_unique": tot["bypasses"] / max(1, tot["uniques"]),
-                  "uniques_per_step": tot["uniques"] / npf},
+                  "uniques_per_step": tot["uniques"] / npf, "inserts_per_step": tot["inserts"] / npf,
+                  "late_fetches_per_step": (s1["late_fetches"] - s0["late_fetches"]) / npf},
         "cpu_baseline": cpu,
     }
     print(json.dumps(res))

@@ -86,8 +86,10 @@ typedef struct {
 typedef struct {
   tbe_batch_stats last;  /* last prefetched batch                                   */
   tbe_batch_stats total; /* sum over all batches since create                       */
-  int64_t h2d_bytes;     /* backing tier -> cache, rows + accumulators, since create */
+  int64_t h2d_bytes;     /* backing tier -> cache, since create                       */
   int64_t d2h_bytes;     /* cache -> backing tier (evictions and flushes)           */
+  int64_t late_fetches;  /* inserted rows that had to wait for a pending write of   */
+                         /* their backing-tier copy (fetched at commit time)        */
   int32_t batch_id;      /* k of the last prefetch                                  */
   int32_t reserved;
 } tbe_stats;
@@ -177,11 +179,12 @@ int tbe_get_stats(tbe_handle h, tbe_stats *out);
  * With h_ms NULL, tbe_get_stage_times returns the number of records.
  */
 #define TBE_STAGE_PREFETCH 0       /* key generation, sort, dedup, probe, compaction (aux stream) */
-#define TBE_STAGE_FILL 1           /* write-back of victims and fetch of missed rows (aux stream) */
+#define TBE_STAGE_FILL 1           /* host link: write-back of parked victims + fetch-ahead of missed rows (aux) */
 #define TBE_STAGE_FORWARD 2        /* pooled lookup (compute stream)                              */
 #define TBE_STAGE_BACKWARD_LONG 3  /* backward of rows with many lookups (compute stream)         */
 #define TBE_STAGE_BACKWARD_SHORT 4 /* backward of all other rows (compute stream)                 */
-#define TBE_NUM_STAGES 5
+#define TBE_STAGE_COMMIT 5         /* victims -> staging, fetched rows -> cache lines (aux stream)  */
+#define TBE_NUM_STAGES 6
 int tbe_set_profiling(tbe_handle h, int32_t enable);
 int64_t tbe_get_stage_times(tbe_handle h, int32_t stage, int64_t capacity, float *h_ms);
 

@@ -41,15 +41,22 @@ struct tbe_ctx {
   ClassInfo ci{};
   DevAlloc mem;
   int32_t *tags = nullptr, *ts = nullptr;
-  float *cache_m = nullptr;
+  float *d_state = nullptr;   // row-wise Adagrad accumulators of all rows of all tables
   float *partials = nullptr;  // segment sums of the backward's longest rows
   char *lines = nullptr;
   BatchBuf buf[2]{};
   SortScratch ss{};
+  Staging st{};
+  uint32_t *d_rb = nullptr;  // row bytes of every table
+  int prev_buf = -1;         // buffer of the batch prefetched before the current one
   BatchCounters *d_total = nullptr;       // running totals of the per-batch counters
   unsigned long long *d_bytes = nullptr;  // [0] backing->cache, [1] cache->backing
-  hipStream_t cs = nullptr, as = nullptr;
+  hipStream_t cs = nullptr, as = nullptr;  // compute / prefetch streams (caller's)
+  hipStream_t ls = nullptr;                // host-link stream: transfer and commit (own, unless cs == as)
+  bool own_ls = false;
   hipEvent_t ev_inputs = nullptr, ev_ready[2] = {nullptr, nullptr}, ev_trained[2] = {nullptr, nullptr};
+  hipEvent_t ev_probed[2] = {nullptr, nullptr};
+  int64_t flush_state_bytes = 0;
   bool trained_recorded[2] = {false, false};
   int32_t max_batch = 0;
   int64_t max_lookups = 0;
@@ -142,9 +149,12 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.loc_u, 4 * N));
   HIP_TRY(h, h->mem.get(&b.status, N));
   HIP_TRY(h, h->mem.get(&b.old_tag, 4 * N));
-  HIP_TRY(h, h->mem.get(&b.old_ts, 4 * N));
   HIP_TRY(h, h->mem.get(&b.touched, 8 * N));
   HIP_TRY(h, h->mem.get(&b.ins_idx, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.ins_tab, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.ins_key, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.ins_src, 8 * N));
+  HIP_TRY(h, h->mem.get(&b.ins_late, N));
   HIP_TRY(h, h->mem.get(&b.byp_idx, 4 * N));
   HIP_TRY(h, h->mem.get(&b.items, 16 * (N / kLongRun + N / kSegment + 2)));
   HIP_TRY(h, h->mem.get(&b.huge, 16 * (N / kSegment + 2)));
@@ -171,18 +181,20 @@ int collect_device_errors(tbe_ctx *h) {
 
 int sync_all(tbe_ctx *h) {
   HIP_TRY(h, hipStreamSynchronize(h->as));
+  HIP_TRY(h, hipStreamSynchronize(h->ls));
   HIP_TRY(h, hipStreamSynchronize(h->cs));
   return TBE_OK;
 }
 
-// Cache -> cache copies for buffer `bi`, then mark the batch ready for forward.
-int enqueue_fill(tbe_ctx *h, int bi) {
+// Victims of batch `bi` to the staging area, its new rows into the cache lines; then the
+// batch is ready for forward.  Must follow the update of the batch before it.
+int enqueue_commit(tbe_ctx *h, int bi) {
   BatchBuf &b = h->buf[bi];
   {
-    StageTimer tm_(h, TBE_STAGE_FILL, h->as);
-    HIP_TRY(h, launch_fill(h->d_tm, h->g, b, h->cache_m, h->d_bytes, h->d_bytes + 1, h->as));
+    StageTimer tm_(h, TBE_STAGE_COMMIT, h->ls);
+    HIP_TRY(h, launch_commit(h->d_tm, b, h->st, h->d_bytes, h->ls));
   }
-  HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->as));
+  HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->ls));
   return TBE_OK;
 }
 
@@ -210,16 +222,32 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     int res = 0;
     HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
     HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->as));
+    // which of the rows to insert have a backing-tier copy that is still being written
+    // (by the write-back of the previous batch's victims or by its backward), then move
+    // the marks on from the previous batch to this one
+    HIP_TRY(h, launch_classify_mark(h->d_tm, h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr, b, h->st, h->d_bytes + 5, h->as));
     hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total);
     hipLaunchKernelGGL(add_totals64_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_bytes + 2);
     HIP_TRY(h, hipGetLastError());
   }
+  if (h->ls != h->as) {
+    HIP_TRY(h, hipEventRecord(h->ev_probed[bi], h->as));
+    HIP_TRY(h, hipStreamWaitEvent(h->ls, h->ev_probed[bi], 0));
+  }
+  {
+    // write-back of the previous batch's victims and fetch-ahead of this batch's rows share
+    // the host link; neither touches a cache line, so a batch in flight is not disturbed,
+    // and the link stream lets the next batch's sort and probe run meanwhile
+    StageTimer tm_(h, TBE_STAGE_FILL, h->ls);
+    HIP_TRY(h, launch_transfer(&b, h->st, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
+  }
+  h->prev_buf = bi;
   h->pend[h->n_pend++] = bi;
   if (in_flight) {
-    h->deferred = bi;  // its copies must not touch rows the batch in flight still uses
+    h->deferred = bi;  // its cache lines may still be in use: commit after that batch's update
     return TBE_OK;
   }
-  return enqueue_fill(h, bi);
+  return enqueue_commit(h, bi);
 }
 
 }  // namespace
@@ -240,13 +268,16 @@ int tbe_host_free(void *h_ptr) { return hipHostFree(h_ptr) == hipSuccess ? TBE_O
 int tbe_destroy(tbe_handle h) {
   if (!h) return TBE_EINVAL;
   (void)hipStreamSynchronize(h->as);
+  (void)hipStreamSynchronize(h->ls);
   (void)hipStreamSynchronize(h->cs);
+  if (h->own_ls) (void)hipStreamDestroy(h->ls);
   h->mem.release();
   drop_profile(h);
   if (h->ev_inputs) (void)hipEventDestroy(h->ev_inputs);
   for (int i = 0; i < 2; i++) {
     if (h->ev_ready[i]) (void)hipEventDestroy(h->ev_ready[i]);
     if (h->ev_trained[i]) (void)hipEventDestroy(h->ev_trained[i]);
+    if (h->ev_probed[i]) (void)hipEventDestroy(h->ev_probed[i]);
   }
   delete h;
   return TBE_OK;
@@ -265,6 +296,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   if (!h) return fail(nullptr, TBE_ENOMEM, "create: host allocation failed");
   h->cs = (hipStream_t)compute_stream;
   h->as = (hipStream_t)aux_stream;
+  h->ls = h->cs;
   h->max_batch = max_batch;
   h->max_lookups = max_lookups;
   h->g.T = num_tables;
@@ -341,11 +373,24 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   CREATE_TRY(h->mem.get(&h->lines, line_bytes));
   CREATE_TRY(h->mem.get(&h->tags, 4 * slots));
   CREATE_TRY(h->mem.get(&h->ts, 4 * slots));
-  CREATE_TRY(h->mem.get(&h->cache_m, 4 * slots));
   if (slots) {
     CREATE_TRY(hipMemset(h->tags, 0xFF, 4 * slots));  // -1 = free
     CREATE_TRY(hipMemset(h->ts, 0xFF, 4 * slots));
-    CREATE_TRY(hipMemset(h->cache_m, 0, 4 * slots));
+  }
+  {  // accumulators of all rows live in HBM; the host arrays give their initial values
+    size_t total_rows = 0;
+    for (int t = 0; t < num_tables; t++) total_rows += (size_t)h->tm[t].rows;
+    CREATE_TRY(h->mem.get(&h->d_state, 4 * total_rows));
+    size_t off = 0;
+    for (int t = 0; t < num_tables; t++) {
+      h->tm[t].dev_m = h->d_state + off;
+      CREATE_TRY(hipMemcpy(h->tm[t].dev_m, h->tm[t].host_m, 4 * (size_t)h->tm[t].rows, hipMemcpyHostToDevice));
+      off += (size_t)h->tm[t].rows;
+    }
+  }
+  if (h->as != h->cs) {
+    CREATE_TRY(hipStreamCreateWithFlags(&h->ls, hipStreamNonBlocking));
+    h->own_ls = true;
   }
   for (int t = 0; t < num_tables; t++) h->tm[t].lines = h->lines + line_off[t];
   CREATE_TRY(h->mem.get(&h->d_tm, sizeof(TableMeta) * num_tables));
@@ -370,6 +415,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     if (rc) { g_create_error = h->err; return bail(rc); }
     CREATE_TRY(hipEventCreateWithFlags(&h->ev_ready[i], hipEventDisableTiming));
     CREATE_TRY(hipEventCreateWithFlags(&h->ev_trained[i], hipEventDisableTiming));
+    CREATE_TRY(hipEventCreateWithFlags(&h->ev_probed[i], hipEventDisableTiming));
   }
   CREATE_TRY(hipEventCreateWithFlags(&h->ev_inputs, hipEventDisableTiming));
   const size_t N = (size_t)max_lookups;
@@ -382,6 +428,25 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     for (const TableMeta &m : h->tm) widest = std::max(widest, m.lanes * (m.dtype == TBE_FP32 ? 4 : 8));
     h->g.partial_stride = widest;
     CREATE_TRY(h->mem.get(&h->partials, 4 * (size_t)widest * (2 * (N / kSegment) + 2)));
+  }
+  {
+    Staging &st = h->st;
+    st.max_inserts = std::min<int64_t>(max_lookups, h->g.total_slots);
+    st.stride = 16;
+    std::vector<uint32_t> rb(num_tables);
+    for (int t = 0; t < num_tables; t++) { rb[t] = h->tm[t].row_bytes; st.stride = std::max(st.stride, rb[t]); }
+    const size_t M = (size_t)st.max_inserts;
+    CREATE_TRY(h->mem.get(&st.in, M * st.stride));
+    CREATE_TRY(h->mem.get(&st.out, M * st.stride));
+    CREATE_TRY(h->mem.get(&st.wb_dst, 8 * M));
+    CREATE_TRY(h->mem.get(&st.wb_rb, 4 * M));
+    CREATE_TRY(h->mem.get(&st.wb_n, 16));
+    CREATE_TRY(hipMemset(st.wb_n, 0, 16));
+    const size_t words = (size_t)((key + 31) / 32) + 1;
+    CREATE_TRY(h->mem.get(&st.dirty, 4 * words));
+    CREATE_TRY(hipMemset(st.dirty, 0, 4 * words));
+    CREATE_TRY(h->mem.get(&h->d_rb, 4 * (size_t)num_tables));
+    CREATE_TRY(hipMemcpy(h->d_rb, rb.data(), 4 * (size_t)num_tables, hipMemcpyHostToDevice));
   }
   CREATE_TRY(h->mem.get(&h->ss.hist, 4 * (256 * 1024 + 256)));
   CREATE_TRY(h->mem.get(&h->ss.blk, 8 * 1024));
@@ -435,22 +500,23 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   const int bi = h->current;
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_LONG, h->cs);
-    HIP_TRY(h, launch_backward_classes(true, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, h->partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(true, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
-    HIP_TRY(h, launch_backward_classes(false, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->cache_m, h->partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(false, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
   }
   h->current = -1;
   if (h->as != h->cs) {
     HIP_TRY(h, hipEventRecord(h->ev_trained[bi], h->cs));
-    // later prefetch work (which may reuse this buffer or move rows this batch used) follows it
+    // later prefetch work may reuse this buffer, later commits overwrite lines this batch used
     HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_trained[bi], 0));
+    HIP_TRY(h, hipStreamWaitEvent(h->ls, h->ev_trained[bi], 0));
   }
   if (h->deferred >= 0) {
     const int d = h->deferred;
     h->deferred = -1;
-    return enqueue_fill(h, d);
+    return enqueue_commit(h, d);
   }
   return TBE_OK;
 }
@@ -460,7 +526,12 @@ int tbe_flush(tbe_handle h) {
   if (h->n_pend > 0 || h->current >= 0) return fail(h, TBE_EORDER, "flush: a batch is still in flight");
   int rc = sync_all(h);
   if (rc) return rc;
-  HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->cache_m, h->d_bytes + 1, h->cs));
+  HIP_TRY(h, launch_transfer(nullptr, h->st, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
+  HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->d_bytes + 1, h->cs));
+  for (const TableMeta &m : h->tm) {
+    HIP_TRY(h, hipMemcpyAsync(m.host_m, m.dev_m, 4 * (size_t)m.rows, hipMemcpyDeviceToHost, h->cs));
+    h->flush_state_bytes += 4 * m.rows;
+  }
   rc = sync_all(h);
   if (rc) return rc;
   return collect_device_errors(h);
@@ -519,7 +590,8 @@ int tbe_get_stats(tbe_handle h, tbe_stats *out) {
   out->total.evictions = (int64_t)tot.evictions;
   out->total.hit_lookups = (int64_t)tot.hit_lookups;
   out->h2d_bytes = (int64_t)b64[0];
-  out->d2h_bytes = (int64_t)b64[1];
+  out->d2h_bytes = (int64_t)b64[1] + h->flush_state_bytes;
+  out->late_fetches = (int64_t)b64[5];
   out->batch_id = h->k;
   return collect_device_errors(h);
 }

@@ -1,7 +1,6 @@
 // Index dedup part 2 (run-length encoding of the sorted keys), the set-associative probe
-// with LRU victim choice, miss-list compaction, and the copies between cache and backing
-// tier.  Paper Section 5.5: tag/state lookup (5.5.1), cache algorithm (5.5.2), data
-// lookup/update (5.5.3) and data movement (5.5.4), one-level cache.
+// with LRU victim choice and miss-list compaction.  Paper Section 5.5: tag/state lookup
+// (5.5.1, probe and grouping by destination) and cache algorithm (5.5.2), one-level cache.
 #include "tbe_internal.h"
 
 namespace tbe {
@@ -206,10 +205,16 @@ __global__ __launch_bounds__(256) void long_runs_kernel(const int32_t *__restric
 
 // ---- pass 3 over the distinct rows after the probe: insert and bypass lists, counters ----
 struct StatusOp {
+  const TableMeta *tm;
+  int T;
   const uint8_t *status;
   const int32_t *run_off;
   const int32_t *old_tag;
+  const uint32_t *uniq_key;
   int32_t *ins_idx;
+  int32_t *ins_tab;
+  uint32_t *ins_key;
+  char **ins_src;
   int32_t *byp_idx;
   // per-thread tallies (the emit kernel keeps one Op copy per thread in registers)
   mutable unsigned int hits, evs;
@@ -220,7 +225,15 @@ struct StatusOp {
   }
   __device__ void emit(int u, int, u64 pre, u64 f) const {
     if (f == 1ull) {
-      ins_idx[pre & 0xFFFFFFFFull] = u;
+      const uint32_t i = (uint32_t)(pre & 0xFFFFFFFFull);
+      const uint32_t key = uniq_key[u];
+      const int t = find_table(tm, T, key);
+      const TableMeta &m = tm[t];
+      const uint32_t row = row_of_key(m, key);
+      ins_idx[i] = u;
+      ins_tab[i] = t;
+      ins_key[i] = key;
+      ins_src[i] = m.host_w + (size_t)row * m.row_bytes;
       if (old_tag[u] >= 0) evs++;
     } else if (f) {
       byp_idx[pre >> 32] = u;
@@ -261,7 +274,7 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
                                                       const uint2 *__restrict__ touched, int32_t *__restrict__ tags,
                                                       int32_t *__restrict__ ts, int32_t *__restrict__ loc_u,
                                                       uint8_t *__restrict__ status, int32_t *__restrict__ old_tag,
-                                                      int32_t *__restrict__ old_ts, const BatchCounters *cnt) {
+                                                      const BatchCounters *cnt) {
   __shared__ int32_t l_tag[kWave];
   __shared__ int32_t l_ts[kWave];
   __shared__ int32_t l_way[kWave];
@@ -328,7 +341,6 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
         if (j < n_cand) {
           const int way = l_way[j];
           old_tag[u] = l_tag[way];
-          old_ts[u] = l_ts[way];
           l_tag[way] = (int32_t)((uniq_key[u] - key0) * m.sets + set);
           l_ts[way] = k;
           loc_u[u] = slot0 + way;
@@ -372,108 +384,13 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
   hipLaunchKernelGGL(probe_kernel, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key, b.touched,
-                     tags, ts, b.loc_u, b.status, b.old_tag, b.old_ts, b.cnt);
-  StatusOp st{b.status, b.run_off, b.old_tag, b.ins_idx, b.byp_idx, 0u, 0u, 0ull};
+                     tags, ts, b.loc_u, b.status, b.old_tag, b.cnt);
+  StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.ins_idx, b.ins_tab, b.ins_key, b.ins_src,
+              b.byp_idx, 0u, 0u, 0ull};
   run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
   const int fin_blocks = (n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096;
   hipLaunchKernelGGL(finalize_kernel, dim3(fin_blocks), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.loc,
                      b.cnt);
-  return hipGetLastError();
-}
-
-// --------------------------------------------------------------------------------------
-// Data movement: 16 lanes per row, 16 bytes per lane and step; the row and its
-// accumulator travel together.  Host rows are reached through the pinned mapping.
-// --------------------------------------------------------------------------------------
-constexpr int kMoveLanes = 16;
-
-__global__ __launch_bounds__(256) void fill_kernel(const TableMeta *__restrict__ tm, int T,
-                                                   const uint32_t *__restrict__ uniq_key,
-                                                   const int32_t *__restrict__ ins_idx,
-                                                   const int32_t *__restrict__ loc_u,
-                                                   const int32_t *__restrict__ old_tag, float *__restrict__ cache_m,
-                                                   const BatchCounters *cnt, u64 *bytes_h2d, u64 *bytes_d2h) {
-  if (cnt->err) return;
-  const int n_ins = cnt->n_ins;
-  const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
-  const int lig = threadIdx.x % kMoveLanes;
-  const int n_groups = gridDim.x * blockDim.x / kMoveLanes;
-  u64 in_b = 0, out_b = 0;
-  for (int i = group; i < n_ins; i += n_groups) {
-    const int u = ins_idx[i];
-    const uint32_t key = uniq_key[u];
-    const TableMeta &m = tm[find_table(tm, T, key)];
-    const uint32_t row = row_of_key(m, key);
-    const int slot = loc_u[u];
-    const int32_t old = old_tag[u];
-    char *line = m.lines + (size_t)(slot - m.slot_base) * m.row_bytes;
-    const char *src = m.host_w + (size_t)row * m.row_bytes;
-    char *dst = m.host_w + (size_t)(old < 0 ? 0 : old) * m.row_bytes;
-    for (uint32_t c = lig * 16; c < m.row_bytes; c += kMoveLanes * 16) {
-      const uint4 fresh = *(const uint4 *)(src + c);
-      if (old >= 0) *(uint4 *)(dst + c) = *(const uint4 *)(line + c);
-      *(uint4 *)(line + c) = fresh;
-    }
-    if (lig == 0) {
-      const float fresh_m = m.host_m[row];
-      if (old >= 0) {
-        m.host_m[old] = cache_m[slot];
-        out_b += m.row_bytes + 4;
-      }
-      cache_m[slot] = fresh_m;
-      in_b += m.row_bytes + 4;
-    }
-  }
-  for (int d = 32; d >= 1; d >>= 1) {
-    in_b += __shfl_xor(in_b, d);
-    out_b += __shfl_xor(out_b, d);
-  }
-  if ((threadIdx.x & 63) == 0) {
-    if (in_b) atomicAdd(bytes_h2d, in_b);
-    if (out_b) atomicAdd(bytes_d2h, out_b);
-  }
-}
-
-hipError_t launch_fill(const TableMeta *tm, const Geometry &g, const BatchBuf &b, float *cache_m, u64 *bytes_h2d,
-                       u64 *bytes_d2h, hipStream_t s) {
-  if (b.n == 0 || g.total_slots == 0) return hipSuccess;
-  hipLaunchKernelGGL(fill_kernel, dim3(2048), dim3(256), 0, s, tm, g.T, b.uniq_key, b.ins_idx, b.loc_u, b.old_tag,
-                     cache_m, b.cnt, bytes_h2d, bytes_d2h);
-  return hipGetLastError();
-}
-
-__global__ __launch_bounds__(256) void flush_kernel(const TableMeta *__restrict__ tm, int T, int64_t total_slots,
-                                                    const int32_t *__restrict__ tags,
-                                                    const float *__restrict__ cache_m, u64 *bytes_d2h) {
-  const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
-  const int lig = threadIdx.x % kMoveLanes;
-  const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / kMoveLanes;
-  u64 out_b = 0;
-  for (int64_t slot = group; slot < total_slots; slot += n_groups) {
-    const int32_t row = tags[slot];
-    if (row < 0) continue;
-    int lo = 0, hi = T - 1;  // table owning this slot: last t with slot_base <= slot
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if ((int64_t)tm[mid].slot_base <= slot) lo = mid; else hi = mid - 1;
-    }
-    const TableMeta &m = tm[lo];
-    const char *line = m.lines + (size_t)(slot - m.slot_base) * m.row_bytes;
-    char *dst = m.host_w + (size_t)row * m.row_bytes;
-    for (uint32_t c = lig * 16; c < m.row_bytes; c += kMoveLanes * 16) *(uint4 *)(dst + c) = *(const uint4 *)(line + c);
-    if (lig == 0) {
-      m.host_m[row] = cache_m[slot];
-      out_b += m.row_bytes + 4;
-    }
-  }
-  for (int d = 32; d >= 1; d >>= 1) out_b += __shfl_xor(out_b, d);
-  if ((threadIdx.x & 63) == 0 && out_b) atomicAdd(bytes_d2h, out_b);
-}
-
-hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, float *cache_m, u64 *bytes_d2h,
-                        hipStream_t s) {
-  if (g.total_slots == 0) return hipSuccess;
-  hipLaunchKernelGGL(flush_kernel, dim3(2048), dim3(256), 0, s, tm, g.T, g.total_slots, tags, cache_m, bytes_d2h);
   return hipGetLastError();
 }
 

@@ -124,16 +124,13 @@ struct RowRef {
   float *m;    // its accumulator
 };
 
-__device__ inline RowRef locate(const TableMeta &m, uint32_t key, int slot, float *cache_m) {
+// The accumulators of all rows stay in HBM (the paper keeps optimizer parameters there,
+// Section 5.6.1): only the row itself is in a cache line or in the backing tier.
+__device__ inline RowRef locate(const TableMeta &m, uint32_t key, int slot) {
   RowRef r;
-  if (slot >= 0) {
-    r.w = m.lines + (size_t)(slot - m.slot_base) * m.row_bytes;
-    r.m = cache_m + slot;
-  } else {
-    const uint32_t row = row_of_key(m, key);
-    r.w = m.host_w + (size_t)row * m.row_bytes;
-    r.m = m.host_m + row;
-  }
+  const uint32_t row = row_of_key(m, key);
+  r.w = slot >= 0 ? m.lines + (size_t)(slot - m.slot_base) * m.row_bytes : m.host_w + (size_t)row * m.row_bytes;
+  r.m = m.dev_m + row;
   return r;
 }
 
@@ -171,14 +168,14 @@ __device__ inline void reduce_grads(float (&g)[Elems<DT>::n], const float *gbase
 
 // row-wise Adagrad on the row of distinct index u, gradient g spread over the group
 template <int DT, int G>
-__device__ inline void update_row(const TableMeta &m, uint32_t key, int slot, float *cache_m,
+__device__ inline void update_row(const TableMeta &m, uint32_t key, int slot,
                                   const float (&g)[Elems<DT>::n], float lr, float eps, int lig, bool active) {
   constexpr int EPL = Elems<DT>::n;
   float sq = 0.f;
 #pragma unroll
   for (int e = 0; e < EPL; e++) sq += g[e] * g[e];
   for (int d = G / 2; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, G);
-  const RowRef r = locate(m, key, slot, cache_m);
+  const RowRef r = locate(m, key, slot);
   const float m_new = *r.m + sq / (float)m.dim;
   if (active) adagrad_apply<DT>(r.w + lig * 16, g, m_new, lr, eps);
   if (lig == 0) *r.m = m_new;
@@ -193,7 +190,7 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
                                                              const int32_t *__restrict__ loc_u,
                                                              const int32_t *__restrict__ sorted_bag,
                                                              const float *__restrict__ grad_out,
-                                                             float *__restrict__ cache_m, float lr, float eps,
+                                                             float lr, float eps,
                                                              const int32_t *__restrict__ table_class,
                                                              const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
@@ -213,7 +210,7 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
     reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, 0, 1, lig, active);
-    update_row<DT, G>(m, key, loc_u[u], cache_m, g, lr, eps, lig, active);
+    update_row<DT, G>(m, key, loc_u[u], g, lr, eps, lig, active);
   }
 }
 
@@ -229,7 +226,7 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
                                                             const int32_t *__restrict__ sorted_bag,
                                                             const uint4 *__restrict__ items,
                                                             const float *__restrict__ grad_out,
-                                                            float *__restrict__ cache_m, float *__restrict__ partials,
+                                                            float *__restrict__ partials,
                                                             int pstride, float lr, float eps,
                                                             const int32_t *__restrict__ table_class,
                                                             const BatchCounters *cnt) {
@@ -265,7 +262,7 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
         g[e] = s;
       }
       if (item.z == 1u) {
-        update_row<DT, G>(m, key, loc_u[u], cache_m, g, lr, eps, lig, active);
+        update_row<DT, G>(m, key, loc_u[u], g, lr, eps, lig, active);
       } else if (active) {
         float *p = partials + (size_t)(item.w + item.y) * pstride + lig * EPL;
 #pragma unroll
@@ -281,7 +278,6 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
                                                                const uint32_t *__restrict__ uniq_key,
                                                                const int32_t *__restrict__ loc_u,
                                                                const uint4 *__restrict__ huge,
-                                                               float *__restrict__ cache_m,
                                                                const float *__restrict__ partials, int pstride,
                                                                float lr, float eps,
                                                                const int32_t *__restrict__ table_class,
@@ -308,7 +304,7 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
 #pragma unroll
         for (int e = 0; e < EPL; e++) g[e] += p[e];
       }
-    update_row<DT, G>(m, key, loc_u[u], cache_m, g, lr, eps, lig, active);
+    update_row<DT, G>(m, key, loc_u[u], g, lr, eps, lig, active);
   }
 }
 
@@ -326,17 +322,16 @@ static void fwd_one(const TableMeta *tm, const int32_t *tables, int count, const
 
 template <int DT, int G>
 static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g,
-                    const BatchBuf &b, const float *grad_out, float *cache_m, float *partials, float lr, float eps,
-                    hipStream_t s) {
+                    const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps, hipStream_t s) {
   if (which == 0) {
     hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, b.items, grad_out, cache_m, partials,
+                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, b.items, grad_out, partials,
                        g.partial_stride, lr, eps, table_class, b.cnt);
     hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, g.T, cls, b.uniq_key, b.loc_u,
-                       b.huge, cache_m, partials, g.partial_stride, lr, eps, table_class, b.cnt);
+                       b.huge, partials, g.partial_stride, lr, eps, table_class, b.cnt);
   } else {
     hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, grad_out, cache_m, lr, eps, table_class, b.cnt);
+                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, table_class, b.cnt);
   }
 }
 
@@ -376,12 +371,12 @@ hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, cons
 // long_rows selects the segment kernels (rows with more than kLongRun lookups) or the
 // group-per-row kernel (all other rows); a step runs both, they touch disjoint rows.
 hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
-                                   const BatchBuf &b, const float *grad_out, float *cache_m, float *partials,
-                                   float lr, float eps, hipStream_t s) {
+                                   const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,
+                                   hipStream_t s) {
   if (b.n == 0) return hipSuccess;
   for (int c = 0; c < ci.n_classes; c++)
     TBE_DISPATCH(ci.cls_dtype[c], ci.cls_lanes[c],
-                 (bwd_one<d, l>(long_rows ? 0 : 1, tm, c, ci.table_class, g, b, grad_out, cache_m, partials, lr, eps, s)));
+                 (bwd_one<d, l>(long_rows ? 0 : 1, tm, c, ci.table_class, g, b, grad_out, partials, lr, eps, s)));
   return hipGetLastError();
 }
 

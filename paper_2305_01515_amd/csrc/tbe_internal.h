@@ -31,7 +31,8 @@ struct TableMeta {
   uint32_t row_bytes;
   char *lines;            // device: cache lines of this table [sets*ways, row_bytes]
   char *host_w;           // pinned host rows [rows, row_bytes]
-  float *host_m;          // pinned host accumulators [rows]
+  float *host_m;          // host accumulators [rows]: read at create, written at flush
+  float *dev_m;           // device: row-wise Adagrad accumulators of ALL rows of the table [rows]
 };
 
 // Device-side scalars of one batch (one per batch buffer).
@@ -62,9 +63,13 @@ struct BatchBuf {
   int32_t *loc_u;       // [N] global slot id or -1
   uint8_t *status;      // [N] Status
   int32_t *old_tag;     // [N] for inserts: row that was evicted, -1 if the entry was free
-  int32_t *old_ts;      // [N] for inserts: timestamp the entry carried
   uint2 *touched;       // [N] (global set id, first distinct row) of every touched set
-  int32_t *ins_idx;     // [N] distinct-row indices of the inserts, ascending
+  int32_t *ins_idx;     // [N] distinct-row indices of the inserts, ascending; per insert also:
+  int32_t *ins_tab;     // [N]   its table
+  uint32_t *ins_key;    // [N]   its sort key
+  char **ins_src;       // [N]   its row in the backing tier
+  uint8_t *ins_late;    // [N]   1 = the backing-tier copy was still being written when the
+                        //       early fetch ran: the row is fetched at commit time instead
   int32_t *byp_idx;     // [N] distinct-row indices of the bypasses, ascending
   uint4 *items;         // [N/kLongRun + N/kSegment + 2] (row, segment, segments, first partial slot)
   uint4 *huge;          // [N/kSegment + 2] rows of several segments: (row, first partial slot, segments, -)
@@ -83,6 +88,20 @@ struct SortScratch {
   uint32_t *vals[2];
   uint32_t *hist;          // [256 * max sort blocks] block histograms, then [256] digit totals
   unsigned long long *blk; // [scan blocks + 1] block sums of the compaction passes
+};
+
+// Staging between the cache and the host link (one instance; the prefetch stage is serial).
+//   in   : rows fetched ahead for the inserts of the batch being prefetched
+//   out  : victims of the last committed batch, waiting to be written back
+struct Staging {
+  char *in;            // [max_inserts * stride]
+  char *out;           // [max_inserts * stride]
+  char **wb_dst;       // [max_inserts] backing-tier row of each staged victim (null = none)
+  uint32_t *wb_rb;     // [max_inserts] row bytes
+  int32_t *wb_n;       // number of staged victims slots (device scalar)
+  uint32_t *dirty;     // bitmap over sort keys: backing-tier copy is being written
+  uint32_t stride;     // bytes per staged row (widest row)
+  int64_t max_inserts;
 };
 
 struct Geometry {
@@ -114,15 +133,23 @@ hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *resul
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
                               hipStream_t s);
-hipError_t launch_fill(const TableMeta *tm, const Geometry &g, const BatchBuf &b, float *cache_m,
-                       unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
-hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, float *cache_m,
-                        unsigned long long *bytes_d2h, hipStream_t s);
+// write back the staged victims and (b != null) fetch ahead the rows b's batch inserts
+hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t *rb_of_table,
+                           unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
+// flag cur's inserts whose backing-tier copy is still being written (dirty bitmap), then
+// clear the marks of `prev` (may be null) and set those of `cur`
+hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, const Staging &st,
+                                unsigned long long *n_late, hipStream_t s);
+// move b's victims to the staging area and its new rows into the cache lines
+hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const Staging &st, unsigned long long *bytes_h2d,
+                         hipStream_t s);
+hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, unsigned long long *bytes_d2h,
+                        hipStream_t s);
 hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
                                   float *out, hipStream_t s);
 hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
-                                   const BatchBuf &b, const float *grad_out, float *cache_m, float *partials,
-                                   float lr, float eps, hipStream_t s);
+                                   const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,
+                                   hipStream_t s);
 
 // ---- small device helpers ----
 

@@ -22,7 +22,7 @@ ERRORS = {0: "TBE_OK", -1: "TBE_EINVAL", -2: "TBE_ERANGE", -3: "TBE_EORDER", -4:
 EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "tbe_flush", "tbe_destroy",
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times"]
-STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4}
+STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5}
 
 
 class TableSpec(C.Structure):
@@ -40,7 +40,7 @@ class BatchStats(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [("last", BatchStats), ("total", BatchStats), ("h2d_bytes", C.c_int64), ("d2h_bytes", C.c_int64),
-                ("batch_id", C.c_int32), ("reserved", C.c_int32)]
+                ("late_fetches", C.c_int64), ("batch_id", C.c_int32), ("reserved", C.c_int32)]
 
 
 class TbeError(RuntimeError):
@@ -169,7 +169,7 @@ class TBE:
         s = Stats()
         self._check(lib().tbe_get_stats(self._h, C.byref(s)), "tbe_get_stats")
         return {"last": s.last.as_dict(), "total": s.total.as_dict(), "h2d_bytes": int(s.h2d_bytes),
-                "d2h_bytes": int(s.d2h_bytes), "batch_id": int(s.batch_id)}
+                "d2h_bytes": int(s.d2h_bytes), "late_fetches": int(s.late_fetches), "batch_id": int(s.batch_id)}
 
     def set_profiling(self, enable: bool):
         self._check(lib().tbe_set_profiling(self._h, 1 if enable else 0), "tbe_set_profiling")
