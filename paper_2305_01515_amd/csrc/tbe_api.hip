@@ -34,6 +34,10 @@ struct DevAlloc {  // everything hipMalloc'ed, freed together
 
 }  // namespace
 
+// Batch buffers rotate over three: the buffer of batch k is still read after k has trained
+// (its bypass list by the commit of batch k+1) while batch k+2 is already being prefetched.
+constexpr int kBatchBufs = 3;
+
 struct tbe_ctx {
   Geometry g{};
   std::vector<TableMeta> tm;  // host copy
@@ -44,7 +48,7 @@ struct tbe_ctx {
   float *d_state = nullptr;   // row-wise Adagrad accumulators of all rows of all tables
   float *partials = nullptr;  // segment sums of the backward's longest rows
   char *lines = nullptr;
-  BatchBuf buf[2]{};
+  BatchBuf buf[kBatchBufs]{};
   SortScratch ss{};
   Staging st{};
   uint32_t *d_rb = nullptr;  // row bytes of every table
@@ -54,10 +58,8 @@ struct tbe_ctx {
   hipStream_t cs = nullptr, as = nullptr;  // compute / prefetch streams (caller's)
   hipStream_t ls = nullptr;                // host-link stream: transfer and commit (own, unless cs == as)
   bool own_ls = false;
-  hipEvent_t ev_inputs = nullptr, ev_ready[2] = {nullptr, nullptr}, ev_trained[2] = {nullptr, nullptr};
-  hipEvent_t ev_probed[2] = {nullptr, nullptr};
+  hipEvent_t ev_inputs = nullptr, ev_ready[kBatchBufs] = {}, ev_trained[kBatchBufs] = {}, ev_probed[kBatchBufs] = {};
   int64_t flush_state_bytes = 0;
-  bool trained_recorded[2] = {false, false};
   int32_t max_batch = 0;
   int64_t max_lookups = 0;
   int32_t k = 0;
@@ -156,6 +158,11 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.ins_src, 8 * N));
   HIP_TRY(h, h->mem.get(&b.ins_late, N));
   HIP_TRY(h, h->mem.get(&b.byp_idx, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.byp_tab, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.byp_key, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.byp_src, 8 * N));
+  HIP_TRY(h, h->mem.get(&b.byp_late, N));
+  HIP_TRY(h, h->mem.get(&b.ovf, N * (size_t)h->g.ovf_stride));
   HIP_TRY(h, h->mem.get(&b.items, 16 * (N / kLongRun + N / kSegment + 2)));
   HIP_TRY(h, h->mem.get(&b.huge, 16 * (N / kSegment + 2)));
   HIP_TRY(h, h->mem.get(&b.cnt, sizeof(BatchCounters)));
@@ -167,7 +174,7 @@ int device_error_code(int e) { return e == 0 ? 0 : e == 1 ? TBE_EINVAL : TBE_ERA
 
 // After a synchronisation: pick up errors the device recorded.
 int collect_device_errors(tbe_ctx *h) {
-  for (int i = 0; i < 2; i++) {
+  for (int i = 0; i < kBatchBufs; i++) {
     BatchCounters c;
     HIP_TRY(h, hipMemcpy(&c, h->buf[i].cnt, sizeof(c), hipMemcpyDeviceToHost));
     if (c.err && !h->sticky) {
@@ -188,11 +195,12 @@ int sync_all(tbe_ctx *h) {
 
 // Victims of batch `bi` to the staging area, its new rows into the cache lines; then the
 // batch is ready for forward.  Must follow the update of the batch before it.
-int enqueue_commit(tbe_ctx *h, int bi) {
+int enqueue_commit(tbe_ctx *h, int bi, bool wb_prev) {
   BatchBuf &b = h->buf[bi];
   {
     StageTimer tm_(h, TBE_STAGE_COMMIT, h->ls);
-    HIP_TRY(h, launch_commit(h->d_tm, b, h->st, h->d_bytes, h->ls));
+    HIP_TRY(h, launch_commit(h->d_tm, b, b.prev_bi >= 0 ? &h->buf[b.prev_bi] : nullptr, wb_prev, h->st, h->d_rb,
+                             h->d_bytes, h->d_bytes + 1, h->ls));
   }
   HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->ls));
   return TBE_OK;
@@ -202,9 +210,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
   if (!d_offsets || batch < 0 || n < 0 || (n > 0 && !d_indices)) return fail(h, TBE_EINVAL, "prefetch: bad argument");
   if (batch > h->max_batch || n > h->max_lookups) return fail(h, TBE_ELIMIT, "prefetch: batch or lookups above the sizes given to tbe_create");
   if (h->n_pend + (h->current >= 0 ? 1 : 0) > 1) return fail(h, TBE_EORDER, "prefetch: more than one batch would be ahead of training");
-  // a free buffer: not pending, not current
-  int bi = 0;
-  while (bi < 2 && (bi == h->current || (h->n_pend > 0 && h->pend[0] == bi))) bi++;
+  const int bi = h->k % kBatchBufs;  // free: at most the batch before this one is still in use
   BatchBuf &b = h->buf[bi];
   const bool in_flight = h->n_pend > 0 || h->current >= 0;
   b.d_indices = d_indices; b.d_offsets = d_offsets; b.batch = batch; b.n = n; b.k = ++h->k;
@@ -241,13 +247,14 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     StageTimer tm_(h, TBE_STAGE_FILL, h->ls);
     HIP_TRY(h, launch_transfer(&b, h->st, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
   }
+  b.prev_bi = h->prev_buf;
   h->prev_buf = bi;
   h->pend[h->n_pend++] = bi;
   if (in_flight) {
     h->deferred = bi;  // its cache lines may still be in use: commit after that batch's update
     return TBE_OK;
   }
-  return enqueue_commit(h, bi);
+  return enqueue_commit(h, bi, false);
 }
 
 }  // namespace
@@ -274,7 +281,7 @@ int tbe_destroy(tbe_handle h) {
   h->mem.release();
   drop_profile(h);
   if (h->ev_inputs) (void)hipEventDestroy(h->ev_inputs);
-  for (int i = 0; i < 2; i++) {
+  for (int i = 0; i < kBatchBufs; i++) {
     if (h->ev_ready[i]) (void)hipEventDestroy(h->ev_ready[i]);
     if (h->ev_trained[i]) (void)hipEventDestroy(h->ev_trained[i]);
     if (h->ev_probed[i]) (void)hipEventDestroy(h->ev_probed[i]);
@@ -354,6 +361,8 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   h->g.sum_dim = (int32_t)col;
   h->g.total_sets = (uint32_t)sets;
   h->g.total_slots = (int64_t)sets * ways;
+  h->g.ovf_stride = 16;
+  for (const TableMeta &m : h->tm) h->g.ovf_stride = std::max(h->g.ovf_stride, m.row_bytes);
   h->g.key_bits = 1;
   while (h->g.key_bits < 32 && (1ull << h->g.key_bits) < key) h->g.key_bits++;
 
@@ -410,7 +419,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
       h->ci.cls_tables[c] = d_ids;
     }
   }
-  for (int i = 0; i < 2; i++) {
+  for (int i = 0; i < kBatchBufs; i++) {
     int rc = alloc_batchbuf(h, h->buf[i], max_lookups);
     if (rc) { g_create_error = h->err; return bail(rc); }
     CREATE_TRY(hipEventCreateWithFlags(&h->ev_ready[i], hipEventDisableTiming));
@@ -432,7 +441,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   {
     Staging &st = h->st;
     st.max_inserts = std::min<int64_t>(max_lookups, h->g.total_slots);
-    st.stride = 16;
+    st.stride = h->g.ovf_stride;
     std::vector<uint32_t> rb(num_tables);
     for (int t = 0; t < num_tables; t++) { rb[t] = h->tm[t].row_bytes; st.stride = std::max(st.stride, rb[t]); }
     const size_t M = (size_t)st.max_inserts;
@@ -513,11 +522,14 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
     HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_trained[bi], 0));
     HIP_TRY(h, hipStreamWaitEvent(h->ls, h->ev_trained[bi], 0));
   }
+  // the rows this batch bypassed were trained on in HBM copies: back to the backing tier,
+  // together with the commit of the next batch when that one is waiting
   if (h->deferred >= 0) {
     const int d = h->deferred;
     h->deferred = -1;
-    return enqueue_commit(h, d);
+    return enqueue_commit(h, d, true);
   }
+  HIP_TRY(h, launch_ovf_writeback(h->buf[bi], h->st, h->d_rb, h->d_bytes + 1, h->ls));
   return TBE_OK;
 }
 

@@ -216,6 +216,10 @@ struct StatusOp {
   uint32_t *ins_key;
   char **ins_src;
   int32_t *byp_idx;
+  int32_t *byp_tab;
+  uint32_t *byp_key;
+  char **byp_src;
+  int32_t *loc_u;
   // per-thread tallies (the emit kernel keeps one Op copy per thread in registers)
   mutable unsigned int hits, evs;
   mutable u64 hit_lookups;
@@ -236,7 +240,15 @@ struct StatusOp {
       ins_src[i] = m.host_w + (size_t)row * m.row_bytes;
       if (old_tag[u] >= 0) evs++;
     } else if (f) {
-      byp_idx[pre >> 32] = u;
+      const uint32_t j = (uint32_t)(pre >> 32);
+      const uint32_t key = uniq_key[u];
+      const int t = find_table(tm, T, key);
+      const TableMeta &m = tm[t];
+      byp_idx[j] = u;
+      byp_tab[j] = t;
+      byp_key[j] = key;
+      byp_src[j] = m.host_w + (size_t)row_of_key(m, key) * m.row_bytes;
+      loc_u[u] = -2 - (int32_t)j;  // the row is served from the j-th overflow slot
     } else if (status[u] == ST_HIT) {
       hits++;
       hit_lookups += (u64)(run_off[u + 1] - run_off[u]);
@@ -386,7 +398,7 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   hipLaunchKernelGGL(probe_kernel, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key, b.touched,
                      tags, ts, b.loc_u, b.status, b.old_tag, b.cnt);
   StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.ins_idx, b.ins_tab, b.ins_key, b.ins_src,
-              b.byp_idx, 0u, 0u, 0ull};
+              b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u, 0u, 0u, 0ull};
   run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
   const int fin_blocks = (n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096;
   hipLaunchKernelGGL(finalize_kernel, dim3(fin_blocks), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.loc,

@@ -33,10 +33,10 @@ __device__ inline void accumulate(float (&acc)[Elems<DT>::n], const uint4 &v) {
 template <int DT, int G>
 __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restrict__ tm,
                                                       const int32_t *__restrict__ class_tables, int B, int sum_dim,
-                                                      const int64_t *__restrict__ indices,
                                                       const int64_t *__restrict__ offsets,
-                                                      const int32_t *__restrict__ loc, float *__restrict__ out,
-                                                      const BatchCounters *cnt) {
+                                                      const int32_t *__restrict__ loc,
+                                                      const char *__restrict__ ovf, uint32_t ovf_stride,
+                                                      float *__restrict__ out, const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   if (cnt->err) return;
   const int t = class_tables[blockIdx.y];
@@ -47,7 +47,6 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
   const bool active = lig * EPL < m.dim;
   const int64_t lo = offsets[(int64_t)t * B + b], hi = offsets[(int64_t)t * B + b + 1];
   const char *lines = m.lines;
-  const char *host_w = m.host_w;
   const uint32_t rb = m.row_bytes;
   const int slot_base = m.slot_base;
   float acc[EPL];
@@ -55,19 +54,14 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
   for (int e = 0; e < EPL; e++) acc[e] = 0.f;
   for (int64_t j0 = lo; j0 < hi; j0 += G) {
     const int nq = (int)((hi - j0) < G ? (hi - j0) : G);
-    int my_loc = -1, my_row = 0;
-    if (lig < nq) {
-      my_loc = loc[j0 + lig];
-      if (my_loc < 0) my_row = (int)indices[j0 + lig];
-    }
+    const int my_loc = lig < nq ? loc[j0 + lig] : 0;
     for (int q = 0; q < nq; q += 4) {
       uint4 v[4];
 #pragma unroll
       for (int x = 0; x < 4; x++) {
         const int src = (q + x) & (G - 1);
         const int l = __shfl(my_loc, src, G);
-        const int r = __shfl(my_row, src, G);
-        const char *p = l >= 0 ? lines + (size_t)(l - slot_base) * rb : host_w + (size_t)r * rb;
+        const char *p = l >= 0 ? lines + (size_t)(l - slot_base) * rb : ovf + (size_t)(-2 - l) * ovf_stride;
         v[x] = (active && q + x < nq) ? *(const uint4 *)(p + lig * 16) : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
@@ -126,11 +120,10 @@ struct RowRef {
 
 // The accumulators of all rows stay in HBM (the paper keeps optimizer parameters there,
 // Section 5.6.1): only the row itself is in a cache line or in the backing tier.
-__device__ inline RowRef locate(const TableMeta &m, uint32_t key, int slot) {
+__device__ inline RowRef locate(const TableMeta &m, uint32_t key, int slot, char *ovf, uint32_t ovf_stride) {
   RowRef r;
-  const uint32_t row = row_of_key(m, key);
-  r.w = slot >= 0 ? m.lines + (size_t)(slot - m.slot_base) * m.row_bytes : m.host_w + (size_t)row * m.row_bytes;
-  r.m = m.dev_m + row;
+  r.w = slot >= 0 ? m.lines + (size_t)(slot - m.slot_base) * m.row_bytes : ovf + (size_t)(-2 - slot) * ovf_stride;
+  r.m = m.dev_m + row_of_key(m, key);
   return r;
 }
 
@@ -168,14 +161,14 @@ __device__ inline void reduce_grads(float (&g)[Elems<DT>::n], const float *gbase
 
 // row-wise Adagrad on the row of distinct index u, gradient g spread over the group
 template <int DT, int G>
-__device__ inline void update_row(const TableMeta &m, uint32_t key, int slot,
+__device__ inline void update_row(const TableMeta &m, uint32_t key, int slot, char *ovf, uint32_t ovf_stride,
                                   const float (&g)[Elems<DT>::n], float lr, float eps, int lig, bool active) {
   constexpr int EPL = Elems<DT>::n;
   float sq = 0.f;
 #pragma unroll
   for (int e = 0; e < EPL; e++) sq += g[e] * g[e];
   for (int d = G / 2; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, G);
-  const RowRef r = locate(m, key, slot);
+  const RowRef r = locate(m, key, slot, ovf, ovf_stride);
   const float m_new = *r.m + sq / (float)m.dim;
   if (active) adagrad_apply<DT>(r.w + lig * 16, g, m_new, lr, eps);
   if (lig == 0) *r.m = m_new;
@@ -191,6 +184,7 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
                                                              const int32_t *__restrict__ sorted_bag,
                                                              const float *__restrict__ grad_out,
                                                              float lr, float eps,
+                                                             char *__restrict__ ovf, uint32_t ovf_stride,
                                                              const int32_t *__restrict__ table_class,
                                                              const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
@@ -210,7 +204,7 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
     reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, 0, 1, lig, active);
-    update_row<DT, G>(m, key, loc_u[u], g, lr, eps, lig, active);
+    update_row<DT, G>(m, key, loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
   }
 }
 
@@ -228,7 +222,8 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
                                                             const float *__restrict__ grad_out,
                                                             float *__restrict__ partials,
                                                             int pstride, float lr, float eps,
-                                                            const int32_t *__restrict__ table_class,
+                                                            char *__restrict__ ovf, uint32_t ovf_stride,
+                                                             const int32_t *__restrict__ table_class,
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int NG = 256 / G;
@@ -262,7 +257,7 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
         g[e] = s;
       }
       if (item.z == 1u) {
-        update_row<DT, G>(m, key, loc_u[u], g, lr, eps, lig, active);
+        update_row<DT, G>(m, key, loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
       } else if (active) {
         float *p = partials + (size_t)(item.w + item.y) * pstride + lig * EPL;
 #pragma unroll
@@ -280,7 +275,8 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
                                                                const uint4 *__restrict__ huge,
                                                                const float *__restrict__ partials, int pstride,
                                                                float lr, float eps,
-                                                               const int32_t *__restrict__ table_class,
+                                                               char *__restrict__ ovf, uint32_t ovf_stride,
+                                                             const int32_t *__restrict__ table_class,
                                                                const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   if (cnt->err) return;
@@ -304,7 +300,7 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
 #pragma unroll
         for (int e = 0; e < EPL; e++) g[e] += p[e];
       }
-    update_row<DT, G>(m, key, loc_u[u], g, lr, eps, lig, active);
+    update_row<DT, G>(m, key, loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
   }
 }
 
@@ -316,8 +312,8 @@ static void fwd_one(const TableMeta *tm, const int32_t *tables, int count, const
                     float *out, hipStream_t s) {
   const int bags_per_block = 256 / G;
   dim3 grid((b.batch + bags_per_block - 1) / bags_per_block, count);
-  hipLaunchKernelGGL((forward_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_indices,
-                     b.d_offsets, b.loc, out, b.cnt);
+  hipLaunchKernelGGL((forward_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_offsets,
+                     b.loc, b.ovf, g.ovf_stride, out, b.cnt);
 }
 
 template <int DT, int G>
@@ -326,12 +322,12 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
   if (which == 0) {
     hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
                        b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, b.items, grad_out, partials,
-                       g.partial_stride, lr, eps, table_class, b.cnt);
+                       g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
     hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, g.T, cls, b.uniq_key, b.loc_u,
-                       b.huge, partials, g.partial_stride, lr, eps, table_class, b.cnt);
+                       b.huge, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   } else {
     hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, table_class, b.cnt);
+                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   }
 }
 

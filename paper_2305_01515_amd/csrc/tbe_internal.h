@@ -52,7 +52,7 @@ struct BatchCounters {
 // batch k is still being trained on.
 struct BatchBuf {
   // per lookup
-  int32_t *loc;         // [N] location of the lookup's row: global slot id, or -1 = backing tier
+  int32_t *loc;         // [N] location of the lookup's row: global slot id, or -2-j = j-th bypassed row (ovf)
   int32_t *sorted_bag;  // [N] global bag id (t*B + b) of the i-th lookup in sorted order
   int32_t *bag_of_pos;  // [N] global bag id of lookup j (input order)
   uint32_t *uid_sorted; // [N] index of the distinct row of the i-th sorted lookup
@@ -60,7 +60,7 @@ struct BatchBuf {
   uint32_t *uniq_key;   // [N]
   int32_t *run_off;     // [N+1] first sorted position of each distinct row; run_off[U] = N
   uint32_t *uniq_sid;   // [N] global set id or kNoSet
-  int32_t *loc_u;       // [N] global slot id or -1
+  int32_t *loc_u;       // [N] global slot id, or -2-j for the j-th bypassed row
   uint8_t *status;      // [N] Status
   int32_t *old_tag;     // [N] for inserts: row that was evicted, -1 if the entry was free
   uint2 *touched;       // [N] (global set id, first distinct row) of every touched set
@@ -70,7 +70,12 @@ struct BatchBuf {
   char **ins_src;       // [N]   its row in the backing tier
   uint8_t *ins_late;    // [N]   1 = the backing-tier copy was still being written when the
                         //       early fetch ran: the row is fetched at commit time instead
-  int32_t *byp_idx;     // [N] distinct-row indices of the bypasses, ascending
+  int32_t *byp_idx;     // [N] distinct-row indices of the bypasses, ascending; per bypass also:
+  int32_t *byp_tab;     // [N]   its table
+  uint32_t *byp_key;    // [N]   its sort key
+  char **byp_src;       // [N]   its row in the backing tier
+  uint8_t *byp_late;    // [N]   as ins_late
+  char *ovf;            // [N * stride] HBM copies of the bypassed rows while their batch trains
   uint4 *items;         // [N/kLongRun + N/kSegment + 2] (row, segment, segments, first partial slot)
   uint4 *huge;          // [N/kSegment + 2] rows of several segments: (row, first partial slot, segments, -)
   BatchCounters *cnt;   // device
@@ -80,6 +85,7 @@ struct BatchBuf {
   int32_t batch;
   int64_t n;
   int32_t k;
+  int32_t prev_bi;      // buffer of the batch prefetched before this one, -1 = none
 };
 
 // Scratch shared by all batches (only used inside the prefetch stage, which is serial).
@@ -109,6 +115,7 @@ struct Geometry {
   int32_t sum_dim;
   int32_t key_bits;     // bits of the largest sort key
   int32_t partial_stride;  // floats per partial-sum slot (widest row, padded to whole lanes)
+  uint32_t ovf_stride;     // bytes per overflow / staging slot (widest row)
   uint32_t total_sets;
   int64_t total_slots;
 };
@@ -141,8 +148,13 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t 
 hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, const Staging &st,
                                 unsigned long long *n_late, hipStream_t s);
 // move b's victims to the staging area and its new rows into the cache lines
-hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const Staging &st, unsigned long long *bytes_h2d,
+// (prev = the batch before, null if none; wb_prev: also write prev's overflow rows back)
+hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, bool wb_prev, const Staging &st,
+                         const uint32_t *rb_of_table, unsigned long long *bytes_h2d, unsigned long long *bytes_d2h,
                          hipStream_t s);
+// after the batch's backward: its bypassed rows go from their HBM copies to the backing tier
+hipError_t launch_ovf_writeback(const BatchBuf &b, const Staging &st, const uint32_t *rb_of_table,
+                                unsigned long long *bytes_d2h, hipStream_t s);
 hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, unsigned long long *bytes_d2h,
                         hipStream_t s);
 hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
