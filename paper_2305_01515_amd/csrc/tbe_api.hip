@@ -148,20 +148,23 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.uniq_key, 4 * N));
   HIP_TRY(h, h->mem.get(&b.run_off, 4 * (N + 1)));
   HIP_TRY(h, h->mem.get(&b.uniq_sid, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.uniq_tab, 4 * N));
   HIP_TRY(h, h->mem.get(&b.loc_u, 4 * N));
   HIP_TRY(h, h->mem.get(&b.status, N));
   HIP_TRY(h, h->mem.get(&b.old_tag, 4 * N));
   HIP_TRY(h, h->mem.get(&b.touched, 8 * N));
   HIP_TRY(h, h->mem.get(&b.ins_idx, 4 * N));
   HIP_TRY(h, h->mem.get(&b.ins_tab, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.ins_slot, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.ins_old, 4 * N));
   HIP_TRY(h, h->mem.get(&b.ins_key, 4 * N));
   HIP_TRY(h, h->mem.get(&b.ins_src, 8 * N));
-  HIP_TRY(h, h->mem.get(&b.ins_late, N));
+  HIP_TRY(h, h->mem.get(&b.ins_where, 4 * N));
   HIP_TRY(h, h->mem.get(&b.byp_idx, 4 * N));
   HIP_TRY(h, h->mem.get(&b.byp_tab, 4 * N));
   HIP_TRY(h, h->mem.get(&b.byp_key, 4 * N));
   HIP_TRY(h, h->mem.get(&b.byp_src, 8 * N));
-  HIP_TRY(h, h->mem.get(&b.byp_late, N));
+  HIP_TRY(h, h->mem.get(&b.byp_where, 4 * N));
   HIP_TRY(h, h->mem.get(&b.ovf, N * (size_t)h->g.ovf_stride));
   HIP_TRY(h, h->mem.get(&b.items, 16 * (N / kLongRun + N / kSegment + 2)));
   HIP_TRY(h, h->mem.get(&b.huge, 16 * (N / kSegment + 2)));
@@ -200,7 +203,7 @@ int enqueue_commit(tbe_ctx *h, int bi, bool wb_prev) {
   {
     StageTimer tm_(h, TBE_STAGE_COMMIT, h->ls);
     HIP_TRY(h, launch_commit(h->d_tm, b, b.prev_bi >= 0 ? &h->buf[b.prev_bi] : nullptr, wb_prev, h->st, h->d_rb,
-                             h->d_bytes, h->d_bytes + 1, h->ls));
+                             h->d_bytes + 1, h->ls));
   }
   HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->ls));
   return TBE_OK;
@@ -446,14 +449,15 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     for (int t = 0; t < num_tables; t++) { rb[t] = h->tm[t].row_bytes; st.stride = std::max(st.stride, rb[t]); }
     const size_t M = (size_t)st.max_inserts;
     CREATE_TRY(h->mem.get(&st.in, M * st.stride));
-    CREATE_TRY(h->mem.get(&st.out, M * st.stride));
+    for (int p2 = 0; p2 < 2; p2++) {
+      CREATE_TRY(h->mem.get(&st.out[p2], M * st.stride));
+    }
     CREATE_TRY(h->mem.get(&st.wb_dst, 8 * M));
     CREATE_TRY(h->mem.get(&st.wb_rb, 4 * M));
     CREATE_TRY(h->mem.get(&st.wb_n, 16));
     CREATE_TRY(hipMemset(st.wb_n, 0, 16));
-    const size_t words = (size_t)((key + 31) / 32) + 1;
-    CREATE_TRY(h->mem.get(&st.dirty, 4 * words));
-    CREATE_TRY(hipMemset(st.dirty, 0, 4 * words));
+    CREATE_TRY(h->mem.get(&st.where, 4 * (size_t)key));
+    CREATE_TRY(hipMemset(st.where, 0, 4 * (size_t)key));
     CREATE_TRY(h->mem.get(&h->d_rb, 4 * (size_t)num_tables));
     CREATE_TRY(hipMemcpy(h->d_rb, rb.data(), 4 * (size_t)num_tables, hipMemcpyHostToDevice));
   }

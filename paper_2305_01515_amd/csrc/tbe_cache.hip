@@ -132,6 +132,7 @@ struct DedupOp {
   uint32_t *uniq_key;
   int32_t *run_off;
   uint32_t *uniq_sid;
+  int32_t *uniq_tab;
   __device__ u64 flag(int i, int) const { return (i == 0 || key[i] != key[i - 1]) ? 1ull : 0ull; }
   __device__ void emit(int i, int, u64 pre, u64 f) const {
     const uint32_t u = (uint32_t)(pre & 0xFFFFFFFFull) + (uint32_t)f - 1u;
@@ -141,7 +142,9 @@ struct DedupOp {
       const uint32_t k = key[i];
       uniq_key[u] = k;
       run_off[u] = i;
-      const TableMeta &m = tm[find_table(tm, T, k)];
+      const int t = find_table(tm, T, k);
+      const TableMeta &m = tm[t];
+      uniq_tab[u] = t;
       uniq_sid[u] = m.sets ? m.set_base + (k - m.key_base) / m.rows_per_set : kNoSet;
     }
   }
@@ -211,8 +214,11 @@ struct StatusOp {
   const int32_t *run_off;
   const int32_t *old_tag;
   const uint32_t *uniq_key;
+  const int32_t *uniq_tab;
   int32_t *ins_idx;
   int32_t *ins_tab;
+  int32_t *ins_slot;
+  int32_t *ins_old;
   uint32_t *ins_key;
   char **ins_src;
   int32_t *byp_idx;
@@ -231,18 +237,21 @@ struct StatusOp {
     if (f == 1ull) {
       const uint32_t i = (uint32_t)(pre & 0xFFFFFFFFull);
       const uint32_t key = uniq_key[u];
-      const int t = find_table(tm, T, key);
+      const int t = uniq_tab[u];
       const TableMeta &m = tm[t];
       const uint32_t row = row_of_key(m, key);
+      const int32_t old = old_tag[u];
       ins_idx[i] = u;
       ins_tab[i] = t;
+      ins_slot[i] = loc_u[u];
+      ins_old[i] = old;
       ins_key[i] = key;
       ins_src[i] = m.host_w + (size_t)row * m.row_bytes;
-      if (old_tag[u] >= 0) evs++;
+      if (old >= 0) evs++;
     } else if (f) {
       const uint32_t j = (uint32_t)(pre >> 32);
       const uint32_t key = uniq_key[u];
-      const int t = find_table(tm, T, key);
+      const int t = uniq_tab[u];
       const TableMeta &m = tm[t];
       byp_idx[j] = u;
       byp_tab[j] = t;
@@ -283,6 +292,7 @@ struct StatusOp {
 // --------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restrict__ tm, int T, int W, int32_t k,
                                                       const uint32_t *__restrict__ uniq_key,
+                                                      const int32_t *__restrict__ uniq_tab,
                                                       const uint2 *__restrict__ touched, int32_t *__restrict__ tags,
                                                       int32_t *__restrict__ ts, int32_t *__restrict__ loc_u,
                                                       uint8_t *__restrict__ status, int32_t *__restrict__ old_tag,
@@ -305,7 +315,7 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
       }
       continue;
     }
-    const TableMeta &m = tm[find_table(tm, T, uniq_key[u0])];
+    const TableMeta &m = tm[uniq_tab[u0]];
     const uint32_t set = head.x - m.set_base;
     const int slot0 = (int)head.x * W;  // global slot id of way 0 (set_base * W == slot_base)
     const uint32_t key0 = m.key_base + set * m.rows_per_set;
@@ -387,7 +397,8 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
                               hipStream_t s) {
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
-  DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid};
+  DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
+            b.uniq_tab};
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
   run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
@@ -395,9 +406,11 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   int64_t max_touched = (int64_t)g.total_sets + g.T;
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
-  hipLaunchKernelGGL(probe_kernel, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key, b.touched,
+  hipLaunchKernelGGL(probe_kernel, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key, b.uniq_tab,
+                     b.touched,
                      tags, ts, b.loc_u, b.status, b.old_tag, b.cnt);
-  StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.ins_idx, b.ins_tab, b.ins_key, b.ins_src,
+  StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.uniq_tab, b.ins_idx, b.ins_tab, b.ins_slot,
+              b.ins_old, b.ins_key, b.ins_src,
               b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u, 0u, 0u, 0ull};
   run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
   const int fin_blocks = (n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096;

@@ -179,6 +179,7 @@ __device__ inline void update_row(const TableMeta &m, uint32_t key, int slot, ch
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__restrict__ tm, int T, int cls, int B,
                                                              int sum_dim, const uint32_t *__restrict__ uniq_key,
+                                                             const int32_t *__restrict__ uniq_tab,
                                                              const int32_t *__restrict__ run_off,
                                                              const int32_t *__restrict__ loc_u,
                                                              const int32_t *__restrict__ sorted_bag,
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
     const int i0 = run_off[u], i1 = run_off[u + 1];
     if (i1 - i0 > kLongRun) continue;
     const uint32_t key = uniq_key[u];
-    const int t = find_table(tm, T, key);
+    const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
@@ -215,6 +216,7 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__restrict__ tm, int T, int cls, int B,
                                                             int sum_dim, const uint32_t *__restrict__ uniq_key,
+                                                             const int32_t *__restrict__ uniq_tab,
                                                             const int32_t *__restrict__ run_off,
                                                             const int32_t *__restrict__ loc_u,
                                                             const int32_t *__restrict__ sorted_bag,
@@ -235,7 +237,7 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
     const uint4 item = items[it];  // (distinct row, segment, segments of the row, first partial slot)
     const int u = (int)item.x;
     const uint32_t key = uniq_key[u];
-    const int t = find_table(tm, T, key);
+    const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
@@ -271,6 +273,7 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int T, int cls,
                                                                const uint32_t *__restrict__ uniq_key,
+                                                             const int32_t *__restrict__ uniq_tab,
                                                                const int32_t *__restrict__ loc_u,
                                                                const uint4 *__restrict__ huge,
                                                                const float *__restrict__ partials, int pstride,
@@ -287,7 +290,7 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
     const uint4 row = huge[hi];  // (distinct row, first partial slot, segments, -)
     const int u = (int)row.x;
     const uint32_t key = uniq_key[u];
-    const int t = find_table(tm, T, key);
+    const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
@@ -321,13 +324,14 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
                     const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps, hipStream_t s) {
   if (which == 0) {
     hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, b.items, grad_out, partials,
+                       b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, b.items, grad_out, partials,
                        g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
-    hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, g.T, cls, b.uniq_key, b.loc_u,
+    hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, g.T, cls, b.uniq_key, b.uniq_tab,
+                       b.loc_u,
                        b.huge, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   } else {
     hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                       b.uniq_key, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
+                       b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   }
 }
 

@@ -10,6 +10,10 @@ constexpr uint32_t kNoSet = 0xFFFFFFFFu;  // global set id of rows of a table wi
 constexpr int kLongRun = 64;              // rows with more lookups than this take the block-wide backward
 constexpr int kSegment = 1024;            // ... in segments of this many lookups, one block each
 
+constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
+constexpr uint32_t kWhereParked = 0x40000000u;    // among the victims the batch before parked
+constexpr uint32_t kWhereIndex = 0x3FFFFFFFu;
+
 enum Status : uint8_t { ST_MISS = 0, ST_HIT = 1, ST_INSERT = 2, ST_BYPASS = 3 };
 
 // Per-table constants, resident in device memory (array of T).
@@ -60,21 +64,24 @@ struct BatchBuf {
   uint32_t *uniq_key;   // [N]
   int32_t *run_off;     // [N+1] first sorted position of each distinct row; run_off[U] = N
   uint32_t *uniq_sid;   // [N] global set id or kNoSet
+  int32_t *uniq_tab;    // [N] table of the distinct row
   int32_t *loc_u;       // [N] global slot id, or -2-j for the j-th bypassed row
   uint8_t *status;      // [N] Status
   int32_t *old_tag;     // [N] for inserts: row that was evicted, -1 if the entry was free
   uint2 *touched;       // [N] (global set id, first distinct row) of every touched set
   int32_t *ins_idx;     // [N] distinct-row indices of the inserts, ascending; per insert also:
   int32_t *ins_tab;     // [N]   its table
+  int32_t *ins_slot;    // [N]   the global slot it takes
+  int32_t *ins_old;     // [N]   the row evicted from that slot, -1 if it was free
   uint32_t *ins_key;    // [N]   its sort key
   char **ins_src;       // [N]   its row in the backing tier
-  uint8_t *ins_late;    // [N]   1 = the backing-tier copy was still being written when the
-                        //       early fetch ran: the row is fetched at commit time instead
+  uint32_t *ins_where;  // [N]   0 = fetch it from the backing tier; else a kWhere* code: the backing-tier
+                        //       copy is stale, the current value is in HBM (see Staging::where)
   int32_t *byp_idx;     // [N] distinct-row indices of the bypasses, ascending; per bypass also:
   int32_t *byp_tab;     // [N]   its table
   uint32_t *byp_key;    // [N]   its sort key
   char **byp_src;       // [N]   its row in the backing tier
-  uint8_t *byp_late;    // [N]   as ins_late
+  uint32_t *byp_where;  // [N]   as ins_where
   char *ovf;            // [N * stride] HBM copies of the bypassed rows while their batch trains
   uint4 *items;         // [N/kLongRun + N/kSegment + 2] (row, segment, segments, first partial slot)
   uint4 *huge;          // [N/kSegment + 2] rows of several segments: (row, first partial slot, segments, -)
@@ -98,14 +105,17 @@ struct SortScratch {
 
 // Staging between the cache and the host link (one instance; the prefetch stage is serial).
 //   in   : rows fetched ahead for the inserts of the batch being prefetched
-//   out  : victims of the last committed batch, waiting to be written back
+//   out  : victims of the last two committed batches (by batch id parity): those of the
+//          latest wait to be written back; a row evicted by batch k and wanted again by k+1
+//          is taken from here instead of making the round trip over the link
 struct Staging {
   char *in;            // [max_inserts * stride]
-  char *out;           // [max_inserts * stride]
+  char *out[2];        // [max_inserts * stride] each
   char **wb_dst;       // [max_inserts] backing-tier row of each staged victim (null = none)
   uint32_t *wb_rb;     // [max_inserts] row bytes
-  int32_t *wb_n;       // number of staged victims slots (device scalar)
-  uint32_t *dirty;     // bitmap over sort keys: backing-tier copy is being written
+  int32_t *wb_n;       // [0] number of parked victim slots, [1] which `out` holds them (device)
+  uint32_t *where;     // [key span] per sort key: 0, or where the row's current value is while its
+                       // backing-tier copy is stale (kWhereOverflow | j, kWhereParked | i)
   uint32_t stride;     // bytes per staged row (widest row)
   int64_t max_inserts;
 };
@@ -143,15 +153,14 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
 // write back the staged victims and (b != null) fetch ahead the rows b's batch inserts
 hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t *rb_of_table,
                            unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
-// flag cur's inserts whose backing-tier copy is still being written (dirty bitmap), then
-// clear the marks of `prev` (may be null) and set those of `cur`
+// look up, for the rows cur inserts or bypasses, whether their backing-tier copy is stale
+// and where the current value is; then remove prev's entries from the map and enter cur's
 hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, const Staging &st,
                                 unsigned long long *n_late, hipStream_t s);
 // move b's victims to the staging area and its new rows into the cache lines
 // (prev = the batch before, null if none; wb_prev: also write prev's overflow rows back)
 hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, bool wb_prev, const Staging &st,
-                         const uint32_t *rb_of_table, unsigned long long *bytes_h2d, unsigned long long *bytes_d2h,
-                         hipStream_t s);
+                         const uint32_t *rb_of_table, unsigned long long *bytes_d2h, hipStream_t s);
 // after the batch's backward: its bypassed rows go from their HBM copies to the backing tier
 hipError_t launch_ovf_writeback(const BatchBuf &b, const Staging &st, const uint32_t *rb_of_table,
                                 unsigned long long *bytes_d2h, hipStream_t s);
