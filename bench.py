@@ -25,17 +25,33 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 HOST_LINK_PEAK_GBS = 64.0  # PCIe Gen5 x16, per direction
 
 
-def algorithmic_bytes(cfg, lookups_per_table, uniques_per_table, batch):
-    """Bytes the method itself must move per step, per kernel ('algorithmic bytes')."""
+def algorithmic_bytes(cfg, lookups_per_table, uniques, long_rows, batch):
+    """Bytes the method itself must move per step, per kernel."""
     from paper_2305_01515_amd import synth
-    fwd = bwd = 0
-    for t, tc in enumerate(cfg.tables):
-        rb = tc.dim * (4 if tc.dtype == synth.FP32 else 2)
-        fwd += lookups_per_table[t] * rb + 4 * lookups_per_table[t]          # rows + locations
-        bwd += uniques_per_table[t] * (2 * rb + 8)                           # row read-modify-write + state
-    fwd += 4 * batch * cfg.sum_dim                                           # pooled output
-    bwd += 4 * batch * cfg.sum_dim                                           # grad_out, read at least once
-    return fwd, bwd
+    T = len(cfg.tables)
+    rows_fwd = sum(lookups_per_table[t] * cfg.tables[t].dim * (4 if cfg.tables[t].dtype == synth.FP32 else 2)
+                   for t in range(T))
+    rb_mean = sum(tc.dim * (4 if tc.dtype == synth.FP32 else 2) for tc in cfg.tables) / T
+    grad_per_lookup = sum(lookups_per_table[t] * cfg.tables[t].dim * 4 for t in range(T))
+    io = 4 * batch * cfg.sum_dim                                   # pooled output / grad_out, once
+    fwd = rows_fwd + 4 * sum(lookups_per_table) + io               # rows per lookup (Eq. 3) + locations + output
+    bwd_short = (uniques - long_rows) * (2 * rb_mean + 8) + io     # row read-modify-write + accumulator + grad_out once
+    bwd_long = long_rows * (2 * rb_mean + 8) + io
+    return fwd, bwd_short, bwd_long, grad_per_lookup
+
+
+def measured_traffic(kernel_substr):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 --pmc summary
+    (profiles/bench_main_pmc.txt: FETCH_SIZE / WRITE_SIZE scaled by the copy-kernel factors)."""
+    path = os.path.join(ROOT, "profiles", "bench_main_pmc.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 4 and f[0] == "traffic" and f[1] == kernel_substr:
+                return float(f[2]) + float(f[3])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(cfg, W0, batches, grads, threads):
@@ -94,7 +110,8 @@ def main():
 
     # inputs of all steps, resident in HBM before anything is timed
     stream = synth.BatchStream(cfg, device=dev)
-    batches = [stream.next() for _ in range(K + Wm + 1)]
+    ISO = 4  # extra steps after the timed region, run stage by stage for isolated kernel times
+    batches = [stream.next() for _ in range(K + Wm + 1 + ISO)]
     grads = [synth.grad_out(cfg, s + 1, device=dev) for s in range(min(K + Wm, 6))]
     max_n = max(int(b[0].numel()) for b in batches)
     out = torch.empty(cfg.batch, cfg.sum_dim, dtype=torch.float32, device=dev)
@@ -128,7 +145,22 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     s1 = g.stats()
-    times = {k: g.stage_times(k) for k in ("prefetch", "fill", "commit", "forward", "backward_long", "backward_short")}
+    STAGES = ("prefetch", "fill", "commit", "forward", "backward_long", "backward_short")
+    times = {k: g.stage_times(k)[:K] for k in STAGES}  # one bracket per stage and timed step
+
+    # isolated pass (not part of `value`): the same kernels with nothing else on the GPU
+    g.forward(batches[Wm + K][0], batches[Wm + K][1], out)
+    g.backward_update(grads[0], cfg.lr, cfg.eps)
+    torch.cuda.synchronize()
+    g.set_profiling(True)
+    for s in range(Wm + K + 1, Wm + K + 1 + ISO):
+        g.prefetch(*batches[s])
+        torch.cuda.synchronize()
+        g.forward(batches[s][0], batches[s][1], out)
+        torch.cuda.synchronize()
+        g.backward_update(grads[s % len(grads)], cfg.lr, cfg.eps)
+        torch.cuda.synchronize()
+    iso = {k: float(np.mean(g.stage_times(k))) for k in STAGES}
 
     # the timed region trained batches Wm..Wm+K-1; it prefetched batches Wm+1..Wm+K (one ahead)
     lookups = sum(int(batches[s][0].numel()) for s in range(Wm, Wm + K))
@@ -142,13 +174,29 @@ def main():
     per_table = [int(off[(t + 1) * cfg.batch] - off[t * cfg.batch]) for t in range(T)]
     scale = (lookups / K) / max(1, sum(per_table))
     per_table = [p * scale for p in per_table]
-    uniq_per_table = [tot["uniques"] / npf / T] * T
-    fwd_b, bwd_b = algorithmic_bytes(cfg, per_table, uniq_per_table, cfg.batch)
+    uniq = tot["uniques"] / npf
+    long_rows = s1["last_long_rows"]
+    fwd_b, bws_b, bwl_b, grad_pl = algorithmic_bytes(cfg, per_table, uniq, long_rows, cfg.batch)
 
     ms = {k: float(np.mean(v)) if v.size else 0.0 for k, v in times.items()}
-    fwd_gbs = fwd_b / (ms["forward"] * 1e-3) / 1e9 if ms["forward"] else 0.0
+
+    def gbs(nbytes, t_ms):
+        return nbytes / (t_ms * 1e-3) / 1e9 if t_ms else 0.0
+
+    def roof(kernel, nbytes, t_ms, substr, iso_ms=None, extra=None):
+        r = {"kernel": kernel, "bound": "hbm", "achieved": gbs(nbytes, t_ms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+             "frac": gbs(nbytes, t_ms) / HBM_PEAK_GBS, "traffic": measured_traffic(substr),
+             "bytes_per_launch": nbytes, "ms_per_launch": t_ms}
+        if iso_ms is not None:  # the same launch with no other stream active
+            r["isolated"] = {"ms_per_launch": iso_ms, "achieved": gbs(nbytes, iso_ms),
+                             "frac": gbs(nbytes, iso_ms) / HBM_PEAK_GBS}
+        if extra:
+            r.update(extra)
+        return r
+
     bwd_ms = ms["backward_long"] + ms["backward_short"]
-    bwd_gbs = bwd_b / (bwd_ms * 1e-3) / 1e9 if bwd_ms else 0.0
+    hit_ms = ms["forward"] + bwd_ms
+    hit_b = fwd_b + bws_b + bwl_b - 4 * cfg.batch * cfg.sum_dim  # grad_out counted once
     fill_ms = ms["fill"]
     res = {
         "metric": "pooled lookups/s (fwd+bwd+update), achieved HBM GB/s, cache hit rate",
@@ -163,26 +211,36 @@ def main():
                                "next-batch prefetch ahead of training",
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
                    "overlap": not args.no_overlap},
-        "roofline": {"kernel": "forward_kernel<fp16, 16 lanes/row> (pooled gather, hit path)",
-                     "bound": "hbm", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "bytes_per_launch": fwd_b, "ms_per_launch": ms["forward"]},
-        "backward": {"kernels": "backward_long_kernel + backward_short_kernel (gradient reduction + row-wise Adagrad)",
-                     "achieved": bwd_gbs, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
-                     "bytes_per_step": bwd_b, "ms_long": ms["backward_long"], "ms_short": ms["backward_short"]},
-        "hit_path": {"ms_fwd_bwd": ms["forward"] + bwd_ms,
-                     "lookups_per_s": (lookups / K) / ((ms["forward"] + bwd_ms) * 1e-3) if bwd_ms else 0.0,
-                     "hbm_frac": (fwd_b + bwd_b) / ((ms["forward"] + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS if bwd_ms else 0.0},
+        # the HBM-bound kernel that takes longest in a step; grad_out counted once (compulsory),
+        # the per-lookup re-reads of gradient rows that miss L2 show up in `traffic`
+        "roofline": roof("backward_short_kernel<fp16, 16 lanes/row> (gradient reduction + row-wise Adagrad, rows with <= 64 lookups)",
+                         bws_b, ms["backward_short"], "backward_short_kernel", iso["backward_short"]),
+        "forward": roof("forward_kernel<fp16, 16 lanes/row> (pooled gather; rows counted once per lookup as in Eq. 3, "
+                        "repeats of hot rows are served by L2, hence frac can exceed 1)",
+                        fwd_b, ms["forward"], "forward_kernel", iso["forward"]),
+        "backward_long": roof("backward_long_kernel + backward_combine_kernel (rows with > 64 lookups)", bwl_b,
+                              ms["backward_long"], "backward_long_kernel", iso["backward_long"]),
+        "hit_path": {"ms_fwd_bwd": hit_ms, "bytes": hit_b, "lookups_per_s": (lookups / K) / (hit_ms * 1e-3) if hit_ms else 0.0,
+                     "achieved": gbs(hit_b, hit_ms), "frac": gbs(hit_b, hit_ms) / HBM_PEAK_GBS,
+                     "frac_if_gradients_counted_per_lookup": gbs(hit_b + grad_pl, hit_ms) / HBM_PEAK_GBS},
+        "hit_path_isolated": {"ms_fwd_bwd": iso["forward"] + iso["backward_long"] + iso["backward_short"],
+                              "achieved": gbs(hit_b, iso["forward"] + iso["backward_long"] + iso["backward_short"]),
+                              "frac": gbs(hit_b, iso["forward"] + iso["backward_long"] + iso["backward_short"]) / HBM_PEAK_GBS,
+                              "frac_if_gradients_counted_per_lookup":
+                              gbs(hit_b + grad_pl, iso["forward"] + iso["backward_long"] + iso["backward_short"]) / HBM_PEAK_GBS},
         "prefetch_stage_ms": ms["prefetch"], "commit_stage_ms": ms["commit"],
-        "host_link": {"ms_fill": fill_ms, "h2d_bytes_per_step": h2d, "d2h_bytes_per_step": d2h,
-                      "h2d_GBps": h2d / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0,
-                      "d2h_GBps": d2h / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0,
-                      "peak_GBps_per_direction": HOST_LINK_PEAK_GBS,
+        "isolated_stage_ms": iso,
+        # the kernel that takes longest overall: bound by the host link, not by HBM
+        "host_link": {"kernel": "transfer_kernel (write-back of parked victims + fetch-ahead of missed rows)",
+                      "bound": "host_link", "ms_per_launch": fill_ms, "h2d_bytes_per_step": h2d, "d2h_bytes_per_step": d2h,
+                      "achieved": max(h2d, d2h) / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0,
+                      "h2d_GBps": gbs(h2d, fill_ms), "d2h_GBps": gbs(d2h, fill_ms), "unit": "GB/s per direction",
+                      "peak": HOST_LINK_PEAK_GBS,
                       "frac": max(h2d, d2h) / (fill_ms * 1e-3) / 1e9 / HOST_LINK_PEAK_GBS if fill_ms else 0.0},
         "cache": {"hit_rate_unique": tot["hits"] / max(1, tot["uniques"]),
                   "hit_rate_lookup": tot["hit_lookups"] / max(1, tot["lookups"]),
                   "bypass_frac_unique": tot["bypasses"] / max(1, tot["uniques"]),
-                  "uniques_per_step": tot["uniques"] / npf, "inserts_per_step": tot["inserts"] / npf,
+                  "uniques_per_step": uniq, "inserts_per_step": tot["inserts"] / npf, "long_rows": long_rows,
                   "late_fetches_per_step": (s1["late_fetches"] - s0["late_fetches"]) / npf},
         "cpu_baseline": cpu,
     }

@@ -91,7 +91,7 @@ typedef struct {
   int64_t late_fetches;  /* inserted rows that had to wait for a pending write of   */
                          /* their backing-tier copy (fetched at commit time)        */
   int32_t batch_id;      /* k of the last prefetch                                  */
-  int32_t reserved;
+  int32_t last_long_rows; /* rows of the last batch with more than 64 lookups (segmented backward) */
 } tbe_stats;
 
 /*

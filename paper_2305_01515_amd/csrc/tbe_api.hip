@@ -597,6 +597,7 @@ int tbe_get_stats(tbe_handle h, tbe_stats *out) {
     out->last.bypasses = c.n_byp;
     out->last.evictions = (int64_t)c.evictions;
     out->last.hit_lookups = (int64_t)c.hit_lookups;
+    out->last_long_rows = c.n_long;
   }
   out->total.lookups = h->total_lookups;
   out->total.uniques = (int64_t)b64[2];

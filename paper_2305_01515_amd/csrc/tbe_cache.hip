@@ -192,8 +192,10 @@ __global__ __launch_bounds__(256) void long_runs_kernel(const int32_t *__restric
       if (lane >= d) { a += oa; b += ob; c += oc; }
     }
     const int ta = __shfl(a, 63), tb = __shfl(b, 63), tc = __shfl(c, 63);
+    const int n_rows = __popcll(__ballot(nseg > 0));
     int ba = 0, bb = 0, bc = 0;
     if (lane == 63) {
+      if (n_rows) atomicAdd(&cnt->n_long, n_rows);
       if (ta) ba = atomicAdd(&cnt->n_items, ta);
       if (tb) bb = atomicAdd(&cnt->n_partials, tb);
       if (tc) bc = atomicAdd(&cnt->n_huge, tc);

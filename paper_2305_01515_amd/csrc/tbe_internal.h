@@ -50,6 +50,8 @@ struct BatchCounters {
   int32_t n_huge;     // rows of more than one segment
   int32_t n_partials; // partial-sum slots handed to those rows
   unsigned long long hits, evictions, hit_lookups;
+  int32_t n_long;     // rows with more than kLongRun lookups
+  int32_t pad0;
 };
 
 // Arrays of one batch; two of these exist so that batch k+1 can be prepared while

@@ -40,7 +40,7 @@ class BatchStats(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [("last", BatchStats), ("total", BatchStats), ("h2d_bytes", C.c_int64), ("d2h_bytes", C.c_int64),
-                ("late_fetches", C.c_int64), ("batch_id", C.c_int32), ("reserved", C.c_int32)]
+                ("late_fetches", C.c_int64), ("batch_id", C.c_int32), ("last_long_rows", C.c_int32)]
 
 
 class TbeError(RuntimeError):
@@ -169,7 +169,7 @@ class TBE:
         s = Stats()
         self._check(lib().tbe_get_stats(self._h, C.byref(s)), "tbe_get_stats")
         return {"last": s.last.as_dict(), "total": s.total.as_dict(), "h2d_bytes": int(s.h2d_bytes),
-                "d2h_bytes": int(s.d2h_bytes), "late_fetches": int(s.late_fetches), "batch_id": int(s.batch_id)}
+                "d2h_bytes": int(s.d2h_bytes), "late_fetches": int(s.late_fetches), "last_long_rows": int(s.last_long_rows), "batch_id": int(s.batch_id)}
 
     def set_profiling(self, enable: bool):
         self._check(lib().tbe_set_profiling(self._h, 1 if enable else 0), "tbe_set_profiling")
