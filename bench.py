@@ -145,8 +145,8 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     s1 = g.stats()
-    STAGES = ("prefetch", "fill", "commit", "forward", "backward_long", "backward_short")
-    first = {k: (Wm if k in ("forward", "backward_long", "backward_short") else Wm + 1) for k in STAGES}
+    STAGES = ("prefetch", "fill", "commit", "forward", "backward_long", "backward_short", "backward_single")
+    first = {k: (Wm if k in ("forward", "backward_long", "backward_short", "backward_single") else Wm + 1) for k in STAGES}
     times = {k: g.stage_times(k)[first[k]:first[k] + K] for k in STAGES}  # the brackets of the timed steps
 
     # isolated pass (not part of `value`): the same kernels with nothing else on the GPU
@@ -195,7 +195,8 @@ def main():
             r.update(extra)
         return r
 
-    bwd_ms = ms["backward_long"] + ms["backward_short"]
+    bwd_ms = ms["backward_long"] + ms["backward_short"] + ms["backward_single"]
+    iso_hit = iso["forward"] + iso["backward_long"] + iso["backward_short"] + iso["backward_single"]
     hit_ms = ms["forward"] + bwd_ms
     hit_b = fwd_b + bws_b + bwl_b - 4 * cfg.batch * cfg.sum_dim  # grad_out counted once
     fill_ms = ms["fill"]
@@ -224,11 +225,11 @@ def main():
         "hit_path": {"ms_fwd_bwd": hit_ms, "bytes": hit_b, "lookups_per_s": (lookups / K) / (hit_ms * 1e-3) if hit_ms else 0.0,
                      "achieved": gbs(hit_b, hit_ms), "frac": gbs(hit_b, hit_ms) / HBM_PEAK_GBS,
                      "frac_if_gradients_counted_per_lookup": gbs(hit_b + grad_pl, hit_ms) / HBM_PEAK_GBS},
-        "hit_path_isolated": {"ms_fwd_bwd": iso["forward"] + iso["backward_long"] + iso["backward_short"],
-                              "achieved": gbs(hit_b, iso["forward"] + iso["backward_long"] + iso["backward_short"]),
-                              "frac": gbs(hit_b, iso["forward"] + iso["backward_long"] + iso["backward_short"]) / HBM_PEAK_GBS,
+        "hit_path_isolated": {"ms_fwd_bwd": iso_hit,
+                              "achieved": gbs(hit_b, iso_hit),
+                              "frac": gbs(hit_b, iso_hit) / HBM_PEAK_GBS,
                               "frac_if_gradients_counted_per_lookup":
-                              gbs(hit_b + grad_pl, iso["forward"] + iso["backward_long"] + iso["backward_short"]) / HBM_PEAK_GBS},
+                              gbs(hit_b + grad_pl, iso_hit) / HBM_PEAK_GBS},
         "prefetch_stage_ms": ms["prefetch"], "commit_stage_ms": ms["commit"],
         "isolated_stage_ms": iso,
         # mean over every launch of the process (warm-up, timed, isolated): what rocprofv3 --stats averages

@@ -166,8 +166,12 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.byp_src, 8 * N));
   HIP_TRY(h, h->mem.get(&b.byp_where, 4 * N));
   HIP_TRY(h, h->mem.get(&b.ovf, N * (size_t)h->g.ovf_stride));
-  HIP_TRY(h, h->mem.get(&b.items, 16 * (N / kLongRun + N / kSegment + 2)));
-  HIP_TRY(h, h->mem.get(&b.huge, 16 * (N / kSegment + 2)));
+  HIP_TRY(h, h->mem.get(&b.mid_idx, 4 * (N / 2 + 1)));
+  HIP_TRY(h, h->mem.get(&b.items, 4 * (N / kLongRun + 1)));
+  HIP_TRY(h, h->mem.get(&b.huge, 4 * (N / kHugeRun + 1)));
+  HIP_TRY(h, h->mem.get(&b.huge_sorted, 4 * (N / kHugeRun + 1)));
+  HIP_TRY(h, h->mem.get(&b.hchunks, 16 * (N / kHugeRun + (size_t)h->g.T + 1)));
+  HIP_TRY(h, h->mem.get(&b.hg_count, 4 * 3 * ((size_t)h->g.T + 1)));
   HIP_TRY(h, h->mem.get(&b.cnt, sizeof(BatchCounters)));
   HIP_TRY(h, hipMemset(b.cnt, 0, sizeof(BatchCounters)));
   return TBE_OK;
@@ -344,7 +348,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     col += s.dim;
     line_off[t] = line_bytes;
     line_bytes += ((size_t)m.sets * ways * m.row_bytes + 255) & ~(size_t)255;
-    if (key > (1ull << 32) || sets * ways >= (1ull << 31) || col >= (1ll << 30)) {
+    if (key > (1ull << 32) || sets * ways >= (1ull << 30) || col >= (1ll << 30)) {
       delete h;
       return fail(nullptr, TBE_ELIMIT, "create: key space, slot count or output width too large");
     }
@@ -439,7 +443,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     int widest = 0;
     for (const TableMeta &m : h->tm) widest = std::max(widest, m.lanes * (m.dtype == TBE_FP32 ? 4 : 8));
     h->g.partial_stride = widest;
-    CREATE_TRY(h->mem.get(&h->partials, 4 * (size_t)widest * (2 * (N / kSegment) + 2)));
+    CREATE_TRY(h->mem.get(&h->partials, 4 * (size_t)widest * kHugeRanges * (N / kHugeRun + 1)));
   }
   {
     Staging &st = h->st;
@@ -514,6 +518,10 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_LONG, h->cs);
     HIP_TRY(h, launch_backward_classes(true, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
+  }
+  {
+    StageTimer tm_(h, TBE_STAGE_BACKWARD_SINGLE, h->cs);
+    HIP_TRY(h, launch_backward_single_classes(h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, lr, eps, h->cs));
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);

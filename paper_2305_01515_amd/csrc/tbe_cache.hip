@@ -168,43 +168,83 @@ struct SetHeadOp {
   __device__ void finish(BatchCounters *cnt, int, u64 total) const { cnt->n_touched = (int32_t)(total & 0xFFFFFFFFull); }
 };
 
-// Work list of the backward for rows with more than kLongRun lookups: one item per
-// segment of kSegment lookups; rows of several segments also get partial-sum slots and an
-// entry in the `huge` list.  List positions are handed out with one atomic per wavefront.
-__global__ __launch_bounds__(256) void long_runs_kernel(const int32_t *__restrict__ run_off, uint4 *items, uint4 *huge,
-                                                        BatchCounters *cnt) {
+// Work lists of the backward by run length (see kLongRun / kHugeRun).  A workgroup takes a
+// contiguous chunk of the distinct rows: it counts the three kinds per wavefront, reserves
+// its list ranges with one atomic per list, then writes the rows out in order.
+__global__ __launch_bounds__(256) void worklist_kernel(const int32_t *__restrict__ run_off, int32_t *mid_idx,
+                                                       int32_t *items, int32_t *huge, BatchCounters *cnt) {
+  __shared__ int s_cnt[4][3];
+  __shared__ int s_base[4][3];
   if (cnt->err) return;
   const int n = cnt->n_uniq;
-  const int lane = threadIdx.x & 63;
-  const int stride = gridDim.x * blockDim.x;
-  const int rounds = (n + stride - 1) / stride;
-  for (int r = 0; r < rounds; r++) {
-    const int u = r * stride + blockIdx.x * blockDim.x + threadIdx.x;
-    int len = 0;
-    if (u < n) len = run_off[u + 1] - run_off[u];
-    const int nseg = len > kLongRun ? (len + kSegment - 1) / kSegment : 0;
-    const int multi = nseg > 1 ? nseg : 0;
-    const int is_huge = nseg > 1 ? 1 : 0;
-    // exclusive prefix sums over the wavefront
-    int a = nseg, b = multi, c = is_huge;
-    for (int d = 1; d < 64; d <<= 1) {
-      const int oa = __shfl_up(a, d), ob = __shfl_up(b, d), oc = __shfl_up(c, d);
-      if (lane >= d) { a += oa; b += ob; c += oc; }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const int per_wave = ((n + gridDim.x * 4 - 1) / (gridDim.x * 4) + 63) / 64 * 64;
+  const int w0 = (blockIdx.x * 4 + wave) * per_wave;
+  const int w1 = min(n, w0 + per_wave);
+  int c_mid = 0, c_item = 0, c_huge = 0;
+  for (int u0 = w0; u0 < w1; u0 += 64) {
+    const int u = u0 + lane;
+    const int len = u < w1 ? run_off[u + 1] - run_off[u] : 0;
+    c_mid += __popcll(__ballot(len >= 2 && len <= kLongRun));
+    c_item += __popcll(__ballot(len > kLongRun && len <= kHugeRun));
+    c_huge += __popcll(__ballot(len > kHugeRun));
+  }
+  if (lane == 0) { s_cnt[wave][0] = c_mid; s_cnt[wave][1] = c_item; s_cnt[wave][2] = c_huge; }
+  __syncthreads();
+  if (threadIdx.x < 3) {
+    const int k = threadIdx.x;
+    const int tot = s_cnt[0][k] + s_cnt[1][k] + s_cnt[2][k] + s_cnt[3][k];
+    int base = 0;
+    if (tot) base = atomicAdd(k == 0 ? &cnt->n_mid : k == 1 ? &cnt->n_items : &cnt->n_huge, tot);
+    if (tot && k != 0) atomicAdd(&cnt->n_long, tot);
+    for (int w = 0; w < 4; w++) { s_base[w][k] = base; base += s_cnt[w][k]; }
+  }
+  __syncthreads();
+  int o_mid = s_base[wave][0], o_item = s_base[wave][1], o_huge = s_base[wave][2];
+  for (int u0 = w0; u0 < w1; u0 += 64) {
+    const int u = u0 + lane;
+    const int len = u < w1 ? run_off[u + 1] - run_off[u] : 0;
+    const bool is_mid = len >= 2 && len <= kLongRun;
+    const bool is_item = len > kLongRun && len <= kHugeRun;
+    const bool is_huge = len > kHugeRun;
+    const uint64_t bm = __ballot(is_mid), bi = __ballot(is_item), bh = __ballot(is_huge);
+    if (is_mid) mid_idx[o_mid + __popcll(bm & lt_mask)] = u;
+    if (is_item) items[o_item + __popcll(bi & lt_mask)] = u;
+    if (is_huge) huge[o_huge + __popcll(bh & lt_mask)] = u;
+    o_mid += __popcll(bm); o_item += __popcll(bi); o_huge += __popcll(bh);
+  }
+}
+
+// Group the huge rows by table and cut every table's group into chunks of `rows per
+// workgroup` of the table's kernel class (256 / lanes per row).  One workgroup; the number
+// of huge rows is small (a batch has fewer than N / kHugeRun of them).
+__global__ __launch_bounds__(1024) void huge_group_kernel(const TableMeta *__restrict__ tm, int T,
+                                                          const int32_t *__restrict__ huge,
+                                                          const int32_t *__restrict__ uniq_tab, int32_t *huge_sorted,
+                                                          uint4 *hchunks, int32_t *hg, BatchCounters *cnt) {
+  if (cnt->err) return;
+  const int n_huge = cnt->n_huge;
+  int32_t *count = hg, *offset = hg + (T + 1), *fill = hg + 2 * (T + 1);
+  for (int t = threadIdx.x; t <= T; t += blockDim.x) count[t] = offset[t] = fill[t] = 0;
+  __syncthreads();
+  for (int h = threadIdx.x; h < n_huge; h += blockDim.x) atomicAdd(&count[uniq_tab[huge[h]]], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int off = 0, nc = 0;
+    for (int t = 0; t < T; t++) {
+      offset[t] = off;
+      const int per = 256 / tm[t].lanes;
+      for (int c = 0; c < count[t]; c += per)
+        hchunks[nc++] = make_uint4((uint32_t)t, (uint32_t)(off + c), (uint32_t)min(per, count[t] - c), 0u);
+      off += count[t];
     }
-    const int ta = __shfl(a, 63), tb = __shfl(b, 63), tc = __shfl(c, 63);
-    const int n_rows = __popcll(__ballot(nseg > 0));
-    int ba = 0, bb = 0, bc = 0;
-    if (lane == 63) {
-      if (n_rows) atomicAdd(&cnt->n_long, n_rows);
-      if (ta) ba = atomicAdd(&cnt->n_items, ta);
-      if (tb) bb = atomicAdd(&cnt->n_partials, tb);
-      if (tc) bc = atomicAdd(&cnt->n_huge, tc);
-    }
-    ba = __shfl(ba, 63); bb = __shfl(bb, 63); bc = __shfl(bc, 63);
-    const int pbase = bb + b - multi;
-    for (int sgm = 0; sgm < nseg; sgm++)
-      items[ba + a - nseg + sgm] = make_uint4((uint32_t)u, (uint32_t)sgm, (uint32_t)nseg, (uint32_t)pbase);
-    if (is_huge) huge[bc + c - 1] = make_uint4((uint32_t)u, (uint32_t)pbase, (uint32_t)nseg, 0u);
+    cnt->n_hchunks = nc;
+  }
+  __syncthreads();
+  for (int h = threadIdx.x; h < n_huge; h += blockDim.x) {
+    const int t = uniq_tab[huge[h]];
+    huge_sorted[offset[t] + atomicAdd(&fill[t], 1)] = h;
   }
 }
 
@@ -384,14 +424,20 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
   }
 }
 
-// per-lookup location, in input order
+// per-lookup location word, in input order
 __global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__restrict__ pos,
                                                        const uint32_t *__restrict__ uid_sorted,
-                                                       const int32_t *__restrict__ loc_u, int32_t *__restrict__ loc,
+                                                       const int32_t *__restrict__ loc_u,
+                                                       const int32_t *__restrict__ run_off, uint32_t *__restrict__ loc,
                                                        const BatchCounters *cnt) {
   if (cnt->err) return;
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x)
-    loc[pos[i]] = loc_u[uid_sorted[i]];
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const uint32_t u = uid_sorted[i];
+    const int32_t lu = loc_u[u];
+    uint32_t w = lu >= 0 ? (uint32_t)lu : (kLocOverflow | (uint32_t)(-2 - lu));
+    if (run_off[u + 1] - run_off[u] == 1) w |= kLocSingle;
+    loc[pos[i]] = w;
+  }
 }
 
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
@@ -404,7 +450,9 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
   run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
-  hipLaunchKernelGGL(long_runs_kernel, dim3(512), dim3(256), 0, s, b.run_off, b.items, b.huge, b.cnt);
+  hipLaunchKernelGGL(worklist_kernel, dim3(1024), dim3(256), 0, s, b.run_off, b.mid_idx, b.items, b.huge, b.cnt);
+  hipLaunchKernelGGL(huge_group_kernel, dim3(1), dim3(1024), 0, s, tm, g.T, b.huge, b.uniq_tab, b.huge_sorted, b.hchunks,
+                     b.hg_count, b.cnt);
   int64_t max_touched = (int64_t)g.total_sets + g.T;
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
@@ -416,8 +464,8 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
               b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u, 0u, 0u, 0ull};
   run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
   const int fin_blocks = (n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096;
-  hipLaunchKernelGGL(finalize_kernel, dim3(fin_blocks), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.loc,
-                     b.cnt);
+  hipLaunchKernelGGL(finalize_kernel, dim3(fin_blocks), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.run_off,
+                     b.loc, b.cnt);
   return hipGetLastError();
 }
 

@@ -34,7 +34,7 @@ template <int DT, int G>
 __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restrict__ tm,
                                                       const int32_t *__restrict__ class_tables, int B, int sum_dim,
                                                       const int64_t *__restrict__ offsets,
-                                                      const int32_t *__restrict__ loc,
+                                                      const uint32_t *__restrict__ loc,
                                                       const char *__restrict__ ovf, uint32_t ovf_stride,
                                                       float *__restrict__ out, const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
@@ -54,14 +54,15 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
   for (int e = 0; e < EPL; e++) acc[e] = 0.f;
   for (int64_t j0 = lo; j0 < hi; j0 += G) {
     const int nq = (int)((hi - j0) < G ? (hi - j0) : G);
-    const int my_loc = lig < nq ? loc[j0 + lig] : 0;
+    const uint32_t my_loc = lig < nq ? loc[j0 + lig] : 0u;
     for (int q = 0; q < nq; q += 4) {
       uint4 v[4];
 #pragma unroll
       for (int x = 0; x < 4; x++) {
         const int src = (q + x) & (G - 1);
-        const int l = __shfl(my_loc, src, G);
-        const char *p = l >= 0 ? lines + (size_t)(l - slot_base) * rb : ovf + (size_t)(-2 - l) * ovf_stride;
+        const uint32_t l = __shfl(my_loc, src, G);
+        const uint32_t ix = l & kLocIndex;
+        const char *p = (l & kLocOverflow) ? ovf + (size_t)ix * ovf_stride : lines + (size_t)((int)ix - slot_base) * rb;
         v[x] = (active && q + x < nq) ? *(const uint4 *)(p + lig * 16) : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
@@ -90,9 +91,19 @@ __device__ inline void load_grad(float (&g)[Elems<DT>::n], const float *p) {
 // m += mean(g^2); w -= lr * g / (sqrt(m) + eps), on the 16 bytes this lane owns.
 // `sq` is the sum of g^2 over the whole row (already reduced over the group).
 template <int DT>
+__device__ inline void adagrad_store(char *wp, uint4 raw, const float (&g)[Elems<DT>::n], float m_new, float lr,
+                                     float eps);
+
+template <int DT>
 __device__ inline void adagrad_apply(char *wp, const float (&g)[Elems<DT>::n], float m_new, float lr, float eps) {
+  adagrad_store<DT>(wp, *(const uint4 *)wp, g, m_new, lr, eps);
+}
+
+// the same with the row's 16 bytes already loaded
+template <int DT>
+__device__ inline void adagrad_store(char *wp, uint4 raw, const float (&g)[Elems<DT>::n], float m_new, float lr,
+                                     float eps) {
   const float denom = sqrtf(m_new) + eps;
-  uint4 raw = *(const uint4 *)wp;
   if constexpr (DT == 0) {
     float w[4] = {__uint_as_float(raw.x), __uint_as_float(raw.y), __uint_as_float(raw.z), __uint_as_float(raw.w)};
 #pragma unroll
@@ -174,58 +185,134 @@ __device__ inline void update_row(const TableMeta &m, uint32_t key, int slot, ch
   if (lig == 0) *r.m = m_new;
 }
 
-// Rows with at most kLongRun lookups: one group of G lanes per distinct row, gradients
-// summed in sorted (= ascending bag) order.
+// Rows with exactly one lookup in the batch (most distinct rows of a power-law batch):
+// their gradient is the bag's gradient, so they are updated bag by bag -- the group holds
+// the bag's gradient slice in registers (read once, coalesced) and walks the bag's
+// lookups, updating the rows flagged kLocSingle, four rows in flight at a time.  No
+// per-lookup gradient read at all.
 template <int DT, int G>
-__global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__restrict__ tm, int T, int cls, int B,
-                                                             int sum_dim, const uint32_t *__restrict__ uniq_key,
+__global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *__restrict__ tm,
+                                                              const int32_t *__restrict__ class_tables, int B,
+                                                              int sum_dim, const int64_t *__restrict__ indices,
+                                                              const int64_t *__restrict__ offsets,
+                                                              const uint32_t *__restrict__ loc,
+                                                              const float *__restrict__ grad_out, float lr, float eps,
+                                                              char *__restrict__ ovf, uint32_t ovf_stride,
+                                                              const BatchCounters *cnt) {
+  constexpr int EPL = Elems<DT>::n;
+  if (cnt->err) return;
+  const int t = class_tables[blockIdx.y];
+  const TableMeta &m = tm[t];
+  const int b = blockIdx.x * (256 / G) + threadIdx.x / G;
+  const int lig = threadIdx.x % G;
+  if (b >= B) return;
+  const int64_t lo = offsets[(int64_t)t * B + b], hi = offsets[(int64_t)t * B + b + 1];
+  if (lo == hi) return;
+  const bool active = lig * EPL < m.dim;
+  char *lines = m.lines;
+  float *dev_m = m.dev_m;
+  const uint32_t rb = m.row_bytes;
+  const int slot_base = m.slot_base;
+  const int gshift = (threadIdx.x & 63) / G * G;  // first lane of this group inside the wavefront
+  float g[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; e++) g[e] = 0.f;
+  if (active) load_grad<DT>(g, grad_out + (size_t)b * sum_dim + m.col + lig * EPL);
+  float sq = 0.f;
+#pragma unroll
+  for (int e = 0; e < EPL; e++) sq += g[e] * g[e];
+  for (int d = G / 2; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, G);
+  const float msq = sq / (float)m.dim;
+  for (int64_t j0 = lo; j0 < hi; j0 += G) {
+    const int nq = (int)((hi - j0) < G ? (hi - j0) : G);
+    uint32_t my_loc = 0u;
+    int my_row = 0;
+    if (lig < nq) {
+      my_loc = loc[j0 + lig];
+      if (my_loc & kLocSingle) my_row = (int)indices[j0 + lig];
+    }
+    uint64_t todo = __ballot((my_loc & kLocSingle) != 0) >> gshift;  // the group's single-lookup rows
+    if (G < 64) todo &= (1ull << G) - 1ull;
+    while (todo) {
+      char *w[4];
+      float *mp[4];
+      float m_old[4];
+      uint4 raw[4];
+      int n = 0;
+#pragma unroll
+      for (int x = 0; x < 4; x++) {
+        if (todo) {
+          const int q = __ffsll((unsigned long long)todo) - 1;
+          todo &= todo - 1;
+          const uint32_t l = __shfl(my_loc, q, G);
+          const int r = __shfl(my_row, q, G);
+          const uint32_t ix = l & kLocIndex;
+          w[x] = ((l & kLocOverflow) ? ovf + (size_t)ix * ovf_stride : lines + (size_t)((int)ix - slot_base) * rb) + lig * 16;
+          mp[x] = dev_m + r;
+          m_old[x] = *mp[x];
+          if (active) raw[x] = *(const uint4 *)w[x];
+          n = x + 1;
+        }
+      }
+#pragma unroll
+      for (int x = 0; x < 4; x++) {
+        if (x < n) {
+          const float m_new = m_old[x] + msq;
+          if (active) adagrad_store<DT>(w[x], raw[x], g, m_new, lr, eps);
+          if (lig == 0) *mp[x] = m_new;
+        }
+      }
+    }
+  }
+}
+
+// Rows with 2..kLongRun lookups: one group of G lanes per distinct row, gradients summed
+// in sorted (= ascending bag) order.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__restrict__ tm, int cls, int B,
+                                                             int sum_dim, const int32_t *__restrict__ mid_idx,
+                                                             const uint32_t *__restrict__ uniq_key,
                                                              const int32_t *__restrict__ uniq_tab,
                                                              const int32_t *__restrict__ run_off,
                                                              const int32_t *__restrict__ loc_u,
                                                              const int32_t *__restrict__ sorted_bag,
-                                                             const float *__restrict__ grad_out,
-                                                             float lr, float eps,
+                                                             const float *__restrict__ grad_out, float lr, float eps,
                                                              char *__restrict__ ovf, uint32_t ovf_stride,
                                                              const int32_t *__restrict__ table_class,
                                                              const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   if (cnt->err) return;
-  const int n_uniq = cnt->n_uniq;
+  const int n_mid = cnt->n_mid;
   const int lig = threadIdx.x % G;
   const int n_groups = gridDim.x * (256 / G);
-  for (int u = blockIdx.x * (256 / G) + threadIdx.x / G; u < n_uniq; u += n_groups) {
-    const int i0 = run_off[u], i1 = run_off[u + 1];
-    if (i1 - i0 > kLongRun) continue;
-    const uint32_t key = uniq_key[u];
+  for (int i = blockIdx.x * (256 / G) + threadIdx.x / G; i < n_mid; i += n_groups) {
+    const int u = mid_idx[i];
     const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;
+    const int i0 = run_off[u], i1 = run_off[u + 1];
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
     reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, 0, 1, lig, active);
-    update_row<DT, G>(m, key, loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
+    update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
   }
 }
 
-// Rows with more lookups are cut into segments of kSegment lookups; one block per segment,
-// its 256/G groups take chunks of G lookups round robin and their partial sums are added in
-// group order through LDS.  A row of one segment is updated at once; otherwise the segment
-// sum goes to the row's slots in `partials` and backward_combine_kernel finishes the row.
+// Rows with kLongRun < lookups <= kHugeRun: one workgroup per row, its 256/G groups take
+// chunks of G lookups round robin; the partial sums are added in group order through LDS.
 template <int DT, int G>
-__global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__restrict__ tm, int T, int cls, int B,
-                                                            int sum_dim, const uint32_t *__restrict__ uniq_key,
-                                                             const int32_t *__restrict__ uniq_tab,
+__global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__restrict__ tm, int cls, int B,
+                                                            int sum_dim, const int32_t *__restrict__ items,
+                                                            const uint32_t *__restrict__ uniq_key,
+                                                            const int32_t *__restrict__ uniq_tab,
                                                             const int32_t *__restrict__ run_off,
                                                             const int32_t *__restrict__ loc_u,
                                                             const int32_t *__restrict__ sorted_bag,
-                                                            const uint4 *__restrict__ items,
-                                                            const float *__restrict__ grad_out,
-                                                            float *__restrict__ partials,
-                                                            int pstride, float lr, float eps,
+                                                            const float *__restrict__ grad_out, float lr, float eps,
                                                             char *__restrict__ ovf, uint32_t ovf_stride,
-                                                             const int32_t *__restrict__ table_class,
+                                                            const int32_t *__restrict__ table_class,
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int NG = 256 / G;
@@ -234,19 +321,16 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
   const int n_items = cnt->n_items;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
   for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
-    const uint4 item = items[it];  // (distinct row, segment, segments of the row, first partial slot)
-    const int u = (int)item.x;
-    const uint32_t key = uniq_key[u];
+    const int u = items[it];
     const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
-    const int i0 = run_off[u] + (int)item.y * kSegment;
-    const int i1 = min(run_off[u + 1], i0 + kSegment);
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, grp, NG, lig, active);
+    reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, run_off[u], run_off[u + 1], grp, NG,
+                        lig, active);
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < EPL; e++) part[grp][lig * EPL + e] = g[e];
@@ -258,38 +342,130 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
         for (int q = 0; q < NG; q++) s += part[q][lig * EPL + e];
         g[e] = s;
       }
-      if (item.z == 1u) {
-        update_row<DT, G>(m, key, loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
-      } else if (active) {
-        float *p = partials + (size_t)(item.w + item.y) * pstride + lig * EPL;
-#pragma unroll
-        for (int e = 0; e < EPL; e++) p[e] = g[e];
-      }
+      update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
     }
   }
 }
 
-// Rows of several segments: add the segment sums in segment order, then update the row.
+// Rows with more than kHugeRun lookups.  Such a row touches a large part of its table's bags,
+// and the lookups of a row are sorted by bag, so the table's huge rows all sweep the same
+// gradient slice.  A workgroup takes (table, up to 256/G of its huge rows, one of
+// kHugeRanges bag ranges): it stages the range tile by tile in LDS (each gradient row read
+// once, coalesced) and every group adds up, from LDS, the lookups of its row that fall into
+// the tile.  The kHugeRanges partial sums of a row go to `partials`; the combine kernel adds
+// them in range order and updates the row.
 template <int DT, int G>
-__global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int T, int cls,
+__global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__restrict__ tm, int cls, int B,
+                                                            int sum_dim, const uint4 *__restrict__ hchunks,
+                                                            const int32_t *__restrict__ huge_sorted,
+                                                            const int32_t *__restrict__ huge,
+                                                            const int32_t *__restrict__ run_off,
+                                                            const int32_t *__restrict__ sorted_bag,
+                                                            const float *__restrict__ grad_out,
+                                                            float *__restrict__ partials, int pstride,
+                                                            const int32_t *__restrict__ table_class,
+                                                            const BatchCounters *cnt) {
+  constexpr int EPL = Elems<DT>::n;
+  constexpr int ROWF = G * EPL;                       // floats per staged gradient row
+  constexpr int TB = kTileBytes / (ROWF * 4);         // bags per tile
+  __shared__ float tile[TB * ROWF];
+  if (cnt->err) return;
+  const int n_work = cnt->n_hchunks * kHugeRanges;
+  const int lig = threadIdx.x % G, grp = threadIdx.x / G;
+  const int gshift = (threadIdx.x & 63) / G * G;
+  const int n_tiles = (B + TB - 1) / TB;
+  const int tiles_per_range = (n_tiles + kHugeRanges - 1) / kHugeRanges;
+  for (int wk = blockIdx.x; wk < n_work; wk += gridDim.x) {
+    const uint4 ch = hchunks[wk / kHugeRanges];  // (table, first position in huge_sorted, rows, -)
+    const int range = wk % kHugeRanges;
+    const int t = (int)ch.x;
+    if (table_class[t] != cls) continue;  // uniform over the block
+    const TableMeta &m = tm[t];
+    const int dim = m.dim;
+    const bool has_row = grp < (int)ch.z;
+    const int h = has_row ? huge_sorted[ch.y + grp] : 0;
+    const int u = huge[h];
+    const int bag0 = t * B;
+    const int i1 = has_row ? run_off[u + 1] : 0;
+    const int tile_lo = range * tiles_per_range, tile_hi = min(n_tiles, tile_lo + tiles_per_range);
+    int i = 0;
+    if (has_row) {  // first lookup of the row at or after the range's first bag
+      int lo = run_off[u], hi = i1;
+      const int first_bag = bag0 + tile_lo * TB;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (sorted_bag[mid] < first_bag) lo = mid + 1; else hi = mid;
+      }
+      i = lo;
+    }
+    float g[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; e++) g[e] = 0.f;
+    int my_bag = 0x7FFFFFFF, fetched_at = -1;
+    for (int tl = tile_lo; tl < tile_hi; tl++) {
+      const int b_first = tl * TB, b_end = min(B, b_first + TB);
+      __syncthreads();  // the previous tile is no longer read
+      for (int x = threadIdx.x * 4; x < (b_end - b_first) * ROWF; x += 256 * 4) {
+        const int bl = x / ROWF, c = x % ROWF;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < dim) v = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + m.col + c);
+        *(float4 *)(tile + x) = v;
+      }
+      __syncthreads();
+      const int end_bag = bag0 + b_end;
+      bool more = has_row;
+      while (more) {
+        if (fetched_at != i) {  // the group's next G bag ids (kept across tiles while unconsumed)
+          my_bag = (i + lig < i1) ? sorted_bag[i + lig] : 0x7FFFFFFF;
+          fetched_at = i;
+        }
+        uint64_t ok = __ballot(my_bag < end_bag) >> gshift;
+        if (G < 64) ok &= (1ull << G) - 1ull;
+        const int n_ok = __popcll(ok);  // lookups are sorted by bag: the group's first n_ok are in the tile
+        for (int q = 0; q < n_ok; q++) {
+          const float *src = tile + (__shfl(my_bag, q, G) - bag0 - b_first) * ROWF + lig * EPL;
+#pragma unroll
+          for (int e = 0; e < EPL; e += 4) {
+            const float4 v = *(const float4 *)(src + e);
+            g[e] += v.x; g[e + 1] += v.y; g[e + 2] += v.z; g[e + 3] += v.w;
+          }
+        }
+        i += n_ok;
+        more = n_ok == G;
+        if (n_ok > 0 && n_ok < G) {  // shift the unconsumed ids to the front
+          my_bag = __shfl(my_bag, (lig + n_ok) & (G - 1), G);
+          if (lig + n_ok >= G) my_bag = (i + lig < i1) ? sorted_bag[i + lig] : 0x7FFFFFFF;
+          fetched_at = i;
+        }
+      }
+    }
+    if (has_row) {
+      float *p = partials + ((size_t)h * kHugeRanges + range) * pstride + lig * EPL;
+#pragma unroll
+      for (int e = 0; e < EPL; e++) p[e] = g[e];
+    }
+  }
+}
+
+// Huge rows: add the partial sums in range order, then update the row.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int cls,
+                                                               const int32_t *__restrict__ huge,
                                                                const uint32_t *__restrict__ uniq_key,
-                                                             const int32_t *__restrict__ uniq_tab,
+                                                               const int32_t *__restrict__ uniq_tab,
                                                                const int32_t *__restrict__ loc_u,
-                                                               const uint4 *__restrict__ huge,
                                                                const float *__restrict__ partials, int pstride,
-                                                               float lr, float eps,
-                                                               char *__restrict__ ovf, uint32_t ovf_stride,
-                                                             const int32_t *__restrict__ table_class,
+                                                               float lr, float eps, char *__restrict__ ovf,
+                                                               uint32_t ovf_stride,
+                                                               const int32_t *__restrict__ table_class,
                                                                const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   if (cnt->err) return;
   const int n_huge = cnt->n_huge;
   const int lig = threadIdx.x % G;
   const int n_groups = gridDim.x * (256 / G);
-  for (int hi = blockIdx.x * (256 / G) + threadIdx.x / G; hi < n_huge; hi += n_groups) {
-    const uint4 row = huge[hi];  // (distinct row, first partial slot, segments, -)
-    const int u = (int)row.x;
-    const uint32_t key = uniq_key[u];
+  for (int h = blockIdx.x * (256 / G) + threadIdx.x / G; h < n_huge; h += n_groups) {
+    const int u = huge[h];
     const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;
     const TableMeta &m = tm[t];
@@ -297,13 +473,12 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    if (active)
-      for (uint32_t sgm = 0; sgm < row.z; sgm++) {
-        const float *p = partials + (size_t)(row.y + sgm) * pstride + lig * EPL;
+    for (int r = 0; r < kHugeRanges; r++) {
+      const float *p = partials + ((size_t)h * kHugeRanges + r) * pstride + lig * EPL;
 #pragma unroll
-        for (int e = 0; e < EPL; e++) g[e] += p[e];
-      }
-    update_row<DT, G>(m, key, loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
+      for (int e = 0; e < EPL; e++) g[e] += p[e];
+    }
+    update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
   }
 }
 
@@ -323,16 +498,28 @@ template <int DT, int G>
 static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g,
                     const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps, hipStream_t s) {
   if (which == 0) {
-    hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                       b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, b.items, grad_out, partials,
-                       g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
-    hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, g.T, cls, b.uniq_key, b.uniq_tab,
-                       b.loc_u,
-                       b.huge, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
+    hipLaunchKernelGGL((backward_huge_kernel<DT, G>), dim3(2048), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.hchunks,
+                       b.huge_sorted, b.huge, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride, table_class,
+                       b.cnt);
+    hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
+                       b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
+    hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items,
+                       b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride,
+                       table_class, b.cnt);
   } else {
-    hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, g.T, cls, b.batch, g.sum_dim,
-                       b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
+    hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.mid_idx,
+                       b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride,
+                       table_class, b.cnt);
   }
+}
+
+template <int DT, int G>
+static void bwd_single_one(const TableMeta *tm, const int32_t *tables, int count, const Geometry &g, const BatchBuf &b,
+                           const float *grad_out, float lr, float eps, hipStream_t s) {
+  const int bags_per_block = 256 / G;
+  dim3 grid((b.batch + bags_per_block - 1) / bags_per_block, count);
+  hipLaunchKernelGGL((backward_single_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_indices,
+                     b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.cnt);
 }
 
 #define TBE_DISPATCH(DT, LANES, CALL)                         \
@@ -368,8 +555,18 @@ hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, cons
   return hipGetLastError();
 }
 
-// long_rows selects the segment kernels (rows with more than kLongRun lookups) or the
-// group-per-row kernel (all other rows); a step runs both, they touch disjoint rows.
+hipError_t launch_backward_single_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
+                                          const float *grad_out, float lr, float eps, hipStream_t s) {
+  if (b.n == 0 || b.batch == 0) return hipSuccess;
+  for (int c = 0; c < ci.n_classes; c++)
+    TBE_DISPATCH(ci.cls_dtype[c], ci.cls_lanes[c],
+                 (bwd_single_one<d, l>(tm, ci.cls_tables[c], ci.cls_count[c], g, b, grad_out, lr, eps, s)));
+  return hipGetLastError();
+}
+
+// long_rows selects the kernels for rows with more than kLongRun lookups (huge + combine +
+// workgroup per row) or the group-per-row kernel (2..kLongRun lookups); a step runs both
+// and the single-lookup kernel, they touch disjoint rows.
 hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
                                    const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,
                                    hipStream_t s) {

@@ -7,12 +7,24 @@ namespace tbe {
 
 constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr uint32_t kNoSet = 0xFFFFFFFFu;  // global set id of rows of a table without cache
-constexpr int kLongRun = 64;              // rows with more lookups than this take the block-wide backward
-constexpr int kSegment = 1024;            // ... in segments of this many lookups, one block each
+// Backward work classes by the number of lookups a distinct row has in the batch:
+//   1            : updated bag by bag (the gradient is the bag's), flagged in the location word
+//   2..kLongRun  : one lane group per row
+//   ..kHugeRun   : one workgroup per row
+//   above        : bag tiles of the gradient staged in LDS and shared by the table's huge rows
+constexpr int kLongRun = 64;
+constexpr int kHugeRun = 1024;
+constexpr int kHugeRanges = 64;           // each huge row's sum is split over this many bag ranges
+constexpr int kTileBytes = 32768;         // gradient tile in LDS
 
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
 constexpr uint32_t kWhereParked = 0x40000000u;    // among the victims the batch before parked
 constexpr uint32_t kWhereIndex = 0x3FFFFFFFu;
+
+// Per-lookup location word (BatchBuf::loc): where the lookup's row is while its batch trains.
+constexpr uint32_t kLocOverflow = 0x80000000u;  // index = overflow slot of a bypassed row, else global cache slot
+constexpr uint32_t kLocSingle = 0x40000000u;    // the row has exactly one lookup in this batch
+constexpr uint32_t kLocIndex = 0x3FFFFFFFu;
 
 enum Status : uint8_t { ST_MISS = 0, ST_HIT = 1, ST_INSERT = 2, ST_BYPASS = 3 };
 
@@ -45,20 +57,20 @@ struct BatchCounters {
   int32_t n_touched;  // sets with at least one distinct row (+ pseudo sets of cacheless tables)
   int32_t n_ins;
   int32_t n_byp;
-  int32_t n_items;    // segments of rows with more than kLongRun lookups
+  int32_t n_items;    // rows with kLongRun < lookups <= kHugeRun
   int32_t err;        // 1 = bad offsets, 2 = index out of range, 0 = none
-  int32_t n_huge;     // rows of more than one segment
-  int32_t n_partials; // partial-sum slots handed to those rows
+  int32_t n_huge;     // rows with more than kHugeRun lookups
+  int32_t n_mid;      // rows with 2..kLongRun lookups
   unsigned long long hits, evictions, hit_lookups;
   int32_t n_long;     // rows with more than kLongRun lookups
-  int32_t pad0;
+  int32_t n_hchunks;  // (table, up to one workgroup's worth of huge rows) chunks
 };
 
 // Arrays of one batch; two of these exist so that batch k+1 can be prepared while
 // batch k is still being trained on.
 struct BatchBuf {
   // per lookup
-  int32_t *loc;         // [N] location of the lookup's row: global slot id, or -2-j = j-th bypassed row (ovf)
+  uint32_t *loc;        // [N] location word of every lookup (kLoc* bits), input order
   int32_t *sorted_bag;  // [N] global bag id (t*B + b) of the i-th lookup in sorted order
   int32_t *bag_of_pos;  // [N] global bag id of lookup j (input order)
   uint32_t *uid_sorted; // [N] index of the distinct row of the i-th sorted lookup
@@ -85,8 +97,12 @@ struct BatchBuf {
   char **byp_src;       // [N]   its row in the backing tier
   uint32_t *byp_where;  // [N]   as ins_where
   char *ovf;            // [N * stride] HBM copies of the bypassed rows while their batch trains
-  uint4 *items;         // [N/kLongRun + N/kSegment + 2] (row, segment, segments, first partial slot)
-  uint4 *huge;          // [N/kSegment + 2] rows of several segments: (row, first partial slot, segments, -)
+  int32_t *mid_idx;     // [N/2 + 1] rows with 2..kLongRun lookups (any order)
+  int32_t *items;       // [N/kLongRun + 1] rows with kLongRun < lookups <= kHugeRun (any order)
+  int32_t *huge;        // [N/kHugeRun + 1] rows with more lookups (any order)
+  int32_t *huge_sorted; // [N/kHugeRun + 1] positions in `huge`, grouped by table
+  uint4 *hchunks;       // [N/kHugeRun + T + 1] (table, first position in huge_sorted, count, -)
+  int32_t *hg_count;    // [3*(T+1)] per-table counters of the grouping
   BatchCounters *cnt;   // device
   // host-side description
   const int64_t *d_indices;
@@ -170,6 +186,8 @@ hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *t
                         hipStream_t s);
 hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
                                   float *out, hipStream_t s);
+hipError_t launch_backward_single_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
+                                          const float *grad_out, float lr, float eps, hipStream_t s);
 hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
                                    const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,
                                    hipStream_t s);
