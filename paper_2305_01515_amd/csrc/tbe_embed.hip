@@ -405,14 +405,23 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
     for (int tl = tile_lo; tl < tile_hi; tl++) {
       const int b_first = tl * TB, b_end = min(B, b_first + TB);
       __syncthreads();  // the previous tile is no longer read
-      for (int x = threadIdx.x * 4; x < (b_end - b_first) * ROWF; x += 256 * 4) {
-        const int bl = x / ROWF, c = x % ROWF;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (c < dim) v = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + m.col + c);
-        *(float4 *)(tile + x) = v;
+      {
+        constexpr int PER = kTileBytes / 16 / 256;  // float4 per thread and tile
+        float4 v[PER];
+        const int n_f = (b_end - b_first) * ROWF;
+#pragma unroll
+        for (int k = 0; k < PER; k++) {
+          const int x = (k * 256 + threadIdx.x) * 4;
+          const int bl = x / ROWF, c = x % ROWF;
+          v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (x < n_f && c < dim) v[k] = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + m.col + c);
+        }
+#pragma unroll
+        for (int k = 0; k < PER; k++) *(float4 *)(tile + (k * 256 + threadIdx.x) * 4) = v[k];
       }
       __syncthreads();
       const int end_bag = bag0 + b_end;
+      const int base_bag = bag0 + b_first;
       bool more = has_row;
       while (more) {
         if (fetched_at != i) {  // the group's next G bag ids (kept across tiles while unconsumed)
@@ -422,17 +431,32 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
         uint64_t ok = __ballot(my_bag < end_bag) >> gshift;
         if (G < 64) ok &= (1ull << G) - 1ull;
         const int n_ok = __popcll(ok);  // lookups are sorted by bag: the group's first n_ok are in the tile
-        for (int q = 0; q < n_ok; q++) {
-          const float *src = tile + (__shfl(my_bag, q, G) - bag0 - b_first) * ROWF + lig * EPL;
+        // the ids after these, fetched now so that the load overlaps the additions
+        const int nxt = (n_ok == G && i + G + lig < i1) ? sorted_bag[i + G + lig] : 0x7FFFFFFF;
+        for (int q = 0; q < n_ok; q += 4) {
+          float4 v[4][EPL / 4];
 #pragma unroll
-          for (int e = 0; e < EPL; e += 4) {
-            const float4 v = *(const float4 *)(src + e);
-            g[e] += v.x; g[e + 1] += v.y; g[e + 2] += v.z; g[e + 3] += v.w;
+          for (int x = 0; x < 4; x++) {
+            const int bq = __shfl(my_bag, (q + x) & (G - 1), G);
+            const float *src = tile + (q + x < n_ok ? bq - base_bag : 0) * ROWF + lig * EPL;
+#pragma unroll
+            for (int e = 0; e < EPL / 4; e++) v[x][e] = *(const float4 *)(src + 4 * e);
           }
+#pragma unroll
+          for (int x = 0; x < 4; x++)
+            if (q + x < n_ok) {
+#pragma unroll
+              for (int e = 0; e < EPL / 4; e++) {
+                g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
+              }
+            }
         }
         i += n_ok;
         more = n_ok == G;
-        if (n_ok > 0 && n_ok < G) {  // shift the unconsumed ids to the front
+        if (n_ok == G) {
+          my_bag = nxt;
+          fetched_at = i;
+        } else if (n_ok > 0) {  // shift the unconsumed ids to the front
           my_bag = __shfl(my_bag, (lig + n_ok) & (G - 1), G);
           if (lig + n_ok >= G) my_bag = (i + lig < i1) ? sorted_bag[i + lig] : 0x7FFFFFFF;
           fetched_at = i;
