@@ -516,8 +516,12 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   if (h->current < 0) return fail(h, TBE_EORDER, "backward_update: no forwarded batch");
   const int bi = h->current;
   {
+    StageTimer tm_(h, TBE_STAGE_BACKWARD_HUGE, h->cs);
+    HIP_TRY(h, launch_backward_classes(2, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
+  }
+  {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_LONG, h->cs);
-    HIP_TRY(h, launch_backward_classes(true, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(0, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SINGLE, h->cs);
@@ -525,7 +529,7 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
-    HIP_TRY(h, launch_backward_classes(false, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(1, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
   }
   h->current = -1;
   if (h->as != h->cs) {

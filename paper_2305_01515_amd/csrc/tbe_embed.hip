@@ -521,12 +521,13 @@ static void fwd_one(const TableMeta *tm, const int32_t *tables, int count, const
 template <int DT, int G>
 static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g,
                     const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps, hipStream_t s) {
-  if (which == 0) {
+  if (which == 2) {
     hipLaunchKernelGGL((backward_huge_kernel<DT, G>), dim3(2048), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.hchunks,
                        b.huge_sorted, b.huge, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride, table_class,
                        b.cnt);
     hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
                        b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
+  } else if (which == 0) {
     hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items,
                        b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride,
                        table_class, b.cnt);
@@ -588,16 +589,17 @@ hipError_t launch_backward_single_classes(const TableMeta *tm, const ClassInfo &
   return hipGetLastError();
 }
 
-// long_rows selects the kernels for rows with more than kLongRun lookups (huge + combine +
-// workgroup per row) or the group-per-row kernel (2..kLongRun lookups); a step runs both
-// and the single-lookup kernel, they touch disjoint rows.
-hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
+// which: 0 = rows with kLongRun < lookups <= kHugeRun (workgroup per row), 1 = rows with
+// 2..kLongRun lookups (group per row), 2 = rows with more than kHugeRun lookups (gradient
+// tiles + combine).  A step runs all three and the single-lookup kernel; they touch
+// disjoint rows.
+hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
                                    const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,
                                    hipStream_t s) {
   if (b.n == 0) return hipSuccess;
   for (int c = 0; c < ci.n_classes; c++)
     TBE_DISPATCH(ci.cls_dtype[c], ci.cls_lanes[c],
-                 (bwd_one<d, l>(long_rows ? 0 : 1, tm, c, ci.table_class, g, b, grad_out, partials, lr, eps, s)));
+                 (bwd_one<d, l>(which, tm, c, ci.table_class, g, b, grad_out, partials, lr, eps, s)));
   return hipGetLastError();
 }
 

@@ -188,7 +188,7 @@ hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, cons
                                   float *out, hipStream_t s);
 hipError_t launch_backward_single_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
                                           const float *grad_out, float lr, float eps, hipStream_t s);
-hipError_t launch_backward_classes(bool long_rows, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
+hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
                                    const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,
                                    hipStream_t s);
 
