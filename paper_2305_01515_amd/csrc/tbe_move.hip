@@ -23,7 +23,7 @@ namespace tbe {
 
 typedef unsigned long long u64;
 constexpr int kMoveLanes = 16;
-constexpr int kLinkBlocks = 128;
+constexpr int kLinkBlocks = 256;
 
 __device__ inline void copy_row(char *dst, const char *src, uint32_t bytes, int lig) {
   for (uint32_t c = lig * 16; c < bytes; c += kMoveLanes * 16) *(uint4 *)(dst + c) = *(const uint4 *)(src + c);
@@ -102,9 +102,11 @@ __global__ void clear_wb_kernel(int32_t *wb_n) {
 
 hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t *rb_of_table, u64 *bytes_h2d,
                            u64 *bytes_d2h, hipStream_t s) {
-  // 128 workgroups keep the link at its two-way peak; more of them only add host requests in
-  // flight, which slows HBM-bound kernels on the other streams (measured: 256 blocks halve a
-  // concurrent copy kernel's bandwidth, 64 blocks cost it 20 % but lose 5 % of the link)
+  // The number of workgroups sets how many host requests are in flight.  Alone, 64 already
+  // reach the link's two-way peak; next to HBM-bound kernels of the other streams the two
+  // kinds of traffic slow each other, and since the link is the critical path of a step it
+  // gets the larger share: 256 workgroups gave the shortest step (128: link 20 % slower;
+  // 512: link at its peak but the training kernels stretched until they became critical)
   hipLaunchKernelGGL(transfer_kernel, dim3(kLinkBlocks), dim3(256), 0, s, st, b ? b->cnt : nullptr,
                      b ? b->ins_src : nullptr, b ? b->ins_tab : nullptr, rb_of_table,
                      b ? b->ins_where : nullptr, b ? b->byp_src : nullptr, b ? b->byp_tab : nullptr,
