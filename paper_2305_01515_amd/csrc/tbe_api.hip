@@ -172,6 +172,7 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.huge_sorted, 4 * (N / kHugeRun + 1)));
   HIP_TRY(h, h->mem.get(&b.hchunks, 16 * (N / kHugeRun + (size_t)h->g.T + 1)));
   HIP_TRY(h, h->mem.get(&b.hg_count, 4 * 3 * ((size_t)h->g.T + 1)));
+  HIP_TRY(h, h->mem.get(&b.hstart, 4 * (N / kHugeRun + 1) * kHugeRanges));
   HIP_TRY(h, h->mem.get(&b.cnt, sizeof(BatchCounters)));
   HIP_TRY(h, hipMemset(b.cnt, 0, sizeof(BatchCounters)));
   return TBE_OK;

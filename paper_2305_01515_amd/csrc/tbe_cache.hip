@@ -248,6 +248,33 @@ __global__ __launch_bounds__(1024) void huge_group_kernel(const TableMeta *__res
   }
 }
 
+// For every huge row and bag range: the first sorted position of the row whose bag lies in
+// the range (the row's lookups are sorted by bag).  One thread per (row, range).
+__global__ __launch_bounds__(256) void huge_starts_kernel(const TableMeta *__restrict__ tm, int B,
+                                                          const int32_t *__restrict__ huge,
+                                                          const int32_t *__restrict__ uniq_tab,
+                                                          const int32_t *__restrict__ run_off,
+                                                          const int32_t *__restrict__ sorted_bag, int32_t *hstart,
+                                                          const BatchCounters *cnt) {
+  if (cnt->err) return;
+  const int n = cnt->n_huge * kHugeRanges;
+  for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < n; x += gridDim.x * blockDim.x) {
+    const int h = x / kHugeRanges, range = x % kHugeRanges;
+    const int u = huge[h];
+    const int t = uniq_tab[u];
+    const int tb = kTileBytes / (tm[t].lanes * (tm[t].dtype == 0 ? 4 : 8) * 4);  // bags per gradient tile
+    const int n_tiles = (B + tb - 1) / tb;
+    const int tiles_per_range = (n_tiles + kHugeRanges - 1) / kHugeRanges;
+    const int first_bag = t * B + range * tiles_per_range * tb;
+    int lo = run_off[u], hi = run_off[u + 1];
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (sorted_bag[mid] < first_bag) lo = mid + 1; else hi = mid;
+    }
+    hstart[x] = lo;
+  }
+}
+
 // ---- pass 3 over the distinct rows after the probe: insert and bypass lists, counters ----
 struct StatusOp {
   const TableMeta *tm;
@@ -453,6 +480,8 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   hipLaunchKernelGGL(worklist_kernel, dim3(1024), dim3(256), 0, s, b.run_off, b.mid_idx, b.items, b.huge, b.cnt);
   hipLaunchKernelGGL(huge_group_kernel, dim3(1), dim3(1024), 0, s, tm, g.T, b.huge, b.uniq_tab, b.huge_sorted, b.hchunks,
                      b.hg_count, b.cnt);
+  hipLaunchKernelGGL(huge_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.huge, b.uniq_tab, b.run_off,
+                     b.sorted_bag, b.hstart, b.cnt);
   int64_t max_touched = (int64_t)g.total_sets + g.T;
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);

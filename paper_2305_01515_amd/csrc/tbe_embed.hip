@@ -359,6 +359,7 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
                                                             int sum_dim, const uint4 *__restrict__ hchunks,
                                                             const int32_t *__restrict__ huge_sorted,
                                                             const int32_t *__restrict__ huge,
+                                                            const int32_t *__restrict__ hstart,
                                                             const int32_t *__restrict__ run_off,
                                                             const int32_t *__restrict__ sorted_bag,
                                                             const float *__restrict__ grad_out,
@@ -388,16 +389,7 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
     const int bag0 = t * B;
     const int i1 = has_row ? run_off[u + 1] : 0;
     const int tile_lo = range * tiles_per_range, tile_hi = min(n_tiles, tile_lo + tiles_per_range);
-    int i = 0;
-    if (has_row) {  // first lookup of the row at or after the range's first bag
-      int lo = run_off[u], hi = i1;
-      const int first_bag = bag0 + tile_lo * TB;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (sorted_bag[mid] < first_bag) lo = mid + 1; else hi = mid;
-      }
-      i = lo;
-    }
+    int i = has_row ? hstart[h * kHugeRanges + range] : 0;  // first lookup of the row in this bag range
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
@@ -522,8 +514,8 @@ template <int DT, int G>
 static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g,
                     const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps, hipStream_t s) {
   if (which == 2) {
-    hipLaunchKernelGGL((backward_huge_kernel<DT, G>), dim3(2048), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.hchunks,
-                       b.huge_sorted, b.huge, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride, table_class,
+    hipLaunchKernelGGL((backward_huge_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.hchunks,
+                       b.huge_sorted, b.huge, b.hstart, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride, table_class,
                        b.cnt);
     hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
                        b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);

@@ -15,7 +15,7 @@ constexpr uint32_t kNoSet = 0xFFFFFFFFu;  // global set id of rows of a table wi
 constexpr int kLongRun = 64;
 constexpr int kHugeRun = 1024;
 constexpr int kHugeRanges = 64;           // each huge row's sum is split over this many bag ranges
-constexpr int kTileBytes = 32768;         // gradient tile in LDS
+constexpr int kTileBytes = 16384;         // gradient tile in LDS
 
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
 constexpr uint32_t kWhereParked = 0x40000000u;    // among the victims the batch before parked
@@ -103,6 +103,7 @@ struct BatchBuf {
   int32_t *huge_sorted; // [N/kHugeRun + 1] positions in `huge`, grouped by table
   uint4 *hchunks;       // [N/kHugeRun + T + 1] (table, first position in huge_sorted, count, -)
   int32_t *hg_count;    // [3*(T+1)] per-table counters of the grouping
+  int32_t *hstart;      // [(N/kHugeRun + 1) * kHugeRanges] first sorted position of a huge row in each bag range
   BatchCounters *cnt;   // device
   // host-side description
   const int64_t *d_indices;
