@@ -187,6 +187,8 @@ def main():
     hit_ms, hit_iso = ms["forward"] + bwd_ms, iso["forward"] + bwd_iso
     hit_b = fwd_b + bwd_b
     fwd_traffic = measured_traffic("forward_kernel")
+    bwd_traffic = {k: measured_traffic(k + "_kernel") for k in BWD}
+    hit_traffic = (fwd_traffic + sum(bwd_traffic.values())) if fwd_traffic and all(bwd_traffic.values()) else None
     fill_ms = ms["fill"]
     res = {
         "metric": "pooled lookups/s (fwd+bwd+update), achieved HBM GB/s, cache hit rate",
@@ -217,12 +219,15 @@ def main():
                      "achieved": gbs(bwd_b, bwd_ms), "frac": gbs(bwd_b, bwd_ms) / HBM_PEAK_GBS,
                      "isolated": {"ms": {k: iso[k] for k in BWD}, "ms_total": bwd_iso, "achieved": gbs(bwd_b, bwd_iso),
                                   "frac": gbs(bwd_b, bwd_iso) / HBM_PEAK_GBS},
-                     "traffic": {k: measured_traffic(k + "_kernel") for k in BWD}},
+                     "traffic": bwd_traffic},
         "hit_path": {"ms_fwd_bwd": hit_ms, "bytes": hit_b, "lookups_per_s": (lookups / K) / (hit_ms * 1e-3) if hit_ms else 0.0,
                      "achieved": gbs(hit_b, hit_ms), "frac": gbs(hit_b, hit_ms) / HBM_PEAK_GBS,
                      "isolated": {"ms_fwd_bwd": hit_iso, "lookups_per_s": (lookups / K) / (hit_iso * 1e-3) if hit_iso else 0.0,
                                   "achieved": gbs(hit_b, hit_iso), "frac": gbs(hit_b, hit_iso) / HBM_PEAK_GBS,
-                                  "frac_if_gradients_counted_per_lookup": gbs(hit_b + grad_pl, hit_iso) / HBM_PEAK_GBS}},
+                                  "frac_if_gradients_counted_per_lookup": gbs(hit_b + grad_pl, hit_iso) / HBM_PEAK_GBS,
+                                  # HBM bytes the counters saw for these kernels / their time: the bandwidth HBM delivered
+                                  "traffic": hit_traffic,
+                                  "traffic_frac": gbs(hit_traffic, hit_iso) / HBM_PEAK_GBS if hit_traffic else None}},
         "prefetch_stage_ms": ms["prefetch"], "commit_stage_ms": ms["commit"],
         "isolated_stage_ms": iso,
         # mean over every launch of the process (warm-up, timed, isolated): what rocprofv3 --stats averages
