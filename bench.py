@@ -133,6 +133,7 @@ def main():
             g.forward(batches[s][0], batches[s][1], out)
             g.backward_update(grads[s % len(grads)], cfg.lr, cfg.eps)
 
+    g.set_inputs_ready(True)  # all index tensors were generated and synchronised above
     g.set_profiling(True)  # stage brackets from the first launch on, so that the means over all
     g.prefetch(*batches[0])  # launches can be compared with a rocprofv3 --stats run of this command
     run(0, Wm)

@@ -131,6 +131,16 @@ int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offset
                  int64_t num_lookups);
 
 /*
+ * By default tbe_prefetch orders its work behind everything enqueued on the compute stream
+ * so far, because the index buffers may have been produced there.  With ready = 1 the
+ * caller guarantees instead that the buffers passed to tbe_prefetch are complete in device
+ * memory when the call is made (e.g. a data loader finished them earlier); the prefetch
+ * stage of the next batch can then start while the current batch is still training
+ * (Section 5.7: the stages of different batches run simultaneously).
+ */
+int tbe_set_inputs_ready(tbe_handle h, int32_t ready);
+
+/*
  * Pooled lookup (Section 2.1.1, sum pooling): for every table t, sample b and d < D_t
  *   d_out[b * sum_dim + col_t + d] = sum over the bag's lookups j of W_t[d_indices[j]][d]
  * with col_t the sum of the dims of the tables before t; an empty bag gives zeros; fp32

@@ -60,6 +60,7 @@ struct tbe_ctx {
   bool own_ls = false;
   hipEvent_t ev_inputs = nullptr, ev_ready[kBatchBufs] = {}, ev_trained[kBatchBufs] = {}, ev_probed[kBatchBufs] = {};
   int64_t flush_state_bytes = 0;
+  bool inputs_ready = false;  // caller guarantees index / offset buffers are complete when tbe_prefetch is called
   int32_t max_batch = 0;
   int64_t max_lookups = 0;
   int32_t k = 0;
@@ -225,10 +226,14 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
   h->total_lookups += n;
   h->last_buf = bi;
   if (h->as != h->cs) {
-    // inputs produced on the compute stream so far, and the last training step that read
-    // this buffer's arrays, come first
-    HIP_TRY(h, hipEventRecord(h->ev_inputs, h->cs));
-    HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_inputs, 0));
+    if (!h->inputs_ready) {  // inputs produced on the compute stream so far come first
+      HIP_TRY(h, hipEventRecord(h->ev_inputs, h->cs));
+      HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_inputs, 0));
+    }
+    // this buffer last served the batch three before: its backward read the buffer's arrays,
+    // and the commit of the batch after it read its bypass list and overflow copies
+    HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_trained[bi], 0));
+    HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_ready[(bi + 1) % kBatchBufs], 0));
   }
   {
     StageTimer tm_(h, TBE_STAGE_PREFETCH, h->as);
@@ -535,8 +540,8 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   h->current = -1;
   if (h->as != h->cs) {
     HIP_TRY(h, hipEventRecord(h->ev_trained[bi], h->cs));
-    // later prefetch work may reuse this buffer, later commits overwrite lines this batch used
-    HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_trained[bi], 0));
+    // later commits overwrite lines this batch used (the prefetch stream only decides on
+    // tags and timestamps, which training never reads, so it does not wait here)
     HIP_TRY(h, hipStreamWaitEvent(h->ls, h->ev_trained[bi], 0));
   }
   // the rows this batch bypassed were trained on in HBM copies: back to the backing tier,
@@ -564,6 +569,12 @@ int tbe_flush(tbe_handle h) {
   rc = sync_all(h);
   if (rc) return rc;
   return collect_device_errors(h);
+}
+
+int tbe_set_inputs_ready(tbe_handle h, int32_t ready) {
+  if (!h) return TBE_EINVAL;
+  h->inputs_ready = ready != 0;
+  return TBE_OK;
 }
 
 int tbe_set_profiling(tbe_handle h, int32_t enable) {

@@ -23,7 +23,8 @@ namespace tbe {
 
 typedef unsigned long long u64;
 constexpr int kMoveLanes = 16;
-constexpr int kLinkBlocks = 256;
+constexpr int kLinkBlocks = 192;  // workgroups of the transfer kernel that work
+constexpr int kLinkXcds = 2;      // ... all placed on this many of the 8 XCDs
 
 __device__ inline void copy_row(char *dst, const char *src, uint32_t bytes, int lig) {
   for (uint32_t c = lig * 16; c < bytes; c += kMoveLanes * 16) *(uint4 *)(dst + c) = *(const uint4 *)(src + c);
@@ -38,13 +39,17 @@ __global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCo
                                                        const int32_t *__restrict__ byp_tab,
                                                        const uint32_t *__restrict__ byp_where, char *__restrict__ ovf,
                                                        u64 *bytes_h2d, u64 *bytes_d2h) {
+  // Workgroups are dealt to the 8 XCDs round robin; only those landing on the first
+  // kLinkXcds work, so that the waves waiting on the host link sit on few CUs.
+  if ((int)(blockIdx.x & 7) >= kLinkXcds) return;
+  const int bid = (blockIdx.x >> 3) * kLinkXcds + (blockIdx.x & 7), n_blocks = (gridDim.x >> 3) * kLinkXcds;
   const int n_wb = *st.wb_n;
   const int n_ins = (cnt && cnt->err == 0) ? cnt->n_ins : 0;
   const int n_byp = (cnt && cnt->err == 0) ? cnt->n_byp : 0;
   const int n = max(n_wb, max(n_ins, n_byp));
-  const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
+  const int group = (bid * blockDim.x + threadIdx.x) / kMoveLanes;
   const int lig = threadIdx.x % kMoveLanes;
-  const int n_groups = gridDim.x * blockDim.x / kMoveLanes;
+  const int n_groups = n_blocks * blockDim.x / kMoveLanes;
   u64 in_b = 0, out_b = 0;
   for (int i = group; i < n; i += n_groups) {
     // issue the host read first, then the write-back, so both directions are busy
@@ -102,12 +107,16 @@ __global__ void clear_wb_kernel(int32_t *wb_n) {
 
 hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t *rb_of_table, u64 *bytes_h2d,
                            u64 *bytes_d2h, hipStream_t s) {
-  // The number of workgroups sets how many host requests are in flight.  Alone, 64 already
-  // reach the link's two-way peak; next to HBM-bound kernels of the other streams the two
-  // kinds of traffic slow each other, and since the link is the critical path of a step it
-  // gets the larger share: 256 workgroups gave the shortest step (128: link 20 % slower;
-  // 512: link at its peak but the training kernels stretched until they became critical)
-  hipLaunchKernelGGL(transfer_kernel, dim3(kLinkBlocks), dim3(256), 0, s, st, b ? b->cnt : nullptr,
+  // How many workgroups wait on the host link, and on how many CUs, decides how the link and
+  // the HBM-bound kernels of the other streams slow each other (measured on the benchmark
+  // workload, step time / forward kernel time while the transfer runs; alone the forward
+  // takes 0.21 ms and the link needs 5.7 ms):
+  //   256 workgroups on all 8 XCDs : 7.6 ms / 1.2 ms     128 on all 8 : 8.0 ms / 0.29 ms
+  //   256 on 1 XCD (fills its CUs) : 8.3 ms / 0.20 ms    128 on 2     : 7.4 ms / 0.34 ms
+  //   192 on 2 XCDs                : 7.2 ms / 0.48 ms    128 on 1     : 7.2 ms / 0.43 ms
+  // Waves stalled on host requests hurt the gathers of whatever shares their CU, so they are
+  // kept on two XCDs, few enough per CU to leave room for the other kernels' workgroups.
+  hipLaunchKernelGGL(transfer_kernel, dim3(kLinkBlocks / kLinkXcds * 8), dim3(256), 0, s, st, b ? b->cnt : nullptr,
                      b ? b->ins_src : nullptr, b ? b->ins_tab : nullptr, rb_of_table,
                      b ? b->ins_where : nullptr, b ? b->byp_src : nullptr, b ? b->byp_tab : nullptr,
                      b ? b->byp_where : nullptr, b ? b->ovf : nullptr, bytes_h2d, bytes_d2h);

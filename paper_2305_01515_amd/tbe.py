@@ -21,7 +21,7 @@ ERRORS = {0: "TBE_OK", -1: "TBE_EINVAL", -2: "TBE_ERANGE", -3: "TBE_EORDER", -4:
           -6: "TBE_EMISMATCH", -7: "TBE_EHIP"}
 EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "tbe_flush", "tbe_destroy",
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
-           "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times"]
+           "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready"]
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
 
 
@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
         l.tbe_host_alloc.argtypes = [C.POINTER(vp), C.c_size_t]
         l.tbe_host_free.argtypes = [vp]
         l.tbe_set_profiling.argtypes = [vp, i32]
+        l.tbe_set_inputs_ready.argtypes = [vp, i32]
         l.tbe_get_stage_times.argtypes = [vp, i32, i64, vp]
         l.tbe_get_stage_times.restype = i64
         _lib = l
@@ -170,6 +171,10 @@ class TBE:
         self._check(lib().tbe_get_stats(self._h, C.byref(s)), "tbe_get_stats")
         return {"last": s.last.as_dict(), "total": s.total.as_dict(), "h2d_bytes": int(s.h2d_bytes),
                 "d2h_bytes": int(s.d2h_bytes), "late_fetches": int(s.late_fetches), "last_long_rows": int(s.last_long_rows), "batch_id": int(s.batch_id)}
+
+    def set_inputs_ready(self, ready: bool):
+        """ready=True: index/offset tensors given to prefetch() are complete when it is called"""
+        self._check(lib().tbe_set_inputs_ready(self._h, 1 if ready else 0), "tbe_set_inputs_ready")
 
     def set_profiling(self, enable: bool):
         self._check(lib().tbe_set_profiling(self._h, 1 if enable else 0), "tbe_set_profiling")

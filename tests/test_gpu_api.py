@@ -153,7 +153,7 @@ def test_zero_and_full_capacity_against_oracle(slots):
         assert tot["bypasses"] == 0 and tot["evictions"] == 0 and tot["hits"] > 0
 
 
-def train(cfg, steps, order, overlap, restart_at=None):
+def train(cfg, steps, order, overlap, restart_at=None, inputs_ready=False):
     """outputs of every step, final tables, final cache state"""
     from paper_2305_01515_amd.tbe import TBE
     _, _, Wp, Mp = make_backing(cfg)
@@ -162,6 +162,8 @@ def train(cfg, steps, order, overlap, restart_at=None):
     batches = [tuple(x.cuda() for x in stream.next()) for _ in range(steps)]
     mx = max(int(b[0].numel()) for b in batches) + 1
     g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, mx, overlap=overlap)
+    torch.cuda.synchronize()
+    g.set_inputs_ready(inputs_ready)
     outs = []
     for s in range(steps):
         if restart_at is not None and s == restart_at:
@@ -198,8 +200,9 @@ def test_overlapped_prefetch_is_bitwise_identical_to_serial():
     every output, every row and the cache state must be equal bit for bit."""
     cfg = mixed(5)
     ref = train(cfg, 8, "serial", overlap=False)
-    for order, overlap in (("early", True), ("early", False), ("serial", True)):
-        got = train(cfg, 8, order, overlap)
+    for order, overlap, ready in (("early", True, False), ("early", False, False), ("serial", True, False),
+                                  ("early", True, True)):
+        got = train(cfg, 8, order, overlap, inputs_ready=ready)
         for a, b in zip(ref[0], got[0]):
             assert torch.equal(a, b)
         for a, b in zip(ref[1] + ref[2], got[1] + got[2]):
