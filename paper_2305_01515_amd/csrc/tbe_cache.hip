@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void huge_starts_kernel(const TableMeta *__res
     const int h = x / kHugeRanges, range = x % kHugeRanges;
     const int u = huge[h];
     const int t = uniq_tab[u];
-    const int tb = kTileBytes / (tm[t].lanes * (tm[t].dtype == 0 ? 4 : 8) * 4);  // bags per gradient tile
+    const int tb = huge_tile_bags(kTileBytes / (tm[t].lanes * (tm[t].dtype == 0 ? 4 : 8) * 4), B);  // bags per gradient tile
     const int n_tiles = (B + tb - 1) / tb;
     const int tiles_per_range = (n_tiles + kHugeRanges - 1) / kHugeRanges;
     const int first_bag = t * B + range * tiles_per_range * tb;

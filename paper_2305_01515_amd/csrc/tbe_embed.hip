@@ -368,12 +368,13 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int ROWF = G * EPL;                       // floats per staged gradient row
-  constexpr int TB = kTileBytes / (ROWF * 4);         // bags per tile
-  __shared__ float tile[TB * ROWF];
+  constexpr int TB_MAX = kTileBytes / (ROWF * 4);     // bags that fit a tile
+  __shared__ float tile[TB_MAX * ROWF];
   if (cnt->err) return;
   const int n_work = cnt->n_hchunks * kHugeRanges;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
   const int gshift = (threadIdx.x & 63) / G * G;
+  const int TB = huge_tile_bags(TB_MAX, B);
   const int n_tiles = (B + TB - 1) / TB;
   const int tiles_per_range = (n_tiles + kHugeRanges - 1) / kHugeRanges;
   for (int wk = blockIdx.x; wk < n_work; wk += gridDim.x) {

@@ -195,6 +195,14 @@ hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassIn
 
 // ---- small device helpers ----
 
+// Bags per gradient tile of the huge-row backward: what fits the LDS tile, but few enough
+// that a batch has at least kHugeRanges tiles -- every range then sums a bounded share of a
+// row's lookups, which bounds the length of the fp32 summation chains.
+__host__ __device__ inline int huge_tile_bags(int fit, int B) {
+  const int cap = (B + kHugeRanges - 1) / kHugeRanges;
+  return fit < cap ? fit : (cap < 1 ? 1 : cap);
+}
+
 // table that owns sort key `key`: last t with key_base[t] <= key
 __device__ inline int find_table(const TableMeta *tm, int T, uint32_t key) {
   int lo = 0, hi = T - 1;

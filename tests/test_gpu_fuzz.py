@@ -1,0 +1,42 @@
+"""Randomised parity: small models drawn from a seed (table count, rows, dims, storage
+types, ways, cache sizes incl. none and more than the rows, batch, pooling, skew, call
+order) against the oracle.  Each case is a few thousand lookups; the shapes hit group sizes
+from 1 to 64 lanes, set counts that are not powers of two, and every backward class."""
+import numpy as np
+import pytest
+
+from paper_2305_01515_amd import synth
+from parity_util import run_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def draw(seed):
+    g = np.random.default_rng(seed)
+    ways = int(g.choice([1, 2, 3, 7, 16, 32, 33, 64]))
+    T = int(g.integers(1, 7))
+    tabs = []
+    for _ in range(T):
+        dtype = int(g.integers(0, 2))
+        epl = 4 if dtype == synth.FP32 else 8
+        dim = epl * int(g.choice([1, 2, 3, 5, 8, 16, 24, 32, 64]))
+        rows = int(g.choice([1, 5, 63, 500, 4097, 30000]))
+        kind = g.choice(["none", "tiny", "some", "all"])
+        slots = {"none": 0, "tiny": ways, "some": max(ways, rows // 7), "all": rows + 3 * ways}[str(kind)]
+        alpha = [None, 0.8, 1.0, 1.3][int(g.integers(0, 4))]
+        if g.random() < 0.5:
+            pool = ("fixed", int(g.integers(0, 40)))
+        else:
+            pool = ("poisson", float(g.choice([0.3, 2.0, 15.0, 60.0])))
+        tabs.append(synth.TableCfg(rows, dim, dtype, alpha, pool[0], pool[1], 0, 150, cache_slots=int(slots)))
+    batch = int(g.choice([1, 2, 17, 64, 300]))
+    order = str(g.choice(["serial", "inline", "ahead", "early"]))
+    overlap = bool(g.integers(0, 2))
+    cfg = synth.WorkloadCfg(f"fuzz{seed}", tabs, batch=batch, ways=ways, steps=4, seed=1000 + seed, init_std=0.05, lr=0.05)
+    return cfg, order, overlap
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_model(seed):
+    cfg, order, overlap = draw(seed)
+    run_parity(cfg, steps=4, order=order, overlap=overlap)
