@@ -35,8 +35,15 @@
  * with the smallest timestamp below k (free entries carry -1; the lowest way wins a
  * tie); the row that was there is evicted and written back, the new row is fetched.  A
  * row whose set has no entry older than k is not cached for this batch ("bypass"): it
- * is read and updated directly in the backing tier.  No row needed by a batch that has not
- * trained is ever evicted (Section 5.7).
+ * leaves no trace in tags or timestamps; the library trains it on a temporary HBM copy
+ * and writes that back right after the batch's backward.  No row needed by a batch that
+ * has not trained is ever evicted (Section 5.7).
+ *
+ * When the backing tier is current: a row's host copy is stale while the row is cached
+ * (write-back cache), while its batch trains if it was bypassed, and while an evicted
+ * copy is still on its way; the row-wise accumulators live in HBM for all rows (the paper
+ * keeps optimizer parameters there, Section 5.6.1) and host_state is only read by
+ * tbe_create and written by tbe_flush.  After tbe_flush both host arrays are current.
  */
 #ifndef TBE_H
 #define TBE_H
@@ -69,7 +76,8 @@ typedef struct {
   int32_t dtype;       /* TBE_FP32 or TBE_FP16                                                   */
   void *host_weights;  /* HOST, pinned (hipHostMalloc / tbe_host_alloc), [rows, dim] row-major:  */
                        /* the backing tier; read and written by GPU kernels over the host link   */
-  float *host_state;   /* HOST, pinned, [rows]: row-wise Adagrad accumulator of the backing tier */
+  float *host_state;   /* HOST, pinned, [rows]: row-wise Adagrad accumulators; read by tbe_create,  */
+                       /* written by tbe_flush (in between they live in HBM)                        */
   int64_t cache_slots; /* HBM slots for this table; S_t = cache_slots / ways (floor); 0 = none   */
 } tbe_table_spec;
 
@@ -78,7 +86,7 @@ typedef struct {
   int64_t uniques;     /* distinct (table, row) pairs                            */
   int64_t hits;        /* distinct rows found in the cache                       */
   int64_t inserts;     /* distinct rows fetched into the cache                   */
-  int64_t bypasses;    /* distinct rows served from the backing tier directly    */
+  int64_t bypasses;    /* distinct rows not cached for this batch (set overflow) */
   int64_t evictions;   /* rows written back to make room (subset of inserts)     */
   int64_t hit_lookups; /* lookups whose row was a hit (lookup-weighted hit count) */
 } tbe_batch_stats;
@@ -158,7 +166,7 @@ int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets
  *   g[d]  = sum over its lookups j of d_grad_out[bag(j) * sum_dim + col_t + d]
  *   m_r  += (1 / D_t) * sum_d g[d]^2
  *   w_r[d] -= lr * g[d] / (sqrt(m_r) + eps)           (with the new m_r)
- * applied in place to the cache line, or to the backing tier for bypassed rows.
+ * applied in place to the cache line (or to the temporary copy of a bypassed row).
  * d_grad_out: DEVICE float[batch * sum_dim], ready on the compute stream.
  * TBE_EORDER without a forwarded batch.
  */

@@ -1,4 +1,5 @@
-// C ABI of libtbe: handle life cycle, the two-stream batch pipeline, observation calls.
+// C ABI of libtbe: handle life cycle, the three-stream batch pipeline (compute, prefetch,
+// host link), observation calls.
 // Declarations and the contract of every call are in include/tbe.h.
 #include <algorithm>
 #include <cstdio>

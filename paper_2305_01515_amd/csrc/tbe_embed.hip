@@ -1,6 +1,6 @@
 // Pooled embedding-bag forward (Section 2.1.1) and the sparse backward fused with row-wise
 // Adagrad (Section 2.1.2, Section 5.9) over cache lines in HBM; rows that bypassed the
-// cache are read from / updated in the pinned backing tier directly.
+// cache are read from / updated in their HBM overflow copies (written back afterwards).
 //
 // A row is handled by G lanes, 16 bytes of the row per lane (4 fp32 or 8 fp16 elements);
 // kernels are instantiated per storage type and G, tables are grouped into such classes.
