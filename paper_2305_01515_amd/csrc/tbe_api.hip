@@ -462,6 +462,8 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     CREATE_TRY(h->mem.get(&st.in, M * st.stride));
     for (int p2 = 0; p2 < 2; p2++) {
       CREATE_TRY(h->mem.get(&st.out[p2], M * st.stride));
+      CREATE_TRY(h->mem.get(&st.wb_skip[p2], M));
+      CREATE_TRY(hipMemset(st.wb_skip[p2], 0, M ? M : 1));
     }
     CREATE_TRY(h->mem.get(&st.wb_dst, 8 * M));
     CREATE_TRY(h->mem.get(&st.wb_rb, 4 * M));

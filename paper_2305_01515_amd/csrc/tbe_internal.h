@@ -132,6 +132,8 @@ struct Staging {
   char *out[2];        // [max_inserts * stride] each
   char **wb_dst;       // [max_inserts] backing-tier row of each staged victim (null = none)
   uint32_t *wb_rb;     // [max_inserts] row bytes
+  uint8_t *wb_skip[2]; // [max_inserts] by parity of the batch that parked the victim: 1 = the next batch
+                       // takes the row straight back (from `out`), so it need not travel to the host
   int32_t *wb_n;       // [0] number of parked victim slots, [1] which `out` holds them (device)
   uint32_t *where;     // [key span] per sort key: 0, or where the row's current value is while its
                        // backing-tier copy is stale (kWhereOverflow | j, kWhereParked | i)

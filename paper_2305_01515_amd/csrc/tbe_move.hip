@@ -70,6 +70,11 @@ __global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCo
     }
     if (i < n_wb) {
       char *dst = st.wb_dst[i];
+      uint8_t *skip = st.wb_skip[st.wb_n[1] & 1] + i;
+      if (*skip) {  // the batch being prefetched takes this row back from the parked copy: the
+        dst = nullptr;  // line stays dirty in HBM and is written back when it is evicted again
+        if (lig == 0) *skip = 0;
+      }
       if (dst) {
         const uint32_t wrb = st.wb_rb[i];
         copy_row(dst, st.out[st.wb_n[1] & 1] + (size_t)i * st.stride, wrb, lig);
@@ -148,13 +153,16 @@ __global__ __launch_bounds__(256) void classify_kernel(const BatchCounters *cnt,
                                                        const uint32_t *__restrict__ byp_key,
                                                        const uint32_t *__restrict__ where,
                                                        uint32_t *__restrict__ ins_where,
-                                                       uint32_t *__restrict__ byp_where, u64 *n_late) {
+                                                       uint32_t *__restrict__ byp_where,
+                                                       uint8_t *__restrict__ prev_wb_skip, u64 *n_late) {
   if (cnt->err) return;
   const int n_ins = cnt->n_ins, n_byp = cnt->n_byp;
   unsigned int late = 0;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_ins + n_byp; i += gridDim.x * blockDim.x) {
     const uint32_t code = where[i < n_ins ? ins_key[i] : byp_key[i - n_ins]];
     if (i < n_ins) ins_where[i] = code; else byp_where[i - n_ins] = code;
+    // a victim the batch before parked and this batch wants back skips the trip to the host
+    if (code & kWhereParked) prev_wb_skip[code & kWhereIndex] = 1;
     late += code != 0;
   }
   for (int d = 32; d >= 1; d >>= 1) late += __shfl_xor(late, d);
@@ -164,7 +172,7 @@ __global__ __launch_bounds__(256) void classify_kernel(const BatchCounters *cnt,
 hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, const Staging &st,
                                 u64 *n_late, hipStream_t s) {
   hipLaunchKernelGGL(classify_kernel, dim3(512), dim3(256), 0, s, cur.cnt, cur.ins_key, cur.byp_key, st.where,
-                     cur.ins_where, cur.byp_where, n_late);
+                     cur.ins_where, cur.byp_where, st.wb_skip[(cur.k - 1) & 1], n_late);
   if (prev)
     hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, prev->cnt, prev->ins_tab, prev->ins_old, prev->byp_key,
                        st.where, 0);
