@@ -80,6 +80,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--tables", type=int, default=32, help="(debug) fewer tables than the named workload")
+    ap.add_argument("--workload", default="main", choices=["main", "tiny", "capacity", "locality"],
+                    help="main = the benchmark workload; the others are the parity configurations, for reference "
+                         "measurements only (no CPU baseline)")
+    ap.add_argument("--alpha", type=float, default=1.0, help="locality: Zipf exponent, 0 = uniform")
+    ap.add_argument("--cache-frac", type=float, default=0.05, help="locality: cached fraction of the rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="run everything on one stream")
     args = ap.parse_args()
@@ -95,13 +100,33 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda"
     K, Wm = args.steps, args.warmup
-    cfg = synth.config_main(tables=args.tables)
+    if args.workload == "main":
+        cfg = synth.config_main(tables=args.tables)
+        desc = ("32 tables x 1M rows x dim 128 fp16, batch 8192, pooling Poisson(30) in [1,200], Zipf 1.1, 64-way LRU "
+                "cache 5% of rows in HBM, backing tier in pinned host memory, next-batch prefetch ahead of training")
+    elif args.workload == "tiny":
+        cfg = synth.config_tiny()
+        desc = "4 tables x 100k rows x dim 64 fp32, batch 512, pooling 20, Zipf 1.05, 32-way cache 10% of rows"
+    elif args.workload == "capacity":
+        # the test box refuses to pin more than about 64 GiB of host memory, so half the rows
+        # (and half the cache: the same 6.25 % of the rows); per-step shape unchanged
+        cfg = synth.config_capacity(rows=1 << 25, cache_bytes=4 << 30)
+        desc = ("8 tables x 32M rows x dim 128 fp16 (64 GiB in pinned host memory; half of the capacity-bound "
+                "configuration's rows), 4 GiB 64-way cache, batch 65536, pooling Poisson(40), Zipf 1.05, 30% of each "
+                "batch re-drawn from the previous 4 batches")
+    else:
+        cfg = synth.config_locality(args.alpha if args.alpha > 0 else None, args.cache_frac)
+        desc = (f"1 table x 100M rows x dim 64 fp16, batch 32768, pooling 32, "
+                f"{'uniform' if args.alpha <= 0 else 'Zipf %g' % args.alpha}, 64-way cache {args.cache_frac:.0%} of rows")
+    if args.workload != "main":
+        args.no_cpu_baseline = True
     T = cfg.num_tables
 
     # backing tier: pinned host tables, initialised on the GPU and copied over
     Wp, Mp = [], []
     for t, tc in enumerate(cfg.tables):
-        w = torch.empty(tc.rows, tc.dim, dtype=torch.float16, pin_memory=True)
+        w = torch.empty(tc.rows, tc.dim, dtype=torch.float32 if tc.dtype == synth.FP32 else torch.float16,
+                        pin_memory=True)
         synth.init_table(cfg, t, device=dev, out=w)
         Wp.append(w)
         Mp.append(torch.zeros(tc.rows, dtype=torch.float32, pin_memory=True))
@@ -187,8 +212,9 @@ def main():
     bwd_ms, bwd_iso = sum(ms[k] for k in BWD), sum(iso[k] for k in BWD)
     hit_ms, hit_iso = ms["forward"] + bwd_ms, iso["forward"] + bwd_iso
     hit_b = fwd_b + bwd_b
-    fwd_traffic = measured_traffic("forward_kernel")
-    bwd_traffic = {k: measured_traffic(k + "_kernel") for k in BWD}
+    # the committed counter summary is of the benchmark workload only
+    fwd_traffic = measured_traffic("forward_kernel") if args.workload == "main" and T == 32 else None
+    bwd_traffic = {k: (measured_traffic(k + "_kernel") if fwd_traffic else None) for k in BWD}
     hit_traffic = (fwd_traffic + sum(bwd_traffic.values())) if fwd_traffic and all(bwd_traffic.values()) else None
     fill_ms = ms["fill"]
     res = {
@@ -198,17 +224,15 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": dt / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 storage / f32 accumulate", "data": "synthetic",
-        "config": {"workload": "32 tables x 1M rows x dim 128 fp16, batch 8192, pooling Poisson(30) in [1,200], "
-                               "Zipf 1.1, 64-way LRU cache 5% of rows in HBM, backing tier in pinned host memory, "
-                               "next-batch prefetch ahead of training",
+        "dtype": "f16 storage / f32 accumulate" if cfg.tables[0].dtype == synth.FP16 else "f32", "data": "synthetic",
+        "config": {"workload": desc,
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
                    "overlap": not args.no_overlap},
         # The HBM-bound kernel that moves most algorithmic bytes on the hit path.  Rows are counted once
         # per lookup (the paper's Eq. 3); repeats of hot rows are served by L2, so achieved can exceed what
         # HBM alone delivers -- `traffic` is what the counters saw.  ms_per_launch is measured in the timed,
         # pipelined region (other streams' kernels share the GPU); `isolated` is the same launch alone.
-        "roofline": {"kernel": "forward_kernel<fp16, 16 lanes/row> (pooled gather)", "bound": "hbm",
+        "roofline": {"kernel": "forward_kernel (pooled gather), %d lanes per row" % (cfg.tables[0].dim // (8 if cfg.tables[0].dtype == synth.FP16 else 4)), "bound": "hbm",
                      "achieved": gbs(fwd_b, ms["forward"]), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs(fwd_b, ms["forward"]) / HBM_PEAK_GBS, "traffic": fwd_traffic,
                      "bytes_per_launch": fwd_b, "ms_per_launch": ms["forward"],
