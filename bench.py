@@ -53,6 +53,32 @@ def measured_traffic(kernel_substr):
     return None
 
 
+def measured_peaks(torch):
+    """What this machine delivers with plain copies (context for the two rooflines): a 1 GiB
+    device-to-device copy (read + write bytes) and 1 GiB pinned host copies each way."""
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    h = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+
+    def rate(fn, nbytes, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    out = {"hbm_copy_GBps": rate(lambda: b.copy_(a), 2 * n),
+           "h2d_GBps": rate(lambda: a.copy_(h, non_blocking=True), n),
+           "d2h_GBps": rate(lambda: h.copy_(a, non_blocking=True), n)}
+    del a, b, h
+    return out
+
+
 def cpu_baseline(cfg, W0, batches, grads, threads):
     """The oracle as it stands, timed on this machine's host cores on the first batches."""
     import numpy as np
@@ -140,6 +166,7 @@ def main():
     max_n = max(int(b[0].numel()) for b in batches)
     out = torch.empty(cfg.batch, cfg.sum_dim, dtype=torch.float32, device=dev)
 
+    peaks = measured_peaks(torch)
     cpu = None
     if not args.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
@@ -269,6 +296,7 @@ def main():
                   "bypass_frac_unique": tot["bypasses"] / max(1, tot["uniques"]),
                   "uniques_per_step": uniq, "inserts_per_step": tot["inserts"] / npf, "long_rows": s1["last_long_rows"],
                   "late_fetches_per_step": (s1["late_fetches"] - s0["late_fetches"]) / npf},
+        "measured_peaks": peaks,  # plain copies on this machine, for context (the fractions above use the nominal peaks)
         "cpu_baseline": cpu,
     }
     print(json.dumps(res))
