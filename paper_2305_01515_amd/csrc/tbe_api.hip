@@ -476,6 +476,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   }
   CREATE_TRY(h->mem.get(&h->ss.hist, 4 * (256 * 1024 + 256)));
   CREATE_TRY(h->mem.get(&h->ss.blk, 8 * 1024));
+  CREATE_TRY(h->mem.get(&h->ss.wl, 4 * 4 * (size_t)kWorklistBlocks));
   CREATE_TRY(h->mem.get(&h->d_total, sizeof(BatchCounters)));
   CREATE_TRY(hipMemset(h->d_total, 0, sizeof(BatchCounters)));
   CREATE_TRY(h->mem.get(&h->d_bytes, 8 * 8));

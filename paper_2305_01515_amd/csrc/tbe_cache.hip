@@ -168,39 +168,77 @@ struct SetHeadOp {
   __device__ void finish(BatchCounters *cnt, int, u64 total) const { cnt->n_touched = (int32_t)(total & 0xFFFFFFFFull); }
 };
 
-// Work lists of the backward by run length (see kLongRun / kHugeRun).  A workgroup takes a
-// contiguous chunk of the distinct rows: it counts the three kinds per wavefront, reserves
-// its list ranges with one atomic per list, then writes the rows out in order.
-__global__ __launch_bounds__(256) void worklist_kernel(const int32_t *__restrict__ run_off, int32_t *mid_idx,
-                                                       int32_t *items, int32_t *huge, BatchCounters *cnt) {
-  __shared__ int s_cnt[4][3];
-  __shared__ int s_base[4][3];
-  if (cnt->err) return;
-  const int n = cnt->n_uniq;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint64_t lt_mask = (1ull << lane) - 1ull;
+// Work lists of the backward by run length (see kLongRun / kHugeRun), in the order of the
+// distinct rows (= table order: the backward kernels give each XCD a contiguous part of a
+// list).  A workgroup takes a contiguous chunk of the distinct rows; the count kernel
+// leaves the three counts of every workgroup in `wl`, the emit kernel adds up the counts
+// of the workgroups before it and writes its rows out in order.
+__device__ inline void worklist_chunk(int n, int &w0, int &w1) {
+  const int wave = threadIdx.x >> 6;
   const int per_wave = ((n + gridDim.x * 4 - 1) / (gridDim.x * 4) + 63) / 64 * 64;
-  const int w0 = (blockIdx.x * 4 + wave) * per_wave;
-  const int w1 = min(n, w0 + per_wave);
-  int c_mid = 0, c_item = 0, c_huge = 0;
+  w0 = (blockIdx.x * 4 + wave) * per_wave;
+  w1 = min(n, w0 + per_wave);
+}
+
+// counts of the wavefront's chunk: (2..kLongRun, kLongRun+1..kHugeRun, more)
+__device__ inline void worklist_tally(const int32_t *__restrict__ run_off, int w0, int w1, int (&c)[3]) {
+  const int lane = threadIdx.x & 63;
+  c[0] = c[1] = c[2] = 0;
   for (int u0 = w0; u0 < w1; u0 += 64) {
     const int u = u0 + lane;
     const int len = u < w1 ? run_off[u + 1] - run_off[u] : 0;
-    c_mid += __popcll(__ballot(len >= 2 && len <= kLongRun));
-    c_item += __popcll(__ballot(len > kLongRun && len <= kHugeRun));
-    c_huge += __popcll(__ballot(len > kHugeRun));
+    c[0] += __popcll(__ballot(len >= 2 && len <= kLongRun));
+    c[1] += __popcll(__ballot(len > kLongRun && len <= kHugeRun));
+    c[2] += __popcll(__ballot(len > kHugeRun));
   }
-  if (lane == 0) { s_cnt[wave][0] = c_mid; s_cnt[wave][1] = c_item; s_cnt[wave][2] = c_huge; }
+}
+
+__global__ __launch_bounds__(256) void worklist_count_kernel(const int32_t *__restrict__ run_off, int32_t *wl,
+                                                             const BatchCounters *cnt) {
+  __shared__ int s_cnt[4][3];
+  if (cnt->err) return;
+  int w0, w1, c[3];
+  worklist_chunk(cnt->n_uniq, w0, w1);
+  worklist_tally(run_off, w0, w1, c);
+  if ((threadIdx.x & 63) == 0)
+    for (int k = 0; k < 3; k++) s_cnt[threadIdx.x >> 6][k] = c[k];
+  __syncthreads();
+  if (threadIdx.x < 3) wl[blockIdx.x * 4 + threadIdx.x] = s_cnt[0][threadIdx.x] + s_cnt[1][threadIdx.x] + s_cnt[2][threadIdx.x] + s_cnt[3][threadIdx.x];
+}
+
+__global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__restrict__ run_off,
+                                                            const int32_t *__restrict__ wl, int32_t *mid_idx,
+                                                            int32_t *items, int32_t *huge, BatchCounters *cnt) {
+  __shared__ int s_cnt[4][3];
+  __shared__ int s_before[4][3];
+  __shared__ int s_base[4][3];
+  if (cnt->err) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  int w0, w1, c[3];
+  worklist_chunk(cnt->n_uniq, w0, w1);
+  worklist_tally(run_off, w0, w1, c);
+  int before[3] = {0, 0, 0};  // rows of each kind in the workgroups before this one
+  for (int b = threadIdx.x; b < (int)blockIdx.x; b += 256)
+    for (int k = 0; k < 3; k++) before[k] += wl[b * 4 + k];
+  for (int k = 0; k < 3; k++)
+    for (int d = 32; d >= 1; d >>= 1) before[k] += __shfl_xor(before[k], d, 64);
+  if (lane == 0)
+    for (int k = 0; k < 3; k++) { s_cnt[wave][k] = c[k]; s_before[wave][k] = before[k]; }
   __syncthreads();
   if (threadIdx.x < 3) {
     const int k = threadIdx.x;
-    const int tot = s_cnt[0][k] + s_cnt[1][k] + s_cnt[2][k] + s_cnt[3][k];
-    int base = 0;
-    if (tot) base = atomicAdd(k == 0 ? &cnt->n_mid : k == 1 ? &cnt->n_items : &cnt->n_huge, tot);
-    if (tot && k != 0) atomicAdd(&cnt->n_long, tot);
+    int base = s_before[0][k] + s_before[1][k] + s_before[2][k] + s_before[3][k];
     for (int w = 0; w < 4; w++) { s_base[w][k] = base; base += s_cnt[w][k]; }
+    if (blockIdx.x == gridDim.x - 1) {  // the last workgroup knows the totals
+      if (k == 0) cnt->n_mid = base;
+      if (k == 1) cnt->n_items = base;
+      if (k == 2) cnt->n_huge = base;
+    }
   }
   __syncthreads();
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0)
+    cnt->n_long = s_base[3][1] + s_cnt[3][1] + s_base[3][2] + s_cnt[3][2];
   int o_mid = s_base[wave][0], o_item = s_base[wave][1], o_huge = s_base[wave][2];
   for (int u0 = w0; u0 < w1; u0 += 64) {
     const int u = u0 + lane;
@@ -477,7 +515,9 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
   run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
-  hipLaunchKernelGGL(worklist_kernel, dim3(1024), dim3(256), 0, s, b.run_off, b.mid_idx, b.items, b.huge, b.cnt);
+  hipLaunchKernelGGL(worklist_count_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, b.cnt);
+  hipLaunchKernelGGL(worklist_emit_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, b.mid_idx, b.items,
+                     b.huge, b.cnt);
   hipLaunchKernelGGL(huge_group_kernel, dim3(1), dim3(1024), 0, s, tm, g.T, b.huge, b.uniq_tab, b.huge_sorted, b.hchunks,
                      b.hg_count, b.cnt);
   hipLaunchKernelGGL(huge_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.huge, b.uniq_tab, b.run_off,

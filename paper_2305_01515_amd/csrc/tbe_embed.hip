@@ -38,10 +38,13 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
                                                       const char *__restrict__ ovf, uint32_t ovf_stride,
                                                       float *__restrict__ out, const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
+  constexpr int R = G < 4 ? G : 4;  // row loads in flight per lane
   if (cnt->err) return;
-  const int t = class_tables[blockIdx.y];
+  // bags are table-major: each XCD takes an eighth of the (table, bag block) pairs
+  const int vb = xcd_block_position(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
+  const int t = class_tables[vb / gridDim.x];
   const TableMeta &m = tm[t];
-  const int b = blockIdx.x * (256 / G) + threadIdx.x / G;
+  const int b = (vb % gridDim.x) * (256 / G) + threadIdx.x / G;
   const int lig = threadIdx.x % G;
   if (b >= B) return;
   const bool active = lig * EPL < m.dim;
@@ -55,10 +58,10 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
   for (int64_t j0 = lo; j0 < hi; j0 += G) {
     const int nq = (int)((hi - j0) < G ? (hi - j0) : G);
     const uint32_t my_loc = lig < nq ? loc[j0 + lig] : 0u;
-    for (int q = 0; q < nq; q += 4) {
-      uint4 v[4];
+    for (int q = 0; q < nq; q += R) {
+      uint4 v[R];
 #pragma unroll
-      for (int x = 0; x < 4; x++) {
+      for (int x = 0; x < R; x++) {
         const int src = (q + x) & (G - 1);
         const uint32_t l = __shfl(my_loc, src, G);
         const uint32_t ix = l & kLocIndex;
@@ -66,7 +69,7 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
         v[x] = (active && q + x < nq) ? *(const uint4 *)(p + lig * 16) : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
-      for (int x = 0; x < 4; x++) accumulate<DT>(acc, v[x]);
+      for (int x = 0; x < R; x++) accumulate<DT>(acc, v[x]);
     }
   }
   if (active) {
@@ -284,8 +287,9 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
   if (cnt->err) return;
   const int n_mid = cnt->n_mid;
   const int lig = threadIdx.x % G;
-  const int n_groups = gridDim.x * (256 / G);
-  for (int i = blockIdx.x * (256 / G) + threadIdx.x / G; i < n_mid; i += n_groups) {
+  int first, end, step;
+  xcd_span(n_mid, 256 / G, first, end, step);  // the list is in table order
+  for (int i = first + threadIdx.x / G; i < end; i += step) {
     const int u = mid_idx[i];
     const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;
@@ -320,7 +324,9 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
   if (cnt->err) return;
   const int n_items = cnt->n_items;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
-  for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+  int first, end, step;
+  xcd_span(n_items, 1, first, end, step);  // the list is in table order
+  for (int it = first; it < end; it += step) {
     const int u = items[it];
     const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;  // uniform over the block
@@ -377,7 +383,9 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
   const int TB = huge_tile_bags(TB_MAX, B);
   const int n_tiles = (B + TB - 1) / TB;
   const int tiles_per_range = (n_tiles + kHugeRanges - 1) / kHugeRanges;
-  for (int wk = blockIdx.x; wk < n_work; wk += gridDim.x) {
+  int first, end, step;
+  xcd_span(n_work, 1, first, end, step);  // work items are in table order
+  for (int wk = first; wk < end; wk += step) {
     const uint4 ch = hchunks[wk / kHugeRanges];  // (table, first position in huge_sorted, rows, -)
     const int range = wk % kHugeRanges;
     const int t = (int)ch.x;
@@ -521,7 +529,7 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
     hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
                        b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   } else if (which == 0) {
-    hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items,
+    hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(8192), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items,
                        b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride,
                        table_class, b.cnt);
   } else {

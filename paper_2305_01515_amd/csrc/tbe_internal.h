@@ -120,6 +120,7 @@ struct SortScratch {
   uint32_t *vals[2];
   uint32_t *hist;          // [256 * max sort blocks] block histograms, then [256] digit totals
   unsigned long long *blk; // [scan blocks + 1] block sums of the compaction passes
+  int32_t *wl;             // [kWorklistBlocks * 4] per-workgroup counts of the backward work lists
 };
 
 // Staging between the cache and the host link (one instance; the prefetch stage is serial).
@@ -203,6 +204,30 @@ hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassIn
 __host__ __device__ inline int huge_tile_bags(int fit, int B) {
   const int cap = (B + kHugeRanges - 1) / kHugeRanges;
   return fit < cap ? fit : (cap < 1 ? 1 : cap);
+}
+
+// Workgroups are handed to the 8 XCDs (each with an L2 of its own) round robin by their
+// linear id.  These helpers turn that id into a position in the work so that every XCD
+// owns one contiguous eighth of it and walks it front to back: work is ordered by table,
+// so a table's rows and its slice of the output gradient are cached in one L2 instead of
+// in all eight.  Only the placement changes; any mapping gives the same results.
+constexpr int kXcds = 8;
+constexpr int kWorklistBlocks = 1024;  // workgroups that build the backward work lists
+
+// position of linear workgroup `id` of `n` when every workgroup is one unit of work
+__device__ inline int xcd_block_position(int id, int n) {
+  const int q = n / kXcds, rem = n % kXcds, x = id % kXcds;
+  return x * q + (x < rem ? x : rem) + id / kXcds;
+}
+
+// [first, end) and step of a grid-stride loop over `n` units, `per_block` units per workgroup
+// and pass, confined to the XCD's eighth; gridDim.x must be a multiple of kXcds
+__device__ inline void xcd_span(int n, int per_block, int &first, int &end, int &step) {
+  const int x = blockIdx.x % kXcds, nb = gridDim.x / kXcds;
+  const int lo = (int)((int64_t)n * x / kXcds);
+  end = (int)((int64_t)n * (x + 1) / kXcds);
+  first = lo + (int)(blockIdx.x / kXcds) * per_block;
+  step = nb * per_block;
 }
 
 // table that owns sort key `key`: last t with key_base[t] <= key
