@@ -115,7 +115,8 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t 
   // How many workgroups wait on the host link, and on how many CUs, decides how the link and
   // the HBM-bound kernels of the other streams slow each other (measured on the benchmark
   // workload, step time / forward kernel time while the transfer runs; alone the forward
-  // takes 0.21 ms and the link needs 5.7 ms):
+  // takes 0.21 ms and the link needs 5.7 ms; the figures compare placements with each
+  // other -- later changes to the other stages lowered all of them by about a millisecond):
   //   256 workgroups on all 8 XCDs : 7.6 ms / 1.2 ms     128 on all 8 : 8.0 ms / 0.29 ms
   //   256 on 1 XCD (fills its CUs) : 8.3 ms / 0.20 ms    128 on 2     : 7.4 ms / 0.34 ms
   //   192 on 2 XCDs                : 7.2 ms / 0.48 ms    128 on 1     : 7.2 ms / 0.43 ms
