@@ -59,6 +59,8 @@ def lib():
         _lib.orc_batch_id.restype = C.c_int32
         _lib.orc_batch_id.argtypes = [C.c_void_p]
         _lib.orc_export_cache_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        _lib.orc_export_cache_freq.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        _lib.orc_set_policy.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_get_stats.argtypes = [C.c_void_p, C.POINTER(Stats), C.POINTER(Stats)]
         _lib.orc_events.restype = C.c_int64
         _lib.orc_events.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 4
@@ -81,7 +83,7 @@ class Oracle:
     float32 -- the backing tier, modified in place (C-contiguous, kept alive here)."""
 
     def __init__(self, weights: Sequence[np.ndarray], state: Sequence[np.ndarray], cache_slots: Sequence[int],
-                 ways: int, threads: int = 1):
+                 ways: int, threads: int = 1, policy: str = "lru"):
         self.weights = list(weights)
         self.state = list(state)
         self.ways = ways
@@ -100,6 +102,9 @@ class Oracle:
         if not self.h:
             raise OracleError(-1, "create")
         lib().orc_set_threads(self.h, threads)
+        rc = lib().orc_set_policy(self.h, {"lru": 0, "lfu": 1}[policy])
+        if rc:
+            raise OracleError(rc, "set_policy")
         self.B = 0
 
     def close(self):
@@ -153,6 +158,11 @@ class Oracle:
         ts = np.empty(n, dtype=np.int32)
         lib().orc_export_cache_state(self.h, t, tags.ctypes.data, ts.ctypes.data)
         return tags, ts
+
+    def cache_freq(self, t: int) -> np.ndarray:
+        f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)
+        lib().orc_export_cache_freq(self.h, t, f.ctypes.data)
+        return f
 
     def stats(self):
         last, total = Stats(), Stats()

@@ -30,7 +30,13 @@
  *     lines are dirty); flush writes back every valid line and keeps the tags;
  *   - row-wise Adagrad: m += mean_d(g_d^2); w_d -= lr * g_d / (sqrt(m) + eps), m starts
  *     wherever the caller's state array starts (0 in the tests), eps outside the root;
- *   - fp16 storage: rows are widened exactly, results are rounded to nearest even.
+ *   - fp16 storage: rows are widened exactly, results are rounded to nearest even;
+ *   - LFU, the other policy the paper tried [Section 5.5.2; it gives no details]: every
+ *     entry also counts the lookups of its row since it was inserted (a row looked up c
+ *     times in a batch adds c; the count saturates at INT32_MAX and is forgotten at
+ *     eviction; free entries count 0).  The two phases, the lock of the ways stamped k
+ *     and the bypass rule are those of LRU; only the choice of the victim differs: the
+ *     smallest count, the smallest timestamp among equal counts, the lowest way after that.
  * All floating-point work is done in fp64 from the stored values and rounded once when
  * stored (fp32 state, fp32 or fp16 weights, fp32 pooled output).
  *
@@ -49,6 +55,9 @@
 #define ORC_ERANGE (-2)
 #define ORC_EORDER (-3)
 #define ORC_ENOMEM (-4)
+
+#define ORC_LRU 0
+#define ORC_LFU 1
 
 typedef struct {
   int64_t rows;        /* H_t */
@@ -71,6 +80,7 @@ typedef struct {
   int64_t sets;
   int64_t *tag;     /* [sets*ways], -1 = free */
   int32_t *ts;      /* [sets*ways], -1 = free */
+  int32_t *freq;    /* [sets*ways], lookups since insertion (kept under both policies, used by LFU) */
   void *lines;      /* [sets*ways, dim] in the storage type */
   float *line_state;/* [sets*ways] */
   /* last prefetched batch */
@@ -88,6 +98,7 @@ typedef struct {
 
 typedef struct {
   int32_t T, ways;
+  int32_t policy;      /* ORC_LRU or ORC_LFU */
   orc_table *tab;
   int32_t k;           /* batch id of the last prefetch */
   int32_t B;
@@ -151,7 +162,7 @@ static size_t esize(int dtype) { return dtype == 0 ? 4 : 2; }
 /* ---------------- life cycle ---------------- */
 
 static void free_table(orc_table *t) {
-  free(t->tag); free(t->ts); free(t->lines); free(t->line_state);
+  free(t->tag); free(t->ts); free(t->freq); free(t->lines); free(t->line_state);
   free(t->uniq); free(t->mult); free(t->hit_row); free(t->ins_row);
   free(t->ins_slot); free(t->ins_old); free(t->byp_row);
 }
@@ -181,9 +192,10 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
     if (slots > 0) {
       tb->tag = (int64_t *)malloc(sizeof(int64_t) * (size_t)slots);
       tb->ts = (int32_t *)malloc(sizeof(int32_t) * (size_t)slots);
+      tb->freq = (int32_t *)calloc((size_t)slots, sizeof(int32_t));
       tb->lines = calloc((size_t)slots * (size_t)s->dim, esize(s->dtype));
       tb->line_state = (float *)calloc((size_t)slots, sizeof(float));
-      if (!tb->tag || !tb->ts || !tb->lines || !tb->line_state) { orc_destroy(h); return NULL; }
+      if (!tb->tag || !tb->ts || !tb->freq || !tb->lines || !tb->line_state) { orc_destroy(h); return NULL; }
       for (int64_t i = 0; i < slots; i++) { tb->tag[i] = -1; tb->ts[i] = -1; }
     }
   }
@@ -191,6 +203,15 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
 }
 
 void orc_set_threads(void *hp, int n) { ((orc *)hp)->threads = n > 0 ? n : 1; }
+
+/* replacement policy; only before the first batch */
+int orc_set_policy(void *hp, int32_t policy) {
+  orc *h = (orc *)hp;
+  if (!h || (policy != ORC_LRU && policy != ORC_LFU)) return ORC_EINVAL;
+  if (h->k != 0) return ORC_EORDER;
+  h->policy = policy;
+  return ORC_OK;
+}
 
 /* ---------------- cache primitives ---------------- */
 
@@ -214,6 +235,11 @@ static void backing_to_line(orc_table *tb, int64_t slot, int64_t r) {
   tb->line_state[slot] = tb->state[r];
 }
 
+static int32_t add_saturating(int32_t a, int64_t b) {
+  int64_t v = (int64_t)a + b;
+  return v > INT32_MAX ? INT32_MAX : (int32_t)v;
+}
+
 static int cmp_i64(const void *a, const void *b) {
   int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
   return x < y ? -1 : x > y;
@@ -232,7 +258,7 @@ static int grow(orc_table *tb, int64_t n) {
   return 0;
 }
 
-/* One table, one batch: distinct rows, then the two-phase LRU pass. */
+/* One table, one batch: distinct rows, then the two-phase replacement pass. */
 static int prefetch_table(orc *h, int t) {
   orc_table *tb = &h->tab[t];
   const int W = h->ways;
@@ -264,6 +290,7 @@ static int prefetch_table(orc *h, int t) {
     int64_t slot = find_slot(tb, W, tb->uniq[i]);
     if (slot >= 0) {
       tb->ts[slot] = k;
+      tb->freq[slot] = add_saturating(tb->freq[slot], tb->mult[i]);
       is_hit[i] = 1;
       tb->hit_row[tb->n_hit++] = tb->uniq[i];
       tb->st.hits++;
@@ -279,8 +306,11 @@ static int prefetch_table(orc *h, int t) {
     if (tb->sets > 0) {
       s = r % tb->sets;
       for (int w = 0; w < W; w++) {
-        int32_t tw = tb->ts[s * W + w];
-        if (tw < k && (victim < 0 || tw < tb->ts[s * W + victim])) victim = w;
+        int32_t tw = tb->ts[s * W + w], fw = tb->freq[s * W + w];
+        if (tw >= k) continue; /* used by this batch: locked */
+        if (victim < 0) { victim = w; continue; }
+        int32_t tv = tb->ts[s * W + victim], fv = tb->freq[s * W + victim];
+        if (h->policy == ORC_LFU ? (fw < fv || (fw == fv && tw < tv)) : (tw < tv)) victim = w;
       }
     }
     if (victim < 0) {
@@ -294,6 +324,7 @@ static int prefetch_table(orc *h, int t) {
     backing_to_line(tb, slot, r);
     tb->tag[slot] = r;
     tb->ts[slot] = k;
+    tb->freq[slot] = add_saturating(0, tb->mult[i]);
     tb->ins_row[tb->n_ins] = r; tb->ins_slot[tb->n_ins] = slot; tb->ins_old[tb->n_ins] = old;
     tb->n_ins++;
     tb->st.inserts++;
@@ -447,6 +478,16 @@ int orc_export_cache_state(void *hp, int32_t t, int64_t *tags, int32_t *ts) {
   orc_table *tb = &h->tab[t];
   int64_t n = tb->sets * h->ways;
   if (n) { memcpy(tags, tb->tag, sizeof(int64_t) * (size_t)n); memcpy(ts, tb->ts, sizeof(int32_t) * (size_t)n); }
+  return ORC_OK;
+}
+
+/* lookup counts of the entries (0 for free ones), same order as the tags */
+int orc_export_cache_freq(void *hp, int32_t t, int32_t *freq) {
+  orc *h = (orc *)hp;
+  if (!h || t < 0 || t >= h->T || !freq) return ORC_EINVAL;
+  orc_table *tb = &h->tab[t];
+  int64_t n = tb->sets * h->ways;
+  if (n) memcpy(freq, tb->freq, sizeof(int32_t) * (size_t)n);
   return ORC_OK;
 }
 
