@@ -147,6 +147,8 @@ def main():
                          "measurements only (no CPU baseline)")
     ap.add_argument("--alpha", type=float, default=1.0, help="locality: Zipf exponent, 0 = uniform")
     ap.add_argument("--cache-frac", type=float, default=0.05, help="locality: cached fraction of the rows")
+    ap.add_argument("--policy", default="lru", choices=["lru", "lfu"],
+                    help="replacement policy; lru is the benchmark's, lfu for the comparison the paper makes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="run everything on one stream")
     args = ap.parse_args()
@@ -180,7 +182,9 @@ def main():
         cfg = synth.config_locality(args.alpha if args.alpha > 0 else None, args.cache_frac)
         desc = (f"1 table x 100M rows x dim 64 fp16, batch 32768, pooling 32, "
                 f"{'uniform' if args.alpha <= 0 else 'Zipf %g' % args.alpha}, 64-way cache {args.cache_frac:.0%} of rows")
-    if args.workload != "main":
+    if args.policy != "lru":
+        desc = desc.replace("LRU ", "").replace("-way cache", "-way LFU cache")
+    if args.workload != "main" or args.policy != "lru":
         args.no_cpu_baseline = True
     T = cfg.num_tables
 
@@ -212,7 +216,8 @@ def main():
         cpu = {"value": v, "unit": "lookups/s", "cores": threads, "kind": "oracle",
                "sample": f"first batches of the same stream from a cold cache ({n} lookups), oracle -O2, OpenMP over tables"}
 
-    g = TBE(Wp, Mp, [tc.cache_slots for tc in cfg.tables], cfg.ways, cfg.batch, max_n + 1, overlap=not args.no_overlap)
+    g = TBE(Wp, Mp, [tc.cache_slots for tc in cfg.tables], cfg.ways, cfg.batch, max_n + 1, overlap=not args.no_overlap,
+            policy=args.policy)
 
     def run(lo, hi):
         # next-batch prefetch is issued ahead of the current batch's training
@@ -290,7 +295,7 @@ def main():
         "dtype": "f16 storage / f32 accumulate" if cfg.tables[0].dtype == synth.FP16 else "f32", "data": "synthetic",
         "config": {"workload": desc,
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
-                   "overlap": not args.no_overlap},
+                   "overlap": not args.no_overlap, "policy": args.policy},
         # The HBM-bound kernel that moves most algorithmic bytes on the hit path.  Rows are counted once
         # per lookup (the paper's Eq. 3); repeats of hot rows are served by L2, so achieved can exceed what
         # HBM alone delivers -- `traffic` is what the counters saw.  ms_per_launch is measured in the timed,

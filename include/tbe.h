@@ -139,6 +139,21 @@ int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offset
                  int64_t num_lookups);
 
 /*
+ * Replacement policy (Section 5.5.2 names the two that were tried).  TBE_POLICY_LRU, the
+ * default: the victim of a miss is the way with the smallest timestamp.  TBE_POLICY_LFU:
+ * every entry counts the lookups of its row since it was inserted (a row looked up c times
+ * in a batch adds c; saturates at INT32_MAX; forgotten at eviction; free entries count 0)
+ * and the victim is the way with the smallest count, the smallest timestamp among equal
+ * counts, the lowest way after that.  Everything else -- hits stamped first, misses in
+ * ascending row order, ways stamped by the current batch are locked, overflow bypasses --
+ * is the same.  The counts are kept under both policies.  Only before the first
+ * tbe_prefetch (TBE_EORDER afterwards); TBE_EINVAL for an unknown policy.
+ */
+#define TBE_POLICY_LRU 0
+#define TBE_POLICY_LFU 1
+int tbe_set_policy(tbe_handle h, int32_t policy);
+
+/*
  * By default tbe_prefetch orders its work behind everything enqueued on the compute stream
  * so far, because the index buffers may have been produced there.  With ready = 1 the
  * caller guarantees instead that the buffers passed to tbe_prefetch are complete in device
@@ -214,6 +229,10 @@ int64_t tbe_num_sets(tbe_handle h, int32_t table);
 /* Copy a table's tags (row id, -1 = free) and timestamps (batch id, -1 = free) to
  * HOST arrays of S_t * ways entries, index set * ways + way.  Synchronises. */
 int tbe_export_cache_state(tbe_handle h, int32_t table, int64_t *h_tags, int32_t *h_ts);
+
+/* Copy a table's per-entry lookup counts (see tbe_set_policy; 0 = free) to a HOST array of
+ * S_t * ways entries, same order as the tags.  Synchronises. */
+int tbe_export_cache_freq(tbe_handle h, int32_t table, int32_t *h_freq);
 
 /*
  * Events of the last prefetched batch.  kind 0 = hits, 1 = inserts, 2 = bypasses.

@@ -45,7 +45,8 @@ struct tbe_ctx {
   TableMeta *d_tm = nullptr;
   ClassInfo ci{};
   DevAlloc mem;
-  int32_t *tags = nullptr, *ts = nullptr;
+  int32_t *tags = nullptr, *ts = nullptr, *freq = nullptr;
+  int policy = TBE_POLICY_LRU;
   float *d_state = nullptr;   // row-wise Adagrad accumulators of all rows of all tables
   float *partials = nullptr;  // segment sums of the backward's longest rows
   char *lines = nullptr;
@@ -241,7 +242,8 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     HIP_TRY(h, launch_keygen(h->d_tm, h->g, b, h->ss.keys[0], h->ss.vals[0], h->as));
     int res = 0;
     HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
-    HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->as));
+    HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->freq,
+                                  h->policy == TBE_POLICY_LFU, h->as));
     // which of the rows to insert have a backing-tier copy that is still being written
     // (by the write-back of the previous batch's victims or by its backward), then move
     // the marks on from the previous batch to this one
@@ -396,9 +398,11 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   CREATE_TRY(h->mem.get(&h->lines, line_bytes));
   CREATE_TRY(h->mem.get(&h->tags, 4 * slots));
   CREATE_TRY(h->mem.get(&h->ts, 4 * slots));
+  CREATE_TRY(h->mem.get(&h->freq, 4 * slots));
   if (slots) {
     CREATE_TRY(hipMemset(h->tags, 0xFF, 4 * slots));  // -1 = free
     CREATE_TRY(hipMemset(h->ts, 0xFF, 4 * slots));
+    CREATE_TRY(hipMemset(h->freq, 0, 4 * slots));
   }
   {  // accumulators of all rows live in HBM; the host arrays give their initial values
     size_t total_rows = 0;
@@ -575,6 +579,14 @@ int tbe_flush(tbe_handle h) {
   return collect_device_errors(h);
 }
 
+int tbe_set_policy(tbe_handle h, int32_t policy) {
+  if (!h) return TBE_EINVAL;
+  if (policy != TBE_POLICY_LRU && policy != TBE_POLICY_LFU) return fail(h, TBE_EINVAL, "set_policy: unknown policy");
+  if (h->k != 0) return fail(h, TBE_EORDER, "set_policy: batches have been prefetched already");
+  h->policy = policy;
+  return TBE_OK;
+}
+
 int tbe_set_inputs_ready(tbe_handle h, int32_t ready) {
   if (!h) return TBE_EINVAL;
   h->inputs_ready = ready != 0;
@@ -652,6 +664,17 @@ int tbe_export_cache_state(tbe_handle h, int32_t table, int64_t *h_tags, int32_t
   HIP_TRY(h, hipMemcpy(tmp.data(), h->tags + m.slot_base, 4 * n, hipMemcpyDeviceToHost));
   for (size_t i = 0; i < n; i++) h_tags[i] = tmp[i];
   HIP_TRY(h, hipMemcpy(h_ts, h->ts + m.slot_base, 4 * n, hipMemcpyDeviceToHost));
+  return TBE_OK;
+}
+
+int tbe_export_cache_freq(tbe_handle h, int32_t table, int32_t *h_freq) {
+  if (!h || table < 0 || table >= h->g.T || !h_freq) return TBE_EINVAL;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  const TableMeta &m = h->tm[table];
+  const size_t n = (size_t)m.sets * h->g.ways;
+  if (n == 0) return TBE_OK;
+  HIP_TRY(h, hipMemcpy(h_freq, h->freq + m.slot_base, 4 * n, hipMemcpyDeviceToHost));
   return TBE_OK;
 }
 

@@ -390,22 +390,32 @@ struct StatusOp {
 };
 
 // --------------------------------------------------------------------------------------
-// Probe + LRU: one wavefront per touched set; lane w holds way w.
-//   phase 1: every distinct row of the set that is found is a hit, its way is stamped k;
-//   phase 2: the ways still older than k are ranked by (timestamp, way); the j-th miss in
-//            ascending row order takes the way of rank j (evicting what it held); misses
-//            beyond the number of such ways bypass the cache.
+// Probe + replacement: one wavefront per touched set; lane w holds way w.
+//   phase 1: every distinct row of the set that is found is a hit, its way is stamped k and
+//            its count grows by the row's lookups in the batch;
+//   phase 2: the ways still older than k are ranked by (timestamp, way) -- LRU -- or by
+//            (count, timestamp, way) -- LFU; the j-th miss in ascending row order takes the
+//            way of rank j (evicting what it held) and starts counting at its own lookups;
+//            misses beyond the number of such ways bypass the cache.
 // Rows of a set arrive in ascending order because the sort key is (set, row div S).
 // --------------------------------------------------------------------------------------
+__device__ inline int32_t add_saturating(int32_t a, int32_t b) {  // a, b >= 0
+  const uint32_t v = (uint32_t)a + (uint32_t)b;
+  return v > 0x7FFFFFFFu ? 0x7FFFFFFF : (int32_t)v;
+}
+
+template <bool LFU>
 __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restrict__ tm, int T, int W, int32_t k,
                                                       const uint32_t *__restrict__ uniq_key,
                                                       const int32_t *__restrict__ uniq_tab,
                                                       const uint2 *__restrict__ touched, int32_t *__restrict__ tags,
-                                                      int32_t *__restrict__ ts, int32_t *__restrict__ loc_u,
-                                                      uint8_t *__restrict__ status, int32_t *__restrict__ old_tag,
-                                                      const BatchCounters *cnt) {
+                                                      int32_t *__restrict__ ts, int32_t *__restrict__ freq,
+                                                      const int32_t *__restrict__ run_off,
+                                                      int32_t *__restrict__ loc_u, uint8_t *__restrict__ status,
+                                                      int32_t *__restrict__ old_tag, const BatchCounters *cnt) {
   __shared__ int32_t l_tag[kWave];
   __shared__ int32_t l_ts[kWave];
+  __shared__ int32_t l_freq[kWave];
   __shared__ int32_t l_way[kWave];
   if (cnt->err) return;
   const int lane = threadIdx.x;
@@ -429,6 +439,7 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
     __syncthreads();
     l_tag[lane] = lane < W ? tags[slot0 + lane] : -2;
     l_ts[lane] = lane < W ? ts[slot0 + lane] : 0x7FFFFFFF;
+    l_freq[lane] = lane < W ? freq[slot0 + lane] : 0;
     __syncthreads();
     // phase 1: hits
     for (int c = u0; c < u1; c += kWave) {
@@ -441,6 +452,7 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
       if (valid) {
         if (hit >= 0) {
           l_ts[hit] = k;
+          l_freq[hit] = add_saturating(l_freq[hit], run_off[u + 1] - run_off[u]);
           loc_u[u] = slot0 + hit;
           status[u] = ST_HIT;
         } else {
@@ -452,10 +464,17 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
     // phase 2: rank the evictable ways
     const int32_t my_ts = l_ts[lane];
     const bool cand = lane < W && my_ts < k;
+    const int32_t my_freq = l_freq[lane];
     int rank = 0;
     for (int w = 0; w < W; w++) {
       const int32_t tw = l_ts[w];
-      if (tw < k && (tw < my_ts || (tw == my_ts && w < lane))) rank++;
+      if (tw >= k) continue;
+      bool first = tw < my_ts || (tw == my_ts && w < lane);
+      if (LFU) {
+        const int32_t fw = l_freq[w];
+        first = fw < my_freq || (fw == my_freq && first);
+      }
+      if (first) rank++;
     }
     const int n_cand = __popcll(__ballot(cand));
     if (cand) l_way[rank] = lane;
@@ -472,6 +491,7 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
           old_tag[u] = l_tag[way];
           l_tag[way] = (int32_t)((uniq_key[u] - key0) * m.sets + set);
           l_ts[way] = k;
+          l_freq[way] = run_off[u + 1] - run_off[u];
           loc_u[u] = slot0 + way;
           status[u] = ST_INSERT;
         } else {
@@ -485,6 +505,7 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
     if (lane < W) {
       tags[slot0 + lane] = l_tag[lane];
       ts[slot0 + lane] = l_ts[lane];
+      freq[slot0 + lane] = l_freq[lane];
     }
   }
 }
@@ -507,7 +528,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__
 
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
-                              hipStream_t s) {
+                              int32_t *freq, bool lfu, hipStream_t s) {
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
   DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
@@ -525,9 +546,12 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   int64_t max_touched = (int64_t)g.total_sets + g.T;
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
-  hipLaunchKernelGGL(probe_kernel, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key, b.uniq_tab,
-                     b.touched,
-                     tags, ts, b.loc_u, b.status, b.old_tag, b.cnt);
+  if (lfu)
+    hipLaunchKernelGGL(probe_kernel<true>, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key,
+                       b.uniq_tab, b.touched, tags, ts, freq, b.run_off, b.loc_u, b.status, b.old_tag, b.cnt);
+  else
+    hipLaunchKernelGGL(probe_kernel<false>, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key,
+                       b.uniq_tab, b.touched, tags, ts, freq, b.run_off, b.loc_u, b.status, b.old_tag, b.cnt);
   StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.uniq_tab, b.ins_idx, b.ins_tab, b.ins_slot,
               b.ins_old, b.ins_key, b.ins_src,
               b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u, 0u, 0u, 0ull};

@@ -171,7 +171,7 @@ hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf 
 hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *result_buf, hipStream_t s);
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
-                              hipStream_t s);
+                              int32_t *freq, bool lfu, hipStream_t s);
 // write back the staged victims and (b != null) fetch ahead the rows b's batch inserts
 hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t *rb_of_table,
                            unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);

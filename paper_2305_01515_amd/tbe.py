@@ -21,7 +21,9 @@ ERRORS = {0: "TBE_OK", -1: "TBE_EINVAL", -2: "TBE_ERANGE", -3: "TBE_EORDER", -4:
           -6: "TBE_EMISMATCH", -7: "TBE_EHIP"}
 EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "tbe_flush", "tbe_destroy",
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
-           "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready"]
+           "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
+           "tbe_set_policy", "tbe_export_cache_freq"]
+POLICIES = {"lru": 0, "lfu": 1}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
 
 
@@ -79,6 +81,8 @@ def lib() -> C.CDLL:
         l.tbe_host_free.argtypes = [vp]
         l.tbe_set_profiling.argtypes = [vp, i32]
         l.tbe_set_inputs_ready.argtypes = [vp, i32]
+        l.tbe_set_policy.argtypes = [vp, i32]
+        l.tbe_export_cache_freq.argtypes = [vp, i32, vp]
         l.tbe_get_stage_times.argtypes = [vp, i32, i64, vp]
         l.tbe_get_stage_times.restype = i64
         _lib = l
@@ -96,7 +100,7 @@ class TBE:
     read and written by the GPU."""
 
     def __init__(self, weights: Sequence[torch.Tensor], state: Sequence[torch.Tensor], cache_slots: Sequence[int],
-                 ways: int, max_batch: int, max_lookups: int, overlap: bool = True):
+                 ways: int, max_batch: int, max_lookups: int, overlap: bool = True, policy: str = "lru"):
         self._h = C.c_void_p()
         T = len(weights)
         self.T, self.ways = T, ways
@@ -119,6 +123,8 @@ class TBE:
         if rc:
             raise TbeError(rc, "tbe_create", lib().tbe_last_error(None).decode())
         self._keep: List[Tuple[torch.Tensor, ...]] = []
+        if policy != "lru":
+            self._check(lib().tbe_set_policy(self._h, POLICIES[policy]), "tbe_set_policy")
 
     def _check(self, rc: int, what: str):
         if rc:
@@ -200,6 +206,11 @@ class TBE:
         ts = np.empty(n, dtype=np.int32)
         self._check(lib().tbe_export_cache_state(self._h, t, tags.ctypes.data, ts.ctypes.data), "tbe_export_cache_state")
         return tags, ts
+
+    def cache_freq(self, t: int) -> np.ndarray:
+        f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)
+        self._check(lib().tbe_export_cache_freq(self._h, t, f.ctypes.data), "tbe_export_cache_freq")
+        return f
 
     def events(self, kind: str):
         """kind 'hit' / 'bypass': (table, row); 'insert': (table, row, slot, old)."""

@@ -2,7 +2,7 @@
 the same seeded inputs and compares them step by step.
 
 Bars (written here once, used by every parity test):
-  - cache state (tags, timestamps), per-batch counters and the hit / insert / bypass
+  - cache state (tags, timestamps, per-entry lookup counts), per-batch counters and the hit / insert / bypass
     event sets: bit-exact;
   - floating point, per vector v against the oracle's r (a pooled bag slice, an updated
     row):  max_d |v - r| <= tol * max(max_d |r|, floor), tol = 1e-5 for fp32 storage and
@@ -52,7 +52,8 @@ def gpu_snapshot(g, T: int):
     """counters, event sets and cache state of the library right after a prefetch"""
     return {"stats": g.stats()["last"],
             "events": {k: _canon(g.events(k)) for k in ("hit", "insert", "bypass")},
-            "state": [g.cache_state(t) for t in range(T)]}
+            "state": [g.cache_state(t) for t in range(T)],
+            "freq": [g.cache_freq(t) for t in range(T)]}
 
 
 def compare_cache_step(o: Oracle, snap, T: int, ctx: str):
@@ -66,6 +67,7 @@ def compare_cache_step(o: Oracle, snap, T: int, ctx: str):
         tg, tsg = snap["state"][t]
         assert np.array_equal(to, tg), f"{ctx}: tags of table {t} differ"
         assert np.array_equal(tso, tsg), f"{ctx}: timestamps of table {t} differ"
+        assert np.array_equal(o.cache_freq(t), snap["freq"][t]), f"{ctx}: lookup counts of table {t} differ"
 
 
 def compare_forward(cfg, out_o: np.ndarray, out_g: np.ndarray, ctx: str):
@@ -89,7 +91,7 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str):
 
 
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
-               oracle_threads: int = 8, max_lookups: int = None, init_device="cpu"):
+               oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru"):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -102,12 +104,12 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     T = cfg.num_tables
     Wn, Mn, Wp, Mp = make_backing(cfg, device=init_device)
     slots = [tc.cache_slots for tc in cfg.tables]
-    o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads)
+    o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads, policy=policy)
     stream = synth.BatchStream(cfg, device="cpu")
     batches = [stream.next() for _ in range(steps)]
     if max_lookups is None:
         max_lookups = max(int(b[0].numel()) for b in batches) + 1
-    g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, max_lookups, overlap=overlap)
+    g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, max_lookups, overlap=overlap, policy=policy)
     dev = [(i.to(device), f.to(device)) for i, f in batches]
     snaps = {}
 
@@ -160,6 +162,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         to, tso = o.cache_state(t)
         tg, tsg = g.cache_state(t)
         assert np.array_equal(to, tg) and np.array_equal(tso, tsg), f"final cache state of table {t} differs"
+        assert np.array_equal(o.cache_freq(t), g.cache_freq(t)), f"final lookup counts of table {t} differ"
     so, sg = o.stats()[1], g.stats()["total"]
     assert so == sg, f"total counters differ: oracle {so} gpu {sg}"
     o.flush()
