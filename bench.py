@@ -142,13 +142,16 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--tables", type=int, default=32, help="(debug) fewer tables than the named workload")
-    ap.add_argument("--workload", default="main", choices=["main", "tiny", "capacity", "locality"],
+    ap.add_argument("--workload", default="main", choices=["main", "tiny", "capacity", "locality", "hetero"],
                     help="main = the benchmark workload; the others are the parity configurations, for reference "
                          "measurements only (no CPU baseline)")
     ap.add_argument("--alpha", type=float, default=1.0, help="locality: Zipf exponent, 0 = uniform")
     ap.add_argument("--cache-frac", type=float, default=0.05, help="locality: cached fraction of the rows")
     ap.add_argument("--policy", default="lru", choices=["lru", "lfu"],
                     help="replacement policy; lru is the benchmark's, lfu for the comparison the paper makes")
+    ap.add_argument("--resident-fraction", type=float, default=-1.0,
+                    help="hetero: share of the HBM budget given to whole tables chosen by the placement solver "
+                         "(Eq. 6); negative = plain split in proportion to lookups x dim")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="run everything on one stream")
     args = ap.parse_args()
@@ -178,6 +181,22 @@ def main():
         desc = ("8 tables x 32M rows x dim 128 fp16 (64 GiB in pinned host memory; half of the capacity-bound "
                 "configuration's rows), 4 GiB 64-way cache, batch 65536, pooling Poisson(40), Zipf 1.05, 30% of each "
                 "batch re-drawn from the previous 4 batches")
+    elif args.workload == "hetero":
+        # 1/10 of the rows of the heterogeneous configuration (its 175 GB do not fit the pinned memory of
+        # the box), cache budget scaled alike; per-step shape unchanged
+        cfg = synth.config_hetero(max_rows=5e6, cache_bytes=(16 << 30) // 10)
+        probe = synth.BatchStream(cfg)
+        _, off = probe.next()
+        lk = [int(off[(t + 1) * cfg.batch] - off[t * cfg.batch]) for t in range(cfg.num_tables)]
+        if args.resident_fraction < 0:
+            synth.split_cache_budget(cfg, lk, cfg.cache_bytes)
+            how = "split in proportion to lookups x dim"
+        else:
+            res = synth.place_and_split_cache_budget(cfg, lk, cfg.cache_bytes, args.resident_fraction)
+            how = (f"{args.resident_fraction:.0%} of it for {len(res)} whole tables chosen by the placement solver, "
+                   "the rest split in proportion to lookups x dim")
+        desc = (f"100 tables, rows log-uniform in [1e4, 5e6] (1/10 of the heterogeneous configuration), dims 64/128/256 "
+                f"fp16, pooling means 1..100, Zipf 0.9..1.3, batch 16384, 64-way cache of 1.6 GiB, {how}")
     else:
         cfg = synth.config_locality(args.alpha if args.alpha > 0 else None, args.cache_frac)
         desc = (f"1 table x 100M rows x dim 64 fp16, batch 32768, pooling 32, "

@@ -253,6 +253,31 @@ const char *tbe_last_error(tbe_handle h);
 int tbe_host_alloc(void **h_ptr, size_t bytes);
 int tbe_host_free(void *h_ptr);
 
+/*
+ * Embedding table assignment (Section 5.6.1, Eq. 6), one GPU.  Host function: HOST pointers
+ * only, no handle, no GPU work.  Every table is assigned to exactly one memory type such
+ * that the tables of a memory type fit its capacity and
+ *     time = sum over tables t of traffic_t / bandwidth_{memory of t}
+ * is minimal.  traffic = D * L * p of Eq. 6 (bytes the table moves per step, any common
+ * unit), bytes = the table's size.  Exact (branch and bound) unless the search visits more
+ * than max_nodes nodes (<= 0: 5 million); then the best assignment found so far is returned
+ * and *h_optimal is 0.  Outputs: h_memory_of_table[num_tables] (index into mems), *h_time
+ * (Eq. 6 of that assignment), *h_optimal; the last two may be null.
+ * Errors: TBE_EINVAL (null pointer, no table or memory type, negative size or traffic,
+ * bandwidth not positive), TBE_ELIMIT (no assignment fits).
+ */
+typedef struct {
+  int64_t bytes;
+  double traffic;
+} tbe_place_table;
+typedef struct {
+  int64_t capacity_bytes;
+  double bandwidth;
+} tbe_place_memory;
+int tbe_plan_placement(const tbe_place_table *tables, int32_t num_tables, const tbe_place_memory *mems,
+                       int32_t num_mems, int64_t max_nodes, int32_t *h_memory_of_table, double *h_time,
+                       int32_t *h_optimal);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtbe.so")
-SOURCES = ["tbe_api.hip", "tbe_sort.hip", "tbe_cache.hip", "tbe_move.hip", "tbe_embed.hip"]
+SOURCES = ["tbe_api.hip", "tbe_sort.hip", "tbe_cache.hip", "tbe_move.hip", "tbe_embed.hip", "tbe_place.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -143,6 +143,33 @@ def split_cache_budget(cfg: WorkloadCfg, lookups_per_table: List[int], cache_byt
         cfg.tables[i].cache_slots = slots[i]
 
 
+def place_and_split_cache_budget(cfg: WorkloadCfg, lookups_per_table: List[int], cache_bytes: int,
+                                 resident_fraction: float, hbm_bandwidth: float = 4e12,
+                                 cached_bandwidth: float = 45e9) -> List[int]:
+    """Size- and bandwidth-aware placement (the paper's embedding table assignment, Section
+    5.6.1): `resident_fraction` of the HBM budget holds whole tables chosen by the library's
+    solver for Eq. 6 (memory types: HBM at `hbm_bandwidth`, the cached host tier at
+    `cached_bandwidth`; sizes = the tables' rows, traffic = lookups x row bytes) -- such a
+    table gets as many cache slots as rows, so it never misses after the first touch; the
+    rest of the budget is split over the other tables in proportion to lookups x dim.
+    Returns the indices of the resident tables."""
+    from . import placement
+    T = len(cfg.tables)
+    row_b = [t.dim * (4 if t.dtype == FP32 else 2) for t in cfg.tables]
+    full = [-(-t.rows // cfg.ways) * cfg.ways for t in cfg.tables]  # slots that hold every row: S * W >= H
+    size = [full[i] * row_b[i] for i in range(T)]
+    traffic = [float(lookups_per_table[i]) * row_b[i] for i in range(T)]
+    res = placement.plan(size, traffic, [int(cache_bytes * resident_fraction), sum(size)],
+                         [hbm_bandwidth, cached_bandwidth])
+    assert res is not None  # the cached tier holds everything
+    resident = [i for i in range(T) if res[0][i] == 0]
+    rest = [0 if i in resident else lookups_per_table[i] for i in range(T)]
+    split_cache_budget(cfg, rest, cache_bytes - sum(size[i] for i in resident))
+    for i in resident:
+        cfg.tables[i].cache_slots = full[i]
+    return resident
+
+
 def config_capacity(seed: int = 3, tables: int = 8, rows: int = 1 << 26, batch: int = 65536,
                     cache_bytes: int = 8 << 30, steps: int = 500) -> WorkloadCfg:
     """8 tables x 64M rows x dim 128 fp16 behind an 8 GiB cache (64-way), batch

@@ -23,6 +23,23 @@ def test_heterogeneous_model_scaled():
     assert st["total"]["hits"] > 0 and st["total"]["inserts"] > 0
 
 
+def test_heterogeneous_model_scaled_with_solver_placement():
+    """The same scaled model with half of the cache budget given to whole tables chosen by the
+    library's solver for Eq. 6 (Section 5.6.1): those tables have as many slots as rows, so
+    after the first touch they never miss, never evict and never bypass."""
+    cfg = synth.config_hetero(max_rows=5e5, batch=2048, cache_bytes=160 << 20)
+    probe = synth.BatchStream(cfg)
+    _, off = probe.next()
+    lookups = [int(off[(t + 1) * cfg.batch] - off[t * cfg.batch]) for t in range(cfg.num_tables)]
+    resident = synth.place_and_split_cache_budget(cfg, lookups, cfg.cache_bytes, 0.5)
+    assert 0 < len(resident) < cfg.num_tables
+    for t in resident:
+        assert cfg.tables[t].cache_slots >= cfg.tables[t].rows
+    assert sum(tc.cache_slots * tc.dim * 2 for tc in cfg.tables) <= cfg.cache_bytes
+    st = run_parity(cfg, steps=4, order="ahead", oracle_threads=16, init_device="cuda")
+    assert st["total"]["hits"] > 0 and st["total"]["inserts"] > 0
+
+
 def test_capacity_bound_scaled():
     """8 tables x dim 128 fp16, 64-way, Poisson(40), Zipf 1.05, 30 % of each batch re-drawn
     from the previous 4 batches; rows 2M per table instead of 64M (1/32), batch 8192
