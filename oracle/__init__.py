@@ -61,6 +61,7 @@ def lib():
         _lib.orc_export_cache_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         _lib.orc_export_cache_freq.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.orc_set_policy.argtypes = [C.c_void_p, C.c_int32]
+        _lib.orc_set_pooling.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_get_stats.argtypes = [C.c_void_p, C.POINTER(Stats), C.POINTER(Stats)]
         _lib.orc_events.restype = C.c_int64
         _lib.orc_events.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 4
@@ -83,7 +84,7 @@ class Oracle:
     float32 -- the backing tier, modified in place (C-contiguous, kept alive here)."""
 
     def __init__(self, weights: Sequence[np.ndarray], state: Sequence[np.ndarray], cache_slots: Sequence[int],
-                 ways: int, threads: int = 1, policy: str = "lru"):
+                 ways: int, threads: int = 1, policy: str = "lru", pooling: str = "sum"):
         self.weights = list(weights)
         self.state = list(state)
         self.ways = ways
@@ -105,6 +106,9 @@ class Oracle:
         rc = lib().orc_set_policy(self.h, {"lru": 0, "lfu": 1}[policy])
         if rc:
             raise OracleError(rc, "set_policy")
+        rc = lib().orc_set_pooling(self.h, {"sum": 0, "mean": 1}[pooling])
+        if rc:
+            raise OracleError(rc, "set_pooling")
         self.B = 0
 
     def close(self):

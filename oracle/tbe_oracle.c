@@ -31,6 +31,10 @@
  *   - row-wise Adagrad: m += mean_d(g_d^2); w_d -= lr * g_d / (sqrt(m) + eps), m starts
  *     wherever the caller's state array starts (0 in the tests), eps outside the root;
  *   - fp16 storage: rows are widened exactly, results are rounded to nearest even;
+ *   - mean pooling, the second pooling mode the paper names [Section 2.1.1]: the pooled
+ *     vector is the sum divided by the number of lookups of the bag (a row looked up twice
+ *     counts twice; an empty bag gives zeros), so a lookup of a bag of L lookups hands
+ *     1/L of the bag's output gradient to its row;
  *   - LFU, the other policy the paper tried [Section 5.5.2; it gives no details]: every
  *     entry also counts the lookups of its row since it was inserted (a row looked up c
  *     times in a batch adds c; the count saturates at INT32_MAX and is forgotten at
@@ -55,6 +59,9 @@
 #define ORC_ERANGE (-2)
 #define ORC_EORDER (-3)
 #define ORC_ENOMEM (-4)
+
+#define ORC_POOL_SUM 0
+#define ORC_POOL_MEAN 1
 
 #define ORC_LRU 0
 #define ORC_LFU 1
@@ -99,6 +106,7 @@ typedef struct {
 typedef struct {
   int32_t T, ways;
   int32_t policy;      /* ORC_LRU or ORC_LFU */
+  int32_t pooling;     /* ORC_POOL_SUM or ORC_POOL_MEAN */
   orc_table *tab;
   int32_t k;           /* batch id of the last prefetch */
   int32_t B;
@@ -203,6 +211,15 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
 }
 
 void orc_set_threads(void *hp, int n) { ((orc *)hp)->threads = n > 0 ? n : 1; }
+
+/* pooling mode; only before the first batch */
+int orc_set_pooling(void *hp, int32_t pooling) {
+  orc *h = (orc *)hp;
+  if (!h || (pooling != ORC_POOL_SUM && pooling != ORC_POOL_MEAN)) return ORC_EINVAL;
+  if (h->k != 0) return ORC_EORDER;
+  h->pooling = pooling;
+  return ORC_OK;
+}
 
 /* replacement policy; only before the first batch */
 int orc_set_policy(void *hp, int32_t policy) {
@@ -395,7 +412,9 @@ int orc_forward(void *hp, float *out) {
         int64_t base = (slot >= 0 ? slot : r) * tb->dim;
         for (int d = 0; d < tb->dim; d++) acc[d] += load_elem(src, tb->dtype, base + d);
       }
-      for (int d = 0; d < tb->dim; d++) out[(int64_t)b * sumD + col + d] = (float)acc[d];
+      int64_t L = h->offsets[(int64_t)t * h->B + b + 1] - h->offsets[(int64_t)t * h->B + b];
+      double div = (h->pooling == ORC_POOL_MEAN && L > 0) ? (double)L : 1.0;
+      for (int d = 0; d < tb->dim; d++) out[(int64_t)b * sumD + col + d] = (float)(acc[d] / div);
     }
     free(acc);
   }
@@ -410,7 +429,7 @@ static int64_t lower_bound(const int64_t *a, int64_t n, int64_t v) {
   return lo;
 }
 
-/* g_r = sum over lookups of r of grad_out[bag]; m_r += mean(g^2); w_r -= lr*g/(sqrt(m_r)+eps) */
+/* g_r = sum over lookups of r of grad_out[bag] (mean pooling: / lookups of the bag); m_r += mean(g^2); w_r -= lr*g/(sqrt(m_r)+eps) */
 int orc_backward_update(void *hp, const float *grad_out, float lr, float eps) {
   orc *h = (orc *)hp;
   if (!h || !grad_out) return ORC_EINVAL;
@@ -427,11 +446,14 @@ int orc_backward_update(void *hp, const float *grad_out, float lr, float eps) {
     if (U == 0) continue;
     double *g = (double *)calloc((size_t)U * (size_t)tb->dim, sizeof(double));
     if (!g) { failed = 1; continue; }
-    for (int32_t b = 0; b < h->B; b++)
+    for (int32_t b = 0; b < h->B; b++) {
+      int64_t L = h->offsets[(int64_t)t * h->B + b + 1] - h->offsets[(int64_t)t * h->B + b];
+      double div = h->pooling == ORC_POOL_MEAN ? (double)L : 1.0;
       for (int64_t j = h->offsets[(int64_t)t * h->B + b]; j < h->offsets[(int64_t)t * h->B + b + 1]; j++) {
         int64_t u = lower_bound(tb->uniq, U, h->indices[j]);
-        for (int d = 0; d < tb->dim; d++) g[u * tb->dim + d] += (double)grad_out[(int64_t)b * sumD + col + d];
+        for (int d = 0; d < tb->dim; d++) g[u * tb->dim + d] += (double)grad_out[(int64_t)b * sumD + col + d] / div;
       }
+    }
     for (int64_t u = 0; u < U; u++) {
       int64_t r = tb->uniq[u];
       int64_t slot = find_slot(tb, h->ways, r);
