@@ -149,6 +149,7 @@ def main():
     ap.add_argument("--cache-frac", type=float, default=0.05, help="locality: cached fraction of the rows")
     ap.add_argument("--policy", default="lru", choices=["lru", "lfu"],
                     help="replacement policy; lru is the benchmark's, lfu for the comparison the paper makes")
+    ap.add_argument("--pooling", default="sum", choices=["sum", "mean"], help="sum is the benchmark's")
     ap.add_argument("--resident-fraction", type=float, default=-1.0,
                     help="hetero: share of the HBM budget given to whole tables chosen by the placement solver "
                          "(Eq. 6); negative = plain split in proportion to lookups x dim")
@@ -203,7 +204,7 @@ def main():
                 f"{'uniform' if args.alpha <= 0 else 'Zipf %g' % args.alpha}, 64-way cache {args.cache_frac:.0%} of rows")
     if args.policy != "lru":
         desc = desc.replace("LRU ", "").replace("-way cache", "-way LFU cache")
-    if args.workload != "main" or args.policy != "lru":
+    if args.workload != "main" or args.policy != "lru" or args.pooling != "sum":
         args.no_cpu_baseline = True
     T = cfg.num_tables
 
@@ -236,7 +237,7 @@ def main():
                "sample": f"first batches of the same stream from a cold cache ({n} lookups), oracle -O2, OpenMP over tables"}
 
     g = TBE(Wp, Mp, [tc.cache_slots for tc in cfg.tables], cfg.ways, cfg.batch, max_n + 1, overlap=not args.no_overlap,
-            policy=args.policy)
+            policy=args.policy, pooling=args.pooling)
 
     def run(lo, hi):
         # next-batch prefetch is issued ahead of the current batch's training
@@ -314,7 +315,7 @@ def main():
         "dtype": "f16 storage / f32 accumulate" if cfg.tables[0].dtype == synth.FP16 else "f32", "data": "synthetic",
         "config": {"workload": desc,
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
-                   "overlap": not args.no_overlap, "policy": args.policy},
+                   "overlap": not args.no_overlap, "policy": args.policy, "pooling": args.pooling},
         # The HBM-bound kernel that moves most algorithmic bytes on the hit path.  Rows are counted once
         # per lookup (the paper's Eq. 3); repeats of hot rows are served by L2, so achieved can exceed what
         # HBM alone delivers -- `traffic` is what the counters saw.  ms_per_launch is measured in the timed,

@@ -139,6 +139,18 @@ int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offset
                  int64_t num_lookups);
 
 /*
+ * Pooling mode (Section 2.1.1 names sum, mean and max; sum and mean are built).
+ * TBE_POOL_SUM, the default.  TBE_POOL_MEAN: tbe_forward divides every pooled vector by the
+ * number of lookups of its bag (a row looked up twice counts twice; an empty bag gives
+ * zeros) and tbe_backward_update hands a lookup of a bag of L lookups 1/L of the bag's
+ * output gradient.  Only before the first tbe_prefetch (TBE_EORDER afterwards); TBE_EINVAL
+ * for an unknown mode.
+ */
+#define TBE_POOL_SUM 0
+#define TBE_POOL_MEAN 1
+int tbe_set_pooling(tbe_handle h, int32_t pooling);
+
+/*
  * Replacement policy (Section 5.5.2 names the two that were tried).  TBE_POLICY_LRU, the
  * default: the victim of a miss is the way with the smallest timestamp.  TBE_POLICY_LFU:
  * every entry counts the lookups of its row since it was inserted (a row looked up c times

@@ -47,6 +47,7 @@ struct tbe_ctx {
   DevAlloc mem;
   int32_t *tags = nullptr, *ts = nullptr, *freq = nullptr;
   int policy = TBE_POLICY_LRU;
+  int pooling = TBE_POOL_SUM;
   float *d_state = nullptr;   // row-wise Adagrad accumulators of all rows of all tables
   float *partials = nullptr;  // segment sums of the backward's longest rows
   char *lines = nullptr;
@@ -147,6 +148,7 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.loc, 4 * N));
   HIP_TRY(h, h->mem.get(&b.sorted_bag, 4 * N));
   HIP_TRY(h, h->mem.get(&b.bag_of_pos, 4 * N));
+  HIP_TRY(h, h->mem.get(&b.inv_len, 4 * (size_t)h->g.T * (size_t)h->max_batch));
   HIP_TRY(h, h->mem.get(&b.uid_sorted, 4 * N));
   HIP_TRY(h, h->mem.get(&b.uniq_key, 4 * N));
   HIP_TRY(h, h->mem.get(&b.run_off, 4 * (N + 1)));
@@ -225,6 +227,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
   BatchBuf &b = h->buf[bi];
   const bool in_flight = h->n_pend > 0 || h->current >= 0;
   b.d_indices = d_indices; b.d_offsets = d_offsets; b.batch = batch; b.n = n; b.k = ++h->k;
+  b.mean = h->pooling == TBE_POOL_MEAN;
   h->total_lookups += n;
   h->last_buf = bi;
   if (h->as != h->cs) {
@@ -584,6 +587,14 @@ int tbe_set_policy(tbe_handle h, int32_t policy) {
   if (policy != TBE_POLICY_LRU && policy != TBE_POLICY_LFU) return fail(h, TBE_EINVAL, "set_policy: unknown policy");
   if (h->k != 0) return fail(h, TBE_EORDER, "set_policy: batches have been prefetched already");
   h->policy = policy;
+  return TBE_OK;
+}
+
+int tbe_set_pooling(tbe_handle h, int32_t pooling) {
+  if (!h) return TBE_EINVAL;
+  if (pooling != TBE_POOL_SUM && pooling != TBE_POOL_MEAN) return fail(h, TBE_EINVAL, "set_pooling: unknown pooling mode");
+  if (h->k != 0) return fail(h, TBE_EORDER, "set_pooling: batches have been prefetched already");
+  h->pooling = pooling;
   return TBE_OK;
 }
 

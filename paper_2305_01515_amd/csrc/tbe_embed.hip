@@ -36,7 +36,8 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
                                                       const int64_t *__restrict__ offsets,
                                                       const uint32_t *__restrict__ loc,
                                                       const char *__restrict__ ovf, uint32_t ovf_stride,
-                                                      float *__restrict__ out, const BatchCounters *cnt) {
+                                                      const float *__restrict__ inv_len, float *__restrict__ out,
+                                                      const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int R = G < 4 ? G : 4;  // row loads in flight per lane
   if (cnt->err) return;
@@ -71,6 +72,11 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
 #pragma unroll
       for (int x = 0; x < R; x++) accumulate<DT>(acc, v[x]);
     }
+  }
+  if (inv_len) {  // mean pooling
+    const float sc = inv_len[(int64_t)t * B + b];
+#pragma unroll
+    for (int e = 0; e < EPL; e++) acc[e] *= sc;
   }
   if (active) {
     float *o = out + (size_t)b * sum_dim + m.col + lig * EPL;
@@ -145,19 +151,24 @@ __device__ inline RowRef locate(const TableMeta &m, uint32_t key, int slot, char
 // lanes: the bag ids are read G at a time (coalesced) and handed round by shuffles, four
 // gradient rows are in flight per lane.  `stride_chunks` > 1 lets several groups share a
 // range chunk-wise (group `first_chunk` of `stride_chunks`).  Summation order is fixed.
-template <int DT, int G>
+template <int DT, int G, bool MEAN>
 __device__ inline void reduce_grads(float (&g)[Elems<DT>::n], const float *gbase, const int32_t *sorted_bag, int bag0,
                                     int sum_dim, int i0, int i1, int first_chunk, int stride_chunks, int lig,
-                                    bool active) {
+                                    bool active, const float *inv_len) {
   constexpr int EPL = Elems<DT>::n;
   for (int base = i0 + first_chunk * G; base < i1; base += stride_chunks * G) {
     const int nq = (i1 - base) < G ? (i1 - base) : G;
-    const int my_bag = lig < nq ? sorted_bag[base + lig] - bag0 : 0;
+    const int my_gbag = lig < nq ? sorted_bag[base + lig] : bag0;
+    const int my_bag = my_gbag - bag0;
+    float my_w = 0.f;  // mean pooling: the weight 1/L of the lookup's bag
+    if (MEAN) my_w = lig < nq ? inv_len[my_gbag] : 0.f;
     for (int q = 0; q < nq; q += 4) {
       float4 v[4][EPL / 4];
+      float w[4];
 #pragma unroll
       for (int x = 0; x < 4; x++) {
         const int bq = __shfl(my_bag, (q + x) & (G - 1), G);
+        if (MEAN) w[x] = __shfl(my_w, (q + x) & (G - 1), G);
         const float *p = gbase + (size_t)bq * sum_dim;
         const bool ok = active && (q + x < nq);
 #pragma unroll
@@ -167,7 +178,12 @@ __device__ inline void reduce_grads(float (&g)[Elems<DT>::n], const float *gbase
       for (int x = 0; x < 4; x++)
 #pragma unroll
         for (int e = 0; e < EPL / 4; e++) {
-          g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
+          if (MEAN) {
+            g[4 * e] += v[x][e].x * w[x]; g[4 * e + 1] += v[x][e].y * w[x];
+            g[4 * e + 2] += v[x][e].z * w[x]; g[4 * e + 3] += v[x][e].w * w[x];
+          } else {
+            g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
+          }
         }
     }
   }
@@ -201,6 +217,7 @@ __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *_
                                                               const uint32_t *__restrict__ loc,
                                                               const float *__restrict__ grad_out, float lr, float eps,
                                                               char *__restrict__ ovf, uint32_t ovf_stride,
+                                                              const float *__restrict__ inv_len,
                                                               const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   if (cnt->err) return;
@@ -221,6 +238,11 @@ __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *_
 #pragma unroll
   for (int e = 0; e < EPL; e++) g[e] = 0.f;
   if (active) load_grad<DT>(g, grad_out + (size_t)b * sum_dim + m.col + lig * EPL);
+  if (inv_len) {  // mean pooling: every lookup of the bag receives 1/L of its gradient
+    const float sc = inv_len[(int64_t)t * B + b];
+#pragma unroll
+    for (int e = 0; e < EPL; e++) g[e] *= sc;
+  }
   float sq = 0.f;
 #pragma unroll
   for (int e = 0; e < EPL; e++) sq += g[e] * g[e];
@@ -271,7 +293,7 @@ __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *_
 
 // Rows with 2..kLongRun lookups: one group of G lanes per distinct row, gradients summed
 // in sorted (= ascending bag) order.
-template <int DT, int G>
+template <int DT, int G, bool MEAN>
 __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__restrict__ tm, int cls, int B,
                                                              int sum_dim, const int32_t *__restrict__ mid_idx,
                                                              const uint32_t *__restrict__ uniq_key,
@@ -282,6 +304,7 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
                                                              const float *__restrict__ grad_out, float lr, float eps,
                                                              char *__restrict__ ovf, uint32_t ovf_stride,
                                                              const int32_t *__restrict__ table_class,
+                                                             const float *__restrict__ inv_len,
                                                              const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   if (cnt->err) return;
@@ -299,14 +322,14 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, 0, 1, lig, active);
+    reduce_grads<DT, G, MEAN>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, 0, 1, lig, active, inv_len);
     update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
   }
 }
 
 // Rows with kLongRun < lookups <= kHugeRun: one workgroup per row, its 256/G groups take
 // chunks of G lookups round robin; the partial sums are added in group order through LDS.
-template <int DT, int G>
+template <int DT, int G, bool MEAN>
 __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__restrict__ tm, int cls, int B,
                                                             int sum_dim, const int32_t *__restrict__ items,
                                                             const uint32_t *__restrict__ uniq_key,
@@ -317,6 +340,7 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
                                                             const float *__restrict__ grad_out, float lr, float eps,
                                                             char *__restrict__ ovf, uint32_t ovf_stride,
                                                             const int32_t *__restrict__ table_class,
+                                                            const float *__restrict__ inv_len,
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int NG = 256 / G;
@@ -335,8 +359,8 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    reduce_grads<DT, G>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, run_off[u], run_off[u + 1], grp, NG,
-                        lig, active);
+    reduce_grads<DT, G, MEAN>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, run_off[u], run_off[u + 1], grp,
+                              NG, lig, active, inv_len);
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < EPL; e++) part[grp][lig * EPL + e] = g[e];
@@ -371,6 +395,7 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
                                                             const float *__restrict__ grad_out,
                                                             float *__restrict__ partials, int pstride,
                                                             const int32_t *__restrict__ table_class,
+                                                            const float *__restrict__ inv_len,
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int ROWF = G * EPL;                       // floats per staged gradient row
@@ -415,7 +440,13 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
           const int x = (k * 256 + threadIdx.x) * 4;
           const int bl = x / ROWF, c = x % ROWF;
           v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (x < n_f && c < dim) v[k] = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + m.col + c);
+          if (x < n_f && c < dim) {
+            v[k] = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + m.col + c);
+            if (inv_len) {  // mean pooling: the staged gradient row already carries the bag's 1/L
+              const float sc = inv_len[bag0 + b_first + bl];
+              v[k].x *= sc; v[k].y *= sc; v[k].z *= sc; v[k].w *= sc;
+            }
+          }
         }
 #pragma unroll
         for (int k = 0; k < PER; k++) *(float4 *)(tile + (k * 256 + threadIdx.x) * 4) = v[k];
@@ -516,7 +547,7 @@ static void fwd_one(const TableMeta *tm, const int32_t *tables, int count, const
   const int bags_per_block = 256 / G;
   dim3 grid((b.batch + bags_per_block - 1) / bags_per_block, count);
   hipLaunchKernelGGL((forward_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_offsets,
-                     b.loc, b.ovf, g.ovf_stride, out, b.cnt);
+                     b.loc, b.ovf, g.ovf_stride, b.mean ? b.inv_len : nullptr, out, b.cnt);
 }
 
 template <int DT, int G>
@@ -525,17 +556,19 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
   if (which == 2) {
     hipLaunchKernelGGL((backward_huge_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.hchunks,
                        b.huge_sorted, b.huge, b.hstart, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride, table_class,
-                       b.cnt);
+                       b.mean ? b.inv_len : nullptr, b.cnt);
     hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
                        b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   } else if (which == 0) {
-    hipLaunchKernelGGL((backward_long_kernel<DT, G>), dim3(8192), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items,
-                       b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride,
-                       table_class, b.cnt);
+    auto kern = b.mean ? backward_long_kernel<DT, G, true> : backward_long_kernel<DT, G, false>;
+    hipLaunchKernelGGL(kern, dim3(8192), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items, b.uniq_key, b.uniq_tab,
+                       b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class,
+                       b.mean ? b.inv_len : nullptr, b.cnt);
   } else {
-    hipLaunchKernelGGL((backward_short_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.mid_idx,
-                       b.uniq_key, b.uniq_tab, b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride,
-                       table_class, b.cnt);
+    auto kern = b.mean ? backward_short_kernel<DT, G, true> : backward_short_kernel<DT, G, false>;
+    hipLaunchKernelGGL(kern, dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.mid_idx, b.uniq_key, b.uniq_tab,
+                       b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class,
+                       b.mean ? b.inv_len : nullptr, b.cnt);
   }
 }
 
@@ -545,7 +578,7 @@ static void bwd_single_one(const TableMeta *tm, const int32_t *tables, int count
   const int bags_per_block = 256 / G;
   dim3 grid((b.batch + bags_per_block - 1) / bags_per_block, count);
   hipLaunchKernelGGL((backward_single_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_indices,
-                     b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.cnt);
+                     b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.mean ? b.inv_len : nullptr, b.cnt);
 }
 
 #define TBE_DISPATCH(DT, LANES, CALL)                         \

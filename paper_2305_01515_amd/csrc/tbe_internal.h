@@ -73,6 +73,8 @@ struct BatchBuf {
   uint32_t *loc;        // [N] location word of every lookup (kLoc* bits), input order
   int32_t *sorted_bag;  // [N] global bag id (t*B + b) of the i-th lookup in sorted order
   int32_t *bag_of_pos;  // [N] global bag id of lookup j (input order)
+  float *inv_len;       // [T * batch] mean pooling: 1 / lookups of the bag (0 for an empty bag)
+  bool mean;            // mean pooling instead of sum: forward and backward weigh by inv_len
   uint32_t *uid_sorted; // [N] index of the distinct row of the i-th sorted lookup
   // per distinct row (ascending key)
   uint32_t *uniq_key;   // [N]

@@ -14,7 +14,7 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
                                                      const int64_t *__restrict__ indices,
                                                      const int64_t *__restrict__ offsets, uint32_t *__restrict__ keys,
                                                      uint32_t *__restrict__ vals, int32_t *__restrict__ bag_of_pos,
-                                                     BatchCounters *cnt) {
+                                                     float *__restrict__ inv_len, BatchCounters *cnt) {
   const int64_t nb = (int64_t)T * B;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t bag = gid / kKeygenLanes;
@@ -28,6 +28,8 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
     if (sub == 0) atomicMax(&cnt->err, 1 /* -TBE_EINVAL */);
     return;
   }
+  // mean pooling (Section 2.1.1): a lookup of a bag of L lookups weighs 1/L
+  if (inv_len && sub == 0) inv_len[bag] = hi > lo ? 1.0f / (float)(hi - lo) : 0.0f;
   const int t = (int)(bag / B);
   const TableMeta m = tm[t];
   for (int64_t j = lo + sub; j < hi; j += kKeygenLanes) {
@@ -57,7 +59,7 @@ hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf 
   if (threads > 0) {
     const int64_t blocks = (threads + 255) / 256;
     hipLaunchKernelGGL(keygen_kernel, dim3((unsigned)blocks), dim3(256), 0, s, tm, g.T, b.batch, b.n, b.d_indices,
-                       b.d_offsets, keys, vals, b.bag_of_pos, b.cnt);
+                       b.d_offsets, keys, vals, b.bag_of_pos, b.mean ? b.inv_len : nullptr, b.cnt);
   }
   return hipGetLastError();
 }

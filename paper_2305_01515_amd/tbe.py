@@ -22,8 +22,9 @@ ERRORS = {0: "TBE_OK", -1: "TBE_EINVAL", -2: "TBE_ERANGE", -3: "TBE_EORDER", -4:
 EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "tbe_flush", "tbe_destroy",
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
-           "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement"]
+           "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling"]
 POLICIES = {"lru": 0, "lfu": 1}
+POOLINGS = {"sum": 0, "mean": 1}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
 
 
@@ -82,6 +83,7 @@ def lib() -> C.CDLL:
         l.tbe_set_profiling.argtypes = [vp, i32]
         l.tbe_set_inputs_ready.argtypes = [vp, i32]
         l.tbe_set_policy.argtypes = [vp, i32]
+        l.tbe_set_pooling.argtypes = [vp, i32]
         l.tbe_export_cache_freq.argtypes = [vp, i32, vp]
         l.tbe_get_stage_times.argtypes = [vp, i32, i64, vp]
         l.tbe_get_stage_times.restype = i64
@@ -100,7 +102,8 @@ class TBE:
     read and written by the GPU."""
 
     def __init__(self, weights: Sequence[torch.Tensor], state: Sequence[torch.Tensor], cache_slots: Sequence[int],
-                 ways: int, max_batch: int, max_lookups: int, overlap: bool = True, policy: str = "lru"):
+                 ways: int, max_batch: int, max_lookups: int, overlap: bool = True, policy: str = "lru",
+                 pooling: str = "sum"):
         self._h = C.c_void_p()
         T = len(weights)
         self.T, self.ways = T, ways
@@ -125,6 +128,8 @@ class TBE:
         self._keep: List[Tuple[torch.Tensor, ...]] = []
         if policy != "lru":
             self._check(lib().tbe_set_policy(self._h, POLICIES[policy]), "tbe_set_policy")
+        if pooling != "sum":
+            self._check(lib().tbe_set_pooling(self._h, POOLINGS[pooling]), "tbe_set_pooling")
 
     def _check(self, rc: int, what: str):
         if rc:

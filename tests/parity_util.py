@@ -91,7 +91,8 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str):
 
 
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
-               oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru"):
+               oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
+               pooling: str = "sum"):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -104,12 +105,12 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     T = cfg.num_tables
     Wn, Mn, Wp, Mp = make_backing(cfg, device=init_device)
     slots = [tc.cache_slots for tc in cfg.tables]
-    o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads, policy=policy)
+    o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads, policy=policy, pooling=pooling)
     stream = synth.BatchStream(cfg, device="cpu")
     batches = [stream.next() for _ in range(steps)]
     if max_lookups is None:
         max_lookups = max(int(b[0].numel()) for b in batches) + 1
-    g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, max_lookups, overlap=overlap, policy=policy)
+    g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, max_lookups, overlap=overlap, policy=policy, pooling=pooling)
     dev = [(i.to(device), f.to(device)) for i, f in batches]
     snaps = {}
 
