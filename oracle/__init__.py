@@ -62,6 +62,11 @@ def lib():
         _lib.orc_export_cache_freq.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.orc_set_policy.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_set_pooling.argtypes = [C.c_void_p, C.c_int32]
+        _lib.orc_set_second_level.argtypes = [C.c_void_p, C.c_void_p]
+        _lib.orc_num_sets2.restype = C.c_int64
+        _lib.orc_num_sets2.argtypes = [C.c_void_p, C.c_int32]
+        _lib.orc_export_second_level.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        _lib.orc_get_second_level_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.orc_get_stats.argtypes = [C.c_void_p, C.POINTER(Stats), C.POINTER(Stats)]
         _lib.orc_events.restype = C.c_int64
         _lib.orc_events.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 4
@@ -84,7 +89,8 @@ class Oracle:
     float32 -- the backing tier, modified in place (C-contiguous, kept alive here)."""
 
     def __init__(self, weights: Sequence[np.ndarray], state: Sequence[np.ndarray], cache_slots: Sequence[int],
-                 ways: int, threads: int = 1, policy: str = "lru", pooling: str = "sum"):
+                 ways: int, threads: int = 1, policy: str = "lru", pooling: str = "sum",
+                 second_level_slots: Optional[Sequence[int]] = None):
         self.weights = list(weights)
         self.state = list(state)
         self.ways = ways
@@ -109,6 +115,12 @@ class Oracle:
         rc = lib().orc_set_pooling(self.h, {"sum": 0, "mean": 1}[pooling])
         if rc:
             raise OracleError(rc, "set_pooling")
+        if second_level_slots is not None:
+            s2 = np.ascontiguousarray(second_level_slots, dtype=np.int64)
+            assert s2.shape == (T,)
+            rc = lib().orc_set_second_level(self.h, s2.ctypes.data)
+            if rc:
+                raise OracleError(rc, "set_second_level")
         self.B = 0
 
     def close(self):
@@ -162,6 +174,20 @@ class Oracle:
         ts = np.empty(n, dtype=np.int32)
         lib().orc_export_cache_state(self.h, t, tags.ctypes.data, ts.ctypes.data)
         return tags, ts
+
+    def second_level_state(self, t: int):
+        n = int(lib().orc_num_sets2(self.h, t)) * self.ways
+        tags = np.empty(n, dtype=np.int64)
+        ts = np.empty(n, dtype=np.int32)
+        lib().orc_export_second_level(self.h, t, tags.ctypes.data, ts.ctypes.data)
+        return tags, ts
+
+    def second_level_stats(self):
+        """(last batch, total), each {'hits', 'demotions', 'evictions', 'bypasses'}"""
+        last, total = np.zeros(4, dtype=np.int64), np.zeros(4, dtype=np.int64)
+        lib().orc_get_second_level_stats(self.h, last.ctypes.data, total.ctypes.data)
+        names = ("hits", "demotions", "evictions", "bypasses")
+        return dict(zip(names, last.tolist())), dict(zip(names, total.tolist()))
 
     def cache_freq(self, t: int) -> np.ndarray:
         f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)

@@ -31,6 +31,18 @@
  *   - row-wise Adagrad: m += mean_d(g_d^2); w_d -= lr * g_d / (sqrt(m) + eps), m starts
  *     wherever the caller's state array starts (0 in the tests), eps outside the root;
  *   - fp16 storage: rows are widened exactly, results are rounded to nearest even;
+ *   - two-level exclusive cache [Section 5.3, 5.5.4]: a second, larger set-associative cache
+ *     (set2(r) = r mod S2, same number of ways, timestamps of its own) sits between the first
+ *     level and the lower tier; a row lives in exactly one of the three places.  Per batch,
+ *     after the first level has decided: (A) every row the first level missed is looked up
+ *     in the second level -- found and inserted into the first level: it moves up and its
+ *     second-level entry becomes free; found but bypassed by the first level: it stays, is
+ *     used in place and is stamped k; not found: it comes from / stays in the lower tier --
+ *     then (B) the rows the first level evicted move down, in ascending row order, each into
+ *     the way of its second-level set with the smallest timestamp < k (free first, lowest
+ *     way among equals), stamped k; what that way held is written back to the lower tier;
+ *     with no such way the row goes to the lower tier directly.  The second level is
+ *     always LRU by the time a row entered it (or was last used in place);
  *   - mean pooling, the second pooling mode the paper names [Section 2.1.1]: the pooled
  *     vector is the sum divided by the number of lookups of the bag (a row looked up twice
  *     counts twice; an empty bag gives zeros), so a lookup of a bag of L lookups hands
@@ -90,6 +102,13 @@ typedef struct {
   int32_t *freq;    /* [sets*ways], lookups since insertion (kept under both policies, used by LFU) */
   void *lines;      /* [sets*ways, dim] in the storage type */
   float *line_state;/* [sets*ways] */
+  /* second level (absent when sets2 == 0) */
+  int64_t sets2;
+  int64_t *tag2;    /* [sets2*ways], -1 = free */
+  int32_t *ts2;     /* [sets2*ways], -1 = free */
+  void *lines2;
+  float *line_state2;
+  int64_t l2_hits, l2_demotions, l2_evictions, l2_bypasses; /* of the last batch */
   /* last prefetched batch */
   int64_t n_uniq;
   int64_t *uniq;    /* sorted distinct rows */
@@ -117,6 +136,7 @@ typedef struct {
   int forwarded, prefetched;
   int threads;
   orc_stats last, total;
+  int64_t l2_last[4], l2_total[4]; /* hits, demotions, evictions, bypasses of the second level */
 } orc;
 
 /* ---------------- fp16 <-> fp64 ---------------- */
@@ -171,6 +191,7 @@ static size_t esize(int dtype) { return dtype == 0 ? 4 : 2; }
 
 static void free_table(orc_table *t) {
   free(t->tag); free(t->ts); free(t->freq); free(t->lines); free(t->line_state);
+  free(t->tag2); free(t->ts2); free(t->lines2); free(t->line_state2);
   free(t->uniq); free(t->mult); free(t->hit_row); free(t->ins_row);
   free(t->ins_slot); free(t->ins_old); free(t->byp_row);
 }
@@ -212,6 +233,27 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
 
 void orc_set_threads(void *hp, int n) { ((orc *)hp)->threads = n > 0 ? n : 1; }
 
+/* second-level cache of slots2[t] entries per table (whole sets of `ways`); only before the first batch */
+int orc_set_second_level(void *hp, const int64_t *slots2) {
+  orc *h = (orc *)hp;
+  if (!h || !slots2) return ORC_EINVAL;
+  if (h->k != 0) return ORC_EORDER;
+  for (int t = 0; t < h->T; t++) {
+    orc_table *tb = &h->tab[t];
+    if (slots2[t] < 0 || tb->sets2) return ORC_EINVAL;
+    tb->sets2 = slots2[t] / h->ways;
+    int64_t n = tb->sets2 * h->ways;
+    if (n == 0) continue;
+    tb->tag2 = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+    tb->ts2 = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
+    tb->lines2 = calloc((size_t)n * (size_t)tb->dim, esize(tb->dtype));
+    tb->line_state2 = (float *)calloc((size_t)n, sizeof(float));
+    if (!tb->tag2 || !tb->ts2 || !tb->lines2 || !tb->line_state2) return ORC_ENOMEM;
+    for (int64_t i = 0; i < n; i++) { tb->tag2[i] = -1; tb->ts2[i] = -1; }
+  }
+  return ORC_OK;
+}
+
 /* pooling mode; only before the first batch */
 int orc_set_pooling(void *hp, int32_t pooling) {
   orc *h = (orc *)hp;
@@ -239,6 +281,30 @@ static int64_t find_slot(const orc_table *tb, int ways, int64_t r) {
   for (int w = 0; w < ways; w++)
     if (tb->tag[s * ways + w] == r) return s * ways + w;
   return -1;
+}
+
+/* slot of row r in table tb's second-level cache, or -1 */
+static int64_t find_slot2(const orc_table *tb, int ways, int64_t r) {
+  if (tb->sets2 == 0) return -1;
+  int64_t s = r % tb->sets2;
+  for (int w = 0; w < ways; w++)
+    if (tb->tag2[s * ways + w] == r) return s * ways + w;
+  return -1;
+}
+
+/* where row r lives: first-level line, second-level line or lower tier */
+static void locate_row(orc_table *tb, int ways, int64_t r, void **base, int64_t *index, float **state) {
+  int64_t slot = find_slot(tb, ways, r);
+  if (slot >= 0) { *base = tb->lines; *index = slot; *state = &tb->line_state[slot]; return; }
+  slot = find_slot2(tb, ways, r);
+  if (slot >= 0) { *base = tb->lines2; *index = slot; *state = &tb->line_state2[slot]; return; }
+  *base = tb->weights; *index = r; *state = &tb->state[r];
+}
+
+static void line2_to_backing(orc_table *tb, int64_t slot2, int64_t r) {
+  size_t rb = (size_t)tb->dim * esize(tb->dtype);
+  memcpy((char *)tb->weights + (size_t)r * rb, (char *)tb->lines2 + (size_t)slot2 * rb, rb);
+  tb->state[r] = tb->line_state2[slot2];
 }
 
 static void line_to_backing(orc_table *tb, int64_t slot, int64_t r) {
@@ -272,6 +338,77 @@ static int grow(orc_table *tb, int64_t n) {
     *ptrs[i] = p;
   }
   tb->cap = c;
+  return 0;
+}
+
+typedef struct { int64_t row, slot; } orc_victim;
+static int cmp_victim(const void *a, const void *b) {
+  int64_t x = ((const orc_victim *)a)->row, y = ((const orc_victim *)b)->row;
+  return x < y ? -1 : x > y;
+}
+
+/* Second level, after the first level has taken its decisions for batch k (its tags are
+ * already those of the new rows, the lines still hold the victims' data). */
+static int second_level(orc *h, orc_table *tb) {
+  const int W = h->ways;
+  const int32_t k = h->k;
+  const size_t rb = (size_t)tb->dim * esize(tb->dtype);
+  tb->l2_hits = tb->l2_demotions = tb->l2_evictions = tb->l2_bypasses = 0;
+  /* the victims' data leave their first-level lines */
+  int64_t nv = 0;
+  orc_victim *vic = (orc_victim *)malloc(sizeof(orc_victim) * (size_t)(tb->n_ins + 1));
+  char *vdata = (char *)malloc(rb * (size_t)(tb->n_ins + 1));
+  float *vstate = (float *)malloc(sizeof(float) * (size_t)(tb->n_ins + 1));
+  if (!vic || !vdata || !vstate) { free(vic); free(vdata); free(vstate); return ORC_ENOMEM; }
+  for (int64_t i = 0; i < tb->n_ins; i++) {
+    if (tb->ins_old[i] < 0) continue;
+    vic[nv].row = tb->ins_old[i]; vic[nv].slot = nv;
+    memcpy(vdata + (size_t)nv * rb, (char *)tb->lines + (size_t)tb->ins_slot[i] * rb, rb);
+    vstate[nv] = tb->line_state[tb->ins_slot[i]];
+    nv++;
+  }
+  /* (A) the rows the first level missed, ascending: inserted ones ... */
+  for (int64_t i = 0; i < tb->n_ins; i++) {
+    int64_t r = tb->ins_row[i], slot = tb->ins_slot[i];
+    int64_t s2 = find_slot2(tb, W, r);
+    if (s2 >= 0) { /* found: moves up, its second-level entry becomes free */
+      memcpy((char *)tb->lines + (size_t)slot * rb, (char *)tb->lines2 + (size_t)s2 * rb, rb);
+      tb->line_state[slot] = tb->line_state2[s2];
+      tb->tag2[s2] = -1; tb->ts2[s2] = -1;
+      tb->l2_hits++;
+    } else {
+      backing_to_line(tb, slot, r);
+    }
+  }
+  /* ... and bypassed ones: used in place */
+  for (int64_t j = 0; j < tb->n_byp; j++) {
+    int64_t s2 = find_slot2(tb, W, tb->byp_row[j]);
+    if (s2 >= 0) { tb->ts2[s2] = k; tb->l2_hits++; }
+  }
+  /* (B) the evicted rows move down in ascending row order */
+  qsort(vic, (size_t)nv, sizeof(orc_victim), cmp_victim);
+  for (int64_t v = 0; v < nv; v++) {
+    int64_t r = vic[v].row, src = vic[v].slot;
+    int64_t s = r % tb->sets2;
+    int way = -1;
+    for (int w = 0; w < W; w++) {
+      int32_t tw = tb->ts2[s * W + w];
+      if (tw < k && (way < 0 || tw < tb->ts2[s * W + way])) way = w;
+    }
+    if (way < 0) { /* every way was stamped by this batch: straight to the lower tier */
+      memcpy((char *)tb->weights + (size_t)r * rb, vdata + (size_t)src * rb, rb);
+      tb->state[r] = vstate[src];
+      tb->l2_bypasses++;
+      continue;
+    }
+    int64_t s2 = s * W + way;
+    if (tb->tag2[s2] >= 0) { line2_to_backing(tb, s2, tb->tag2[s2]); tb->l2_evictions++; }
+    memcpy((char *)tb->lines2 + (size_t)s2 * rb, vdata + (size_t)src * rb, rb);
+    tb->line_state2[s2] = vstate[src];
+    tb->tag2[s2] = r; tb->ts2[s2] = k;
+    tb->l2_demotions++;
+  }
+  free(vic); free(vdata); free(vstate);
   return 0;
 }
 
@@ -337,8 +474,11 @@ static int prefetch_table(orc *h, int t) {
     }
     int64_t slot = s * W + victim;
     int64_t old = tb->tag[slot];
-    if (old >= 0) { line_to_backing(tb, slot, old); tb->st.evictions++; }
-    backing_to_line(tb, slot, r);
+    if (old >= 0) tb->st.evictions++;
+    if (tb->sets2 == 0) { /* one level: the victim goes to the lower tier, the row comes from it */
+      if (old >= 0) line_to_backing(tb, slot, old);
+      backing_to_line(tb, slot, r);
+    }
     tb->tag[slot] = r;
     tb->ts[slot] = k;
     tb->freq[slot] = add_saturating(0, tb->mult[i]);
@@ -347,6 +487,7 @@ static int prefetch_table(orc *h, int t) {
     tb->st.inserts++;
   }
   free(is_hit);
+  if (tb->sets2 > 0) return second_level(h, tb);
   return 0;
 }
 
@@ -384,6 +525,14 @@ int orc_prefetch(void *hp, const int64_t *indices, const int64_t *offsets, int32
   memset(&h->last, 0, sizeof(h->last));
   for (int t = 0; t < h->T; t++) add_stats(&h->last, &h->tab[t].st);
   add_stats(&h->total, &h->last);
+  memset(h->l2_last, 0, sizeof(h->l2_last));
+  for (int t = 0; t < h->T; t++) {
+    orc_table *tb = &h->tab[t];
+    if (tb->sets2 == 0) continue;
+    h->l2_last[0] += tb->l2_hits; h->l2_last[1] += tb->l2_demotions;
+    h->l2_last[2] += tb->l2_evictions; h->l2_last[3] += tb->l2_bypasses;
+  }
+  for (int i = 0; i < 4; i++) h->l2_total[i] += h->l2_last[i];
   h->prefetched = 1; h->forwarded = 0;
   return ORC_OK;
 }
@@ -406,10 +555,9 @@ int orc_forward(void *hp, float *out) {
     for (int32_t b = 0; b < h->B; b++) {
       for (int d = 0; d < tb->dim; d++) acc[d] = 0.0;
       for (int64_t j = h->offsets[(int64_t)t * h->B + b]; j < h->offsets[(int64_t)t * h->B + b + 1]; j++) {
-        int64_t r = h->indices[j];
-        int64_t slot = find_slot(tb, h->ways, r);
-        const void *src = slot >= 0 ? tb->lines : tb->weights;
-        int64_t base = (slot >= 0 ? slot : r) * tb->dim;
+        void *src; int64_t at; float *st_unused;
+        locate_row(tb, h->ways, h->indices[j], &src, &at, &st_unused);
+        int64_t base = at * tb->dim;
         for (int d = 0; d < tb->dim; d++) acc[d] += load_elem(src, tb->dtype, base + d);
       }
       int64_t L = h->offsets[(int64_t)t * h->B + b + 1] - h->offsets[(int64_t)t * h->B + b];
@@ -455,11 +603,9 @@ int orc_backward_update(void *hp, const float *grad_out, float lr, float eps) {
       }
     }
     for (int64_t u = 0; u < U; u++) {
-      int64_t r = tb->uniq[u];
-      int64_t slot = find_slot(tb, h->ways, r);
-      void *wbase = slot >= 0 ? tb->lines : tb->weights;
-      float *mptr = slot >= 0 ? &tb->line_state[slot] : &tb->state[r];
-      int64_t base = (slot >= 0 ? slot : r) * tb->dim;
+      void *wbase; int64_t at; float *mptr;
+      locate_row(tb, h->ways, tb->uniq[u], &wbase, &at, &mptr);
+      int64_t base = at * tb->dim;
       double sq = 0.0;
       for (int d = 0; d < tb->dim; d++) sq += g[u * tb->dim + d] * g[u * tb->dim + d];
       double m = (double)*mptr + sq / (double)tb->dim;
@@ -485,6 +631,8 @@ int orc_flush(void *hp) {
     orc_table *tb = &h->tab[t];
     for (int64_t s = 0; s < tb->sets * h->ways; s++)
       if (tb->tag[s] >= 0) line_to_backing(tb, s, tb->tag[s]);
+    for (int64_t s = 0; s < tb->sets2 * h->ways; s++)
+      if (tb->tag2[s] >= 0) line2_to_backing(tb, s, tb->tag2[s]);
   }
   return ORC_OK;
 }
@@ -492,6 +640,25 @@ int orc_flush(void *hp) {
 /* ---------------- observation ---------------- */
 
 int64_t orc_num_sets(void *hp, int32_t t) { return ((orc *)hp)->tab[t].sets; }
+int64_t orc_num_sets2(void *hp, int32_t t) { return ((orc *)hp)->tab[t].sets2; }
+
+int orc_export_second_level(void *hp, int32_t t, int64_t *tags, int32_t *ts) {
+  orc *h = (orc *)hp;
+  if (!h || t < 0 || t >= h->T) return ORC_EINVAL;
+  orc_table *tb = &h->tab[t];
+  int64_t n = tb->sets2 * h->ways;
+  if (n) { memcpy(tags, tb->tag2, sizeof(int64_t) * (size_t)n); memcpy(ts, tb->ts2, sizeof(int32_t) * (size_t)n); }
+  return ORC_OK;
+}
+
+/* second-level counters: hits, demotions, evictions, bypasses -- of the last batch and in total */
+int orc_get_second_level_stats(void *hp, int64_t *last4, int64_t *total4) {
+  orc *h = (orc *)hp;
+  if (!h) return ORC_EINVAL;
+  if (last4) memcpy(last4, h->l2_last, sizeof(h->l2_last));
+  if (total4) memcpy(total4, h->l2_total, sizeof(h->l2_total));
+  return ORC_OK;
+}
 int32_t orc_batch_id(void *hp) { return ((orc *)hp)->k; }
 
 int orc_export_cache_state(void *hp, int32_t t, int64_t *tags, int32_t *ts) {
@@ -546,10 +713,9 @@ int orc_read_row(void *hp, int32_t t, int64_t r, double *w, float *m) {
   orc *h = (orc *)hp;
   if (!h || t < 0 || t >= h->T || r < 0 || r >= h->tab[t].rows) return ORC_EINVAL;
   orc_table *tb = &h->tab[t];
-  int64_t slot = find_slot(tb, h->ways, r);
-  const void *src = slot >= 0 ? tb->lines : tb->weights;
-  int64_t base = (slot >= 0 ? slot : r) * tb->dim;
-  for (int d = 0; d < tb->dim; d++) w[d] = load_elem(src, tb->dtype, base + d);
-  *m = slot >= 0 ? tb->line_state[slot] : tb->state[r];
+  void *src; int64_t at; float *st;
+  locate_row(tb, h->ways, r, &src, &at, &st);
+  for (int d = 0; d < tb->dim; d++) w[d] = load_elem(src, tb->dtype, at * tb->dim + d);
+  *m = *st;
   return ORC_OK;
 }
