@@ -39,10 +39,13 @@
  *     second-level entry becomes free; found but bypassed by the first level: it stays, is
  *     used in place and is stamped k; not found: it comes from / stays in the lower tier --
  *     then (B) the rows the first level evicted move down, in ascending row order, each into
- *     the way of its second-level set with the smallest timestamp < k (free first, lowest
+ *     the way of its second-level set with the smallest timestamp < k - 1 (free first, lowest
  *     way among equals), stamped k; what that way held is written back to the lower tier;
- *     with no such way the row goes to the lower tier directly.  The second level is
- *     always LRU by the time a row entered it (or was last used in place);
+ *     with no such way the row goes to the lower tier directly.  An entry stamped by this
+ *     batch or the one before is thus never replaced: its data may still be on its way
+ *     (the paper's pipelining rule, Section 5.7, applied to the second level, whose moves
+ *     trail the decisions by a batch).  The second level is always LRU by the time a row
+ *     entered it (or was last used in place);
  *   - mean pooling, the second pooling mode the paper names [Section 2.1.1]: the pooled
  *     vector is the sum divided by the number of lookups of the bag (a row looked up twice
  *     counts twice; an empty bag gives zeros), so a lookup of a bag of L lookups hands
@@ -393,9 +396,9 @@ static int second_level(orc *h, orc_table *tb) {
     int way = -1;
     for (int w = 0; w < W; w++) {
       int32_t tw = tb->ts2[s * W + w];
-      if (tw < k && (way < 0 || tw < tb->ts2[s * W + way])) way = w;
+      if (tw < k - 1 && (way < 0 || tw < tb->ts2[s * W + way])) way = w;
     }
-    if (way < 0) { /* every way was stamped by this batch: straight to the lower tier */
+    if (way < 0) { /* every way was stamped by this batch or the one before: straight to the lower tier */
       memcpy((char *)tb->weights + (size_t)r * rb, vdata + (size_t)src * rb, rb);
       tb->state[r] = vstate[src];
       tb->l2_bypasses++;

@@ -50,8 +50,9 @@ class TwoLevelModel:
         self.l2 = [dict() for _ in range(s2)]
 
     @staticmethod
-    def _victim_way(entries, ways, k):
-        cand = [(entries[w][1] if w in entries else -1, w) for w in range(ways) if w not in entries or entries[w][1] < k]
+    def _victim_way(entries, ways, before):
+        """way whose entry is free or stamped earlier than `before`: oldest first, lowest way among equals"""
+        cand = [(entries[w][1] if w in entries else -1, w) for w in range(ways) if w not in entries or entries[w][1] < before]
         return min(cand)[1] if cand else None
 
     def batch(self, rows, k):
@@ -89,7 +90,7 @@ class TwoLevelModel:
         ev2 = byp2 = 0
         for v in sorted(victims):
             ent = self.l2[v % self.s2]
-            w = self._victim_way(ent, self.w, k)
+            w = self._victim_way(ent, self.w, k - 1)  # entries of this batch and the one before stay
             if w is None:
                 byp2 += 1
                 continue
@@ -148,8 +149,10 @@ def test_hand_worked_example():
     o.prefetch(np.array([3, 6, 7]), np.array([0, 3]))       # k=6: 3 (L2 hit, moves up), 6 inserted, 7 bypasses
     assert o.cache_state(0)[0].tolist() == [3, 6]
     assert o.events("bypass")[1].tolist() == [7]
-    # victims 1 and 5 move down: row 3's way is free (-1), then the oldest (row 4, ts 5)
-    assert contents(o.second_level_state(0)[0]) == {1, 5}
+    # victims 1 and 5 move down in that order: row 1 takes the way row 3 left; row 4 entered at k=5, the batch
+    # before, so its way stays and row 5 goes straight to the lower tier
+    assert o.second_level_state(0)[0].tolist() == [1, 4] and o.second_level_state(0)[1].tolist() == [6, 5]
+    assert o.second_level_stats()[0] == {"hits": 1, "demotions": 1, "evictions": 0, "bypasses": 1}
 
 
 def uncached_reference(rows, dims, dt, steps, seed):
