@@ -139,6 +139,38 @@ int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offset
                  int64_t num_lookups);
 
 /*
+ * Second-level cache (Section 5.3, 5.5.4: two-level exclusive hierarchy).  Adds, between the
+ * cache in HBM and the backing tier, a second set-associative LRU cache whose lines the
+ * library allocates in pinned host memory: per table factor * S_t sets of `ways` entries,
+ * set2(r) = r mod (factor * S_t); tags and timestamps in HBM.  A row lives in exactly one of
+ * the three places.  Per batch, after the first level has decided:
+ *   (A) every row the first level missed is looked up in the second level: found and inserted
+ *       into the first level -> it moves up and its second-level entry becomes free; found but
+ *       bypassed by the first level -> it stays, is used in place and is stamped k; not found
+ *       -> it comes from / stays in the backing tier;
+ *   (B) the rows the first level evicted move down in ascending row order, each into the way
+ *       of its second-level set with the smallest timestamp < k - 1 (free first, lowest way
+ *       among equals), stamped k; what that way held is written to the backing tier; with no
+ *       such way the row goes to the backing tier directly.  Entries stamped by the current
+ *       batch or the one before are never replaced (their data may still be in flight).
+ * tbe_flush also writes every valid second-level line to the backing tier.  Values do not
+ * depend on the hierarchy.  Only before the first tbe_prefetch (TBE_EORDER afterwards or when
+ * called twice); allocates (TBE_ENOMEM / TBE_EHIP if that fails); TBE_EINVAL for a factor
+ * outside 1..1024 or when no table has a first-level cache; TBE_ELIMIT when 2^31 slots or
+ * 2^29 possible inserts per batch are exceeded.
+ */
+int tbe_enable_second_level(tbe_handle h, int32_t factor);
+/* Sets of a table's second-level cache (0 without one). */
+int64_t tbe_num_sets2(tbe_handle h, int32_t table);
+/* Copy a table's second-level tags and timestamps to HOST arrays of tbe_num_sets2 * ways
+ * entries, index set * ways + way.  Synchronises. */
+int tbe_export_second_level_state(tbe_handle h, int32_t table, int64_t *h_tags, int32_t *h_ts);
+/* Second-level counters of the last prefetched batch and in total, HOST int64[4] each: rows
+ * found there, victims moved down into it, rows it evicted to the backing tier, victims
+ * that found no way and went to the backing tier directly.  Synchronises. */
+int tbe_get_second_level_stats(tbe_handle h, int64_t *h_last4, int64_t *h_total4);
+
+/*
  * Pooling mode (Section 2.1.1 names sum, mean and max; sum and mean are built).
  * TBE_POOL_SUM, the default.  TBE_POOL_MEAN: tbe_forward divides every pooled vector by the
  * number of lookups of its bag (a row looked up twice counts twice; an empty bag gives

@@ -48,6 +48,9 @@ struct tbe_ctx {
   int32_t *tags = nullptr, *ts = nullptr, *freq = nullptr;
   int policy = TBE_POLICY_LRU;
   int pooling = TBE_POOL_SUM;
+  Level2 l2;                    // second-level cache (off unless tbe_enable_second_level was called)
+  char *lines2 = nullptr;       // its lines: one pinned host allocation
+  unsigned long long *d_l2tot = nullptr;  // running totals of the four second-level counters
   float *d_state = nullptr;   // row-wise Adagrad accumulators of all rows of all tables
   float *partials = nullptr;  // segment sums of the backward's longest rows
   char *lines = nullptr;
@@ -134,6 +137,15 @@ __global__ void add_totals_kernel(const BatchCounters *c, BatchCounters *tot) {
   }
 }
 
+__global__ void add_l2_totals_kernel(const BatchCounters *c, unsigned long long *t) {
+  if (threadIdx.x == 0 && c->err == 0) {
+    t[0] += (unsigned long long)c->l2_hits;
+    t[1] += (unsigned long long)c->l2_demotions;
+    t[2] += (unsigned long long)c->l2_evictions;
+    t[3] += (unsigned long long)c->l2_bypasses;
+  }
+}
+
 // 64-bit totals: [0] uniques [1] inserts [2] bypasses
 __global__ void add_totals64_kernel(const BatchCounters *c, unsigned long long *t64) {
   if (threadIdx.x == 0 && c->err == 0) {
@@ -212,7 +224,7 @@ int enqueue_commit(tbe_ctx *h, int bi, bool wb_prev) {
   BatchBuf &b = h->buf[bi];
   {
     StageTimer tm_(h, TBE_STAGE_COMMIT, h->ls);
-    HIP_TRY(h, launch_commit(h->d_tm, b, b.prev_bi >= 0 ? &h->buf[b.prev_bi] : nullptr, wb_prev, h->st, h->d_rb,
+    HIP_TRY(h, launch_commit(h->d_tm, b, b.prev_bi >= 0 ? &h->buf[b.prev_bi] : nullptr, wb_prev, h->st, h->l2, h->d_rb,
                              h->d_bytes + 1, h->ls));
   }
   HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->ls));
@@ -246,13 +258,14 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     int res = 0;
     HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
     HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->freq,
-                                  h->policy == TBE_POLICY_LFU, h->as));
+                                  h->policy == TBE_POLICY_LFU, h->l2, h->as));
     // which of the rows to insert have a backing-tier copy that is still being written
     // (by the write-back of the previous batch's victims or by its backward), then move
     // the marks on from the previous batch to this one
-    HIP_TRY(h, launch_classify_mark(h->d_tm, h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr, b, h->st, h->d_bytes + 5, h->as));
+    HIP_TRY(h, launch_classify_mark(h->d_tm, h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr, b, h->st, h->l2, h->d_bytes + 5, h->as));
     hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total);
     hipLaunchKernelGGL(add_totals64_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_bytes + 2);
+    if (h->l2.on) hipLaunchKernelGGL(add_l2_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_l2tot);
     HIP_TRY(h, hipGetLastError());
   }
   if (h->ls != h->as) {
@@ -264,7 +277,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     // the host link; neither touches a cache line, so a batch in flight is not disturbed,
     // and the link stream lets the next batch's sort and probe run meanwhile
     StageTimer tm_(h, TBE_STAGE_FILL, h->ls);
-    HIP_TRY(h, launch_transfer(&b, h->st, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
+    HIP_TRY(h, launch_transfer(&b, h->st, h->l2, b.k, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
   }
   b.prev_bi = h->prev_buf;
   h->prev_buf = bi;
@@ -298,6 +311,7 @@ int tbe_destroy(tbe_handle h) {
   (void)hipStreamSynchronize(h->cs);
   if (h->own_ls) (void)hipStreamDestroy(h->ls);
   h->mem.release();
+  if (h->lines2) (void)hipHostFree(h->lines2);
   drop_profile(h);
   if (h->ev_inputs) (void)hipEventDestroy(h->ev_inputs);
   for (int i = 0; i < kBatchBufs; i++) {
@@ -571,8 +585,8 @@ int tbe_flush(tbe_handle h) {
   if (h->n_pend > 0 || h->current >= 0) return fail(h, TBE_EORDER, "flush: a batch is still in flight");
   int rc = sync_all(h);
   if (rc) return rc;
-  HIP_TRY(h, launch_transfer(nullptr, h->st, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
-  HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->d_bytes + 1, h->cs));
+  HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
+  HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->l2, h->d_bytes, h->d_bytes + 1, h->cs));
   for (const TableMeta &m : h->tm) {
     HIP_TRY(h, hipMemcpyAsync(m.host_m, m.dev_m, 4 * (size_t)m.rows, hipMemcpyDeviceToHost, h->cs));
     h->flush_state_bytes += 4 * m.rows;
@@ -588,6 +602,100 @@ int tbe_set_policy(tbe_handle h, int32_t policy) {
   if (h->k != 0) return fail(h, TBE_EORDER, "set_policy: batches have been prefetched already");
   h->policy = policy;
   return TBE_OK;
+}
+
+int tbe_enable_second_level(tbe_handle h, int32_t factor) {
+  if (!h) return TBE_EINVAL;
+  if (factor < 1 || factor > 1024) return fail(h, TBE_EINVAL, "enable_second_level: factor must be 1..1024");
+  if (h->k != 0) return fail(h, TBE_EORDER, "enable_second_level: batches have been prefetched already");
+  if (h->l2.on) return fail(h, TBE_EORDER, "enable_second_level: already enabled");
+  if (h->st.max_inserts >= (1ll << 29)) return fail(h, TBE_ELIMIT, "enable_second_level: too many possible inserts per batch");
+  int64_t slots2 = 0;
+  size_t bytes2 = 0;
+  for (TableMeta &m : h->tm) {
+    if ((int64_t)m.sets * factor * h->g.ways + slots2 >= (1ll << 31)) return fail(h, TBE_ELIMIT, "enable_second_level: too many second-level slots");
+    slots2 += (int64_t)m.sets * factor * h->g.ways;
+    bytes2 += (size_t)m.sets * factor * h->g.ways * m.row_bytes;
+  }
+  if (slots2 == 0) return fail(h, TBE_EINVAL, "enable_second_level: no table has a first-level cache");
+  HIP_TRY(h, hipHostMalloc((void **)&h->lines2, bytes2, hipHostMallocDefault));
+  Level2 &l2 = h->l2;
+  const size_t M = (size_t)h->st.max_inserts;
+  HIP_TRY(h, h->mem.get(&l2.tags2, 4 * (size_t)slots2));
+  HIP_TRY(h, h->mem.get(&l2.ts2, 4 * (size_t)slots2));
+  HIP_TRY(h, hipMemset(l2.tags2, 0xFF, 4 * (size_t)slots2));
+  HIP_TRY(h, hipMemset(l2.ts2, 0xFF, 4 * (size_t)slots2));
+  for (int p2 = 0; p2 < 2; p2++) {
+    HIP_TRY(h, h->mem.get(&l2.out2[p2], M * h->st.stride));
+    // the skip flags of the staged second-level victims follow those of the first-level ones
+    HIP_TRY(h, h->mem.get(&h->st.wb_skip[p2], 2 * M));
+    HIP_TRY(h, hipMemset(h->st.wb_skip[p2], 0, 2 * M ? 2 * M : 1));
+  }
+  HIP_TRY(h, h->mem.get(&l2.wb2_dst, 8 * M));
+  HIP_TRY(h, hipMemset(l2.wb2_dst, 0, 8 * M ? 8 * M : 8));
+  HIP_TRY(h, h->mem.get(&h->d_l2tot, 8 * 4));
+  HIP_TRY(h, hipMemset(h->d_l2tot, 0, 8 * 4));
+  for (int i = 0; i < kBatchBufs; i++) {
+    BatchBuf &b = h->buf[i];
+    const size_t N = (size_t)std::max<int64_t>(h->max_lookups, 1);
+    HIP_TRY(h, h->mem.get(&b.src2, 4 * N));
+    HIP_TRY(h, h->mem.get(&b.dst2, 4 * N));
+    HIP_TRY(h, h->mem.get(&b.evict2, 4 * N));
+    HIP_TRY(h, h->mem.get(&b.ins_dst, 8 * N));
+    HIP_TRY(h, h->mem.get(&b.l2v_src, 8 * N));
+    HIP_TRY(h, h->mem.get(&b.l2v_dst, 8 * N));
+    HIP_TRY(h, h->mem.get(&b.l2v_key, 4 * N));
+  }
+  int64_t base = 0;
+  size_t off = 0;
+  for (TableMeta &m : h->tm) {
+    m.sets2 = m.sets * (uint32_t)factor;
+    m.slot2_base = (int32_t)base;
+    m.lines2 = h->lines2 + off;
+    base += (int64_t)m.sets2 * h->g.ways;
+    off += (size_t)m.sets2 * h->g.ways * m.row_bytes;
+  }
+  HIP_TRY(h, hipMemcpy(h->d_tm, h->tm.data(), sizeof(TableMeta) * h->tm.size(), hipMemcpyHostToDevice));
+  l2.factor = factor;
+  l2.total_slots2 = slots2;
+  l2.on = true;
+  return TBE_OK;
+}
+
+int64_t tbe_num_sets2(tbe_handle h, int32_t table) {
+  if (!h || table < 0 || table >= h->g.T) return TBE_EINVAL;
+  return h->tm[table].sets2;
+}
+
+int tbe_export_second_level_state(tbe_handle h, int32_t table, int64_t *h_tags, int32_t *h_ts) {
+  if (!h || table < 0 || table >= h->g.T || !h_tags || !h_ts) return TBE_EINVAL;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  const TableMeta &m = h->tm[table];
+  const size_t n = (size_t)m.sets2 * h->g.ways;
+  if (n == 0) return TBE_OK;
+  std::vector<int32_t> tmp(n);
+  HIP_TRY(h, hipMemcpy(tmp.data(), h->l2.tags2 + m.slot2_base, 4 * n, hipMemcpyDeviceToHost));
+  for (size_t i = 0; i < n; i++) h_tags[i] = tmp[i];
+  HIP_TRY(h, hipMemcpy(h_ts, h->l2.ts2 + m.slot2_base, 4 * n, hipMemcpyDeviceToHost));
+  return TBE_OK;
+}
+
+int tbe_get_second_level_stats(tbe_handle h, int64_t *h_last4, int64_t *h_total4) {
+  if (!h || !h_last4 || !h_total4) return TBE_EINVAL;
+  for (int i = 0; i < 4; i++) h_last4[i] = h_total4[i] = 0;
+  if (!h->l2.on) return TBE_OK;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  if (h->last_buf >= 0) {
+    BatchCounters c;
+    HIP_TRY(h, hipMemcpy(&c, h->buf[h->last_buf].cnt, sizeof(c), hipMemcpyDeviceToHost));
+    h_last4[0] = c.l2_hits; h_last4[1] = c.l2_demotions; h_last4[2] = c.l2_evictions; h_last4[3] = c.l2_bypasses;
+  }
+  unsigned long long t[4];
+  HIP_TRY(h, hipMemcpy(t, h->d_l2tot, sizeof(t), hipMemcpyDeviceToHost));
+  for (int i = 0; i < 4; i++) h_total4[i] = (int64_t)t[i];
+  return collect_device_errors(h);
 }
 
 int tbe_set_pooling(tbe_handle h, int32_t pooling) {

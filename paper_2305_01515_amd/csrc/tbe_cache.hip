@@ -333,6 +333,10 @@ struct StatusOp {
   uint32_t *byp_key;
   char **byp_src;
   int32_t *loc_u;
+  // second level (all null without one)
+  const int32_t *src2, *dst2, *evict2;
+  char **ins_dst, **l2v_src, **l2v_dst;
+  uint32_t *l2v_key;
   // per-thread tallies (the emit kernel keeps one Op copy per thread in registers)
   mutable unsigned int hits, evs;
   mutable u64 hit_lookups;
@@ -354,6 +358,16 @@ struct StatusOp {
       ins_old[i] = old;
       ins_key[i] = key;
       ins_src[i] = m.host_w + (size_t)row * m.row_bytes;
+      if (src2) {  // second level: the row may come from there, the victim may go there
+        const int32_t s2 = src2[u], d2 = dst2[u], e2 = evict2[u];
+        if (s2 >= 0) ins_src[i] = m.lines2 + (size_t)(s2 - m.slot2_base) * m.row_bytes;
+        char *dst = old >= 0 ? m.host_w + (size_t)old * m.row_bytes : nullptr;
+        if (old >= 0 && d2 >= 0) dst = m.lines2 + (size_t)(d2 - m.slot2_base) * m.row_bytes;
+        ins_dst[i] = dst;
+        l2v_src[i] = e2 >= 0 ? dst : nullptr;  // the line the victim takes still holds the row it pushes out
+        l2v_dst[i] = e2 >= 0 ? m.host_w + (size_t)e2 * m.row_bytes : nullptr;
+        l2v_key[i] = e2 >= 0 ? key_of_row(m, (uint32_t)e2) : 0u;
+      }
       if (old >= 0) evs++;
     } else if (f) {
       const uint32_t j = (uint32_t)(pre >> 32);
@@ -364,6 +378,8 @@ struct StatusOp {
       byp_tab[j] = t;
       byp_key[j] = key;
       byp_src[j] = m.host_w + (size_t)row_of_key(m, key) * m.row_bytes;
+      if (src2 && src2[u] >= 0)  // lives in the second level: used in place
+        byp_src[j] = m.lines2 + (size_t)(src2[u] - m.slot2_base) * m.row_bytes;
       loc_u[u] = -2 - (int32_t)j;  // the row is served from the j-th overflow slot
     } else if (status[u] == ST_HIT) {
       hits++;
@@ -404,7 +420,7 @@ __device__ inline int32_t add_saturating(int32_t a, int32_t b) {  // a, b >= 0
   return v > 0x7FFFFFFFu ? 0x7FFFFFFF : (int32_t)v;
 }
 
-template <bool LFU>
+template <bool LFU, bool L2>
 __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restrict__ tm, int T, int W, int32_t k,
                                                       const uint32_t *__restrict__ uniq_key,
                                                       const int32_t *__restrict__ uniq_tab,
@@ -412,8 +428,14 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
                                                       int32_t *__restrict__ ts, int32_t *__restrict__ freq,
                                                       const int32_t *__restrict__ run_off,
                                                       int32_t *__restrict__ loc_u, uint8_t *__restrict__ status,
-                                                      int32_t *__restrict__ old_tag, const BatchCounters *cnt) {
+                                                      int32_t *__restrict__ old_tag, int32_t *__restrict__ tags2,
+                                                      int32_t *__restrict__ ts2, int l2_factor,
+                                                      int32_t *__restrict__ src2, int32_t *__restrict__ dst2,
+                                                      int32_t *__restrict__ evict2, BatchCounters *cnt) {
   __shared__ int32_t l_tag[kWave];
+  __shared__ int32_t l_tag2[L2 ? kWave : 1], l_ts2[L2 ? kWave : 1], l_way2[L2 ? kWave : 1];
+  __shared__ int32_t v_row[L2 ? kWave : 1], v_u[L2 ? kWave : 1];
+  int n_l2hit = 0, n_l2dem = 0, n_l2ev = 0, n_l2byp = 0;  // this lane's share of the second-level counters
   __shared__ int32_t l_ts[kWave];
   __shared__ int32_t l_freq[kWave];
   __shared__ int32_t l_way[kWave];
@@ -429,6 +451,7 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
       for (int u = u0 + lane; u < u1; u += kWave) {
         loc_u[u] = -1;
         status[u] = ST_BYPASS;
+        if (L2) src2[u] = dst2[u] = evict2[u] = -1;
       }
       continue;
     }
@@ -507,6 +530,102 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
       ts[slot0 + lane] = l_ts[lane];
       freq[slot0 + lane] = l_freq[lane];
     }
+    if (L2) {
+      // ---- second level (exclusive): the rows this set missed are looked up there, then the
+      // rows this set evicted move down.  sets2 = l2_factor * sets, so a row r of this set
+      // belongs to second-level set  set + sets * ((r div sets) mod l2_factor)  and no other
+      // first-level set shares it: this wavefront owns all of them.
+      int n_v = 0;  // the victims of this set: at most W, one per lane
+      for (int c = u0; c < u1; c += kWave) {
+        const int u = c + lane;
+        const bool valid = u < u1;
+        if (valid) src2[u] = dst2[u] = evict2[u] = -1;
+        const bool isv = valid && status[u] == ST_INSERT && old_tag[u] >= 0;
+        const uint64_t vm = __ballot(isv);
+        if (isv) {
+          const int p = n_v + __popcll(vm & lt_mask);
+          v_row[p] = old_tag[u];
+          v_u[p] = u;
+        }
+        n_v += __popcll(vm);
+      }
+      __syncthreads();
+      const int32_t my_v = lane < n_v ? v_row[lane] : -1;
+      const int my_vset = my_v >= 0 ? (int)(((uint32_t)my_v / m.sets) % (uint32_t)l2_factor) : -1;
+      for (int j = 0; j < l2_factor; j++) {
+        const int slot20 = m.slot2_base + (int)(set + (uint32_t)j * m.sets) * W;
+        l_tag2[lane] = lane < W ? tags2[slot20 + lane] : -2;
+        l_ts2[lane] = lane < W ? ts2[slot20 + lane] : 0x7FFFFFFF;
+        __syncthreads();
+        // (A) missed rows of this second-level set: found and inserted above -> moves up, its entry
+        // becomes free; found but bypassed above -> stays, used in place, stamped k
+        for (int c = u0; c < u1; c += kWave) {
+          const int u = c + lane;
+          const uint32_t q = u < u1 ? uniq_key[u] - key0 : 0u;  // row div sets
+          const bool mine = u < u1 && status[u] != ST_HIT && (int)(q % (uint32_t)l2_factor) == j;
+          const int32_t row = mine ? (int32_t)(q * m.sets + set) : -3;
+          int hw = -1;
+          for (int w = 0; w < W; w++)
+            if (l_tag2[w] == row) hw = w;
+          if (hw >= 0) {
+            src2[u] = slot20 + hw;
+            if (status[u] == ST_INSERT) { l_tag2[hw] = -1; l_ts2[hw] = -1; } else l_ts2[hw] = k;
+            n_l2hit++;
+          }
+        }
+        __syncthreads();
+        // (B) victims of this second-level set in ascending row order take the ways older than
+        // k - 1 in order of (timestamp, way); entries of this batch and the one before stay
+        const bool vmine = my_vset == j;
+        int vrank = 0;
+        for (int w = 0; w < n_v; w++) {
+          const int32_t o = v_row[w];
+          if ((int)(((uint32_t)o / m.sets) % (uint32_t)l2_factor) == j && o < my_v) vrank++;
+        }
+        const int32_t my_ts2 = l_ts2[lane];
+        const bool cand2 = lane < W && my_ts2 < k - 1;
+        int rank2 = 0;
+        for (int w = 0; w < W; w++) {
+          const int32_t tw = l_ts2[w];
+          if (tw < k - 1 && (tw < my_ts2 || (tw == my_ts2 && w < lane))) rank2++;
+        }
+        const int n_cand2 = __popcll(__ballot(cand2));
+        if (cand2) l_way2[rank2] = lane;
+        __syncthreads();
+        if (vmine) {
+          if (vrank < n_cand2) {
+            const int way = l_way2[vrank];
+            const int32_t held = l_tag2[way];
+            evict2[v_u[lane]] = held;
+            dst2[v_u[lane]] = slot20 + way;
+            l_tag2[way] = my_v;
+            l_ts2[way] = k;
+            n_l2dem++;
+            if (held >= 0) n_l2ev++;
+          } else {
+            n_l2byp++;  // no way to take: the victim goes to the lower tier
+          }
+        }
+        __syncthreads();
+        if (lane < W) {
+          tags2[slot20 + lane] = l_tag2[lane];
+          ts2[slot20 + lane] = l_ts2[lane];
+        }
+        __syncthreads();
+      }
+    }
+  }
+  if (L2) {
+    for (int d = 32; d >= 1; d >>= 1) {
+      n_l2hit += __shfl_xor(n_l2hit, d); n_l2dem += __shfl_xor(n_l2dem, d);
+      n_l2ev += __shfl_xor(n_l2ev, d); n_l2byp += __shfl_xor(n_l2byp, d);
+    }
+    if (lane == 0) {
+      if (n_l2hit) atomicAdd(&cnt->l2_hits, n_l2hit);
+      if (n_l2dem) atomicAdd(&cnt->l2_demotions, n_l2dem);
+      if (n_l2ev) atomicAdd(&cnt->l2_evictions, n_l2ev);
+      if (n_l2byp) atomicAdd(&cnt->l2_bypasses, n_l2byp);
+    }
   }
 }
 
@@ -528,7 +647,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__
 
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
-                              int32_t *freq, bool lfu, hipStream_t s) {
+                              int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s) {
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
   DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
@@ -546,15 +665,17 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   int64_t max_touched = (int64_t)g.total_sets + g.T;
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
-  if (lfu)
-    hipLaunchKernelGGL(probe_kernel<true>, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key,
-                       b.uniq_tab, b.touched, tags, ts, freq, b.run_off, b.loc_u, b.status, b.old_tag, b.cnt);
-  else
-    hipLaunchKernelGGL(probe_kernel<false>, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key,
-                       b.uniq_tab, b.touched, tags, ts, freq, b.run_off, b.loc_u, b.status, b.old_tag, b.cnt);
+  auto probe = l2.on ? (lfu ? probe_kernel<true, true> : probe_kernel<false, true>)
+                     : (lfu ? probe_kernel<true, false> : probe_kernel<false, false>);
+  hipLaunchKernelGGL(probe, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key, b.uniq_tab, b.touched,
+                     tags, ts, freq, b.run_off, b.loc_u, b.status, b.old_tag, l2.tags2, l2.ts2, l2.factor,
+                     l2.on ? b.src2 : nullptr, l2.on ? b.dst2 : nullptr, l2.on ? b.evict2 : nullptr, b.cnt);
   StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.uniq_tab, b.ins_idx, b.ins_tab, b.ins_slot,
               b.ins_old, b.ins_key, b.ins_src,
-              b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u, 0u, 0u, 0ull};
+              b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u,
+              l2.on ? b.src2 : nullptr, l2.on ? b.dst2 : nullptr, l2.on ? b.evict2 : nullptr,
+              l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr, l2.on ? b.l2v_dst : nullptr,
+              l2.on ? b.l2v_key : nullptr, 0u, 0u, 0ull};
   run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
   const int fin_blocks = (n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096;
   hipLaunchKernelGGL(finalize_kernel, dim3(fin_blocks), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.run_off,

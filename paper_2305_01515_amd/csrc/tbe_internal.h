@@ -49,6 +49,11 @@ struct TableMeta {
   char *host_w;           // pinned host rows [rows, row_bytes]
   float *host_m;          // host accumulators [rows]: read at create, written at flush
   float *dev_m;           // device: row-wise Adagrad accumulators of ALL rows of the table [rows]
+  // second-level cache (Section 5.3): sets2 = l2_factor * sets, so the second-level sets of the
+  // rows of first-level set s are s, s + sets, s + 2 sets, ... and belong to that set alone
+  uint32_t sets2;         // 0 = no second level for this table
+  int32_t slot2_base;     // global id of second-level slot 0 of this table
+  char *lines2;           // pinned host: second-level lines [sets2*ways, row_bytes]
 };
 
 // Device-side scalars of one batch (one per batch buffer).
@@ -64,6 +69,9 @@ struct BatchCounters {
   unsigned long long hits, evictions, hit_lookups;
   int32_t n_long;     // rows with more than kLongRun lookups
   int32_t n_hchunks;  // (table, up to one workgroup's worth of huge rows) chunks
+  // second level: missed rows found there, victims moved down into it, rows it evicted to the
+  // lower tier, victims that found no way and went to the lower tier directly
+  int32_t l2_hits, l2_demotions, l2_evictions, l2_bypasses;
 };
 
 // Arrays of one batch; two of these exist so that batch k+1 can be prepared while
@@ -84,13 +92,22 @@ struct BatchBuf {
   int32_t *loc_u;       // [N] global slot id, or -2-j for the j-th bypassed row
   uint8_t *status;      // [N] Status
   int32_t *old_tag;     // [N] for inserts: row that was evicted, -1 if the entry was free
+  // second level, per distinct row (null without one):
+  int32_t *src2;        // [N] missed row: global second-level slot it was found in, -1 = not there
+  int32_t *dst2;        // [N] insert with a victim: second-level slot the victim moves to, -1 = lower tier
+  int32_t *evict2;      // [N] ... and the row that slot held (evicted to the lower tier), -1 = it was free
   uint2 *touched;       // [N] (global set id, first distinct row) of every touched set
   int32_t *ins_idx;     // [N] distinct-row indices of the inserts, ascending; per insert also:
   int32_t *ins_tab;     // [N]   its table
   int32_t *ins_slot;    // [N]   the global slot it takes
   int32_t *ins_old;     // [N]   the row evicted from that slot, -1 if it was free
   uint32_t *ins_key;    // [N]   its sort key
-  char **ins_src;       // [N]   its row in the backing tier
+  char **ins_src;       // [N]   where its row is fetched from (lower tier or second-level line)
+  char **ins_dst;       // [N]   second level only: where its victim goes (second-level line or lower tier)
+  char **l2v_src;       // [N]   second level only: line of the row the victim pushes out of the second
+                        //       level (null = none), l2v_dst its row in the lower tier, l2v_key its sort key
+  char **l2v_dst;
+  uint32_t *l2v_key;
   uint32_t *ins_where;  // [N]   0 = fetch it from the backing tier; else a kWhere* code: the backing-tier
                         //       copy is stale, the current value is in HBM (see Staging::where)
   int32_t *byp_idx;     // [N] distinct-row indices of the bypasses, ascending; per bypass also:
@@ -144,6 +161,19 @@ struct Staging {
   int64_t max_inserts;
 };
 
+// Second-level cache: tags and timestamps in HBM, lines in pinned host memory (TableMeta),
+// and the staging of the rows it evicts: such a row is read into `out2` by the transfer of
+// the batch that pushes it out and written to the lower tier by the next transfer, exactly
+// like a first-level victim parked in Staging::out; its map code is kWhereParked | (max_inserts + i).
+struct Level2 {
+  bool on = false;
+  int32_t factor = 0;
+  int64_t total_slots2 = 0;
+  int32_t *tags2 = nullptr, *ts2 = nullptr;
+  char *out2[2] = {nullptr, nullptr};  // [max_inserts * stride] each, by batch parity
+  char **wb2_dst = nullptr;            // [max_inserts] lower-tier row of each staged second-level victim
+};
+
 struct Geometry {
   int32_t T, ways;
   int32_t sum_dim;
@@ -173,23 +203,23 @@ hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf 
 hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *result_buf, hipStream_t s);
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
-                              int32_t *freq, bool lfu, hipStream_t s);
+                              int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s);
 // write back the staged victims and (b != null) fetch ahead the rows b's batch inserts
-hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t *rb_of_table,
+hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, int k, const uint32_t *rb_of_table,
                            unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
 // look up, for the rows cur inserts or bypasses, whether their backing-tier copy is stale
 // and where the current value is; then remove prev's entries from the map and enter cur's
 hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, const Staging &st,
-                                unsigned long long *n_late, hipStream_t s);
+                                const Level2 &l2, unsigned long long *n_late, hipStream_t s);
 // move b's victims to the staging area and its new rows into the cache lines
 // (prev = the batch before, null if none; wb_prev: also write prev's overflow rows back)
 hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, bool wb_prev, const Staging &st,
-                         const uint32_t *rb_of_table, unsigned long long *bytes_d2h, hipStream_t s);
+                         const Level2 &l2, const uint32_t *rb_of_table, unsigned long long *bytes_d2h, hipStream_t s);
 // after the batch's backward: its bypassed rows go from their HBM copies to the backing tier
 hipError_t launch_ovf_writeback(const BatchBuf &b, const Staging &st, const uint32_t *rb_of_table,
                                 unsigned long long *bytes_d2h, hipStream_t s);
-hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, unsigned long long *bytes_d2h,
-                        hipStream_t s);
+hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, const Level2 &l2,
+                        unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
 hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
                                   float *out, hipStream_t s);
 hipError_t launch_backward_single_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,

@@ -38,7 +38,9 @@ __global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCo
                                                        char *const *__restrict__ byp_src,
                                                        const int32_t *__restrict__ byp_tab,
                                                        const uint32_t *__restrict__ byp_where, char *__restrict__ ovf,
-                                                       u64 *bytes_h2d, u64 *bytes_d2h) {
+                                                       char *const *__restrict__ l2v_src,
+                                                       char *const *__restrict__ wb2_dst, char *out2_even,
+                                                       char *out2_odd, int k, u64 *bytes_h2d, u64 *bytes_d2h) {
   // Workgroups are dealt to the 8 XCDs round robin; only those landing on the first
   // kLinkXcds work, so that the waves waiting on the host link sit on few CUs.
   if ((int)(blockIdx.x & 7) >= kLinkXcds) return;
@@ -80,6 +82,27 @@ __global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCo
         copy_row(dst, st.out[st.wb_n[1] & 1] + (size_t)i * st.stride, wrb, lig);
         if (lig == 0) out_b += wrb;
       }
+      if (wb2_dst) {  // second level: the row this victim pushed out of it goes to the lower tier
+        char *dst2 = wb2_dst[i];
+        uint8_t *skip2 = st.wb_skip[st.wb_n[1] & 1] + st.max_inserts + i;
+        if (dst2 && *skip2) {
+          dst2 = nullptr;
+          if (lig == 0) *skip2 = 0;
+        }
+        if (dst2) {
+          const uint32_t wrb = st.wb_rb[i];
+          copy_row(dst2, ((st.wb_n[1] & 1) ? out2_odd : out2_even) + (size_t)i * st.stride, wrb, lig);
+          if (lig == 0) out_b += wrb;
+        }
+      }
+    }
+    if (l2v_src && i < n_ins) {  // second level: the row an insert's victim pushes out is read while its
+      const char *src = l2v_src[i];  // line still holds it (the victim is written there by the next transfer)
+      if (src) {
+        const uint32_t vrb = rb_of_table[ins_tab[i]];
+        copy_row(((k & 1) ? out2_odd : out2_even) + (size_t)i * st.stride, src, vrb, lig);
+        if (lig == 0) in_b += vrb;
+      }
     }
     if (fetch) {
       char *dst = st.in + (size_t)i * st.stride;
@@ -110,8 +133,8 @@ __global__ void clear_wb_kernel(int32_t *wb_n) {
   if (threadIdx.x == 0) wb_n[0] = 0;
 }
 
-hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t *rb_of_table, u64 *bytes_h2d,
-                           u64 *bytes_d2h, hipStream_t s) {
+hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, int k, const uint32_t *rb_of_table,
+                           u64 *bytes_h2d, u64 *bytes_d2h, hipStream_t s) {
   // How many workgroups wait on the host link, and on how many CUs, decides how the link and
   // the HBM-bound kernels of the other streams slow each other (measured on the benchmark
   // workload, step time / forward kernel time while the transfer runs; alone the forward
@@ -125,7 +148,8 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t 
   hipLaunchKernelGGL(transfer_kernel, dim3(kLinkBlocks / kLinkXcds * 8), dim3(256), 0, s, st, b ? b->cnt : nullptr,
                      b ? b->ins_src : nullptr, b ? b->ins_tab : nullptr, rb_of_table,
                      b ? b->ins_where : nullptr, b ? b->byp_src : nullptr, b ? b->byp_tab : nullptr,
-                     b ? b->byp_where : nullptr, b ? b->ovf : nullptr, bytes_h2d, bytes_d2h);
+                     b ? b->byp_where : nullptr, b ? b->ovf : nullptr, (b && l2.on) ? b->l2v_src : nullptr,
+                     l2.on ? l2.wb2_dst : nullptr, l2.out2[0], l2.out2[1], k, bytes_h2d, bytes_d2h);
   hipLaunchKernelGGL(clear_wb_kernel, dim3(1), dim3(64), 0, s, st.wb_n);
   return hipGetLastError();
 }
@@ -136,7 +160,10 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const uint32_t 
 __global__ __launch_bounds__(256) void mark_kernel(const TableMeta *__restrict__ tm, const BatchCounters *cnt,
                                                    const int32_t *__restrict__ ins_tab,
                                                    const int32_t *__restrict__ ins_old,
-                                                   const uint32_t *__restrict__ byp_key, uint32_t *where, int set) {
+                                                   const uint32_t *__restrict__ byp_key,
+                                                   char *const *__restrict__ l2v_src,
+                                                   const uint32_t *__restrict__ l2v_key, uint32_t max_inserts,
+                                                   uint32_t *where, int set) {
   if (cnt->err) return;
   const int n_ins = cnt->n_ins, n_byp = cnt->n_byp;
   const int stride = gridDim.x * blockDim.x;
@@ -144,6 +171,8 @@ __global__ __launch_bounds__(256) void mark_kernel(const TableMeta *__restrict__
     if (i < n_ins) {
       const int32_t old = ins_old[i];
       if (old >= 0) where[key_of_row(tm[ins_tab[i]], (uint32_t)old)] = set ? (kWhereParked | (uint32_t)i) : 0u;
+      // the row pushed out of the second level is staged like a victim, behind the victims
+      if (l2v_src && l2v_src[i]) where[l2v_key[i]] = set ? (kWhereParked | (max_inserts + (uint32_t)i)) : 0u;
     } else {
       where[byp_key[i - n_ins]] = set ? (kWhereOverflow | (uint32_t)(i - n_ins)) : 0u;
     }
@@ -171,14 +200,15 @@ __global__ __launch_bounds__(256) void classify_kernel(const BatchCounters *cnt,
 }
 
 hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, const Staging &st,
-                                u64 *n_late, hipStream_t s) {
+                                const Level2 &l2, u64 *n_late, hipStream_t s) {
+  const uint32_t M = (uint32_t)st.max_inserts;
   hipLaunchKernelGGL(classify_kernel, dim3(512), dim3(256), 0, s, cur.cnt, cur.ins_key, cur.byp_key, st.where,
                      cur.ins_where, cur.byp_where, st.wb_skip[(cur.k - 1) & 1], n_late);
   if (prev)
     hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, prev->cnt, prev->ins_tab, prev->ins_old, prev->byp_key,
-                       st.where, 0);
+                       l2.on ? prev->l2v_src : nullptr, prev->l2v_key, M, st.where, 0);
   hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, cur.cnt, cur.ins_tab, cur.ins_old, cur.byp_key,
-                     st.where, 1);
+                     l2.on ? cur.l2v_src : nullptr, cur.l2v_key, M, st.where, 1);
   return hipGetLastError();
 }
 
@@ -196,7 +226,12 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
                                                      char *const *__restrict__ prev_byp_src,
                                                      const int32_t *__restrict__ prev_byp_tab,
                                                      const char *__restrict__ prev_ovf, int wb_prev, int k,
+                                                     char *const *__restrict__ ins_dst,
+                                                     char *const *__restrict__ l2v_src,
+                                                     char *const *__restrict__ l2v_dst, char **wb2_dst,
+                                                     const char *__restrict__ out2_prev,
                                                      const uint32_t *__restrict__ rb_of_table, u64 *bytes_d2h) {
+  const uint32_t M = (uint32_t)st.max_inserts;  // map codes kWhereParked | (M + i): rows staged in out2
   if (cnt->err) return;
   const int n_ins = cnt->n_ins, n_byp = cnt->n_byp;
   const int n_prev = (prev_cnt && prev_cnt->err == 0) ? prev_cnt->n_byp : 0;
@@ -222,9 +257,11 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
     const uint32_t code = ins_where[i];
     const uint32_t rb = m.row_bytes;
     char *line = m.lines + (size_t)(slot - m.slot_base) * rb;
+    const uint32_t ix = code & kWhereIndex;
     const char *src = code == 0             ? st.in + (size_t)i * st.stride
-                      : (code & kWhereOverflow) ? prev_ovf + (size_t)(code & kWhereIndex) * st.stride
-                                                : st.out[ppar] + (size_t)(code & kWhereIndex) * st.stride;
+                      : (code & kWhereOverflow) ? prev_ovf + (size_t)ix * st.stride
+                      : ix >= M                 ? out2_prev + (size_t)(ix - M) * st.stride
+                                                : st.out[ppar] + (size_t)ix * st.stride;
     char *park = st.out[par] + (size_t)i * st.stride;
     for (uint32_t c = lig * 16; c < rb; c += kMoveLanes * 16) {
       const uint4 fresh = *(const uint4 *)(src + c);
@@ -232,15 +269,18 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
       *(uint4 *)(line + c) = fresh;
     }
     if (lig == 0) {
-      st.wb_dst[i] = old >= 0 ? m.host_w + (size_t)old * rb : nullptr;
+      st.wb_dst[i] = old < 0 ? nullptr : ins_dst ? ins_dst[i] : m.host_w + (size_t)old * rb;
       st.wb_rb[i] = rb;
+      if (wb2_dst) wb2_dst[i] = l2v_src[i] ? l2v_dst[i] : nullptr;
     }
   }
   for (int j = group; j < n_byp; j += n_groups) {  // late bypassed rows
     const uint32_t code = byp_where[j];
     if (code == 0) continue;
-    const char *src = (code & kWhereOverflow) ? prev_ovf + (size_t)(code & kWhereIndex) * st.stride
-                                              : st.out[ppar] + (size_t)(code & kWhereIndex) * st.stride;
+    const uint32_t ix = code & kWhereIndex;
+    const char *src = (code & kWhereOverflow) ? prev_ovf + (size_t)ix * st.stride
+                      : ix >= M               ? out2_prev + (size_t)(ix - M) * st.stride
+                                              : st.out[ppar] + (size_t)ix * st.stride;
     copy_row(ovf + (size_t)j * st.stride, src, rb_of_table[byp_tab[j]], lig);
   }
   for (int d = 32; d >= 1; d >>= 1) out_b += __shfl_xor(out_b, d);
@@ -276,11 +316,13 @@ hipError_t launch_ovf_writeback(const BatchBuf &b, const Staging &st, const uint
 }
 
 hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, bool wb_prev, const Staging &st,
-                         const uint32_t *rb_of_table, u64 *bytes_d2h, hipStream_t s) {
+                         const Level2 &l2, const uint32_t *rb_of_table, u64 *bytes_d2h, hipStream_t s) {
   hipLaunchKernelGGL(commit_kernel, dim3(4096), dim3(256), 0, s, tm, st, b.cnt, b.ins_tab, b.ins_where, b.ins_slot,
                      b.ins_old, b.byp_tab, b.byp_where, b.ovf, prev ? prev->cnt : nullptr,
                      prev ? prev->byp_src : nullptr, prev ? prev->byp_tab : nullptr, prev ? prev->ovf : nullptr,
-                     (prev && wb_prev) ? 1 : 0, b.k, rb_of_table, bytes_d2h);
+                     (prev && wb_prev) ? 1 : 0, b.k, l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr,
+                     l2.on ? b.l2v_dst : nullptr, l2.on ? l2.wb2_dst : nullptr, l2.out2[(b.k & 1) ^ 1], rb_of_table,
+                     bytes_d2h);
   return hipGetLastError();
 }
 
@@ -307,9 +349,41 @@ __global__ __launch_bounds__(256) void flush_kernel(const TableMeta *__restrict_
   if ((threadIdx.x & 63) == 0 && out_b) atomicAdd(bytes_d2h, out_b);
 }
 
-hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, u64 *bytes_d2h, hipStream_t s) {
-  if (g.total_slots == 0) return hipSuccess;
-  hipLaunchKernelGGL(flush_kernel, dim3(1024), dim3(256), 0, s, tm, g.T, g.total_slots, tags, bytes_d2h);
+// flush of the second level: every valid line goes to its row in the lower tier (host to
+// host through the GPU); the levels are exclusive, so no row is written twice
+__global__ __launch_bounds__(256) void flush2_kernel(const TableMeta *__restrict__ tm, int T, int64_t total_slots2,
+                                                     const int32_t *__restrict__ tags2, u64 *bytes_h2d,
+                                                     u64 *bytes_d2h) {
+  const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
+  const int lig = threadIdx.x % kMoveLanes;
+  const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / kMoveLanes;
+  u64 b = 0;
+  for (int64_t slot = group; slot < total_slots2; slot += n_groups) {
+    const int32_t row = tags2[slot];
+    if (row < 0) continue;
+    int lo = 0, hi = T - 1;  // table owning this slot: last t with slot2_base <= slot
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if ((int64_t)tm[mid].slot2_base <= slot) lo = mid; else hi = mid - 1;
+    }
+    const TableMeta &m = tm[lo];
+    copy_row(m.host_w + (size_t)row * m.row_bytes, m.lines2 + (size_t)(slot - m.slot2_base) * m.row_bytes, m.row_bytes, lig);
+    if (lig == 0) b += m.row_bytes;
+  }
+  for (int d = 32; d >= 1; d >>= 1) b += __shfl_xor(b, d);
+  if ((threadIdx.x & 63) == 0 && b) {
+    atomicAdd(bytes_h2d, b);
+    atomicAdd(bytes_d2h, b);
+  }
+}
+
+hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, const Level2 &l2, u64 *bytes_h2d,
+                        u64 *bytes_d2h, hipStream_t s) {
+  if (g.total_slots)
+    hipLaunchKernelGGL(flush_kernel, dim3(1024), dim3(256), 0, s, tm, g.T, g.total_slots, tags, bytes_d2h);
+  if (l2.on && l2.total_slots2)
+    hipLaunchKernelGGL(flush2_kernel, dim3(kLinkBlocks), dim3(256), 0, s, tm, g.T, l2.total_slots2, l2.tags2, bytes_h2d,
+                       bytes_d2h);
   return hipGetLastError();
 }
 

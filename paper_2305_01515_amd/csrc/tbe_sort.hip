@@ -49,6 +49,7 @@ __global__ void reset_counters_kernel(BatchCounters *cnt) {
     cnt->n_uniq = cnt->n_touched = cnt->n_ins = cnt->n_byp = cnt->n_items = cnt->err = 0;
     cnt->n_huge = cnt->n_mid = cnt->n_long = cnt->n_hchunks = 0;
     cnt->hits = cnt->evictions = cnt->hit_lookups = 0;
+    cnt->l2_hits = cnt->l2_demotions = cnt->l2_evictions = cnt->l2_bypasses = 0;
   }
 }
 

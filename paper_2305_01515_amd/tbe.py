@@ -22,7 +22,8 @@ ERRORS = {0: "TBE_OK", -1: "TBE_EINVAL", -2: "TBE_ERANGE", -3: "TBE_EORDER", -4:
 EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "tbe_flush", "tbe_destroy",
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
-           "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling"]
+           "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling",
+           "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
@@ -84,6 +85,11 @@ def lib() -> C.CDLL:
         l.tbe_set_inputs_ready.argtypes = [vp, i32]
         l.tbe_set_policy.argtypes = [vp, i32]
         l.tbe_set_pooling.argtypes = [vp, i32]
+        l.tbe_enable_second_level.argtypes = [vp, i32]
+        l.tbe_num_sets2.argtypes = [vp, i32]
+        l.tbe_num_sets2.restype = i64
+        l.tbe_export_second_level_state.argtypes = [vp, i32, vp, vp]
+        l.tbe_get_second_level_stats.argtypes = [vp, vp, vp]
         l.tbe_export_cache_freq.argtypes = [vp, i32, vp]
         l.tbe_get_stage_times.argtypes = [vp, i32, i64, vp]
         l.tbe_get_stage_times.restype = i64
@@ -103,7 +109,7 @@ class TBE:
 
     def __init__(self, weights: Sequence[torch.Tensor], state: Sequence[torch.Tensor], cache_slots: Sequence[int],
                  ways: int, max_batch: int, max_lookups: int, overlap: bool = True, policy: str = "lru",
-                 pooling: str = "sum"):
+                 pooling: str = "sum", second_level_factor: int = 0):
         self._h = C.c_void_p()
         T = len(weights)
         self.T, self.ways = T, ways
@@ -130,6 +136,8 @@ class TBE:
             self._check(lib().tbe_set_policy(self._h, POLICIES[policy]), "tbe_set_policy")
         if pooling != "sum":
             self._check(lib().tbe_set_pooling(self._h, POOLINGS[pooling]), "tbe_set_pooling")
+        if second_level_factor:
+            self._check(lib().tbe_enable_second_level(self._h, second_level_factor), "tbe_enable_second_level")
 
     def _check(self, rc: int, what: str):
         if rc:
@@ -211,6 +219,21 @@ class TBE:
         ts = np.empty(n, dtype=np.int32)
         self._check(lib().tbe_export_cache_state(self._h, t, tags.ctypes.data, ts.ctypes.data), "tbe_export_cache_state")
         return tags, ts
+
+    def second_level_state(self, t: int) -> Tuple[np.ndarray, np.ndarray]:
+        n = int(lib().tbe_num_sets2(self._h, t)) * self.ways
+        tags = np.empty(n, dtype=np.int64)
+        ts = np.empty(n, dtype=np.int32)
+        self._check(lib().tbe_export_second_level_state(self._h, t, tags.ctypes.data, ts.ctypes.data),
+                    "tbe_export_second_level_state")
+        return tags, ts
+
+    def second_level_stats(self):
+        last, total = np.zeros(4, dtype=np.int64), np.zeros(4, dtype=np.int64)
+        self._check(lib().tbe_get_second_level_stats(self._h, last.ctypes.data, total.ctypes.data),
+                    "tbe_get_second_level_stats")
+        names = ("hits", "demotions", "evictions", "bypasses")
+        return dict(zip(names, last.tolist())), dict(zip(names, total.tolist()))
 
     def cache_freq(self, t: int) -> np.ndarray:
         f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)

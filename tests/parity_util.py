@@ -53,7 +53,8 @@ def gpu_snapshot(g, T: int):
     return {"stats": g.stats()["last"],
             "events": {k: _canon(g.events(k)) for k in ("hit", "insert", "bypass")},
             "state": [g.cache_state(t) for t in range(T)],
-            "freq": [g.cache_freq(t) for t in range(T)]}
+            "freq": [g.cache_freq(t) for t in range(T)],
+            "l2": [g.second_level_state(t) for t in range(T)], "l2_stats": g.second_level_stats()[0]}
 
 
 def compare_cache_step(o: Oracle, snap, T: int, ctx: str):
@@ -68,6 +69,11 @@ def compare_cache_step(o: Oracle, snap, T: int, ctx: str):
         assert np.array_equal(to, tg), f"{ctx}: tags of table {t} differ"
         assert np.array_equal(tso, tsg), f"{ctx}: timestamps of table {t} differ"
         assert np.array_equal(o.cache_freq(t), snap["freq"][t]), f"{ctx}: lookup counts of table {t} differ"
+        t2o, ts2o = o.second_level_state(t)
+        t2g, ts2g = snap["l2"][t]
+        assert np.array_equal(t2o, t2g), f"{ctx}: second-level tags of table {t} differ"
+        assert np.array_equal(ts2o, ts2g), f"{ctx}: second-level timestamps of table {t} differ"
+    assert o.second_level_stats()[0] == snap["l2_stats"], f"{ctx}: second-level counters differ: oracle {o.second_level_stats()[0]} gpu {snap['l2_stats']}"
 
 
 def compare_forward(cfg, out_o: np.ndarray, out_g: np.ndarray, ctx: str):
@@ -92,7 +98,7 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str):
 
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
-               pooling: str = "sum"):
+               pooling: str = "sum", second_level_factor: int = 0):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -105,12 +111,14 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     T = cfg.num_tables
     Wn, Mn, Wp, Mp = make_backing(cfg, device=init_device)
     slots = [tc.cache_slots for tc in cfg.tables]
-    o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads, policy=policy, pooling=pooling)
+    slots2 = [second_level_factor * (s // cfg.ways) * cfg.ways for s in slots] if second_level_factor else None
+    o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads, policy=policy, pooling=pooling, second_level_slots=slots2)
     stream = synth.BatchStream(cfg, device="cpu")
     batches = [stream.next() for _ in range(steps)]
     if max_lookups is None:
         max_lookups = max(int(b[0].numel()) for b in batches) + 1
-    g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, max_lookups, overlap=overlap, policy=policy, pooling=pooling)
+    g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, max_lookups, overlap=overlap, policy=policy, pooling=pooling,
+            second_level_factor=second_level_factor)
     dev = [(i.to(device), f.to(device)) for i, f in batches]
     snaps = {}
 
@@ -164,12 +172,16 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         tg, tsg = g.cache_state(t)
         assert np.array_equal(to, tg) and np.array_equal(tso, tsg), f"final cache state of table {t} differs"
         assert np.array_equal(o.cache_freq(t), g.cache_freq(t)), f"final lookup counts of table {t} differ"
+        for a, b in zip(o.second_level_state(t), g.second_level_state(t)):
+            assert np.array_equal(a, b), f"final second-level state of table {t} differs"
+    assert o.second_level_stats()[1] == g.second_level_stats()[1], "total second-level counters differ"
     so, sg = o.stats()[1], g.stats()["total"]
     assert so == sg, f"total counters differ: oracle {so} gpu {sg}"
     o.flush()
     g.flush()
     compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush")
     st = g.stats()
+    st["second_level_total"] = g.second_level_stats()[1]
     g.close()
     o.close()
     return st

@@ -40,3 +40,15 @@ def draw(seed):
 def test_random_model(seed):
     cfg, order, overlap = draw(seed)
     run_parity(cfg, steps=4, order=order, overlap=overlap)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_model_two_level(seed):
+    """the same draws with a second-level cache, LFU or LRU and sum or mean pooling, more steps
+    (rows must be pushed down, found again, and pushed out of the second level)"""
+    cfg, order, overlap = draw(100 + seed)
+    if not any(t.cache_slots >= cfg.ways for t in cfg.tables):
+        cfg.tables[0].cache_slots = cfg.ways
+    g = np.random.default_rng(seed)
+    run_parity(cfg, steps=7, order=order, overlap=overlap, second_level_factor=int(g.choice([1, 2, 5])),
+               policy=str(g.choice(["lru", "lfu"])), pooling=str(g.choice(["sum", "mean"])))
