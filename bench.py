@@ -149,6 +149,8 @@ def main():
     ap.add_argument("--cache-frac", type=float, default=0.05, help="locality: cached fraction of the rows")
     ap.add_argument("--policy", default="lru", choices=["lru", "lfu"],
                     help="replacement policy; lru is the benchmark's, lfu for the comparison the paper makes")
+    ap.add_argument("--second-level", type=int, default=0,
+                    help="factor of a second-level cache in pinned host memory (0 = none, the benchmark's)")
     ap.add_argument("--pooling", default="sum", choices=["sum", "mean"], help="sum is the benchmark's")
     ap.add_argument("--resident-fraction", type=float, default=-1.0,
                     help="hetero: share of the HBM budget given to whole tables chosen by the placement solver "
@@ -204,7 +206,7 @@ def main():
                 f"{'uniform' if args.alpha <= 0 else 'Zipf %g' % args.alpha}, 64-way cache {args.cache_frac:.0%} of rows")
     if args.policy != "lru":
         desc = desc.replace("LRU ", "").replace("-way cache", "-way LFU cache")
-    if args.workload != "main" or args.policy != "lru" or args.pooling != "sum":
+    if args.workload != "main" or args.policy != "lru" or args.pooling != "sum" or args.second_level:
         args.no_cpu_baseline = True
     T = cfg.num_tables
 
@@ -237,7 +239,7 @@ def main():
                "sample": f"first batches of the same stream from a cold cache ({n} lookups), oracle -O2, OpenMP over tables"}
 
     g = TBE(Wp, Mp, [tc.cache_slots for tc in cfg.tables], cfg.ways, cfg.batch, max_n + 1, overlap=not args.no_overlap,
-            policy=args.policy, pooling=args.pooling)
+            policy=args.policy, pooling=args.pooling, second_level_factor=args.second_level)
 
     def run(lo, hi):
         # next-batch prefetch is issued ahead of the current batch's training
@@ -252,12 +254,14 @@ def main():
     run(0, Wm)
     torch.cuda.synchronize()
     s0 = g.stats()
+    l2_0 = g.second_level_stats() if args.second_level else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run(Wm, Wm + K)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     s1 = g.stats()
+    l2_1 = g.second_level_stats() if args.second_level else None
     BWD = ("backward_single", "backward_short", "backward_long", "backward_huge")
     STAGES = ("prefetch", "fill", "commit", "forward") + BWD
     first = {k: (Wm if k in ("forward",) + BWD else Wm + 1) for k in STAGES}
@@ -315,7 +319,8 @@ def main():
         "dtype": "f16 storage / f32 accumulate" if cfg.tables[0].dtype == synth.FP16 else "f32", "data": "synthetic",
         "config": {"workload": desc,
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
-                   "overlap": not args.no_overlap, "policy": args.policy, "pooling": args.pooling},
+                   "overlap": not args.no_overlap, "policy": args.policy, "pooling": args.pooling,
+                   "second_level_factor": args.second_level},
         # The HBM-bound kernel that moves most algorithmic bytes on the hit path.  Rows are counted once
         # per lookup (the paper's Eq. 3); repeats of hot rows are served by L2, so achieved can exceed what
         # HBM alone delivers -- `traffic` is what the counters saw.  ms_per_launch is measured in the timed,
@@ -360,10 +365,17 @@ def main():
         "measured_peaks": peaks,  # plain copies on this machine, for context (the fractions above use the nominal peaks)
         "cpu_baseline": cpu,
     }
+    second_level = None
+    if args.second_level:
+        l2a, l2b = l2_0[1], l2_1[1]
+        second_level = {k: (l2b[k] - l2a[k]) / npf for k in l2b}
+        second_level["hit_rate_of_first_level_misses"] = (l2b["hits"] - l2a["hits"]) / max(1, tot["inserts"] + tot["bypasses"])
     g.close()
-    if args.workload == "main":
+    if args.workload == "main" and not args.second_level:
         res["all_hit_control"] = all_hit_control(TBE, cfg, Wp, Mp, batches[Wm + K], grads, out, max_n, hit_b,
                                                  not args.no_overlap)
+    if args.second_level:
+        res["second_level"] = second_level
     print(json.dumps(res))
 
 
