@@ -398,6 +398,12 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   for (const TableMeta &m : h->tm) h->g.ovf_stride = std::max(h->g.ovf_stride, m.row_bytes);
   h->g.key_bits = 1;
   while (h->g.key_bits < 32 && (1ull << h->g.key_bits) < key) h->g.key_bits++;
+  {  // sort payload (bag, position inside the bag) when both fit 32 bits
+    int bag_bits = 0;
+    while ((1ll << bag_bits) < (int64_t)num_tables * max_batch) bag_bits++;
+    h->g.within_bits = std::min(24, 32 - bag_bits);
+    if (h->g.within_bits < 1) h->g.within_bits = 0;
+  }
 
   auto bail = [&](int code) { tbe_destroy(h); return code; };
   auto hipbail = [&](hipError_t e, const char *what) {

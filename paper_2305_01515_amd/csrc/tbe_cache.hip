@@ -127,6 +127,8 @@ struct DedupOp {
   const uint32_t *key;      // sorted
   const uint32_t *pos;      // lookup position of each sorted element
   const int32_t *bag_of_pos;
+  const BatchCounters *cnt;  // cnt->packed: the payload carries the bag
+  int within_bits;
   uint32_t *uid_sorted;
   int32_t *sorted_bag;
   uint32_t *uniq_key;
@@ -137,7 +139,7 @@ struct DedupOp {
   __device__ void emit(int i, int, u64 pre, u64 f) const {
     const uint32_t u = (uint32_t)(pre & 0xFFFFFFFFull) + (uint32_t)f - 1u;
     uid_sorted[i] = u;
-    sorted_bag[i] = bag_of_pos[pos[i]];
+    sorted_bag[i] = cnt->packed ? (int32_t)(pos[i] >> within_bits) : bag_of_pos[pos[i]];
     if (f) {
       const uint32_t k = key[i];
       uniq_key[u] = k;
@@ -634,14 +636,18 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__
                                                        const uint32_t *__restrict__ uid_sorted,
                                                        const int32_t *__restrict__ loc_u,
                                                        const int32_t *__restrict__ run_off, uint32_t *__restrict__ loc,
+                                                       const int64_t *__restrict__ offsets, int within_bits,
                                                        const BatchCounters *cnt) {
   if (cnt->err) return;
+  const bool packed = cnt->packed != 0;
+  const uint32_t within_mask = (1u << within_bits) - 1u;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
     const uint32_t u = uid_sorted[i];
     const int32_t lu = loc_u[u];
     uint32_t w = lu >= 0 ? (uint32_t)lu : (kLocOverflow | (uint32_t)(-2 - lu));
     if (run_off[u + 1] - run_off[u] == 1) w |= kLocSingle;
-    loc[pos[i]] = w;
+    const uint32_t p = pos[i];  // the lookup's position: as is, or bag start + position inside the bag
+    loc[packed ? (uint32_t)offsets[p >> within_bits] + (p & within_mask) : p] = w;
   }
 }
 
@@ -650,7 +656,7 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
                               int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s) {
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
-  DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
+  DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.cnt, g.within_bits, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
             b.uniq_tab};
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
@@ -679,7 +685,7 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
   const int fin_blocks = (n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096;
   hipLaunchKernelGGL(finalize_kernel, dim3(fin_blocks), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.run_off,
-                     b.loc, b.cnt);
+                     b.loc, b.d_offsets, g.within_bits, b.cnt);
   return hipGetLastError();
 }
 

@@ -72,6 +72,10 @@ struct BatchCounters {
   // second level: missed rows found there, victims moved down into it, rows it evicted to the
   // lower tier, victims that found no way and went to the lower tier directly
   int32_t l2_hits, l2_demotions, l2_evictions, l2_bypasses;
+  // 1 = the sort payload of a lookup is (bag << within_bits) | position inside the bag, which spares
+  // the gather of the bag ids after the sort; 0 = a bag is too long for that, the payload is the
+  // lookup's position and the bag comes from bag_of_pos
+  int32_t packed;
 };
 
 // Arrays of one batch; two of these exist so that batch k+1 can be prepared while
@@ -178,6 +182,7 @@ struct Geometry {
   int32_t T, ways;
   int32_t sum_dim;
   int32_t key_bits;     // bits of the largest sort key
+  int32_t within_bits;  // bits left for the position inside the bag in a packed sort payload (0 = never packed)
   int32_t partial_stride;  // floats per partial-sum slot (widest row, padded to whole lanes)
   uint32_t ovf_stride;     // bytes per overflow / staging slot (widest row)
   uint32_t total_sets;

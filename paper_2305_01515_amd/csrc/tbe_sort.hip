@@ -10,11 +10,20 @@ namespace tbe {
 // --------------------------------------------------------------------------------------
 constexpr int kKeygenLanes = 8;
 
+// Does every bag fit the packed payload?  (cnt->packed starts at 1.)
+__global__ __launch_bounds__(256) void baglen_kernel(int64_t nb, const int64_t *__restrict__ offsets, int within_bits,
+                                                     BatchCounters *cnt) {
+  const int64_t bag = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool too_long = bag < nb && offsets[bag + 1] - offsets[bag] > (1ll << within_bits);
+  if (__ballot(too_long) && (threadIdx.x & 63) == 0) atomicMin(&cnt->packed, 0);
+}
+
 __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict__ tm, int T, int B, int64_t N,
                                                      const int64_t *__restrict__ indices,
                                                      const int64_t *__restrict__ offsets, uint32_t *__restrict__ keys,
                                                      uint32_t *__restrict__ vals, int32_t *__restrict__ bag_of_pos,
-                                                     float *__restrict__ inv_len, BatchCounters *cnt) {
+                                                     float *__restrict__ inv_len, int within_bits,
+                                                     BatchCounters *cnt) {
   const int64_t nb = (int64_t)T * B;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t bag = gid / kKeygenLanes;
@@ -32,6 +41,7 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
   if (inv_len && sub == 0) inv_len[bag] = hi > lo ? 1.0f / (float)(hi - lo) : 0.0f;
   const int t = (int)(bag / B);
   const TableMeta m = tm[t];
+  const bool packed = cnt->packed != 0;
   for (int64_t j = lo + sub; j < hi; j += kKeygenLanes) {
     int64_t r = indices[j];
     if (r < 0 || r >= m.rows) {
@@ -39,28 +49,37 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
       r = 0;
     }
     keys[j] = key_of_row(m, (uint32_t)r);
-    vals[j] = (uint32_t)j;
-    bag_of_pos[j] = (int32_t)bag;
+    if (packed) {
+      vals[j] = ((uint32_t)bag << within_bits) | (uint32_t)(j - lo);
+    } else {
+      vals[j] = (uint32_t)j;
+      bag_of_pos[j] = (int32_t)bag;
+    }
   }
 }
 
-__global__ void reset_counters_kernel(BatchCounters *cnt) {
+__global__ void reset_counters_kernel(BatchCounters *cnt, int within_bits) {
   if (threadIdx.x == 0) {
     cnt->n_uniq = cnt->n_touched = cnt->n_ins = cnt->n_byp = cnt->n_items = cnt->err = 0;
     cnt->n_huge = cnt->n_mid = cnt->n_long = cnt->n_hchunks = 0;
     cnt->hits = cnt->evictions = cnt->hit_lookups = 0;
     cnt->l2_hits = cnt->l2_demotions = cnt->l2_evictions = cnt->l2_bypasses = 0;
+    cnt->packed = within_bits > 0 ? 1 : 0;
   }
 }
 
 hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf &b, uint32_t *keys, uint32_t *vals,
                          hipStream_t s) {
-  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, s, b.cnt);
+  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, s, b.cnt, g.within_bits);
+  const int64_t nb = (int64_t)g.T * b.batch;
+  if (g.within_bits > 0 && nb > 0)
+    hipLaunchKernelGGL(baglen_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, nb, b.d_offsets, g.within_bits,
+                       b.cnt);
   const int64_t threads = (int64_t)g.T * b.batch * kKeygenLanes;
   if (threads > 0) {
     const int64_t blocks = (threads + 255) / 256;
     hipLaunchKernelGGL(keygen_kernel, dim3((unsigned)blocks), dim3(256), 0, s, tm, g.T, b.batch, b.n, b.d_indices,
-                       b.d_offsets, keys, vals, b.bag_of_pos, b.mean ? b.inv_len : nullptr, b.cnt);
+                       b.d_offsets, keys, vals, b.bag_of_pos, b.mean ? b.inv_len : nullptr, g.within_bits, b.cnt);
   }
   return hipGetLastError();
 }

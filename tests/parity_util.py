@@ -98,7 +98,7 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str):
 
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
-               pooling: str = "sum", second_level_factor: int = 0):
+               pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -117,7 +117,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     batches = [stream.next() for _ in range(steps)]
     if max_lookups is None:
         max_lookups = max(int(b[0].numel()) for b in batches) + 1
-    g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, max_lookups, overlap=overlap, policy=policy, pooling=pooling,
+    g = TBE(Wp, Mp, slots, cfg.ways, max_batch or cfg.batch, max_lookups, overlap=overlap, policy=policy, pooling=pooling,
             second_level_factor=second_level_factor)
     dev = [(i.to(device), f.to(device)) for i, f in batches]
     snaps = {}

@@ -68,3 +68,12 @@ def test_main_config_full_size():
     cfg = synth.config_main()
     st = run_parity(cfg, steps=3, order="ahead", oracle_threads=16, init_device="cuda")
     assert st["total"]["bypasses"] > 0
+
+
+@pytest.mark.parametrize("max_batch", [1 << 20, 1 << 27])
+def test_sort_payload_with_and_without_the_bag(max_batch):
+    """The sort payload carries (bag, position inside the bag) when both fit 32 bits.  The split is
+    fixed by tables x max_batch: with 2^20 bags' worth of room the model's bags (up to 200 lookups)
+    fit; with 2^27 only bags of up to 4 lookups would, so the batch falls back to plain positions and
+    the gathered bag ids.  Both must give the same results."""
+    run_parity(small_cfg(synth.FP16, 8, seed=91), steps=4, order="ahead", max_batch=max_batch)
