@@ -9,7 +9,7 @@
  *               LRU victims, write the victims back and fetch the missed rows
  *               (paper Section 5.5: tag/state lookup, cache algorithm, data
  *               lookup/update, data movement; Section 5.7: prefetch stage "4a");
- *   forward   : pooled (sum) embedding-bag lookup (Section 2.1.1);
+ *   forward   : pooled (sum, optionally mean) embedding-bag lookup (Section 2.1.1);
  *   backward  : per-row gradient aggregation + row-wise Adagrad applied where the row
  *               lives (Section 2.1.2 Eq. 2, Section 5.9);
  *   flush     : write every cached row back to the backing tier (write-back rule of
@@ -20,7 +20,8 @@
  *     crosses the boundary; tbe_last_error() gives a text for the last failure;
  *   - pointers named d_* are DEVICE pointers, h_* are HOST pointers;
  *   - the caller owns every buffer it passes in; the library owns the cache lines, tags,
- *     timestamps and all scratch memory, allocated once in tbe_create;
+ *     timestamps and all scratch memory, allocated once in tbe_create (the optional
+ *     second level: in tbe_enable_second_level);
  *   - work is enqueued on the two HIP streams given at creation and the calls return
  *     without waiting for the GPU, except tbe_flush, tbe_get_stats and the tbe_export_*
  *     calls, which synchronise both streams;
@@ -44,6 +45,10 @@
  * copy is still on its way; the row-wise accumulators live in HBM for all rows (the paper
  * keeps optimizer parameters there, Section 5.6.1) and host_state is only read by
  * tbe_create and written by tbe_flush.  After tbe_flush both host arrays are current.
+ *
+ * Optional, each selected by one call before the first batch: LFU instead of LRU
+ * (tbe_set_policy), mean instead of sum pooling (tbe_set_pooling), a second-level cache in
+ * pinned host memory between the two tiers (tbe_enable_second_level).
  */
 #ifndef TBE_H
 #define TBE_H

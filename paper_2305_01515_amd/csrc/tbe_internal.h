@@ -78,13 +78,15 @@ struct BatchCounters {
   int32_t packed;
 };
 
-// Arrays of one batch; two of these exist so that batch k+1 can be prepared while
-// batch k is still being trained on.
+// Arrays of one batch; three of these rotate: batch k+1 is prepared while batch k trains, and
+// batch k's bypass list and overflow copies are still read by the commit of batch k+1 while
+// batch k+2 is already being prepared.
 struct BatchBuf {
   // per lookup
   uint32_t *loc;        // [N] location word of every lookup (kLoc* bits), input order
   int32_t *sorted_bag;  // [N] global bag id (t*B + b) of the i-th lookup in sorted order
-  int32_t *bag_of_pos;  // [N] global bag id of lookup j (input order)
+  int32_t *bag_of_pos;  // [N] global bag id of lookup j (input order); only written when the sort payload
+                        //     does not carry the bag (BatchCounters::packed == 0)
   float *inv_len;       // [T * batch] mean pooling: 1 / lookups of the bag (0 for an empty bag)
   bool mean;            // mean pooling instead of sum: forward and backward weigh by inv_len
   uint32_t *uid_sorted; // [N] index of the distinct row of the i-th sorted lookup
