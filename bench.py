@@ -136,13 +136,77 @@ def all_hit_control(TBE, cfg, Wp, Mp, batch, grads, out, max_n, hit_bytes, overl
             "hit_path_bytes": hit_bytes, "frac": hit_bytes / dt / 1e9 / HBM_PEAK_GBS}
 
 
+def locality_sweep(args):
+    """The (index distribution, cache size) sweep of the locality configuration: 1 table x 100M rows x
+    dim 64 fp16, batch 32768, pooling 32; for every point 100 warm-up steps, then `--steps` measured
+    steps, pipelined.  One table in pinned memory serves all points (the values do not matter to the
+    hit rates).  Prints one JSON line with the whole table."""
+    import torch
+    from paper_2305_01515_amd import synth
+    from paper_2305_01515_amd.tbe import TBE
+    dev = "cuda"
+    warm, K = 100, args.steps
+    base = synth.config_locality(None, 0.01)
+    tc = base.tables[0]
+    w = torch.empty(tc.rows, tc.dim, dtype=torch.float16, pin_memory=True)
+    synth.init_table(base, 0, device=dev, out=w)
+    m = torch.zeros(tc.rows, dtype=torch.float32, pin_memory=True)
+    out = torch.empty(base.batch, base.sum_dim, dtype=torch.float32, device=dev)
+    grads = [synth.grad_out(base, s + 1, device=dev) for s in range(4)]
+    points = []
+    for alpha in (None, 0.8, 1.0, 1.2, 1.4):
+        stream = synth.BatchStream(synth.config_locality(alpha, 0.01), device=dev)
+        batches = [stream.next() for _ in range(warm + K + 1)]
+        max_n = max(int(b[0].numel()) for b in batches)
+        for frac in (0.01, 0.02, 0.05, 0.10, 0.25):
+            cfg = synth.config_locality(alpha, frac)
+            g = TBE([w], [m], [cfg.tables[0].cache_slots], cfg.ways, cfg.batch, max_n + 1, overlap=not args.no_overlap,
+                    policy=args.policy)
+            g.set_inputs_ready(True)
+
+            def run(lo, hi):
+                for s in range(lo, hi):
+                    g.prefetch(*batches[s + 1])
+                    g.forward(batches[s][0], batches[s][1], out)
+                    g.backward_update(grads[s % len(grads)], cfg.lr, cfg.eps)
+
+            g.prefetch(*batches[0])
+            run(0, warm)
+            torch.cuda.synchronize()
+            s0 = g.stats()
+            t0 = time.perf_counter()
+            run(warm, warm + K)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            s1 = g.stats()
+            g.forward(batches[warm + K][0], batches[warm + K][1], out)
+            g.backward_update(grads[0], cfg.lr, cfg.eps)
+            torch.cuda.synchronize()
+            g.close()
+            tot = {k: s1["total"][k] - s0["total"][k] for k in s1["total"]}
+            n = sum(int(batches[s][0].numel()) for s in range(warm, warm + K))
+            points.append({"alpha": alpha, "cache_frac": frac, "hit_rate_unique": tot["hits"] / max(1, tot["uniques"]),
+                           "hit_rate_lookup": tot["hit_lookups"] / max(1, tot["lookups"]),
+                           "uniques_per_step": tot["uniques"] / K, "ms_per_step": dt / K * 1e3, "lookups_per_s": n / dt,
+                           "h2d_GBps": (s1["h2d_bytes"] - s0["h2d_bytes"]) / dt / 1e9,
+                           "d2h_GBps": (s1["d2h_bytes"] - s0["d2h_bytes"]) / dt / 1e9})
+            print("point", points[-1], file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "locality sweep: hit rate and pooled lookups/s per (index distribution, cache size)",
+                      "unit": "lookups/s", "n_gpus": 1, "steps": K, "warmup": warm, "data": "synthetic",
+                      "dtype": "f16 storage / f32 accumulate",
+                      "config": {"workload": "1 table x 100M rows x dim 64 fp16, batch 32768, pooling 32, 64-way cache, "
+                                             "uniform / Zipf 0.8 / 1.0 / 1.2 / 1.4 x cache 1 / 2 / 5 / 10 / 25 % of rows",
+                                 "policy": args.policy},
+                      "sweep": points}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--tables", type=int, default=32, help="(debug) fewer tables than the named workload")
-    ap.add_argument("--workload", default="main", choices=["main", "tiny", "capacity", "locality", "hetero"],
+    ap.add_argument("--workload", default="main", choices=["main", "tiny", "capacity", "locality", "hetero", "locality_sweep"],
                     help="main = the benchmark workload; the others are the parity configurations, for reference "
                          "measurements only (no CPU baseline)")
     ap.add_argument("--alpha", type=float, default=1.0, help="locality: Zipf exponent, 0 = uniform")
@@ -168,6 +232,8 @@ def main():
     from paper_2305_01515_amd.tbe import TBE
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "locality_sweep":
+        return locality_sweep(args)
     dev = "cuda"
     K, Wm = args.steps, args.warmup
     if args.workload == "main":
