@@ -48,6 +48,7 @@ struct tbe_ctx {
   int32_t *tags = nullptr, *ts = nullptr, *freq = nullptr;
   int policy = TBE_POLICY_LRU;
   int pooling = TBE_POOL_SUM;
+  size_t huge_slots = 0;        // (huge row, bag range) pairs a batch can have
   Level2 l2;                    // second-level cache (off unless tbe_enable_second_level was called)
   char *lines2 = nullptr;       // its lines: one pinned host allocation
   unsigned long long *d_l2tot = nullptr;  // running totals of the four second-level counters
@@ -189,7 +190,7 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.huge_sorted, 4 * (N / kHugeRun + 1)));
   HIP_TRY(h, h->mem.get(&b.hchunks, 16 * (N / kHugeRun + (size_t)h->g.T + 1)));
   HIP_TRY(h, h->mem.get(&b.hg_count, 4 * 3 * ((size_t)h->g.T + 1)));
-  HIP_TRY(h, h->mem.get(&b.hstart, 4 * (N / kHugeRun + 1) * kHugeRanges));
+  HIP_TRY(h, h->mem.get(&b.hstart, 4 * h->huge_slots));
   HIP_TRY(h, h->mem.get(&b.cnt, sizeof(BatchCounters)));
   HIP_TRY(h, hipMemset(b.cnt, 0, sizeof(BatchCounters)));
   return TBE_OK;
@@ -460,6 +461,13 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
       h->ci.cls_tables[c] = d_ids;
     }
   }
+  {  // (huge row, bag range) pairs of a batch: 64 ranges for at most N / kHugeRun rows, or more ranges for few
+     // rows -- then ranges x chunks <= kHugeTargetItems and a chunk has at most 256 / lanes rows
+    int min_lanes = 64;
+    for (const TableMeta &m : h->tm) min_lanes = std::min(min_lanes, (int)m.lanes);
+    h->huge_slots = std::max<size_t>((size_t)kHugeRanges * ((size_t)max_lookups / kHugeRun + 1),
+                                     (size_t)kHugeTargetItems * (256 / min_lanes));
+  }
   for (int i = 0; i < kBatchBufs; i++) {
     int rc = alloc_batchbuf(h, h->buf[i], max_lookups);
     if (rc) { g_create_error = h->err; return bail(rc); }
@@ -477,7 +485,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     int widest = 0;
     for (const TableMeta &m : h->tm) widest = std::max(widest, m.lanes * (m.dtype == TBE_FP32 ? 4 : 8));
     h->g.partial_stride = widest;
-    CREATE_TRY(h->mem.get(&h->partials, 4 * (size_t)widest * kHugeRanges * (N / kHugeRun + 1)));
+    CREATE_TRY(h->mem.get(&h->partials, 4 * (size_t)widest * h->huge_slots));
   }
   {
     Staging &st = h->st;

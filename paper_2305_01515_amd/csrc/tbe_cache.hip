@@ -297,14 +297,15 @@ __global__ __launch_bounds__(256) void huge_starts_kernel(const TableMeta *__res
                                                           const int32_t *__restrict__ sorted_bag, int32_t *hstart,
                                                           const BatchCounters *cnt) {
   if (cnt->err) return;
-  const int n = cnt->n_huge * kHugeRanges;
+  const int R = huge_ranges(cnt->n_hchunks);
+  const int n = cnt->n_huge * R;
   for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < n; x += gridDim.x * blockDim.x) {
-    const int h = x / kHugeRanges, range = x % kHugeRanges;
+    const int h = x / R, range = x % R;
     const int u = huge[h];
     const int t = uniq_tab[u];
     const int tb = huge_tile_bags(kTileBytes / (tm[t].lanes * (tm[t].dtype == 0 ? 4 : 8) * 4), B);  // bags per gradient tile
     const int n_tiles = (B + tb - 1) / tb;
-    const int tiles_per_range = (n_tiles + kHugeRanges - 1) / kHugeRanges;
+    const int tiles_per_range = (n_tiles + R - 1) / R;
     const int first_bag = t * B + range * tiles_per_range * tb;
     int lo = run_off[u], hi = run_off[u + 1];
     while (lo < hi) {

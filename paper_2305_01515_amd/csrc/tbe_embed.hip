@@ -380,9 +380,9 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
 // Rows with more than kHugeRun lookups.  Such a row touches a large part of its table's bags,
 // and the lookups of a row are sorted by bag, so the table's huge rows all sweep the same
 // gradient slice.  A workgroup takes (table, up to 256/G of its huge rows, one of
-// kHugeRanges bag ranges): it stages the range tile by tile in LDS (each gradient row read
+// the batch's bag ranges, see huge_ranges): it stages the range tile by tile in LDS (each gradient row read
 // once, coalesced) and every group adds up, from LDS, the lookups of its row that fall into
-// the tile.  The kHugeRanges partial sums of a row go to `partials`; the combine kernel adds
+// the tile.  The partial sums of a row, one per range, go to `partials`; the combine kernel adds
 // them in range order and updates the row.
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__restrict__ tm, int cls, int B,
@@ -402,17 +402,18 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
   constexpr int TB_MAX = kTileBytes / (ROWF * 4);     // bags that fit a tile
   __shared__ float tile[TB_MAX * ROWF];
   if (cnt->err) return;
-  const int n_work = cnt->n_hchunks * kHugeRanges;
+  const int R = huge_ranges(cnt->n_hchunks);
+  const int n_work = cnt->n_hchunks * R;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
   const int gshift = (threadIdx.x & 63) / G * G;
   const int TB = huge_tile_bags(TB_MAX, B);
   const int n_tiles = (B + TB - 1) / TB;
-  const int tiles_per_range = (n_tiles + kHugeRanges - 1) / kHugeRanges;
+  const int tiles_per_range = (n_tiles + R - 1) / R;
   int first, end, step;
   xcd_span(n_work, 1, first, end, step);  // work items are in table order
   for (int wk = first; wk < end; wk += step) {
-    const uint4 ch = hchunks[wk / kHugeRanges];  // (table, first position in huge_sorted, rows, -)
-    const int range = wk % kHugeRanges;
+    const uint4 ch = hchunks[wk / R];  // (table, first position in huge_sorted, rows, -)
+    const int range = wk % R;
     const int t = (int)ch.x;
     if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
@@ -423,7 +424,7 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
     const int bag0 = t * B;
     const int i1 = has_row ? run_off[u + 1] : 0;
     const int tile_lo = range * tiles_per_range, tile_hi = min(n_tiles, tile_lo + tiles_per_range);
-    int i = has_row ? hstart[h * kHugeRanges + range] : 0;  // first lookup of the row in this bag range
+    int i = has_row ? hstart[h * R + range] : 0;  // first lookup of the row in this bag range
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
@@ -496,14 +497,16 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
       }
     }
     if (has_row) {
-      float *p = partials + ((size_t)h * kHugeRanges + range) * pstride + lig * EPL;
+      float *p = partials + ((size_t)h * R + range) * pstride + lig * EPL;
 #pragma unroll
       for (int e = 0; e < EPL; e++) p[e] = g[e];
     }
   }
 }
 
-// Huge rows: add the partial sums in range order, then update the row.
+// Huge rows: add the partial sums, then update the row.  One workgroup per row: its 256/G
+// groups each add a contiguous share of the ranges in range order, the shares are added in
+// group order through LDS (a fixed order, so the result is reproducible).
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int cls,
                                                                const int32_t *__restrict__ huge,
@@ -516,25 +519,41 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
                                                                const int32_t *__restrict__ table_class,
                                                                const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
+  constexpr int NG = 256 / G;
+  __shared__ float part[NG][G * EPL + 1];
   if (cnt->err) return;
   const int n_huge = cnt->n_huge;
-  const int lig = threadIdx.x % G;
-  const int n_groups = gridDim.x * (256 / G);
-  for (int h = blockIdx.x * (256 / G) + threadIdx.x / G; h < n_huge; h += n_groups) {
+  const int R = huge_ranges(cnt->n_hchunks);
+  const int lig = threadIdx.x % G, grp = threadIdx.x / G;
+  const int per = (R + NG - 1) / NG;
+  for (int h = blockIdx.x; h < n_huge; h += gridDim.x) {
     const int u = huge[h];
     const int t = uniq_tab[u];
-    if (table_class[t] != cls) continue;
+    if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    for (int r = 0; r < kHugeRanges; r++) {
-      const float *p = partials + ((size_t)h * kHugeRanges + r) * pstride + lig * EPL;
+    const int r1 = min(R, (grp + 1) * per);
+    for (int r = grp * per; r < r1; r++) {
+      const float *p = partials + ((size_t)h * R + r) * pstride + lig * EPL;
 #pragma unroll
       for (int e = 0; e < EPL; e++) g[e] += p[e];
     }
-    update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < EPL; e++) part[grp][lig * EPL + e] = g[e];
+    __syncthreads();
+    if (grp == 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; e++) {
+        float s = 0.f;
+        for (int q = 0; q < NG; q++) s += part[q][lig * EPL + e];
+        g[e] = s;
+      }
+      update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
+    }
   }
 }
 
@@ -557,7 +576,7 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
     hipLaunchKernelGGL((backward_huge_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.hchunks,
                        b.huge_sorted, b.huge, b.hstart, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride, table_class,
                        b.mean ? b.inv_len : nullptr, b.cnt);
-    hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(256), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
+    hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(1024), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
                        b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   } else if (which == 0) {
     auto kern = b.mean ? backward_long_kernel<DT, G, true> : backward_long_kernel<DT, G, false>;

@@ -14,7 +14,9 @@ constexpr uint32_t kNoSet = 0xFFFFFFFFu;  // global set id of rows of a table wi
 //   above        : bag tiles of the gradient staged in LDS and shared by the table's huge rows
 constexpr int kLongRun = 64;
 constexpr int kHugeRun = 1024;
-constexpr int kHugeRanges = 64;           // each huge row's sum is split over this many bag ranges
+constexpr int kHugeRanges = 64;           // each huge row's sum is split over at least this many bag ranges
+constexpr int kHugeTargetItems = 2048;    // ... and over more when the batch has few huge rows, so that the
+constexpr int kHugeMaxRanges = 1024;      //     kernel still has about this many work items (at most this many ranges)
 constexpr int kTileBytes = 16384;         // gradient tile in LDS
 
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
@@ -128,7 +130,7 @@ struct BatchBuf {
   int32_t *huge_sorted; // [N/kHugeRun + 1] positions in `huge`, grouped by table
   uint4 *hchunks;       // [N/kHugeRun + T + 1] (table, first position in huge_sorted, count, -)
   int32_t *hg_count;    // [3*(T+1)] per-table counters of the grouping
-  int32_t *hstart;      // [(N/kHugeRun + 1) * kHugeRanges] first sorted position of a huge row in each bag range
+  int32_t *hstart;      // [huge rows * huge_ranges] first sorted position of a huge row in each bag range
   BatchCounters *cnt;   // device
   // host-side description
   const int64_t *d_indices;
@@ -238,6 +240,13 @@ hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassIn
 // ---- small device helpers ----
 
 // Bags per gradient tile of the huge-row backward: what fits the LDS tile, but few enough
+// Bag ranges of the huge-row backward for a batch with n_hchunks (table, row group) chunks: a
+// function of the batch alone, so the summation order is reproducible.
+__host__ __device__ inline int huge_ranges(int n_hchunks) {
+  const int r = n_hchunks > 0 ? kHugeTargetItems / n_hchunks : kHugeRanges;
+  return r < kHugeRanges ? kHugeRanges : (r > kHugeMaxRanges ? kHugeMaxRanges : r);
+}
+
 // that a batch has at least kHugeRanges tiles -- every range then sums a bounded share of a
 // row's lookups, which bounds the length of the fp32 summation chains.
 __host__ __device__ inline int huge_tile_bags(int fit, int B) {
