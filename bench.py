@@ -220,6 +220,8 @@ def main():
                     help="hetero: share of the HBM budget given to whole tables chosen by the placement solver "
                          "(Eq. 6); negative = plain split in proportion to lookups x dim")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-control", action="store_true", help="skip the all-hit control run after the benchmark "
+                    "(so that a profile of the process holds the benchmark's launches only)")
     ap.add_argument("--no-overlap", action="store_true", help="run everything on one stream")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -437,7 +439,7 @@ def main():
         second_level = {k: (l2b[k] - l2a[k]) / npf for k in l2b}
         second_level["hit_rate_of_first_level_misses"] = (l2b["hits"] - l2a["hits"]) / max(1, tot["inserts"] + tot["bypasses"])
     g.close()
-    if args.workload == "main" and not args.second_level:
+    if args.workload == "main" and not args.second_level and not args.no_control:
         res["all_hit_control"] = all_hit_control(TBE, cfg, Wp, Mp, batches[Wm + K], grads, out, max_n, hit_b,
                                                  not args.no_overlap)
     if args.second_level:
