@@ -303,7 +303,14 @@ def main():
         nb = 3
         v, n = cpu_baseline(cfg, Wp, [(b[0].cpu().numpy(), b[1].cpu().numpy()) for b in batches[:nb]],
                             [g.cpu().numpy() for g in grads[:nb]], threads)
-        cpu = {"value": v, "unit": "lookups/s", "cores": threads, "kind": "oracle",
+        model = ""
+        try:
+            with open("/proc/cpuinfo") as f:
+                model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+        except OSError:
+            pass
+        cpu = {"value": v, "unit": "lookups/s", "cores": threads, "kind": "oracle", "cpu_model": model,
+               "host_cpus": os.cpu_count(),
                "sample": f"first batches of the same stream from a cold cache ({n} lookups), oracle -O2, OpenMP over tables"}
 
     g = TBE(Wp, Mp, [tc.cache_slots for tc in cfg.tables], cfg.ways, cfg.batch, max_n + 1, overlap=not args.no_overlap,
