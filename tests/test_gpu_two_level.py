@@ -67,3 +67,16 @@ def test_second_level_errors():
     g.forward(idx, off)
     g.backward_update(torch.zeros(8, 8, device="cuda"), 0.1, 1e-8)
     g.close()
+
+
+@pytest.mark.parametrize("factor", [0, 2])
+def test_long_run_scaled(factor):
+    """40 steps of the benchmark workload's shape at 1/16 of the rows and batch, prefetch ahead and
+    pipelined: late rows, skipped write-backs, bypasses and (factor 2) second-level traffic in steady
+    state, compared with the oracle every fifth step and after the flush."""
+    cfg = synth.config_main(tables=6, rows=62500, batch=512)
+    st = run_parity(cfg, steps=40, order="ahead", second_level_factor=factor, check_every=5, oracle_threads=6)
+    assert st["late_fetches"] > 0 and st["total"]["bypasses"] > 0 and st["total"]["evictions"] > 0
+    if factor:
+        l2 = st["second_level_total"]
+        assert l2["hits"] > 0 and l2["evictions"] > 0
