@@ -63,6 +63,10 @@ def lib():
         _lib.orc_set_policy.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_set_pooling.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_set_second_level.argtypes = [C.c_void_p, C.c_void_p]
+        _lib.orc_enable_deferred_init.argtypes = [C.c_void_p, C.c_uint64, C.c_double]
+        _lib.orc_export_initialised.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        _lib.orc_init_normal.restype = C.c_double
+        _lib.orc_init_normal.argtypes = [C.c_uint64, C.c_int32, C.c_int64, C.c_int32]
         _lib.orc_num_sets2.restype = C.c_int64
         _lib.orc_num_sets2.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_export_second_level.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
@@ -90,7 +94,7 @@ class Oracle:
 
     def __init__(self, weights: Sequence[np.ndarray], state: Sequence[np.ndarray], cache_slots: Sequence[int],
                  ways: int, threads: int = 1, policy: str = "lru", pooling: str = "sum",
-                 second_level_slots: Optional[Sequence[int]] = None):
+                 second_level_slots: Optional[Sequence[int]] = None, deferred_init=None):
         self.weights = list(weights)
         self.state = list(state)
         self.ways = ways
@@ -121,7 +125,18 @@ class Oracle:
             rc = lib().orc_set_second_level(self.h, s2.ctypes.data)
             if rc:
                 raise OracleError(rc, "set_second_level")
+        if deferred_init is not None:  # (seed, std)
+            rc = lib().orc_enable_deferred_init(self.h, int(deferred_init[0]), float(deferred_init[1]))
+            if rc:
+                raise OracleError(rc, "enable_deferred_init")
         self.B = 0
+
+    def initialised(self, t: int) -> np.ndarray:
+        out = np.empty(self.weights[t].shape[0], dtype=np.uint8)
+        rc = lib().orc_export_initialised(self.h, t, out.ctypes.data)
+        if rc:
+            raise OracleError(rc, "export_initialised")
+        return out
 
     def close(self):
         if self.h:

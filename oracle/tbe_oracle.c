@@ -46,6 +46,13 @@
  *     (the paper's pipelining rule, Section 5.7, applied to the second level, whose moves
  *     trail the decisions by a batch).  The second level is always LRU by the time a row
  *     entered it (or was last used in place);
+ *   - deferred initialisation on read [Section 5.4.2]: with it enabled a row of the lower tier
+ *     has no value until it is first read from there (a first-level miss that the second
+ *     level does not hold); it is then given normal random values, std * z, z from a
+ *     counter-based generator of (seed, table, row, element) -- so the values do not depend on
+ *     the order of the reads and equal a table initialised in advance with the same
+ *     generator: two 24-bit uniforms u1 in (0, 1], u2 in [0, 1) from one 64-bit hash per
+ *     element pair, z = sqrt(-2 ln u1) * (cos | sin)(2 pi u2), rounded once to the storage type;
  *   - mean pooling, the second pooling mode the paper names [Section 2.1.1]: the pooled
  *     vector is the sum divided by the number of lookups of the bag (a row looked up twice
  *     counts twice; an empty bag gives zeros), so a lookup of a bag of L lookups hands
@@ -112,6 +119,8 @@ typedef struct {
   void *lines2;
   float *line_state2;
   int64_t l2_hits, l2_demotions, l2_evictions, l2_bypasses; /* of the last batch */
+  unsigned char *initialised; /* deferred initialisation: [rows] 1 = the row has a value (null = off) */
+  int32_t index;              /* table number (enters the generator) */
   /* last prefetched batch */
   int64_t n_uniq;
   int64_t *uniq;    /* sorted distinct rows */
@@ -129,6 +138,9 @@ typedef struct {
   int32_t T, ways;
   int32_t policy;      /* ORC_LRU or ORC_LFU */
   int32_t pooling;     /* ORC_POOL_SUM or ORC_POOL_MEAN */
+  int deferred;        /* deferred initialisation on read */
+  uint64_t init_seed;
+  double init_std;
   orc_table *tab;
   int32_t k;           /* batch id of the last prefetch */
   int32_t B;
@@ -194,7 +206,7 @@ static size_t esize(int dtype) { return dtype == 0 ? 4 : 2; }
 
 static void free_table(orc_table *t) {
   free(t->tag); free(t->ts); free(t->freq); free(t->lines); free(t->line_state);
-  free(t->tag2); free(t->ts2); free(t->lines2); free(t->line_state2);
+  free(t->tag2); free(t->ts2); free(t->lines2); free(t->line_state2); free(t->initialised);
   free(t->uniq); free(t->mult); free(t->hit_row); free(t->ins_row);
   free(t->ins_slot); free(t->ins_old); free(t->byp_row);
 }
@@ -254,6 +266,55 @@ int orc_set_second_level(void *hp, const int64_t *slots2) {
     if (!tb->tag2 || !tb->ts2 || !tb->lines2 || !tb->line_state2) return ORC_ENOMEM;
     for (int64_t i = 0; i < n; i++) { tb->tag2[i] = -1; tb->ts2[i] = -1; }
   }
+  return ORC_OK;
+}
+
+/* ---------------- deferred initialisation: the counter-based generator ---------------- */
+
+static uint64_t mix64(uint64_t x) { /* the finaliser of splitmix64 */
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
+/* standard normal number of element d of row r of table t */
+static double init_normal(uint64_t seed, int32_t t, int64_t r, int32_t d) {
+  uint64_t table_key = mix64(seed ^ ((uint64_t)(t + 1) * 0xD1342543DE82EF95ull));
+  uint64_t h = mix64(table_key + (uint64_t)r * 0x2545F4914F6CDD1Dull + (uint64_t)(d / 2));
+  double u1 = (double)((h >> 40) + 1) / 16777216.0;       /* (0, 1] */
+  double u2 = (double)((h >> 8) & 0xFFFFFFull) / 16777216.0; /* [0, 1) */
+  double rad = sqrt(-2.0 * log(u1)), ang = 6.283185307179586476925 * u2;
+  return (d & 1) ? rad * sin(ang) : rad * cos(ang);
+}
+double orc_init_normal(uint64_t seed, int32_t t, int64_t r, int32_t d) { return init_normal(seed, t, r, d); }
+
+/* first read of a row from the lower tier gives it its value */
+static void ensure_initialised(const orc *h, orc_table *tb, int64_t r) {
+  if (!tb->initialised || tb->initialised[r]) return;
+  for (int d = 0; d < tb->dim; d++)
+    store_elem(tb->weights, tb->dtype, r * tb->dim + d, h->init_std * init_normal(h->init_seed, tb->index, r, d));
+  tb->initialised[r] = 1;
+}
+
+/* rows get their values on first read from the lower tier; only before the first batch */
+int orc_enable_deferred_init(void *hp, uint64_t seed, double std) {
+  orc *h = (orc *)hp;
+  if (!h || !(std >= 0.0)) return ORC_EINVAL;
+  if (h->k != 0 || h->deferred) return ORC_EORDER;
+  for (int t = 0; t < h->T; t++) {
+    h->tab[t].initialised = (unsigned char *)calloc((size_t)h->tab[t].rows, 1);
+    if (!h->tab[t].initialised) return ORC_ENOMEM;
+    h->tab[t].index = t;
+  }
+  h->deferred = 1; h->init_seed = seed; h->init_std = std;
+  return ORC_OK;
+}
+
+int orc_export_initialised(void *hp, int32_t t, unsigned char *out) {
+  orc *h = (orc *)hp;
+  if (!h || t < 0 || t >= h->T || !out || !h->tab[t].initialised) return ORC_EINVAL;
+  memcpy(out, h->tab[t].initialised, (size_t)h->tab[t].rows);
   return ORC_OK;
 }
 
@@ -380,6 +441,7 @@ static int second_level(orc *h, orc_table *tb) {
       tb->tag2[s2] = -1; tb->ts2[s2] = -1;
       tb->l2_hits++;
     } else {
+      ensure_initialised(h, tb, r);
       backing_to_line(tb, slot, r);
     }
   }
@@ -387,6 +449,7 @@ static int second_level(orc *h, orc_table *tb) {
   for (int64_t j = 0; j < tb->n_byp; j++) {
     int64_t s2 = find_slot2(tb, W, tb->byp_row[j]);
     if (s2 >= 0) { tb->ts2[s2] = k; tb->l2_hits++; }
+    else ensure_initialised(h, tb, tb->byp_row[j]);
   }
   /* (B) the evicted rows move down in ascending row order */
   qsort(vic, (size_t)nv, sizeof(orc_victim), cmp_victim);
@@ -473,6 +536,7 @@ static int prefetch_table(orc *h, int t) {
     if (victim < 0) {
       tb->byp_row[tb->n_byp++] = r;
       tb->st.bypasses++;
+      if (tb->sets2 == 0) ensure_initialised(h, tb, r); /* read from the lower tier directly */
       continue;
     }
     int64_t slot = s * W + victim;
@@ -480,6 +544,7 @@ static int prefetch_table(orc *h, int t) {
     if (old >= 0) tb->st.evictions++;
     if (tb->sets2 == 0) { /* one level: the victim goes to the lower tier, the row comes from it */
       if (old >= 0) line_to_backing(tb, slot, old);
+      ensure_initialised(h, tb, r);
       backing_to_line(tb, slot, r);
     }
     tb->tag[slot] = r;
