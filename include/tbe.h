@@ -176,6 +176,27 @@ int tbe_export_second_level_state(tbe_handle h, int32_t table, int64_t *h_tags, 
 int tbe_get_second_level_stats(tbe_handle h, int64_t *h_last4, int64_t *h_total4);
 
 /*
+ * Deferred initialisation on read (Section 5.4.2).  With it enabled the rows of the backing
+ * tier need no initial values: a row gets its value when it is first fetched from the backing
+ * tier (a miss that the second level does not hold) -- normal random numbers std * z made up
+ * on the GPU instead of read over the host link, z from a counter-based generator of
+ * (seed, table, row, element), so the values do not depend on the order of the reads and equal
+ * a table initialised in advance with the same generator:
+ *   key   = mix(seed ^ (table + 1) * 0xD1342543DE82EF95),  mix = the finaliser of splitmix64
+ *   h     = mix(key + row * 0x2545F4914F6CDD1D + element / 2)        (64-bit arithmetic)
+ *   u1    = ((h >> 40) + 1) / 2^24,  u2 = ((h >> 8) & 0xFFFFFF) / 2^24
+ *   z     = sqrt(-2 ln u1) * cos(2 pi u2) for even elements, ... * sin(2 pi u2) for odd ones
+ * in fp32, rounded to the storage type.  The row reaches host_weights when it is evicted,
+ * written back or flushed; rows never read keep whatever host_weights held.  host_state is
+ * used as always.  Only before the first tbe_prefetch (TBE_EORDER afterwards or when called
+ * twice); allocates one bit per row; TBE_EINVAL for a negative std.
+ */
+int tbe_enable_deferred_init(tbe_handle h, uint64_t seed, float std);
+/* Which rows of a table have a value (1) -- HOST uint8[rows].  Synchronises.  TBE_EORDER when
+ * deferred initialisation is not enabled. */
+int tbe_export_initialised(tbe_handle h, int32_t table, uint8_t *h_flags);
+
+/*
  * Pooling mode (Section 2.1.1 names sum, mean and max; sum and mean are built).
  * TBE_POOL_SUM, the default.  TBE_POOL_MEAN: tbe_forward divides every pooled vector by the
  * number of lookups of its bag (a row looked up twice counts twice; an empty bag gives

@@ -48,6 +48,8 @@ struct tbe_ctx {
   int32_t *tags = nullptr, *ts = nullptr, *freq = nullptr;
   int policy = TBE_POLICY_LRU;
   int pooling = TBE_POOL_SUM;
+  DeferredInit di;              // deferred initialisation on read (off unless enabled)
+  uint32_t *init_bits = nullptr;
   size_t huge_slots = 0;        // (huge row, bag range) pairs a batch can have
   Level2 l2;                    // second-level cache (off unless tbe_enable_second_level was called)
   char *lines2 = nullptr;       // its lines: one pinned host allocation
@@ -278,7 +280,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     // the host link; neither touches a cache line, so a batch in flight is not disturbed,
     // and the link stream lets the next batch's sort and probe run meanwhile
     StageTimer tm_(h, TBE_STAGE_FILL, h->ls);
-    HIP_TRY(h, launch_transfer(&b, h->st, h->l2, b.k, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
+    HIP_TRY(h, launch_transfer(&b, h->st, h->l2, h->di, b.k, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
   }
   b.prev_bi = h->prev_buf;
   h->prev_buf = bi;
@@ -599,7 +601,7 @@ int tbe_flush(tbe_handle h) {
   if (h->n_pend > 0 || h->current >= 0) return fail(h, TBE_EORDER, "flush: a batch is still in flight");
   int rc = sync_all(h);
   if (rc) return rc;
-  HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
+  HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, h->di, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
   HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->l2, h->d_bytes, h->d_bytes + 1, h->cs));
   for (const TableMeta &m : h->tm) {
     HIP_TRY(h, hipMemcpyAsync(m.host_m, m.dev_m, 4 * (size_t)m.rows, hipMemcpyDeviceToHost, h->cs));
@@ -710,6 +712,39 @@ int tbe_get_second_level_stats(tbe_handle h, int64_t *h_last4, int64_t *h_total4
   HIP_TRY(h, hipMemcpy(t, h->d_l2tot, sizeof(t), hipMemcpyDeviceToHost));
   for (int i = 0; i < 4; i++) h_total4[i] = (int64_t)t[i];
   return collect_device_errors(h);
+}
+
+int tbe_enable_deferred_init(tbe_handle h, uint64_t seed, float std) {
+  if (!h) return TBE_EINVAL;
+  if (!(std >= 0.f)) return fail(h, TBE_EINVAL, "enable_deferred_init: std must be >= 0");
+  if (h->k != 0) return fail(h, TBE_EORDER, "enable_deferred_init: batches have been prefetched already");
+  if (h->di.tm) return fail(h, TBE_EORDER, "enable_deferred_init: already enabled");
+  size_t words = 0;
+  for (const TableMeta &m : h->tm) words += ((size_t)m.rows + 31) / 32;
+  HIP_TRY(h, h->mem.get(&h->init_bits, 4 * words));
+  HIP_TRY(h, hipMemset(h->init_bits, 0, 4 * words));
+  size_t off = 0;
+  for (TableMeta &m : h->tm) {
+    m.init_bits = h->init_bits + off;
+    off += ((size_t)m.rows + 31) / 32;
+  }
+  HIP_TRY(h, hipMemcpy(h->d_tm, h->tm.data(), sizeof(TableMeta) * h->tm.size(), hipMemcpyHostToDevice));
+  h->di.tm = h->d_tm;
+  h->di.seed = seed;
+  h->di.std = std;
+  return TBE_OK;
+}
+
+int tbe_export_initialised(tbe_handle h, int32_t table, uint8_t *h_flags) {
+  if (!h || table < 0 || table >= h->g.T || !h_flags) return TBE_EINVAL;
+  if (!h->di.tm) return fail(h, TBE_EORDER, "export_initialised: deferred initialisation is not enabled");
+  int rc = sync_all(h);
+  if (rc) return rc;
+  const TableMeta &m = h->tm[table];
+  std::vector<uint32_t> w(((size_t)m.rows + 31) / 32);
+  HIP_TRY(h, hipMemcpy(w.data(), m.init_bits, 4 * w.size(), hipMemcpyDeviceToHost));
+  for (int64_t r = 0; r < m.rows; r++) h_flags[r] = (uint8_t)((w[(size_t)r >> 5] >> (r & 31)) & 1u);
+  return TBE_OK;
 }
 
 int tbe_set_pooling(tbe_handle h, int32_t pooling) {

@@ -56,6 +56,7 @@ struct TableMeta {
   uint32_t sets2;         // 0 = no second level for this table
   int32_t slot2_base;     // global id of second-level slot 0 of this table
   char *lines2;           // pinned host: second-level lines [sets2*ways, row_bytes]
+  uint32_t *init_bits;    // device: deferred initialisation, one bit per row (1 = the row has a value); null = off
 };
 
 // Device-side scalars of one batch (one per batch buffer).
@@ -214,7 +215,16 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
                               int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s);
 // write back the staged victims and (b != null) fetch ahead the rows b's batch inserts
-hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, int k, const uint32_t *rb_of_table,
+// Deferred initialisation on read (Section 5.4.2): a row of the backing tier has no value until it is
+// first fetched; the fetch then makes it up instead of reading it.
+struct DeferredInit {
+  const TableMeta *tm = nullptr;  // device table descriptions (init_bits); null = off
+  unsigned long long seed = 0;
+  float std = 0.f;
+};
+
+hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, const DeferredInit &di, int k,
+                           const uint32_t *rb_of_table,
                            unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
 // look up, for the rows cur inserts or bypasses, whether their backing-tier copy is stale
 // and where the current value is; then remove prev's entries from the map and enter cur's

@@ -17,6 +17,7 @@
 //              the staging area, the new rows move in; late rows are copied HBM to HBM from
 //              where the map pointed.  Also writes batch k's overflow copies back.
 // Host rows are reached through the pinned mapping, 16 lanes per row, 16 bytes per lane.
+#include <hip/hip_fp16.h>
 #include "tbe_internal.h"
 
 namespace tbe {
@@ -25,6 +26,49 @@ typedef unsigned long long u64;
 constexpr int kMoveLanes = 16;
 constexpr int kLinkBlocks = 192;  // workgroups of the transfer kernel that work
 constexpr int kLinkXcds = 2;      // ... all placed on this many of the 8 XCDs
+
+// ---- deferred initialisation: counter-based normal numbers of (seed, table, row, element) ----
+// One 64-bit hash (the finaliser of splitmix64) per element pair gives two 24-bit uniforms,
+// u1 in (0, 1] and u2 in [0, 1); z = sqrt(-2 ln u1) * (cos | sin)(2 pi u2).
+__device__ inline u64 mix64(u64 x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
+__device__ inline u64 init_table_key(u64 seed, int t) { return mix64(seed ^ ((u64)(t + 1) * 0xD1342543DE82EF95ull)); }
+
+// the 16 bytes of row `row` that start at element e0 (4 fp32 or 8 fp16 values), std * z each
+__device__ inline uint4 init_chunk(u64 table_key, uint32_t row, int dtype, uint32_t e0, float std) {
+  float z[8];
+  const int pairs = dtype == 0 ? 2 : 4;
+  for (int p = 0; p < pairs; p++) {
+    const u64 h = mix64(table_key + (u64)row * 0x2545F4914F6CDD1Dull + (u64)(e0 / 2 + p));
+    const float u1 = (float)((uint32_t)(h >> 40) + 1u) * (1.0f / 16777216.0f);
+    const float u2 = (float)((uint32_t)(h >> 8) & 0xFFFFFFu) * (1.0f / 16777216.0f);
+    const float rad = sqrtf(-2.0f * logf(u1));
+    float sn, cs;
+    sincospif(2.0f * u2, &sn, &cs);  // the angle 2 pi u2 without rounding 2 pi
+    z[2 * p] = std * (rad * cs);
+    z[2 * p + 1] = std * (rad * sn);
+  }
+  if (dtype == 0) return make_uint4(__float_as_uint(z[0]), __float_as_uint(z[1]), __float_as_uint(z[2]), __float_as_uint(z[3]));
+  uint32_t w[4];
+  for (int i = 0; i < 4; i++)
+    w[i] = (uint32_t)__half_as_ushort(__float2half_rn(z[2 * i])) | ((uint32_t)__half_as_ushort(__float2half_rn(z[2 * i + 1])) << 16);
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Has row `row` of table m a value yet?  If not, it gets one now: lane 0 of the group marks the
+// row and tells the others what the mark was before.
+__device__ inline bool needs_init(const TableMeta &m, uint32_t row, int lig) {
+  const uint32_t bit = 1u << (row & 31);
+  uint32_t before = 0;
+  if (lig == 0) before = atomicOr(m.init_bits + (row >> 5), bit);
+  before = __shfl(before, 0, kMoveLanes);
+  return (before & bit) == 0;
+}
 
 __device__ inline void copy_row(char *dst, const char *src, uint32_t bytes, int lig) {
   for (uint32_t c = lig * 16; c < bytes; c += kMoveLanes * 16) *(uint4 *)(dst + c) = *(const uint4 *)(src + c);
@@ -40,7 +84,11 @@ __global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCo
                                                        const uint32_t *__restrict__ byp_where, char *__restrict__ ovf,
                                                        char *const *__restrict__ l2v_src,
                                                        char *const *__restrict__ wb2_dst, char *out2_even,
-                                                       char *out2_odd, int k, u64 *bytes_h2d, u64 *bytes_d2h) {
+                                                       char *out2_odd, int k, const TableMeta *__restrict__ di_tm,
+                                                       u64 di_seed, float di_std,
+                                                       const uint32_t *__restrict__ ins_key,
+                                                       const uint32_t *__restrict__ byp_key, u64 *bytes_h2d,
+                                                       u64 *bytes_d2h) {
   // Workgroups are dealt to the 8 XCDs round robin; only those landing on the first
   // kLinkXcds work, so that the waves waiting on the host link sit on few CUs.
   if ((int)(blockIdx.x & 7) >= kLinkXcds) return;
@@ -57,16 +105,33 @@ __global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCo
     // issue the host read first, then the write-back, so both directions are busy
     uint4 fresh[4];
     uint32_t rb = 0;
-    bool fetch = false;
+    bool fetch = false, made_up = false;
     if (i < n_ins) {
       fetch = ins_where[i] == 0;
       if (fetch) {
-        rb = rb_of_table[ins_tab[i]];
-        const char *src = ins_src[i];
+        const int t = ins_tab[i];
+        rb = rb_of_table[t];
+        if (di_tm) {  // deferred initialisation: a row read for the first time gets its value here
+          const TableMeta &m = di_tm[t];
+          const uint32_t row = row_of_key(m, ins_key[i]);
+          made_up = needs_init(m, row, lig);
+          if (made_up) {
+            const u64 tk = init_table_key(di_seed, t);
+            const uint32_t esz = m.dtype == 0 ? 4u : 2u;
 #pragma unroll
-        for (int q = 0; q < 4; q++) {
-          const uint32_t c = lig * 16 + q * kMoveLanes * 16;
-          if (c < rb) fresh[q] = *(const uint4 *)(src + c);
+            for (int q = 0; q < 4; q++) {
+              const uint32_t c = lig * 16 + q * kMoveLanes * 16;
+              if (c < rb) fresh[q] = init_chunk(tk, row, m.dtype, c / esz, di_std);
+            }
+          }
+        }
+        if (!made_up) {
+          const char *src = ins_src[i];
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const uint32_t c = lig * 16 + q * kMoveLanes * 16;
+            if (c < rb) fresh[q] = *(const uint4 *)(src + c);
+          }
         }
       }
     }
@@ -111,12 +176,27 @@ __global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCo
         const uint32_t c = lig * 16 + q * kMoveLanes * 16;
         if (c < rb) *(uint4 *)(dst + c) = fresh[q];
       }
-      if (lig == 0) in_b += rb;
+      if (lig == 0 && !made_up) in_b += rb;
     }
     if (i < n_byp && byp_where[i] == 0) {  // bypassed rows of this batch: HBM copy for its training
-      const uint32_t brb = rb_of_table[byp_tab[i]];
-      copy_row(ovf + (size_t)i * st.stride, byp_src[i], brb, lig);
-      if (lig == 0) in_b += brb;
+      const int t = byp_tab[i];
+      const uint32_t brb = rb_of_table[t];
+      bool fresh_row = false;
+      if (di_tm) {
+        const TableMeta &m = di_tm[t];
+        const uint32_t row = row_of_key(m, byp_key[i]);
+        fresh_row = needs_init(m, row, lig);
+        if (fresh_row) {
+          const u64 tk = init_table_key(di_seed, t);
+          const uint32_t esz = m.dtype == 0 ? 4u : 2u;
+          for (uint32_t c = lig * 16; c < brb; c += kMoveLanes * 16)
+            *(uint4 *)(ovf + (size_t)i * st.stride + c) = init_chunk(tk, row, m.dtype, c / esz, di_std);
+        }
+      }
+      if (!fresh_row) {
+        copy_row(ovf + (size_t)i * st.stride, byp_src[i], brb, lig);
+        if (lig == 0) in_b += brb;
+      }
     }
   }
   for (int d = 32; d >= 1; d >>= 1) {
@@ -133,8 +213,8 @@ __global__ void clear_wb_kernel(int32_t *wb_n) {
   if (threadIdx.x == 0) wb_n[0] = 0;
 }
 
-hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, int k, const uint32_t *rb_of_table,
-                           u64 *bytes_h2d, u64 *bytes_d2h, hipStream_t s) {
+hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, const DeferredInit &di, int k,
+                           const uint32_t *rb_of_table, u64 *bytes_h2d, u64 *bytes_d2h, hipStream_t s) {
   // How many workgroups wait on the host link, and on how many CUs, decides how the link and
   // the HBM-bound kernels of the other streams slow each other (measured on the benchmark
   // workload, step time / forward kernel time while the transfer runs; alone the forward
@@ -149,7 +229,8 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l
                      b ? b->ins_src : nullptr, b ? b->ins_tab : nullptr, rb_of_table,
                      b ? b->ins_where : nullptr, b ? b->byp_src : nullptr, b ? b->byp_tab : nullptr,
                      b ? b->byp_where : nullptr, b ? b->ovf : nullptr, (b && l2.on) ? b->l2v_src : nullptr,
-                     l2.on ? l2.wb2_dst : nullptr, l2.out2[0], l2.out2[1], k, bytes_h2d, bytes_d2h);
+                     l2.on ? l2.wb2_dst : nullptr, l2.out2[0], l2.out2[1], k, b ? di.tm : nullptr, di.seed, di.std,
+                     b ? b->ins_key : nullptr, b ? b->byp_key : nullptr, bytes_h2d, bytes_d2h);
   hipLaunchKernelGGL(clear_wb_kernel, dim3(1), dim3(64), 0, s, st.wb_n);
   return hipGetLastError();
 }

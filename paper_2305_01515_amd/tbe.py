@@ -23,7 +23,7 @@ EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
            "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling",
-           "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats"]
+           "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
         l.tbe_set_policy.argtypes = [vp, i32]
         l.tbe_set_pooling.argtypes = [vp, i32]
         l.tbe_enable_second_level.argtypes = [vp, i32]
+        l.tbe_enable_deferred_init.argtypes = [vp, C.c_uint64, C.c_float]
+        l.tbe_export_initialised.argtypes = [vp, i32, vp]
         l.tbe_num_sets2.argtypes = [vp, i32]
         l.tbe_num_sets2.restype = i64
         l.tbe_export_second_level_state.argtypes = [vp, i32, vp, vp]
@@ -109,7 +111,7 @@ class TBE:
 
     def __init__(self, weights: Sequence[torch.Tensor], state: Sequence[torch.Tensor], cache_slots: Sequence[int],
                  ways: int, max_batch: int, max_lookups: int, overlap: bool = True, policy: str = "lru",
-                 pooling: str = "sum", second_level_factor: int = 0):
+                 pooling: str = "sum", second_level_factor: int = 0, deferred_init=None):
         self._h = C.c_void_p()
         T = len(weights)
         self.T, self.ways = T, ways
@@ -138,6 +140,9 @@ class TBE:
             self._check(lib().tbe_set_pooling(self._h, POOLINGS[pooling]), "tbe_set_pooling")
         if second_level_factor:
             self._check(lib().tbe_enable_second_level(self._h, second_level_factor), "tbe_enable_second_level")
+        if deferred_init is not None:  # (seed, std)
+            self._check(lib().tbe_enable_deferred_init(self._h, int(deferred_init[0]), float(deferred_init[1])),
+                        "tbe_enable_deferred_init")
 
     def _check(self, rc: int, what: str):
         if rc:
@@ -234,6 +239,11 @@ class TBE:
                     "tbe_get_second_level_stats")
         names = ("hits", "demotions", "evictions", "bypasses")
         return dict(zip(names, last.tolist())), dict(zip(names, total.tolist()))
+
+    def initialised(self, t: int) -> np.ndarray:
+        out = np.empty(self.weights[t].shape[0], dtype=np.uint8)
+        self._check(lib().tbe_export_initialised(self._h, t, out.ctypes.data), "tbe_export_initialised")
+        return out
 
     def cache_freq(self, t: int) -> np.ndarray:
         f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)

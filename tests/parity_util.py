@@ -84,10 +84,21 @@ def compare_forward(cfg, out_o: np.ndarray, out_g: np.ndarray, ctx: str):
         col += tc.dim
 
 
-def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str):
+def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None):
+    """only[t]: boolean mask of the rows to compare (deferred initialisation: the rows that have a value;
+    the others must still hold the NaN they were filled with, on both sides)"""
     step = 1 << 21  # rows per comparison chunk (keeps the fp64 temporaries small)
     for t, tc in enumerate(cfg.tables):
         wg, mg = Wp[t].numpy(), Mp[t].numpy()
+        if only is not None:
+            keep = only[t].astype(bool)
+            assert np.isnan(wg[~keep].astype(np.float32)).all() and np.isnan(Wn[t][~keep].astype(np.float32)).all(), \
+                f"{ctx}: a row of table {t} that was never read has been written"
+            e = vec_err(wg[keep], Wn[t][keep], floor=1e-3 * cfg.init_std)
+            assert e <= TOL[tc.dtype], f"{ctx}: initialised rows of table {t} off by {e:.3e}"
+            em = vec_err(mg[:, None], Mn[t][:, None], floor=1e-12)
+            assert em <= 1e-5, f"{ctx}: accumulators of table {t} off by {em:.3e}"
+            continue
         for r0 in range(0, tc.rows, step):
             r1 = min(tc.rows, r0 + step)
             e = vec_err(wg[r0:r1], Wn[t][r0:r1], floor=1e-3 * cfg.init_std)
@@ -98,7 +109,7 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str):
 
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
-               pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None):
+               pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None, deferred_init=None):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -110,15 +121,20 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
 
     T = cfg.num_tables
     Wn, Mn, Wp, Mp = make_backing(cfg, device=init_device)
+    if deferred_init is not None:  # (seed, std): the tables start without values; nothing may read the NaN
+        for w, wn in zip(Wp, Wn):
+            w.fill_(float("nan"))
+            wn.fill(np.nan)
     slots = [tc.cache_slots for tc in cfg.tables]
     slots2 = [second_level_factor * (s // cfg.ways) * cfg.ways for s in slots] if second_level_factor else None
-    o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads, policy=policy, pooling=pooling, second_level_slots=slots2)
+    o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads, policy=policy, pooling=pooling, second_level_slots=slots2,
+               deferred_init=deferred_init)
     stream = synth.BatchStream(cfg, device="cpu")
     batches = [stream.next() for _ in range(steps)]
     if max_lookups is None:
         max_lookups = max(int(b[0].numel()) for b in batches) + 1
     g = TBE(Wp, Mp, slots, cfg.ways, max_batch or cfg.batch, max_lookups, overlap=overlap, policy=policy, pooling=pooling,
-            second_level_factor=second_level_factor)
+            second_level_factor=second_level_factor, deferred_init=deferred_init)
     dev = [(i.to(device), f.to(device)) for i, f in batches]
     snaps = {}
 
@@ -179,7 +195,12 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     assert so == sg, f"total counters differ: oracle {so} gpu {sg}"
     o.flush()
     g.flush()
-    compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush")
+    only = None
+    if deferred_init is not None:
+        only = [o.initialised(t) for t in range(T)]
+        for t in range(T):
+            assert np.array_equal(only[t], g.initialised(t)), f"rows of table {t} that have a value differ"
+    compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush", only=only)
     st = g.stats()
     st["second_level_total"] = g.second_level_stats()[1]
     g.close()

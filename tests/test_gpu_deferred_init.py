@@ -1,0 +1,69 @@
+"""GPU parity of deferred initialisation on read (Section 5.4.2): the tables start filled with
+NaN on both sides, so any read of a row that has no value yet would poison the outputs; the
+rows that got a value, the pooled outputs and (after flush) those rows' trained values must
+agree with the oracle, the other rows must still be NaN."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2305_01515_amd import synth
+from parity_util import run_parity
+from test_gpu_parity import small_cfg
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", [synth.FP32, synth.FP16])
+@pytest.mark.parametrize("ways", [1, 8, 64])
+def test_small_mixed_model_deferred(dtype, ways):
+    cfg = small_cfg(dtype, ways, seed=50 + ways)
+    st = run_parity(cfg, steps=6, order="serial", deferred_init=(1234 + ways, cfg.init_std))
+    assert st["total"]["bypasses"] > 0 and st["total"]["evictions"] > 0
+
+
+@pytest.mark.parametrize("order", ["inline", "ahead", "early"])
+def test_deferred_call_orders_with_second_level(order):
+    cfg = small_cfg(synth.FP16, 16, seed=83)
+    run_parity(cfg, steps=8, order=order, deferred_init=(9, cfg.init_std), second_level_factor=2)
+
+
+def test_main_shape_scaled_deferred():
+    cfg = synth.config_main(tables=4, rows=62500, batch=512)
+    st = run_parity(cfg, steps=8, order="ahead", deferred_init=(2024, cfg.init_std), check_every=3)
+    # rows made up on the GPU never crossed the link
+    assert st["h2d_bytes"] < st["total"]["inserts"] * 256
+
+
+def test_generated_values_are_those_of_the_generator():
+    """one table without cache: every row is read once as a bypass, trained with a zero gradient and
+    written back: the backing tier then holds the generator's values"""
+    from oracle import lib as olib
+    from paper_2305_01515_amd.tbe import TBE
+    H, D, seed, std = 512, 24, 31337, 0.7
+    for dt, tol in ((torch.float32, 2e-6), (torch.float16, 1e-3)):
+        w = torch.full((H, D), float("nan"), dtype=dt).pin_memory()
+        m = torch.zeros(H, dtype=torch.float32).pin_memory()
+        g = TBE([w], [m], [0], 4, H, H + 1, deferred_init=(seed, std))
+        idx = torch.arange(H, device="cuda")
+        off = torch.arange(H + 1, device="cuda")
+        g.forward(idx, off)
+        g.backward_update(torch.zeros(H, D, device="cuda"), 0.1, 1e-8)
+        g.flush()
+        assert g.initialised(0).all()
+        g.close()
+        ref = np.array([[std * olib().orc_init_normal(seed, 0, r, d) for d in range(D)] for r in range(H)])
+        got = w.numpy().astype(np.float64)
+        assert np.abs(got - ref).max() <= tol * np.abs(ref).max()
+
+
+def test_deferred_init_errors():
+    from paper_2305_01515_amd.tbe import TBE, lib
+    w = [torch.zeros(100, 8, dtype=torch.float32).pin_memory()]
+    m = [torch.zeros(100, dtype=torch.float32).pin_memory()]
+    g = TBE(w, m, [16], 4, 8, 64)
+    flags = np.zeros(100, dtype=np.uint8)
+    assert lib().tbe_export_initialised(g._h, 0, flags.ctypes.data) == -3
+    assert lib().tbe_enable_deferred_init(g._h, 1, -1.0) == -1
+    assert lib().tbe_enable_deferred_init(g._h, 1, 0.5) == 0
+    assert lib().tbe_enable_deferred_init(g._h, 1, 0.5) == -3
+    g.close()
