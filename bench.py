@@ -215,6 +215,8 @@ def main():
                     help="replacement policy; lru is the benchmark's, lfu for the comparison the paper makes")
     ap.add_argument("--second-level", type=int, default=0,
                     help="factor of a second-level cache in pinned host memory (0 = none, the benchmark's)")
+    ap.add_argument("--deferred-init", action="store_true",
+                    help="rows get their initial values on first read, on the GPU (not the benchmark's setting)")
     ap.add_argument("--pooling", default="sum", choices=["sum", "mean"], help="sum is the benchmark's")
     ap.add_argument("--resident-fraction", type=float, default=-1.0,
                     help="hetero: share of the HBM budget given to whole tables chosen by the placement solver "
@@ -274,7 +276,7 @@ def main():
                 f"{'uniform' if args.alpha <= 0 else 'Zipf %g' % args.alpha}, 64-way cache {args.cache_frac:.0%} of rows")
     if args.policy != "lru":
         desc = desc.replace("LRU ", "").replace("-way cache", "-way LFU cache")
-    if args.workload != "main" or args.policy != "lru" or args.pooling != "sum" or args.second_level:
+    if args.workload != "main" or args.policy != "lru" or args.pooling != "sum" or args.second_level or args.deferred_init:
         args.no_cpu_baseline = True
     T = cfg.num_tables
 
@@ -314,7 +316,8 @@ def main():
                "sample": f"first batches of the same stream from a cold cache ({n} lookups), oracle -O2, OpenMP over tables"}
 
     g = TBE(Wp, Mp, [tc.cache_slots for tc in cfg.tables], cfg.ways, cfg.batch, max_n + 1, overlap=not args.no_overlap,
-            policy=args.policy, pooling=args.pooling, second_level_factor=args.second_level)
+            policy=args.policy, pooling=args.pooling, second_level_factor=args.second_level,
+            deferred_init=(cfg.seed, cfg.init_std) if args.deferred_init else None)
 
     def run(lo, hi):
         # next-batch prefetch is issued ahead of the current batch's training
@@ -395,7 +398,7 @@ def main():
         "config": {"workload": desc,
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
                    "overlap": not args.no_overlap, "policy": args.policy, "pooling": args.pooling,
-                   "second_level_factor": args.second_level},
+                   "second_level_factor": args.second_level, "deferred_init": args.deferred_init},
         # The HBM-bound kernel that moves most algorithmic bytes on the hit path.  Rows are counted once
         # per lookup (the paper's Eq. 3); repeats of hot rows are served by L2, so achieved can exceed what
         # HBM alone delivers -- `traffic` is what the counters saw.  ms_per_launch is measured in the timed,
@@ -446,7 +449,7 @@ def main():
         second_level = {k: (l2b[k] - l2a[k]) / npf for k in l2b}
         second_level["hit_rate_of_first_level_misses"] = (l2b["hits"] - l2a["hits"]) / max(1, tot["inserts"] + tot["bypasses"])
     g.close()
-    if args.workload == "main" and not args.second_level and not args.no_control:
+    if args.workload == "main" and not args.second_level and not args.no_control and not args.deferred_init:
         res["all_hit_control"] = all_hit_control(TBE, cfg, Wp, Mp, batches[Wm + K], grads, out, max_n, hit_b,
                                                  not args.no_overlap)
     if args.second_level:
