@@ -116,7 +116,7 @@ class Oracle:
         rc = lib().orc_set_policy(self.h, {"lru": 0, "lfu": 1}[policy])
         if rc:
             raise OracleError(rc, "set_policy")
-        rc = lib().orc_set_pooling(self.h, {"sum": 0, "mean": 1}[pooling])
+        rc = lib().orc_set_pooling(self.h, {"sum": 0, "mean": 1, "max": 2}[pooling])
         if rc:
             raise OracleError(rc, "set_pooling")
         if second_level_slots is not None:

@@ -57,6 +57,10 @@
  *     vector is the sum divided by the number of lookups of the bag (a row looked up twice
  *     counts twice; an empty bag gives zeros), so a lookup of a bag of L lookups hands
  *     1/L of the bag's output gradient to its row;
+ *   - max pooling, the third pooling mode [Section 2.1.1]: element d of the pooled vector is
+ *     the largest element d among the bag's rows (an empty bag gives zeros); in backward the
+ *     bag's output gradient of element d goes to the lookup that supplied the maximum, the
+ *     first such lookup of the bag when several tie, and to no other;
  *   - LFU, the other policy the paper tried [Section 5.5.2; it gives no details]: every
  *     entry also counts the lookups of its row since it was inserted (a row looked up c
  *     times in a batch adds c; the count saturates at INT32_MAX and is forgotten at
@@ -84,6 +88,7 @@
 
 #define ORC_POOL_SUM 0
 #define ORC_POOL_MEAN 1
+#define ORC_POOL_MAX 2
 
 #define ORC_LRU 0
 #define ORC_LFU 1
@@ -148,6 +153,8 @@ typedef struct {
   int64_t *indices;
   int64_t *offsets;
   int64_t cap_idx, cap_off;
+  int64_t *argmax;     /* max pooling: [B * sum of dims] lookup (position in indices) that supplied each maximum, -1 = empty bag */
+  int64_t cap_arg;
   int forwarded, prefetched;
   int threads;
   orc_stats last, total;
@@ -215,7 +222,7 @@ void orc_destroy(void *hp) {
   orc *h = (orc *)hp;
   if (!h) return;
   for (int t = 0; t < h->T; t++) free_table(&h->tab[t]);
-  free(h->tab); free(h->indices); free(h->offsets); free(h);
+  free(h->tab); free(h->indices); free(h->offsets); free(h->argmax); free(h);
 }
 
 void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
@@ -321,7 +328,7 @@ int orc_export_initialised(void *hp, int32_t t, unsigned char *out) {
 /* pooling mode; only before the first batch */
 int orc_set_pooling(void *hp, int32_t pooling) {
   orc *h = (orc *)hp;
-  if (!h || (pooling != ORC_POOL_SUM && pooling != ORC_POOL_MEAN)) return ORC_EINVAL;
+  if (!h || (pooling != ORC_POOL_SUM && pooling != ORC_POOL_MEAN && pooling != ORC_POOL_MAX)) return ORC_EINVAL;
   if (h->k != 0) return ORC_EORDER;
   h->pooling = pooling;
   return ORC_OK;
@@ -613,6 +620,12 @@ int orc_forward(void *hp, float *out) {
   int64_t sumD = 0;
   for (int t = 0; t < h->T; t++) sumD += h->tab[t].dim;
   int failed = 0;
+  if (h->pooling == ORC_POOL_MAX && (int64_t)h->B * sumD > h->cap_arg) {
+    free(h->argmax);
+    h->cap_arg = (int64_t)h->B * sumD;
+    h->argmax = (int64_t *)malloc(sizeof(int64_t) * (size_t)h->cap_arg);
+    if (!h->argmax) { h->cap_arg = 0; return ORC_ENOMEM; }
+  }
 #pragma omp parallel for schedule(dynamic, 1) num_threads(h->threads)
   for (int t = 0; t < h->T; t++) {
     orc_table *tb = &h->tab[t];
@@ -622,12 +635,22 @@ int orc_forward(void *hp, float *out) {
     if (!acc) { failed = 1; continue; }
     for (int32_t b = 0; b < h->B; b++) {
       for (int d = 0; d < tb->dim; d++) acc[d] = 0.0;
-      for (int64_t j = h->offsets[(int64_t)t * h->B + b]; j < h->offsets[(int64_t)t * h->B + b + 1]; j++) {
+      int64_t first = h->offsets[(int64_t)t * h->B + b];
+      for (int64_t j = first; j < h->offsets[(int64_t)t * h->B + b + 1]; j++) {
         void *src; int64_t at; float *st_unused;
         locate_row(tb, h->ways, h->indices[j], &src, &at, &st_unused);
         int64_t base = at * tb->dim;
+        if (h->pooling == ORC_POOL_MAX) { /* the first lookup supplies the maximum until a larger value comes */
+          for (int d = 0; d < tb->dim; d++) {
+            double v = load_elem(src, tb->dtype, base + d);
+            if (j == first || v > acc[d]) { acc[d] = v; h->argmax[(int64_t)b * sumD + col + d] = j; }
+          }
+          continue;
+        }
         for (int d = 0; d < tb->dim; d++) acc[d] += load_elem(src, tb->dtype, base + d);
       }
+      if (h->pooling == ORC_POOL_MAX && first == h->offsets[(int64_t)t * h->B + b + 1])
+        for (int d = 0; d < tb->dim; d++) h->argmax[(int64_t)b * sumD + col + d] = -1;
       int64_t L = h->offsets[(int64_t)t * h->B + b + 1] - h->offsets[(int64_t)t * h->B + b];
       double div = (h->pooling == ORC_POOL_MEAN && L > 0) ? (double)L : 1.0;
       for (int d = 0; d < tb->dim; d++) out[(int64_t)b * sumD + col + d] = (float)(acc[d] / div);
@@ -667,7 +690,10 @@ int orc_backward_update(void *hp, const float *grad_out, float lr, float eps) {
       double div = h->pooling == ORC_POOL_MEAN ? (double)L : 1.0;
       for (int64_t j = h->offsets[(int64_t)t * h->B + b]; j < h->offsets[(int64_t)t * h->B + b + 1]; j++) {
         int64_t u = lower_bound(tb->uniq, U, h->indices[j]);
-        for (int d = 0; d < tb->dim; d++) g[u * tb->dim + d] += (double)grad_out[(int64_t)b * sumD + col + d] / div;
+        for (int d = 0; d < tb->dim; d++) {
+          if (h->pooling == ORC_POOL_MAX && h->argmax[(int64_t)b * sumD + col + d] != j) continue;
+          g[u * tb->dim + d] += (double)grad_out[(int64_t)b * sumD + col + d] / div;
+        }
       }
     }
     for (int64_t u = 0; u < U; u++) {
