@@ -106,6 +106,6 @@ def test_pooling_is_fixed_before_the_first_batch():
     from oracle import lib
     W, M = make_tables([10], [4], [np.float32])
     o = Oracle(W, M, [4], ways=2)
-    assert lib().orc_set_pooling(o.h, 2) != 0
+    assert lib().orc_set_pooling(o.h, 3) != 0
     o.prefetch(np.array([1]), np.array([0, 1]))
     assert lib().orc_set_pooling(o.h, 1) != 0
