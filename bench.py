@@ -217,7 +217,7 @@ def main():
                     help="factor of a second-level cache in pinned host memory (0 = none, the benchmark's)")
     ap.add_argument("--deferred-init", action="store_true",
                     help="rows get their initial values on first read, on the GPU (not the benchmark's setting)")
-    ap.add_argument("--pooling", default="sum", choices=["sum", "mean"], help="sum is the benchmark's")
+    ap.add_argument("--pooling", default="sum", choices=["sum", "mean", "max"], help="sum is the benchmark's")
     ap.add_argument("--resident-fraction", type=float, default=-1.0,
                     help="hetero: share of the HBM budget given to whole tables chosen by the placement solver "
                          "(Eq. 6); negative = plain split in proportion to lookups x dim")

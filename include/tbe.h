@@ -197,15 +197,20 @@ int tbe_enable_deferred_init(tbe_handle h, uint64_t seed, float std);
 int tbe_export_initialised(tbe_handle h, int32_t table, uint8_t *h_flags);
 
 /*
- * Pooling mode (Section 2.1.1 names sum, mean and max; sum and mean are built).
+ * Pooling mode (Section 2.1.1 names sum, mean and max).
  * TBE_POOL_SUM, the default.  TBE_POOL_MEAN: tbe_forward divides every pooled vector by the
  * number of lookups of its bag (a row looked up twice counts twice; an empty bag gives
  * zeros) and tbe_backward_update hands a lookup of a bag of L lookups 1/L of the bag's
- * output gradient.  Only before the first tbe_prefetch (TBE_EORDER afterwards); TBE_EINVAL
- * for an unknown mode.
+ * output gradient.  TBE_POOL_MAX: element d of a pooled vector is the largest element d among
+ * the bag's rows (an empty bag gives zeros), and in tbe_backward_update element d of the bag's
+ * output gradient goes to the lookup that supplied that maximum -- the first such lookup of
+ * the bag when several tie -- and to no other (the first call with TBE_POOL_MAX allocates the
+ * record of who supplied each maximum).  Only before the first tbe_prefetch (TBE_EORDER
+ * afterwards); TBE_EINVAL for an unknown mode.
  */
 #define TBE_POOL_SUM 0
 #define TBE_POOL_MEAN 1
+#define TBE_POOL_MAX 2
 int tbe_set_pooling(tbe_handle h, int32_t pooling);
 
 /*

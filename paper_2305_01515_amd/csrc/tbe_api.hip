@@ -243,6 +243,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
   const bool in_flight = h->n_pend > 0 || h->current >= 0;
   b.d_indices = d_indices; b.d_offsets = d_offsets; b.batch = batch; b.n = n; b.k = ++h->k;
   b.mean = h->pooling == TBE_POOL_MEAN;
+  b.maxp = h->pooling == TBE_POOL_MAX;
   h->total_lookups += n;
   h->last_buf = bi;
   if (h->as != h->cs) {
@@ -749,8 +750,15 @@ int tbe_export_initialised(tbe_handle h, int32_t table, uint8_t *h_flags) {
 
 int tbe_set_pooling(tbe_handle h, int32_t pooling) {
   if (!h) return TBE_EINVAL;
-  if (pooling != TBE_POOL_SUM && pooling != TBE_POOL_MEAN) return fail(h, TBE_EINVAL, "set_pooling: unknown pooling mode");
+  if (pooling != TBE_POOL_SUM && pooling != TBE_POOL_MEAN && pooling != TBE_POOL_MAX)
+    return fail(h, TBE_EINVAL, "set_pooling: unknown pooling mode");
   if (h->k != 0) return fail(h, TBE_EORDER, "set_pooling: batches have been prefetched already");
+  if (pooling == TBE_POOL_MAX && !h->buf[0].argpos) {  // who supplied each maximum, and the lookups' positions in their bags
+    for (int i = 0; i < kBatchBufs; i++) {
+      HIP_TRY(h, h->mem.get(&h->buf[i].argpos, 4 * (size_t)h->max_batch * (size_t)h->g.sum_dim));
+      HIP_TRY(h, h->mem.get(&h->buf[i].sorted_within, 4 * (size_t)std::max<int64_t>(h->max_lookups, 1)));
+    }
+  }
   h->pooling = pooling;
   return TBE_OK;
 }

@@ -129,6 +129,8 @@ struct DedupOp {
   const int32_t *bag_of_pos;
   const BatchCounters *cnt;  // cnt->packed: the payload carries the bag
   int within_bits;
+  const int64_t *offsets;
+  int32_t *sorted_within;    // max pooling only (else null): position of the lookup inside its bag
   uint32_t *uid_sorted;
   int32_t *sorted_bag;
   uint32_t *uniq_key;
@@ -139,7 +141,11 @@ struct DedupOp {
   __device__ void emit(int i, int, u64 pre, u64 f) const {
     const uint32_t u = (uint32_t)(pre & 0xFFFFFFFFull) + (uint32_t)f - 1u;
     uid_sorted[i] = u;
-    sorted_bag[i] = cnt->packed ? (int32_t)(pos[i] >> within_bits) : bag_of_pos[pos[i]];
+    const uint32_t p = pos[i];
+    const int32_t bag = cnt->packed ? (int32_t)(p >> within_bits) : bag_of_pos[p];
+    sorted_bag[i] = bag;
+    if (sorted_within)
+      sorted_within[i] = cnt->packed ? (int32_t)(p & ((1u << within_bits) - 1u)) : (int32_t)((int64_t)p - offsets[bag]);
     if (f) {
       const uint32_t k = key[i];
       uniq_key[u] = k;
@@ -183,25 +189,28 @@ __device__ inline void worklist_chunk(int n, int &w0, int &w1) {
 }
 
 // counts of the wavefront's chunk: (2..kLongRun, kLongRun+1..kHugeRun, more)
-__device__ inline void worklist_tally(const int32_t *__restrict__ run_off, int w0, int w1, int (&c)[3]) {
+__device__ inline void worklist_tally(const int32_t *__restrict__ run_off, int w0, int w1, int huge_from,
+                                      int (&c)[3]) {
   const int lane = threadIdx.x & 63;
   c[0] = c[1] = c[2] = 0;
   for (int u0 = w0; u0 < w1; u0 += 64) {
     const int u = u0 + lane;
     const int len = u < w1 ? run_off[u + 1] - run_off[u] : 0;
     c[0] += __popcll(__ballot(len >= 2 && len <= kLongRun));
-    c[1] += __popcll(__ballot(len > kLongRun && len <= kHugeRun));
-    c[2] += __popcll(__ballot(len > kHugeRun));
+    c[1] += __popcll(__ballot(len > kLongRun && len <= huge_from));
+    c[2] += __popcll(__ballot(len > huge_from));
   }
 }
 
+// huge_from: rows with more lookups than this go to the huge list (kHugeRun; INT_MAX under max
+// pooling, whose backward has no huge-row kernel: such rows are handled as long ones)
 __global__ __launch_bounds__(256) void worklist_count_kernel(const int32_t *__restrict__ run_off, int32_t *wl,
-                                                             const BatchCounters *cnt) {
+                                                             int huge_from, const BatchCounters *cnt) {
   __shared__ int s_cnt[4][3];
   if (cnt->err) return;
   int w0, w1, c[3];
   worklist_chunk(cnt->n_uniq, w0, w1);
-  worklist_tally(run_off, w0, w1, c);
+  worklist_tally(run_off, w0, w1, huge_from, c);
   if ((threadIdx.x & 63) == 0)
     for (int k = 0; k < 3; k++) s_cnt[threadIdx.x >> 6][k] = c[k];
   __syncthreads();
@@ -210,7 +219,8 @@ __global__ __launch_bounds__(256) void worklist_count_kernel(const int32_t *__re
 
 __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__restrict__ run_off,
                                                             const int32_t *__restrict__ wl, int32_t *mid_idx,
-                                                            int32_t *items, int32_t *huge, BatchCounters *cnt) {
+                                                            int32_t *items, int32_t *huge, int huge_from,
+                                                            BatchCounters *cnt) {
   __shared__ int s_cnt[4][3];
   __shared__ int s_before[4][3];
   __shared__ int s_base[4][3];
@@ -219,7 +229,7 @@ __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__res
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   int w0, w1, c[3];
   worklist_chunk(cnt->n_uniq, w0, w1);
-  worklist_tally(run_off, w0, w1, c);
+  worklist_tally(run_off, w0, w1, huge_from, c);
   int before[3] = {0, 0, 0};  // rows of each kind in the workgroups before this one
   for (int b = threadIdx.x; b < (int)blockIdx.x; b += 256)
     for (int k = 0; k < 3; k++) before[k] += wl[b * 4 + k];
@@ -246,8 +256,8 @@ __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__res
     const int u = u0 + lane;
     const int len = u < w1 ? run_off[u + 1] - run_off[u] : 0;
     const bool is_mid = len >= 2 && len <= kLongRun;
-    const bool is_item = len > kLongRun && len <= kHugeRun;
-    const bool is_huge = len > kHugeRun;
+    const bool is_item = len > kLongRun && len <= huge_from;
+    const bool is_huge = len > huge_from;
     const uint64_t bm = __ballot(is_mid), bi = __ballot(is_item), bh = __ballot(is_huge);
     if (is_mid) mid_idx[o_mid + __popcll(bm & lt_mask)] = u;
     if (is_item) items[o_item + __popcll(bi & lt_mask)] = u;
@@ -657,14 +667,16 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
                               int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s) {
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
-  DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.cnt, g.within_bits, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
+  DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.cnt, g.within_bits, b.d_offsets,
+            b.maxp ? b.sorted_within : nullptr, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
             b.uniq_tab};
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
   run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
-  hipLaunchKernelGGL(worklist_count_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, b.cnt);
+  const int huge_from = b.maxp ? 0x7FFFFFFF : kHugeRun;
+  hipLaunchKernelGGL(worklist_count_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, huge_from, b.cnt);
   hipLaunchKernelGGL(worklist_emit_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, b.mid_idx, b.items,
-                     b.huge, b.cnt);
+                     b.huge, huge_from, b.cnt);
   hipLaunchKernelGGL(huge_group_kernel, dim3(1), dim3(1024), 0, s, tm, g.T, b.huge, b.uniq_tab, b.huge_sorted, b.hchunks,
                      b.hg_count, b.cnt);
   hipLaunchKernelGGL(huge_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.huge, b.uniq_tab, b.run_off,

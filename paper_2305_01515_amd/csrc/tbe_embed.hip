@@ -85,6 +85,73 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
   }
 }
 
+// Max pooling (Section 2.1.1): element d of the pooled vector is the largest element d among the
+// bag's rows; `argpos` records, per pooled element, the position inside the bag of the lookup
+// that supplied it -- the first one when several tie (lookups are visited in bag order), -1 for
+// an empty bag, whose pooled vector is zero.  The backward sends the gradient there.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void forward_max_kernel(const TableMeta *__restrict__ tm,
+                                                          const int32_t *__restrict__ class_tables, int B, int sum_dim,
+                                                          const int64_t *__restrict__ offsets,
+                                                          const uint32_t *__restrict__ loc,
+                                                          const char *__restrict__ ovf, uint32_t ovf_stride,
+                                                          float *__restrict__ out, int32_t *__restrict__ argpos,
+                                                          const BatchCounters *cnt) {
+  constexpr int EPL = Elems<DT>::n;
+  constexpr int R = G < 4 ? G : 4;
+  if (cnt->err) return;
+  const int vb = xcd_block_position(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
+  const int t = class_tables[vb / gridDim.x];
+  const TableMeta &m = tm[t];
+  const int b = (vb % gridDim.x) * (256 / G) + threadIdx.x / G;
+  const int lig = threadIdx.x % G;
+  if (b >= B) return;
+  const bool active = lig * EPL < m.dim;
+  const int64_t lo = offsets[(int64_t)t * B + b], hi = offsets[(int64_t)t * B + b + 1];
+  const char *lines = m.lines;
+  const uint32_t rb = m.row_bytes;
+  const int slot_base = m.slot_base;
+  float best[EPL];
+  int who[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; e++) { best[e] = 0.f; who[e] = -1; }
+  for (int64_t j0 = lo; j0 < hi; j0 += G) {
+    const int nq = (int)((hi - j0) < G ? (hi - j0) : G);
+    const uint32_t my_loc = lig < nq ? loc[j0 + lig] : 0u;
+    for (int q = 0; q < nq; q += R) {
+      uint4 v[R];
+#pragma unroll
+      for (int x = 0; x < R; x++) {
+        const uint32_t l = __shfl(my_loc, (q + x) & (G - 1), G);
+        const uint32_t ix = l & kLocIndex;
+        const char *p = (l & kLocOverflow) ? ovf + (size_t)ix * ovf_stride : lines + (size_t)((int)ix - slot_base) * rb;
+        v[x] = (active && q + x < nq) ? *(const uint4 *)(p + lig * 16) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int x = 0; x < R; x++) {  // in bag order: a later lookup wins only with a larger value
+        if (q + x >= nq) continue;
+        float f[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; e++) f[e] = 0.f;
+        accumulate<DT>(f, v[x]);
+        const int within = (int)(j0 - lo) + q + x;
+#pragma unroll
+        for (int e = 0; e < EPL; e++)
+          if (who[e] < 0 || f[e] > best[e]) { best[e] = f[e]; who[e] = within; }
+      }
+    }
+  }
+  if (active) {
+    float *o = out + (size_t)b * sum_dim + m.col + lig * EPL;
+    int32_t *a = argpos + (size_t)b * sum_dim + m.col + lig * EPL;
+#pragma unroll
+    for (int e = 0; e < EPL; e += 4) {
+      *(float4 *)(o + e) = make_float4(best[e], best[e + 1], best[e + 2], best[e + 3]);
+      *(int4 *)(a + e) = make_int4(who[e], who[e + 1], who[e + 2], who[e + 3]);
+    }
+  }
+}
+
 // --------------------------------------------------------------------------------------
 // backward
 // --------------------------------------------------------------------------------------
@@ -151,17 +218,26 @@ __device__ inline RowRef locate(const TableMeta &m, uint32_t key, int slot, char
 // lanes: the bag ids are read G at a time (coalesced) and handed round by shuffles, four
 // gradient rows are in flight per lane.  `stride_chunks` > 1 lets several groups share a
 // range chunk-wise (group `first_chunk` of `stride_chunks`).  Summation order is fixed.
-template <int DT, int G, bool MEAN>
+// MODE: kSum, kMean (every gradient row weighs 1 / lookups of its bag, from inv_len) or kMax (a
+// lookup receives element d of its bag's gradient only if it supplied the maximum: argbase points
+// at the row's columns of the recorded positions, sorted_within gives the lookup's own position).
+constexpr int kSum = 0, kMean = 1, kMax = 2;
+
+template <int DT, int G, int MODE>
 __device__ inline void reduce_grads(float (&g)[Elems<DT>::n], const float *gbase, const int32_t *sorted_bag, int bag0,
                                     int sum_dim, int i0, int i1, int first_chunk, int stride_chunks, int lig,
-                                    bool active, const float *inv_len) {
+                                    bool active, const float *inv_len, const int32_t *argbase,
+                                    const int32_t *sorted_within) {
   constexpr int EPL = Elems<DT>::n;
+  constexpr bool MEAN = MODE == kMean;
   for (int base = i0 + first_chunk * G; base < i1; base += stride_chunks * G) {
     const int nq = (i1 - base) < G ? (i1 - base) : G;
     const int my_gbag = lig < nq ? sorted_bag[base + lig] : bag0;
     const int my_bag = my_gbag - bag0;
     float my_w = 0.f;  // mean pooling: the weight 1/L of the lookup's bag
     if (MEAN) my_w = lig < nq ? inv_len[my_gbag] : 0.f;
+    int my_within = -2;  // max pooling: the lookup's position inside its bag
+    if (MODE == kMax) my_within = lig < nq ? sorted_within[base + lig] : -2;
     for (int q = 0; q < nq; q += 4) {
       float4 v[4][EPL / 4];
       float w[4];
@@ -169,10 +245,23 @@ __device__ inline void reduce_grads(float (&g)[Elems<DT>::n], const float *gbase
       for (int x = 0; x < 4; x++) {
         const int bq = __shfl(my_bag, (q + x) & (G - 1), G);
         if (MEAN) w[x] = __shfl(my_w, (q + x) & (G - 1), G);
+        int within = 0;
+        if (MODE == kMax) within = __shfl(my_within, (q + x) & (G - 1), G);
         const float *p = gbase + (size_t)bq * sum_dim;
         const bool ok = active && (q + x < nq);
 #pragma unroll
         for (int e = 0; e < EPL / 4; e++) v[x][e] = ok ? *(const float4 *)(p + 4 * e) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (MODE == kMax && ok) {
+          const int32_t *a = argbase + (size_t)bq * sum_dim;
+#pragma unroll
+          for (int e = 0; e < EPL / 4; e++) {
+            const int4 who = *(const int4 *)(a + 4 * e);
+            if (who.x != within) v[x][e].x = 0.f;
+            if (who.y != within) v[x][e].y = 0.f;
+            if (who.z != within) v[x][e].z = 0.f;
+            if (who.w != within) v[x][e].w = 0.f;
+          }
+        }
       }
 #pragma unroll
       for (int x = 0; x < 4; x++)
@@ -291,9 +380,107 @@ __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *_
   }
 }
 
+// The same for max pooling: the row receives the elements of the bag's gradient whose maximum
+// its lookup supplied (recorded by the forward), so the masked gradient and its sum of squares
+// differ from row to row.  Rows with exactly one lookup in the batch, bag by bag, the bag's
+// gradient slice and the recorded positions of its elements in registers.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void backward_single_max_kernel(const TableMeta *__restrict__ tm,
+                                                              const int32_t *__restrict__ class_tables, int B,
+                                                              int sum_dim, const int64_t *__restrict__ indices,
+                                                              const int64_t *__restrict__ offsets,
+                                                              const uint32_t *__restrict__ loc,
+                                                              const float *__restrict__ grad_out, float lr, float eps,
+                                                              char *__restrict__ ovf, uint32_t ovf_stride,
+                                                              const int32_t *__restrict__ argpos,
+                                                              const BatchCounters *cnt) {
+  constexpr int EPL = Elems<DT>::n;
+  if (cnt->err) return;
+  const int t = class_tables[blockIdx.y];
+  const TableMeta &m = tm[t];
+  const int b = blockIdx.x * (256 / G) + threadIdx.x / G;
+  const int lig = threadIdx.x % G;
+  if (b >= B) return;
+  const int64_t lo = offsets[(int64_t)t * B + b], hi = offsets[(int64_t)t * B + b + 1];
+  if (lo == hi) return;
+  const bool active = lig * EPL < m.dim;
+  char *lines = m.lines;
+  float *dev_m = m.dev_m;
+  const uint32_t rb = m.row_bytes;
+  const int slot_base = m.slot_base;
+  const int gshift = (threadIdx.x & 63) / G * G;  // first lane of this group inside the wavefront
+  float g[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; e++) g[e] = 0.f;
+  if (active) load_grad<DT>(g, grad_out + (size_t)b * sum_dim + m.col + lig * EPL);
+  int aw[EPL];  // who supplied the maximum of this lane's elements
+#pragma unroll
+  for (int e = 0; e < EPL; e++) aw[e] = -1;
+  if (active) {
+    const int32_t *a = argpos + (size_t)b * sum_dim + m.col + lig * EPL;
+#pragma unroll
+    for (int e = 0; e < EPL; e += 4) {
+      const int4 w4 = *(const int4 *)(a + e);
+      aw[e] = w4.x; aw[e + 1] = w4.y; aw[e + 2] = w4.z; aw[e + 3] = w4.w;
+    }
+  }
+  const float inv_dim = 1.0f / (float)m.dim;
+  for (int64_t j0 = lo; j0 < hi; j0 += G) {
+    const int nq = (int)((hi - j0) < G ? (hi - j0) : G);
+    uint32_t my_loc = 0u;
+    int my_row = 0;
+    if (lig < nq) {
+      my_loc = loc[j0 + lig];
+      if (my_loc & kLocSingle) my_row = (int)indices[j0 + lig];
+    }
+    uint64_t todo = __ballot((my_loc & kLocSingle) != 0) >> gshift;  // the group's single-lookup rows
+    if (G < 64) todo &= (1ull << G) - 1ull;
+    while (todo) {
+      char *w[4];
+      float *mp[4];
+      float m_old[4];
+      uint4 raw[4];
+      int within[4];
+      int n = 0;
+#pragma unroll
+      for (int x = 0; x < 4; x++) {
+        if (todo) {
+          const int q = __ffsll((unsigned long long)todo) - 1;
+          todo &= todo - 1;
+          const uint32_t l = __shfl(my_loc, q, G);
+          const int r = __shfl(my_row, q, G);
+          const uint32_t ix = l & kLocIndex;
+          w[x] = ((l & kLocOverflow) ? ovf + (size_t)ix * ovf_stride : lines + (size_t)((int)ix - slot_base) * rb) + lig * 16;
+          mp[x] = dev_m + r;
+          m_old[x] = *mp[x];
+          within[x] = (int)(j0 - lo) + q;
+          if (active) raw[x] = *(const uint4 *)w[x];
+          n = x + 1;
+        }
+      }
+#pragma unroll
+      for (int x = 0; x < 4; x++) {
+        if (x < n) {  // n is the same for all lanes of the group
+          float gm[EPL];
+          float sq = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; e++) {
+            gm[e] = aw[e] == within[x] ? g[e] : 0.f;
+            sq += gm[e] * gm[e];
+          }
+          for (int d = G / 2; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, G);
+          const float m_new = m_old[x] + sq * inv_dim;
+          if (active) adagrad_store<DT>(w[x], raw[x], gm, m_new, lr, eps);
+          if (lig == 0) *mp[x] = m_new;
+        }
+      }
+    }
+  }
+}
+
 // Rows with 2..kLongRun lookups: one group of G lanes per distinct row, gradients summed
 // in sorted (= ascending bag) order.
-template <int DT, int G, bool MEAN>
+template <int DT, int G, int MODE>
 __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__restrict__ tm, int cls, int B,
                                                              int sum_dim, const int32_t *__restrict__ mid_idx,
                                                              const uint32_t *__restrict__ uniq_key,
@@ -305,6 +492,8 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
                                                              char *__restrict__ ovf, uint32_t ovf_stride,
                                                              const int32_t *__restrict__ table_class,
                                                              const float *__restrict__ inv_len,
+                                                             const int32_t *__restrict__ argpos,
+                                                             const int32_t *__restrict__ sorted_within,
                                                              const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   if (cnt->err) return;
@@ -322,14 +511,15 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    reduce_grads<DT, G, MEAN>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, 0, 1, lig, active, inv_len);
+    reduce_grads<DT, G, MODE>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, 0, 1, lig, active, inv_len,
+                              MODE == kMax ? argpos + m.col + lig * EPL : nullptr, sorted_within);
     update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
   }
 }
 
 // Rows with kLongRun < lookups <= kHugeRun: one workgroup per row, its 256/G groups take
 // chunks of G lookups round robin; the partial sums are added in group order through LDS.
-template <int DT, int G, bool MEAN>
+template <int DT, int G, int MODE>
 __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__restrict__ tm, int cls, int B,
                                                             int sum_dim, const int32_t *__restrict__ items,
                                                             const uint32_t *__restrict__ uniq_key,
@@ -341,6 +531,8 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
                                                             char *__restrict__ ovf, uint32_t ovf_stride,
                                                             const int32_t *__restrict__ table_class,
                                                             const float *__restrict__ inv_len,
+                                                            const int32_t *__restrict__ argpos,
+                                                            const int32_t *__restrict__ sorted_within,
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int NG = 256 / G;
@@ -359,8 +551,9 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    reduce_grads<DT, G, MEAN>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, run_off[u], run_off[u + 1], grp,
-                              NG, lig, active, inv_len);
+    reduce_grads<DT, G, MODE>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, run_off[u], run_off[u + 1], grp,
+                              NG, lig, active, inv_len, MODE == kMax ? argpos + m.col + lig * EPL : nullptr,
+                              sorted_within);
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < EPL; e++) part[grp][lig * EPL + e] = g[e];
@@ -565,8 +758,12 @@ static void fwd_one(const TableMeta *tm, const int32_t *tables, int count, const
                     float *out, hipStream_t s) {
   const int bags_per_block = 256 / G;
   dim3 grid((b.batch + bags_per_block - 1) / bags_per_block, count);
-  hipLaunchKernelGGL((forward_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_offsets,
-                     b.loc, b.ovf, g.ovf_stride, b.mean ? b.inv_len : nullptr, out, b.cnt);
+  if (b.maxp)
+    hipLaunchKernelGGL((forward_max_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_offsets,
+                       b.loc, b.ovf, g.ovf_stride, out, b.argpos, b.cnt);
+  else
+    hipLaunchKernelGGL((forward_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_offsets,
+                       b.loc, b.ovf, g.ovf_stride, b.mean ? b.inv_len : nullptr, out, b.cnt);
 }
 
 template <int DT, int G>
@@ -579,15 +776,17 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
     hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(1024), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
                        b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   } else if (which == 0) {
-    auto kern = b.mean ? backward_long_kernel<DT, G, true> : backward_long_kernel<DT, G, false>;
+    auto kern = b.maxp ? backward_long_kernel<DT, G, kMax>
+                : b.mean ? backward_long_kernel<DT, G, kMean> : backward_long_kernel<DT, G, kSum>;
     hipLaunchKernelGGL(kern, dim3(8192), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items, b.uniq_key, b.uniq_tab,
                        b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class,
-                       b.mean ? b.inv_len : nullptr, b.cnt);
+                       b.mean ? b.inv_len : nullptr, b.argpos, b.sorted_within, b.cnt);
   } else {
-    auto kern = b.mean ? backward_short_kernel<DT, G, true> : backward_short_kernel<DT, G, false>;
+    auto kern = b.maxp ? backward_short_kernel<DT, G, kMax>
+                : b.mean ? backward_short_kernel<DT, G, kMean> : backward_short_kernel<DT, G, kSum>;
     hipLaunchKernelGGL(kern, dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.mid_idx, b.uniq_key, b.uniq_tab,
                        b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class,
-                       b.mean ? b.inv_len : nullptr, b.cnt);
+                       b.mean ? b.inv_len : nullptr, b.argpos, b.sorted_within, b.cnt);
   }
 }
 
@@ -596,8 +795,12 @@ static void bwd_single_one(const TableMeta *tm, const int32_t *tables, int count
                            const float *grad_out, float lr, float eps, hipStream_t s) {
   const int bags_per_block = 256 / G;
   dim3 grid((b.batch + bags_per_block - 1) / bags_per_block, count);
-  hipLaunchKernelGGL((backward_single_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_indices,
-                     b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.mean ? b.inv_len : nullptr, b.cnt);
+  if (b.maxp)
+    hipLaunchKernelGGL((backward_single_max_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim,
+                       b.d_indices, b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.argpos, b.cnt);
+  else
+    hipLaunchKernelGGL((backward_single_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_indices,
+                       b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.mean ? b.inv_len : nullptr, b.cnt);
 }
 
 #define TBE_DISPATCH(DT, LANES, CALL)                         \

@@ -92,6 +92,10 @@ struct BatchBuf {
                         //     does not carry the bag (BatchCounters::packed == 0)
   float *inv_len;       // [T * batch] mean pooling: 1 / lookups of the bag (0 for an empty bag)
   bool mean;            // mean pooling instead of sum: forward and backward weigh by inv_len
+  bool maxp;            // max pooling: forward records who supplied each maximum, backward sends the gradient there
+  int32_t *argpos;      // [batch * sum_dim] max pooling: position inside its bag of the lookup that supplied the
+                        //     maximum of each pooled element (-1 for an empty bag); null unless max pooling is set
+  int32_t *sorted_within; // [N] max pooling: position inside its bag of the i-th lookup in sorted order
   uint32_t *uid_sorted; // [N] index of the distinct row of the i-th sorted lookup
   // per distinct row (ascending key)
   uint32_t *uniq_key;   // [N]

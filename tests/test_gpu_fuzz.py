@@ -51,4 +51,4 @@ def test_random_model_two_level(seed):
         cfg.tables[0].cache_slots = cfg.ways
     g = np.random.default_rng(seed)
     run_parity(cfg, steps=7, order=order, overlap=overlap, second_level_factor=int(g.choice([1, 2, 5])),
-               policy=str(g.choice(["lru", "lfu"])), pooling=str(g.choice(["sum", "mean"])))
+               policy=str(g.choice(["lru", "lfu"])), pooling=str(g.choice(["sum", "mean", "max"])))

@@ -37,7 +37,7 @@ def test_pooling_errors():
     w = [torch.zeros(100, 8, dtype=torch.float32).pin_memory()]
     m = [torch.zeros(100, dtype=torch.float32).pin_memory()]
     g = TBE(w, m, [16], 4, 8, 64)
-    assert lib().tbe_set_pooling(g._h, 2) == -1
+    assert lib().tbe_set_pooling(g._h, 3) == -1
     assert lib().tbe_set_pooling(g._h, 1) == 0
     idx = torch.tensor([1, 2, 3], device="cuda")
     off = torch.tensor([0, 1, 2, 3, 3, 3, 3, 3, 3], device="cuda")
