@@ -229,6 +229,20 @@ int tbe_set_pooling(tbe_handle h, int32_t pooling);
 int tbe_set_policy(tbe_handle h, int32_t policy);
 
 /*
+ * Prefetch depth (Section 5.7: the caches are accessed several batches in advance).  With depth
+ * D > 1 tbe_prefetch accepts up to D batches ahead of training.  The pipeline itself stays one
+ * batch deep -- the host link is its bottleneck and is busy at that depth, and no row needed
+ * by a batch that has not trained is evicted because a batch's rows enter their cache lines
+ * only after the batch before has trained -- so batches beyond the next one are queued and
+ * their work is issued, in order, as soon as the batch before them has been forwarded.
+ * Results are those of depth 1.  The index buffers of a queued batch must stay valid and
+ * unchanged until its tbe_backward_update has completed.  tbe_get_stats and the tbe_export_*
+ * calls describe the last batch whose work has been issued, not the last one accepted.
+ * depth 1..64 (TBE_EINVAL); not while batches are queued (TBE_EORDER).  Default 1.
+ */
+int tbe_set_prefetch_depth(tbe_handle h, int32_t depth);
+
+/*
  * By default tbe_prefetch orders its work behind everything enqueued on the compute stream
  * so far, because the index buffers may have been produced there.  With ready = 1 the
  * caller guarantees instead that the buffers passed to tbe_prefetch are complete in device

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <deque>
 #include <vector>
 
 #include "../../include/tbe.h"
@@ -76,6 +77,11 @@ struct tbe_ctx {
   // pipeline: buffers prefetched and waiting for forward (oldest first), the buffer that
   // was forwarded and waits for its update, and a buffer whose copies wait for that update
   int pend[2] = {-1, -1};
+  // batches accepted by tbe_prefetch further ahead than the pipeline runs: their work is issued, in order, as
+  // soon as the batch before has been forwarded
+  struct Queued { const int64_t *d_indices, *d_offsets; int32_t batch; int64_t n; };
+  std::deque<Queued> queued;
+  int depth = 1;                // batches tbe_prefetch may run ahead of training
   int n_pend = 0;
   int current = -1;
   int deferred = -1;
@@ -525,10 +531,37 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   return TBE_OK;
 }
 
+// issue the work of queued batches as far as the pipeline takes them (one batch ahead of training)
+static int pump_queue(tbe_ctx *h) {
+  while (!h->queued.empty() && h->n_pend + (h->current >= 0 ? 1 : 0) <= 1) {
+    const tbe_ctx::Queued q = h->queued.front();
+    h->queued.pop_front();
+    int rc = do_prefetch(h, q.d_indices, q.d_offsets, q.batch, q.n);
+    if (rc) return rc;
+  }
+  return TBE_OK;
+}
+
 int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch, int64_t num_lookups) {
   if (!h) return TBE_EINVAL;
   if (h->sticky) return h->sticky;
+  const int ahead = h->n_pend + (h->current >= 0 ? 1 : 0) + (int)h->queued.size();
+  if (h->depth > 1 && (ahead > 1 || !h->queued.empty())) {  // beyond what runs now: keep it for later
+    if (!d_offsets || batch < 0 || num_lookups < 0 || (num_lookups > 0 && !d_indices)) return fail(h, TBE_EINVAL, "prefetch: bad argument");
+    if (batch > h->max_batch || num_lookups > h->max_lookups) return fail(h, TBE_ELIMIT, "prefetch: batch or lookups above the sizes given to tbe_create");
+    if (ahead > h->depth) return fail(h, TBE_EORDER, "prefetch: more batches ahead of training than the prefetch depth");
+    h->queued.push_back({d_indices, d_offsets, batch, num_lookups});
+    return TBE_OK;
+  }
   return do_prefetch(h, d_indices, d_offsets, batch, num_lookups);
+}
+
+int tbe_set_prefetch_depth(tbe_handle h, int32_t depth) {
+  if (!h) return TBE_EINVAL;
+  if (depth < 1 || depth > 64) return fail(h, TBE_EINVAL, "set_prefetch_depth: depth must be 1..64");
+  if (!h->queued.empty()) return fail(h, TBE_EORDER, "set_prefetch_depth: batches are queued");
+  h->depth = depth;
+  return TBE_OK;
 }
 
 int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch, int64_t num_lookups,
@@ -537,6 +570,10 @@ int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets
   if (h->sticky) return h->sticky;
   if (!d_out) return fail(h, TBE_EINVAL, "forward: null output");
   if (h->current >= 0) return fail(h, TBE_EORDER, "forward: the previous batch has not been updated");
+  if (h->n_pend == 0 && !h->queued.empty()) {
+    int rc = pump_queue(h);
+    if (rc) return rc;
+  }
   if (h->n_pend == 0) {
     int rc = do_prefetch(h, d_indices, d_offsets, batch, num_lookups);
     if (rc) return rc;
@@ -554,7 +591,7 @@ int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets
     HIP_TRY(h, launch_forward_classes(h->d_tm, h->ci, h->g, b, d_out, h->cs));
   }
   h->current = bi;
-  return TBE_OK;
+  return pump_queue(h);  // the next queued batch is prefetched while this one trains
 }
 
 int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float eps) {
@@ -591,15 +628,16 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   if (h->deferred >= 0) {
     const int d = h->deferred;
     h->deferred = -1;
-    return enqueue_commit(h, d, true);
+    int rc = enqueue_commit(h, d, true);
+    return rc ? rc : pump_queue(h);
   }
   HIP_TRY(h, launch_ovf_writeback(h->buf[bi], h->st, h->d_rb, h->d_bytes + 1, h->ls));
-  return TBE_OK;
+  return pump_queue(h);
 }
 
 int tbe_flush(tbe_handle h) {
   if (!h) return TBE_EINVAL;
-  if (h->n_pend > 0 || h->current >= 0) return fail(h, TBE_EORDER, "flush: a batch is still in flight");
+  if (h->n_pend > 0 || h->current >= 0 || !h->queued.empty()) return fail(h, TBE_EORDER, "flush: a batch is still in flight");
   int rc = sync_all(h);
   if (rc) return rc;
   HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, h->di, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first

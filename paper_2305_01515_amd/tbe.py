@@ -23,7 +23,7 @@ EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
            "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling",
-           "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats"]
+           "tbe_set_prefetch_depth", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1, "max": 2}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
@@ -86,6 +86,7 @@ def lib() -> C.CDLL:
         l.tbe_set_policy.argtypes = [vp, i32]
         l.tbe_set_pooling.argtypes = [vp, i32]
         l.tbe_enable_second_level.argtypes = [vp, i32]
+        l.tbe_set_prefetch_depth.argtypes = [vp, i32]
         l.tbe_enable_deferred_init.argtypes = [vp, C.c_uint64, C.c_float]
         l.tbe_export_initialised.argtypes = [vp, i32, vp]
         l.tbe_num_sets2.argtypes = [vp, i32]
@@ -134,6 +135,7 @@ class TBE:
         if rc:
             raise TbeError(rc, "tbe_create", lib().tbe_last_error(None).decode())
         self._keep: List[Tuple[torch.Tensor, ...]] = []
+        self._depth = 1
         if policy != "lru":
             self._check(lib().tbe_set_policy(self._h, POLICIES[policy]), "tbe_set_policy")
         if pooling != "sum":
@@ -166,7 +168,7 @@ class TBE:
     def prefetch(self, indices: torch.Tensor, offsets: torch.Tensor):
         assert indices.is_cuda and offsets.is_cuda and indices.dtype == torch.int64 and offsets.dtype == torch.int64
         self._keep.append((indices, offsets))
-        self._keep = self._keep[-4:]
+        self._keep = self._keep[-(4 + 2 * self._depth):]
         self._check(lib().tbe_prefetch(self._h, indices.data_ptr(), offsets.data_ptr(),
                                        self._batch_of(offsets, self.T), indices.numel()), "tbe_prefetch")
 
@@ -176,7 +178,7 @@ class TBE:
             out = torch.empty(B, self.sum_dim, dtype=torch.float32, device=indices.device)
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == B * self.sum_dim
         self._keep.append((indices, offsets, out))
-        self._keep = self._keep[-4:]
+        self._keep = self._keep[-(4 + 2 * self._depth):]
         self._check(lib().tbe_forward(self._h, indices.data_ptr(), offsets.data_ptr(), B, indices.numel(),
                                       out.data_ptr()), "tbe_forward")
         return out
@@ -244,6 +246,10 @@ class TBE:
         out = np.empty(self.weights[t].shape[0], dtype=np.uint8)
         self._check(lib().tbe_export_initialised(self._h, t, out.ctypes.data), "tbe_export_initialised")
         return out
+
+    def set_prefetch_depth(self, depth: int):
+        self._check(lib().tbe_set_prefetch_depth(self._h, depth), "tbe_set_prefetch_depth")
+        self._depth = depth  # tensors of queued batches are kept alive that much longer
 
     def cache_freq(self, t: int) -> np.ndarray:
         f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)

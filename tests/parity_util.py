@@ -153,6 +153,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         compare_forward(cfg, out_o, out_g.cpu().numpy(), f"step {s + 1}")
         o.backward_update(synth.grad_out(cfg, s + 1).numpy(), cfg.lr, cfg.eps)
 
+    pushed = 0
     for s in range(steps):
         go = synth.grad_out(cfg, s + 1).to(device)
         idx, off = dev[s]
@@ -170,6 +171,15 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             out = g.forward(idx, off)
             if s + 1 < steps:
                 gpu_prefetch(s + 1)
+            g.backward_update(go, cfg.lr, cfg.eps)
+        elif order.startswith("deep"):  # deepN: N batches accepted ahead of training
+            depth = int(order[4:])
+            if s == 0:
+                g.set_prefetch_depth(depth)
+            while pushed < min(steps, s + 1 + depth):
+                g.prefetch(*dev[pushed])
+                pushed += 1
+            out = g.forward(idx, off)
             g.backward_update(go, cfg.lr, cfg.eps)
         elif order == "early":
             if s == 0:

@@ -228,3 +228,32 @@ def test_repeated_runs_are_reproducible():
     a = train(cfg, 5, "early", overlap=True)
     b = train(cfg, 5, "early", overlap=True)
     assert all(torch.equal(x, y) for x, y in zip(a[0] + a[1] + a[2], b[0] + b[1] + b[2]))
+
+
+@pytest.mark.parametrize("depth", [2, 5])
+def test_prefetch_depth_queues_batches(depth):
+    """tbe_prefetch accepts `depth` batches ahead of training; results are those of depth 1 (the
+    oracle's), the queue refuses one batch too many, flush refuses while batches are queued."""
+    from paper_2305_01515_amd.tbe import TbeError
+    from parity_util import run_parity
+    from test_gpu_parity import small_cfg
+    run_parity(small_cfg(synth.FP16, 8, seed=95), steps=9, order=f"deep{depth}", second_level_factor=2 if depth == 5 else 0)
+    cfg = small_cfg(synth.FP32, 4, seed=96, batch=16)
+    g, _, _ = make(cfg, max_lookups=1 << 16)
+    stream = synth.BatchStream(cfg, device="cuda")
+    bs = [stream.next() for _ in range(depth + 2)]
+    g.set_prefetch_depth(depth)
+    for b in bs[:depth + 1]:  # the batch about to train and `depth` batches after it
+        g.prefetch(*b)
+    with pytest.raises(TbeError) as e:
+        g.prefetch(*bs[depth + 1])
+    assert e.value.code == -3
+    with pytest.raises(TbeError):
+        g.flush()
+    with pytest.raises(TbeError):
+        g.set_prefetch_depth(1)
+    for b in bs[:depth + 1]:
+        g.forward(*b)
+        g.backward_update(torch.zeros(cfg.batch, cfg.sum_dim, device="cuda"), 0.1, 1e-8)
+    g.flush()
+    g.close()
