@@ -222,6 +222,8 @@ def main():
                     help="hetero: share of the HBM budget given to whole tables chosen by the placement solver "
                          "(Eq. 6); negative = plain split in proportion to lookups x dim")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wait-for-compute", action="store_true",
+                    help="leave the default ordering of tbe_prefetch behind the compute stream in place")
     ap.add_argument("--no-control", action="store_true", help="skip the all-hit control run after the benchmark "
                     "(so that a profile of the process holds the benchmark's launches only)")
     ap.add_argument("--no-overlap", action="store_true", help="run everything on one stream")
@@ -326,7 +328,7 @@ def main():
             g.forward(batches[s][0], batches[s][1], out)
             g.backward_update(grads[s % len(grads)], cfg.lr, cfg.eps)
 
-    g.set_inputs_ready(True)  # all index tensors were generated and synchronised above
+    g.set_inputs_ready(not args.wait_for_compute)  # all index tensors were generated and synchronised above
     g.set_profiling(True)  # stage brackets from the first launch on, so that the means over all
     g.prefetch(*batches[0])  # launches can be compared with a rocprofv3 --stats run of this command
     run(0, Wm)
