@@ -80,3 +80,13 @@ def test_long_run_scaled(factor):
     if factor:
         l2 = st["second_level_total"]
         assert l2["hits"] > 0 and l2["evictions"] > 0
+
+
+def test_main_config_full_size_two_level():
+    """The benchmark's workload at full size with a second level twice the first, prefetch ahead as
+    bench.py issues it, deferred initialisation from NaN-filled tables on top: every prefetch compared."""
+    cfg = synth.config_main()
+    st = run_parity(cfg, steps=5, order="ahead", oracle_threads=16, init_device="cuda", second_level_factor=2,
+                    deferred_init=(7, cfg.init_std))
+    l2 = st["second_level_total"]
+    assert l2["demotions"] > 0 and l2["hits"] > 0 and st["total"]["bypasses"] > 0 and st["late_fetches"] > 0
