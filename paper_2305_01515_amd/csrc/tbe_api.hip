@@ -138,29 +138,22 @@ void drop_profile(tbe_ctx *h) {
 
 int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 
-__global__ void add_totals_kernel(const BatchCounters *c, BatchCounters *tot) {
-  if (threadIdx.x == 0 && c->err == 0) {
-    tot->hits += c->hits;
-    tot->evictions += c->evictions;
-    tot->hit_lookups += c->hit_lookups;
-  }
-}
-
-__global__ void add_l2_totals_kernel(const BatchCounters *c, unsigned long long *t) {
-  if (threadIdx.x == 0 && c->err == 0) {
-    t[0] += (unsigned long long)c->l2_hits;
-    t[1] += (unsigned long long)c->l2_demotions;
-    t[2] += (unsigned long long)c->l2_evictions;
-    t[3] += (unsigned long long)c->l2_bypasses;
-  }
-}
-
-// 64-bit totals: [0] uniques [1] inserts [2] bypasses
-__global__ void add_totals64_kernel(const BatchCounters *c, unsigned long long *t64) {
-  if (threadIdx.x == 0 && c->err == 0) {
-    t64[0] += (unsigned long long)c->n_uniq;
-    t64[1] += (unsigned long long)c->n_ins;
-    t64[2] += (unsigned long long)c->n_byp;
+// Running totals of a batch's counters: tot (hits, evictions, lookups that hit), t64 ([0] distinct
+// rows, [1] inserts, [2] bypasses) and, with a second level, l2 (its four counters).
+__global__ void add_totals_kernel(const BatchCounters *c, BatchCounters *tot, unsigned long long *t64,
+                                  unsigned long long *l2) {
+  if (threadIdx.x != 0 || c->err != 0) return;
+  tot->hits += c->hits;
+  tot->evictions += c->evictions;
+  tot->hit_lookups += c->hit_lookups;
+  t64[0] += (unsigned long long)c->n_uniq;
+  t64[1] += (unsigned long long)c->n_ins;
+  t64[2] += (unsigned long long)c->n_byp;
+  if (l2) {
+    l2[0] += (unsigned long long)c->l2_hits;
+    l2[1] += (unsigned long long)c->l2_demotions;
+    l2[2] += (unsigned long long)c->l2_evictions;
+    l2[3] += (unsigned long long)c->l2_bypasses;
   }
 }
 
@@ -273,9 +266,8 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     // (by the write-back of the previous batch's victims or by its backward), then move
     // the marks on from the previous batch to this one
     HIP_TRY(h, launch_classify_mark(h->d_tm, h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr, b, h->st, h->l2, h->d_bytes + 5, h->as));
-    hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total);
-    hipLaunchKernelGGL(add_totals64_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_bytes + 2);
-    if (h->l2.on) hipLaunchKernelGGL(add_l2_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_l2tot);
+    hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total, h->d_bytes + 2,
+                       h->l2.on ? h->d_l2tot : nullptr);
     HIP_TRY(h, hipGetLastError());
   }
   if (h->ls != h->as) {

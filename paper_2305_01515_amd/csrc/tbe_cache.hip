@@ -55,18 +55,18 @@ __global__ __launch_bounds__(kScanThreads) void compact_count_kernel(Op op, cons
   if (tid == 0) blk[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
 }
 
-__global__ __launch_bounds__(kScanBlocks) void compact_blockscan_kernel(u64 *blk, int nb, const BatchCounters *cnt) {
-  __shared__ u64 wsum[kScanBlocks / 64];
-  if (cnt->err) return;
+// sum of blk[0 .. count) over the workgroup (every thread gets it); wsum: 4 words of LDS
+__device__ inline u64 block_sum_of(const u64 *blk, int count, u64 *wsum) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const u64 v = tid < nb ? blk[tid] : 0;
-  const u64 incl = wave_incl_scan(v, lane);
-  if (lane == 63) wsum[wave] = incl;
+  u64 v = 0;
+  for (int b = tid; b < count; b += kScanThreads) v += blk[b];
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
   __syncthreads();
-  u64 wb = 0;
-  for (int w = 0; w < wave; w++) wb += wsum[w];
-  if (tid < nb) blk[tid] = wb + incl - v;
-  if (tid == nb - 1) blk[nb] = wb + incl;
+  if (lane == 0) wsum[wave] = v;
+  __syncthreads();
+  v = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  __syncthreads();
+  return v;
 }
 
 template <class Op>
@@ -78,7 +78,10 @@ __global__ __launch_bounds__(kScanThreads) void compact_emit_kernel(Op op, const
   const int chunk = scan_chunk(n, gridDim.x);
   const int base = blockIdx.x * chunk, end = min(n, base + chunk);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  u64 carry = blk[blockIdx.x];
+  // flags in the workgroups before this one (each adds up the few hundred block sums itself: one
+  // launch less than a separate scan of them)
+  u64 carry = block_sum_of(blk, blockIdx.x, wsum);
+  const u64 total = blockIdx.x == 0 ? block_sum_of(blk, gridDim.x, wsum) : 0;
   for (int tile = base; tile < end; tile += kScanTile) {
     const int i0 = tile + tid * kScanItems;
     u64 f[kScanItems];
@@ -106,7 +109,7 @@ __global__ __launch_bounds__(kScanThreads) void compact_emit_kernel(Op op, const
     __syncthreads();
   }
   op.thread_done(cnt, lane);
-  if (blockIdx.x == 0 && tid == 0) op.finish(cnt, n, blk[gridDim.x]);
+  if (blockIdx.x == 0 && tid == 0) op.finish(cnt, n, total);
 }
 
 template <class Op>
@@ -116,7 +119,6 @@ static void run_compaction(Op op, const int32_t *n_ptr, int n_fixed, int n_bound
   if (nb > kScanBlocks) nb = kScanBlocks;
   if (nb < 1) nb = 1;
   hipLaunchKernelGGL(compact_count_kernel<Op>, dim3(nb), dim3(kScanThreads), 0, s, op, n_ptr, n_fixed, blk, cnt);
-  hipLaunchKernelGGL(compact_blockscan_kernel, dim3(1), dim3(kScanBlocks), 0, s, blk, nb, cnt);
   hipLaunchKernelGGL(compact_emit_kernel<Op>, dim3(nb), dim3(kScanThreads), 0, s, op, n_ptr, n_fixed, blk, cnt);
 }
 
