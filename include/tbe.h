@@ -183,10 +183,12 @@ int tbe_get_second_level_stats(tbe_handle h, int64_t *h_last4, int64_t *h_total4
  * (seed, table, row, element), so the values do not depend on the order of the reads and equal
  * a table initialised in advance with the same generator:
  *   key   = mix(seed ^ (table + 1) * 0xD1342543DE82EF95),  mix = the finaliser of splitmix64
- *   h     = mix(key + row * 0x2545F4914F6CDD1D + element / 2)        (64-bit arithmetic)
- *   u1    = ((h >> 40) + 1) / 2^24,  u2 = ((h >> 8) & 0xFFFFFF) / 2^24
- *   z     = sqrt(-2 ln u1) * cos(2 pi u2) for even elements, ... * sin(2 pi u2) for odd ones
- * in fp32, rounded to the storage type.  The row reaches host_weights when it is evicted,
+ *   h_j   = mix(key + row * 0x2545F4914F6CDD1D + element * 3 + j),  j = 0, 1, 2   (64-bit arithmetic)
+ *   S     = sum over the twelve 16-bit fields f of h_0, h_1, h_2 of (2 f + 1)  -  12 * 65536
+ *   value = fl32( fl32(S) * (std * 2^-17) )     -- z = S / 2^17 is the classic twelve-uniform
+ *           approximation of a standard normal number (mean 0, variance 1, |z| < 6)
+ * rounded to nearest even when the storage is fp16.  Integer arithmetic and one fp32 product:
+ * the stored bits do not depend on who evaluates the definition.  The row reaches host_weights when it is evicted,
  * written back or flushed; rows never read keep whatever host_weights held.  host_state is
  * used as always.  Only before the first tbe_prefetch (TBE_EORDER afterwards or when called
  * twice); allocates one bit per row; TBE_EINVAL for a negative std.

@@ -65,8 +65,10 @@ def lib():
         _lib.orc_set_second_level.argtypes = [C.c_void_p, C.c_void_p]
         _lib.orc_enable_deferred_init.argtypes = [C.c_void_p, C.c_uint64, C.c_double]
         _lib.orc_export_initialised.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
-        _lib.orc_init_normal.restype = C.c_double
-        _lib.orc_init_normal.argtypes = [C.c_uint64, C.c_int32, C.c_int64, C.c_int32]
+        _lib.orc_init_sum.restype = C.c_int32
+        _lib.orc_init_sum.argtypes = [C.c_uint64, C.c_int32, C.c_int64, C.c_int32]
+        _lib.orc_init_value.restype = C.c_float
+        _lib.orc_init_value.argtypes = [C.c_uint64, C.c_float, C.c_int32, C.c_int64, C.c_int32]
         _lib.orc_num_sets2.restype = C.c_int64
         _lib.orc_num_sets2.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_export_second_level.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]

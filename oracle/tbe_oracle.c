@@ -51,8 +51,11 @@
  *     level does not hold); it is then given normal random values, std * z, z from a
  *     counter-based generator of (seed, table, row, element) -- so the values do not depend on
  *     the order of the reads and equal a table initialised in advance with the same
- *     generator: two 24-bit uniforms u1 in (0, 1], u2 in [0, 1) from one 64-bit hash per
- *     element pair, z = sqrt(-2 ln u1) * (cos | sin)(2 pi u2), rounded once to the storage type;
+ *     generator: z is the centred sum of twelve 16-bit uniforms (three 64-bit hashes per
+ *     element), the classic twelve-uniform approximation of a normal number (mean 0, variance
+ *     1, |z| < 6) -- integer arithmetic up to one fp32 multiplication by std * 2^-17, which is
+ *     fixed to fp32 so that both sides store bit-identical values (with max pooling a value
+ *     that differed in its last bit could change which lookup supplies a maximum);
  *   - mean pooling, the second pooling mode the paper names [Section 2.1.1]: the pooled
  *     vector is the sum divided by the number of lookups of the bag (a row looked up twice
  *     counts twice; an empty bag gives zeros), so a lookup of a bag of L lookups hands
@@ -285,22 +288,30 @@ static uint64_t mix64(uint64_t x) { /* the finaliser of splitmix64 */
   return x ^ (x >> 31);
 }
 
-/* standard normal number of element d of row r of table t */
-static double init_normal(uint64_t seed, int32_t t, int64_t r, int32_t d) {
+/* Element d of row r of table t: S = sum over twelve 16-bit fields f of (2 f + 1), minus 12 * 65536
+ * -- an integer with mean 0; z = S / 2^17 has variance 1 (twelve uniforms on (0, 1) minus 6). */
+static int32_t init_sum(uint64_t seed, int32_t t, int64_t r, int32_t d) {
   uint64_t table_key = mix64(seed ^ ((uint64_t)(t + 1) * 0xD1342543DE82EF95ull));
-  uint64_t h = mix64(table_key + (uint64_t)r * 0x2545F4914F6CDD1Dull + (uint64_t)(d / 2));
-  double u1 = (double)((h >> 40) + 1) / 16777216.0;       /* (0, 1] */
-  double u2 = (double)((h >> 8) & 0xFFFFFFull) / 16777216.0; /* [0, 1) */
-  double rad = sqrt(-2.0 * log(u1)), ang = 6.283185307179586476925 * u2;
-  return (d & 1) ? rad * sin(ang) : rad * cos(ang);
+  int64_t s = -12 * 65536;
+  for (int j = 0; j < 3; j++) {
+    uint64_t h = mix64(table_key + (uint64_t)r * 0x2545F4914F6CDD1Dull + (uint64_t)d * 3u + (uint64_t)j);
+    for (int f = 0; f < 4; f++) s += 2 * (int64_t)((h >> (16 * f)) & 0xFFFFu) + 1;
+  }
+  return (int32_t)s;
 }
-double orc_init_normal(uint64_t seed, int32_t t, int64_t r, int32_t d) { return init_normal(seed, t, r, d); }
+int32_t orc_init_sum(uint64_t seed, int32_t t, int64_t r, int32_t d) { return init_sum(seed, t, r, d); }
+/* the value itself, in the precision the definition fixes: one fp32 product */
+static float init_value(uint64_t seed, float std, int32_t t, int64_t r, int32_t d) {
+  float scale = std * 0x1p-17f; /* exact */
+  return (float)init_sum(seed, t, r, d) * scale;
+}
+float orc_init_value(uint64_t seed, float std, int32_t t, int64_t r, int32_t d) { return init_value(seed, std, t, r, d); }
 
 /* first read of a row from the lower tier gives it its value */
 static void ensure_initialised(const orc *h, orc_table *tb, int64_t r) {
   if (!tb->initialised || tb->initialised[r]) return;
   for (int d = 0; d < tb->dim; d++)
-    store_elem(tb->weights, tb->dtype, r * tb->dim + d, h->init_std * init_normal(h->init_seed, tb->index, r, d));
+    store_elem(tb->weights, tb->dtype, r * tb->dim + d, (double)init_value(h->init_seed, (float)h->init_std, tb->index, r, d));
   tb->initialised[r] = 1;
 }
 

@@ -28,8 +28,9 @@ constexpr int kLinkBlocks = 192;  // workgroups of the transfer kernel that work
 constexpr int kLinkXcds = 2;      // ... all placed on this many of the 8 XCDs
 
 // ---- deferred initialisation: counter-based normal numbers of (seed, table, row, element) ----
-// One 64-bit hash (the finaliser of splitmix64) per element pair gives two 24-bit uniforms,
-// u1 in (0, 1] and u2 in [0, 1); z = sqrt(-2 ln u1) * (cos | sin)(2 pi u2).
+// z = centred sum of twelve 16-bit uniforms (three 64-bit hashes per element, the finaliser of
+// splitmix64), integer arithmetic up to one fp32 product -- the stored bits are the same
+// wherever the definition is evaluated.
 __device__ inline u64 mix64(u64 x) {
   x += 0x9E3779B97F4A7C15ull;
   x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -39,24 +40,33 @@ __device__ inline u64 mix64(u64 x) {
 
 __device__ inline u64 init_table_key(u64 seed, int t) { return mix64(seed ^ ((u64)(t + 1) * 0xD1342543DE82EF95ull)); }
 
+__device__ inline float init_value(u64 table_key, uint32_t row, uint32_t e, float scale) {
+  int32_t s = -12 * 65536;
+#pragma unroll
+  for (int j = 0; j < 3; j++) {
+    const u64 h = mix64(table_key + (u64)row * 0x2545F4914F6CDD1Dull + (u64)e * 3u + (u64)j);
+    s += 2 * (int32_t)((h & 0xFFFFu) + ((h >> 16) & 0xFFFFu) + ((h >> 32) & 0xFFFFu) + (h >> 48)) + 4;
+  }
+  float v = __fmul_rn((float)s, scale);
+  // The fp32 product is the value; the fp16 table stores its rounding.  Without this barrier the
+  // compiler folds product and conversion into one mixed-precision instruction that rounds once,
+  // which differs from rounding the fp32 value wherever that value is an fp16 tie.
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
 // the 16 bytes of row `row` that start at element e0 (4 fp32 or 8 fp16 values), std * z each
 __device__ inline uint4 init_chunk(u64 table_key, uint32_t row, int dtype, uint32_t e0, float std) {
-  float z[8];
-  const int pairs = dtype == 0 ? 2 : 4;
-  for (int p = 0; p < pairs; p++) {
-    const u64 h = mix64(table_key + (u64)row * 0x2545F4914F6CDD1Dull + (u64)(e0 / 2 + p));
-    const float u1 = (float)((uint32_t)(h >> 40) + 1u) * (1.0f / 16777216.0f);
-    const float u2 = (float)((uint32_t)(h >> 8) & 0xFFFFFFu) * (1.0f / 16777216.0f);
-    const float rad = sqrtf(-2.0f * logf(u1));
-    float sn, cs;
-    sincospif(2.0f * u2, &sn, &cs);  // the angle 2 pi u2 without rounding 2 pi
-    z[2 * p] = std * (rad * cs);
-    z[2 * p + 1] = std * (rad * sn);
-  }
-  if (dtype == 0) return make_uint4(__float_as_uint(z[0]), __float_as_uint(z[1]), __float_as_uint(z[2]), __float_as_uint(z[3]));
+  const float scale = std * 0x1p-17f;  // exact
+  if (dtype == 0)
+    return make_uint4(__float_as_uint(init_value(table_key, row, e0, scale)),
+                      __float_as_uint(init_value(table_key, row, e0 + 1, scale)),
+                      __float_as_uint(init_value(table_key, row, e0 + 2, scale)),
+                      __float_as_uint(init_value(table_key, row, e0 + 3, scale)));
   uint32_t w[4];
   for (int i = 0; i < 4; i++)
-    w[i] = (uint32_t)__half_as_ushort(__float2half_rn(z[2 * i])) | ((uint32_t)__half_as_ushort(__float2half_rn(z[2 * i + 1])) << 16);
+    w[i] = (uint32_t)__half_as_ushort(__float2half_rn(init_value(table_key, row, e0 + 2 * i, scale))) |
+           ((uint32_t)__half_as_ushort(__float2half_rn(init_value(table_key, row, e0 + 2 * i + 1, scale))) << 16);
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
