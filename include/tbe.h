@@ -214,6 +214,16 @@ int tbe_export_initialised(tbe_handle h, int32_t table, uint8_t *h_flags);
 #define TBE_POOL_MEAN 1
 #define TBE_POOL_MAX 2
 int tbe_set_pooling(tbe_handle h, int32_t pooling);
+/*
+ * Max pooling (Section 2.1.1): who supplied each maximum of the batch that was forwarded last
+ * and has not been updated yet.  d_argmax: DEVICE int32[batch, sum of dims], caller-owned;
+ * element [b, col_t + d] = position inside bag (t, b) of the lookup whose row supplied
+ * pooled element d (0 = the bag's first lookup; the first of several equal values), -1 for
+ * an empty bag.  Written on the compute stream, like tbe_forward's output; does not
+ * synchronise.  TBE_EORDER unless the pooling mode is TBE_POOL_MAX and a forwarded batch
+ * is waiting for its update.
+ */
+int tbe_export_argmax(tbe_handle h, int32_t *d_argmax);
 
 /*
  * Replacement policy (Section 5.5.2 names the two that were tried).  TBE_POLICY_LRU, the

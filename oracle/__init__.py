@@ -76,6 +76,7 @@ def lib():
         _lib.orc_get_stats.argtypes = [C.c_void_p, C.POINTER(Stats), C.POINTER(Stats)]
         _lib.orc_events.restype = C.c_int64
         _lib.orc_events.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 4
+        _lib.orc_export_argmax.argtypes = [C.c_void_p, C.c_void_p]
         _lib.orc_read_row.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
         _lib.orc_double_to_half.restype = C.c_uint16
         _lib.orc_double_to_half.argtypes = [C.c_double]
@@ -166,6 +167,15 @@ class Oracle:
         if rc:
             raise OracleError(rc, "forward")
         return out
+
+    def argmax(self) -> np.ndarray:
+        """max pooling, between forward and backward_update: [B, sum of dims] position inside its bag of
+        the lookup that supplied each pooled element (-1: empty bag)"""
+        a = np.empty((self.B, self.sum_dim), dtype=np.int32)
+        rc = lib().orc_export_argmax(self.h, a.ctypes.data)
+        if rc:
+            raise OracleError(rc, "export_argmax")
+        return a
 
     def backward_update(self, grad_out: np.ndarray, lr: float, eps: float):
         g = np.ascontiguousarray(grad_out, dtype=np.float32)

@@ -813,6 +813,25 @@ int64_t orc_events(void *hp, int kind, int64_t *table, int64_t *row, int64_t *sl
   return n;
 }
 
+/* max pooling, after a forward: out[b, col_t + d] = position inside bag (t, b) of the lookup that
+ * supplied pooled element d (the first of several equal ones), -1 for an empty bag */
+int orc_export_argmax(void *hp, int32_t *out) {
+  orc *h = (orc *)hp;
+  if (!h || !out) return ORC_EINVAL;
+  if (h->pooling != ORC_POOL_MAX || !h->forwarded) return ORC_EORDER;
+  int64_t sumD = 0, col = 0;
+  for (int t = 0; t < h->T; t++) sumD += h->tab[t].dim;
+  for (int t = 0; t < h->T; t++) {
+    for (int32_t b = 0; b < h->B; b++)
+      for (int d = 0; d < h->tab[t].dim; d++) {
+        int64_t j = h->argmax[(int64_t)b * sumD + col + d];
+        out[(int64_t)b * sumD + col + d] = j < 0 ? -1 : (int32_t)(j - h->offsets[(int64_t)t * h->B + b]);
+      }
+    col += h->tab[t].dim;
+  }
+  return ORC_OK;
+}
+
 /* current value of a row and its accumulator, wherever they live */
 int orc_read_row(void *hp, int32_t t, int64_t r, double *w, float *m) {
   orc *h = (orc *)hp;

@@ -793,6 +793,16 @@ int tbe_set_pooling(tbe_handle h, int32_t pooling) {
   return TBE_OK;
 }
 
+int tbe_export_argmax(tbe_handle h, int32_t *d_argmax) {
+  if (!h || !d_argmax) return TBE_EINVAL;
+  if (h->sticky) return h->sticky;
+  if (h->pooling != TBE_POOL_MAX) return fail(h, TBE_EORDER, "export_argmax: the pooling mode is not max");
+  if (h->current < 0) return fail(h, TBE_EORDER, "export_argmax: no forwarded batch waits for its update");
+  const BatchBuf &b = h->buf[h->current];
+  HIP_TRY(h, hipMemcpyAsync(d_argmax, b.argpos, 4 * (size_t)b.batch * (size_t)h->g.sum_dim, hipMemcpyDeviceToDevice, h->cs));
+  return TBE_OK;
+}
+
 int tbe_set_inputs_ready(tbe_handle h, int32_t ready) {
   if (!h) return TBE_EINVAL;
   h->inputs_ready = ready != 0;

@@ -23,7 +23,7 @@ EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
            "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling",
-           "tbe_set_prefetch_depth", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats"]
+           "tbe_set_prefetch_depth", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1, "max": 2}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
@@ -85,6 +85,7 @@ def lib() -> C.CDLL:
         l.tbe_set_inputs_ready.argtypes = [vp, i32]
         l.tbe_set_policy.argtypes = [vp, i32]
         l.tbe_set_pooling.argtypes = [vp, i32]
+        l.tbe_export_argmax.argtypes = [vp, vp]
         l.tbe_enable_second_level.argtypes = [vp, i32]
         l.tbe_set_prefetch_depth.argtypes = [vp, i32]
         l.tbe_enable_deferred_init.argtypes = [vp, C.c_uint64, C.c_float]
@@ -136,6 +137,7 @@ class TBE:
             raise TbeError(rc, "tbe_create", lib().tbe_last_error(None).decode())
         self._keep: List[Tuple[torch.Tensor, ...]] = []
         self._depth = 1
+        self._forwarded = (0, None)
         if policy != "lru":
             self._check(lib().tbe_set_policy(self._h, POLICIES[policy]), "tbe_set_policy")
         if pooling != "sum":
@@ -179,8 +181,21 @@ class TBE:
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == B * self.sum_dim
         self._keep.append((indices, offsets, out))
         self._keep = self._keep[-(4 + 2 * self._depth):]
+        self._forwarded = (B, indices.device)
         self._check(lib().tbe_forward(self._h, indices.data_ptr(), offsets.data_ptr(), B, indices.numel(),
                                       out.data_ptr()), "tbe_forward")
+        return out
+
+    def argmax(self, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """max pooling, between forward and backward_update: int32 [B, sum_dim], position inside its bag
+        of the lookup that supplied each pooled element (-1: empty bag)"""
+        B, device = self._forwarded
+        if device is None:  # nothing has been forwarded: the library reports the order error
+            out = out if out is not None else torch.empty(1, dtype=torch.int32, device="cuda")
+        elif out is None:
+            out = torch.empty(B, self.sum_dim, dtype=torch.int32, device=device)
+        assert out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and out.numel() >= B * self.sum_dim
+        self._check(lib().tbe_export_argmax(self._h, out.data_ptr()), "tbe_export_argmax")
         return out
 
     def backward_update(self, grad_out: torch.Tensor, lr: float, eps: float):

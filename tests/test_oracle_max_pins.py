@@ -66,6 +66,7 @@ def test_max_hand_example_with_tie_and_duplicate():
     o = Oracle(W, M, [0], ways=2, pooling="max")
     o.prefetch(np.array([0, 1, 2, 1, 2]), np.array([0, 4, 4, 5]))
     assert o.forward().tolist() == [[3.0, 5.0], [0.0, 0.0], [3.0, 2.0]]
+    assert o.argmax().tolist() == [[1, 0], [-1, -1], [0, 0]]
     go = np.array([[10.0, 20.0], [7.0, 7.0], [1.0, 2.0]], dtype=np.float32)
     lr, eps = 0.5, 1e-8
     o.backward_update(go, lr, eps)
@@ -75,6 +76,31 @@ def test_max_hand_example_with_tie_and_duplicate():
         m = (g * g).mean()
         assert M[0][r] == pytest.approx(m)
         np.testing.assert_allclose(W[0][r], W0[r] - lr * g / (math.sqrt(m) + eps), rtol=1e-6)
+
+
+def test_argmax_is_numpy_argmax_of_the_gathered_rows():
+    # fp16 tables with a small spread: plenty of equal values, so 'the first of several' is exercised
+    rows, dims, B = [50, 9], [8, 4], 40
+    W, M = make_tables(rows, dims, [np.float16, np.float32], seed=21, std=0.01)
+    W[1][:] = np.round(W[1] * 300) / 300  # equal values in the fp32 table too
+    W0 = [w.copy() for w in W]
+    o = Oracle(W, M, [16, 0], ways=4, pooling="max")
+    idx, off = random_batch(rows, B, 7, seed=5)
+    o.prefetch(idx, off)
+    o.forward()
+    a = o.argmax()
+    col, ties = 0, 0
+    for t in range(2):
+        for b in range(B):
+            lo, hi = off[t * B + b], off[t * B + b + 1]
+            if lo == hi:
+                assert (a[b, col:col + dims[t]] == -1).all()
+                continue
+            vals = W0[t][idx[lo:hi]].astype(np.float64)
+            assert np.array_equal(a[b, col:col + dims[t]], vals.argmax(axis=0))  # numpy returns the first maximum
+            ties += int(((vals == vals.max(axis=0)).sum(axis=0) > 1).sum())
+        col += dims[t]
+    assert ties > 10
 
 
 def test_bags_of_one_lookup_pool_alike():
