@@ -633,6 +633,13 @@ int tbe_flush(tbe_handle h) {
   int rc = sync_all(h);
   if (rc) return rc;
   HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, h->di, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
+  if (h->prev_buf >= 0) {
+    // Every copy in the backing tier is current now, so the next batch must find no row marked
+    // "still on its way".  Left in place, such a mark would make that batch ask the transfer to skip
+    // a write-back that has already happened, and the request would hit a later batch's victim.
+    HIP_TRY(h, launch_unmark(h->d_tm, h->buf[h->prev_buf], h->st, h->l2, h->cs));
+    h->prev_buf = -1;
+  }
   HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->l2, h->d_bytes, h->d_bytes + 1, h->cs));
   for (const TableMeta &m : h->tm) {
     HIP_TRY(h, hipMemcpyAsync(m.host_m, m.dev_m, 4 * (size_t)m.rows, hipMemcpyDeviceToHost, h->cs));

@@ -241,6 +241,7 @@ hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf 
 // after the batch's backward: its bypassed rows go from their HBM copies to the backing tier
 hipError_t launch_ovf_writeback(const BatchBuf &b, const Staging &st, const uint32_t *rb_of_table,
                                 unsigned long long *bytes_d2h, hipStream_t s);
+hipError_t launch_unmark(const TableMeta *tm, const BatchBuf &last, const Staging &st, const Level2 &l2, hipStream_t s);
 hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, const Level2 &l2,
                         unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
 hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,

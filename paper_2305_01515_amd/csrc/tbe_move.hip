@@ -303,6 +303,13 @@ hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const
   return hipGetLastError();
 }
 
+// After a flush nothing is on its way to the backing tier any more: the marks of the last batch go.
+hipError_t launch_unmark(const TableMeta *tm, const BatchBuf &last, const Staging &st, const Level2 &l2, hipStream_t s) {
+  hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, last.cnt, last.ins_tab, last.ins_old, last.byp_key,
+                     l2.on ? last.l2v_src : nullptr, last.l2v_key, (uint32_t)st.max_inserts, st.where, 0);
+  return hipGetLastError();
+}
+
 // The batch before (`prev`, may be absent) has trained when this runs, so a late row's
 // current value is where its code says: prev's overflow copy or prev's parked victim, both
 // still in HBM.  With wb_prev set the kernel also writes prev's overflow rows back.

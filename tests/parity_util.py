@@ -146,11 +146,14 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None):
 
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
-               pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None, deferred_init=None):
+               pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None, deferred_init=None,
+               flush_every: int = 0):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
               'early'    prefetch(k+1) is issued before forward(k)
+    flush_every = n ('serial' and 'inline' only, where no batch is in flight between steps): both sides
+    flush after every n-th step, the backing tiers are compared, and training goes on.
     Cache state, counters and event sets are compared after every `check_every`-th
     prefetch (the library's snapshot is taken right after its prefetch call, the oracle,
     which is strictly sequential, is compared when it reaches that batch)."""
@@ -241,6 +244,13 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         else:
             raise ValueError(order)
         oracle_step(s, out)
+        if flush_every and (s + 1) % flush_every == 0 and s + 1 < steps:
+            assert order in ("serial", "inline")
+            o.flush()
+            g.flush()
+            if parted["at"] is None:
+                only = [o.initialised(t) for t in range(T)] if deferred_init is not None else None
+                compare_backing(cfg, Wn, Mn, Wp, Mp, f"flush after step {s + 1}", only=only)
     assert not snaps
     # final cache state must agree whatever the call order was
     for t in range(T):

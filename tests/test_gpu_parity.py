@@ -77,3 +77,16 @@ def test_sort_payload_with_and_without_the_bag(max_batch):
     fit; with 2^27 only bags of up to 4 lookups would, so the batch falls back to plain positions and
     the gathered bag ids.  Both must give the same results."""
     run_parity(small_cfg(synth.FP16, 8, seed=91), steps=4, order="ahead", max_batch=max_batch)
+
+
+@pytest.mark.parametrize("second_level_factor", [0, 2, 5])
+@pytest.mark.parametrize("pooling", ["sum", "max"])
+def test_flush_between_steps_then_train_on(second_level_factor, pooling):
+    """flush in the middle of training: the backing tier is compared at every flush and training goes on.
+    The caches are small against the batches, so rows evicted by the batch before a flush come back right
+    after it -- the case where a leftover 'still on its way' mark would make a later write-back be skipped."""
+    cfg = small_cfg(synth.FP16, 4, seed=123)
+    st = run_parity(cfg, steps=8, order="serial", flush_every=1, second_level_factor=second_level_factor, pooling=pooling)
+    assert st["total"]["evictions"] > 0 and st["parted_at"] is None
+    run_parity(small_cfg(synth.FP32, 8, seed=124), steps=7, order="inline", flush_every=2, second_level_factor=second_level_factor,
+               pooling=pooling, deferred_init=(5, 0.05))
