@@ -102,6 +102,7 @@ int fail(tbe_ctx *h, int code, const std::string &msg) {
 }
 
 int hipfail(tbe_ctx *h, hipError_t e, const char *what) {
+  (void)hipGetLastError();  // HIP keeps the error until it is read: the next launch check must not report it again
   return fail(h, e == hipErrorOutOfMemory ? TBE_ENOMEM : TBE_EHIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 

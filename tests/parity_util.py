@@ -6,7 +6,7 @@ Bars (written here once, used by every parity test):
     event sets: bit-exact;
   - floating point, per vector v against the oracle's r (a pooled bag slice, an updated
     row):  max_d |v - r| <= tol * max(max_d |r|, floor), tol = 1e-5 for fp32 storage and
-    2e-3 for fp16 storage (fp32 accumulation); the accumulator m always with 1e-5;
+    2e-3 for fp16 storage (fp32 accumulation); the accumulator m always with 1e-5 (floor M_FLOOR);
   - max pooling, who supplied each maximum: equal, except where two different rows' values lie within
     the floating-point bar of each other in the oracle (stored values agree only to that bar once rows
     have been updated, so either row may hold the larger one).  Such a choice is checked to be a valid
@@ -22,6 +22,13 @@ from oracle import Oracle
 from paper_2305_01515_amd import synth
 
 TOL = {synth.FP32: 1e-5, synth.FP16: 2e-3}
+# Accumulators: |m - ref| <= 1e-5 * max(ref, M_FLOOR).  The synthetic output gradients are N(0, 1), so a row's
+# gradient element is an fp32 sum of O(1) terms with an absolute error near 1e-7 whatever the sum comes to.
+# When a few terms cancel (g = 1e-3 from three terms of size 1, seen with max pooling on a table of dim 4,
+# where a single element carries the whole row gradient) m = mean(g^2) is tiny and that absolute error is
+# 1e-4 of it; the floor keeps the bar at 1e-8 absolute there, far below any lost or misplaced contribution
+# (at least 1/D of a squared gradient, ~2e-3).
+M_FLOOR = 1e-3
 
 
 def vec_err(got: np.ndarray, ref: np.ndarray, floor: float) -> float:
@@ -133,14 +140,14 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None):
                 f"{ctx}: a row of table {t} that was never read has been written"
             e = vec_err(wg[keep], Wn[t][keep], floor=1e-3 * cfg.init_std)
             assert e <= TOL[tc.dtype], f"{ctx}: initialised rows of table {t} off by {e:.3e}"
-            em = vec_err(mg[:, None], Mn[t][:, None], floor=1e-12)
+            em = vec_err(mg[:, None], Mn[t][:, None], floor=M_FLOOR)
             assert em <= 1e-5, f"{ctx}: accumulators of table {t} off by {em:.3e}"
             continue
         for r0 in range(0, tc.rows, step):
             r1 = min(tc.rows, r0 + step)
             e = vec_err(wg[r0:r1], Wn[t][r0:r1], floor=1e-3 * cfg.init_std)
             assert e <= TOL[tc.dtype], f"{ctx}: rows {r0}..{r1} of table {t} off by {e:.3e}"
-            em = vec_err(mg[r0:r1, None], Mn[t][r0:r1, None], floor=1e-12)
+            em = vec_err(mg[r0:r1, None], Mn[t][r0:r1, None], floor=M_FLOOR)
             assert em <= 1e-5, f"{ctx}: accumulators {r0}..{r1} of table {t} off by {em:.3e}"
 
 

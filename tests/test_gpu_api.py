@@ -257,3 +257,21 @@ def test_prefetch_depth_queues_batches(depth):
         g.backward_update(torch.zeros(cfg.batch, cfg.sum_dim, device="cuda"), 0.1, 1e-8)
     g.flush()
     g.close()
+
+
+def test_failed_allocation_does_not_leak_into_later_calls():
+    """max pooling keeps 4 bytes per pooled element of max_batch bags, three times: for 2^29 bags of 48
+    elements that is 309 GB, more than the GPU has.  The refusal
+    must name the allocation, and the error must not surface again at the next kernel launch of another handle."""
+    from paper_2305_01515_amd.tbe import TBE, TbeError
+    cfg = little()
+    _, _, Wp, Mp = make_backing(cfg)
+    with pytest.raises(TbeError, match="TBE_ENOMEM"):
+        TBE(Wp, Mp, [64, 0], cfg.ways, 1 << 29, 4096, pooling="max")
+    g = TBE(Wp, Mp, [64, 0], cfg.ways, cfg.batch, 4096)
+    idx, off = batch_of(cfg)
+    g.prefetch(idx, off)
+    g.forward(idx, off)
+    g.backward_update(torch.zeros(cfg.batch, 48, device="cuda"), 0.1, 1e-8)
+    g.flush()
+    g.close()

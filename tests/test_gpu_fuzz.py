@@ -52,3 +52,31 @@ def test_random_model_two_level(seed):
     g = np.random.default_rng(seed)
     run_parity(cfg, steps=7, order=order, overlap=overlap, second_level_factor=int(g.choice([1, 2, 5])),
                policy=str(g.choice(["lru", "lfu"])), pooling=str(g.choice(["sum", "mean", "max"])))
+
+
+def draw_options(seed):
+    """every option of the library at once: a model as above plus second level, policy, pooling, deferred
+    initialisation, a deeper prefetch queue, flushes between steps, and the width of the sort payload"""
+    cfg, order, overlap = draw(seed)
+    g = np.random.default_rng(seed)
+    two = bool(g.integers(0, 2))
+    if two and not any(t.cache_slots >= cfg.ways for t in cfg.tables):
+        cfg.tables[0].cache_slots = cfg.ways
+    kw = dict(second_level_factor=int(g.choice([1, 2, 5])) if two else 0, policy=str(g.choice(["lru", "lfu"])),
+              pooling=str(g.choice(["sum", "mean", "max"])), deferred_init=(seed, 0.05) if g.integers(0, 2) else None)
+    if g.integers(0, 4) == 0:
+        order = "deep%d" % int(g.integers(2, 5))
+    steps = int(g.integers(3, 9))
+    if order in ("serial", "inline") and g.integers(0, 2):
+        kw["flush_every"] = int(g.integers(1, 4))
+    if g.integers(0, 3) == 0:
+        kw["max_batch"] = int(g.choice([cfg.batch, 1 << 20, 1 << 27]))
+        if kw["pooling"] == "max":  # max pooling keeps 4 bytes per pooled element of max_batch bags, three times
+            kw["max_batch"] = min(kw["max_batch"], max(cfg.batch, (1 << 30) // sum(t.dim for t in cfg.tables)))
+    return cfg, dict(steps=steps, order=order, overlap=overlap, **kw)
+
+
+@pytest.mark.parametrize("seed", range(5000, 5032))
+def test_random_model_every_option(seed):
+    cfg, kw = draw_options(seed)
+    run_parity(cfg, **kw)
