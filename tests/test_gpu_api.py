@@ -275,3 +275,40 @@ def test_failed_allocation_does_not_leak_into_later_calls():
     g.backward_update(torch.zeros(cfg.batch, 48, device="cuda"), 0.1, 1e-8)
     g.flush()
     g.close()
+
+
+def test_two_handles_interleaved_equal_each_alone():
+    """A model may keep several groups of tables, each behind its own handle, on one GPU.  The handles share
+    nothing: driven in turns (and with their prefetches overlapping each other's training) each must produce,
+    bit for bit, what it produces alone."""
+    from paper_2305_01515_amd.tbe import TBE
+    cfgs = [mixed(11), little(seed=12, slots=(64, 32))]
+    steps = 6
+    alone = [train(c, steps, "early", overlap=True) for c in cfgs]
+    run = []
+    for c in cfgs:
+        _, _, Wp, Mp = make_backing(c)
+        stream = synth.BatchStream(c)
+        batches = [tuple(x.cuda() for x in stream.next()) for _ in range(steps)]
+        mx = max(int(b[0].numel()) for b in batches) + 1
+        g = TBE(Wp, Mp, [t.cache_slots for t in c.tables], c.ways, c.batch, mx, overlap=True)
+        run.append(dict(cfg=c, Wp=Wp, Mp=Mp, batches=batches, g=g, outs=[]))
+    torch.cuda.synchronize()
+    for r in run:
+        r["g"].prefetch(*r["batches"][0])
+    for s in range(steps):
+        for r in run:
+            if s + 1 < steps:
+                r["g"].prefetch(*r["batches"][s + 1])
+        for r in run:
+            r["outs"].append(r["g"].forward(*r["batches"][s]))
+        for r in reversed(run):
+            r["g"].backward_update(synth.grad_out(r["cfg"], s + 1).cuda(), r["cfg"].lr, r["cfg"].eps)
+    for r, ref in zip(run, alone):
+        state = [r["g"].cache_state(t) for t in range(r["cfg"].num_tables)]
+        r["g"].flush()
+        r["g"].close()
+        assert all(torch.equal(a.cpu(), b) for a, b in zip(r["outs"], ref[0]))
+        assert all(torch.equal(a, b) for a, b in zip(r["Wp"] + r["Mp"], ref[1] + ref[2]))
+        for (ta, sa), (tb, sb) in zip(state, ref[3]):
+            assert np.array_equal(ta, tb) and np.array_equal(sa, sb)
