@@ -77,6 +77,7 @@ def lib():
         _lib.orc_events.restype = C.c_int64
         _lib.orc_events.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 4
         _lib.orc_export_argmax.argtypes = [C.c_void_p, C.c_void_p]
+        _lib.orc_export_row_peak.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.orc_read_row.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
         _lib.orc_double_to_half.restype = C.c_uint16
         _lib.orc_double_to_half.argtypes = [C.c_double]
@@ -233,6 +234,15 @@ class Oracle:
         arrs = [np.empty(n, dtype=np.int64) for _ in range(4)]
         lib().orc_events(self.h, kid, *[a.ctypes.data for a in arrs])
         return tuple(arrs) if kid == 1 else (arrs[0], arrs[1])
+
+    def row_peak(self, t: int) -> np.ndarray:
+        """float32 [rows]: the largest |element| each row has held before or after any of its updates (0: never
+        updated).  Bookkeeping for the tests' error bars; it enters no result."""
+        p = np.empty(self.weights[t].shape[0], dtype=np.float32)
+        rc = lib().orc_export_row_peak(self.h, t, p.ctypes.data)
+        if rc:
+            raise OracleError(rc, "export_row_peak")
+        return p
 
     def read_row(self, t: int, r: int):
         w = np.empty(self.dims[t], dtype=np.float64)

@@ -129,6 +129,8 @@ typedef struct {
   int64_t l2_hits, l2_demotions, l2_evictions, l2_bypasses; /* of the last batch */
   unsigned char *initialised; /* deferred initialisation: [rows] 1 = the row has a value (null = off) */
   int32_t index;              /* table number (enters the generator) */
+  float *peak;      /* [rows] bookkeeping for the tests, enters no result: the largest |element| a row has
+                       held before or after any of its updates (0 = never updated) */
   /* last prefetched batch */
   int64_t n_uniq;
   int64_t *uniq;    /* sorted distinct rows */
@@ -216,7 +218,7 @@ static size_t esize(int dtype) { return dtype == 0 ? 4 : 2; }
 
 static void free_table(orc_table *t) {
   free(t->tag); free(t->ts); free(t->freq); free(t->lines); free(t->line_state);
-  free(t->tag2); free(t->ts2); free(t->lines2); free(t->line_state2); free(t->initialised);
+  free(t->tag2); free(t->ts2); free(t->lines2); free(t->line_state2); free(t->initialised); free(t->peak);
   free(t->uniq); free(t->mult); free(t->hit_row); free(t->ins_row);
   free(t->ins_slot); free(t->ins_old); free(t->byp_row);
 }
@@ -242,6 +244,8 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
     tb->rows = s->rows; tb->dim = s->dim; tb->dtype = s->dtype;
     tb->weights = s->weights; tb->state = s->state;
     tb->sets = s->cache_slots / ways;
+    tb->peak = (float *)calloc((size_t)s->rows, sizeof(float));
+    if (!tb->peak) { orc_destroy(h); return NULL; }
     int64_t slots = tb->sets * ways;
     if (slots > 0) {
       tb->tag = (int64_t *)malloc(sizeof(int64_t) * (size_t)slots);
@@ -505,6 +509,7 @@ static int prefetch_table(orc *h, int t) {
   int64_t n = hi - lo;
   memset(&tb->st, 0, sizeof(tb->st));
   tb->n_uniq = tb->n_hit = tb->n_ins = tb->n_byp = 0;
+  tb->l2_hits = tb->l2_demotions = tb->l2_evictions = tb->l2_bypasses = 0; /* per batch, also when the table has no lookups */
   tb->st.lookups = n;
   if (n == 0) return 0;
   if (grow(tb, n)) return ORC_ENOMEM;
@@ -715,10 +720,15 @@ int orc_backward_update(void *hp, const float *grad_out, float lr, float eps) {
       for (int d = 0; d < tb->dim; d++) sq += g[u * tb->dim + d] * g[u * tb->dim + d];
       double m = (double)*mptr + sq / (double)tb->dim;
       double denom = sqrt(m) + (double)eps;
+      double pk = (double)tb->peak[tb->uniq[u]];
       for (int d = 0; d < tb->dim; d++) {
         double w = load_elem(wbase, tb->dtype, base + d);
         store_elem(wbase, tb->dtype, base + d, w - (double)lr * g[u * tb->dim + d] / denom);
+        double w1 = load_elem(wbase, tb->dtype, base + d);
+        if (fabs(w) > pk) pk = fabs(w);
+        if (fabs(w1) > pk) pk = fabs(w1);
       }
+      tb->peak[tb->uniq[u]] = (float)pk;
       *mptr = (float)m;
     }
     free(g);
@@ -829,6 +839,14 @@ int orc_export_argmax(void *hp, int32_t *out) {
       }
     col += h->tab[t].dim;
   }
+  return ORC_OK;
+}
+
+/* bookkeeping for the tests: per row, the largest |element| it has held before or after any of its updates */
+int orc_export_row_peak(void *hp, int32_t t, float *out) {
+  orc *h = (orc *)hp;
+  if (!h || t < 0 || t >= h->T || !out) return ORC_EINVAL;
+  memcpy(out, h->tab[t].peak, sizeof(float) * (size_t)h->tab[t].rows);
   return ORC_OK;
 }
 

@@ -5,8 +5,12 @@ Bars (written here once, used by every parity test):
   - cache state (tags, timestamps, per-entry lookup counts), per-batch counters and the hit / insert / bypass
     event sets: bit-exact;
   - floating point, per vector v against the oracle's r (a pooled bag slice, an updated
-    row):  max_d |v - r| <= tol * max(max_d |r|, floor), tol = 1e-5 for fp32 storage and
-    2e-3 for fp16 storage (fp32 accumulation); the accumulator m always with 1e-5 (floor M_FLOOR);
+    row):  max_d |v - r| <= tol * max(max_d |r|, peak, floor), tol = 1e-5 for fp32 storage and
+    2e-3 for fp16 storage (fp32 accumulation); the accumulator m always with 1e-5 (floor M_FLOOR).
+    `peak` is the largest magnitude the row (for a pooled slice: any row of the bag) has held since the
+    run began, kept by the oracle: a rounding that fell differently on the two sides while a row was
+    large stays in it as an absolute difference when the row shrinks (one fp16 ulp taken at 0.5 is four
+    ulps at 0.15), so the bar is relative to the largest value the rounding can stem from;
   - max pooling, who supplied each maximum: equal, except where two different rows' values lie within
     the floating-point bar of each other in the oracle (stored values agree only to that bar once rows
     have been updated, so either row may hold the larger one).  Such a choice is checked to be a valid
@@ -31,11 +35,14 @@ TOL = {synth.FP32: 1e-5, synth.FP16: 2e-3}
 M_FLOOR = 1e-3
 
 
-def vec_err(got: np.ndarray, ref: np.ndarray, floor: float) -> float:
-    """largest norm-wise relative error over the rows of two [n, d] arrays"""
+def vec_err(got: np.ndarray, ref: np.ndarray, floor, peak=None) -> float:
+    """largest norm-wise relative error over the rows of two [n, d] arrays; floor: a number or one per row;
+    peak: per row, a magnitude the scale must not fall below (None: none)"""
     got = got.astype(np.float64)
     ref = ref.astype(np.float64)
     scale = np.maximum(np.abs(ref).max(axis=-1), floor)
+    if peak is not None:
+        scale = np.maximum(scale, peak)
     return float((np.abs(got - ref).max(axis=-1) / scale).max()) if got.size else 0.0
 
 
@@ -88,10 +95,26 @@ def compare_cache_step(o: Oracle, snap, T: int, ctx: str):
     assert o.second_level_stats()[0] == snap["l2_stats"], f"{ctx}: second-level counters differ: oracle {o.second_level_stats()[0]} gpu {snap['l2_stats']}"
 
 
-def compare_forward(cfg, out_o: np.ndarray, out_g: np.ndarray, ctx: str):
+def bag_peaks(cfg, o: Oracle, idx: np.ndarray, off: np.ndarray):
+    """per table, per bag: the largest peak (see the header) among the rows the bag looks up; 0 for an empty bag"""
+    B, res = cfg.batch, []
+    for t in range(cfg.num_tables):
+        o_t = off[t * B:(t + 1) * B + 1]
+        pk = o.row_peak(t)[idx[o_t[0]:o_t[-1]]]
+        out = np.zeros(B, dtype=np.float32)
+        full = np.flatnonzero(np.diff(o_t) > 0)
+        if len(full):
+            out[full] = np.maximum.reduceat(pk, (o_t[full] - o_t[0]))
+        res.append(out)
+    return res
+
+
+def compare_forward(cfg, out_o: np.ndarray, out_g: np.ndarray, ctx: str, peaks=None):
+    """peaks (max pooling, where one row's element is the pooled element): bag_peaks()"""
     col = 0
     for t, tc in enumerate(cfg.tables):
-        e = vec_err(out_g[:, col:col + tc.dim], out_o[:, col:col + tc.dim], floor=1e-3 * cfg.init_std)
+        e = vec_err(out_g[:, col:col + tc.dim], out_o[:, col:col + tc.dim], floor=1e-3 * cfg.init_std,
+                    peak=None if peaks is None else peaks[t])
         assert e <= TOL[tc.dtype], f"{ctx}: pooled output of table {t} off by {e:.3e}"
         col += tc.dim
 
@@ -107,6 +130,7 @@ def compare_argmax(cfg, o: Oracle, idx: np.ndarray, off: np.ndarray, arg_g: np.n
     cols = np.cumsum([0] + [tc.dim for tc in cfg.tables])
     flips = np.argwhere(a_o != arg_g)
     rows_seen = {}
+    peak = [o.row_peak(t) for t in range(cfg.num_tables)] if len(flips) else None
     for b, c in flips:
         t = int(np.searchsorted(cols, c, side="right") - 1)
         tc, d = cfg.tables[t], int(c - cols[t])
@@ -119,16 +143,17 @@ def compare_argmax(cfg, o: Oracle, idx: np.ndarray, off: np.ndarray, arg_g: np.n
                 rows_seen[(t, r)] = o.read_row(t, r)[0]
         w_o, w_g = rows_seen[(t, r_o)], rows_seen[(t, r_g)]
         floor = 1e-3 * cfg.init_std
-        band = TOL[tc.dtype] * (max(np.abs(w_o).max(), floor) + max(np.abs(w_g).max(), floor))
+        s_o, s_g = max(np.abs(w_o).max(), peak[t][r_o], floor), max(np.abs(w_g).max(), peak[t][r_g], floor)
+        band = TOL[tc.dtype] * (s_o + s_g)
         assert 0.0 <= w_o[d] - w_g[d] <= band, \
             f"{ctx}: bag {b} of table {t}, element {d}: took row {r_g} ({w_g[d]!r}) where row {r_o} ({w_o[d]!r}) is larger by more than the bar"
-        assert abs(float(out_g[b, c]) - w_g[d]) <= TOL[tc.dtype] * max(np.abs(w_g).max(), floor), \
-            f"{ctx}: bag {b} of table {t}, element {d}: pooled value is not that of the row that supplied it"
+        assert abs(float(out_g[b, c]) - w_g[d]) <= TOL[tc.dtype] * s_g, \
+            f"{ctx}: bag {b} of table {t}, element {d}: pooled value {float(out_g[b, c])!r} is not that of the row that supplied it (row {r_g}: {w_g[d]!r})"
         out_g[b, c] = w_o[d]
     return len(flips)
 
 
-def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None):
+def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None, peak=None):
     """only[t]: boolean mask of the rows to compare (deferred initialisation: the rows that have a value;
     the others must still hold the NaN they were filled with, on both sides)"""
     step = 1 << 21  # rows per comparison chunk (keeps the fp64 temporaries small)
@@ -138,14 +163,14 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None):
             keep = only[t].astype(bool)
             assert np.isnan(wg[~keep].astype(np.float32)).all() and np.isnan(Wn[t][~keep].astype(np.float32)).all(), \
                 f"{ctx}: a row of table {t} that was never read has been written"
-            e = vec_err(wg[keep], Wn[t][keep], floor=1e-3 * cfg.init_std)
+            e = vec_err(wg[keep], Wn[t][keep], floor=1e-3 * cfg.init_std, peak=None if peak is None else peak[t][keep])
             assert e <= TOL[tc.dtype], f"{ctx}: initialised rows of table {t} off by {e:.3e}"
             em = vec_err(mg[:, None], Mn[t][:, None], floor=M_FLOOR)
             assert em <= 1e-5, f"{ctx}: accumulators of table {t} off by {em:.3e}"
             continue
         for r0 in range(0, tc.rows, step):
             r1 = min(tc.rows, r0 + step)
-            e = vec_err(wg[r0:r1], Wn[t][r0:r1], floor=1e-3 * cfg.init_std)
+            e = vec_err(wg[r0:r1], Wn[t][r0:r1], floor=1e-3 * cfg.init_std, peak=None if peak is None else peak[t][r0:r1])
             assert e <= TOL[tc.dtype], f"{ctx}: rows {r0}..{r1} of table {t} off by {e:.3e}"
             em = vec_err(mg[r0:r1, None], Mn[t][r0:r1, None], floor=M_FLOOR)
             assert em <= 1e-5, f"{ctx}: accumulators {r0}..{r1} of table {t} off by {em:.3e}"
@@ -210,7 +235,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
                 n = compare_argmax(cfg, o, idx.numpy(), off.numpy(), arg_g.cpu().numpy(), out_g, f"step {s + 1}")
                 if n:
                     parted["at"], parted["elements"] = s + 1, n
-            compare_forward(cfg, out_o, out_g, f"step {s + 1}")
+            compare_forward(cfg, out_o, out_g, f"step {s + 1}",
+                            peaks=bag_peaks(cfg, o, idx.numpy(), off.numpy()) if pooling == "max" else None)
         o.backward_update(synth.grad_out(cfg, s + 1).numpy(), cfg.lr, cfg.eps)
 
     pushed = 0
@@ -257,7 +283,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             g.flush()
             if parted["at"] is None:
                 only = [o.initialised(t) for t in range(T)] if deferred_init is not None else None
-                compare_backing(cfg, Wn, Mn, Wp, Mp, f"flush after step {s + 1}", only=only)
+                compare_backing(cfg, Wn, Mn, Wp, Mp, f"flush after step {s + 1}", only=only,
+                                peak=[o.row_peak(t) for t in range(T)])
     assert not snaps
     # final cache state must agree whatever the call order was
     for t in range(T):
@@ -278,7 +305,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         for t in range(T):
             assert np.array_equal(only[t], g.initialised(t)), f"rows of table {t} that have a value differ"
     if parted["at"] is None:
-        compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush", only=only)
+        compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush", only=only, peak=[o.row_peak(t) for t in range(T)])
     st = g.stats()
     st["parted_at"], st["parted_elements"] = parted["at"], parted["elements"]
     st["second_level_total"] = g.second_level_stats()[1]

@@ -241,3 +241,26 @@ def test_victim_goes_straight_down_when_its_second_level_set_is_locked():
     assert o.cache_state(0)[0].tolist() == [0] and o.second_level_state(0)[0].tolist() == [1]
     np.testing.assert_allclose(W[0][2], W0[2] - 0.5 / (1.0 + 1e-8), rtol=1e-6)
     assert M[0][2] == pytest.approx(1.0)
+
+
+def test_counters_are_per_batch_also_for_a_table_without_lookups():
+    # two tables, each against its own dictionary model; the second one sits out every other batch, and a
+    # batch's second-level counters must then be those of the first table alone
+    ways, H = 2, 40
+    W, M = make_tables([H, H], [4, 4], [np.float32] * 2)
+    o = Oracle(W, M, [2 * ways] * 2, ways=ways, second_level_slots=[4 * ways] * 2)
+    models = [TwoLevelModel(2, 4, ways), TwoLevelModel(2, 4, ways)]
+    g = RNG(77)
+    total = np.zeros(4, dtype=np.int64)
+    idle_after_busy = 0
+    for k in range(1, 80):
+        rows = [g.integers(0, H, size=int(g.integers(3, 9))), g.integers(0, H, size=0 if k % 2 else int(g.integers(3, 9)))]
+        o.prefetch(np.concatenate(rows), np.array([0, len(rows[0]), len(rows[0]) + len(rows[1])]))
+        per = [m.batch(r.tolist(), k) if len(r) else (0, 0, 0, 0) for m, r in zip(models, rows)]
+        want = np.array(per).sum(axis=0)
+        total += want
+        last, tot = o.second_level_stats()
+        assert list(last.values()) == want.tolist() and list(tot.values()) == total.tolist()
+        idle_after_busy += int(len(rows[1]) == 0 and k > 1 and prev_busy > 0)
+        prev_busy = sum(per[1])
+    assert idle_after_busy > 10  # the case that matters: an idle batch right after one that moved rows
