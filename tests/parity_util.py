@@ -179,11 +179,15 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None, peak=None):
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
                pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None, deferred_init=None,
-               flush_every: int = 0):
+               flush_every: int = 0, misuse: int = 0):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
               'early'    prefetch(k+1) is issued before forward(k)
+    misuse = seed (0: off): between the regular calls, calls that the library must refuse -- an update with
+    nothing forwarded, a second forward, a flush with a batch in flight, a forward whose buffers are not those
+    of the pending prefetch, a batch above the sizes given at creation, a change of policy or pooling after
+    the first batch -- each checked for its error code; the run must come out as if they had not been made.
     flush_every = n ('serial' and 'inline' only, where no batch is in flight between steps): both sides
     flush after every n-th step, the backing tiers are compared, and training goes on.
     Cache state, counters and event sets are compared after every `check_every`-th
@@ -218,9 +222,60 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
 
     parted = {"at": None, "elements": 0}
 
+    from paper_2305_01515_amd.tbe import TbeError, lib
+    poke_rng = np.random.default_rng(misuse)
+    poked = {"n": 0}
+    EORDER, ELIMIT, EMISMATCH = -3, -5, -6
+
+    def refused(code, fn, *args):
+        try:
+            fn(*args)
+        except TbeError as e:
+            assert e.code == code, f"refused with {e.code}, expected {code}: {e}"
+            poked["n"] += 1
+            return
+        raise AssertionError(f"{getattr(fn, '__name__', fn)} was accepted where it must be refused")
+
+    def set_mode(which, value):
+        rc = getattr(lib(), which)(g._h, value)
+        if rc:
+            raise TbeError(rc, which)
+
+    def poke(stage, idx=None, off=None):
+        if not misuse or poke_rng.random() < 0.4:
+            return
+        zero_go = torch.zeros(cfg.batch, cfg.sum_dim, device=device)
+        if stage == "not forwarded":
+            choice = int(poke_rng.integers(0, 4))
+            if choice == 0:
+                refused(EORDER, g.backward_update, zero_go, cfg.lr, cfg.eps)
+            elif choice == 1:
+                refused(EORDER, g.argmax)
+            elif choice == 2 and poked.get("started"):
+                refused(EORDER, set_mode, "tbe_set_policy", 1)
+            elif order in ("serial", "ahead", "early") and idx.numel():  # the batch's prefetch is pending: other buffers are a mismatch
+                refused(EMISMATCH, g.forward, idx.clone(), off)
+        else:  # a forwarded batch waits for its update
+            choice = int(poke_rng.integers(0, 5))
+            if choice == 0:
+                refused(EORDER, g.forward, idx, off)
+            elif choice == 1:
+                refused(EORDER, g.flush)
+            elif choice == 2:
+                refused(EORDER, set_mode, "tbe_set_pooling", 1)
+            elif choice == 3 and pooling != "max":
+                refused(EORDER, g.argmax)
+            elif choice == 4:
+                too_many = torch.zeros(max_lookups + 1, dtype=torch.int64, device=device)
+                refused(ELIMIT, g.prefetch, too_many, torch.zeros_like(off))
+
     def gpu_forward(idx, off):
+        poke("not forwarded", idx, off)
         out = g.forward(idx, off)
-        return out, (g.argmax() if pooling == "max" else None)
+        poked["started"] = True  # from the first batch on the modes are fixed
+        arg = g.argmax() if pooling == "max" else None
+        poke("forwarded", idx, off)
+        return out, arg
 
     def oracle_step(s, res_g):
         out_g, arg_g = res_g
@@ -308,6 +363,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush", only=only, peak=[o.row_peak(t) for t in range(T)])
     st = g.stats()
     st["parted_at"], st["parted_elements"] = parted["at"], parted["elements"]
+    st["refused_calls"] = poked["n"]
     st["second_level_total"] = g.second_level_stats()[1]
     g.close()
     o.close()

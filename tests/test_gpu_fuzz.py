@@ -56,7 +56,8 @@ def test_random_model_two_level(seed):
 
 def draw_options(seed):
     """every option of the library at once: a model as above plus second level, policy, pooling, deferred
-    initialisation, a deeper prefetch queue, flushes between steps, and the width of the sort payload"""
+    initialisation, a deeper prefetch queue, flushes between steps, the width of the sort payload, and calls
+    that must be refused sprinkled in between"""
     cfg, order, overlap = draw(seed)
     g = np.random.default_rng(seed)
     two = bool(g.integers(0, 2))
@@ -73,6 +74,8 @@ def draw_options(seed):
         kw["max_batch"] = int(g.choice([cfg.batch, 1 << 20, 1 << 27]))
         if kw["pooling"] == "max":  # max pooling keeps 4 bytes per pooled element of max_batch bags, three times
             kw["max_batch"] = min(kw["max_batch"], max(cfg.batch, (1 << 30) // sum(t.dim for t in cfg.tables)))
+    if g.integers(0, 2):
+        kw["misuse"] = seed + 1  # refused calls in between, see parity_util.run_parity
     return cfg, dict(steps=steps, order=order, overlap=overlap, **kw)
 
 
