@@ -1,0 +1,81 @@
+"""GPU parity at the top of the index ranges: a table of 2^31 - 7 rows (the limit is rows < 2^31) followed by a
+second table, so that the sort keys of the second table lie above 2^31 and the whole key span just below 2^32.
+The big table is 34 GB in pinned host memory; only the rows the batches touch carry values (the rest stays
+zero, on the oracle's side as untouched pages of a zero-filled array), and only those are compared at the end,
+together with a sample of rows that nothing may have written."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import Oracle
+from paper_2305_01515_amd import synth
+from parity_util import TOL, compare_cache_step, compare_forward, gpu_snapshot, vec_err
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def test_rows_just_below_2_to_31_and_keys_above_it():
+    from paper_2305_01515_amd.tbe import TBE
+    rows, ways, sets, B, steps = (1 << 31) - 7, 8, 61, 64, 6
+    T = synth.TableCfg
+    cfg = synth.WorkloadCfg("limits", [T(rows, 8, synth.FP16, None, "fixed", 1, cache_slots=ways * sets),
+                                       T(1000, 16, synth.FP32, None, "fixed", 1, cache_slots=64)],
+                            batch=B, ways=ways, steps=steps, seed=1, init_std=0.05, lr=0.05)
+    rng = np.random.default_rng(2031)
+    top = (rows // sets) * sets
+    special = np.array([0, 1, 2, sets - 1, sets, sets + 1, rows - 1, rows - 2, rows - sets, rows - sets - 1, top - 1, top,
+                        min(top + 1, rows - 1), 1 << 30, (1 << 30) + 1, (1 << 31) - 8, (1 << 31) - 9], dtype=np.int64)
+    pool = np.unique(np.concatenate([special, rng.integers(0, rows, size=3000), rows - 1 - rng.integers(0, 5000, size=300)]))
+    # backing tiers: zeros, values only where the batches look
+    Wp = [torch.zeros(rows, 8, dtype=torch.float16, pin_memory=True), torch.empty(1000, 16, dtype=torch.float32, pin_memory=True)]
+    Mp = [torch.zeros(rows, dtype=torch.float32, pin_memory=True), torch.zeros(1000, dtype=torch.float32, pin_memory=True)]
+    vals = (rng.standard_normal((len(pool), 8)) * 0.05).astype(np.float16)
+    Wp[0][torch.from_numpy(pool)] = torch.from_numpy(vals)
+    Wp[1].copy_(torch.from_numpy((rng.standard_normal((1000, 16)) * 0.05).astype(np.float32)))
+    Wn = [np.zeros((rows, 8), dtype=np.float16), Wp[1].numpy().copy()]
+    Wn[0][pool] = vals
+    Mn = [np.zeros(rows, dtype=np.float32), np.zeros(1000, dtype=np.float32)]
+    slots = [ways * sets, 64]
+    o = Oracle(Wn, Mn, slots, ways, threads=2)
+    batches = []
+    for _ in range(steps):
+        lens = np.concatenate([rng.integers(0, 40, size=B), rng.integers(0, 6, size=B)])
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        n_big = int(lens[:B].sum())
+        idx = np.concatenate([pool[rng.integers(0, len(pool), size=n_big)], rng.integers(0, 1000, size=int(lens[B:].sum()))])
+        assert n_big > len(special)
+        idx[:len(special)] = special  # every step sees the corner rows
+        batches.append((torch.from_numpy(idx.astype(np.int64)), torch.from_numpy(off)))
+    g = TBE(Wp, Mp, slots, ways, B, max(int(b[0].numel()) for b in batches) + 1, overlap=True)
+    dev = [(i.cuda(), f.cuda()) for i, f in batches]
+    snaps = {}
+    g.prefetch(*dev[0])
+    snaps[0] = gpu_snapshot(g, 2)
+    for s in range(steps):
+        out = g.forward(*dev[s])
+        if s + 1 < steps:
+            g.prefetch(*dev[s + 1])
+            snaps[s + 1] = gpu_snapshot(g, 2)
+        g.backward_update(synth.grad_out(cfg, s + 1).cuda(), cfg.lr, cfg.eps)
+        idx, off = batches[s]
+        o.prefetch(idx.numpy(), off.numpy())
+        compare_cache_step(o, snaps.pop(s), 2, f"step {s + 1}")
+        compare_forward(cfg, o.forward(), out.cpu().numpy(), f"step {s + 1}")
+        o.backward_update(synth.grad_out(cfg, s + 1).numpy(), cfg.lr, cfg.eps)
+    st = g.stats()["total"]
+    assert st == o.stats()[1] and st["evictions"] > 100 and st["bypasses"] > 0 and st["hits"] > 0
+    o.flush()
+    g.flush()
+    touched = torch.from_numpy(pool)
+    assert vec_err(Wp[0][touched].numpy(), Wn[0][pool], floor=1e-3 * cfg.init_std) <= TOL[synth.FP16]
+    assert vec_err(Mp[0][touched].numpy()[:, None], Mn[0][pool][:, None], floor=1e-3) <= 1e-5
+    assert vec_err(Wp[1].numpy(), Wn[1], floor=1e-3 * cfg.init_std) <= TOL[synth.FP32]
+    # nothing else was written: a stretch at either end and in the middle, minus the touched rows
+    for lo in (0, 1 << 30, rows - 200000):
+        blk = Wp[0][lo:lo + 200000].numpy()
+        mask = np.ones(200000, dtype=bool)
+        inside = pool[(pool >= lo) & (pool < lo + 200000)] - lo
+        mask[inside] = False
+        assert not blk[mask].any() and not Mp[0][lo:lo + 200000].numpy()[mask].any()
+    g.close()
+    o.close()
