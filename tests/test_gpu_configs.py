@@ -67,3 +67,45 @@ def test_locality_full_size_point():
     Zipf 1.0, cache 5 % of the rows: the full shape of one sweep point."""
     cfg = synth.config_locality(1.0, 0.05)
     run_parity(cfg, steps=3, order="ahead", oracle_threads=4, init_device="cuda")
+
+
+def test_main_config_overlapped_equals_serial_bit_for_bit():
+    """The benchmark's workload at full size, trained twice from the same tables: once strictly serial on one
+    stream, once the way bench.py drives it (three streams, the next batch's prefetch issued before this batch's
+    forward).  Same kernels and same summation order, so every pooled output, the cache state and all 32M rows
+    must come out equal bit for bit; a missing wait between the streams shows up here as a difference."""
+    import numpy as np
+    import torch
+    from paper_2305_01515_amd.tbe import TBE
+    cfg = synth.config_main()
+    steps, T = 10, cfg.num_tables
+    stream = synth.BatchStream(cfg)
+    batches = [tuple(x.cuda() for x in stream.next()) for _ in range(steps)]
+    mx = max(int(b[0].numel()) for b in batches) + 1
+    slots = [t.cache_slots for t in cfg.tables]
+    runs = []
+    for overlap in (False, True):
+        Wp = [torch.empty(tc.rows, tc.dim, dtype=torch.float16, pin_memory=True) for tc in cfg.tables]
+        Mp = [torch.zeros(tc.rows, dtype=torch.float32, pin_memory=True) for tc in cfg.tables]
+        for t in range(T):
+            synth.init_table(cfg, t, device="cuda", out=Wp[t])
+        g = TBE(Wp, Mp, slots, cfg.ways, cfg.batch, mx, overlap=overlap)
+        torch.cuda.synchronize()
+        sums = []
+        if overlap:
+            g.prefetch(*batches[0])
+        for s in range(steps):
+            if overlap and s + 1 < steps:
+                g.prefetch(*batches[s + 1])
+            out = g.forward(*batches[s])
+            g.backward_update(synth.grad_out(cfg, s + 1, device="cuda"), cfg.lr, cfg.eps)
+            sums.append(out.clone())
+        state = [g.cache_state(t) for t in range(T)]
+        g.flush()
+        g.close()
+        runs.append((sums, Wp, Mp, state))
+    a, b = runs
+    assert all(torch.equal(x, y) for x, y in zip(a[0], b[0]))
+    assert all(torch.equal(x, y) for x, y in zip(a[1] + a[2], b[1] + b[2]))
+    for (ta, sa), (tb, sb) in zip(a[3], b[3]):
+        assert np.array_equal(ta, tb) and np.array_equal(sa, sb)
