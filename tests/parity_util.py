@@ -97,7 +97,7 @@ def compare_cache_step(o: Oracle, snap, T: int, ctx: str):
 
 def bag_peaks(cfg, o: Oracle, idx: np.ndarray, off: np.ndarray):
     """per table, per bag: the largest peak (see the header) among the rows the bag looks up; 0 for an empty bag"""
-    B, res = cfg.batch, []
+    B, res = (len(off) - 1) // cfg.num_tables, []
     for t in range(cfg.num_tables):
         o_t = off[t * B:(t + 1) * B + 1]
         pk = o.row_peak(t)[idx[o_t[0]:o_t[-1]]]
@@ -126,7 +126,7 @@ def compare_argmax(cfg, o: Oracle, idx: np.ndarray, off: np.ndarray, arg_g: np.n
     value must be that of the row it chose.  out_g is patched at those elements (they were checked here)."""
     a_o = o.argmax()
     assert a_o.shape == arg_g.shape
-    B = cfg.batch
+    B = (len(off) - 1) // cfg.num_tables
     cols = np.cumsum([0] + [tc.dim for tc in cfg.tables])
     flips = np.argwhere(a_o != arg_g)
     rows_seen = {}
@@ -151,6 +151,18 @@ def compare_argmax(cfg, o: Oracle, idx: np.ndarray, off: np.ndarray, arg_g: np.n
             f"{ctx}: bag {b} of table {t}, element {d}: pooled value {float(out_g[b, c])!r} is not that of the row that supplied it (row {r_g}: {w_g[d]!r})"
         out_g[b, c] = w_o[d]
     return len(flips)
+
+
+def first_bags(idx: torch.Tensor, off: torch.Tensor, T: int, n: int):
+    """the batch made of the first n bags of every table of a table-major CSR batch"""
+    B = (off.numel() - 1) // T
+    parts, lens = [], []
+    for t in range(T):
+        lo, hi = int(off[t * B]), int(off[t * B + n])
+        parts.append(idx[lo:hi])
+        lens.append(off[t * B + 1:t * B + n + 1] - off[t * B:t * B + n])
+    new_off = torch.cat([torch.zeros(1, dtype=torch.int64), torch.cumsum(torch.cat(lens), 0)])
+    return torch.cat(parts).contiguous(), new_off.contiguous()
 
 
 def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None, peak=None):
@@ -179,7 +191,7 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None, peak=None):
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
                pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None, deferred_init=None,
-               flush_every: int = 0, misuse: int = 0):
+               flush_every: int = 0, misuse: int = 0, vary_batch: int = 0):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -188,6 +200,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     nothing forwarded, a second forward, a flush with a batch in flight, a forward whose buffers are not those
     of the pending prefetch, a batch above the sizes given at creation, a change of policy or pooling after
     the first batch -- each checked for its error code; the run must come out as if they had not been made.
+    vary_batch = seed (0: off): every step trains on the first n bags of each table only, n drawn per step from
+    1..batch (the library is created for the full batch).
     flush_every = n ('serial' and 'inline' only, where no batch is in flight between steps): both sides
     flush after every n-th step, the backing tiers are compared, and training goes on.
     Cache state, counters and event sets are compared after every `check_every`-th
@@ -207,6 +221,11 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
                deferred_init=deferred_init)
     stream = synth.BatchStream(cfg, device="cpu")
     batches = [stream.next() for _ in range(steps)]
+    sizes = [cfg.batch] * steps
+    if vary_batch:
+        vr = np.random.default_rng(vary_batch)
+        sizes = [int(vr.choice([1, cfg.batch, int(vr.integers(1, cfg.batch + 1))])) for _ in range(steps)]
+        batches = [first_bags(i, f, T, n) for (i, f), n in zip(batches, sizes)]
     if max_lookups is None:
         max_lookups = max(int(b[0].numel()) for b in batches) + 1
     g = TBE(Wp, Mp, slots, cfg.ways, max_batch or cfg.batch, max_lookups, overlap=overlap, policy=policy, pooling=pooling,
@@ -292,11 +311,11 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
                     parted["at"], parted["elements"] = s + 1, n
             compare_forward(cfg, out_o, out_g, f"step {s + 1}",
                             peaks=bag_peaks(cfg, o, idx.numpy(), off.numpy()) if pooling == "max" else None)
-        o.backward_update(synth.grad_out(cfg, s + 1).numpy(), cfg.lr, cfg.eps)
+        o.backward_update(synth.grad_out(cfg, s + 1)[:sizes[s]].numpy(), cfg.lr, cfg.eps)
 
     pushed = 0
     for s in range(steps):
-        go = synth.grad_out(cfg, s + 1).to(device)
+        go = synth.grad_out(cfg, s + 1)[:sizes[s]].to(device)
         idx, off = dev[s]
         if order == "serial":
             gpu_prefetch(s)

@@ -57,7 +57,7 @@ def test_random_model_two_level(seed):
 def draw_options(seed):
     """every option of the library at once: a model as above plus second level, policy, pooling, deferred
     initialisation, a deeper prefetch queue, flushes between steps, the width of the sort payload, and calls
-    that must be refused sprinkled in between"""
+    that must be refused sprinkled in between, batches of varying size"""
     cfg, order, overlap = draw(seed)
     g = np.random.default_rng(seed)
     two = bool(g.integers(0, 2))
@@ -76,6 +76,8 @@ def draw_options(seed):
             kw["max_batch"] = min(kw["max_batch"], max(cfg.batch, (1 << 30) // sum(t.dim for t in cfg.tables)))
     if g.integers(0, 2):
         kw["misuse"] = seed + 1  # refused calls in between, see parity_util.run_parity
+    if g.integers(0, 3) == 0:
+        kw["vary_batch"] = seed + 2  # a different number of bags every step
     return cfg, dict(steps=steps, order=order, overlap=overlap, **kw)
 
 
