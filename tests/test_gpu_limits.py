@@ -16,6 +16,10 @@ pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 def test_rows_just_below_2_to_31_and_keys_above_it():
     from paper_2305_01515_amd.tbe import TBE
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    torch._C._host_emptyCache()  # 43 GB are pinned below; the box allows about 64 GiB in all
     rows, ways, sets, B, steps = (1 << 31) - 7, 8, 61, 64, 6
     T = synth.TableCfg
     cfg = synth.WorkloadCfg("limits", [T(rows, 8, synth.FP16, None, "fixed", 1, cache_slots=ways * sets),
