@@ -24,8 +24,9 @@ namespace tbe {
 
 typedef unsigned long long u64;
 constexpr int kMoveLanes = 16;
-constexpr int kLinkBlocks = 192;  // workgroups of the transfer kernel that work
-constexpr int kLinkXcds = 2;      // ... all placed on this many of the 8 XCDs
+constexpr int kLinkBlocks = 192;   // workgroups of the smaller kernels that write to the host link
+constexpr int kLinkCus = 48;       // workgroups of the transfer kernel: 1024 threads each, a CU each
+constexpr int kLinkThreads = 1024;
 
 // ---- deferred initialisation: counter-based normal numbers of (seed, table, row, element) ----
 // z = centred sum of twelve 16-bit uniforms (three 64-bit hashes per element, the finaliser of
@@ -84,7 +85,7 @@ __device__ inline void copy_row(char *dst, const char *src, uint32_t bytes, int 
   for (uint32_t c = lig * 16; c < bytes; c += kMoveLanes * 16) *(uint4 *)(dst + c) = *(const uint4 *)(src + c);
 }
 
-__global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCounters *cnt,
+__global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, const BatchCounters *cnt,
                                                        char *const *__restrict__ ins_src,
                                                        const int32_t *__restrict__ ins_tab,
                                                        const uint32_t *__restrict__ rb_of_table,
@@ -99,10 +100,12 @@ __global__ __launch_bounds__(256) void transfer_kernel(Staging st, const BatchCo
                                                        const uint32_t *__restrict__ ins_key,
                                                        const uint32_t *__restrict__ byp_key, u64 *bytes_h2d,
                                                        u64 *bytes_d2h) {
-  // Workgroups are dealt to the 8 XCDs round robin; only those landing on the first
-  // kLinkXcds work, so that the waves waiting on the host link sit on few CUs.
-  if ((int)(blockIdx.x & 7) >= kLinkXcds) return;
-  const int bid = (blockIdx.x >> 3) * kLinkXcds + (blockIdx.x & 7), n_blocks = (gridDim.x >> 3) * kLinkXcds;
+  // Waves that wait on the host link slow the memory accesses of every wave that shares their CU,
+  // so this kernel keeps its CUs to itself: a workgroup of 16 wavefronts that claims 128 vector
+  // registers per lane fills the register files of a CU's four SIMDs, and no wave of another
+  // kernel is placed beside it (the clobber makes the compiler allocate up to v127).
+  asm volatile("" ::: "v127");
+  const int bid = blockIdx.x, n_blocks = gridDim.x;
   const int n_wb = *st.wb_n;
   const int n_ins = (cnt && cnt->err == 0) ? cnt->n_ins : 0;
   const int n_byp = (cnt && cnt->err == 0) ? cnt->n_byp : 0;
@@ -225,17 +228,19 @@ __global__ void clear_wb_kernel(int32_t *wb_n) {
 
 hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, const DeferredInit &di, int k,
                            const uint32_t *rb_of_table, u64 *bytes_h2d, u64 *bytes_d2h, hipStream_t s) {
-  // How many workgroups wait on the host link, and on how many CUs, decides how the link and
-  // the HBM-bound kernels of the other streams slow each other (measured on the benchmark
-  // workload, step time / forward kernel time while the transfer runs; alone the forward
-  // takes 0.21 ms and the link needs 5.7 ms; the figures compare placements with each
-  // other -- later changes to the other stages lowered all of them by about a millisecond):
-  //   256 workgroups on all 8 XCDs : 7.6 ms / 1.2 ms     128 on all 8 : 8.0 ms / 0.29 ms
-  //   256 on 1 XCD (fills its CUs) : 8.3 ms / 0.20 ms    128 on 2     : 7.4 ms / 0.34 ms
-  //   192 on 2 XCDs                : 7.2 ms / 0.48 ms    128 on 1     : 7.2 ms / 0.43 ms
-  // Waves stalled on host requests hurt the gathers of whatever shares their CU, so they are
-  // kept on two XCDs, few enough per CU to leave room for the other kernels' workgroups.
-  hipLaunchKernelGGL(transfer_kernel, dim3(kLinkBlocks / kLinkXcds * 8), dim3(256), 0, s, st, b ? b->cnt : nullptr,
+  // How many waves wait on the host link, and where, decides how the link and the HBM-bound kernels
+  // of the other streams slow each other.  Measured on the benchmark workload (step / transfer
+  // kernel / prefetch stage / forward kernel while the transfer runs, ms; alone the forward takes
+  // 0.20 and the prefetch stage 0.94):
+  //   192 workgroups of 256 threads on two XCDs, CUs shared with other kernels : 6.40 / 5.63 / 4.8 / 0.45
+  //   512 such workgroups on two XCDs (they fill them)                         : 6.92 / 5.42 / 5.8 / 0.23
+  //   32 workgroups of 1024 threads, a CU each (any XCD)                       : 7.44 / 6.66 / 1.7 / 0.25
+  //   48                                                                       : 6.31 / 5.55 / 1.9 / 0.28
+  //   64                                                                       : 6.29 / 5.56 / 2.0 / 0.30
+  //   96                                                                       : 6.60 / 5.84 / 3.1 / 0.42
+  // The link needs about 750 waves; given CUs of their own (48 of 256) they leave the other
+  // streams' kernels at 1.3 to 2 times their stand-alone time instead of 2.5 to 5 times.
+  hipLaunchKernelGGL(transfer_kernel, dim3(kLinkCus), dim3(kLinkThreads), 0, s, st, b ? b->cnt : nullptr,
                      b ? b->ins_src : nullptr, b ? b->ins_tab : nullptr, rb_of_table,
                      b ? b->ins_where : nullptr, b ? b->byp_src : nullptr, b ? b->byp_tab : nullptr,
                      b ? b->byp_where : nullptr, b ? b->ovf : nullptr, (b && l2.on) ? b->l2v_src : nullptr,
