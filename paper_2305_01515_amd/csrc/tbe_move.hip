@@ -81,6 +81,15 @@ __device__ inline bool needs_init(const TableMeta &m, uint32_t row, int lig) {
   return (before & bit) == 0;
 }
 
+typedef uint32_t mv_u32x4 __attribute__((ext_vector_type(4)));
+// A row on its way to host memory: non-temporal stores (the transfer of the benchmark workload
+// 5.52 -> 5.36 ms; non-temporal loads from host memory change nothing).
+__device__ inline void copy_row_to_host(char *dst, const char *src, uint32_t bytes, int lig) {
+  for (uint32_t c = lig * 16; c < bytes; c += kMoveLanes * 16) {
+    const mv_u32x4 v = *(const mv_u32x4 *)(src + c);
+    __builtin_nontemporal_store(v, (mv_u32x4 *)(dst + c));
+  }
+}
 __device__ inline void copy_row(char *dst, const char *src, uint32_t bytes, int lig) {
   for (uint32_t c = lig * 16; c < bytes; c += kMoveLanes * 16) *(uint4 *)(dst + c) = *(const uint4 *)(src + c);
 }
@@ -157,7 +166,7 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
       }
       if (dst) {
         const uint32_t wrb = st.wb_rb[i];
-        copy_row(dst, st.out[st.wb_n[1] & 1] + (size_t)i * st.stride, wrb, lig);
+        copy_row_to_host(dst, st.out[st.wb_n[1] & 1] + (size_t)i * st.stride, wrb, lig);
         if (lig == 0) out_b += wrb;
       }
       if (wb2_dst) {  // second level: the row this victim pushed out of it goes to the lower tier
@@ -169,7 +178,7 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
         }
         if (dst2) {
           const uint32_t wrb = st.wb_rb[i];
-          copy_row(dst2, ((st.wb_n[1] & 1) ? out2_odd : out2_even) + (size_t)i * st.stride, wrb, lig);
+          copy_row_to_host(dst2, ((st.wb_n[1] & 1) ? out2_odd : out2_even) + (size_t)i * st.stride, wrb, lig);
           if (lig == 0) out_b += wrb;
         }
       }
@@ -350,7 +359,7 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
   if (wb_prev)
     for (int j = group; j < n_prev; j += n_groups) {
       const uint32_t rb = rb_of_table[prev_byp_tab[j]];
-      copy_row(prev_byp_src[j], prev_ovf + (size_t)j * st.stride, rb, lig);
+      copy_row_to_host(prev_byp_src[j], prev_ovf + (size_t)j * st.stride, rb, lig);
       if (lig == 0) out_b += rb;
     }
   for (int i = group; i < n_ins; i += n_groups) {
@@ -403,7 +412,7 @@ __global__ __launch_bounds__(256) void ovf_writeback_kernel(Staging st, const Ba
   u64 out_b = 0;
   for (int j = group; j < n_byp; j += n_groups) {
     const uint32_t rb = rb_of_table[byp_tab[j]];
-    copy_row(byp_src[j], ovf + (size_t)j * st.stride, rb, lig);
+    copy_row_to_host(byp_src[j], ovf + (size_t)j * st.stride, rb, lig);
     if (lig == 0) out_b += rb;
   }
   for (int d = 32; d >= 1; d >>= 1) out_b += __shfl_xor(out_b, d);
@@ -445,7 +454,7 @@ __global__ __launch_bounds__(256) void flush_kernel(const TableMeta *__restrict_
       if ((int64_t)tm[mid].slot_base <= slot) lo = mid; else hi = mid - 1;
     }
     const TableMeta &m = tm[lo];
-    copy_row(m.host_w + (size_t)row * m.row_bytes, m.lines + (size_t)(slot - m.slot_base) * m.row_bytes, m.row_bytes, lig);
+    copy_row_to_host(m.host_w + (size_t)row * m.row_bytes, m.lines + (size_t)(slot - m.slot_base) * m.row_bytes, m.row_bytes, lig);
     if (lig == 0) out_b += m.row_bytes;
   }
   for (int d = 32; d >= 1; d >>= 1) out_b += __shfl_xor(out_b, d);
