@@ -43,6 +43,24 @@ def test_ragged_sizes_span_tiles():
     run_parity(cfg, steps=3, order="serial")
 
 
+def test_sixteen_lane_rows_at_every_chunk_boundary():
+    """Rows of 16 lanes take the forward's unrolled path: a bag is read in chunks of 16 lookups, each chunk in
+    two halves of 8.  Fixed bag lengths on both sides of every boundary, rows that fill all 16 lanes and rows
+    that leave three idle, both storage types, cached tables and one without a cache (every row read from its
+    overflow copy)."""
+    T = synth.TableCfg
+    lengths = [1, 4, 5, 7, 8, 9, 12, 13, 15, 16, 17, 24, 25, 31, 32, 33]
+    tabs = []
+    for i, L in enumerate(lengths):
+        dtype = synth.FP16 if i % 2 else synth.FP32
+        full = 128 if dtype == synth.FP16 else 64
+        dim = full if i % 4 < 2 else full * 13 // 16
+        tabs.append(T(4000 + 37 * i, dim, dtype, 1.1, "fixed", L, cache_slots=0 if i % 5 == 4 else 16 * (11 + i)))
+    cfg = synth.WorkloadCfg("chunks", tabs, batch=50, ways=16, steps=3, seed=41, init_std=0.05, lr=0.05)
+    st = run_parity(cfg, steps=3, order="ahead")
+    assert st["total"]["bypasses"] > 0 and st["total"]["hits"] > 0
+
+
 def test_tiny_config_full():
     cfg = synth.config_tiny()
     st = run_parity(cfg, steps=cfg.steps, order="serial")
