@@ -229,7 +229,8 @@ int enqueue_commit(tbe_ctx *h, int bi, bool wb_prev) {
   BatchBuf &b = h->buf[bi];
   {
     StageTimer tm_(h, TBE_STAGE_COMMIT, h->ls);
-    HIP_TRY(h, launch_commit(h->d_tm, b, b.prev_bi >= 0 ? &h->buf[b.prev_bi] : nullptr, wb_prev, h->st, h->l2, h->d_rb,
+    const int prev_mode = !wb_prev ? kPrevKeep : b.parks_prev ? kPrevPark : kPrevWrite;
+    HIP_TRY(h, launch_commit(h->d_tm, b, b.prev_bi >= 0 ? &h->buf[b.prev_bi] : nullptr, prev_mode, h->st, h->l2, h->d_rb,
                              h->d_bytes + 1, h->ls));
   }
   HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->ls));
@@ -246,6 +247,9 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
   b.d_indices = d_indices; b.d_offsets = d_offsets; b.batch = batch; b.n = n; b.k = ++h->k;
   b.mean = h->pooling == TBE_POOL_MEAN;
   b.maxp = h->pooling == TBE_POOL_MAX;
+  // A batch prefetched while its predecessor is still in flight is committed right after that one's
+  // update, and its commit then parks the predecessor's overflow copies for the next transfer.
+  b.parks_prev = in_flight && h->prev_buf >= 0 && h->st.max_parked > 0 && !h->l2.on;
   h->total_lookups += n;
   h->last_buf = bi;
   if (h->as != h->cs) {
@@ -268,7 +272,9 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     // which of the rows to insert have a backing-tier copy that is still being written
     // (by the write-back of the previous batch's victims or by its backward), then move
     // the marks on from the previous batch to this one
-    HIP_TRY(h, launch_classify_mark(h->d_tm, h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr, b, h->st, h->l2, h->d_bytes + 5, h->as));
+    const BatchBuf *prev = h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr;
+    const BatchBuf *pp = (prev && prev->parks_prev && prev->prev_bi >= 0) ? &h->buf[prev->prev_bi] : nullptr;
+    HIP_TRY(h, launch_classify_mark(h->d_tm, pp, prev, b, h->st, h->l2, h->d_bytes + 5, h->as));
     hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total, h->d_bytes + 2,
                        h->l2.on ? h->d_l2tot : nullptr);
     HIP_TRY(h, hipGetLastError());
@@ -498,14 +504,18 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     std::vector<uint32_t> rb(num_tables);
     for (int t = 0; t < num_tables; t++) { rb[t] = h->tm[t].row_bytes; st.stride = std::max(st.stride, rb[t]); }
     const size_t M = (size_t)st.max_inserts;
+    // room behind the victims for the overflow copies a commit parks with them (a batch bypasses at
+    // most as many rows as it has lookups); none when the indices would not fit the map's codes
+    st.max_parked = (M + (size_t)max_lookups <= (size_t)kWhereIndex) ? max_lookups : 0;
+    const size_t P = M + (size_t)st.max_parked;
     CREATE_TRY(h->mem.get(&st.in, M * st.stride));
     for (int p2 = 0; p2 < 2; p2++) {
-      CREATE_TRY(h->mem.get(&st.out[p2], M * st.stride));
-      CREATE_TRY(h->mem.get(&st.wb_skip[p2], M));
-      CREATE_TRY(hipMemset(st.wb_skip[p2], 0, M ? M : 1));
+      CREATE_TRY(h->mem.get(&st.out[p2], P * st.stride));
+      CREATE_TRY(h->mem.get(&st.wb_skip[p2], P));
+      CREATE_TRY(hipMemset(st.wb_skip[p2], 0, P ? P : 1));
     }
-    CREATE_TRY(h->mem.get(&st.wb_dst, 8 * M));
-    CREATE_TRY(h->mem.get(&st.wb_rb, 4 * M));
+    CREATE_TRY(h->mem.get(&st.wb_dst, 8 * P));
+    CREATE_TRY(h->mem.get(&st.wb_rb, 4 * P));
     CREATE_TRY(h->mem.get(&st.wb_n, 16));
     CREATE_TRY(hipMemset(st.wb_n, 0, 16));
     CREATE_TRY(h->mem.get(&st.where, 4 * (size_t)key));
@@ -632,7 +642,13 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
     int rc = enqueue_commit(h, d, true);
     return rc ? rc : pump_queue(h);
   }
-  HIP_TRY(h, launch_ovf_writeback(h->buf[bi], h->st, h->d_rb, h->d_bytes + 1, h->ls));
+  {
+    // no batch has been prefetched after this one, so no transfer has run since its commit: the
+    // overflow copies that commit parked (the previous batch's) go home first, then this batch's
+    const BatchBuf &b = h->buf[bi];
+    const BatchBuf *parked_prev = (b.parks_prev && b.prev_bi >= 0) ? &h->buf[b.prev_bi] : nullptr;
+    HIP_TRY(h, launch_ovf_writeback(b, parked_prev, h->st, h->d_rb, h->d_bytes + 1, h->ls));
+  }
   return pump_queue(h);
 }
 
@@ -646,7 +662,9 @@ int tbe_flush(tbe_handle h) {
     // Every copy in the backing tier is current now, so the next batch must find no row marked
     // "still on its way".  Left in place, such a mark would make that batch ask the transfer to skip
     // a write-back that has already happened, and the request would hit a later batch's victim.
-    HIP_TRY(h, launch_unmark(h->d_tm, h->buf[h->prev_buf], h->st, h->l2, h->cs));
+    const BatchBuf &last = h->buf[h->prev_buf];
+    HIP_TRY(h, launch_unmark(h->d_tm, last, (last.parks_prev && last.prev_bi >= 0) ? &h->buf[last.prev_bi] : nullptr, h->st,
+                             h->l2, h->cs));
     h->prev_buf = -1;
   }
   HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->l2, h->d_bytes, h->d_bytes + 1, h->cs));

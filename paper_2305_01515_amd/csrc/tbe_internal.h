@@ -144,6 +144,7 @@ struct BatchBuf {
   int64_t n;
   int32_t k;
   int32_t prev_bi;      // buffer of the batch prefetched before this one, -1 = none
+  bool parks_prev;      // this batch's commit parks the overflow copies of the batch before it among its victims
 };
 
 // Scratch shared by all batches (only used inside the prefetch stage, which is serial).
@@ -162,7 +163,7 @@ struct SortScratch {
 //          is taken from here instead of making the round trip over the link
 struct Staging {
   char *in;            // [max_inserts * stride]
-  char *out[2];        // [max_inserts * stride] each
+  char *out[2];        // [(max_inserts + max_parked) * stride] each
   char **wb_dst;       // [max_inserts] backing-tier row of each staged victim (null = none)
   uint32_t *wb_rb;     // [max_inserts] row bytes
   uint8_t *wb_skip[2]; // [max_inserts] by parity of the batch that parked the victim: 1 = the next batch
@@ -172,6 +173,7 @@ struct Staging {
                        // backing-tier copy is stale (kWhereOverflow | j, kWhereParked | i)
   uint32_t stride;     // bytes per staged row (widest row)
   int64_t max_inserts;
+  int64_t max_parked;  // room behind the victims for the overflow copies parked with them (0: they are never parked)
 };
 
 // Second-level cache: tags and timestamps in HBM, lines in pinned host memory (TableMeta),
@@ -232,16 +234,20 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l
                            unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
 // look up, for the rows cur inserts or bypasses, whether their backing-tier copy is stale
 // and where the current value is; then remove prev's entries from the map and enter cur's
-hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, const Staging &st,
-                                const Level2 &l2, unsigned long long *n_late, hipStream_t s);
-// move b's victims to the staging area and its new rows into the cache lines
-// (prev = the batch before, null if none; wb_prev: also write prev's overflow rows back)
-hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, bool wb_prev, const Staging &st,
+// pp: the batch before prev when prev's commit parked pp's overflow copies (their marks go now), else null
+hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *pp, const BatchBuf *prev, const BatchBuf &cur,
+                                const Staging &st, const Level2 &l2, unsigned long long *n_late, hipStream_t s);
+// prev_mode: what becomes of prev's overflow copies: kPrevKeep (nothing), kPrevWrite (to the backing tier now),
+// kPrevPark (among this batch's parked victims: the next transfer writes them)
+constexpr int kPrevKeep = 0, kPrevWrite = 1, kPrevPark = 2;
+hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, int prev_mode, const Staging &st,
                          const Level2 &l2, const uint32_t *rb_of_table, unsigned long long *bytes_d2h, hipStream_t s);
 // after the batch's backward: its bypassed rows go from their HBM copies to the backing tier
-hipError_t launch_ovf_writeback(const BatchBuf &b, const Staging &st, const uint32_t *rb_of_table,
-                                unsigned long long *bytes_d2h, hipStream_t s);
-hipError_t launch_unmark(const TableMeta *tm, const BatchBuf &last, const Staging &st, const Level2 &l2, hipStream_t s);
+// parked_prev: the batch whose overflow copies b's commit parked and no transfer has written yet (else null)
+hipError_t launch_ovf_writeback(const BatchBuf &b, const BatchBuf *parked_prev, const Staging &st,
+                                const uint32_t *rb_of_table, unsigned long long *bytes_d2h, hipStream_t s);
+hipError_t launch_unmark(const TableMeta *tm, const BatchBuf &last, const BatchBuf *parked_prev, const Staging &st,
+                         const Level2 &l2, hipStream_t s);
 hipError_t launch_flush(const TableMeta *tm, const Geometry &g, const int32_t *tags, const Level2 &l2,
                         unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
 hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,

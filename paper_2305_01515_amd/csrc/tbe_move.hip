@@ -262,15 +262,24 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l
 // Enter (set) or remove (clear) in the map the rows whose backing-tier copy batch `b` leaves
 // stale for a while: the rows it evicted (parked victim i, written back by the next
 // transfer) and the rows it bypassed (overflow copy j, written back after its backward).
+// byp_mode: what the rows the batch bypassed get: kMarkClear, kMarkOverflow (overflow copy j of this
+// batch) or kMarkParked (the next batch's commit parks copy j behind its own n_ins victims:
+// kWhereParked | (next->n_ins + j)).  vic_mode: kMarkClear / kMarkOverflow (= set) for its victims, or
+// kMarkKeep to leave them alone.
+constexpr int kMarkClear = 0, kMarkOverflow = 1, kMarkParked = 2, kMarkKeep = 3;
+
 __global__ __launch_bounds__(256) void mark_kernel(const TableMeta *__restrict__ tm, const BatchCounters *cnt,
                                                    const int32_t *__restrict__ ins_tab,
                                                    const int32_t *__restrict__ ins_old,
                                                    const uint32_t *__restrict__ byp_key,
                                                    char *const *__restrict__ l2v_src,
                                                    const uint32_t *__restrict__ l2v_key, uint32_t max_inserts,
-                                                   uint32_t *where, int set) {
+                                                   uint32_t *where, int vic_mode, int byp_mode,
+                                                   const BatchCounters *next_cnt) {
   if (cnt->err) return;
-  const int n_ins = cnt->n_ins, n_byp = cnt->n_byp;
+  const int n_ins = vic_mode == kMarkKeep ? 0 : cnt->n_ins, n_byp = cnt->n_byp;
+  const int set = vic_mode != kMarkClear;
+  const uint32_t park_base = (byp_mode == kMarkParked && next_cnt) ? (uint32_t)next_cnt->n_ins : 0u;
   const int stride = gridDim.x * blockDim.x;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_ins + n_byp; i += stride) {
     if (i < n_ins) {
@@ -279,7 +288,8 @@ __global__ __launch_bounds__(256) void mark_kernel(const TableMeta *__restrict__
       // the row pushed out of the second level is staged like a victim, behind the victims
       if (l2v_src && l2v_src[i]) where[l2v_key[i]] = set ? (kWhereParked | (max_inserts + (uint32_t)i)) : 0u;
     } else {
-      where[byp_key[i - n_ins]] = set ? (kWhereOverflow | (uint32_t)(i - n_ins)) : 0u;
+      const uint32_t j = (uint32_t)(i - n_ins);
+      where[byp_key[j]] = byp_mode == kMarkOverflow ? (kWhereOverflow | j) : byp_mode == kMarkParked ? (kWhereParked | (park_base + j)) : 0u;
     }
   }
 }
@@ -304,29 +314,49 @@ __global__ __launch_bounds__(256) void classify_kernel(const BatchCounters *cnt,
   if ((threadIdx.x & 63) == 0 && late) atomicAdd(n_late, (unsigned long long)late);
 }
 
-hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, const Staging &st,
-                                const Level2 &l2, u64 *n_late, hipStream_t s) {
+hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *pp, const BatchBuf *prev, const BatchBuf &cur,
+                                const Staging &st, const Level2 &l2, u64 *n_late, hipStream_t s) {
   const uint32_t M = (uint32_t)st.max_inserts;
   hipLaunchKernelGGL(classify_kernel, dim3(512), dim3(256), 0, s, cur.cnt, cur.ins_key, cur.byp_key, st.where,
                      cur.ins_where, cur.byp_where, st.wb_skip[(cur.k - 1) & 1], n_late);
+  // The marks move on in this order (a later one may overwrite an earlier one's entry, never the
+  // other way round): the overflow copies that prev's commit parked are home once the transfer of
+  // this batch is through; prev's victims likewise; prev's own overflow copies are either home
+  // already or will be parked by this batch's commit behind its victims; then this batch's rows.
+  if (pp)
+    hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, pp->cnt, pp->ins_tab, pp->ins_old, pp->byp_key,
+                       (char *const *)nullptr, (const uint32_t *)nullptr, M, st.where, kMarkKeep, kMarkClear,
+                       (const BatchCounters *)nullptr);
   if (prev)
     hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, prev->cnt, prev->ins_tab, prev->ins_old, prev->byp_key,
-                       l2.on ? prev->l2v_src : nullptr, prev->l2v_key, M, st.where, 0);
+                       l2.on ? prev->l2v_src : nullptr, prev->l2v_key, M, st.where, kMarkClear,
+                       cur.parks_prev ? kMarkParked : kMarkClear, cur.cnt);
   hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, cur.cnt, cur.ins_tab, cur.ins_old, cur.byp_key,
-                     l2.on ? cur.l2v_src : nullptr, cur.l2v_key, M, st.where, 1);
+                     l2.on ? cur.l2v_src : nullptr, cur.l2v_key, M, st.where, kMarkOverflow, kMarkOverflow,
+                     (const BatchCounters *)nullptr);
   return hipGetLastError();
 }
 
-// After a flush nothing is on its way to the backing tier any more: the marks of the last batch go.
-hipError_t launch_unmark(const TableMeta *tm, const BatchBuf &last, const Staging &st, const Level2 &l2, hipStream_t s) {
+// After a flush nothing is on its way to the backing tier any more: the marks of the last batch go,
+// and those of the overflow copies its commit parked (parked_prev: the batch they belonged to).
+hipError_t launch_unmark(const TableMeta *tm, const BatchBuf &last, const BatchBuf *parked_prev, const Staging &st,
+                         const Level2 &l2, hipStream_t s) {
+  if (parked_prev)
+    hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, parked_prev->cnt, parked_prev->ins_tab,
+                       parked_prev->ins_old, parked_prev->byp_key, (char *const *)nullptr, (const uint32_t *)nullptr,
+                       (uint32_t)st.max_inserts, st.where, kMarkKeep, kMarkClear, (const BatchCounters *)nullptr);
   hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, last.cnt, last.ins_tab, last.ins_old, last.byp_key,
-                     l2.on ? last.l2v_src : nullptr, last.l2v_key, (uint32_t)st.max_inserts, st.where, 0);
+                     l2.on ? last.l2v_src : nullptr, last.l2v_key, (uint32_t)st.max_inserts, st.where, kMarkClear, kMarkClear,
+                     (const BatchCounters *)nullptr);
   return hipGetLastError();
 }
 
 // The batch before (`prev`, may be absent) has trained when this runs, so a late row's
 // current value is where its code says: prev's overflow copy or prev's parked victim, both
-// still in HBM.  With wb_prev set the kernel also writes prev's overflow rows back.
+// still in HBM.  prev_mode says what becomes of prev's overflow rows: written back here (kPrevWrite), or
+// parked behind this batch's victims for the next transfer to write them (kPrevPark): the link's
+// write direction then carries them beside that transfer's fetches, which costs the transfer a
+// hundredth of its time, instead of alone between two transfers.
 __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict__ tm, Staging st,
                                                      const BatchCounters *cnt, const int32_t *__restrict__ ins_tab,
                                                      const uint32_t *__restrict__ ins_where,
@@ -352,15 +382,25 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
   const int n_groups = gridDim.x * blockDim.x / kMoveLanes;
   const int par = k & 1, ppar = par ^ 1;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    st.wb_n[0] = n_ins;
+    st.wb_n[0] = n_ins + (wb_prev == kPrevPark ? n_prev : 0);
     st.wb_n[1] = par;
   }
   u64 out_b = 0;
-  if (wb_prev)
+  if (wb_prev == kPrevWrite)
     for (int j = group; j < n_prev; j += n_groups) {
       const uint32_t rb = rb_of_table[prev_byp_tab[j]];
       copy_row_to_host(prev_byp_src[j], prev_ovf + (size_t)j * st.stride, rb, lig);
       if (lig == 0) out_b += rb;
+    }
+  if (wb_prev == kPrevPark)
+    for (int j = group; j < n_prev; j += n_groups) {
+      const uint32_t rb = rb_of_table[prev_byp_tab[j]];
+      const size_t slot = (size_t)n_ins + (size_t)j;
+      copy_row(st.out[par] + slot * st.stride, prev_ovf + (size_t)j * st.stride, rb, lig);
+      if (lig == 0) {
+        st.wb_dst[slot] = prev_byp_src[j];
+        st.wb_rb[slot] = rb;
+      }
     }
   for (int i = group; i < n_ins; i += n_groups) {
     const TableMeta &m = tm[ins_tab[i]];
@@ -372,7 +412,7 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
     const uint32_t ix = code & kWhereIndex;
     const char *src = code == 0             ? st.in + (size_t)i * st.stride
                       : (code & kWhereOverflow) ? prev_ovf + (size_t)ix * st.stride
-                      : ix >= M                 ? out2_prev + (size_t)(ix - M) * st.stride
+                      : (out2_prev && ix >= M)  ? out2_prev + (size_t)(ix - M) * st.stride
                                                 : st.out[ppar] + (size_t)ix * st.stride;
     char *park = st.out[par] + (size_t)i * st.stride;
     for (uint32_t c = lig * 16; c < rb; c += kMoveLanes * 16) {
@@ -391,7 +431,7 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
     if (code == 0) continue;
     const uint32_t ix = code & kWhereIndex;
     const char *src = (code & kWhereOverflow) ? prev_ovf + (size_t)ix * st.stride
-                      : ix >= M               ? out2_prev + (size_t)(ix - M) * st.stride
+                      : (out2_prev && ix >= M) ? out2_prev + (size_t)(ix - M) * st.stride
                                               : st.out[ppar] + (size_t)ix * st.stride;
     copy_row(ovf + (size_t)j * st.stride, src, rb_of_table[byp_tab[j]], lig);
   }
@@ -419,20 +459,51 @@ __global__ __launch_bounds__(256) void ovf_writeback_kernel(Staging st, const Ba
   if ((threadIdx.x & 63) == 0 && out_b) atomicAdd(bytes_d2h, out_b);
 }
 
-hipError_t launch_ovf_writeback(const BatchBuf &b, const Staging &st, const uint32_t *rb_of_table, u64 *bytes_d2h,
-                                hipStream_t s) {
-  if (b.n == 0) return hipSuccess;
+// The overflow copies that batch b's commit parked behind its victims (those of the batch before
+// it), written to the backing tier ahead of their turn: they must be home before b's own, newer
+// copies of the same rows are written.  Their slots are emptied, so the next transfer passes them by.
+__global__ __launch_bounds__(256) void parked_copies_writeback_kernel(Staging st, const BatchCounters *cnt,
+                                                                      const BatchCounters *prev_cnt, u64 *bytes_d2h) {
+  if (cnt->err || prev_cnt->err) return;
+  const int base = cnt->n_ins, n = prev_cnt->n_byp;
+  const char *out = st.out[st.wb_n[1] & 1];
+  const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
+  const int lig = threadIdx.x % kMoveLanes;
+  const int n_groups = gridDim.x * blockDim.x / kMoveLanes;
+  u64 out_b = 0;
+  for (int j = group; j < n; j += n_groups) {
+    const size_t slot = (size_t)base + (size_t)j;
+    char *dst = st.wb_dst[slot];
+    if (dst) {
+      const uint32_t rb = st.wb_rb[slot];
+      copy_row_to_host(dst, out + slot * st.stride, rb, lig);
+      if (lig == 0) out_b += rb;
+    }
+  }
+  __syncthreads();  // every lane of a group has read its slot's destination
+  for (int j = group; j < n; j += n_groups)
+    if (lig == 0) st.wb_dst[(size_t)base + (size_t)j] = nullptr;
+  for (int d = 32; d >= 1; d >>= 1) out_b += __shfl_xor(out_b, d);
+  if ((threadIdx.x & 63) == 0 && out_b) atomicAdd(bytes_d2h, out_b);
+}
+
+hipError_t launch_ovf_writeback(const BatchBuf &b, const BatchBuf *parked_prev, const Staging &st,
+                                const uint32_t *rb_of_table, u64 *bytes_d2h, hipStream_t s) {
+  if (parked_prev)
+    hipLaunchKernelGGL(parked_copies_writeback_kernel, dim3(kLinkBlocks), dim3(256), 0, s, st, b.cnt, parked_prev->cnt,
+                       bytes_d2h);
+  if (b.n == 0) return hipGetLastError();
   hipLaunchKernelGGL(ovf_writeback_kernel, dim3(kLinkBlocks), dim3(256), 0, s, st, b.cnt, b.byp_src, b.byp_tab, b.ovf,
                      rb_of_table, bytes_d2h);
   return hipGetLastError();
 }
 
-hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, bool wb_prev, const Staging &st,
+hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, int prev_mode, const Staging &st,
                          const Level2 &l2, const uint32_t *rb_of_table, u64 *bytes_d2h, hipStream_t s) {
   hipLaunchKernelGGL(commit_kernel, dim3(4096), dim3(256), 0, s, tm, st, b.cnt, b.ins_tab, b.ins_where, b.ins_slot,
                      b.ins_old, b.byp_tab, b.byp_where, b.ovf, prev ? prev->cnt : nullptr,
                      prev ? prev->byp_src : nullptr, prev ? prev->byp_tab : nullptr, prev ? prev->ovf : nullptr,
-                     (prev && wb_prev) ? 1 : 0, b.k, l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr,
+                     prev ? prev_mode : kPrevKeep, b.k, l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr,
                      l2.on ? b.l2v_dst : nullptr, l2.on ? l2.wb2_dst : nullptr, l2.out2[(b.k & 1) ^ 1], rb_of_table,
                      bytes_d2h);
   return hipGetLastError();
