@@ -118,11 +118,43 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
   const int n_wb = *st.wb_n;
   const int n_ins = (cnt && cnt->err == 0) ? cnt->n_ins : 0;
   const int n_byp = (cnt && cnt->err == 0) ? cnt->n_byp : 0;
-  const int n = max(n_wb, max(n_ins, n_byp));
+  // One pass of the loop fetches item i and writes back slot i.  When there are more slots to write
+  // than items to fetch (the overflow copies parked behind the victims), the surplus is paired with
+  // the first passes (slot i + n) instead of forming a tail of passes that only write: the link's two
+  // directions stay busy together to the end.
+  const int n = max((n_wb + 1) / 2, max(n_ins, n_byp));
   const int group = (bid * blockDim.x + threadIdx.x) / kMoveLanes;
   const int lig = threadIdx.x % kMoveLanes;
   const int n_groups = n_blocks * blockDim.x / kMoveLanes;
   u64 in_b = 0, out_b = 0;
+  const int wpar = st.wb_n[1] & 1;
+  auto write_back = [&](int w) {
+    if (w >= n_wb) return;
+    char *dst = st.wb_dst[w];
+    uint8_t *skip = st.wb_skip[wpar] + w;
+    if (*skip) {  // the batch being prefetched takes this row back from the parked copy: the
+      dst = nullptr;  // line stays dirty in HBM and is written back when it is evicted again
+      if (lig == 0) *skip = 0;
+    }
+    if (dst) {
+      const uint32_t wrb = st.wb_rb[w];
+      copy_row_to_host(dst, st.out[wpar] + (size_t)w * st.stride, wrb, lig);
+      if (lig == 0) out_b += wrb;
+    }
+    if (wb2_dst) {  // second level: the row this victim pushed out of it goes to the lower tier
+      char *dst2 = wb2_dst[w];
+      uint8_t *skip2 = st.wb_skip[wpar] + st.max_inserts + w;
+      if (dst2 && *skip2) {
+        dst2 = nullptr;
+        if (lig == 0) *skip2 = 0;
+      }
+      if (dst2) {
+        const uint32_t wrb = st.wb_rb[w];
+        copy_row_to_host(dst2, (wpar ? out2_odd : out2_even) + (size_t)w * st.stride, wrb, lig);
+        if (lig == 0) out_b += wrb;
+      }
+    }
+  };
   for (int i = group; i < n; i += n_groups) {
     // issue the host read first, then the write-back, so both directions are busy
     uint4 fresh[4];
@@ -157,32 +189,8 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
         }
       }
     }
-    if (i < n_wb) {
-      char *dst = st.wb_dst[i];
-      uint8_t *skip = st.wb_skip[st.wb_n[1] & 1] + i;
-      if (*skip) {  // the batch being prefetched takes this row back from the parked copy: the
-        dst = nullptr;  // line stays dirty in HBM and is written back when it is evicted again
-        if (lig == 0) *skip = 0;
-      }
-      if (dst) {
-        const uint32_t wrb = st.wb_rb[i];
-        copy_row_to_host(dst, st.out[st.wb_n[1] & 1] + (size_t)i * st.stride, wrb, lig);
-        if (lig == 0) out_b += wrb;
-      }
-      if (wb2_dst) {  // second level: the row this victim pushed out of it goes to the lower tier
-        char *dst2 = wb2_dst[i];
-        uint8_t *skip2 = st.wb_skip[st.wb_n[1] & 1] + st.max_inserts + i;
-        if (dst2 && *skip2) {
-          dst2 = nullptr;
-          if (lig == 0) *skip2 = 0;
-        }
-        if (dst2) {
-          const uint32_t wrb = st.wb_rb[i];
-          copy_row_to_host(dst2, ((st.wb_n[1] & 1) ? out2_odd : out2_even) + (size_t)i * st.stride, wrb, lig);
-          if (lig == 0) out_b += wrb;
-        }
-      }
-    }
+    write_back(i);
+    write_back(i + n);  // the slots beyond the loop's length ride along with the first ones
     if (l2v_src && i < n_ins) {  // second level: the row an insert's victim pushes out is read while its
       const char *src = l2v_src[i];  // line still holds it (the victim is written there by the next transfer)
       if (src) {
