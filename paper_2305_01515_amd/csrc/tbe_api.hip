@@ -192,6 +192,7 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.items, 4 * (N / kLongRun + 1)));
   HIP_TRY(h, h->mem.get(&b.huge, 4 * (N / kHugeRun + 1)));
   HIP_TRY(h, h->mem.get(&b.huge_sorted, 4 * (N / kHugeRun + 1)));
+  HIP_TRY(h, h->mem.get(&b.wide, 4 * (N / kHugeRun + 1)));
   HIP_TRY(h, h->mem.get(&b.hchunks, 16 * (N / kHugeRun + (size_t)h->g.T + 1)));
   HIP_TRY(h, h->mem.get(&b.hg_count, 4 * 3 * ((size_t)h->g.T + 1)));
   HIP_TRY(h, h->mem.get(&b.hstart, 4 * h->huge_slots));
@@ -616,8 +617,10 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
     HIP_TRY(h, launch_backward_classes(2, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
   }
   {
+    // with the combine of the huge rows' partial sums, which both this kernel and the one before fill
     StageTimer tm_(h, TBE_STAGE_BACKWARD_LONG, h->cs);
     HIP_TRY(h, launch_backward_classes(0, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(3, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SINGLE, h->cs);

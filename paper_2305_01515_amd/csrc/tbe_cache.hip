@@ -273,10 +273,14 @@ __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__res
 // of huge rows is small (a batch has fewer than N / kHugeRun of them).
 __global__ __launch_bounds__(1024) void huge_group_kernel(const TableMeta *__restrict__ tm, int T,
                                                           const int32_t *__restrict__ huge,
-                                                          const int32_t *__restrict__ uniq_tab, int32_t *huge_sorted,
-                                                          uint4 *hchunks, int32_t *hg, BatchCounters *cnt) {
+                                                          const int32_t *__restrict__ uniq_tab,
+                                                          const int32_t *__restrict__ run_off, int32_t *huge_sorted,
+                                                          int32_t *wide, uint4 *hchunks, int32_t *hg,
+                                                          BatchCounters *cnt) {
+  __shared__ int s_wide;
   if (cnt->err) return;
   const int n_huge = cnt->n_huge;
+  if (threadIdx.x == 0) s_wide = 0;
   int32_t *count = hg, *offset = hg + (T + 1), *fill = hg + 2 * (T + 1);
   for (int t = threadIdx.x; t <= T; t += blockDim.x) count[t] = offset[t] = fill[t] = 0;
   __syncthreads();
@@ -295,9 +299,13 @@ __global__ __launch_bounds__(1024) void huge_group_kernel(const TableMeta *__res
   }
   __syncthreads();
   for (int h = threadIdx.x; h < n_huge; h += blockDim.x) {
-    const int t = uniq_tab[huge[h]];
+    const int u = huge[h];
+    const int t = uniq_tab[u];
     huge_sorted[offset[t] + atomicAdd(&fill[t], 1)] = h;
+    if (run_off[u + 1] - run_off[u] > kWideRun) wide[atomicAdd(&s_wide, 1)] = h;
   }
+  __syncthreads();
+  if (threadIdx.x == 0) cnt->n_wide = s_wide;
 }
 
 // For every huge row and bag range: the first sorted position of the row whose bag lies in
@@ -679,7 +687,7 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   hipLaunchKernelGGL(worklist_count_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, huge_from, b.cnt);
   hipLaunchKernelGGL(worklist_emit_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, b.mid_idx, b.items,
                      b.huge, huge_from, b.cnt);
-  hipLaunchKernelGGL(huge_group_kernel, dim3(1), dim3(1024), 0, s, tm, g.T, b.huge, b.uniq_tab, b.huge_sorted, b.hchunks,
+  hipLaunchKernelGGL(huge_group_kernel, dim3(1), dim3(1024), 0, s, tm, g.T, b.huge, b.uniq_tab, b.run_off, b.huge_sorted, b.wide, b.hchunks,
                      b.hg_count, b.cnt);
   hipLaunchKernelGGL(huge_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.huge, b.uniq_tab, b.run_off,
                      b.sorted_bag, b.hstart, b.cnt);

@@ -624,6 +624,10 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
                                                             const float *__restrict__ inv_len,
                                                             const int32_t *__restrict__ argpos,
                                                             const int32_t *__restrict__ sorted_within,
+                                                            const int32_t *__restrict__ huge,
+                                                            const int32_t *__restrict__ wide,
+                                                            const int32_t *__restrict__ hstart,
+                                                            float *__restrict__ partials, int pstride,
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int NG = 256 / G;
@@ -657,6 +661,43 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
         g[e] = s;
       }
       update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
+    }
+  }
+  // The widest rows (more than kWideRun lookups: a table with a steep power law and long bags has
+  // rows with a quarter of its lookups) would each keep one lane group of the tile kernel below busy
+  // long after the others of its chunk are done, so that kernel leaves them out.  They are summed
+  // here the same way as the rows above, a workgroup per (row, bag range of the tile kernel): the
+  // lookups of such a row visit nearly every bag in ascending order, several times each, so the
+  // gradient reads stay in L1 / L2.  The sums go to the row's slots of `partials` for the combine kernel.
+  const int R = huge_ranges(cnt->n_hchunks);
+  const int n_wide_work = cnt->n_wide * R;
+  xcd_span(n_wide_work, 1, first, end, step);
+  for (int wk = first; wk < end; wk += step) {
+    const int h = wide[wk / R], range = wk % R;
+    const int u = huge[h];
+    const int t = uniq_tab[u];
+    if (table_class[t] != cls) continue;  // uniform over the block
+    const TableMeta &m = tm[t];
+    const bool active = lig * EPL < m.dim;
+    const int i0 = hstart[h * R + range];
+    const int i1 = range + 1 < R ? hstart[h * R + range + 1] : run_off[u + 1];
+    float g[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; e++) g[e] = 0.f;
+    reduce_grads<DT, G, MODE>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, grp, NG, lig, active,
+                              inv_len, MODE == kMax ? argpos + m.col + lig * EPL : nullptr, sorted_within);
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < EPL; e++) part[grp][lig * EPL + e] = g[e];
+    __syncthreads();
+    if (grp == 0) {
+      float *p = partials + ((size_t)h * R + range) * pstride + lig * EPL;
+#pragma unroll
+      for (int e = 0; e < EPL; e++) {
+        float sum = 0.f;
+        for (int q = 0; q < NG; q++) sum += part[q][lig * EPL + e];
+        p[e] = sum;
+      }
     }
   }
 }
@@ -702,11 +743,12 @@ __global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__r
     if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
     const int dim = m.dim;
-    const bool has_row = grp < (int)ch.z;
+    bool has_row = grp < (int)ch.z;
     const int h = has_row ? huge_sorted[ch.y + grp] : 0;
     const int u = huge[h];
     const int bag0 = t * B;
     const int i1 = has_row ? run_off[u + 1] : 0;
+    if (has_row && i1 - run_off[u] > kWideRun) has_row = false;  // left to backward_wide_kernel
     const int tile_lo = range * tiles_per_range, tile_hi = min(n_tiles, tile_lo + tiles_per_range);
     int i = has_row ? hstart[h * R + range] : 0;  // first lookup of the row in this bag range
     float g[EPL];
@@ -864,6 +906,7 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
     hipLaunchKernelGGL((backward_huge_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.hchunks,
                        b.huge_sorted, b.huge, b.hstart, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride, table_class,
                        b.mean ? b.inv_len : nullptr, b.cnt);
+  } else if (which == 3) {
     hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(1024), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
                        b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   } else if (which == 0) {
@@ -871,7 +914,8 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
                 : b.mean ? backward_long_kernel<DT, G, kMean> : backward_long_kernel<DT, G, kSum>;
     hipLaunchKernelGGL(kern, dim3(8192), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items, b.uniq_key, b.uniq_tab,
                        b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class,
-                       b.mean ? b.inv_len : nullptr, b.argpos, b.sorted_within, b.cnt);
+                       b.mean ? b.inv_len : nullptr, b.argpos, b.sorted_within, b.huge, b.wide, b.hstart, partials,
+                       g.partial_stride, b.cnt);
   } else {
     auto kern = b.maxp ? backward_short_kernel<DT, G, kMax>
                 : b.mean ? backward_short_kernel<DT, G, kMean> : backward_short_kernel<DT, G, kSum>;
@@ -936,9 +980,10 @@ hipError_t launch_backward_single_classes(const TableMeta *tm, const ClassInfo &
   return hipGetLastError();
 }
 
-// which: 0 = rows with kLongRun < lookups <= kHugeRun (workgroup per row), 1 = rows with
-// 2..kLongRun lookups (group per row), 2 = rows with more than kHugeRun lookups (gradient
-// tiles + combine).  A step runs all three and the single-lookup kernel; they touch
+// which: 0 = rows with kLongRun < lookups <= kHugeRun (workgroup per row; also the bag ranges of the
+// rows with more than kWideRun lookups), 1 = rows with 2..kLongRun lookups (group per row), 2 = rows
+// with more than kHugeRun lookups (gradient tiles), 3 = the combine of those rows' partial sums
+// (after 2 and 0).  A step runs all three and the single-lookup kernel; they touch
 // disjoint rows.
 hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
                                    const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,

@@ -18,6 +18,10 @@ constexpr int kHugeRanges = 64;           // each huge row's sum is split over a
 constexpr int kHugeTargetItems = 2048;    // ... and over more when the batch has few huge rows, so that the
 constexpr int kHugeMaxRanges = 1024;      //     kernel still has about this many work items (at most this many ranges)
 constexpr int kTileBytes = 16384;         // gradient tile in LDS
+#ifndef TBE_WIDE_RUN
+#define TBE_WIDE_RUN 32768
+#endif
+constexpr int kWideRun = TBE_WIDE_RUN;    // huge rows with more lookups: a whole workgroup per (row, bag range)
 
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
 constexpr uint32_t kWhereParked = 0x40000000u;    // among the victims the batch before parked
@@ -72,6 +76,7 @@ struct BatchCounters {
   unsigned long long hits, evictions, hit_lookups;
   int32_t n_long;     // rows with more than kLongRun lookups
   int32_t n_hchunks;  // (table, up to one workgroup's worth of huge rows) chunks
+  int32_t n_wide;     // huge rows with more than kWideRun lookups
   // second level: missed rows found there, victims moved down into it, rows it evicted to the
   // lower tier, victims that found no way and went to the lower tier directly
   int32_t l2_hits, l2_demotions, l2_evictions, l2_bypasses;
@@ -133,6 +138,7 @@ struct BatchBuf {
   int32_t *items;       // [N/kLongRun + 1] rows with kLongRun < lookups <= kHugeRun (any order)
   int32_t *huge;        // [N/kHugeRun + 1] rows with more lookups (any order)
   int32_t *huge_sorted; // [N/kHugeRun + 1] positions in `huge`, grouped by table
+  int32_t *wide;        // [N/kHugeRun + 1] positions in `huge` of the rows with more than kWideRun lookups (any order)
   uint4 *hchunks;       // [N/kHugeRun + T + 1] (table, first position in huge_sorted, count, -)
   int32_t *hg_count;    // [3*(T+1)] per-table counters of the grouping
   int32_t *hstart;      // [huge rows * huge_ranges] first sorted position of a huge row in each bag range

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
 __global__ void reset_counters_kernel(BatchCounters *cnt, int within_bits) {
   if (threadIdx.x == 0) {
     cnt->n_uniq = cnt->n_touched = cnt->n_ins = cnt->n_byp = cnt->n_items = cnt->err = 0;
-    cnt->n_huge = cnt->n_mid = cnt->n_long = cnt->n_hchunks = 0;
+    cnt->n_huge = cnt->n_mid = cnt->n_long = cnt->n_hchunks = cnt->n_wide = 0;
     cnt->hits = cnt->evictions = cnt->hit_lookups = 0;
     cnt->l2_hits = cnt->l2_demotions = cnt->l2_evictions = cnt->l2_bypasses = 0;
     cnt->packed = within_bits > 0 ? 1 : 0;
