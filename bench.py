@@ -8,7 +8,7 @@ pooling Poisson(30), Zipf 1.1, 64-way cache holding 5 % of the rows, backing tie
 pinned host memory, next-batch prefetch issued ahead of training).  All inputs of the
 timed steps are generated beforehand and resident in HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line; the comments beside the fields below say what each one is.
 """
 from __future__ import annotations
 
@@ -26,7 +26,8 @@ HOST_LINK_PEAK_GBS = 64.0  # PCIe Gen5 x16, per direction
 
 
 def algorithmic_bytes(cfg, lookups_per_table, uniques, batch):
-    """Bytes the method itself must move per step."""
+    """Bytes the method itself must move per step: rows once per lookup, location words and pooled output in the
+    forward; rows read and written once per distinct row, accumulators and the output gradient once in the backward."""
     from paper_2305_01515_amd import synth
     T = len(cfg.tables)
     rows_fwd = sum(lookups_per_table[t] * cfg.tables[t].dim * (4 if cfg.tables[t].dtype == synth.FP32 else 2)
