@@ -204,8 +204,8 @@ def locality_sweep(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 200 for the benchmark workload, as its configuration says; 20 for the others)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default 10 / 5)")
     ap.add_argument("--tables", type=int, default=32, help="(debug) fewer tables than the named workload")
     ap.add_argument("--workload", default="main", choices=["main", "tiny", "capacity", "locality", "hetero", "locality_sweep"],
                     help="main = the benchmark workload; the others are the parity configurations, for reference "
@@ -229,6 +229,10 @@ def main():
                     "(so that a profile of the process holds the benchmark's launches only)")
     ap.add_argument("--no-overlap", action="store_true", help="run everything on one stream")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 200 if args.workload == "main" else 100 if args.workload == "locality_sweep" else 20
+    if args.warmup is None:
+        args.warmup = 10 if args.workload == "main" else 5
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
