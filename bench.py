@@ -101,13 +101,13 @@ def cpu_baseline(cfg, W0, batches, grads, threads):
     return n / dt, n
 
 
-def all_hit_control(TBE, cfg, Wp, Mp, batch, grads, out, max_n, hit_bytes, overlap, steps=10):
+def all_hit_control(TBE, cfg, Wp, Mp, batch, grads, out, max_n, hit_bytes, overlap, inputs_ready=True, steps=10):
     """The same shapes with no miss traffic at all: a cache as large as the tables and one batch
     replayed, so every distinct row hits.  Prefetch stage, forward and backward run pipelined as in the
     timed region; the host link is idle.  Not part of `value`."""
     import torch
     g = TBE(Wp, Mp, [tc.rows + cfg.ways for tc in cfg.tables], cfg.ways, cfg.batch, max_n + 1, overlap=overlap)
-    g.set_inputs_ready(True)
+    g.set_inputs_ready(inputs_ready)
 
     def run(n):
         for s in range(n):
@@ -461,7 +461,7 @@ def main():
     g.close()
     if args.workload == "main" and not args.second_level and not args.no_control and not args.deferred_init:
         res["all_hit_control"] = all_hit_control(TBE, cfg, Wp, Mp, batches[Wm + K], grads, out, max_n, hit_b,
-                                                 not args.no_overlap)
+                                                 not args.no_overlap, not args.wait_for_compute)
     if args.second_level:
         res["second_level"] = second_level
     print(json.dumps(res))
