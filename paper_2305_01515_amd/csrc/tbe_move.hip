@@ -255,6 +255,7 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l
   //   48                                                                       : 6.31 / 5.55 / 1.9 / 0.28
   //   64                                                                       : 6.29 / 5.56 / 2.0 / 0.30
   //   96                                                                       : 6.60 / 5.84 / 3.1 / 0.42
+  // (with the overflow copies riding along, later: 40 CUs 5.81 ms per step, 48: 5.67, 56: 5.70, 64: 5.93, 72: 6.03)
   // The link needs about 750 waves; given CUs of their own (48 of 256) they leave the other
   // streams' kernels at 1.3 to 2 times their stand-alone time instead of 2.5 to 5 times.
   hipLaunchKernelGGL(transfer_kernel, dim3(kLinkCus), dim3(kLinkThreads), 0, s, st, b ? b->cnt : nullptr,
