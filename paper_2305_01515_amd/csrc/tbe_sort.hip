@@ -113,13 +113,23 @@ __global__ __launch_bounds__(kSortThreads) void sort_upsweep_kernel(const uint32
 }
 
 // One block per digit: exclusive scan, over the sort blocks, of that digit's counts (in
-// place) and the digit's total.  nb <= kMaxSortBlocks = block size.
-__global__ __launch_bounds__(kMaxSortBlocks) void sort_scan_kernel(uint32_t *hist, int nb, uint32_t *digit_total) {
-  __shared__ uint32_t wsum[kMaxSortBlocks / 64];
+// place) and the digit's total.  nb <= kMaxSortBlocks.
+__global__ __launch_bounds__(256) void sort_scan_kernel(uint32_t *hist, int nb, uint32_t *digit_total) {
+  // 256 threads with four counts each (not one thread per count): a workgroup of 1024 threads waits for
+  // half a CU's wave slots at once, which took this small kernel 60 to 80 us instead of 5 whenever the
+  // other streams' kernels kept the CUs busy
+  constexpr int kPer = kMaxSortBlocks / 256;
+  __shared__ uint32_t wsum[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint32_t *row = hist + (size_t)blockIdx.x * nb;
-  const uint32_t v = tid < nb ? row[tid] : 0u;
-  uint32_t incl = v;
+  uint32_t v[kPer], mine = 0;
+#pragma unroll
+  for (int q = 0; q < kPer; q++) {
+    const int i = tid * kPer + q;
+    v[q] = i < nb ? row[i] : 0u;
+    mine += v[q];
+  }
+  uint32_t incl = mine;
   for (int d = 1; d < 64; d <<= 1) {
     uint32_t o = __shfl_up(incl, d);
     if (lane >= d) incl += o;
@@ -128,8 +138,14 @@ __global__ __launch_bounds__(kMaxSortBlocks) void sort_scan_kernel(uint32_t *his
   __syncthreads();
   uint32_t wb = 0;
   for (int w = 0; w < wave; w++) wb += wsum[w];
-  if (tid < nb) row[tid] = wb + incl - v;
-  if (tid == kMaxSortBlocks - 1) digit_total[blockIdx.x] = wb + incl;
+  uint32_t pre = wb + incl - mine;
+#pragma unroll
+  for (int q = 0; q < kPer; q++) {
+    const int i = tid * kPer + q;
+    if (i < nb) row[i] = pre;
+    pre += v[q];
+  }
+  if (tid == 255) digit_total[blockIdx.x] = wb + incl;
 }
 
 __global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
@@ -253,7 +269,7 @@ hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *resul
     const uint32_t mask = (1u << w) - 1u;
     hipLaunchKernelGGL(sort_upsweep_kernel, dim3(used_blocks), dim3(kSortThreads), 0, s, ss.keys[cur], (int)n, shift,
                        mask, chunk, ss.hist);
-    hipLaunchKernelGGL(sort_scan_kernel, dim3(kRadix), dim3(kMaxSortBlocks), 0, s, ss.hist, used_blocks,
+    hipLaunchKernelGGL(sort_scan_kernel, dim3(kRadix), dim3(256), 0, s, ss.hist, used_blocks,
                        ss.hist + kRadix * kMaxSortBlocks);
     hipLaunchKernelGGL(sort_downsweep_kernel, dim3(used_blocks), dim3(kSortThreads), 0, s, ss.keys[cur], ss.vals[cur],
                        ss.keys[cur ^ 1], ss.vals[cur ^ 1], (int)n, shift, mask, chunk, ss.hist,
