@@ -260,7 +260,8 @@ int tbe_set_prefetch_depth(tbe_handle h, int32_t depth);
  * caller guarantees instead that the buffers passed to tbe_prefetch are complete in device
  * memory when the call is made (e.g. a data loader finished them earlier); the prefetch
  * stage of the next batch can then start while the current batch is still training
- * (Section 5.7: the stages of different batches run simultaneously).
+ * (Section 5.7: the stages of different batches run simultaneously); it is ordered only
+ * behind the last tbe_forward launched, whose output the model is waiting for.
  */
 int tbe_set_inputs_ready(tbe_handle h, int32_t ready);
 
