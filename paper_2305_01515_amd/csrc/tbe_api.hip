@@ -3,7 +3,6 @@
 // Declarations and the contract of every call are in include/tbe.h.
 #include <algorithm>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
