@@ -118,7 +118,10 @@ typedef struct {
  *   aux_stream        : hipStream_t on which prefetch work runs; may equal compute_stream
  *                       (then nothing overlaps).  Both must have the default priority.
  * The sum over tables of the key spans (about the row counts, rounded up to whole sets)
- * must stay below 2^32 (TBE_ELIMIT).  All device memory is allocated here (TBE_ENOMEM).
+ * must stay below 2^32 (TBE_ELIMIT).  All device memory is allocated here (TBE_ENOMEM): the cache
+ * lines and, sized for the worst case of max_lookups distinct rows that all miss, about
+ * 5 * max_lookups rows of staging (three batches' copies of bypassed rows, two sets of rows
+ * parked for write-back) plus some hundred bytes per lookup of index arrays.
  */
 int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables, int32_t ways,
                int32_t max_batch, int64_t max_lookups, void *compute_stream, void *aux_stream);
