@@ -293,6 +293,30 @@ int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets
 int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float eps);
 
 /*
+ * tbe_backward_update for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same backward, same kernels, same results, but the one
+ * scratch buffer the backward's kernels use -- the partial sums of the rows with the most lookups,
+ * which tbe_backward_update keeps in memory that tbe_create allocated -- lies in a fixed array of
+ * TBE_STATIC_SCRATCH_BYTES bytes inside the library's device image instead (every GPU the library
+ * runs on holds one such array until the process ends).  The call allocates nothing: no hipMalloc,
+ * no hipFree, no event or stream creation; it only enqueues kernels and records / waits for events
+ * that tbe_create made.
+ *   - TBE_ELIMIT when the handle's worst case does not fit: 4 bytes x the widest row's elements
+ *     (rounded up to whole 16-byte lanes, a power of two of them) x max(64 * (max_lookups / 1024 + 1), 2048 * 256 / the
+ *     narrowest row's lanes) above TBE_STATIC_SCRATCH_BYTES -- e.g. dim 128 and max_lookups up to about a
+ *     million fit; the error text gives the figure;
+ *   - TBE_EORDER while stage timing is on (tbe_set_profiling creates events per call), when the
+ *     current GPU is not the one the handle was created on, or without a forwarded batch;
+ *   - the array keeps the last call's contents; nothing in it has to start at zero (every partial sum
+ *     a batch reads it has written before, in the same call);
+ *   - all handles on one GPU share that GPU's array: calls of this function that overlap on one GPU
+ *     (two handles whose compute streams run concurrently) race.  tbe_backward_update is not affected.
+ * May be mixed freely with tbe_backward_update on the same handle.
+ */
+#define TBE_STATIC_SCRATCH_BYTES (32u << 20)
+int tbe_backward_update_static(tbe_handle h, const float *d_grad_out, float lr, float eps);
+
+/*
  * Write every valid cache line and its accumulator to the backing tier (Section 5.5.4,
  * write-back) and wait for both streams: afterwards the host arrays hold the current model.
  * Tags and timestamps stay.  TBE_EORDER while a batch is prefetched or forwarded but not

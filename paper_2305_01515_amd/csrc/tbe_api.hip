@@ -7,6 +7,7 @@
 #include <new>
 #include <string>
 #include <deque>
+#include <mutex>
 #include <vector>
 
 #include "../../include/tbe.h"
@@ -14,9 +15,36 @@
 
 using namespace tbe;
 
+// Scratch memory of tbe_backward_update_static: the partial sums of the backward's longest rows, for callers
+// that must not allocate.  One copy per GPU, at an address of its own, held until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels are given the address it returns.
+constexpr size_t kStaticScratchBytes = (size_t)TBE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local std::string g_create_error;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on every GPU the library has been used on
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+hipError_t static_scratch_of_current_device(void **out, int *device) {
+  *out = nullptr;
+  hipError_t e = hipGetDevice(device);
+  if (e != hipSuccess) return e;
+  if (*device < 0 || *device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[*device]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[*device] = p;
+  }
+  *out = g_scratch_ptr[*device];
+  return hipSuccess;
+}
 
 struct DevAlloc {  // everything hipMalloc'ed, freed together
   std::vector<void *> ptrs;
@@ -57,6 +85,8 @@ struct tbe_ctx {
   unsigned long long *d_l2tot = nullptr;  // running totals of the four second-level counters
   float *d_state = nullptr;   // row-wise Adagrad accumulators of all rows of all tables
   float *partials = nullptr;  // segment sums of the backward's longest rows
+  float *static_partials = nullptr;  // the same in the library's static scratch array on this handle's GPU
+  int device = -1;                   // GPU the handle was created on
   char *lines = nullptr;
   BatchBuf buf[kBatchBufs]{};
   SortScratch ss{};
@@ -534,6 +564,11 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     CREATE_TRY(h->mem.get(&h->d_rb, 4 * (size_t)num_tables));
     CREATE_TRY(hipMemcpy(h->d_rb, rb.data(), 4 * (size_t)num_tables, hipMemcpyHostToDevice));
   }
+  {
+    void *p = nullptr;
+    CREATE_TRY(static_scratch_of_current_device(&p, &h->device));
+    h->static_partials = (float *)p;
+  }
   CREATE_TRY(h->mem.get(&h->ss.hist, 4 * (256 * 1024 + 256)));
   CREATE_TRY(h->mem.get(&h->ss.blk, 8 * 1024));
   CREATE_TRY(h->mem.get(&h->ss.wl, 4 * 4 * (size_t)kWorklistBlocks));
@@ -620,21 +655,21 @@ int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets
   return pump_queue(h);  // the next queued batch is prefetched while this one trains
 }
 
-int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float eps) {
-  if (!h) return TBE_EINVAL;
+// The backward of the forwarded batch with the partial sums of its longest rows in `partials`.
+static int backward_update_with(tbe_ctx *h, const float *d_grad_out, float lr, float eps, float *partials) {
   if (h->sticky) return h->sticky;
   if (!d_grad_out) return fail(h, TBE_EINVAL, "backward_update: null gradient");
   if (h->current < 0) return fail(h, TBE_EORDER, "backward_update: no forwarded batch");
   const int bi = h->current;
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_HUGE, h->cs);
-    HIP_TRY(h, launch_backward_classes(2, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(2, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
   }
   {
     // with the combine of the huge rows' partial sums, which both this kernel and the one before fill
     StageTimer tm_(h, TBE_STAGE_BACKWARD_LONG, h->cs);
-    HIP_TRY(h, launch_backward_classes(0, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
-    HIP_TRY(h, launch_backward_classes(3, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(0, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(3, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SINGLE, h->cs);
@@ -642,7 +677,7 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
-    HIP_TRY(h, launch_backward_classes(1, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, h->partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(1, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
   }
   h->current = -1;
   if (h->as != h->cs) {
@@ -667,6 +702,28 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
     HIP_TRY(h, launch_ovf_writeback(b, parked_prev, h->st, h->d_rb, h->d_bytes + 1, h->ls));
   }
   return pump_queue(h);
+}
+
+int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float eps) {
+  if (!h) return TBE_EINVAL;
+  return backward_update_with(h, d_grad_out, lr, eps, h->partials);
+}
+
+// bytes of partial sums a batch of this handle can need at most
+static size_t static_scratch_needed(const tbe_ctx *h) { return 4 * (size_t)h->g.partial_stride * h->huge_slots; }
+
+int tbe_backward_update_static(tbe_handle h, const float *d_grad_out, float lr, float eps) {
+  if (!h) return TBE_EINVAL;
+  if (h->profiling) return fail(h, TBE_EORDER, "backward_update_static: stage timing is on (it creates events)");
+  if (static_scratch_needed(h) > kStaticScratchBytes)
+    return fail(h, TBE_ELIMIT, "backward_update_static: a batch of max_lookups could need " +
+                                   std::to_string(static_scratch_needed(h)) + " bytes of partial sums, the static scratch holds " +
+                                   std::to_string(kStaticScratchBytes));
+  int dev = -1;
+  HIP_TRY(h, hipGetDevice(&dev));
+  if (dev != h->device || !h->static_partials)
+    return fail(h, TBE_EORDER, "backward_update_static: the handle was created on another GPU than the current one");
+  return backward_update_with(h, d_grad_out, lr, eps, h->static_partials);
 }
 
 int tbe_flush(tbe_handle h) {

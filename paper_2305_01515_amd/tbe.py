@@ -23,7 +23,7 @@ EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
            "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling",
-           "tbe_set_prefetch_depth", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax"]
+           "tbe_set_prefetch_depth", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax", "tbe_backward_update_static"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1, "max": 2}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
         l.tbe_prefetch.argtypes = [vp, vp, vp, i32, i64]
         l.tbe_forward.argtypes = [vp, vp, vp, i32, i64, vp]
         l.tbe_backward_update.argtypes = [vp, vp, C.c_float, C.c_float]
+        l.tbe_backward_update_static.argtypes = [vp, vp, C.c_float, C.c_float]
         l.tbe_flush.argtypes = [vp]
         l.tbe_destroy.argtypes = [vp]
         l.tbe_get_stats.argtypes = [vp, C.POINTER(Stats)]
@@ -203,6 +204,13 @@ class TBE:
         self._keep.append((grad_out,))
         self._keep = self._keep[-6:]
         self._check(lib().tbe_backward_update(self._h, grad_out.data_ptr(), lr, eps), "tbe_backward_update")
+
+    def backward_update_static(self, grad_out: torch.Tensor, lr: float, eps: float):
+        """backward_update with its scratch buffer in the library's static device array: allocates nothing"""
+        assert grad_out.is_cuda and grad_out.dtype == torch.float32 and grad_out.is_contiguous()
+        self._keep.append((grad_out,))
+        self._keep = self._keep[-6:]
+        self._check(lib().tbe_backward_update_static(self._h, grad_out.data_ptr(), lr, eps), "tbe_backward_update_static")
 
     def flush(self):
         self._check(lib().tbe_flush(self._h), "tbe_flush")
