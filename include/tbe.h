@@ -320,7 +320,9 @@ int tbe_backward_update_static(tbe_handle h, const float *d_grad_out, float lr, 
  * Write every valid cache line and its accumulator to the backing tier (Section 5.5.4,
  * write-back) and wait for both streams: afterwards the host arrays hold the current model.
  * Tags and timestamps stay.  TBE_EORDER while a batch is prefetched or forwarded but not
- * updated.  Also reports errors the device found earlier.
+ * updated.  Also reports errors the device found earlier: once the device has refused a batch
+ * (TBE_EINVAL / TBE_ERANGE, which stick), tbe_flush drops that batch and any behind it, writes
+ * the state of the last batch that trained to the backing tier and returns the error code.
  */
 int tbe_flush(tbe_handle h);
 
@@ -362,6 +364,10 @@ int tbe_export_cache_state(tbe_handle h, int32_t table, int64_t *h_tags, int32_t
 /* Copy a table's per-entry lookup counts (see tbe_set_policy; 0 = free) to a HOST array of
  * S_t * ways entries, same order as the tags.  Synchronises. */
 int tbe_export_cache_freq(tbe_handle h, int32_t table, int32_t *h_freq);
+/* The reverse: overwrite a table's per-entry lookup counts from a HOST array in the same order (values >= 0;
+ * restoring a saved cache state, and how the tests reach counts near INT32_MAX).  Synchronises.
+ * TBE_EORDER while a batch is prefetched or forwarded but not updated. */
+int tbe_import_cache_freq(tbe_handle h, int32_t table, const int32_t *h_freq);
 
 /*
  * Events of the last prefetched batch.  kind 0 = hits, 1 = inserts, 2 = bypasses.

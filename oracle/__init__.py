@@ -60,6 +60,7 @@ def lib():
         _lib.orc_batch_id.argtypes = [C.c_void_p]
         _lib.orc_export_cache_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         _lib.orc_export_cache_freq.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        _lib.orc_import_cache_freq.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.orc_set_policy.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_set_pooling.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_set_second_level.argtypes = [C.c_void_p, C.c_void_p]
@@ -221,6 +222,14 @@ class Oracle:
         f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)
         lib().orc_export_cache_freq(self.h, t, f.ctypes.data)
         return f
+
+    def set_cache_freq(self, t: int, freq: np.ndarray):
+        """test hook: overwrite the per-entry lookup counts of table t"""
+        f = np.ascontiguousarray(freq, dtype=np.int32)
+        assert f.size == self.num_sets(t) * self.ways
+        rc = lib().orc_import_cache_freq(self.h, t, f.ctypes.data)
+        if rc:
+            raise OracleError(rc, "import_cache_freq")
 
     def stats(self):
         last, total = Stats(), Stats()

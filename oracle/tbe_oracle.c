@@ -5,7 +5,7 @@
  *
  * What it computes (paper sections in brackets):
  *   - pooled lookup: for every (table, sample) bag, the sum of the looked-up rows
- *     [Section 2.1.1, "embedding table operators ... pool the result using sum"];
+ *     [Section 2.1.1];
  *   - sparse backward with row-wise Adagrad: every distinct row of a batch receives the
  *     sum of the output gradients of the bags that looked it up (once per lookup), one
  *     accumulator per row [Section 2.1.2: optimizers with few states per row, Adagrad;
@@ -782,6 +782,15 @@ int orc_export_cache_state(void *hp, int32_t t, int64_t *tags, int32_t *ts) {
   orc_table *tb = &h->tab[t];
   int64_t n = tb->sets * h->ways;
   if (n) { memcpy(tags, tb->tag, sizeof(int64_t) * (size_t)n); memcpy(ts, tb->ts, sizeof(int32_t) * (size_t)n); }
+  return ORC_OK;
+}
+
+/* Test hook: overwrite the per-entry lookup counts of a table (same layout as the export).  Lets a
+ * test start from counts near INT32_MAX without replaying two billion lookups. */
+int orc_import_cache_freq(void *hp, int32_t t, const int32_t *freq) {
+  orc *h = (orc *)hp;
+  if (!h || t < 0 || t >= h->T || !freq) return ORC_EINVAL;
+  memcpy(h->tab[t].freq, freq, sizeof(int32_t) * (size_t)(h->tab[t].sets * h->ways));
   return ORC_OK;
 }
 

@@ -728,9 +728,19 @@ int tbe_backward_update_static(tbe_handle h, const float *d_grad_out, float lr, 
 
 int tbe_flush(tbe_handle h) {
   if (!h) return TBE_EINVAL;
-  if (h->n_pend > 0 || h->current >= 0 || !h->queued.empty()) return fail(h, TBE_EORDER, "flush: a batch is still in flight");
   int rc = sync_all(h);
   if (rc) return rc;
+  if (h->n_pend > 0 || h->current >= 0 || !h->queued.empty()) {
+    // Allowed only after the device has refused a batch (bad offsets, index out of range): that batch and
+    // any behind it do nothing and never will (the error sticks), so they are dropped here and the flush
+    // brings the backing tier up to the last batch that trained.
+    (void)collect_device_errors(h);
+    if (!h->sticky) return fail(h, TBE_EORDER, "flush: a batch is still in flight");
+    h->n_pend = 0;
+    h->current = -1;
+    h->deferred = -1;
+    h->queued.clear();
+  }
   HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, h->di, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
   if (h->prev_buf >= 0) {
     // Every copy in the backing tier is current now, so the next batch must find no row marked
@@ -999,6 +1009,19 @@ int tbe_export_cache_freq(tbe_handle h, int32_t table, int32_t *h_freq) {
   const size_t n = (size_t)m.sets * h->g.ways;
   if (n == 0) return TBE_OK;
   HIP_TRY(h, hipMemcpy(h_freq, h->freq + m.slot_base, 4 * n, hipMemcpyDeviceToHost));
+  return TBE_OK;
+}
+
+int tbe_import_cache_freq(tbe_handle h, int32_t table, const int32_t *h_freq) {
+  if (!h || table < 0 || table >= h->g.T || !h_freq) return TBE_EINVAL;
+  if (h->n_pend > 0 || h->current >= 0 || !h->queued.empty()) return fail(h, TBE_EORDER, "import_cache_freq: a batch is still in flight");
+  int rc = sync_all(h);
+  if (rc) return rc;
+  const TableMeta &m = h->tm[table];
+  const size_t n = (size_t)m.sets * h->g.ways;
+  for (size_t i = 0; i < n; i++)
+    if (h_freq[i] < 0) return fail(h, TBE_EINVAL, "import_cache_freq: negative count");
+  if (n) HIP_TRY(h, hipMemcpy(h->freq + m.slot_base, h_freq, 4 * n, hipMemcpyHostToDevice));
   return TBE_OK;
 }
 

@@ -383,12 +383,27 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
                                                      const char *__restrict__ out2_prev,
                                                      const uint32_t *__restrict__ rb_of_table, u64 *bytes_d2h) {
   const uint32_t M = (uint32_t)st.max_inserts;  // map codes kWhereParked | (M + i): rows staged in out2
-  if (cnt->err) return;
-  const int n_ins = cnt->n_ins, n_byp = cnt->n_byp;
   const int n_prev = (prev_cnt && prev_cnt->err == 0) ? prev_cnt->n_byp : 0;
   const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
   const int lig = threadIdx.x % kMoveLanes;
   const int n_groups = gridDim.x * blockDim.x / kMoveLanes;
+  if (cnt->err) {
+    // This batch is refused (bad offsets or an index out of range) and does nothing, and no batch follows it
+    // (the error sticks).  The batch before it has trained on its overflow copies, though: they go home now,
+    // whatever was planned for them, so that a flush leaves the backing tier with that batch's updates.
+    if (wb_prev != kPrevKeep) {
+      u64 b = 0;
+      for (int j = group; j < n_prev; j += n_groups) {
+        const uint32_t rb = rb_of_table[prev_byp_tab[j]];
+        copy_row_to_host(prev_byp_src[j], prev_ovf + (size_t)j * st.stride, rb, lig);
+        if (lig == 0) b += rb;
+      }
+      for (int d = 32; d >= 1; d >>= 1) b += __shfl_xor(b, d);
+      if ((threadIdx.x & 63) == 0 && b) atomicAdd(bytes_d2h, b);
+    }
+    return;
+  }
+  const int n_ins = cnt->n_ins, n_byp = cnt->n_byp;
   const int par = k & 1, ppar = par ^ 1;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     st.wb_n[0] = n_ins + (wb_prev == kPrevPark ? n_prev : 0);

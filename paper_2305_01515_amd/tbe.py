@@ -6,6 +6,7 @@ loaded the import of this module's `lib()` fails.
 """
 from __future__ import annotations
 
+import collections
 import ctypes as C
 import os
 from typing import Dict, List, Optional, Sequence, Tuple
@@ -23,7 +24,7 @@ EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
            "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling",
-           "tbe_set_prefetch_depth", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax", "tbe_backward_update_static"]
+           "tbe_set_prefetch_depth", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax", "tbe_backward_update_static", "tbe_import_cache_freq"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1, "max": 2}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_long": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_huge": 7}
@@ -96,6 +97,7 @@ def lib() -> C.CDLL:
         l.tbe_export_second_level_state.argtypes = [vp, i32, vp, vp]
         l.tbe_get_second_level_stats.argtypes = [vp, vp, vp]
         l.tbe_export_cache_freq.argtypes = [vp, i32, vp]
+        l.tbe_import_cache_freq.argtypes = [vp, i32, vp]
         l.tbe_get_stage_times.argtypes = [vp, i32, i64, vp]
         l.tbe_get_stage_times.restype = i64
         _lib = l
@@ -136,7 +138,13 @@ class TBE:
                               C.c_void_p(self.compute_stream.cuda_stream), C.c_void_p(self.aux_stream.cuda_stream))
         if rc:
             raise TbeError(rc, "tbe_create", lib().tbe_last_error(None).decode())
-        self._keep: List[Tuple[torch.Tensor, ...]] = []
+        # Tensors the library still reads are kept alive per batch: a record is opened by prefetch() (or by a
+        # forward() that prefetches itself), gets the output at forward() and the gradient at backward_update(),
+        # and is dropped three trained batches later -- the library's batch buffers rotate over three, and every
+        # kernel that reads a batch's tensors is ordered before the prefetch stage of the third batch after it.
+        self._ahead: collections.deque = collections.deque()    # prefetched, not forwarded yet
+        self._current: Optional[list] = None                    # forwarded, not updated yet
+        self._trained: collections.deque = collections.deque(maxlen=3)
         self._depth = 1
         self._forwarded = (0, None)
         if policy != "lru":
@@ -170,21 +178,21 @@ class TBE:
 
     def prefetch(self, indices: torch.Tensor, offsets: torch.Tensor):
         assert indices.is_cuda and offsets.is_cuda and indices.dtype == torch.int64 and offsets.dtype == torch.int64
-        self._keep.append((indices, offsets))
-        self._keep = self._keep[-(4 + 2 * self._depth):]
         self._check(lib().tbe_prefetch(self._h, indices.data_ptr(), offsets.data_ptr(),
                                        self._batch_of(offsets, self.T), indices.numel()), "tbe_prefetch")
+        self._ahead.append([indices, offsets])
 
     def forward(self, indices: torch.Tensor, offsets: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         B = self._batch_of(offsets, self.T)
         if out is None:
             out = torch.empty(B, self.sum_dim, dtype=torch.float32, device=indices.device)
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == B * self.sum_dim
-        self._keep.append((indices, offsets, out))
-        self._keep = self._keep[-(4 + 2 * self._depth):]
-        self._forwarded = (B, indices.device)
         self._check(lib().tbe_forward(self._h, indices.data_ptr(), offsets.data_ptr(), B, indices.numel(),
                                       out.data_ptr()), "tbe_forward")
+        self._forwarded = (B, indices.device)
+        rec = self._ahead.popleft() if self._ahead else [indices, offsets]  # none pending: it prefetched itself
+        rec.append(out)
+        self._current = rec
         return out
 
     def argmax(self, out: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -201,16 +209,19 @@ class TBE:
 
     def backward_update(self, grad_out: torch.Tensor, lr: float, eps: float):
         assert grad_out.is_cuda and grad_out.dtype == torch.float32 and grad_out.is_contiguous()
-        self._keep.append((grad_out,))
-        self._keep = self._keep[-6:]
         self._check(lib().tbe_backward_update(self._h, grad_out.data_ptr(), lr, eps), "tbe_backward_update")
+        self._retire(grad_out)
 
     def backward_update_static(self, grad_out: torch.Tensor, lr: float, eps: float):
         """backward_update with its scratch buffer in the library's static device array: allocates nothing"""
         assert grad_out.is_cuda and grad_out.dtype == torch.float32 and grad_out.is_contiguous()
-        self._keep.append((grad_out,))
-        self._keep = self._keep[-6:]
         self._check(lib().tbe_backward_update_static(self._h, grad_out.data_ptr(), lr, eps), "tbe_backward_update_static")
+        self._retire(grad_out)
+
+    def _retire(self, grad_out: torch.Tensor):
+        rec, self._current = (self._current or []), None
+        rec.append(grad_out)
+        self._trained.append(rec)
 
     def flush(self):
         self._check(lib().tbe_flush(self._h), "tbe_flush")
@@ -278,6 +289,11 @@ class TBE:
         f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)
         self._check(lib().tbe_export_cache_freq(self._h, t, f.ctypes.data), "tbe_export_cache_freq")
         return f
+
+    def set_cache_freq(self, t: int, freq: np.ndarray):
+        f = np.ascontiguousarray(freq, dtype=np.int32)
+        assert f.size == self.num_sets(t) * self.ways
+        self._check(lib().tbe_import_cache_freq(self._h, t, f.ctypes.data), "tbe_import_cache_freq")
 
     def events(self, kind: str):
         """kind 'hit' / 'bypass': (table, row); 'insert': (table, row, slot, old)."""

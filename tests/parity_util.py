@@ -5,12 +5,17 @@ Bars (written here once, used by every parity test):
   - cache state (tags, timestamps, per-entry lookup counts), per-batch counters and the hit / insert / bypass
     event sets: bit-exact;
   - floating point, per vector v against the oracle's r (a pooled bag slice, an updated
-    row):  max_d |v - r| <= tol * max(max_d |r|, peak, floor), tol = 1e-5 for fp32 storage and
+    row):  max_d |v - r| <= tol * max(max_d |r|, floor), tol = 1e-5 for fp32 storage and
     2e-3 for fp16 storage (fp32 accumulation); the accumulator m always with 1e-5 (floor M_FLOOR).
-    `peak` is the largest magnitude the row (for a pooled slice: any row of the bag) has held since the
-    run began, kept by the oracle: a rounding that fell differently on the two sides while a row was
-    large stays in it as an absolute difference when the row shrinks (one fp16 ulp taken at 0.5 is four
-    ulps at 0.15), so the bar is relative to the largest value the rounding can stem from;
+    This plain bar is applied to every vector first.  Only for fp16 storage under max pooling a vector
+    that misses it is then held against the wider scale max(max_d |r|, peak, floor), `peak` being the
+    largest magnitude the row (for a pooled slice: any row of the bag) has held since the run began, kept
+    by the oracle: a rounding to binary16 that fell differently on the two sides while a row was large
+    stays in it as an absolute difference when the row shrinks (one fp16 ulp taken at 0.5 is four ulps at
+    0.15), and max pooling's sparse gradients make rows grow to 1 and shrink again within a few steps.
+    Every vector that needed the wider scale is counted (`Tally`); run_parity returns the count and the
+    worst ratio to the plain bar, and asserts that the count is 0 for fp32 storage and for sum and mean
+    pooling;
   - max pooling, who supplied each maximum: equal, except where two different rows' values lie within
     the floating-point bar of each other in the oracle (stored values agree only to that bar once rows
     have been updated, so either row may hold the larger one).  Such a choice is checked to be a valid
@@ -35,6 +40,19 @@ TOL = {synth.FP32: 1e-5, synth.FP16: 2e-3}
 M_FLOOR = 1e-3
 
 
+class Tally:
+    """vectors (rows, pooled slices) that missed the plain bar and were accepted on the peak scale"""
+
+    def __init__(self):
+        self.vectors = 0          # how many
+        self.checked = 0          # out of how many compared
+        self.worst_plain = 0.0    # largest error / plain bar seen on any vector (<= 1: within the stated tolerance)
+
+    def as_dict(self):
+        return {"vectors_on_peak_scale": self.vectors, "vectors_compared": self.checked,
+                "worst_error_over_plain_bar": self.worst_plain}
+
+
 def vec_err(got: np.ndarray, ref: np.ndarray, floor, peak=None) -> float:
     """largest norm-wise relative error over the rows of two [n, d] arrays; floor: a number or one per row;
     peak: per row, a magnitude the scale must not fall below (None: none)"""
@@ -44,6 +62,31 @@ def vec_err(got: np.ndarray, ref: np.ndarray, floor, peak=None) -> float:
     if peak is not None:
         scale = np.maximum(scale, peak)
     return float((np.abs(got - ref).max(axis=-1) / scale).max()) if got.size else 0.0
+
+
+def check_vectors(got: np.ndarray, ref: np.ndarray, tol: float, floor, peak, tally: Tally, what: str):
+    """Every row of got against ref on the plain bar  max_d|got - ref| <= tol * max(max_d|ref|, floor).
+    peak (per row, or None): rows that miss the plain bar may pass on the scale max(.., peak) instead and
+    are counted in `tally`; with peak None a miss is a failure."""
+    if not got.size:
+        return
+    got = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    err = np.abs(got - ref).max(axis=-1)
+    scale = np.maximum(np.abs(ref).max(axis=-1), floor)
+    ratio = err / (tol * scale)
+    if tally is not None:
+        tally.checked += int(ratio.size)
+        tally.worst_plain = max(tally.worst_plain, float(ratio.max()))
+    bad = ratio > 1.0
+    if not bad.any():
+        return
+    assert peak is not None, f"{what} off by {float((err / scale).max()):.3e} (bar {tol:g})"
+    wide = np.maximum(scale[bad], np.asarray(peak, dtype=np.float64)[bad] if np.ndim(peak) else peak)
+    e = float((err[bad] / wide).max())
+    assert e <= tol, f"{what} off by {e:.3e} even on the peak scale (bar {tol:g}); {float((err / scale).max()):.3e} on the plain one"
+    if tally is not None:
+        tally.vectors += int(bad.sum())
 
 
 def make_backing(cfg, device="cpu"):
@@ -109,13 +152,13 @@ def bag_peaks(cfg, o: Oracle, idx: np.ndarray, off: np.ndarray):
     return res
 
 
-def compare_forward(cfg, out_o: np.ndarray, out_g: np.ndarray, ctx: str, peaks=None):
-    """peaks (max pooling, where one row's element is the pooled element): bag_peaks()"""
+def compare_forward(cfg, out_o: np.ndarray, out_g: np.ndarray, ctx: str, peaks=None, tally: Tally = None):
+    """peaks (fp16 storage under max pooling, where one row's element is the pooled element): bag_peaks()"""
     col = 0
     for t, tc in enumerate(cfg.tables):
-        e = vec_err(out_g[:, col:col + tc.dim], out_o[:, col:col + tc.dim], floor=1e-3 * cfg.init_std,
-                    peak=None if peaks is None else peaks[t])
-        assert e <= TOL[tc.dtype], f"{ctx}: pooled output of table {t} off by {e:.3e}"
+        check_vectors(out_g[:, col:col + tc.dim], out_o[:, col:col + tc.dim], TOL[tc.dtype], 1e-3 * cfg.init_std,
+                      peaks[t] if peaks is not None and tc.dtype == synth.FP16 else None, tally,
+                      f"{ctx}: pooled output of table {t}")
         col += tc.dim
 
 
@@ -165,9 +208,10 @@ def first_bags(idx: torch.Tensor, off: torch.Tensor, T: int, n: int):
     return torch.cat(parts).contiguous(), new_off.contiguous()
 
 
-def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None, peak=None):
+def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None, peak=None, tally: Tally = None):
     """only[t]: boolean mask of the rows to compare (deferred initialisation: the rows that have a value;
-    the others must still hold the NaN they were filled with, on both sides)"""
+    the others must still hold the NaN they were filled with, on both sides).  peak[t] (or None): per row,
+    the wider scale that fp16 rows may fall back on (see the header); never used for fp32 storage."""
     step = 1 << 21  # rows per comparison chunk (keeps the fp64 temporaries small)
     for t, tc in enumerate(cfg.tables):
         wg, mg = Wp[t].numpy(), Mp[t].numpy()
@@ -175,15 +219,17 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None, peak=None):
             keep = only[t].astype(bool)
             assert np.isnan(wg[~keep].astype(np.float32)).all() and np.isnan(Wn[t][~keep].astype(np.float32)).all(), \
                 f"{ctx}: a row of table {t} that was never read has been written"
-            e = vec_err(wg[keep], Wn[t][keep], floor=1e-3 * cfg.init_std, peak=None if peak is None else peak[t][keep])
-            assert e <= TOL[tc.dtype], f"{ctx}: initialised rows of table {t} off by {e:.3e}"
+            check_vectors(wg[keep], Wn[t][keep], TOL[tc.dtype], 1e-3 * cfg.init_std,
+                          peak[t][keep] if peak is not None and tc.dtype == synth.FP16 else None, tally,
+                          f"{ctx}: initialised rows of table {t}")
             em = vec_err(mg[:, None], Mn[t][:, None], floor=M_FLOOR)
             assert em <= 1e-5, f"{ctx}: accumulators of table {t} off by {em:.3e}"
             continue
         for r0 in range(0, tc.rows, step):
             r1 = min(tc.rows, r0 + step)
-            e = vec_err(wg[r0:r1], Wn[t][r0:r1], floor=1e-3 * cfg.init_std, peak=None if peak is None else peak[t][r0:r1])
-            assert e <= TOL[tc.dtype], f"{ctx}: rows {r0}..{r1} of table {t} off by {e:.3e}"
+            check_vectors(wg[r0:r1], Wn[t][r0:r1], TOL[tc.dtype], 1e-3 * cfg.init_std,
+                          peak[t][r0:r1] if peak is not None and tc.dtype == synth.FP16 else None, tally,
+                          f"{ctx}: rows {r0}..{r1} of table {t}")
             em = vec_err(mg[r0:r1, None], Mn[t][r0:r1, None], floor=M_FLOOR)
             assert em <= 1e-5, f"{ctx}: accumulators {r0}..{r1} of table {t} off by {em:.3e}"
 
@@ -240,6 +286,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             snaps[s] = gpu_snapshot(g, T)
 
     parted = {"at": None, "elements": 0}
+    tally = Tally()
+    peak_allowed = pooling == "max"  # the wider scale is for fp16 rows under max pooling only (see the header)
 
     from paper_2305_01515_amd.tbe import TbeError, lib
     poke_rng = np.random.default_rng(misuse)
@@ -310,7 +358,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
                 if n:
                     parted["at"], parted["elements"] = s + 1, n
             compare_forward(cfg, out_o, out_g, f"step {s + 1}",
-                            peaks=bag_peaks(cfg, o, idx.numpy(), off.numpy()) if pooling == "max" else None)
+                            peaks=bag_peaks(cfg, o, idx.numpy(), off.numpy()) if peak_allowed else None, tally=tally)
         o.backward_update(synth.grad_out(cfg, s + 1)[:sizes[s]].numpy(), cfg.lr, cfg.eps)
 
     pushed = 0
@@ -358,7 +406,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             if parted["at"] is None:
                 only = [o.initialised(t) for t in range(T)] if deferred_init is not None else None
                 compare_backing(cfg, Wn, Mn, Wp, Mp, f"flush after step {s + 1}", only=only,
-                                peak=[o.row_peak(t) for t in range(T)])
+                                peak=[o.row_peak(t) for t in range(T)] if peak_allowed else None, tally=tally)
     assert not snaps
     # final cache state must agree whatever the call order was
     for t in range(T):
@@ -379,8 +427,12 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         for t in range(T):
             assert np.array_equal(only[t], g.initialised(t)), f"rows of table {t} that have a value differ"
     if parted["at"] is None:
-        compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush", only=only, peak=[o.row_peak(t) for t in range(T)])
+        compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush", only=only,
+                        peak=[o.row_peak(t) for t in range(T)] if peak_allowed else None, tally=tally)
+    if not peak_allowed or all(tc.dtype == synth.FP32 for tc in cfg.tables):
+        assert tally.vectors == 0
     st = g.stats()
+    st["tolerance"] = tally.as_dict()
     st["parted_at"], st["parted_elements"] = parted["at"], parted["elements"]
     st["refused_calls"] = poked["n"]
     st["second_level_total"] = g.second_level_stats()[1]

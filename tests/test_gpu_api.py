@@ -312,3 +312,77 @@ def test_two_handles_interleaved_equal_each_alone():
         assert all(torch.equal(a, b) for a, b in zip(r["Wp"] + r["Mp"], ref[1] + ref[2]))
         for (ta, sa), (tb, sb) in zip(state, ref[3]):
             assert np.array_equal(ta, tb) and np.array_equal(sa, sb)
+
+
+def test_binding_keeps_queued_batches_alive_at_depth_four():
+    """With four batches accepted ahead of training the library reads a queued batch's index tensors several
+    steps after tbe_prefetch returned.  The caller here keeps a batch's tensors only until its forward() call
+    and churns the allocator in between (fresh tensors of the same sizes, filled with out-of-range values):
+    the binding must hold on to everything the library still reads.  Result: equal, bit for bit, to a run
+    whose caller keeps every tensor."""
+    cfg = little()
+    stream = synth.BatchStream(cfg)
+    batches = [stream.next() for _ in range(12)]
+    runs = []
+    for careless in (False, True):
+        g, Wp, Mp = make(cfg)
+        g.set_prefetch_depth(4)
+        held, pushed, outs, junk = [], 0, [], []
+        for s in range(len(batches)):
+            while pushed < min(len(batches), s + 5):
+                b = tuple(x.cuda().clone() for x in batches[pushed])
+                g.prefetch(*b)
+                held.append(b)
+                pushed += 1
+            idx, off = held[0] if careless else held[s]
+            out = g.forward(idx, off)
+            if careless:
+                held.pop(0)
+                del idx, off
+                junk = [torch.full_like(batches[s][0].cuda(), 1 << 40) for _ in range(4)]
+            g.backward_update(synth.grad_out(cfg, s + 1).cuda(), cfg.lr, cfg.eps)
+            outs.append(out.clone())
+        g.flush()
+        g.close()
+        runs.append((outs, Wp, Mp))
+    a, b = runs
+    assert all(torch.equal(x, y) for x, y in zip(a[0], b[0]))
+    assert all(torch.equal(x, y) for x, y in zip(a[1] + a[2], b[1] + b[2]))
+
+
+def test_bad_batch_prefetched_ahead_does_not_lose_the_last_good_batch():
+    """A good batch that bypasses rows trains while a batch with an out-of-range index is already prefetched
+    behind it.  The bad batch is refused on the device; the good batch's bypassed rows, which were trained on in
+    HBM copies, must still reach the backing tier: after the flush (which reports the error) the tables equal
+    the oracle's after the good batches."""
+    from oracle import Oracle
+    from paper_2305_01515_amd.tbe import TbeError
+    from parity_util import compare_backing
+    cfg = little()
+    g, Wp, Mp = make(cfg)
+    Wn = [w.numpy().copy() for w in Wp]
+    Mn = [m.numpy().copy() for m in Mp]
+    o = Oracle(Wn, Mn, [t.cache_slots for t in cfg.tables], cfg.ways)
+    stream = synth.BatchStream(cfg)
+    good = [stream.next() for _ in range(3)]
+    bad_idx, bad_off = stream.next()
+    bad_idx = bad_idx.clone()
+    bad_idx[0] = cfg.tables[0].rows  # one past the end of table 0
+    dev = [tuple(x.cuda() for x in b) for b in good] + [(bad_idx.cuda(), bad_off.cuda())]
+    g.prefetch(*dev[0])
+    for s in range(3):
+        g.prefetch(*dev[s + 1])  # the last one is the bad batch
+        g.forward(*dev[s])
+        go = synth.grad_out(cfg, s + 1)
+        g.backward_update(go.cuda(), cfg.lr, cfg.eps)
+        o.prefetch(good[s][0].numpy(), good[s][1].numpy())
+        o.forward()
+        o.backward_update(go.numpy(), cfg.lr, cfg.eps)
+    assert o.stats()[0]["bypasses"] > 0, "the last good batch bypasses no row: the case is not exercised"
+    with pytest.raises(TbeError) as e:
+        g.flush()
+    assert e.value.code == -2
+    o.flush()
+    compare_backing(cfg, Wn, Mn, Wp, Mp, "after the refused batch")
+    g.close()
+    o.close()

@@ -203,3 +203,39 @@ def test_policy_is_fixed_before_the_first_batch():
     assert lib().orc_set_policy(o.h, 7) != 0
     with pytest.raises(KeyError):
         Oracle(W, M, [4], ways=2, policy="fifo")
+
+
+def test_lfu_count_saturates_at_int32_max():
+    """The per-entry lookup count stops at INT32_MAX: it neither wraps to a negative number nor grows on in a
+    wider type.  Hand-worked on one set of two ways (counts are put near the limit through the oracle's test
+    hook; reaching them by lookups would take two billion of them):
+      batch 1: row 0 three times, row 1 twice           -> ways (0, 1) hold rows (0, 1), counts (3, 2)
+      counts set to (INT32_MAX - 2, INT32_MAX - 1)
+      batch 2: row 0 five times, row 1 once             -> both hit; exact sums would be INT32_MAX + 3 and INT32_MAX:
+                                                           both counts must read INT32_MAX
+      batch 3: row 2 once (a miss)                      -> candidates tie on count and on timestamp (2, 2), so the
+                                                           lowest way goes: row 0 leaves way 0.  A wider counter would
+                                                           keep row 0 (larger count) and evict row 1 from way 1; a
+                                                           wrapped one would read negative in the export."""
+    big = np.iinfo(np.int32).max
+    W, M = make_tables([10], [4], [np.float32])
+    o = Oracle(W, M, [2], ways=2, policy="lfu")
+
+    def batch(rows):
+        idx = np.array(rows, dtype=np.int64)
+        o.prefetch(idx, np.array([0, len(rows)], dtype=np.int64))
+        o.forward()
+        o.backward_update(np.zeros((1, 4), dtype=np.float32), 0.01, 1e-8)
+
+    batch([0, 0, 0, 1, 1])
+    assert o.cache_state(0)[0].tolist() == [0, 1] and o.cache_freq(0).tolist() == [3, 2]
+    o.set_cache_freq(0, np.array([big - 2, big - 1], dtype=np.int32))
+    batch([0, 0, 0, 0, 0, 1])
+    assert o.cache_freq(0).tolist() == [big, big]
+    batch([2])
+    tags, ts = o.cache_state(0)
+    assert tags.tolist() == [2, 1] and ts.tolist() == [3, 2]
+    assert o.cache_freq(0).tolist() == [1, big]
+    _, rows, slots, old = o.events("insert")
+    assert (rows.tolist(), slots.tolist(), old.tolist()) == ([2], [0], [0])
+    o.close()
