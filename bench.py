@@ -350,7 +350,7 @@ def main():
     dt = time.perf_counter() - t0
     s1 = g.stats()
     l2_1 = g.second_level_stats() if args.second_level else None
-    BWD = ("backward_single", "backward_short", "backward_long", "backward_huge")
+    BWD = ("backward_single", "backward_short", "backward_heavy", "backward_combine")
     STAGES = ("prefetch", "fill", "commit", "forward") + BWD
     first = {k: (Wm if k in ("forward",) + BWD else Wm + 1) for k in STAGES}
     times = {k: g.stage_times(k)[first[k]:first[k] + K] for k in STAGES}  # the brackets of the timed steps

@@ -345,11 +345,12 @@ int tbe_get_stats(tbe_handle h, tbe_stats *out);
 #define TBE_STAGE_PREFETCH 0       /* key generation, sort, dedup, probe, compaction (aux stream) */
 #define TBE_STAGE_FILL 1           /* host link: write-back of parked victims + fetch-ahead of missed rows (aux) */
 #define TBE_STAGE_FORWARD 2        /* pooled lookup (compute stream)                              */
-#define TBE_STAGE_BACKWARD_LONG 3  /* backward of rows with 65..1024 lookups + combine of the rows with more (compute stream) */
+#define TBE_STAGE_BACKWARD_COMBINE 3 /* heavy rows: sum of the partial sums + update (compute stream) */
 #define TBE_STAGE_BACKWARD_SHORT 4 /* backward of rows with 2..64 lookups (compute stream)          */
 #define TBE_STAGE_COMMIT 5         /* victims -> staging, fetched rows -> cache lines (aux stream)  */
 #define TBE_STAGE_BACKWARD_SINGLE 6 /* backward of rows with one lookup, bag by bag (compute stream) */
-#define TBE_STAGE_BACKWARD_HUGE 7  /* partial sums of the rows with more than 1024 lookups (compute stream) */
+#define TBE_STAGE_BACKWARD_HEAVY 7 /* rows with more than 64 lookups: partial sums per bag range from gradient tiles in LDS
+                                      (max pooling: one workgroup per row, update included) (compute stream) */
 #define TBE_NUM_STAGES 8
 int tbe_set_profiling(tbe_handle h, int32_t enable);
 int64_t tbe_get_stage_times(tbe_handle h, int32_t stage, int64_t capacity, float *h_ms);

@@ -84,6 +84,7 @@ struct tbe_ctx {
   char *lines2 = nullptr;       // its lines: one pinned host allocation
   unsigned long long *d_l2tot = nullptr;  // running totals of the four second-level counters
   float *d_state = nullptr;   // row-wise Adagrad accumulators of all rows of all tables
+  float *d_slot_m = nullptr;  // ... and of the rows in the cache lines, by slot
   float *partials = nullptr;  // segment sums of the backward's longest rows
   float *static_partials = nullptr;  // the same in the library's static scratch array on this handle's GPU
   int device = -1;                   // GPU the handle was created on
@@ -221,13 +222,12 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.byp_where, 4 * N));
   HIP_TRY(h, h->mem.get(&b.ovf, N * (size_t)h->g.ovf_stride));
   HIP_TRY(h, h->mem.get(&b.mid_idx, 4 * (N / 2 + 1)));
-  HIP_TRY(h, h->mem.get(&b.items, 4 * (N / kLongRun + 1)));
-  HIP_TRY(h, h->mem.get(&b.huge, 4 * (N / kHugeRun + 1)));
-  HIP_TRY(h, h->mem.get(&b.huge_sorted, 4 * (N / kHugeRun + 1)));
-  HIP_TRY(h, h->mem.get(&b.wide, 4 * (N / kHugeRun + 1)));
-  HIP_TRY(h, h->mem.get(&b.hchunks, 16 * (N / kHugeRun + (size_t)h->g.T + 1)));
-  HIP_TRY(h, h->mem.get(&b.hg_count, 4 * 3 * ((size_t)h->g.T + 1)));
-  HIP_TRY(h, h->mem.get(&b.hstart, 4 * h->huge_slots));
+  HIP_TRY(h, h->mem.get(&b.heavy, 4 * (N / 32 + 1)));  // rows: N / 65 at most; extra parts: N / kHeavySplit at most
+  HIP_TRY(h, h->mem.get(&b.heavy_sub, 4 * (N / 32 + 1)));
+  HIP_TRY(h, h->mem.get(&b.hchunks, 16 * (N / 32 + (size_t)h->g.T + 1)));
+  HIP_TRY(h, h->mem.get(&b.hg_count, 4 * ((size_t)h->g.T + 1)));
+  HIP_TRY(h, hipMemset(b.hg_count, 0, 4 * ((size_t)h->g.T + 1)));
+  HIP_TRY(h, h->mem.get(&b.hstart, 4 * (h->huge_slots + 1)));
   HIP_TRY(h, h->mem.get(&b.cnt, sizeof(BatchCounters)));
   HIP_TRY(h, hipMemset(b.cnt, 0, sizeof(BatchCounters)));
   return TBE_OK;
@@ -493,7 +493,12 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     CREATE_TRY(hipStreamCreateWithFlags(&h->ls, hipStreamNonBlocking));
     h->own_ls = true;
   }
-  for (int t = 0; t < num_tables; t++) h->tm[t].lines = h->lines + line_off[t];
+  CREATE_TRY(h->mem.get(&h->d_slot_m, 4 * slots));
+  if (slots) CREATE_TRY(hipMemset(h->d_slot_m, 0, 4 * slots));
+  for (int t = 0; t < num_tables; t++) {
+    h->tm[t].lines = h->lines + line_off[t];
+    h->tm[t].slot_m = h->d_slot_m + h->tm[t].slot_base;
+  }
   CREATE_TRY(h->mem.get(&h->d_tm, sizeof(TableMeta) * num_tables));
   CREATE_TRY(hipMemcpy(h->d_tm, h->tm.data(), sizeof(TableMeta) * num_tables, hipMemcpyHostToDevice));
   {  // class tables
@@ -511,13 +516,11 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
       h->ci.cls_tables[c] = d_ids;
     }
   }
-  {  // (huge row, bag range) pairs of a batch: 64 ranges for at most N / kHugeRun rows, or more ranges for few
-     // rows -- then ranges x chunks <= kHugeTargetItems and a chunk has at most 256 / lanes rows
-    int min_lanes = 64;
-    for (const TableMeta &m : h->tm) min_lanes = std::min(min_lanes, (int)m.lanes);
-    h->huge_slots = std::max<size_t>((size_t)kHugeRanges * ((size_t)max_lookups / kHugeRun + 1),
-                                     (size_t)kHugeTargetItems * (256 / min_lanes));
-  }
+  // (heavy-list entry, bag range) pairs of a batch, one partial sum each: a batch has at most N / 32 entries
+  // (N / 65 heavy rows, N / kHeavySplit more for the parts of the hot ones); the number of ranges is chosen
+  // per batch so that the pairs fit (heavy_ranges)
+  h->huge_slots = std::max<size_t>(4 * ((size_t)max_lookups / (kLongRun + 1) + 1), 32768);
+  h->g.partial_slots = (int64_t)h->huge_slots;
   for (int i = 0; i < kBatchBufs; i++) {
     int rc = alloc_batchbuf(h, h->buf[i], max_lookups);
     if (rc) { g_create_error = h->err; return bail(rc); }
@@ -662,14 +665,12 @@ static int backward_update_with(tbe_ctx *h, const float *d_grad_out, float lr, f
   if (h->current < 0) return fail(h, TBE_EORDER, "backward_update: no forwarded batch");
   const int bi = h->current;
   {
-    StageTimer tm_(h, TBE_STAGE_BACKWARD_HUGE, h->cs);
-    HIP_TRY(h, launch_backward_classes(2, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+    StageTimer tm_(h, TBE_STAGE_BACKWARD_HEAVY, h->cs);
+    HIP_TRY(h, launch_backward_classes(kBwdHeavy, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
   }
   {
-    // with the combine of the huge rows' partial sums, which both this kernel and the one before fill
-    StageTimer tm_(h, TBE_STAGE_BACKWARD_LONG, h->cs);
-    HIP_TRY(h, launch_backward_classes(0, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
-    HIP_TRY(h, launch_backward_classes(3, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+    StageTimer tm_(h, TBE_STAGE_BACKWARD_COMBINE, h->cs);
+    HIP_TRY(h, launch_backward_classes(kBwdCombine, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SINGLE, h->cs);
@@ -677,7 +678,7 @@ static int backward_update_with(tbe_ctx *h, const float *d_grad_out, float lr, f
   }
   {
     StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
-    HIP_TRY(h, launch_backward_classes(1, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+    HIP_TRY(h, launch_backward_classes(kBwdShort, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
   }
   h->current = -1;
   if (h->as != h->cs) {
@@ -751,7 +752,7 @@ int tbe_flush(tbe_handle h) {
                              h->l2, h->cs));
     h->prev_buf = -1;
   }
-  HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->l2, h->d_bytes, h->d_bytes + 1, h->cs));
+  HIP_TRY(h, launch_flush(h->d_tm, h->g, h->tags, h->l2, h->d_bytes, h->d_bytes + 1, h->cs));  // also slot accumulators -> dev_m
   for (const TableMeta &m : h->tm) {
     HIP_TRY(h, hipMemcpyAsync(m.host_m, m.dev_m, 4 * (size_t)m.rows, hipMemcpyDeviceToHost, h->cs));
     h->flush_state_bytes += 4 * m.rows;
@@ -971,7 +972,7 @@ int tbe_get_stats(tbe_handle h, tbe_stats *out) {
     out->last.bypasses = c.n_byp;
     out->last.evictions = (int64_t)c.evictions;
     out->last.hit_lookups = (int64_t)c.hit_lookups;
-    out->last_long_rows = c.n_long;
+    out->last_long_rows = c.n_heavy;
   }
   out->total.lookups = h->total_lookups;
   out->total.uniques = (int64_t)b64[2];

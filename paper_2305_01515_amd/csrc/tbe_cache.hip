@@ -178,11 +178,11 @@ struct SetHeadOp {
   __device__ void finish(BatchCounters *cnt, int, u64 total) const { cnt->n_touched = (int32_t)(total & 0xFFFFFFFFull); }
 };
 
-// Work lists of the backward by run length (see kLongRun / kHugeRun), in the order of the
-// distinct rows (= table order: the backward kernels give each XCD a contiguous part of a
-// list).  A workgroup takes a contiguous chunk of the distinct rows; the count kernel
-// leaves the three counts of every workgroup in `wl`, the emit kernel adds up the counts
-// of the workgroups before it and writes its rows out in order.
+// Work lists of the backward by run length (see kLongRun), in the order of the distinct rows (= table
+// order: the backward kernels give each XCD a contiguous part of a list).  A workgroup takes a contiguous
+// chunk of the distinct rows; the count kernel leaves the two counts of every workgroup in `wl`, the
+// emit kernel adds up the counts of the workgroups before it and writes its rows out in order.  It also
+// counts the heavy rows of every table.
 __device__ inline void worklist_chunk(int n, int &w0, int &w1) {
   const int wave = threadIdx.x >> 6;
   const int per_wave = ((n + gridDim.x * 4 - 1) / (gridDim.x * 4) + 63) / 64 * 64;
@@ -190,143 +190,152 @@ __device__ inline void worklist_chunk(int n, int &w0, int &w1) {
   w1 = min(n, w0 + per_wave);
 }
 
-// counts of the wavefront's chunk: (2..kLongRun, kLongRun+1..kHugeRun, more)
-__device__ inline void worklist_tally(const int32_t *__restrict__ run_off, int w0, int w1, int huge_from,
-                                      int (&c)[3]) {
+__device__ inline int wave_sum(int v) {
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+// counts of the wavefront's chunk: (rows with 2..kLongRun lookups, heavy-list entries of the rows with more)
+__device__ inline void worklist_tally(const int32_t *__restrict__ run_off, int w0, int w1, int (&c)[2]) {
   const int lane = threadIdx.x & 63;
-  c[0] = c[1] = c[2] = 0;
+  c[0] = c[1] = 0;
   for (int u0 = w0; u0 < w1; u0 += 64) {
     const int u = u0 + lane;
     const int len = u < w1 ? run_off[u + 1] - run_off[u] : 0;
     c[0] += __popcll(__ballot(len >= 2 && len <= kLongRun));
-    c[1] += __popcll(__ballot(len > kLongRun && len <= huge_from));
-    c[2] += __popcll(__ballot(len > huge_from));
+    if (__ballot(len > kLongRun)) c[1] += wave_sum(len > kLongRun ? heavy_parts(len) : 0);
   }
 }
 
-// huge_from: rows with more lookups than this go to the huge list (kHugeRun; INT_MAX under max
-// pooling, whose backward has no huge-row kernel: such rows are handled as long ones)
 __global__ __launch_bounds__(256) void worklist_count_kernel(const int32_t *__restrict__ run_off, int32_t *wl,
-                                                             int huge_from, const BatchCounters *cnt) {
-  __shared__ int s_cnt[4][3];
+                                                             const BatchCounters *cnt) {
+  __shared__ int s_cnt[4][2];
   if (cnt->err) return;
-  int w0, w1, c[3];
+  int w0, w1, c[2];
   worklist_chunk(cnt->n_uniq, w0, w1);
-  worklist_tally(run_off, w0, w1, huge_from, c);
+  worklist_tally(run_off, w0, w1, c);
   if ((threadIdx.x & 63) == 0)
-    for (int k = 0; k < 3; k++) s_cnt[threadIdx.x >> 6][k] = c[k];
+    for (int k = 0; k < 2; k++) s_cnt[threadIdx.x >> 6][k] = c[k];
   __syncthreads();
-  if (threadIdx.x < 3) wl[blockIdx.x * 4 + threadIdx.x] = s_cnt[0][threadIdx.x] + s_cnt[1][threadIdx.x] + s_cnt[2][threadIdx.x] + s_cnt[3][threadIdx.x];
+  if (threadIdx.x < 2) wl[blockIdx.x * 2 + threadIdx.x] = s_cnt[0][threadIdx.x] + s_cnt[1][threadIdx.x] + s_cnt[2][threadIdx.x] + s_cnt[3][threadIdx.x];
 }
 
 __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__restrict__ run_off,
+                                                            const int32_t *__restrict__ uniq_tab,
                                                             const int32_t *__restrict__ wl, int32_t *mid_idx,
-                                                            int32_t *items, int32_t *huge, int huge_from,
-                                                            BatchCounters *cnt) {
-  __shared__ int s_cnt[4][3];
-  __shared__ int s_before[4][3];
-  __shared__ int s_base[4][3];
+                                                            int32_t *heavy, int32_t *heavy_sub,
+                                                            int32_t *heavy_per_table, BatchCounters *cnt) {
+  __shared__ int s_cnt[4][2];
+  __shared__ int s_before[4][2];
+  __shared__ int s_base[4][2];
   if (cnt->err) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
-  int w0, w1, c[3];
+  int w0, w1, c[2];
   worklist_chunk(cnt->n_uniq, w0, w1);
-  worklist_tally(run_off, w0, w1, huge_from, c);
-  int before[3] = {0, 0, 0};  // rows of each kind in the workgroups before this one
+  worklist_tally(run_off, w0, w1, c);
+  int before[2] = {0, 0};  // rows of each kind in the workgroups before this one
   for (int b = threadIdx.x; b < (int)blockIdx.x; b += 256)
-    for (int k = 0; k < 3; k++) before[k] += wl[b * 4 + k];
-  for (int k = 0; k < 3; k++)
+    for (int k = 0; k < 2; k++) before[k] += wl[b * 2 + k];
+  for (int k = 0; k < 2; k++)
     for (int d = 32; d >= 1; d >>= 1) before[k] += __shfl_xor(before[k], d, 64);
   if (lane == 0)
-    for (int k = 0; k < 3; k++) { s_cnt[wave][k] = c[k]; s_before[wave][k] = before[k]; }
+    for (int k = 0; k < 2; k++) { s_cnt[wave][k] = c[k]; s_before[wave][k] = before[k]; }
   __syncthreads();
-  if (threadIdx.x < 3) {
+  if (threadIdx.x < 2) {
     const int k = threadIdx.x;
     int base = s_before[0][k] + s_before[1][k] + s_before[2][k] + s_before[3][k];
     for (int w = 0; w < 4; w++) { s_base[w][k] = base; base += s_cnt[w][k]; }
     if (blockIdx.x == gridDim.x - 1) {  // the last workgroup knows the totals
       if (k == 0) cnt->n_mid = base;
-      if (k == 1) cnt->n_items = base;
-      if (k == 2) cnt->n_huge = base;
+      if (k == 1) cnt->n_heavy = base;
     }
   }
   __syncthreads();
-  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0)
-    cnt->n_long = s_base[3][1] + s_cnt[3][1] + s_base[3][2] + s_cnt[3][2];
-  int o_mid = s_base[wave][0], o_item = s_base[wave][1], o_huge = s_base[wave][2];
+  int o_mid = s_base[wave][0], o_heavy = s_base[wave][1];
   for (int u0 = w0; u0 < w1; u0 += 64) {
     const int u = u0 + lane;
     const int len = u < w1 ? run_off[u + 1] - run_off[u] : 0;
     const bool is_mid = len >= 2 && len <= kLongRun;
-    const bool is_item = len > kLongRun && len <= huge_from;
-    const bool is_huge = len > huge_from;
-    const uint64_t bm = __ballot(is_mid), bi = __ballot(is_item), bh = __ballot(is_huge);
+    const bool is_heavy = len > kLongRun;
+    const uint64_t bm = __ballot(is_mid);
     if (is_mid) mid_idx[o_mid + __popcll(bm & lt_mask)] = u;
-    if (is_item) items[o_item + __popcll(bi & lt_mask)] = u;
-    if (is_huge) huge[o_huge + __popcll(bh & lt_mask)] = u;
-    o_mid += __popcll(bm); o_item += __popcll(bi); o_huge += __popcll(bh);
-  }
-}
-
-// Group the huge rows by table and cut every table's group into chunks of `rows per
-// workgroup` of the table's kernel class (256 / lanes per row).  One workgroup; the number
-// of huge rows is small (a batch has fewer than N / kHugeRun of them).
-__global__ __launch_bounds__(1024) void huge_group_kernel(const TableMeta *__restrict__ tm, int T,
-                                                          const int32_t *__restrict__ huge,
-                                                          const int32_t *__restrict__ uniq_tab,
-                                                          const int32_t *__restrict__ run_off, int32_t *huge_sorted,
-                                                          int32_t *wide, uint4 *hchunks, int32_t *hg,
-                                                          BatchCounters *cnt) {
-  __shared__ int s_wide;
-  if (cnt->err) return;
-  const int n_huge = cnt->n_huge;
-  if (threadIdx.x == 0) s_wide = 0;
-  int32_t *count = hg, *offset = hg + (T + 1), *fill = hg + 2 * (T + 1);
-  for (int t = threadIdx.x; t <= T; t += blockDim.x) count[t] = offset[t] = fill[t] = 0;
-  __syncthreads();
-  for (int h = threadIdx.x; h < n_huge; h += blockDim.x) atomicAdd(&count[uniq_tab[huge[h]]], 1);
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int off = 0, nc = 0;
-    for (int t = 0; t < T; t++) {
-      offset[t] = off;
-      const int per = 256 / tm[t].lanes;
-      for (int c = 0; c < count[t]; c += per)
-        hchunks[nc++] = make_uint4((uint32_t)t, (uint32_t)(off + c), (uint32_t)min(per, count[t] - c), 0u);
-      off += count[t];
+    o_mid += __popcll(bm);
+    if (__ballot(is_heavy)) {  // uniform: the entries of the wavefront's heavy rows, in row order
+      const int parts = is_heavy ? heavy_parts(len) : 0;
+      int incl = parts;
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+      }
+      const int at = o_heavy + incl - parts;
+      for (int q = 0; q < parts; q++) {
+        heavy[at + q] = u;
+        heavy_sub[at + q] = q | (parts << 16);
+      }
+      if (is_heavy) atomicAdd(&heavy_per_table[uniq_tab[u]], parts);
+      o_heavy += __shfl(incl, 63, 64);
     }
-    cnt->n_hchunks = nc;
   }
-  __syncthreads();
-  for (int h = threadIdx.x; h < n_huge; h += blockDim.x) {
-    const int u = huge[h];
-    const int t = uniq_tab[u];
-    huge_sorted[offset[t] + atomicAdd(&fill[t], 1)] = h;
-    if (run_off[u + 1] - run_off[u] > kWideRun) wide[atomicAdd(&s_wide, 1)] = h;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) cnt->n_wide = s_wide;
 }
 
-// For every huge row and bag range: the first sorted position of the row whose bag lies in
-// the range (the row's lookups are sorted by bag).  One thread per (row, range).
-__global__ __launch_bounds__(256) void huge_starts_kernel(const TableMeta *__restrict__ tm, int B,
-                                                          const int32_t *__restrict__ huge,
-                                                          const int32_t *__restrict__ uniq_tab,
-                                                          const int32_t *__restrict__ run_off,
-                                                          const int32_t *__restrict__ sorted_bag, int32_t *hstart,
-                                                          const BatchCounters *cnt) {
+// The heavy list is in table order.  Cut every table's part into chunks of the rows one workgroup of the
+// tile kernel takes (heavy_chunk_rows of the table's lanes per row), and fix the number of bag ranges of
+// this batch.  One workgroup; tables are taken 256 at a time.
+__global__ __launch_bounds__(256) void heavy_group_kernel(const TableMeta *__restrict__ tm, int T,
+                                                          const int32_t *__restrict__ heavy_per_table,
+                                                          uint4 *hchunks, long long slot_capacity, BatchCounters *cnt) {
+  __shared__ int s_rows[4], s_chunks[4];
+  __shared__ int s_carry[2];
   if (cnt->err) return;
-  const int R = huge_ranges(cnt->n_hchunks);
-  const int n = cnt->n_huge * R;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) s_carry[0] = s_carry[1] = 0;
+  __syncthreads();
+  for (int t0 = 0; t0 < T; t0 += 256) {
+    const int t = t0 + tid;
+    const int rows = t < T ? heavy_per_table[t] : 0;
+    const int per = t < T ? heavy_chunk_rows(tm[t].lanes, tm[t].dtype) : 1;
+    const int chunks = (rows + per - 1) / per;
+    int ir = rows, ic = chunks;  // inclusive scans over the workgroup
+    for (int d = 1; d < 64; d <<= 1) {
+      const int a = __shfl_up(ir, d), b = __shfl_up(ic, d);
+      if (lane >= d) { ir += a; ic += b; }
+    }
+    if (lane == 63) { s_rows[wave] = ir; s_chunks[wave] = ic; }
+    __syncthreads();
+    int row0 = s_carry[0] + ir - rows, chunk0 = s_carry[1] + ic - chunks;
+    for (int w = 0; w < wave; w++) { row0 += s_rows[w]; chunk0 += s_chunks[w]; }
+    for (int c = 0; c < chunks; c++)
+      hchunks[chunk0 + c] = make_uint4((uint32_t)t, (uint32_t)(row0 + c * per), (uint32_t)min(per, rows - c * per), 0u);
+    __syncthreads();
+    if (tid == 255) { s_carry[0] = row0 + rows; s_carry[1] = chunk0 + chunks; }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    cnt->n_hchunks = s_carry[1];
+    cnt->h_ranges = heavy_ranges(s_carry[1], cnt->n_heavy, slot_capacity);
+  }
+}
+
+// For every entry of the heavy list and bag range: the first sorted position of the entry's row whose bag
+// lies in the range (the row's lookups are sorted by bag).  One thread per (entry, range).
+__global__ __launch_bounds__(256) void heavy_starts_kernel(const TableMeta *__restrict__ tm, int B,
+                                                           const int32_t *__restrict__ heavy,
+                                                           const int32_t *__restrict__ uniq_tab,
+                                                           const int32_t *__restrict__ run_off,
+                                                           const int32_t *__restrict__ sorted_bag, int32_t *hstart,
+                                                           const BatchCounters *cnt) {
+  if (cnt->err) return;
+  const int R = cnt->h_ranges;
+  const int n = cnt->n_heavy * R;
   for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < n; x += gridDim.x * blockDim.x) {
     const int h = x / R, range = x % R;
-    const int u = huge[h];
+    const int u = heavy[h];
     const int t = uniq_tab[u];
-    const int tb = huge_tile_bags(kTileBytes / (tm[t].lanes * (tm[t].dtype == 0 ? 4 : 8) * 4), B);  // bags per gradient tile
+    const int tb = heavy_tile_bags(tm[t].lanes, tm[t].dtype);
     const int n_tiles = (B + tb - 1) / tb;
     const int tiles_per_range = (n_tiles + R - 1) / R;
-    const int first_bag = t * B + range * tiles_per_range * tb;
+    const long long first_bag = (long long)t * B + (long long)range * tiles_per_range * tb;
     int lo = run_off[u], hi = run_off[u + 1];
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;
@@ -683,14 +692,15 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
   run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
-  const int huge_from = b.maxp ? 0x7FFFFFFF : kHugeRun;
-  hipLaunchKernelGGL(worklist_count_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, huge_from, b.cnt);
-  hipLaunchKernelGGL(worklist_emit_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, b.mid_idx, b.items,
-                     b.huge, huge_from, b.cnt);
-  hipLaunchKernelGGL(huge_group_kernel, dim3(1), dim3(1024), 0, s, tm, g.T, b.huge, b.uniq_tab, b.run_off, b.huge_sorted, b.wide, b.hchunks,
-                     b.hg_count, b.cnt);
-  hipLaunchKernelGGL(huge_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.huge, b.uniq_tab, b.run_off,
-                     b.sorted_bag, b.hstart, b.cnt);
+  hipLaunchKernelGGL(worklist_count_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, b.cnt);
+  hipLaunchKernelGGL(worklist_emit_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, b.uniq_tab, ss.wl, b.mid_idx,
+                     b.heavy, b.heavy_sub, b.hg_count, b.cnt);
+  if (!b.maxp) {  // the tile kernel's chunks and range starts (max pooling takes heavy rows a workgroup each)
+    hipLaunchKernelGGL(heavy_group_kernel, dim3(1), dim3(256), 0, s, tm, g.T, b.hg_count, b.hchunks,
+                       (long long)g.partial_slots, b.cnt);
+    hipLaunchKernelGGL(heavy_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.heavy, b.uniq_tab, b.run_off,
+                       b.sorted_bag, b.hstart, b.cnt);
+  }
   int64_t max_touched = (int64_t)g.total_sets + g.T;
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);

@@ -297,11 +297,18 @@ struct RowRef {
 };
 
 // The accumulators of all rows stay in HBM (the paper keeps optimizer parameters there,
-// Section 5.6.1): only the row itself is in a cache line or in the backing tier.
+// Section 5.6.1).  That of a cached row is kept in an array indexed by cache slot (the commit
+// moves it there with the row), so the hit path touches a few megabytes of accumulators instead
+// of four bytes here and there among those of all rows; a bypassed row's stays where all rows' are.
 __device__ inline RowRef locate(const TableMeta &m, uint32_t key, int slot, char *ovf, uint32_t ovf_stride) {
   RowRef r;
-  r.w = slot >= 0 ? m.lines + (size_t)(slot - m.slot_base) * m.row_bytes : ovf + (size_t)(-2 - slot) * ovf_stride;
-  r.m = m.dev_m + row_of_key(m, key);
+  if (slot >= 0) {
+    r.w = m.lines + (size_t)(slot - m.slot_base) * m.row_bytes;
+    r.m = m.slot_m + (slot - m.slot_base);
+  } else {
+    r.w = ovf + (size_t)(-2 - slot) * ovf_stride;
+    r.m = m.dev_m + row_of_key(m, key);
+  }
   return r;
 }
 
@@ -392,7 +399,7 @@ __device__ inline void update_row(const TableMeta &m, uint32_t key, int slot, ch
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *__restrict__ tm,
                                                               const int32_t *__restrict__ class_tables, int B,
-                                                              int sum_dim, const int64_t *__restrict__ indices,
+                                                              int sum_dim, const uint32_t *__restrict__ byp_key,
                                                               const int64_t *__restrict__ offsets,
                                                               const uint32_t *__restrict__ loc,
                                                               const float *__restrict__ grad_out, float lr, float eps,
@@ -410,7 +417,7 @@ __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *_
   if (lo == hi) return;
   const bool active = lig * EPL < m.dim;
   char *lines = m.lines;
-  float *dev_m = m.dev_m;
+  float *slot_m = m.slot_m;
   const uint32_t rb = m.row_bytes;
   const int slot_base = m.slot_base;
   const int gshift = (threadIdx.x & 63) / G * G;  // first lane of this group inside the wavefront
@@ -430,12 +437,7 @@ __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *_
   const float msq = sq / (float)m.dim;
   for (int64_t j0 = lo; j0 < hi; j0 += G) {
     const int nq = (int)((hi - j0) < G ? (hi - j0) : G);
-    uint32_t my_loc = 0u;
-    int my_row = 0;
-    if (lig < nq) {
-      my_loc = loc[j0 + lig];
-      if (my_loc & kLocSingle) my_row = (int)indices[j0 + lig];
-    }
+    const uint32_t my_loc = lig < nq ? loc[j0 + lig] : 0u;
     uint64_t todo = __ballot((my_loc & kLocSingle) != 0) >> gshift;  // the group's single-lookup rows
     if (G < 64) todo &= (1ull << G) - 1ull;
     while (todo) {
@@ -450,10 +452,14 @@ __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *_
           const int q = __ffsll((unsigned long long)todo) - 1;
           todo &= todo - 1;
           const uint32_t l = __shfl(my_loc, q, G);
-          const int r = __shfl(my_row, q, G);
           const uint32_t ix = l & kLocIndex;
-          w[x] = ((l & kLocOverflow) ? ovf + (size_t)ix * ovf_stride : lines + (size_t)((int)ix - slot_base) * rb) + lig * 16;
-          mp[x] = dev_m + r;
+          if (l & kLocOverflow) {  // a bypassed row: its copy, and its accumulator among those of all rows
+            w[x] = ovf + (size_t)ix * ovf_stride + lig * 16;
+            mp[x] = m.dev_m + row_of_key(m, byp_key[ix]);
+          } else {
+            w[x] = lines + (size_t)((int)ix - slot_base) * rb + lig * 16;
+            mp[x] = slot_m + ((int)ix - slot_base);
+          }
           m_old[x] = *mp[x];
           if (active) raw[x] = load_once(w[x]);
           n = x + 1;
@@ -478,7 +484,7 @@ __global__ __launch_bounds__(256) void backward_single_kernel(const TableMeta *_
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_single_max_kernel(const TableMeta *__restrict__ tm,
                                                               const int32_t *__restrict__ class_tables, int B,
-                                                              int sum_dim, const int64_t *__restrict__ indices,
+                                                              int sum_dim, const uint32_t *__restrict__ byp_key,
                                                               const int64_t *__restrict__ offsets,
                                                               const uint32_t *__restrict__ loc,
                                                               const float *__restrict__ grad_out, float lr, float eps,
@@ -496,7 +502,7 @@ __global__ __launch_bounds__(256) void backward_single_max_kernel(const TableMet
   if (lo == hi) return;
   const bool active = lig * EPL < m.dim;
   char *lines = m.lines;
-  float *dev_m = m.dev_m;
+  float *slot_m = m.slot_m;
   const uint32_t rb = m.row_bytes;
   const int slot_base = m.slot_base;
   const int gshift = (threadIdx.x & 63) / G * G;  // first lane of this group inside the wavefront
@@ -518,12 +524,7 @@ __global__ __launch_bounds__(256) void backward_single_max_kernel(const TableMet
   const float inv_dim = 1.0f / (float)m.dim;
   for (int64_t j0 = lo; j0 < hi; j0 += G) {
     const int nq = (int)((hi - j0) < G ? (hi - j0) : G);
-    uint32_t my_loc = 0u;
-    int my_row = 0;
-    if (lig < nq) {
-      my_loc = loc[j0 + lig];
-      if (my_loc & kLocSingle) my_row = (int)indices[j0 + lig];
-    }
+    const uint32_t my_loc = lig < nq ? loc[j0 + lig] : 0u;
     uint64_t todo = __ballot((my_loc & kLocSingle) != 0) >> gshift;  // the group's single-lookup rows
     if (G < 64) todo &= (1ull << G) - 1ull;
     while (todo) {
@@ -539,10 +540,14 @@ __global__ __launch_bounds__(256) void backward_single_max_kernel(const TableMet
           const int q = __ffsll((unsigned long long)todo) - 1;
           todo &= todo - 1;
           const uint32_t l = __shfl(my_loc, q, G);
-          const int r = __shfl(my_row, q, G);
           const uint32_t ix = l & kLocIndex;
-          w[x] = ((l & kLocOverflow) ? ovf + (size_t)ix * ovf_stride : lines + (size_t)((int)ix - slot_base) * rb) + lig * 16;
-          mp[x] = dev_m + r;
+          if (l & kLocOverflow) {  // a bypassed row: its copy, and its accumulator among those of all rows
+            w[x] = ovf + (size_t)ix * ovf_stride + lig * 16;
+            mp[x] = m.dev_m + row_of_key(m, byp_key[ix]);
+          } else {
+            w[x] = lines + (size_t)((int)ix - slot_base) * rb + lig * 16;
+            mp[x] = slot_m + ((int)ix - slot_base);
+          }
           m_old[x] = *mp[x];
           within[x] = (int)(j0 - lo) + q;
           if (active) raw[x] = load_once(w[x]);
@@ -608,11 +613,14 @@ __global__ __launch_bounds__(256) void backward_short_kernel(const TableMeta *__
   }
 }
 
-// Rows with kLongRun < lookups <= kHugeRun: one workgroup per row, its 256/G groups take
-// chunks of G lookups round robin; the partial sums are added in group order through LDS.
+// Max pooling, and rows narrower than 4 lanes: rows with more than kLongRun lookups, one workgroup per row, its 256/G groups take
+// chunks of G lookups round robin; the partial sums are added in group order through LDS.  (The
+// gradient a lookup receives is masked by who supplied each maximum, so the bags' gradient rows cannot
+// be shared between rows the way the tile kernel below shares them.)
 template <int DT, int G, int MODE>
 __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__restrict__ tm, int cls, int B,
-                                                            int sum_dim, const int32_t *__restrict__ items,
+                                                            int sum_dim, const int32_t *__restrict__ heavy,
+                                                            const int32_t *__restrict__ heavy_sub,
                                                             const uint32_t *__restrict__ uniq_key,
                                                             const int32_t *__restrict__ uniq_tab,
                                                             const int32_t *__restrict__ run_off,
@@ -624,21 +632,18 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
                                                             const float *__restrict__ inv_len,
                                                             const int32_t *__restrict__ argpos,
                                                             const int32_t *__restrict__ sorted_within,
-                                                            const int32_t *__restrict__ huge,
-                                                            const int32_t *__restrict__ wide,
-                                                            const int32_t *__restrict__ hstart,
-                                                            float *__restrict__ partials, int pstride,
                                                             const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int NG = 256 / G;
   __shared__ float part[NG][G * EPL + 1];
   if (cnt->err) return;
-  const int n_items = cnt->n_items;
+  const int n_heavy = cnt->n_heavy;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
   int first, end, step;
-  xcd_span(n_items, 1, first, end, step);  // the list is in table order
+  xcd_span(n_heavy, 1, first, end, step);  // the list is in table order
   for (int it = first; it < end; it += step) {
-    const int u = items[it];
+    if (heavy_sub[it] & 0xFFFF) continue;  // a hot row has several entries: it is taken whole at its first
+    const int u = heavy[it];
     const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
@@ -663,179 +668,193 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
       update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
     }
   }
-  // The widest rows (more than kWideRun lookups: a table with a steep power law and long bags has
-  // rows with a quarter of its lookups) would each keep one lane group of the tile kernel below busy
-  // long after the others of its chunk are done, so that kernel leaves them out.  They are summed
-  // here the same way as the rows above, a workgroup per (row, bag range of the tile kernel): the
-  // lookups of such a row visit nearly every bag in ascending order, several times each, so the
-  // gradient reads stay in L1 / L2.  The sums go to the row's slots of `partials` for the combine kernel.
-  const int R = huge_ranges(cnt->n_hchunks);
-  const int n_wide_work = cnt->n_wide * R;
-  xcd_span(n_wide_work, 1, first, end, step);
-  for (int wk = first; wk < end; wk += step) {
-    const int h = wide[wk / R], range = wk % R;
-    const int u = huge[h];
-    const int t = uniq_tab[u];
-    if (table_class[t] != cls) continue;  // uniform over the block
-    const TableMeta &m = tm[t];
-    const bool active = lig * EPL < m.dim;
-    const int i0 = hstart[h * R + range];
-    const int i1 = range + 1 < R ? hstart[h * R + range + 1] : run_off[u + 1];
-    float g[EPL];
+}
+
+// Heavy rows (more than kLongRun lookups; sum and mean pooling).  Such rows carry most of a power-law
+// batch's lookups, and the lookups of a row are sorted by bag, so all heavy rows of a table sweep the
+// table's slice of the output gradient front to back.  A workgroup takes (table, chunk of the table's
+// heavy rows, bag range): it streams the range through LDS tile by tile -- every gradient row is read
+// from memory once per chunk, coalesced, the next tile's loads in flight while this one is consumed --
+// and each lane group adds up, from LDS, the lookups of its up to kHeavyRowsPerGroup rows that fall
+// into the tile (sums in registers).  The partial sums of a row, one per range, go to `partials`; the
+// combine kernel adds them in range order and updates the row.
+//
+// A lane group keeps, per row, a window of G consecutive sorted bag ids (one per lane), how many of
+// them it has consumed, and the position of the window; lookups are sorted by bag, so the ones inside
+// the tile are a prefix of what is left of the window.
+struct HeavySlot {
+  int bag;   // this lane's bag id of the window (0x7FFFFFFF outside the row's lookups of this range)
+  int next;  // ... of the entry's next window, requested when this one was started
+  int used;  // ids of the window consumed so far (same in all lanes of the group)
+};
+
+// this lane's bag id of the window that starts at sorted position `at`, for a row whose lookups of the
+// range are [lo, hi)
+__device__ inline int heavy_window(const int32_t *__restrict__ sorted_bag, int at, int lo, int hi, int lig) {
+  const int p = at + lig;
+  return (p >= lo && p < hi) ? sorted_bag[p] : 0x7FFFFFFF;
+}
+
+// win: in LDS, (sorted position of the window after `next`, end of the row's lookups inside this bag range,
+// distance between the entry's windows) -- touched once per G lookups, so they need not sit in registers
+template <int DT, int G>
+__device__ inline void heavy_consume(HeavySlot &sl, int4 *win, float (&g)[Elems<DT>::n], const float *tile,
+                                     int row_stride, int base_bag, int end_bag,
+                                     const int32_t *__restrict__ sorted_bag, int lig, int gshift) {
+  constexpr int EPL = Elems<DT>::n;
+  constexpr int Q = EPL == 8 ? 2 : 4;  // gradient rows read from LDS before they are added
+  while (true) {
+    uint64_t ok = __ballot(lig >= sl.used && sl.bag < end_bag) >> gshift;
+    if (G < 64) ok &= (1ull << G) - 1ull;
+    const int n_ok = __popcll(ok);  // lanes used .. used + n_ok - 1 hold lookups of this tile
+    if (n_ok == 0) break;
+    for (int q = 0; q < n_ok; q += Q) {
+      float4 v[Q][EPL / 4];
 #pragma unroll
-    for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    reduce_grads<DT, G, MODE>(g, grad_out + m.col + lig * EPL, sorted_bag, t * B, sum_dim, i0, i1, grp, NG, lig, active,
-                              inv_len, MODE == kMax ? argpos + m.col + lig * EPL : nullptr, sorted_within);
-    __syncthreads();
+      for (int x = 0; x < Q; x++) {
+        const int bq = __shfl(sl.bag, (sl.used + q + x) & (G - 1), G);
+        const float *src = tile + (q + x < n_ok ? bq - base_bag : 0) * row_stride + lig * EPL;
 #pragma unroll
-    for (int e = 0; e < EPL; e++) part[grp][lig * EPL + e] = g[e];
-    __syncthreads();
-    if (grp == 0) {
-      float *p = partials + ((size_t)h * R + range) * pstride + lig * EPL;
-#pragma unroll
-      for (int e = 0; e < EPL; e++) {
-        float sum = 0.f;
-        for (int q = 0; q < NG; q++) sum += part[q][lig * EPL + e];
-        p[e] = sum;
+        for (int e = 0; e < EPL / 4; e++) v[x][e] = *(const float4 *)(src + 4 * e);
       }
+#pragma unroll
+      for (int x = 0; x < Q; x++)
+        if (q + x < n_ok) {
+#pragma unroll
+          for (int e = 0; e < EPL / 4; e++) {
+            g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
+          }
+        }
     }
+    sl.used += n_ok;
+    if (sl.used < G) break;  // what is left of the window lies behind this tile
+    int4 w = *win;           // window used up: on to the one requested before, and request the one after it
+    sl.used = 0;
+    sl.bag = sl.next;
+    sl.next = heavy_window(sorted_bag, w.x, 0, w.y, lig);
+    w.x += w.z;
+    if (lig == 0) *win = w;
   }
 }
 
-// Rows with more than kHugeRun lookups.  Such a row touches a large part of its table's bags,
-// and the lookups of a row are sorted by bag, so the table's huge rows all sweep the same
-// gradient slice.  A workgroup takes (table, up to 256/G of its huge rows, one of
-// the batch's bag ranges, see huge_ranges): it stages the range tile by tile in LDS (each gradient row read
-// once, coalesced) and every group adds up, from LDS, the lookups of its row that fall into
-// the tile.  The partial sums of a row, one per range, go to `partials`; the combine kernel adds
-// them in range order and updates the row.
 template <int DT, int G>
-__global__ __launch_bounds__(256) void backward_huge_kernel(const TableMeta *__restrict__ tm, int cls, int B,
-                                                            int sum_dim, const uint4 *__restrict__ hchunks,
-                                                            const int32_t *__restrict__ huge_sorted,
-                                                            const int32_t *__restrict__ huge,
-                                                            const int32_t *__restrict__ hstart,
-                                                            const int32_t *__restrict__ run_off,
-                                                            const int32_t *__restrict__ sorted_bag,
-                                                            const float *__restrict__ grad_out,
-                                                            float *__restrict__ partials, int pstride,
-                                                            const int32_t *__restrict__ table_class,
-                                                            const float *__restrict__ inv_len,
-                                                            const BatchCounters *cnt) {
+__global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const TableMeta *__restrict__ tm, int cls, int B,
+                                                                       int sum_dim, const uint4 *__restrict__ hchunks,
+                                                                       const int32_t *__restrict__ heavy,
+                                                                       const int32_t *__restrict__ heavy_sub,
+                                                                       const int32_t *__restrict__ hstart,
+                                                                       const int32_t *__restrict__ run_off,
+                                                                       const int32_t *__restrict__ sorted_bag,
+                                                                       const float *__restrict__ grad_out,
+                                                                       float *__restrict__ partials, int pstride,
+                                                                       const int32_t *__restrict__ table_class,
+                                                                       const float *__restrict__ inv_len,
+                                                                       const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
-  constexpr int ROWF = G * EPL;                       // floats per staged gradient row
-  constexpr int TB_MAX = kTileBytes / (ROWF * 4);     // bags that fit a tile
-  __shared__ float tile[TB_MAX * ROWF];
+  constexpr int ROWF = G * EPL;                           // floats per gradient row as the lanes see it
+  constexpr int STRIDE = ROWF + (ROWF >= 32 ? 4 : 0);     // ... and per staged row (wide rows: 16 bytes of padding,
+                                                          //     so that the groups of a wavefront start in different banks)
+  constexpr int TB = kHeavyTileBytes / (ROWF * 4);        // bags per tile (= heavy_tile_bags)
+  constexpr int NG = kHeavyThreads / G;                   // lane groups
+  constexpr int RPG = heavy_rows_per_group(DT);
+  constexpr int PER = kHeavyTileBytes / 16 / kHeavyThreads;  // float4 per thread and tile
+  __shared__ float tile[TB * STRIDE];
+  __shared__ int4 s_win[RPG][NG];  // per (row of a group, group): see heavy_consume
   if (cnt->err) return;
-  const int R = huge_ranges(cnt->n_hchunks);
+  const int R = cnt->h_ranges;
   const int n_work = cnt->n_hchunks * R;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
   const int gshift = (threadIdx.x & 63) / G * G;
-  const int TB = huge_tile_bags(TB_MAX, B);
   const int n_tiles = (B + TB - 1) / TB;
   const int tiles_per_range = (n_tiles + R - 1) / R;
   int first, end, step;
   xcd_span(n_work, 1, first, end, step);  // work items are in table order
   for (int wk = first; wk < end; wk += step) {
-    const uint4 ch = hchunks[wk / R];  // (table, first position in huge_sorted, rows, -)
+    const uint4 ch = hchunks[wk / R];  // (table, first position in `heavy`, rows, -)
     const int range = wk % R;
     const int t = (int)ch.x;
     if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
-    const int dim = m.dim;
-    bool has_row = grp < (int)ch.z;
-    const int h = has_row ? huge_sorted[ch.y + grp] : 0;
-    const int u = huge[h];
+    const int dim = m.dim, col = m.col;
     const int bag0 = t * B;
-    const int i1 = has_row ? run_off[u + 1] : 0;
-    if (has_row && i1 - run_off[u] > kWideRun) has_row = false;  // left to backward_wide_kernel
-    const int tile_lo = range * tiles_per_range, tile_hi = min(n_tiles, tile_lo + tiles_per_range);
-    int i = has_row ? hstart[h * R + range] : 0;  // first lookup of the row in this bag range
-    float g[EPL];
+    const int tile_lo = min(n_tiles, range * tiles_per_range), tile_hi = min(n_tiles, tile_lo + tiles_per_range);
+    HeavySlot sl[RPG];
+    float g[RPG][EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    int my_bag = 0x7FFFFFFF, fetched_at = -1;
-    for (int tl = tile_lo; tl < tile_hi; tl++) {
-      const int b_first = tl * TB, b_end = min(B, b_first + TB);
-      __syncthreads();  // the previous tile is no longer read
-      {
-        constexpr int PER = kTileBytes / 16 / 256;  // float4 per thread and tile
-        float4 v[PER];
-        const int n_f = (b_end - b_first) * ROWF;
+    for (int s = 0; s < RPG; s++) {
+      const int j = s * NG + grp;  // the chunk's row j: rows are dealt round the groups
+      const bool has = j < (int)ch.z;
+      const int h = (int)ch.y + (has ? j : 0);
+      const int u = heavy[h];
+      // The row's lookups of this bag range are the sorted positions [lo, hi).  The row is read in windows of G
+      // positions counted from its first lookup; this entry is part `part` of `parts` and takes the windows
+      // part, part + parts, ...: the first of them that reaches into the range, its ids before lo counting as used.
+      const int sub = heavy_sub[h], part = sub & 0xFFFF, parts = sub >> 16;
+      const int run0 = run_off[u];
+      const int lo = has ? hstart[h * R + range] : 0;
+      const int hi = !has ? 0 : (range + 1 < R ? hstart[h * R + range + 1] : run_off[u + 1]);
+      const int w0 = (lo - run0) / G;                               // window that holds position lo
+      const int w = w0 + ((part - w0) % parts + parts) % parts;     // first window >= w0 of this part
+      const int at = run0 + w * G, stride = parts * G;
+      if (lig == 0) s_win[s][grp] = make_int4(at + 2 * stride, hi, stride, 0);  // only this group reads it
+      sl[s].used = (w == w0 && lo > at) ? lo - at : 0;
+      sl[s].bag = heavy_window(sorted_bag, at, lo, hi, lig);
+      sl[s].next = heavy_window(sorted_bag, at + stride, lo, hi, lig);
 #pragma unroll
-        for (int k = 0; k < PER; k++) {
-          const int x = (k * 256 + threadIdx.x) * 4;
-          const int bl = x / ROWF, c = x % ROWF;
-          v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (x < n_f && c < dim) {
-            v[k] = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + m.col + c);
-            if (inv_len) {  // mean pooling: the staged gradient row already carries the bag's 1/L
-              const float sc = inv_len[bag0 + b_first + bl];
-              v[k].x *= sc; v[k].y *= sc; v[k].z *= sc; v[k].w *= sc;
-            }
+      for (int e = 0; e < EPL; e++) g[s][e] = 0.f;
+    }
+    // this thread's share of a tile: float4 number k * threads + tid of the tile's TB x ROWF floats
+    auto load_tile = [&](int tl, float4 (&v)[PER]) {
+      const int b_first = tl * TB, n_f = (min(B, b_first + TB) - b_first) * ROWF;
+#pragma unroll
+      for (int k = 0; k < PER; k++) {
+        const int x = (k * kHeavyThreads + threadIdx.x) * 4;
+        const int bl = x / ROWF, c = x % ROWF;
+        v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (x < n_f && c < dim) {
+          v[k] = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + col + c);
+          if (inv_len) {  // mean pooling: the staged gradient row already carries the bag's 1/L
+            const float sc = inv_len[bag0 + b_first + bl];
+            v[k].x *= sc; v[k].y *= sc; v[k].z *= sc; v[k].w *= sc;
           }
         }
+      }
+    };
+    float4 pre[PER];
+    if (tile_lo < tile_hi) load_tile(tile_lo, pre);
+    for (int tl = tile_lo; tl < tile_hi; tl++) {
+      __syncthreads();  // the previous tile is no longer read
 #pragma unroll
-        for (int k = 0; k < PER; k++) *(float4 *)(tile + (k * 256 + threadIdx.x) * 4) = v[k];
+      for (int k = 0; k < PER; k++) {
+        const int x = (k * kHeavyThreads + threadIdx.x) * 4;
+        *(float4 *)(tile + (x / ROWF) * STRIDE + x % ROWF) = pre[k];
       }
       __syncthreads();
-      const int end_bag = bag0 + b_end;
-      const int base_bag = bag0 + b_first;
-      bool more = has_row;
-      while (more) {
-        if (fetched_at != i) {  // the group's next G bag ids (kept across tiles while unconsumed)
-          my_bag = (i + lig < i1) ? sorted_bag[i + lig] : 0x7FFFFFFF;
-          fetched_at = i;
-        }
-        uint64_t ok = __ballot(my_bag < end_bag) >> gshift;
-        if (G < 64) ok &= (1ull << G) - 1ull;
-        const int n_ok = __popcll(ok);  // lookups are sorted by bag: the group's first n_ok are in the tile
-        // the ids after these, fetched now so that the load overlaps the additions
-        const int nxt = (n_ok == G && i + G + lig < i1) ? sorted_bag[i + G + lig] : 0x7FFFFFFF;
-        for (int q = 0; q < n_ok; q += 4) {
-          float4 v[4][EPL / 4];
+      if (tl + 1 < tile_hi) load_tile(tl + 1, pre);  // in flight while this tile is consumed
+      const int base_bag = bag0 + tl * TB, end_bag = bag0 + min(B, (tl + 1) * TB);
 #pragma unroll
-          for (int x = 0; x < 4; x++) {
-            const int bq = __shfl(my_bag, (q + x) & (G - 1), G);
-            const float *src = tile + (q + x < n_ok ? bq - base_bag : 0) * ROWF + lig * EPL;
-#pragma unroll
-            for (int e = 0; e < EPL / 4; e++) v[x][e] = *(const float4 *)(src + 4 * e);
-          }
-#pragma unroll
-          for (int x = 0; x < 4; x++)
-            if (q + x < n_ok) {
-#pragma unroll
-              for (int e = 0; e < EPL / 4; e++) {
-                g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
-              }
-            }
-        }
-        i += n_ok;
-        more = n_ok == G;
-        if (n_ok == G) {
-          my_bag = nxt;
-          fetched_at = i;
-        } else if (n_ok > 0) {  // shift the unconsumed ids to the front
-          my_bag = __shfl(my_bag, (lig + n_ok) & (G - 1), G);
-          if (lig + n_ok >= G) my_bag = (i + lig < i1) ? sorted_bag[i + lig] : 0x7FFFFFFF;
-          fetched_at = i;
-        }
-      }
+      for (int s = 0; s < RPG; s++)
+        heavy_consume<DT, G>(sl[s], &s_win[s][grp], g[s], tile, STRIDE, base_bag, end_bag, sorted_bag, lig, gshift);
     }
-    if (has_row) {
-      float *p = partials + ((size_t)h * R + range) * pstride + lig * EPL;
 #pragma unroll
-      for (int e = 0; e < EPL; e++) p[e] = g[e];
+    for (int s = 0; s < RPG; s++) {
+      const int j = s * NG + grp;
+      if (j < (int)ch.z) {
+        float *p = partials + ((size_t)((int)ch.y + j) * R + range) * pstride + lig * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4) *(float4 *)(p + e) = make_float4(g[s][e], g[s][e + 1], g[s][e + 2], g[s][e + 3]);
+      }
     }
   }
 }
 
-// Huge rows: add the partial sums, then update the row.  One workgroup per row: its 256/G
+// Heavy rows: add the partial sums, then update the row.  One workgroup per row: its 256/G
 // groups each add a contiguous share of the ranges in range order, the shares are added in
 // group order through LDS (a fixed order, so the result is reproducible).
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int cls,
-                                                               const int32_t *__restrict__ huge,
+                                                               const int32_t *__restrict__ heavy,
+                                                               const int32_t *__restrict__ heavy_sub,
                                                                const uint32_t *__restrict__ uniq_key,
                                                                const int32_t *__restrict__ uniq_tab,
                                                                const int32_t *__restrict__ loc_u,
@@ -848,12 +867,16 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
   constexpr int NG = 256 / G;
   __shared__ float part[NG][G * EPL + 1];
   if (cnt->err) return;
-  const int n_huge = cnt->n_huge;
-  const int R = huge_ranges(cnt->n_hchunks);
+  const int n_heavy = cnt->n_heavy;
+  const int R = cnt->h_ranges;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
-  const int per = (R + NG - 1) / NG;
-  for (int h = blockIdx.x; h < n_huge; h += gridDim.x) {
-    const int u = huge[h];
+  int first, end, step;
+  xcd_span(n_heavy, 1, first, end, step);  // the list is in table order
+  for (int h = first; h < end; h += step) {
+    const int sub = heavy_sub[h];
+    if (sub & 0xFFFF) continue;  // the entries of a row's parts follow its first one: their sums are added here
+    const int n_sums = (sub >> 16) * R, per = (n_sums + NG - 1) / NG;
+    const int u = heavy[h];
     const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;  // uniform over the block
     const TableMeta &m = tm[t];
@@ -861,8 +884,8 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    const int r1 = min(R, (grp + 1) * per);
-    for (int r = grp * per; r < r1; r++) {
+    const int r1 = min(n_sums, (grp + 1) * per);
+    for (int r = grp * per; r < r1; r++) {  // (part, range) pairs in order: slot (h + part) * R + range = h * R + r
       const float *p = partials + ((size_t)h * R + r) * pstride + lig * EPL;
 #pragma unroll
       for (int e = 0; e < EPL; e++) g[e] += p[e];
@@ -902,20 +925,25 @@ static void fwd_one(const TableMeta *tm, const int32_t *tables, int count, const
 template <int DT, int G>
 static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *table_class, const Geometry &g,
                     const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps, hipStream_t s) {
-  if (which == 2) {
-    hipLaunchKernelGGL((backward_huge_kernel<DT, G>), dim3(4096), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.hchunks,
-                       b.huge_sorted, b.huge, b.hstart, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride, table_class,
-                       b.mean ? b.inv_len : nullptr, b.cnt);
-  } else if (which == 3) {
-    hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(1024), dim3(256), 0, s, tm, cls, b.huge, b.uniq_key,
-                       b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
-  } else if (which == 0) {
+  // The tile kernel serves rows of at least 4 lanes (64 bytes); narrower rows, whose lane groups would outnumber
+  // what its bookkeeping in LDS is sized for, take the workgroup-per-row kernel, as max pooling does.
+  constexpr bool kTiled = G >= 4;
+  const bool tiled = kTiled && !b.maxp;
+  if (which == kBwdHeavy && tiled) {
+    if constexpr (kTiled)
+      hipLaunchKernelGGL((backward_heavy_kernel<DT, G>), dim3(1024), dim3(kHeavyThreads), 0, s, tm, cls, b.batch, g.sum_dim,
+                         b.hchunks, b.heavy, b.heavy_sub, b.hstart, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride,
+                         table_class, b.mean ? b.inv_len : nullptr, b.cnt);
+  } else if (which == kBwdHeavy) {
     auto kern = b.maxp ? backward_long_kernel<DT, G, kMax>
                 : b.mean ? backward_long_kernel<DT, G, kMean> : backward_long_kernel<DT, G, kSum>;
-    hipLaunchKernelGGL(kern, dim3(8192), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.items, b.uniq_key, b.uniq_tab,
+    hipLaunchKernelGGL(kern, dim3(8192), dim3(256), 0, s, tm, cls, b.batch, g.sum_dim, b.heavy, b.heavy_sub, b.uniq_key, b.uniq_tab,
                        b.run_off, b.loc_u, b.sorted_bag, grad_out, lr, eps, b.ovf, g.ovf_stride, table_class,
-                       b.mean ? b.inv_len : nullptr, b.argpos, b.sorted_within, b.huge, b.wide, b.hstart, partials,
-                       g.partial_stride, b.cnt);
+                       b.mean ? b.inv_len : nullptr, b.argpos, b.sorted_within, b.cnt);
+  } else if (which == kBwdCombine) {
+    if (tiled)
+      hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(2048), dim3(256), 0, s, tm, cls, b.heavy, b.heavy_sub, b.uniq_key,
+                         b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
   } else {
     auto kern = b.maxp ? backward_short_kernel<DT, G, kMax>
                 : b.mean ? backward_short_kernel<DT, G, kMean> : backward_short_kernel<DT, G, kSum>;
@@ -932,9 +960,9 @@ static void bwd_single_one(const TableMeta *tm, const int32_t *tables, int count
   dim3 grid((b.batch + bags_per_block - 1) / bags_per_block, count);
   if (b.maxp)
     hipLaunchKernelGGL((backward_single_max_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim,
-                       b.d_indices, b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.argpos, b.cnt);
+                       b.byp_key, b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.argpos, b.cnt);
   else
-    hipLaunchKernelGGL((backward_single_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.d_indices,
+    hipLaunchKernelGGL((backward_single_kernel<DT, G>), grid, dim3(256), 0, s, tm, tables, b.batch, g.sum_dim, b.byp_key,
                        b.d_offsets, b.loc, grad_out, lr, eps, b.ovf, g.ovf_stride, b.mean ? b.inv_len : nullptr, b.cnt);
 }
 
@@ -980,11 +1008,8 @@ hipError_t launch_backward_single_classes(const TableMeta *tm, const ClassInfo &
   return hipGetLastError();
 }
 
-// which: 0 = rows with kLongRun < lookups <= kHugeRun (workgroup per row; also the bag ranges of the
-// rows with more than kWideRun lookups), 1 = rows with 2..kLongRun lookups (group per row), 2 = rows
-// with more than kHugeRun lookups (gradient tiles), 3 = the combine of those rows' partial sums
-// (after 2 and 0).  A step runs all three and the single-lookup kernel; they touch
-// disjoint rows.
+// A step runs the heavy kernel, the combine, the single-lookup kernel and the short kernel; they
+// touch disjoint rows (the combine after the heavy kernel).
 hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
                                    const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,
                                    hipStream_t s) {

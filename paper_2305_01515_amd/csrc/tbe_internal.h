@@ -9,19 +9,22 @@ constexpr int kWave = 64;                 // CDNA wavefront width
 constexpr uint32_t kNoSet = 0xFFFFFFFFu;  // global set id of rows of a table without cache
 // Backward work classes by the number of lookups a distinct row has in the batch:
 //   1            : updated bag by bag (the gradient is the bag's), flagged in the location word
-//   2..kLongRun  : one lane group per row
-//   ..kHugeRun   : one workgroup per row
-//   above        : bag tiles of the gradient staged in LDS and shared by the table's huge rows
+//   2..kLongRun  : one lane group per row, gradient rows gathered per lookup
+//   above        : "heavy" rows.  The table's gradient slice is streamed through LDS tile by tile, once per
+//                  (chunk of up to heavy_chunk_rows of the table's heavy rows, bag range),
+//                  and every lane group adds up, from LDS, the lookups of its rows that fall into the tile;
+//                  the partial sums of a row, one per bag range, are added up by the combine kernel.
+//                  (Max pooling, whose gradient is masked per lookup, takes these rows one workgroup each.)
 constexpr int kLongRun = 64;
-constexpr int kHugeRun = 1024;
-constexpr int kHugeRanges = 64;           // each huge row's sum is split over at least this many bag ranges
-constexpr int kHugeTargetItems = 2048;    // ... and over more when the batch has few huge rows, so that the
-constexpr int kHugeMaxRanges = 1024;      //     kernel still has about this many work items (at most this many ranges)
-constexpr int kTileBytes = 16384;         // gradient tile in LDS
-#ifndef TBE_WIDE_RUN
-#define TBE_WIDE_RUN 32768
-#endif
-constexpr int kWideRun = TBE_WIDE_RUN;    // huge rows with more lookups: a whole workgroup per (row, bag range)
+constexpr int kHeavyThreads = 1024;       // workgroup of the tile kernel: 1024 / lanes-per-row lane groups
+// rows whose sums a lane group keeps in registers (8 fp16 elements per lane need twice the registers of 4 fp32)
+__host__ __device__ constexpr int heavy_rows_per_group(int dtype) { return dtype == 0 ? 8 : 6; }
+constexpr int kHeavySplit = 2048;          // a heavy row with more lookups is entered into the heavy list in several
+constexpr int kHeavyMaxParts = 64;         // parts (at most this many), each taking every parts-th window of G lookups,
+                                           // so that no lane group has a hot row's lookups all to itself
+constexpr int kHeavyTileBytes = 32768;    // gradient tile in LDS (rows padded by 16 bytes against bank conflicts)
+constexpr int kHeavyTargetItems = 512;    // (chunk, bag range) work items the ranges are chosen for
+constexpr int kHeavyMaxRanges = 128;
 
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
 constexpr uint32_t kWhereParked = 0x40000000u;    // among the victims the batch before parked
@@ -52,9 +55,12 @@ struct TableMeta {
   int32_t lanes;          // lanes per row: 16 bytes of the row per lane
   uint32_t row_bytes;
   char *lines;            // device: cache lines of this table [sets*ways, row_bytes]
+  float *slot_m;          // device: accumulators of the rows in those lines [sets*ways] (while a row is cached its
+                          // accumulator lives here, next to 6 MB of its kind, instead of among those of all rows)
   char *host_w;           // pinned host rows [rows, row_bytes]
   float *host_m;          // host accumulators [rows]: read at create, written at flush
-  float *dev_m;           // device: row-wise Adagrad accumulators of ALL rows of the table [rows]
+  float *dev_m;           // device: row-wise Adagrad accumulators of ALL rows of the table [rows]: current for
+                          // the rows that are not in a cache line (commit moves them in and out with the row)
   // second-level cache (Section 5.3): sets2 = l2_factor * sets, so the second-level sets of the
   // rows of first-level set s are s, s + sets, s + 2 sets, ... and belong to that set alone
   uint32_t sets2;         // 0 = no second level for this table
@@ -69,14 +75,12 @@ struct BatchCounters {
   int32_t n_touched;  // sets with at least one distinct row (+ pseudo sets of cacheless tables)
   int32_t n_ins;
   int32_t n_byp;
-  int32_t n_items;    // rows with kLongRun < lookups <= kHugeRun
+  int32_t n_heavy;    // entries of the heavy list (rows with more than kLongRun lookups, a hot row several times)
   int32_t err;        // 1 = bad offsets, 2 = index out of range, 0 = none
-  int32_t n_huge;     // rows with more than kHugeRun lookups
+  int32_t h_ranges;   // bag ranges the heavy rows' sums are split over in this batch
   int32_t n_mid;      // rows with 2..kLongRun lookups
   unsigned long long hits, evictions, hit_lookups;
-  int32_t n_long;     // rows with more than kLongRun lookups
-  int32_t n_hchunks;  // (table, up to one workgroup's worth of huge rows) chunks
-  int32_t n_wide;     // huge rows with more than kWideRun lookups
+  int32_t n_hchunks;  // (table, up to one workgroup's worth of heavy rows) chunks
   // second level: missed rows found there, victims moved down into it, rows it evicted to the
   // lower tier, victims that found no way and went to the lower tier directly
   int32_t l2_hits, l2_demotions, l2_evictions, l2_bypasses;
@@ -134,14 +138,12 @@ struct BatchBuf {
   char **byp_src;       // [N]   its row in the backing tier
   uint32_t *byp_where;  // [N]   as ins_where
   char *ovf;            // [N * stride] HBM copies of the bypassed rows while their batch trains
-  int32_t *mid_idx;     // [N/2 + 1] rows with 2..kLongRun lookups (any order)
-  int32_t *items;       // [N/kLongRun + 1] rows with kLongRun < lookups <= kHugeRun (any order)
-  int32_t *huge;        // [N/kHugeRun + 1] rows with more lookups (any order)
-  int32_t *huge_sorted; // [N/kHugeRun + 1] positions in `huge`, grouped by table
-  int32_t *wide;        // [N/kHugeRun + 1] positions in `huge` of the rows with more than kWideRun lookups (any order)
-  uint4 *hchunks;       // [N/kHugeRun + T + 1] (table, first position in huge_sorted, count, -)
-  int32_t *hg_count;    // [3*(T+1)] per-table counters of the grouping
-  int32_t *hstart;      // [huge rows * huge_ranges] first sorted position of a huge row in each bag range
+  int32_t *mid_idx;     // [N/2 + 1] rows with 2..kLongRun lookups, in the order of the distinct rows (table order)
+  int32_t *heavy;       // [N/32 + 1] rows with more lookups, same order, one entry per part of a row (heavy_parts)
+  int32_t *heavy_sub;   // [N/32 + 1] per entry: part number | parts << 16
+  uint4 *hchunks;       // [N/kLongRun + T + 1] (table, first position in `heavy`, count, -)
+  int32_t *hg_count;    // [T] heavy rows per table
+  int32_t *hstart;      // [heavy rows * h_ranges] first sorted position of a heavy row in each bag range
   BatchCounters *cnt;   // device
   // host-side description
   const int64_t *d_indices;
@@ -201,6 +203,7 @@ struct Geometry {
   int32_t key_bits;     // bits of the largest sort key
   int32_t within_bits;  // bits left for the position inside the bag in a packed sort payload (0 = never packed)
   int32_t partial_stride;  // floats per partial-sum slot (widest row, padded to whole lanes)
+  int64_t partial_slots;   // slots of the partial-sum buffer (heavy rows x bag ranges of a batch fit in)
   uint32_t ovf_stride;     // bytes per overflow / staging slot (widest row)
   uint32_t total_sets;
   int64_t total_slots;
@@ -260,25 +263,37 @@ hipError_t launch_forward_classes(const TableMeta *tm, const ClassInfo &ci, cons
                                   float *out, hipStream_t s);
 hipError_t launch_backward_single_classes(const TableMeta *tm, const ClassInfo &ci, const Geometry &g, const BatchBuf &b,
                                           const float *grad_out, float lr, float eps, hipStream_t s);
+// which: kBwdHeavy (tile kernel; under max pooling the workgroup-per-row kernel instead), kBwdCombine (sums of the
+// tile kernel's partial sums + update; nothing under max pooling), kBwdShort (rows with 2..kLongRun lookups)
+constexpr int kBwdHeavy = 0, kBwdCombine = 1, kBwdShort = 2;
 hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassInfo &ci, const Geometry &g,
                                    const BatchBuf &b, const float *grad_out, float *partials, float lr, float eps,
                                    hipStream_t s);
 
 // ---- small device helpers ----
 
-// Bags per gradient tile of the huge-row backward: what fits the LDS tile, but few enough
-// Bag ranges of the huge-row backward for a batch with n_hchunks (table, row group) chunks: a
-// function of the batch alone, so the summation order is reproducible.
-__host__ __device__ inline int huge_ranges(int n_hchunks) {
-  const int r = n_hchunks > 0 ? kHugeTargetItems / n_hchunks : kHugeRanges;
-  return r < kHugeRanges ? kHugeRanges : (r > kHugeMaxRanges ? kHugeMaxRanges : r);
+// Bag ranges of the heavy-row backward for a batch with n_hchunks (table, row group) chunks and n_heavy
+// heavy rows: enough ranges for about kHeavyTargetItems work items, no more than the partial-sum buffer
+// (slot_capacity slots of one row each) holds.  A function of the batch alone, so the summation order is
+// reproducible.
+__host__ __device__ inline int heavy_ranges(int n_hchunks, int n_heavy, long long slot_capacity) {
+  if (n_hchunks < 1 || n_heavy < 1) return 1;
+  long long r = (kHeavyTargetItems + n_hchunks - 1) / n_hchunks;
+  if (r > kHeavyMaxRanges) r = kHeavyMaxRanges;
+  if (r > slot_capacity / n_heavy) r = slot_capacity / n_heavy;
+  return r < 1 ? 1 : (int)r;
 }
 
-// that a batch has at least kHugeRanges tiles -- every range then sums a bounded share of a
-// row's lookups, which bounds the length of the fp32 summation chains.
-__host__ __device__ inline int huge_tile_bags(int fit, int B) {
-  const int cap = (B + kHugeRanges - 1) / kHugeRanges;
-  return fit < cap ? fit : (cap < 1 ? 1 : cap);
+// Heavy rows a workgroup of the tile kernel takes at once, and bags per gradient tile, for rows of
+// `lanes` lanes of 16 bytes (4 fp32 or 8 fp16 elements each).
+__host__ __device__ inline int heavy_chunk_rows(int lanes, int dtype) { return kHeavyThreads / lanes * heavy_rows_per_group(dtype); }
+// parts a heavy row of `len` lookups is split into
+__host__ __device__ inline int heavy_parts(int len) {
+  const int p = (len + kHeavySplit - 1) / kHeavySplit;
+  return p < 1 ? 1 : (p > kHeavyMaxParts ? kHeavyMaxParts : p);
+}
+__host__ __device__ inline int heavy_tile_bags(int lanes, int dtype) {
+  return kHeavyTileBytes / (lanes * (dtype == 0 ? 4 : 8) * 4);
 }
 
 // Workgroups are handed to the 8 XCDs (each with an L2 of its own) round robin by their
@@ -302,6 +317,15 @@ __device__ inline void xcd_span(int n, int per_block, int &first, int &end, int 
   const int lo = (int)((int64_t)n * x / kXcds);
   end = (int)((int64_t)n * (x + 1) / kXcds);
   first = lo + (int)(blockIdx.x / kXcds) * per_block;
+  step = nb * per_block;
+}
+
+// the same for a kernel whose workgroups are numbered `id` of `nblocks` (a multiple of kXcds)
+__device__ inline void xcd_span_of(int id, int nblocks, int n, int per_block, int &first, int &end, int &step) {
+  const int x = id % kXcds, nb = nblocks / kXcds;
+  const int lo = (int)((int64_t)n * x / kXcds);
+  end = (int)((int64_t)n * (x + 1) / kXcds);
+  first = lo + (id / kXcds) * per_block;
   step = nb * per_block;
 }
 

@@ -381,7 +381,8 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
                                                      char *const *__restrict__ l2v_src,
                                                      char *const *__restrict__ l2v_dst, char **wb2_dst,
                                                      const char *__restrict__ out2_prev,
-                                                     const uint32_t *__restrict__ rb_of_table, u64 *bytes_d2h) {
+                                                     const uint32_t *__restrict__ rb_of_table,
+                                                     const uint32_t *__restrict__ ins_key, u64 *bytes_d2h) {
   const uint32_t M = (uint32_t)st.max_inserts;  // map codes kWhereParked | (M + i): rows staged in out2
   const int n_prev = (prev_cnt && prev_cnt->err == 0) ? prev_cnt->n_byp : 0;
   const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
@@ -439,6 +440,15 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
                       : (out2_prev && ix >= M)  ? out2_prev + (size_t)(ix - M) * st.stride
                                                 : st.out[ppar] + (size_t)ix * st.stride;
     char *park = st.out[par] + (size_t)i * st.stride;
+    // The accumulators move with the rows: the victim's back among those of all rows, the new row's to the
+    // slot (a row is in a cache line or among the others, never both, so the two differ).  Both are requested
+    // before the row is copied, so that they travel beside it.
+    float *sm = m.slot_m + (slot - m.slot_base);
+    float m_victim = 0.f, m_fresh = 0.f;
+    if (lig == 0) {
+      m_victim = *sm;
+      m_fresh = m.dev_m[row_of_key(m, ins_key[i])];
+    }
     for (uint32_t c = lig * 16; c < rb; c += kMoveLanes * 16) {
       const uint4 fresh = *(const uint4 *)(src + c);
       if (old >= 0) *(uint4 *)(park + c) = *(const uint4 *)(line + c);
@@ -448,6 +458,8 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
       st.wb_dst[i] = old < 0 ? nullptr : ins_dst ? ins_dst[i] : m.host_w + (size_t)old * rb;
       st.wb_rb[i] = rb;
       if (wb2_dst) wb2_dst[i] = l2v_src[i] ? l2v_dst[i] : nullptr;
+      if (old >= 0) m.dev_m[old] = m_victim;
+      *sm = m_fresh;
     }
   }
   for (int j = group; j < n_byp; j += n_groups) {  // late bypassed rows
@@ -529,11 +541,11 @@ hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf 
                      prev ? prev->byp_src : nullptr, prev ? prev->byp_tab : nullptr, prev ? prev->ovf : nullptr,
                      prev ? prev_mode : kPrevKeep, b.k, l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr,
                      l2.on ? b.l2v_dst : nullptr, l2.on ? l2.wb2_dst : nullptr, l2.out2[(b.k & 1) ^ 1], rb_of_table,
-                     bytes_d2h);
+                     b.ins_key, bytes_d2h);
   return hipGetLastError();
 }
 
-// flush: every valid line goes to the backing tier (the accumulators are copied by the host code)
+// flush: every valid line goes to the backing tier, its accumulator to those of all rows (which the host code copies)
 __global__ __launch_bounds__(256) void flush_kernel(const TableMeta *__restrict__ tm, int T, int64_t total_slots,
                                                     const int32_t *__restrict__ tags, u64 *bytes_d2h) {
   const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
@@ -550,7 +562,10 @@ __global__ __launch_bounds__(256) void flush_kernel(const TableMeta *__restrict_
     }
     const TableMeta &m = tm[lo];
     copy_row_to_host(m.host_w + (size_t)row * m.row_bytes, m.lines + (size_t)(slot - m.slot_base) * m.row_bytes, m.row_bytes, lig);
-    if (lig == 0) out_b += m.row_bytes;
+    if (lig == 0) {
+      out_b += m.row_bytes;
+      m.dev_m[row] = m.slot_m[slot - m.slot_base];  // the caller copies dev_m to the host; the line stays valid
+    }
   }
   for (int d = 32; d >= 1; d >>= 1) out_b += __shfl_xor(out_b, d);
   if ((threadIdx.x & 63) == 0 && out_b) atomicAdd(bytes_d2h, out_b);

@@ -58,10 +58,12 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
   }
 }
 
-__global__ void reset_counters_kernel(BatchCounters *cnt, int within_bits) {
+__global__ void reset_counters_kernel(BatchCounters *cnt, int within_bits, int32_t *heavy_per_table, int T) {
+  for (int t = threadIdx.x; t < T; t += blockDim.x) heavy_per_table[t] = 0;
   if (threadIdx.x == 0) {
-    cnt->n_uniq = cnt->n_touched = cnt->n_ins = cnt->n_byp = cnt->n_items = cnt->err = 0;
-    cnt->n_huge = cnt->n_mid = cnt->n_long = cnt->n_hchunks = cnt->n_wide = 0;
+    cnt->n_uniq = cnt->n_touched = cnt->n_ins = cnt->n_byp = cnt->n_heavy = cnt->err = 0;
+    cnt->n_mid = cnt->n_hchunks = 0;
+    cnt->h_ranges = 1;
     cnt->hits = cnt->evictions = cnt->hit_lookups = 0;
     cnt->l2_hits = cnt->l2_demotions = cnt->l2_evictions = cnt->l2_bypasses = 0;
     cnt->packed = within_bits > 0 ? 1 : 0;
@@ -70,7 +72,7 @@ __global__ void reset_counters_kernel(BatchCounters *cnt, int within_bits) {
 
 hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf &b, uint32_t *keys, uint32_t *vals,
                          hipStream_t s) {
-  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, s, b.cnt, g.within_bits);
+  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, s, b.cnt, g.within_bits, b.hg_count, g.T);
   const int64_t nb = (int64_t)g.T * b.batch;
   if (g.within_bits > 0 && nb > 0)
     hipLaunchKernelGGL(baglen_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, nb, b.d_offsets, g.within_bits,
