@@ -9,7 +9,7 @@
  *               LRU victims, write the victims back and fetch the missed rows
  *               (paper Section 5.5: tag/state lookup, cache algorithm, data
  *               lookup/update, data movement; Section 5.7: prefetch stage "4a");
- *   forward   : pooled (sum, optionally mean) embedding-bag lookup (Section 2.1.1);
+ *   forward   : pooled (sum, optionally mean or max) embedding-bag lookup (Section 2.1.1);
  *   backward  : per-row gradient aggregation + row-wise Adagrad applied where the row
  *               lives (Section 2.1.2 Eq. 2, Section 5.9);
  *   flush     : write every cached row back to the backing tier (write-back rule of
@@ -43,12 +43,15 @@
  * When the backing tier is current: a row's host copy is stale while the row is cached
  * (write-back cache), while its batch trains if it was bypassed, and while an evicted
  * copy is still on its way; the row-wise accumulators live in HBM for all rows (the paper
- * keeps optimizer parameters there, Section 5.6.1) and host_state is only read by
- * tbe_create and written by tbe_flush.  After tbe_flush both host arrays are current.
+ * keeps optimizer parameters there, Section 5.6.1; 4 bytes per row of every table, beside the
+ * cache lines) and host_state is only read by tbe_create and written by tbe_flush.  After
+ * tbe_flush both host arrays are current.
  *
  * Optional, each selected by one call before the first batch: LFU instead of LRU
- * (tbe_set_policy), mean instead of sum pooling (tbe_set_pooling), a second-level cache in
- * pinned host memory between the two tiers (tbe_enable_second_level).
+ * (tbe_set_policy), mean or max instead of sum pooling (tbe_set_pooling), a second-level cache in
+ * pinned host memory between the two tiers (tbe_enable_second_level), initial values made up on
+ * first read instead of stored (tbe_enable_deferred_init), batches accepted several ahead of
+ * training (tbe_set_prefetch_depth).
  */
 #ifndef TBE_H
 #define TBE_H
@@ -301,10 +304,10 @@ int tbe_backward_update(tbe_handle h, const float *d_grad_out, float lr, float e
  * runs on holds one such array until the process ends).  The call allocates nothing: no hipMalloc,
  * no hipFree, no event or stream creation; it only enqueues kernels and records / waits for events
  * that tbe_create made.
- *   - TBE_ELIMIT when the handle's worst case does not fit: 4 bytes x the widest row's elements
- *     (rounded up to whole 16-byte lanes, a power of two of them) x max(64 * (max_lookups / 1024 + 1), 2048 * 256 / the
- *     narrowest row's lanes) above TBE_STATIC_SCRATCH_BYTES -- e.g. dim 128 and max_lookups up to about a
- *     million fit; the error text gives the figure;
+ *   - TBE_ELIMIT when the handle's worst case does not fit: 4 bytes x the widest row's elements (rounded
+ *     up to whole 16-byte lanes, a power of two of them) x max(4 * (max_lookups / 65 + 1), 32768) partial
+ *     sums above TBE_STATIC_SCRATCH_BYTES -- e.g. dim 128 and max_lookups up to about a million fit; the
+ *     error text gives the figure;
  *   - TBE_EORDER while stage timing is on (tbe_set_profiling creates events per call), when the
  *     current GPU is not the one the handle was created on, or without a forwarded batch;
  *   - the array keeps the last call's contents; nothing in it has to start at zero (every partial sum

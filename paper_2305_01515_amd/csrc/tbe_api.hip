@@ -225,8 +225,9 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.heavy, 4 * (N / 32 + 1)));  // rows: N / 65 at most; extra parts: N / kHeavySplit at most
   HIP_TRY(h, h->mem.get(&b.heavy_sub, 4 * (N / 32 + 1)));
   HIP_TRY(h, h->mem.get(&b.hchunks, 16 * (N / 32 + (size_t)h->g.T + 1)));
-  HIP_TRY(h, h->mem.get(&b.hg_count, 4 * ((size_t)h->g.T + 1)));
-  HIP_TRY(h, hipMemset(b.hg_count, 0, 4 * ((size_t)h->g.T + 1)));
+  HIP_TRY(h, h->mem.get(&b.hg_count, 4 * 2 * ((size_t)h->g.T + 1)));
+  HIP_TRY(h, hipMemset(b.hg_count, 0, 4 * 2 * ((size_t)h->g.T + 1)));
+  HIP_TRY(h, h->mem.get(&b.hperm, 4 * (N / 32 + 1)));
   HIP_TRY(h, h->mem.get(&b.hstart, 4 * (h->huge_slots + 1)));
   HIP_TRY(h, h->mem.get(&b.cnt, sizeof(BatchCounters)));
   HIP_TRY(h, hipMemset(b.cnt, 0, sizeof(BatchCounters)));

@@ -284,7 +284,8 @@ __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__res
 // this batch.  One workgroup; tables are taken 256 at a time.
 __global__ __launch_bounds__(256) void heavy_group_kernel(const TableMeta *__restrict__ tm, int T,
                                                           const int32_t *__restrict__ heavy_per_table,
-                                                          uint4 *hchunks, long long slot_capacity, BatchCounters *cnt) {
+                                                          int32_t *first_of_table, uint4 *hchunks,
+                                                          long long slot_capacity, BatchCounters *cnt) {
   __shared__ int s_rows[4], s_chunks[4];
   __shared__ int s_carry[2];
   if (cnt->err) return;
@@ -305,6 +306,7 @@ __global__ __launch_bounds__(256) void heavy_group_kernel(const TableMeta *__res
     __syncthreads();
     int row0 = s_carry[0] + ir - rows, chunk0 = s_carry[1] + ic - chunks;
     for (int w = 0; w < wave; w++) { row0 += s_rows[w]; chunk0 += s_chunks[w]; }
+    if (t < T) first_of_table[t] = row0;
     for (int c = 0; c < chunks; c++)
       hchunks[chunk0 + c] = make_uint4((uint32_t)t, (uint32_t)(row0 + c * per), (uint32_t)min(per, rows - c * per), 0u);
     __syncthreads();
@@ -314,6 +316,53 @@ __global__ __launch_bounds__(256) void heavy_group_kernel(const TableMeta *__res
   if (tid == 0) {
     cnt->n_hchunks = s_carry[1];
     cnt->h_ranges = heavy_ranges(s_carry[1], cnt->n_heavy, slot_capacity);
+  }
+}
+
+// Order of a table's heavy-list entries for the tile kernel: by lookups per entry, descending, in classes of
+// powers of two (entries of a class keep their order, so the result is a function of the batch alone).  The
+// tile kernel deals the entries round its lane groups in this order, so the groups that share a wavefront --
+// which runs as long as its busiest group -- get rows of like length.  One wavefront per table.
+__global__ __launch_bounds__(64) void heavy_order_kernel(const int32_t *__restrict__ heavy_per_table,
+                                                         const int32_t *__restrict__ first_of_table,
+                                                         const int32_t *__restrict__ heavy,
+                                                         const int32_t *__restrict__ heavy_sub,
+                                                         const int32_t *__restrict__ run_off, int32_t *hperm,
+                                                         const BatchCounters *cnt) {
+  __shared__ int s_base[32];
+  if (cnt->err) return;
+  const int t = blockIdx.x, lane = threadIdx.x;
+  const int n = heavy_per_table[t], first = first_of_table[t];
+  if (n == 0) return;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  auto klass = [&](int h) {  // 31 - floor(log2(lookups per entry)): longer entries first
+    const int u = heavy[h];
+    const int len = (run_off[u + 1] - run_off[u]) / (heavy_sub[h] >> 16);
+    return __clz(len < 1 ? 1 : len);
+  };
+  if (lane < 32) s_base[lane] = 0;
+  __syncthreads();
+  for (int i0 = 0; i0 < n; i0 += 64)
+    if (i0 + lane < n) atomicAdd(&s_base[klass(first + i0 + lane)], 1);
+  __syncthreads();
+  if (lane == 0) {
+    int at = 0;
+    for (int k = 0; k < 32; k++) { const int c = s_base[k]; s_base[k] = at; at += c; }
+  }
+  __syncthreads();
+  for (int i0 = 0; i0 < n; i0 += 64) {
+    const bool valid = i0 + lane < n;
+    const int k = valid ? klass(first + i0 + lane) : -1;
+    uint64_t todo = __ballot(valid);
+    while (todo) {  // one class at a time, its entries in order
+      const int kk = __shfl(k, __ffsll((unsigned long long)todo) - 1, 64);
+      const uint64_t same = __ballot(k == kk);
+      if (k == kk) hperm[first + s_base[kk] + __popcll(same & lt_mask)] = first + i0 + lane;
+      __syncthreads();
+      if (lane == 0) s_base[kk] += __popcll(same);
+      __syncthreads();
+      todo &= ~same;
+    }
   }
 }
 
@@ -696,8 +745,10 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   hipLaunchKernelGGL(worklist_emit_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, b.uniq_tab, ss.wl, b.mid_idx,
                      b.heavy, b.heavy_sub, b.hg_count, b.cnt);
   if (!b.maxp) {  // the tile kernel's chunks and range starts (max pooling takes heavy rows a workgroup each)
-    hipLaunchKernelGGL(heavy_group_kernel, dim3(1), dim3(256), 0, s, tm, g.T, b.hg_count, b.hchunks,
+    hipLaunchKernelGGL(heavy_group_kernel, dim3(1), dim3(256), 0, s, tm, g.T, b.hg_count, b.hg_count + g.T + 1, b.hchunks,
                        (long long)g.partial_slots, b.cnt);
+    hipLaunchKernelGGL(heavy_order_kernel, dim3(g.T), dim3(64), 0, s, b.hg_count, b.hg_count + g.T + 1, b.heavy,
+                       b.heavy_sub, b.run_off, b.hperm, b.cnt);
     hipLaunchKernelGGL(heavy_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.heavy, b.uniq_tab, b.run_off,
                        b.sorted_bag, b.hstart, b.cnt);
   }

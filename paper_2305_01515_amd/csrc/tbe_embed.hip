@@ -684,8 +684,9 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
 // the tile are a prefix of what is left of the window.
 struct HeavySlot {
   int bag;   // this lane's bag id of the window (0x7FFFFFFF outside the row's lookups of this range)
-  int next;  // ... of the entry's next window, requested when this one was started
+  int next;  // ... of the entry's next window, requested at the end of the tile in which the one before was taken up
   int used;  // ids of the window consumed so far (same in all lanes of the group)
+  int need;  // 1 = `next` has been taken up and not been requested again yet
 };
 
 // this lane's bag id of the window that starts at sorted position `at`, for a row whose lookups of the
@@ -697,9 +698,10 @@ __device__ inline int heavy_window(const int32_t *__restrict__ sorted_bag, int a
 
 // win: in LDS, (sorted position of the window after `next`, end of the row's lookups inside this bag range,
 // distance between the entry's windows) -- touched once per G lookups, so they need not sit in registers
+// zero_row: index of a staged row of zeros, read in place of the lookups a quad does not have
 template <int DT, int G>
 __device__ inline void heavy_consume(HeavySlot &sl, int4 *win, float (&g)[Elems<DT>::n], const float *tile,
-                                     int row_stride, int base_bag, int end_bag,
+                                     int row_stride, int zero_row, int base_bag, int end_bag,
                                      const int32_t *__restrict__ sorted_bag, int lig, int gshift) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int Q = EPL == 8 ? 2 : 4;  // gradient rows read from LDS before they are added
@@ -713,25 +715,38 @@ __device__ inline void heavy_consume(HeavySlot &sl, int4 *win, float (&g)[Elems<
 #pragma unroll
       for (int x = 0; x < Q; x++) {
         const int bq = __shfl(sl.bag, (sl.used + q + x) & (G - 1), G);
-        const float *src = tile + (q + x < n_ok ? bq - base_bag : 0) * row_stride + lig * EPL;
+        const float *src = tile + (q + x < n_ok ? bq - base_bag : zero_row) * row_stride + lig * EPL;
 #pragma unroll
         for (int e = 0; e < EPL / 4; e++) v[x][e] = *(const float4 *)(src + 4 * e);
       }
 #pragma unroll
       for (int x = 0; x < Q; x++)
-        if (q + x < n_ok) {
 #pragma unroll
-          for (int e = 0; e < EPL / 4; e++) {
-            g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
-          }
+        for (int e = 0; e < EPL / 4; e++) {
+          g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
         }
     }
     sl.used += n_ok;
     if (sl.used < G) break;  // what is left of the window lies behind this tile
-    int4 w = *win;           // window used up: on to the one requested before, and request the one after it
-    sl.used = 0;
-    sl.bag = sl.next;
+    sl.used = 0;             // window used up
+    if (!sl.need) {          // on to the one requested before; the one after it is requested when this tile is done,
+      sl.bag = sl.next;      // so that no wave waits for memory between two rows (heavy_refill)
+      sl.need = 1;
+    } else {                 // a second window inside one tile (a hot row's part): fetched on the spot
+      int4 w = *win;
+      sl.bag = heavy_window(sorted_bag, w.x, 0, w.y, lig);
+      w.x += w.z;
+      if (lig == 0) *win = w;
+    }
+  }
+}
+
+// after a tile: request the next window of every row whose spare one has been taken up
+__device__ inline void heavy_refill(HeavySlot &sl, int4 *win, const int32_t *__restrict__ sorted_bag, int lig) {
+  if (sl.need) {
+    int4 w = *win;
     sl.next = heavy_window(sorted_bag, w.x, 0, w.y, lig);
+    sl.need = 0;
     w.x += w.z;
     if (lig == 0) *win = w;
   }
@@ -742,6 +757,7 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
                                                                        int sum_dim, const uint4 *__restrict__ hchunks,
                                                                        const int32_t *__restrict__ heavy,
                                                                        const int32_t *__restrict__ heavy_sub,
+                                                                       const int32_t *__restrict__ hperm,
                                                                        const int32_t *__restrict__ hstart,
                                                                        const int32_t *__restrict__ run_off,
                                                                        const int32_t *__restrict__ sorted_bag,
@@ -758,9 +774,11 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
   constexpr int NG = kHeavyThreads / G;                   // lane groups
   constexpr int RPG = heavy_rows_per_group(DT);
   constexpr int PER = kHeavyTileBytes / 16 / kHeavyThreads;  // float4 per thread and tile
-  __shared__ float tile[TB * STRIDE];
+  constexpr int PH = PER < 3 ? PER : 3;                      // ... of which this many are requested at a time
+  __shared__ float tile[(TB + 1) * STRIDE];  // row TB stays zero
   __shared__ int4 s_win[RPG][NG];  // per (row of a group, group): see heavy_consume
   if (cnt->err) return;
+  for (int i = threadIdx.x; i < STRIDE; i += kHeavyThreads) tile[TB * STRIDE + i] = 0.f;
   const int R = cnt->h_ranges;
   const int n_work = cnt->n_hchunks * R;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
@@ -782,9 +800,9 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
     float g[RPG][EPL];
 #pragma unroll
     for (int s = 0; s < RPG; s++) {
-      const int j = s * NG + grp;  // the chunk's row j: rows are dealt round the groups
+      const int j = s * NG + grp;  // the chunk's j-th entry in the table's order by length: dealt round the groups
       const bool has = j < (int)ch.z;
-      const int h = (int)ch.y + (has ? j : 0);
+      const int h = hperm[(int)ch.y + (has ? j : 0)];
       const int u = heavy[h];
       // The row's lookups of this bag range are the sorted positions [lo, hi).  The row is read in windows of G
       // positions counted from its first lookup; this entry is part `part` of `parts` and takes the windows
@@ -800,47 +818,52 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
       sl[s].used = (w == w0 && lo > at) ? lo - at : 0;
       sl[s].bag = heavy_window(sorted_bag, at, lo, hi, lig);
       sl[s].next = heavy_window(sorted_bag, at + stride, lo, hi, lig);
+      sl[s].need = 0;
 #pragma unroll
       for (int e = 0; e < EPL; e++) g[s][e] = 0.f;
     }
-    // this thread's share of a tile: float4 number k * threads + tid of the tile's TB x ROWF floats
-    auto load_tile = [&](int tl, float4 (&v)[PER]) {
-      const int b_first = tl * TB, n_f = (min(B, b_first + TB) - b_first) * ROWF;
-#pragma unroll
-      for (int k = 0; k < PER; k++) {
-        const int x = (k * kHeavyThreads + threadIdx.x) * 4;
-        const int bl = x / ROWF, c = x % ROWF;
-        v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (x < n_f && c < dim) {
-          v[k] = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + col + c);
-          if (inv_len) {  // mean pooling: the staged gradient row already carries the bag's 1/L
-            const float sc = inv_len[bag0 + b_first + bl];
-            v[k].x *= sc; v[k].y *= sc; v[k].z *= sc; v[k].w *= sc;
-          }
-        }
-      }
-    };
-    float4 pre[PER];
-    if (tile_lo < tile_hi) load_tile(tile_lo, pre);
     for (int tl = tile_lo; tl < tile_hi; tl++) {
+      // stage the tile: this thread's share is float4 number k * threads + tid of the tile's TB x ROWF floats,
+      // all of them requested before the first is stored
+      const int b_first = tl * TB, n_f = (min(B, b_first + TB) - b_first) * ROWF;
       __syncthreads();  // the previous tile is no longer read
 #pragma unroll
-      for (int k = 0; k < PER; k++) {
-        const int x = (k * kHeavyThreads + threadIdx.x) * 4;
-        *(float4 *)(tile + (x / ROWF) * STRIDE + x % ROWF) = pre[k];
+      for (int k0 = 0; k0 < PER; k0 += PH) {  // PH requests in flight, then their stores
+        float4 v[PH];
+#pragma unroll
+        for (int k = 0; k < PH; k++) {
+          const int x = ((k0 + k) * kHeavyThreads + threadIdx.x) * 4;
+          const int bl = x / ROWF, c = x % ROWF;
+          v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (k0 + k < PER && x < n_f && c < dim) {
+            v[k] = *(const float4 *)(grad_out + (size_t)(b_first + bl) * sum_dim + col + c);
+            if (inv_len) {  // mean pooling: the staged gradient row already carries the bag's 1/L
+              const float sc = inv_len[bag0 + b_first + bl];
+              v[k].x *= sc; v[k].y *= sc; v[k].z *= sc; v[k].w *= sc;
+            }
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < PH; k++) {
+          const int x = ((k0 + k) * kHeavyThreads + threadIdx.x) * 4;
+          if (k0 + k < PER) *(float4 *)(tile + (x / ROWF) * STRIDE + x % ROWF) = v[k];
+        }
       }
       __syncthreads();
-      if (tl + 1 < tile_hi) load_tile(tl + 1, pre);  // in flight while this tile is consumed
-      const int base_bag = bag0 + tl * TB, end_bag = bag0 + min(B, (tl + 1) * TB);
+      const int base_bag = bag0 + b_first, end_bag = bag0 + min(B, b_first + TB);
 #pragma unroll
       for (int s = 0; s < RPG; s++)
-        heavy_consume<DT, G>(sl[s], &s_win[s][grp], g[s], tile, STRIDE, base_bag, end_bag, sorted_bag, lig, gshift);
+        heavy_consume<DT, G>(sl[s], &s_win[s][grp], g[s], tile, STRIDE, TB, base_bag, end_bag, sorted_bag, lig, gshift);
+      // the rows' next windows are requested behind the tile's work, all together (a request in front of
+      // the work would make the first wait for a window hold up for the others as well)
+#pragma unroll
+      for (int s = 0; s < RPG; s++) heavy_refill(sl[s], &s_win[s][grp], sorted_bag, lig);
     }
 #pragma unroll
     for (int s = 0; s < RPG; s++) {
       const int j = s * NG + grp;
       if (j < (int)ch.z) {
-        float *p = partials + ((size_t)((int)ch.y + j) * R + range) * pstride + lig * EPL;
+        float *p = partials + ((size_t)hperm[(int)ch.y + j] * R + range) * pstride + lig * EPL;
 #pragma unroll
         for (int e = 0; e < EPL; e += 4) *(float4 *)(p + e) = make_float4(g[s][e], g[s][e + 1], g[s][e + 2], g[s][e + 3]);
       }
@@ -848,9 +871,9 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
   }
 }
 
-// Heavy rows: add the partial sums, then update the row.  One workgroup per row: its 256/G
-// groups each add a contiguous share of the ranges in range order, the shares are added in
-// group order through LDS (a fixed order, so the result is reproducible).
+// Heavy rows: add the partial sums, then update the row.  One lane group per row; the sums of a row's
+// parts and bag ranges lie one behind the other and are added in that order (a fixed order, so the result
+// is reproducible), four loads in flight.
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int cls,
                                                                const int32_t *__restrict__ heavy,
@@ -865,44 +888,40 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
                                                                const BatchCounters *cnt) {
   constexpr int EPL = Elems<DT>::n;
   constexpr int NG = 256 / G;
-  __shared__ float part[NG][G * EPL + 1];
   if (cnt->err) return;
   const int n_heavy = cnt->n_heavy;
   const int R = cnt->h_ranges;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
   int first, end, step;
-  xcd_span(n_heavy, 1, first, end, step);  // the list is in table order
-  for (int h = first; h < end; h += step) {
+  xcd_span(n_heavy, NG, first, end, step);  // the list is in table order
+  for (int h = first + grp; h < end; h += step) {
     const int sub = heavy_sub[h];
     if (sub & 0xFFFF) continue;  // the entries of a row's parts follow its first one: their sums are added here
-    const int n_sums = (sub >> 16) * R, per = (n_sums + NG - 1) / NG;
+    const int n_sums = (sub >> 16) * R;  // (part, range) pairs in order: slot (h + part) * R + range = h * R + r
     const int u = heavy[h];
     const int t = uniq_tab[u];
-    if (table_class[t] != cls) continue;  // uniform over the block
+    if (table_class[t] != cls) continue;
     const TableMeta &m = tm[t];
     const bool active = lig * EPL < m.dim;
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    const int r1 = min(n_sums, (grp + 1) * per);
-    for (int r = grp * per; r < r1; r++) {  // (part, range) pairs in order: slot (h + part) * R + range = h * R + r
-      const float *p = partials + ((size_t)h * R + r) * pstride + lig * EPL;
+    const float *p0 = partials + (size_t)h * R * pstride + lig * EPL;
+    for (int r = 0; r < n_sums; r += 4) {
+      float4 v[4][EPL / 4];
 #pragma unroll
-      for (int e = 0; e < EPL; e++) g[e] += p[e];
+      for (int x = 0; x < 4; x++)
+#pragma unroll
+        for (int e = 0; e < EPL / 4; e++)
+          v[x][e] = r + x < n_sums ? *(const float4 *)(p0 + (size_t)(r + x) * pstride + 4 * e) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int x = 0; x < 4; x++)
+#pragma unroll
+        for (int e = 0; e < EPL / 4; e++) {
+          g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
+        }
     }
-    __syncthreads();
-#pragma unroll
-    for (int e = 0; e < EPL; e++) part[grp][lig * EPL + e] = g[e];
-    __syncthreads();
-    if (grp == 0) {
-#pragma unroll
-      for (int e = 0; e < EPL; e++) {
-        float s = 0.f;
-        for (int q = 0; q < NG; q++) s += part[q][lig * EPL + e];
-        g[e] = s;
-      }
-      update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
-    }
+    update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
   }
 }
 
@@ -932,7 +951,7 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
   if (which == kBwdHeavy && tiled) {
     if constexpr (kTiled)
       hipLaunchKernelGGL((backward_heavy_kernel<DT, G>), dim3(1024), dim3(kHeavyThreads), 0, s, tm, cls, b.batch, g.sum_dim,
-                         b.hchunks, b.heavy, b.heavy_sub, b.hstart, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride,
+                         b.hchunks, b.heavy, b.heavy_sub, b.hperm, b.hstart, b.run_off, b.sorted_bag, grad_out, partials, g.partial_stride,
                          table_class, b.mean ? b.inv_len : nullptr, b.cnt);
   } else if (which == kBwdHeavy) {
     auto kern = b.maxp ? backward_long_kernel<DT, G, kMax>

@@ -22,8 +22,20 @@ __host__ __device__ constexpr int heavy_rows_per_group(int dtype) { return dtype
 constexpr int kHeavySplit = 2048;          // a heavy row with more lookups is entered into the heavy list in several
 constexpr int kHeavyMaxParts = 64;         // parts (at most this many), each taking every parts-th window of G lookups,
                                            // so that no lane group has a hot row's lookups all to itself
-constexpr int kHeavyTileBytes = 32768;    // gradient tile in LDS (rows padded by 16 bytes against bank conflicts)
-constexpr int kHeavyTargetItems = 512;    // (chunk, bag range) work items the ranges are chosen for
+// Gradient tile in LDS (wide rows padded by 16 bytes against bank conflicts).  A big tile matters: the lane groups
+// of a wavefront run in lockstep, each over its own row's lookups inside the tile, and the more lookups a tile
+// holds per row the less their counts differ (benchmark workload, tile kernel: 32 KB 0.145 ms, 64 KB 0.125, 96 KB 0.110).
+#ifndef TBE_HEAVY_TILE_BYTES
+#define TBE_HEAVY_TILE_BYTES 98304
+#endif
+constexpr int kHeavyTileBytes = TBE_HEAVY_TILE_BYTES;    // gradient tile in LDS (rows padded by 16 bytes against bank conflicts)
+// (chunk, bag range) work items the ranges are chosen for: one workgroup of 1024 threads per CU.  Measured on
+// the benchmark workload (32 chunks; tile kernel + combine, ms): 256 items 0.110 + 0.024, 512 items 0.124 + 0.039,
+// 1024 items 0.148 + 0.079 -- more ranges mean more partial sums to write and to add up.
+#ifndef TBE_HEAVY_TARGET_ITEMS
+#define TBE_HEAVY_TARGET_ITEMS 256
+#endif
+constexpr int kHeavyTargetItems = TBE_HEAVY_TARGET_ITEMS;    // (chunk, bag range) work items the ranges are chosen for
 constexpr int kHeavyMaxRanges = 128;
 
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
@@ -142,7 +154,9 @@ struct BatchBuf {
   int32_t *heavy;       // [N/32 + 1] rows with more lookups, same order, one entry per part of a row (heavy_parts)
   int32_t *heavy_sub;   // [N/32 + 1] per entry: part number | parts << 16
   uint4 *hchunks;       // [N/kLongRun + T + 1] (table, first position in `heavy`, count, -)
-  int32_t *hg_count;    // [T] heavy rows per table
+  int32_t *hg_count;    // [2 * (T + 1)] heavy-list entries per table, then the position of each table's first entry
+  int32_t *hperm;       // [N/32 + 1] the heavy list's positions, every table's entries ordered by lookups per entry
+                        //     (descending, by power of two): lane groups that share a wavefront get rows of like length
   int32_t *hstart;      // [heavy rows * h_ranges] first sorted position of a heavy row in each bag range
   BatchCounters *cnt;   // device
   // host-side description
