@@ -176,9 +176,18 @@ __global__ void stream_pin_kernel() {}
 
 // Running totals of a batch's counters: tot (hits, evictions, lookups that hit), t64 ([0] distinct
 // rows, [1] inserts, [2] bypasses) and, with a second level, l2 (its four counters).
-__global__ void add_totals_kernel(const BatchCounters *c, BatchCounters *tot, unsigned long long *t64,
-                                  unsigned long long *l2) {
-  if (threadIdx.x != 0 || c->err != 0) return;
+// Also completes the batch's own counters: evictions and lookups that hit from the per-wavefront sums of the
+// status pass, hits as what is left of the distinct rows.  One wavefront.
+__global__ void add_totals_kernel(BatchCounters *c, BatchCounters *tot, unsigned long long *t64,
+                                  unsigned long long *l2, const unsigned long long *tally, int tally_waves) {
+  if (c->err != 0) return;
+  unsigned long long e = 0, l = 0;
+  for (int w = threadIdx.x; w < tally_waves; w += 64) { e += tally[2 * w]; l += tally[2 * w + 1]; }
+  for (int d = 32; d >= 1; d >>= 1) { e += __shfl_xor(e, d); l += __shfl_xor(l, d); }
+  if (threadIdx.x != 0) return;
+  c->hits = (unsigned long long)(c->n_uniq - c->n_ins - c->n_byp);
+  c->evictions = e;
+  c->hit_lookups = l;
   tot->hits += c->hits;
   tot->evictions += c->evictions;
   tot->hit_lookups += c->hit_lookups;
@@ -199,7 +208,6 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.sorted_bag, 4 * N));
   HIP_TRY(h, h->mem.get(&b.bag_of_pos, 4 * N));
   HIP_TRY(h, h->mem.get(&b.inv_len, 4 * (size_t)h->g.T * (size_t)h->max_batch));
-  HIP_TRY(h, h->mem.get(&b.uid_sorted, 4 * N));
   HIP_TRY(h, h->mem.get(&b.uniq_key, 4 * N));
   HIP_TRY(h, h->mem.get(&b.run_off, 4 * (N + 1)));
   HIP_TRY(h, h->mem.get(&b.uniq_sid, 4 * N));
@@ -316,7 +324,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     const BatchBuf *pp = (prev && prev->parks_prev && prev->prev_bi >= 0) ? &h->buf[prev->prev_bi] : nullptr;
     HIP_TRY(h, launch_classify_mark(h->d_tm, pp, prev, b, h->st, h->l2, h->d_bytes + 5, h->as));
     hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total, h->d_bytes + 2,
-                       h->l2.on ? h->d_l2tot : nullptr);
+                       h->l2.on ? h->d_l2tot : nullptr, h->ss.tally, n > 0 ? h->ss.tally_waves : 0);
     HIP_TRY(h, hipGetLastError());
   }
   if (h->ls != h->as) {
@@ -565,6 +573,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     CREATE_TRY(hipMemset(st.wb_n, 0, 16));
     CREATE_TRY(h->mem.get(&st.where, 4 * (size_t)key));
     CREATE_TRY(hipMemset(st.where, 0, 4 * (size_t)key));
+    CREATE_TRY(h->mem.get(&h->ss.loc_of_key, 4 * (size_t)key));
     CREATE_TRY(h->mem.get(&h->d_rb, 4 * (size_t)num_tables));
     CREATE_TRY(hipMemcpy(h->d_rb, rb.data(), 4 * (size_t)num_tables, hipMemcpyHostToDevice));
   }
@@ -574,7 +583,8 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     h->static_partials = (float *)p;
   }
   CREATE_TRY(h->mem.get(&h->ss.hist, 4 * (256 * 1024 + 256)));
-  CREATE_TRY(h->mem.get(&h->ss.blk, 8 * 1024));
+  CREATE_TRY(h->mem.get(&h->ss.blk, 8 * (8192 + 1)));
+  CREATE_TRY(h->mem.get(&h->ss.tally, 8 * 2 * 8192));
   CREATE_TRY(h->mem.get(&h->ss.wl, 4 * 4 * (size_t)kWorklistBlocks));
   CREATE_TRY(h->mem.get(&h->d_total, sizeof(BatchCounters)));
   CREATE_TRY(hipMemset(h->d_total, 0, sizeof(BatchCounters)));

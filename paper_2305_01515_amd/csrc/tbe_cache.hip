@@ -8,14 +8,21 @@ namespace tbe {
 // --------------------------------------------------------------------------------------
 // Generic flag -> exclusive prefix -> emit skeleton over n elements (n may live on the
 // device).  Two 32-bit counters are scanned at once, packed into one 64-bit word.
-//   count kernel : block sums of op.flag(i) over the block's contiguous chunk
-//   block scan   : exclusive scan of the block sums (single block), total at [nblocks]
+//   count kernel : sum of op.flag(i) over the contiguous chunk of every wavefront, and per workgroup
 //   emit kernel  : op.emit(i, exclusive prefix, flag) for every element, in order
+// The unit is the wavefront: each one walks a chunk of its own and scans with lane shuffles only, so
+// the emit pass has no barrier inside its loop -- a wave that waits for memory holds up nobody.  (With
+// a workgroup-wide scan per tile, two barriers each, the waves of a workgroup ran at the pace of the
+// slowest one, tile after tile: the emit passes of the benchmark workload took 0.11 ms each.)
 // --------------------------------------------------------------------------------------
 constexpr int kScanThreads = 256;
-constexpr int kScanItems = 4;
-constexpr int kScanTile = kScanThreads * kScanItems;
-constexpr int kScanBlocks = 512;
+constexpr int kScanWavesPerBlock = kScanThreads / kWave;
+constexpr int kScanItems = 4;                    // consecutive elements per lane and step
+constexpr int kScanStep = kWave * kScanItems;    // elements per wavefront and step
+#ifndef TBE_SCAN_BLOCKS
+#define TBE_SCAN_BLOCKS 1024
+#endif
+constexpr int kScanBlocks = TBE_SCAN_BLOCKS;     // workgroups at most (SortScratch::blk holds 5 words per workgroup)
 
 typedef unsigned long long u64;
 
@@ -27,63 +34,70 @@ __device__ inline u64 wave_incl_scan(u64 v, int lane) {
   return v;
 }
 
-__device__ inline int scan_chunk(int n, int nblocks) {
-  const int tiles = (n + kScanTile - 1) / kScanTile;
-  const int tpb = (tiles + nblocks - 1) / nblocks;
-  return tpb * kScanTile;
+__device__ inline u64 wave_total(u64 v) {
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  return v;
 }
 
+// elements per wavefront: n spread over all wavefronts of the grid, in whole steps
+__device__ inline int scan_chunk(int n, int nblocks) {
+  const int waves = nblocks * kScanWavesPerBlock;
+  const int steps = (n + kScanStep - 1) / kScanStep;
+  return (steps + waves - 1) / waves * kScanStep;
+}
+
+// blk: [0, nblocks) sums per workgroup; [nblocks, nblocks * 5) sums per wavefront
 template <class Op>
 __global__ __launch_bounds__(kScanThreads) void compact_count_kernel(Op op, const int32_t *n_ptr, int n_fixed,
                                                                      u64 *blk, const BatchCounters *cnt) {
-  __shared__ u64 wsum[4];
+  __shared__ u64 wsum[kScanWavesPerBlock];
   if (cnt->err) return;
   const int n = n_ptr ? *n_ptr : n_fixed;
   const int chunk = scan_chunk(n, gridDim.x);
-  const int base = blockIdx.x * chunk, end = min(n, base + chunk);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int w = blockIdx.x * kScanWavesPerBlock + wave;
+  const int64_t base64 = (int64_t)w * chunk;
+  const int base = (int)(base64 < n ? base64 : n), end = (int)(base64 + chunk < n ? base64 + chunk : n);
   u64 s = 0;
-  for (int tile = base; tile < end; tile += kScanTile) {
-    const int i0 = tile + tid * kScanItems;
+  for (int i0 = base + lane * kScanItems; i0 < end; i0 += kScanStep) {
 #pragma unroll
     for (int q = 0; q < kScanItems; q++)
       if (i0 + q < end) s += op.flag(i0 + q, n);
   }
-  for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d);
-  if (lane == 0) wsum[wave] = s;
+  s = wave_total(s);
+  if (lane == 0) {
+    wsum[wave] = s;
+    blk[gridDim.x + w] = s;
+  }
   __syncthreads();
-  if (tid == 0) blk[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-}
-
-// sum of blk[0 .. count) over the workgroup (every thread gets it); wsum: 4 words of LDS
-__device__ inline u64 block_sum_of(const u64 *blk, int count, u64 *wsum) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  u64 v = 0;
-  for (int b = tid; b < count; b += kScanThreads) v += blk[b];
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-  __syncthreads();
-  if (lane == 0) wsum[wave] = v;
-  __syncthreads();
-  v = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-  __syncthreads();
-  return v;
+  if (tid == 0) {
+    u64 t = 0;
+    for (int k = 0; k < kScanWavesPerBlock; k++) t += wsum[k];
+    blk[blockIdx.x] = t;
+  }
 }
 
 template <class Op>
 __global__ __launch_bounds__(kScanThreads) void compact_emit_kernel(Op op, const int32_t *n_ptr, int n_fixed,
                                                                     const u64 *blk, BatchCounters *cnt) {
-  __shared__ u64 wsum[4];
   if (cnt->err) return;
   const int n = n_ptr ? *n_ptr : n_fixed;
   const int chunk = scan_chunk(n, gridDim.x);
-  const int base = blockIdx.x * chunk, end = min(n, base + chunk);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // flags in the workgroups before this one (each adds up the few hundred block sums itself: one
-  // launch less than a separate scan of them)
-  u64 carry = block_sum_of(blk, blockIdx.x, wsum);
-  const u64 total = blockIdx.x == 0 ? block_sum_of(blk, gridDim.x, wsum) : 0;
-  for (int tile = base; tile < end; tile += kScanTile) {
-    const int i0 = tile + tid * kScanItems;
+  const int w = blockIdx.x * kScanWavesPerBlock + wave;
+  const int64_t base64 = (int64_t)w * chunk;
+  const int base = (int)(base64 < n ? base64 : n), end = (int)(base64 + chunk < n ? base64 + chunk : n);
+  // flags before this wavefront: the workgroups before its own, then the waves before it in its own
+  u64 carry = 0;
+  for (int b = lane; b < (int)blockIdx.x; b += kWave) carry += blk[b];
+  if (lane < wave) carry += blk[gridDim.x + blockIdx.x * kScanWavesPerBlock + lane];
+  carry = wave_total(carry);
+  u64 total = 0;
+  if (blockIdx.x == 0 && wave == 0) {
+    for (int b = lane; b < (int)gridDim.x; b += kWave) total += blk[b];
+    total = wave_total(total);
+  }
+  for (int i0 = base + lane * kScanItems; i0 - lane * kScanItems < end; i0 += kScanStep) {
     u64 f[kScanItems];
     u64 tsum = 0;
 #pragma unroll
@@ -92,34 +106,28 @@ __global__ __launch_bounds__(kScanThreads) void compact_emit_kernel(Op op, const
       tsum += f[q];
     }
     const u64 incl = wave_incl_scan(tsum, lane);
-    if (lane == 63) wsum[wave] = incl;
-    __syncthreads();
-    u64 wb = 0, all = 0;
-    for (int w = 0; w < 4; w++) {
-      if (w < wave) wb += wsum[w];
-      all += wsum[w];
-    }
-    u64 pre = carry + wb + incl - tsum;
+    u64 pre = carry + incl - tsum;
 #pragma unroll
     for (int q = 0; q < kScanItems; q++) {
       if (i0 + q < end) op.emit(i0 + q, n, pre, f[q]);
       pre += f[q];
     }
-    carry += all;
-    __syncthreads();
+    carry += __shfl(incl, 63, 64);
   }
   op.thread_done(cnt, lane);
   if (blockIdx.x == 0 && tid == 0) op.finish(cnt, n, total);
 }
 
+// returns the number of workgroups of the two kernels
 template <class Op>
-static void run_compaction(Op op, const int32_t *n_ptr, int n_fixed, int n_bound, u64 *blk, BatchCounters *cnt,
+static int run_compaction(Op op, const int32_t *n_ptr, int n_fixed, int n_bound, u64 *blk, BatchCounters *cnt,
                            hipStream_t s) {
-  int nb = (n_bound + kScanTile - 1) / kScanTile;
+  int nb = (n_bound + kScanThreads * kScanItems - 1) / (kScanThreads * kScanItems);
   if (nb > kScanBlocks) nb = kScanBlocks;
   if (nb < 1) nb = 1;
   hipLaunchKernelGGL(compact_count_kernel<Op>, dim3(nb), dim3(kScanThreads), 0, s, op, n_ptr, n_fixed, blk, cnt);
   hipLaunchKernelGGL(compact_emit_kernel<Op>, dim3(nb), dim3(kScanThreads), 0, s, op, n_ptr, n_fixed, blk, cnt);
+  return nb;
 }
 
 // ---- pass 1 over the N sorted lookups: distinct rows, run starts, set ids ----
@@ -133,7 +141,6 @@ struct DedupOp {
   int within_bits;
   const int64_t *offsets;
   int32_t *sorted_within;    // max pooling only (else null): position of the lookup inside its bag
-  uint32_t *uid_sorted;
   int32_t *sorted_bag;
   uint32_t *uniq_key;
   int32_t *run_off;
@@ -142,7 +149,6 @@ struct DedupOp {
   __device__ u64 flag(int i, int) const { return (i == 0 || key[i] != key[i - 1]) ? 1ull : 0ull; }
   __device__ void emit(int i, int, u64 pre, u64 f) const {
     const uint32_t u = (uint32_t)(pre & 0xFFFFFFFFull) + (uint32_t)f - 1u;
-    uid_sorted[i] = u;
     const uint32_t p = pos[i];
     const int32_t bag = cnt->packed ? (int32_t)(p >> within_bits) : bag_of_pos[p];
     sorted_bag[i] = bag;
@@ -228,11 +234,23 @@ __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__res
   __shared__ int s_cnt[4][2];
   __shared__ int s_before[4][2];
   __shared__ int s_base[4][2];
+  // Heavy-list entries per table: gathered in LDS for the tables this workgroup's rows belong to (its rows are
+  // consecutive, so these are few) and added to the totals once per table -- thousands of atomic additions
+  // from all over the chip to a few dozen addresses took ten times as long as the rest of this kernel.
+  constexpr int kLocalTables = 256;
+  __shared__ int s_tab[kLocalTables];
+  __shared__ int s_tab0;
   if (cnt->err) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   int w0, w1, c[2];
   worklist_chunk(cnt->n_uniq, w0, w1);
+  s_tab[threadIdx.x] = 0;
+  if (threadIdx.x == 0) {
+    int b0, b1;
+    worklist_chunk(cnt->n_uniq, b0, b1);  // wave 0: the workgroup's first row
+    s_tab0 = b0 < cnt->n_uniq ? uniq_tab[b0] : 0;
+  }
   worklist_tally(run_off, w0, w1, c);
   int before[2] = {0, 0};  // rows of each kind in the workgroups before this one
   for (int b = threadIdx.x; b < (int)blockIdx.x; b += 256)
@@ -273,10 +291,15 @@ __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__res
         heavy[at + q] = u;
         heavy_sub[at + q] = q | (parts << 16);
       }
-      if (is_heavy) atomicAdd(&heavy_per_table[uniq_tab[u]], parts);
+      if (is_heavy) {
+        const int t = uniq_tab[u], rel = t - s_tab0;
+        if (rel >= 0 && rel < kLocalTables) atomicAdd(&s_tab[rel], parts); else atomicAdd(&heavy_per_table[t], parts);
+      }
       o_heavy += __shfl(incl, 63, 64);
     }
   }
+  __syncthreads();
+  if (s_tab[threadIdx.x]) atomicAdd(&heavy_per_table[s_tab0 + threadIdx.x], s_tab[threadIdx.x]);
 }
 
 // The heavy list is in table order.  Cut every table's part into chunks of the rows one workgroup of the
@@ -414,18 +437,26 @@ struct StatusOp {
   uint32_t *byp_key;
   char **byp_src;
   int32_t *loc_u;
+  uint32_t *loc_of_key;  // [key span] the location word of every distinct row of this batch, by sort key
   // second level (all null without one)
   const int32_t *src2, *dst2, *evict2;
   char **ins_dst, **l2v_src, **l2v_dst;
   uint32_t *l2v_key;
-  // per-thread tallies (the emit kernel keeps one Op copy per thread in registers)
-  mutable unsigned int hits, evs;
+  // per-thread tallies (the emit kernel keeps one Op copy per thread in registers); every wavefront leaves
+  // its sums in `tally` (two words each), which the kernel that keeps the running totals adds up -- thousands
+  // of atomic additions to one counter from all over the chip would take longer than the pass itself
+  u64 *tally;
+  mutable unsigned int evs;
   mutable u64 hit_lookups;
   __device__ u64 flag(int u, int) const {
     const uint8_t s = status[u];
     return s == ST_INSERT ? 1ull : s == ST_BYPASS ? (1ull << 32) : 0ull;
   }
   __device__ void emit(int u, int, u64 pre, u64 f) const {
+    {  // where the row's lookups find it: cache slot, or overflow copy number (the bypass list's order)
+      const uint32_t w = f > 1ull ? (kLocOverflow | (uint32_t)(pre >> 32)) : (uint32_t)loc_u[u];
+      loc_of_key[uniq_key[u]] = run_off[u + 1] - run_off[u] == 1 ? (w | kLocSingle) : w;
+    }
     if (f == 1ull) {
       const uint32_t i = (uint32_t)(pre & 0xFFFFFFFFull);
       const uint32_t key = uniq_key[u];
@@ -463,21 +494,19 @@ struct StatusOp {
         byp_src[j] = m.lines2 + (size_t)(src2[u] - m.slot2_base) * m.row_bytes;
       loc_u[u] = -2 - (int32_t)j;  // the row is served from the j-th overflow slot
     } else if (status[u] == ST_HIT) {
-      hits++;
       hit_lookups += (u64)(run_off[u + 1] - run_off[u]);
     }
   }
-  __device__ void thread_done(BatchCounters *cnt, int lane) const {
-    u64 h = hits, e = evs, l = hit_lookups;
+  __device__ void thread_done(BatchCounters *, int lane) const {
+    u64 e = evs, l = hit_lookups;
     for (int d = 32; d >= 1; d >>= 1) {
-      h += __shfl_xor(h, d);
       e += __shfl_xor(e, d);
       l += __shfl_xor(l, d);
     }
     if (lane == 0) {
-      if (h) atomicAdd(&cnt->hits, h);
-      if (e) atomicAdd(&cnt->evictions, e);
-      if (l) atomicAdd(&cnt->hit_lookups, l);
+      const int w = blockIdx.x * kScanWavesPerBlock + (threadIdx.x >> 6);
+      tally[2 * w] = e;
+      tally[2 * w + 1] = l;
     }
   }
   __device__ void finish(BatchCounters *cnt, int, u64 total) const {
@@ -710,23 +739,34 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
   }
 }
 
-// per-lookup location word, in input order
-__global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__restrict__ pos,
-                                                       const uint32_t *__restrict__ uid_sorted,
-                                                       const int32_t *__restrict__ loc_u,
-                                                       const int32_t *__restrict__ run_off, uint32_t *__restrict__ loc,
-                                                       const int64_t *__restrict__ offsets, int within_bits,
-                                                       const BatchCounters *cnt) {
+// Per-lookup location word, in input order: every lookup works out its sort key again and reads the word its
+// distinct row left in the map over the keys.  8 lanes per bag, coalesced reads of the indices and writes of
+// the words; the reads of the map are random, but repeat for the hot rows.  (Writing the words from the sorted
+// side instead, one 4-byte store per lookup all over the array, cost 260 MB of write traffic for 31 MB of
+// words and 0.15 ms on the benchmark workload.)
+constexpr int kLocateLanes = 8;
+__global__ __launch_bounds__(256) void locate_kernel(const TableMeta *__restrict__ tm, int T, int B,
+                                                     const int64_t *__restrict__ indices,
+                                                     const int64_t *__restrict__ offsets,
+                                                     const uint32_t *__restrict__ loc_of_key,
+                                                     uint32_t *__restrict__ loc, const BatchCounters *cnt) {
   if (cnt->err) return;
-  const bool packed = cnt->packed != 0;
-  const uint32_t within_mask = (1u << within_bits) - 1u;
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-    const uint32_t u = uid_sorted[i];
-    const int32_t lu = loc_u[u];
-    uint32_t w = lu >= 0 ? (uint32_t)lu : (kLocOverflow | (uint32_t)(-2 - lu));
-    if (run_off[u + 1] - run_off[u] == 1) w |= kLocSingle;
-    const uint32_t p = pos[i];  // the lookup's position: as is, or bag start + position inside the bag
-    loc[packed ? (uint32_t)offsets[p >> within_bits] + (p & within_mask) : p] = w;
+  const int64_t nb = (int64_t)T * B;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t bag = gid / kLocateLanes;
+  const int sub = (int)(gid % kLocateLanes);
+  if (bag >= nb) return;
+  const int64_t lo = offsets[bag], hi = offsets[bag + 1];
+  const TableMeta &m = tm[(int)(bag / B)];
+  const uint32_t sets = m.sets, rps = m.rows_per_set, base = m.key_base;
+  for (int64_t j = lo + sub; j < hi; j += kLocateLanes) {
+    const uint32_t r = (uint32_t)indices[j];
+    uint32_t key = base + r;
+    if (sets) {
+      const uint32_t q = r / sets;
+      key = base + (r - q * sets) * rps + q;
+    }
+    loc[j] = loc_of_key[key];
   }
 }
 
@@ -736,7 +776,7 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
   DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.cnt, g.within_bits, b.d_offsets,
-            b.maxp ? b.sorted_within : nullptr, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
+            b.maxp ? b.sorted_within : nullptr, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
             b.uniq_tab};
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
@@ -762,14 +802,14 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
                      l2.on ? b.src2 : nullptr, l2.on ? b.dst2 : nullptr, l2.on ? b.evict2 : nullptr, b.cnt);
   StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.uniq_tab, b.ins_idx, b.ins_tab, b.ins_slot,
               b.ins_old, b.ins_key, b.ins_src,
-              b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u,
+              b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u, ss.loc_of_key,
               l2.on ? b.src2 : nullptr, l2.on ? b.dst2 : nullptr, l2.on ? b.evict2 : nullptr,
               l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr, l2.on ? b.l2v_dst : nullptr,
-              l2.on ? b.l2v_key : nullptr, 0u, 0u, 0ull};
-  run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
-  const int fin_blocks = (n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096;
-  hipLaunchKernelGGL(finalize_kernel, dim3(fin_blocks), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.run_off,
-                     b.loc, b.d_offsets, g.within_bits, b.cnt);
+              l2.on ? b.l2v_key : nullptr, ss.tally, 0u, 0ull};
+  ss.tally_waves = run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s) * kScanWavesPerBlock;
+  const int64_t threads = (int64_t)g.T * b.batch * kLocateLanes;
+  hipLaunchKernelGGL(locate_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, tm, g.T, b.batch, b.d_indices,
+                     b.d_offsets, ss.loc_of_key, b.loc, b.cnt);
   return hipGetLastError();
 }
 

@@ -319,8 +319,14 @@ __global__ __launch_bounds__(256) void classify_kernel(const BatchCounters *cnt,
     if (code & kWhereParked) prev_wb_skip[code & kWhereIndex] = 1;
     late += code != 0;
   }
+  __shared__ unsigned int s_late[4];
   for (int d = 32; d >= 1; d >>= 1) late += __shfl_xor(late, d);
-  if ((threadIdx.x & 63) == 0 && late) atomicAdd(n_late, (unsigned long long)late);
+  if ((threadIdx.x & 63) == 0) s_late[threadIdx.x >> 6] = late;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    late = s_late[0] + s_late[1] + s_late[2] + s_late[3];
+    if (late) atomicAdd(n_late, (unsigned long long)late);
+  }
 }
 
 hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *pp, const BatchBuf *prev, const BatchBuf &cur,
