@@ -208,6 +208,7 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.sorted_bag, 4 * N));
   HIP_TRY(h, h->mem.get(&b.bag_of_pos, 4 * N));
   HIP_TRY(h, h->mem.get(&b.inv_len, 4 * (size_t)h->g.T * (size_t)h->max_batch));
+  HIP_TRY(h, h->mem.get(&b.uid_sorted, 4 * N));
   HIP_TRY(h, h->mem.get(&b.uniq_key, 4 * N));
   HIP_TRY(h, h->mem.get(&b.run_off, 4 * (N + 1)));
   HIP_TRY(h, h->mem.get(&b.uniq_sid, 4 * N));
@@ -573,7 +574,6 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     CREATE_TRY(hipMemset(st.wb_n, 0, 16));
     CREATE_TRY(h->mem.get(&st.where, 4 * (size_t)key));
     CREATE_TRY(hipMemset(st.where, 0, 4 * (size_t)key));
-    CREATE_TRY(h->mem.get(&h->ss.loc_of_key, 4 * (size_t)key));
     CREATE_TRY(h->mem.get(&h->d_rb, 4 * (size_t)num_tables));
     CREATE_TRY(hipMemcpy(h->d_rb, rb.data(), 4 * (size_t)num_tables, hipMemcpyHostToDevice));
   }

@@ -77,10 +77,33 @@ __global__ __launch_bounds__(kScanThreads) void compact_count_kernel(Op op, cons
   }
 }
 
+// Per-table constants the emit passes need for every flagged element, copied to LDS by the workgroup (a
+// look-up in the table descriptions in memory is a chain of dependent loads per element otherwise).
+#ifndef TBE_FINALIZE_BLOCKS
+#define TBE_FINALIZE_BLOCKS 512  // a multiple of 8
+#endif
+constexpr int kLutTables = 512;  // models with more tables read the descriptions from memory
+struct TableLut {
+  uint32_t key_base[kLutTables], sets[kLutTables], rows_per_set[kLutTables], set_base[kLutTables], row_bytes[kLutTables];
+  char *host_w[kLutTables];
+  char *lines2[kLutTables];
+  int32_t slot2_base[kLutTables];
+};
+
+__device__ inline void fill_lut(TableLut &l, const TableMeta *tm, int T) {
+  for (int t = threadIdx.x; t < T && t < kLutTables; t += blockDim.x) {
+    l.key_base[t] = tm[t].key_base; l.sets[t] = tm[t].sets; l.rows_per_set[t] = tm[t].rows_per_set;
+    l.set_base[t] = tm[t].set_base; l.row_bytes[t] = tm[t].row_bytes; l.host_w[t] = tm[t].host_w;
+    l.lines2[t] = tm[t].lines2; l.slot2_base[t] = tm[t].slot2_base;
+  }
+}
+
 template <class Op>
 __global__ __launch_bounds__(kScanThreads) void compact_emit_kernel(Op op, const int32_t *n_ptr, int n_fixed,
                                                                     const u64 *blk, BatchCounters *cnt) {
+  __shared__ TableLut s_lut;
   if (cnt->err) return;
+  if (op.prepare(s_lut)) __syncthreads();
   const int n = n_ptr ? *n_ptr : n_fixed;
   const int chunk = scan_chunk(n, gridDim.x);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -141,14 +164,22 @@ struct DedupOp {
   int within_bits;
   const int64_t *offsets;
   int32_t *sorted_within;    // max pooling only (else null): position of the lookup inside its bag
+  uint32_t *uid_sorted;
   int32_t *sorted_bag;
   uint32_t *uniq_key;
   int32_t *run_off;
   uint32_t *uniq_sid;
   int32_t *uniq_tab;
+  mutable const TableLut *lut;  // null: the model has too many tables for it
+  __device__ bool prepare(TableLut &l) const {
+    lut = T <= kLutTables ? &l : nullptr;
+    if (lut) fill_lut(l, tm, T);
+    return lut != nullptr;
+  }
   __device__ u64 flag(int i, int) const { return (i == 0 || key[i] != key[i - 1]) ? 1ull : 0ull; }
   __device__ void emit(int i, int, u64 pre, u64 f) const {
     const uint32_t u = (uint32_t)(pre & 0xFFFFFFFFull) + (uint32_t)f - 1u;
+    uid_sorted[i] = u;
     const uint32_t p = pos[i];
     const int32_t bag = cnt->packed ? (int32_t)(p >> within_bits) : bag_of_pos[p];
     sorted_bag[i] = bag;
@@ -158,10 +189,20 @@ struct DedupOp {
       const uint32_t k = key[i];
       uniq_key[u] = k;
       run_off[u] = i;
-      const int t = find_table(tm, T, k);
-      const TableMeta &m = tm[t];
-      uniq_tab[u] = t;
-      uniq_sid[u] = m.sets ? m.set_base + (k - m.key_base) / m.rows_per_set : kNoSet;
+      if (lut) {
+        int lo = 0, hi = T - 1;  // table that owns the key: last t with key_base[t] <= k
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if (lut->key_base[mid] <= k) lo = mid; else hi = mid - 1;
+        }
+        uniq_tab[u] = lo;
+        uniq_sid[u] = lut->sets[lo] ? lut->set_base[lo] + (k - lut->key_base[lo]) / lut->rows_per_set[lo] : kNoSet;
+      } else {
+        const int t = find_table(tm, T, k);
+        const TableMeta &m = tm[t];
+        uniq_tab[u] = t;
+        uniq_sid[u] = m.sets ? m.set_base + (k - m.key_base) / m.rows_per_set : kNoSet;
+      }
     }
   }
   __device__ void thread_done(BatchCounters *, int) const {}
@@ -176,6 +217,7 @@ struct SetHeadOp {
   const uint32_t *uniq_sid;
   const int32_t *run_off;
   uint2 *touched;
+  __device__ bool prepare(TableLut &) const { return false; }
   __device__ u64 flag(int u, int) const { return (u == 0 || uniq_sid[u] != uniq_sid[u - 1]) ? 1ull : 0ull; }
   __device__ void emit(int u, int, u64 pre, u64 f) const {
     if (f) touched[pre & 0xFFFFFFFFull] = make_uint2(uniq_sid[u], (uint32_t)u);
@@ -437,7 +479,6 @@ struct StatusOp {
   uint32_t *byp_key;
   char **byp_src;
   int32_t *loc_u;
-  uint32_t *loc_of_key;  // [key span] the location word of every distinct row of this batch, by sort key
   // second level (all null without one)
   const int32_t *src2, *dst2, *evict2;
   char **ins_dst, **l2v_src, **l2v_dst;
@@ -448,21 +489,46 @@ struct StatusOp {
   u64 *tally;
   mutable unsigned int evs;
   mutable u64 hit_lookups;
+  mutable const TableLut *lut;  // null: the model has too many tables for it
+  __device__ bool prepare(TableLut &l) const {
+    lut = T <= kLutTables ? &l : nullptr;
+    if (lut) fill_lut(l, tm, T);
+    return lut != nullptr;
+  }
+  struct TabView {
+    uint32_t key_base, sets, rows_per_set, row_bytes;
+    char *host_w, *lines2;
+    int32_t slot2_base;
+    __device__ uint32_t row_of(uint32_t key) const {
+      const uint32_t local = key - key_base;
+      if (sets == 0) return local;
+      const uint32_t s = local / rows_per_set;
+      return (local - s * rows_per_set) * sets + s;
+    }
+    __device__ uint32_t key_of(uint32_t row) const {
+      if (sets == 0) return key_base + row;
+      const uint32_t q = row / sets;
+      return key_base + (row - q * sets) * rows_per_set + q;
+    }
+  };
+  __device__ TabView view(int t) const {
+    if (lut)
+      return TabView{lut->key_base[t], lut->sets[t], lut->rows_per_set[t], lut->row_bytes[t], lut->host_w[t], lut->lines2[t],
+                     lut->slot2_base[t]};
+    const TableMeta &m = tm[t];
+    return TabView{m.key_base, m.sets, m.rows_per_set, m.row_bytes, m.host_w, m.lines2, m.slot2_base};
+  }
   __device__ u64 flag(int u, int) const {
     const uint8_t s = status[u];
     return s == ST_INSERT ? 1ull : s == ST_BYPASS ? (1ull << 32) : 0ull;
   }
   __device__ void emit(int u, int, u64 pre, u64 f) const {
-    {  // where the row's lookups find it: cache slot, or overflow copy number (the bypass list's order)
-      const uint32_t w = f > 1ull ? (kLocOverflow | (uint32_t)(pre >> 32)) : (uint32_t)loc_u[u];
-      loc_of_key[uniq_key[u]] = run_off[u + 1] - run_off[u] == 1 ? (w | kLocSingle) : w;
-    }
     if (f == 1ull) {
       const uint32_t i = (uint32_t)(pre & 0xFFFFFFFFull);
       const uint32_t key = uniq_key[u];
       const int t = uniq_tab[u];
-      const TableMeta &m = tm[t];
-      const uint32_t row = row_of_key(m, key);
+      const TabView m = view(t);
+      const uint32_t row = m.row_of(key);
       const int32_t old = old_tag[u];
       ins_idx[i] = u;
       ins_tab[i] = t;
@@ -478,18 +544,18 @@ struct StatusOp {
         ins_dst[i] = dst;
         l2v_src[i] = e2 >= 0 ? dst : nullptr;  // the line the victim takes still holds the row it pushes out
         l2v_dst[i] = e2 >= 0 ? m.host_w + (size_t)e2 * m.row_bytes : nullptr;
-        l2v_key[i] = e2 >= 0 ? key_of_row(m, (uint32_t)e2) : 0u;
+        l2v_key[i] = e2 >= 0 ? m.key_of((uint32_t)e2) : 0u;
       }
       if (old >= 0) evs++;
     } else if (f) {
       const uint32_t j = (uint32_t)(pre >> 32);
       const uint32_t key = uniq_key[u];
       const int t = uniq_tab[u];
-      const TableMeta &m = tm[t];
+      const TabView m = view(t);
       byp_idx[j] = u;
       byp_tab[j] = t;
       byp_key[j] = key;
-      byp_src[j] = m.host_w + (size_t)row_of_key(m, key) * m.row_bytes;
+      byp_src[j] = m.host_w + (size_t)m.row_of(key) * m.row_bytes;
       if (src2 && src2[u] >= 0)  // lives in the second level: used in place
         byp_src[j] = m.lines2 + (size_t)(src2[u] - m.slot2_base) * m.row_bytes;
       loc_u[u] = -2 - (int32_t)j;  // the row is served from the j-th overflow slot
@@ -739,34 +805,44 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
   }
 }
 
-// Per-lookup location word, in input order: every lookup works out its sort key again and reads the word its
-// distinct row left in the map over the keys.  8 lanes per bag, coalesced reads of the indices and writes of
-// the words; the reads of the map are random, but repeat for the hot rows.  (Writing the words from the sorted
-// side instead, one 4-byte store per lookup all over the array, cost 260 MB of write traffic for 31 MB of
-// words and 0.15 ms on the benchmark workload.)
-constexpr int kLocateLanes = 8;
-__global__ __launch_bounds__(256) void locate_kernel(const TableMeta *__restrict__ tm, int T, int B,
-                                                     const int64_t *__restrict__ indices,
-                                                     const int64_t *__restrict__ offsets,
-                                                     const uint32_t *__restrict__ loc_of_key,
-                                                     uint32_t *__restrict__ loc, const BatchCounters *cnt) {
+// Per-lookup location word, in input order, written from the sorted side: lookup i of the sorted sequence
+// belongs to distinct row uid_sorted[i], whose word goes to the lookup's position.  These are 4-byte stores all
+// over the array, but not without order: the sorted sequence and the input are both table-major, so the words
+// of one table land in that table's stretch of the array (a megabyte in the benchmark workload).  Each XCD takes
+// a contiguous eighth of the sorted sequence, i.e. whole tables, so a table's stretch is written through one L2,
+// where the stores meet and leave as full lines; the streamed inputs are read around the cache.  (Workgroups
+// dealt round robin over the XCDs wrote every line from eight L2s, in eight partial pieces: 260 MB of write
+// traffic for 31 MB of words.)
+__global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__restrict__ pos,
+                                                       const uint32_t *__restrict__ uid_sorted,
+                                                       const int32_t *__restrict__ loc_u,
+                                                       const int32_t *__restrict__ run_off, uint32_t *__restrict__ loc,
+                                                       const int64_t *__restrict__ offsets, int within_bits,
+                                                       const BatchCounters *cnt) {
   if (cnt->err) return;
-  const int64_t nb = (int64_t)T * B;
-  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t bag = gid / kLocateLanes;
-  const int sub = (int)(gid % kLocateLanes);
-  if (bag >= nb) return;
-  const int64_t lo = offsets[bag], hi = offsets[bag + 1];
-  const TableMeta &m = tm[(int)(bag / B)];
-  const uint32_t sets = m.sets, rps = m.rows_per_set, base = m.key_base;
-  for (int64_t j = lo + sub; j < hi; j += kLocateLanes) {
-    const uint32_t r = (uint32_t)indices[j];
-    uint32_t key = base + r;
-    if (sets) {
-      const uint32_t q = r / sets;
-      key = base + (r - q * sets) * rps + q;
+  const bool packed = cnt->packed != 0;
+  const uint32_t within_mask = (1u << within_bits) - 1u;
+  constexpr int K = 4;  // lookups per thread and pass, a workgroup's width apart: their loads are in flight together
+  int first, end, step;
+  xcd_span(n, 256 * K, first, end, step);
+  for (int i0 = first + threadIdx.x; i0 < end; i0 += step) {
+    uint32_t u[K], p[K], w[K], at[K];
+#pragma unroll
+    for (int q = 0; q < K; q++) {
+      const int i = i0 + q * 256;
+      u[q] = i < end ? __builtin_nontemporal_load(uid_sorted + i) : 0u;
+      p[q] = i < end ? __builtin_nontemporal_load(pos + i) : 0u;  // the lookup's position: as is, or (bag, position inside it)
     }
-    loc[j] = loc_of_key[key];
+#pragma unroll
+    for (int q = 0; q < K; q++) {
+      const int32_t lu = loc_u[u[q]];
+      w[q] = lu >= 0 ? (uint32_t)lu : (kLocOverflow | (uint32_t)(-2 - lu));
+      if (run_off[u[q] + 1] - run_off[u[q]] == 1) w[q] |= kLocSingle;
+      at[q] = packed ? (uint32_t)offsets[p[q] >> within_bits] + (p[q] & within_mask) : p[q];
+    }
+#pragma unroll
+    for (int q = 0; q < K; q++)
+      if (i0 + q * 256 < end) loc[at[q]] = w[q];
   }
 }
 
@@ -776,8 +852,8 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
   DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.cnt, g.within_bits, b.d_offsets,
-            b.maxp ? b.sorted_within : nullptr, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
-            b.uniq_tab};
+            b.maxp ? b.sorted_within : nullptr, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
+            b.uniq_tab, nullptr};
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
   run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
@@ -802,14 +878,13 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
                      l2.on ? b.src2 : nullptr, l2.on ? b.dst2 : nullptr, l2.on ? b.evict2 : nullptr, b.cnt);
   StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.uniq_tab, b.ins_idx, b.ins_tab, b.ins_slot,
               b.ins_old, b.ins_key, b.ins_src,
-              b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u, ss.loc_of_key,
+              b.byp_idx, b.byp_tab, b.byp_key, b.byp_src, b.loc_u,
               l2.on ? b.src2 : nullptr, l2.on ? b.dst2 : nullptr, l2.on ? b.evict2 : nullptr,
               l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr, l2.on ? b.l2v_dst : nullptr,
-              l2.on ? b.l2v_key : nullptr, ss.tally, 0u, 0ull};
+              l2.on ? b.l2v_key : nullptr, ss.tally, 0u, 0ull, nullptr};
   ss.tally_waves = run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s) * kScanWavesPerBlock;
-  const int64_t threads = (int64_t)g.T * b.batch * kLocateLanes;
-  hipLaunchKernelGGL(locate_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, tm, g.T, b.batch, b.d_indices,
-                     b.d_offsets, ss.loc_of_key, b.loc, b.cnt);
+  hipLaunchKernelGGL(finalize_kernel, dim3(TBE_FINALIZE_BLOCKS), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.run_off,
+                     b.loc, b.d_offsets, g.within_bits, b.cnt);
   return hipGetLastError();
 }
 

@@ -117,6 +117,7 @@ struct BatchBuf {
   int32_t *argpos;      // [batch * sum_dim] max pooling: position inside its bag of the lookup that supplied the
                         //     maximum of each pooled element (-1 for an empty bag); null unless max pooling is set
   int32_t *sorted_within; // [N] max pooling: position inside its bag of the i-th lookup in sorted order
+  uint32_t *uid_sorted; // [N] index of the distinct row of the i-th sorted lookup
   // per distinct row (ascending key)
   uint32_t *uniq_key;   // [N]
   int32_t *run_off;     // [N+1] first sorted position of each distinct row; run_off[U] = N
@@ -177,9 +178,6 @@ struct SortScratch {
   int32_t *wl;             // [kWorklistBlocks * 4] per-workgroup counts of the backward work lists
   unsigned long long *tally;  // [2 * wavefronts of a compaction pass] (evictions, lookups that hit) per wavefront of
   int tally_waves;            //     the last batch's status pass, and how many wavefronts that pass had
-  uint32_t *loc_of_key;    // [key span] per sort key: the location word of the row, written for every distinct row
-                           //     of the batch being prefetched and read for every lookup of it (entries of rows that
-                           //     are not in the batch are stale and never read)
 };
 
 // Staging between the cache and the host link (one instance; the prefetch stage is serial).
