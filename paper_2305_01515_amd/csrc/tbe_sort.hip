@@ -109,7 +109,28 @@ __global__ __launch_bounds__(kSortThreads) void sort_upsweep_kernel(const uint32
   __syncthreads();
   const int base = blockIdx.x * chunk;
   const int end = min(n, base + chunk);
-  for (int i = base + tid; i < end; i += kSortThreads) atomicAdd(&h[(keys[i] >> shift) & mask], 1u);
+  // Four keys per thread and step, their loads in flight together.  After the first pass equal keys lie side
+  // by side, and a power-law batch has keys with thousands of copies: a wavefront whose 64 keys share one digit
+  // adds them with one atomic instead of 64 to the same LDS word.
+  for (int i0 = base; i0 < end; i0 += 4 * kSortThreads) {
+    uint32_t k[4];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const int i = i0 + q * kSortThreads + tid;
+      k[q] = i < end ? keys[i] : 0u;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const bool valid = i0 + q * kSortThreads + tid < end;
+      const uint32_t d = valid ? (k[q] >> shift) & mask : 0xFFFFFFFFu;
+      const uint32_t d0 = __shfl(d, 0, 64);
+      if (__all(d == d0)) {
+        if ((tid & 63) == 0 && valid) atomicAdd(&h[d0], 64u);
+      } else if (valid) {
+        atomicAdd(&h[d], 1u);
+      }
+    }
+  }
   __syncthreads();
   hist[tid * gridDim.x + blockIdx.x] = h[tid];
 }
