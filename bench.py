@@ -27,7 +27,8 @@ HOST_LINK_PEAK_GBS = 64.0  # PCIe Gen5 x16, per direction
 
 def algorithmic_bytes(cfg, lookups_per_table, uniques, batch):
     """Bytes the method itself must move per step: rows once per lookup, location words and pooled output in the
-    forward; rows read and written once per distinct row, accumulators and the output gradient once in the backward."""
+    forward; rows read and written once per distinct row, accumulators and the output gradient once in the backward.
+    Returns (forward, backward, gradient rows if counted per lookup, forward with every distinct row counted once)."""
     from paper_2305_01515_amd import synth
     T = len(cfg.tables)
     rows_fwd = sum(lookups_per_table[t] * cfg.tables[t].dim * (4 if cfg.tables[t].dtype == synth.FP32 else 2)
@@ -37,21 +38,41 @@ def algorithmic_bytes(cfg, lookups_per_table, uniques, batch):
     io = 4 * batch * cfg.sum_dim                                   # pooled output / grad_out, once
     fwd = rows_fwd + 4 * sum(lookups_per_table) + io               # rows per lookup (Eq. 3) + locations + output
     bwd = uniques * (2 * rb_mean + 8) + io                         # row read-modify-write + accumulator + grad_out once
-    return fwd, bwd, grad_per_lookup
+    fwd_unique = uniques * rb_mean + 4 * sum(lookups_per_table) + io  # what HBM has to deliver when repeats hit the caches
+    return fwd, bwd, grad_per_lookup, fwd_unique
+
+
+def sources_sha():
+    """sha-256 (16 hex digits) over the HIP sources the library is built from: names a build"""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2305_01515_amd", "csrc")
+    h = hashlib.sha256()
+    for n in sorted(os.listdir(d)):
+        if n.endswith((".hip", ".h")):
+            h.update(n.encode())
+            h.update(open(os.path.join(d, n), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def measured_traffic(kernel_substr):
     """HBM bytes per launch of a kernel from the committed rocprofv3 --pmc summary
-    (profiles/bench_main_pmc.txt: FETCH_SIZE / WRITE_SIZE scaled by the copy-kernel factors)."""
+    (profiles/bench_main_pmc.txt: FETCH_SIZE / WRITE_SIZE scaled by the copy-kernel factors) -- only when that
+    summary was taken with the sources this run is built from (its `sources_sha` line), else None: counter
+    figures of another build beside this run's timings would say nothing."""
     path = os.path.join(ROOT, "profiles", "bench_main_pmc.txt")
     try:
-        for line in open(path):
-            f = line.split()
-            if len(f) >= 4 and f[0] == "traffic" and f[1] == kernel_substr:
-                return float(f[2]) + float(f[3])
+        lines = open(path).read().splitlines()
     except OSError:
-        pass
-    return None
+        return None
+    sha = [l.split()[1] for l in lines if l.startswith("sources_sha ") and len(l.split()) > 1]
+    if not sha or sha[0] != sources_sha():
+        return None
+    tot = None
+    for line in lines:
+        f = line.split()
+        if len(f) >= 4 and f[0] == "traffic" and f[1] == kernel_substr:
+            tot = (tot or 0.0) + float(f[2]) + float(f[3])
+    return tot
 
 
 def measured_peaks(torch):
@@ -382,7 +403,7 @@ def main():
     scale = (lookups / K) / max(1, sum(per_table))
     per_table = [p * scale for p in per_table]
     uniq = tot["uniques"] / npf
-    fwd_b, bwd_b, grad_pl = algorithmic_bytes(cfg, per_table, uniq, cfg.batch)
+    fwd_b, bwd_b, grad_pl, fwd_uniq_b = algorithmic_bytes(cfg, per_table, uniq, cfg.batch)
 
     ms = {k: float(np.mean(v)) if v.size else 0.0 for k, v in times.items()}
 
@@ -393,10 +414,13 @@ def main():
     hit_ms, hit_iso = ms["forward"] + bwd_ms, iso["forward"] + bwd_iso
     hit_b = fwd_b + bwd_b
     # the committed counter summary is of the benchmark workload only
-    fwd_traffic = measured_traffic("forward_kernel") if args.workload == "main" and T == 32 else None
+    main32 = (args.workload == "main" and T == 32 and args.policy == "lru" and args.pooling == "sum"
+              and not args.second_level and not args.deferred_init)
+    fwd_traffic = measured_traffic("forward_kernel") if main32 else None
     bwd_traffic = {k: (measured_traffic(k + "_kernel") if fwd_traffic else None) for k in BWD}
     hit_traffic = (fwd_traffic + sum(bwd_traffic.values())) if fwd_traffic and all(bwd_traffic.values()) else None
     fill_ms = ms["fill"]
+    link_gbs = max(h2d, d2h) / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0
     res = {
         "metric": "pooled lookups/s (fwd+bwd+update), achieved HBM GB/s, cache hit rate",
         "value": lookups / dt,
@@ -409,28 +433,47 @@ def main():
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
                    "overlap": not args.no_overlap, "policy": args.policy, "pooling": args.pooling,
                    "second_level_factor": args.second_level, "deferred_init": args.deferred_init},
-        # The HBM-bound kernel that moves most algorithmic bytes on the hit path.  Rows are counted once
-        # per lookup (the paper's Eq. 3); repeats of hot rows are served by L2, so achieved can exceed what
-        # HBM alone delivers -- `traffic` is what the counters saw.  ms_per_launch is measured in the timed,
-        # pipelined region (other streams' kernels share the GPU); `isolated` is the same launch alone.
-        "roofline": {"kernel": "forward_kernel (pooled gather), %d lanes per row" % (cfg.tables[0].dim // (8 if cfg.tables[0].dtype == synth.FP16 else 4)), "bound": "hbm",
-                     "achieved": gbs(fwd_b, ms["forward"]), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs(fwd_b, ms["forward"]) / HBM_PEAK_GBS, "traffic": fwd_traffic,
-                     "bytes_per_launch": fwd_b, "ms_per_launch": ms["forward"],
-                     "isolated": {"ms_per_launch": iso["forward"], "achieved": gbs(fwd_b, iso["forward"]),
-                                  "frac": gbs(fwd_b, iso["forward"]) / HBM_PEAK_GBS,
-                                  "traffic_frac": gbs(fwd_traffic, iso["forward"]) / HBM_PEAK_GBS if fwd_traffic else None}},
-        # backward = four kernels by lookups per row (1 / 2..64 / 65..1024 / more), back to back
+        # The dominant kernel of a step: transfer_kernel (write-back of parked victims beside the fetch-ahead of the
+        # missed rows), bound by the host link.  achieved = bytes of the busier direction per launch / mean launch time,
+        # measured live in the timed, pipelined region with HIP events on the link stream; peak = PCIe Gen5 x16 per
+        # direction.  bytes_per_launch: the miss path's algorithmic bytes (inserted + bypassed rows in, evicted + bypassed
+        # rows out, a row's bytes each), counted by the kernel itself.  traffic: HBM bytes of the kernel per launch from
+        # the committed counter summary, null unless that summary is of this build.
+        "roofline": {"kernel": "transfer_kernel (host link: write-back of parked victims + fetch-ahead of missed rows)",
+                     "bound": "host_link", "achieved": link_gbs, "peak": HOST_LINK_PEAK_GBS, "unit": "GB/s",
+                     "frac": link_gbs / HOST_LINK_PEAK_GBS, "traffic": measured_traffic("transfer_kernel") if main32 else None,
+                     "bytes_per_launch": {"h2d": h2d, "d2h": d2h}, "ms_per_launch": fill_ms,
+                     "h2d_GBps": gbs(h2d, fill_ms), "d2h_GBps": gbs(d2h, fill_ms),
+                     "isolated": {"ms_per_launch": iso["fill"]}},
+        # Forward kernel.  hbm: what HBM delivered -- counter traffic (committed summary of this build, else null) over
+        # the launch time, against the 8 TB/s peak.  eq3_rate_GBps counts every row once per lookup (the paper's Eq. 3);
+        # repeats of hot rows are served by L2, so it is a rate at L2 level and NOT a fraction of the HBM peak.
+        "forward": {"kernel": "forward_kernel (pooled gather), %d lanes per row" % (cfg.tables[0].dim // (8 if cfg.tables[0].dtype == synth.FP16 else 4)),
+                    "ms_per_launch": ms["forward"], "isolated_ms_per_launch": iso["forward"],
+                    "eq3_bytes_per_launch": fwd_b, "eq3_rate_GBps": gbs(fwd_b, ms["forward"]),
+                    "eq3_rate_isolated_GBps": gbs(fwd_b, iso["forward"]),
+                    "unique_row_bytes_per_launch": fwd_uniq_b,
+                    "hbm": {"traffic": fwd_traffic, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "achieved": gbs(fwd_traffic, ms["forward"]) if fwd_traffic else None,
+                            "frac": gbs(fwd_traffic, ms["forward"]) / HBM_PEAK_GBS if fwd_traffic else None,
+                            "isolated_frac": gbs(fwd_traffic, iso["forward"]) / HBM_PEAK_GBS if fwd_traffic else None}},
+        # backward = single-lookup rows bag by bag / rows with 2..64 lookups / heavy rows through LDS tiles / their combine
         "backward": {"bound": "hbm", "bytes_per_step": bwd_b, "ms": {k: ms[k] for k in BWD}, "ms_total": bwd_ms,
                      "achieved": gbs(bwd_b, bwd_ms), "frac": gbs(bwd_b, bwd_ms) / HBM_PEAK_GBS,
                      "isolated": {"ms": {k: iso[k] for k in BWD}, "ms_total": bwd_iso, "achieved": gbs(bwd_b, bwd_iso),
                                   "frac": gbs(bwd_b, bwd_iso) / HBM_PEAK_GBS},
-                     "traffic": bwd_traffic},
-        "hit_path": {"ms_fwd_bwd": hit_ms, "bytes": hit_b, "lookups_per_s": (lookups / K) / (hit_ms * 1e-3) if hit_ms else 0.0,
+                     "traffic": bwd_traffic,
+                     "traffic_over_compulsory": (sum(bwd_traffic.values()) / bwd_b) if bwd_traffic and all(bwd_traffic.values()) else None},
+        # Hit path = forward + backward + update kernels of a step against the 8 TB/s HBM peak.  bytes: rows once per
+        # lookup in the forward (Eq. 3), once per distinct row (read + write) in the backward.  frac_unique_rows counts
+        # the forward's rows once per distinct row as well: the bytes HBM itself has to deliver.
+        "hit_path": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "ms_fwd_bwd": hit_ms, "bytes": hit_b, "lookups_per_s": (lookups / K) / (hit_ms * 1e-3) if hit_ms else 0.0,
                      "achieved": gbs(hit_b, hit_ms), "frac": gbs(hit_b, hit_ms) / HBM_PEAK_GBS,
+                     "frac_unique_rows": gbs(fwd_uniq_b + bwd_b, hit_ms) / HBM_PEAK_GBS,
                      "isolated": {"ms_fwd_bwd": hit_iso, "lookups_per_s": (lookups / K) / (hit_iso * 1e-3) if hit_iso else 0.0,
                                   "achieved": gbs(hit_b, hit_iso), "frac": gbs(hit_b, hit_iso) / HBM_PEAK_GBS,
-                                  "frac_if_gradients_counted_per_lookup": gbs(hit_b + grad_pl, hit_iso) / HBM_PEAK_GBS,
+                                  "frac_unique_rows": gbs(fwd_uniq_b + bwd_b, hit_iso) / HBM_PEAK_GBS,
                                   # HBM bytes the counters saw for these kernels / their time: the bandwidth HBM delivered
                                   "traffic": hit_traffic,
                                   "traffic_frac": gbs(hit_traffic, hit_iso) / HBM_PEAK_GBS if hit_traffic else None}},
@@ -438,19 +481,20 @@ def main():
         "isolated_stage_ms": iso,
         # mean over every launch of the process (warm-up, timed, isolated): what rocprofv3 --stats averages
         "all_launches_stage_ms": all_launches,
-        # the kernel that takes longest overall: bound by the host link, not by HBM
-        "host_link": {"kernel": "transfer_kernel (write-back of parked victims + fetch-ahead of missed rows)",
-                      "bound": "host_link", "ms_per_launch": fill_ms, "h2d_bytes_per_step": h2d, "d2h_bytes_per_step": d2h,
-                      "achieved": max(h2d, d2h) / (fill_ms * 1e-3) / 1e9 if fill_ms else 0.0,
-                      "h2d_GBps": gbs(h2d, fill_ms), "d2h_GBps": gbs(d2h, fill_ms), "unit": "GB/s per direction",
-                      "peak": HOST_LINK_PEAK_GBS,
-                      "frac": max(h2d, d2h) / (fill_ms * 1e-3) / 1e9 / HOST_LINK_PEAK_GBS if fill_ms else 0.0},
         "cache": {"hit_rate_unique": tot["hits"] / max(1, tot["uniques"]),
                   "hit_rate_lookup": tot["hit_lookups"] / max(1, tot["lookups"]),
                   "bypass_frac_unique": tot["bypasses"] / max(1, tot["uniques"]),
                   "uniques_per_step": uniq, "inserts_per_step": tot["inserts"] / npf, "long_rows": s1["last_long_rows"],
                   "late_fetches_per_step": (s1["late_fetches"] - s0["late_fetches"]) / npf},
         "measured_peaks": peaks,  # plain copies on this machine, for context (the fractions above use the nominal peaks)
+        "sources_sha": sources_sha(),
+        # HBM the library holds beside the cache lines, in bytes: accumulators of all rows (4 B per row), the map of
+        # rows whose backing-tier copy is momentarily stale (4 B per sort key), tags / timestamps / counts / slot
+        # accumulators (16 B per slot) -- scales with the rows, not with the cache
+        "hbm_footprint": {"cache_lines": sum(tc.cache_slots // cfg.ways * cfg.ways * tc.dim * (4 if tc.dtype == synth.FP32 else 2) for tc in cfg.tables),
+                          "accumulators_all_rows": 4 * sum(tc.rows for tc in cfg.tables),
+                          "stale_copy_map": 4 * sum(tc.rows for tc in cfg.tables),
+                          "per_slot_state": 16 * sum(tc.cache_slots // cfg.ways * cfg.ways for tc in cfg.tables)},
         "cpu_baseline": cpu,
     }
     second_level = None

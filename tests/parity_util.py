@@ -234,10 +234,29 @@ def compare_backing(cfg, Wn, Mn, Wp, Mp, ctx: str, only=None, peak=None, tally: 
             assert em <= 1e-5, f"{ctx}: accumulators {r0}..{r1} of table {t} off by {em:.3e}"
 
 
+def compare_backing_touched(cfg, Wn, Mn, Wp, Mp, touched, ctx: str, tally: Tally = None):
+    """For tables too large to widen row by row: the rows some batch looked up (touched[t]: sorted row ids) are
+    held against the bar like everywhere else; all other rows must be bit for bit what both sides started from
+    (checked by one whole-table byte comparison after the touched rows have been made equal); accumulators of
+    all rows against theirs."""
+    for t, tc in enumerate(cfg.tables):
+        wg, mg = Wp[t].numpy(), Mp[t].numpy()
+        rows = touched[t]
+        check_vectors(wg[rows], Wn[t][rows], TOL[tc.dtype], 1e-3 * cfg.init_std, None, tally, f"{ctx}: touched rows of table {t}")
+        Wn[t][rows] = wg[rows]
+        assert torch.equal(torch.from_numpy(wg.view(np.int16 if tc.dtype == synth.FP16 else np.int32)),
+                           torch.from_numpy(Wn[t].view(np.int16 if tc.dtype == synth.FP16 else np.int32))), \
+            f"{ctx}: a row of table {t} that no batch looked up has changed"
+        step = 1 << 24
+        for r0 in range(0, tc.rows, step):
+            em = vec_err(mg[r0:r0 + step, None], Mn[t][r0:r0 + step, None], floor=M_FLOOR)
+            assert em <= 1e-5, f"{ctx}: accumulators {r0}.. of table {t} off by {em:.3e}"
+
+
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
                pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None, deferred_init=None,
-               flush_every: int = 0, misuse: int = 0, vary_batch: int = 0):
+               flush_every: int = 0, misuse: int = 0, vary_batch: int = 0, touched_only: bool = False):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -426,7 +445,13 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         only = [o.initialised(t) for t in range(T)]
         for t in range(T):
             assert np.array_equal(only[t], g.initialised(t)), f"rows of table {t} that have a value differ"
-    if parted["at"] is None:
+    if parted["at"] is None and touched_only:
+        # touched_only: tables of tens of GiB; rows that were looked up against the bar, the rest bit for bit
+        assert deferred_init is None and not peak_allowed
+        touched = [np.unique(np.concatenate([i.numpy()[int(f[t * (len(f) - 1) // T]):int(f[(t + 1) * (len(f) - 1) // T])]
+                                             for i, f in batches])) for t in range(T)]
+        compare_backing_touched(cfg, Wn, Mn, Wp, Mp, touched, "after flush", tally=tally)
+    elif parted["at"] is None:
         compare_backing(cfg, Wn, Mn, Wp, Mp, "after flush", only=only,
                         peak=[o.row_peak(t) for t in range(T)] if peak_allowed else None, tally=tally)
     if not peak_allowed or all(tc.dtype == synth.FP32 for tc in cfg.tables):

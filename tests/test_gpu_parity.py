@@ -82,13 +82,13 @@ def test_small_model_exercises_every_path():
 
 def test_main_config_full_size():
     """The benchmark's workload at full size (32 tables x 1M rows x dim 128 fp16, batch
-    8192), prefetch issued ahead as bench.py does; 20 steps, every pooled output compared, the cache
+    8192), prefetch issued ahead as bench.py does; 12 steps, every pooled output compared, the cache
     state after every fourth prefetch and the last, all 32M rows after the flush.  Every vector is held
     against the plain bar (2e-3 of the vector's own largest magnitude); the tally printed below says how
     close the worst one came."""
     cfg = synth.config_main()
-    st = run_parity(cfg, steps=20, order="ahead", oracle_threads=16, init_device="cuda", check_every=4)
-    print("main configuration, 20 steps:", st["tolerance"])
+    st = run_parity(cfg, steps=12, order="ahead", oracle_threads=16, init_device="cuda", check_every=4)
+    print("main configuration, 12 steps:", st["tolerance"])
     assert st["total"]["bypasses"] > 0 and st["total"]["evictions"] > 0
     assert st["tolerance"]["vectors_on_peak_scale"] == 0 and st["tolerance"]["worst_error_over_plain_bar"] <= 1.0
 
