@@ -17,6 +17,11 @@ class PlaceMemory(C.Structure):
     _fields_ = [("capacity_bytes", C.c_int64), ("bandwidth", C.c_double)]
 
 
+def _solver_library():
+    """the library that exports tbe_plan_placement (libtbe; the sanitizer run of the tests swaps in a host-only build)"""
+    return _tbe.lib()
+
+
 def plan(size: Sequence[int], traffic: Sequence[float], capacity: Sequence[int], bandwidth: Sequence[float],
          max_nodes: int = 0) -> Optional[Tuple[List[int], float, bool]]:
     """(memory type of every table, lookup time of Eq. 6, proven optimal) or None when no
@@ -24,7 +29,7 @@ def plan(size: Sequence[int], traffic: Sequence[float], capacity: Sequence[int],
     T, M = len(size), len(capacity)
     if len(traffic) != T or len(bandwidth) != M:
         raise ValueError("size/traffic and capacity/bandwidth must have equal lengths")
-    l = _tbe.lib()
+    l = _solver_library()
     l.tbe_plan_placement.argtypes = [C.POINTER(PlaceTable), C.c_int32, C.POINTER(PlaceMemory), C.c_int32, C.c_int64,
                                      C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     tabs = (PlaceTable * max(T, 1))(*[PlaceTable(int(s), float(x)) for s, x in zip(size, traffic)])

@@ -10,6 +10,15 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
+    san = os.environ.get("TBE_SANITIZED_LIBS")
+    if san:  # tests/sanitize_cpu_side.py: the oracle and the host-only solver built with ASan + UBSan
+        import ctypes
+        import oracle
+        from paper_2305_01515_amd import placement
+        oracle._LIB = os.path.join(san, "libtbe_oracle_san.so")
+        oracle.build = lambda force=False: oracle._LIB
+        solver = ctypes.CDLL(os.path.join(san, "libtbe_place_san.so"))
+        placement._solver_library = lambda: solver
 
 
 @pytest.fixture(autouse=True, scope="module")
