@@ -64,6 +64,7 @@ def lib():
         _lib.orc_set_policy.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_set_pooling.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_set_second_level.argtypes = [C.c_void_p, C.c_void_p]
+        _lib.orc_set_second_level_lock.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_enable_deferred_init.argtypes = [C.c_void_p, C.c_uint64, C.c_double]
         _lib.orc_export_initialised.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.orc_init_sum.restype = C.c_int32
@@ -99,7 +100,7 @@ class Oracle:
 
     def __init__(self, weights: Sequence[np.ndarray], state: Sequence[np.ndarray], cache_slots: Sequence[int],
                  ways: int, threads: int = 1, policy: str = "lru", pooling: str = "sum",
-                 second_level_slots: Optional[Sequence[int]] = None, deferred_init=None):
+                 second_level_slots: Optional[Sequence[int]] = None, deferred_init=None, second_level_lock: int = 2):
         self.weights = list(weights)
         self.state = list(state)
         self.ways = ways
@@ -127,6 +128,10 @@ class Oracle:
         if second_level_slots is not None:
             s2 = np.ascontiguousarray(second_level_slots, dtype=np.int64)
             assert s2.shape == (T,)
+            if second_level_lock != 2:  # 1: only the current batch's entries are locked (the plain reading)
+                rc = lib().orc_set_second_level_lock(self.h, second_level_lock)
+                if rc:
+                    raise OracleError(rc, "set_second_level_lock")
             rc = lib().orc_set_second_level(self.h, s2.ctypes.data)
             if rc:
                 raise OracleError(rc, "set_second_level")

@@ -162,6 +162,9 @@ typedef struct {
   int64_t cap_arg;
   int forwarded, prefetched;
   int threads;
+  int32_t lock2;       /* second level: entries stamped within the last `lock2` batches (the current one included)
+                          are not replaced.  2 = the reading the library follows (this batch and the one before);
+                          1 = the plain reading of Section 5.7 (this batch only), kept for the comparison of the two */
   orc_stats last, total;
   int64_t l2_last[4], l2_total[4]; /* hits, demotions, evictions, bypasses of the second level */
 } orc;
@@ -234,7 +237,7 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
   if (!specs || T <= 0 || ways <= 0) return NULL;
   orc *h = (orc *)calloc(1, sizeof(orc));
   if (!h) return NULL;
-  h->T = T; h->ways = ways; h->threads = 1;
+  h->T = T; h->ways = ways; h->threads = 1; h->lock2 = 2;
   h->tab = (orc_table *)calloc((size_t)T, sizeof(orc_table));
   for (int t = 0; t < T; t++) {
     orc_table *tb = &h->tab[t];
@@ -263,6 +266,15 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
 void orc_set_threads(void *hp, int n) { ((orc *)hp)->threads = n > 0 ? n : 1; }
 
 /* second-level cache of slots2[t] entries per table (whole sets of `ways`); only before the first batch */
+/* Batches whose second-level entries are locked (see orc.lock2): 1 or 2, before the first batch. */
+int orc_set_second_level_lock(void *hp, int32_t batches) {
+  orc *h = (orc *)hp;
+  if (!h || batches < 1 || batches > 2) return ORC_EINVAL;
+  if (h->k != 0) return ORC_EORDER;
+  h->lock2 = batches;
+  return ORC_OK;
+}
+
 int orc_set_second_level(void *hp, const int64_t *slots2) {
   orc *h = (orc *)hp;
   if (!h || !slots2) return ORC_EINVAL;
@@ -481,7 +493,7 @@ static int second_level(orc *h, orc_table *tb) {
     int way = -1;
     for (int w = 0; w < W; w++) {
       int32_t tw = tb->ts2[s * W + w];
-      if (tw < k - 1 && (way < 0 || tw < tb->ts2[s * W + way])) way = w;
+      if (tw < k - (h->lock2 - 1) && (way < 0 || tw < tb->ts2[s * W + way])) way = w;
     }
     if (way < 0) { /* every way was stamped by this batch or the one before: straight to the lower tier */
       memcpy((char *)tb->weights + (size_t)r * rb, vdata + (size_t)src * rb, rb);

@@ -264,3 +264,47 @@ def test_counters_are_per_batch_also_for_a_table_without_lookups():
         idle_after_busy += int(len(rows[1]) == 0 and k > 1 and prev_busy > 0)
         prev_busy = sum(per[1])
     assert idle_after_busy > 10  # the case that matters: an idle batch right after one that moved rows
+
+
+def test_two_batch_lock_of_the_second_level_changes_nothing_but_its_occupancy():
+    """The library's second level does not replace entries stamped by the current batch OR the one before (its data
+    moves trail its decisions by a batch); a sequential model has no data in flight and would lock the current
+    batch's entries only (the plain reading of the rule of Section 5.7).  Both rules run side by side on the same
+    stream: pooled outputs, every row and accumulator, the first level's tags and timestamps and the first level's
+    counters must be identical batch for batch -- the first level never looks at the second -- and only the
+    second level's contents and counters may differ.  The cost of the extra lock is then a number: rows found in
+    the second level under either rule (printed; the two-batch lock keeps recently demoted rows longer and lets
+    more victims pass the second level by)."""
+    rows, dims = [3000, 800], [8, 4]
+    ways = 4
+    slots1, slots2 = [ways * 12, ways * 5], [ways * 12, ways * 5]  # small second level: sets fill up within two batches
+    runs = []
+    for lock in (1, 2):
+        W, M = make_tables(rows, dims, [np.float32, np.float16], seed=5)
+        o = Oracle(W, M, slots1, ways=ways, second_level_slots=slots2, second_level_lock=lock)
+        trace, found, passed_by = [], 0, 0
+        for k in range(1, 41):
+            idx, off = random_batch(rows, 24, 5, seed=100 + k, skew=k % 3 != 0)
+            o.prefetch(idx, off)
+            out = o.forward().copy()
+            go = RNG(k).standard_normal((24, sum(dims))).astype(np.float32)
+            o.backward_update(go, 0.05, 1e-8)
+            l2 = o.second_level_stats()[0]
+            found += l2["hits"]
+            passed_by += l2["bypasses"]
+            trace.append((out, [tuple(a.copy() for a in o.cache_state(t)) for t in range(2)], o.stats()[0]))
+        l2_state = [tuple(a.copy() for a in o.second_level_state(t)) for t in range(2)]
+        o.flush()
+        o.close()
+        runs.append((trace, W, M, l2_state, found, passed_by))
+    a, b = runs
+    for k, ((out_a, st_a, cnt_a), (out_b, st_b, cnt_b)) in enumerate(zip(a[0], b[0])):
+        assert np.array_equal(out_a, out_b), f"pooled output of batch {k + 1} depends on the second level's rule"
+        assert cnt_a == cnt_b
+        for (ta, sa), (tb, sb) in zip(st_a, st_b):
+            assert np.array_equal(ta, tb) and np.array_equal(sa, sb)
+    for t in range(2):
+        assert np.array_equal(a[1][t], b[1][t]) and np.array_equal(a[2][t], b[2][t])
+    assert any(not np.array_equal(x[0], y[0]) for x, y in zip(a[3], b[3])), "the two rules never differed: the case is too easy"
+    assert a[5] <= b[5]  # the wider lock can only make more victims pass the second level by ... on this stream
+    print(f"second-level hits: lock of 1 batch {a[4]}, of 2 batches {b[4]}; victims passing it by: {a[5]} / {b[5]}")
