@@ -372,8 +372,8 @@ def main():
     s1 = g.stats()
     l2_1 = g.second_level_stats() if args.second_level else None
     BWD = ("backward_single", "backward_short", "backward_heavy", "backward_combine")
-    STAGES = ("prefetch", "fill", "commit", "forward") + BWD
-    first = {k: (Wm if k in ("forward",) + BWD else Wm + 1) for k in STAGES}
+    STAGES = ("prefetch", "fill", "commit", "forward", "backward") + BWD
+    first = {k: (Wm if k in ("forward", "backward") + BWD else Wm + 1) for k in STAGES}
     times = {k: g.stage_times(k)[first[k]:first[k] + K] for k in STAGES}  # the brackets of the timed steps
 
     # isolated pass (not part of `value`): the same kernels with nothing else on the GPU
@@ -410,7 +410,8 @@ def main():
     def gbs(nbytes, t_ms):
         return nbytes / (t_ms * 1e-3) / 1e9 if t_ms else 0.0
 
-    bwd_ms, bwd_iso = sum(ms[k] for k in BWD), sum(iso[k] for k in BWD)
+    # the whole backward, one bracket from before its first kernel to after its last
+    bwd_ms, bwd_iso = ms["backward"], iso["backward"]
     hit_ms, hit_iso = ms["forward"] + bwd_ms, iso["forward"] + bwd_iso
     hit_b = fwd_b + bwd_b
     # the committed counter summary is of the benchmark workload only
@@ -457,7 +458,9 @@ def main():
                             "achieved": gbs(fwd_traffic, ms["forward"]) if fwd_traffic else None,
                             "frac": gbs(fwd_traffic, ms["forward"]) / HBM_PEAK_GBS if fwd_traffic else None,
                             "isolated_frac": gbs(fwd_traffic, iso["forward"]) / HBM_PEAK_GBS if fwd_traffic else None}},
-        # backward = single-lookup rows bag by bag / rows with 2..64 lookups / heavy rows through LDS tiles / their combine
+        # backward = single-lookup rows bag by bag / rows with 2..64 lookups / heavy rows through LDS tiles / their combine;
+        # ms_total is the bracket around all of them, ms the brackets of the single kernels inside it (rocprofv3's
+        # kernel durations are these, less the events' overhead)
         "backward": {"bound": "hbm", "bytes_per_step": bwd_b, "ms": {k: ms[k] for k in BWD}, "ms_total": bwd_ms,
                      "achieved": gbs(bwd_b, bwd_ms), "frac": gbs(bwd_b, bwd_ms) / HBM_PEAK_GBS,
                      "isolated": {"ms": {k: iso[k] for k in BWD}, "ms_total": bwd_iso, "achieved": gbs(bwd_b, bwd_iso),

@@ -354,7 +354,9 @@ int tbe_get_stats(tbe_handle h, tbe_stats *out);
 #define TBE_STAGE_BACKWARD_SINGLE 6 /* backward of rows with one lookup, bag by bag (compute stream) */
 #define TBE_STAGE_BACKWARD_HEAVY 7 /* rows with more than 64 lookups: partial sums per bag range from gradient tiles in LDS
                                       (max pooling: one workgroup per row, update included) (compute stream) */
-#define TBE_NUM_STAGES 8
+#define TBE_STAGE_BACKWARD 8       /* the whole backward: from before its first kernel to after its last (compute stream);
+                                      brackets 7, 3, 6, 4 lie inside it, one behind the other */
+#define TBE_NUM_STAGES 9
 int tbe_set_profiling(tbe_handle h, int32_t enable);
 int64_t tbe_get_stage_times(tbe_handle h, int32_t stage, int64_t capacity, float *h_ms);
 

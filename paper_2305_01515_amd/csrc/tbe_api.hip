@@ -99,8 +99,10 @@ struct tbe_ctx {
   hipStream_t cs = nullptr, as = nullptr;  // compute / prefetch streams (caller's)
   hipStream_t ls = nullptr;                // host-link stream: transfer and commit (own, unless cs == as)
   bool own_ls = false;
+
   hipEvent_t ev_fwd = nullptr;  // the last forward launched
   bool fwd_recorded = false;
+  int last_trained = -1;        // buffer of the batch whose backward was launched last
   hipEvent_t ev_inputs = nullptr, ev_ready[kBatchBufs] = {}, ev_trained[kBatchBufs] = {}, ev_probed[kBatchBufs] = {};
   int64_t flush_state_bytes = 0;
   bool inputs_ready = false;  // caller guarantees index / offset buffers are complete when tbe_prefetch is called
@@ -299,12 +301,14 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     if (!h->inputs_ready) {  // inputs produced on the compute stream so far come first
       HIP_TRY(h, hipEventRecord(h->ev_inputs, h->cs));
       HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_inputs, 0));
-    } else if (h->fwd_recorded) {
-      // the last forward launched goes first: both it and this stage are bound by HBM, and the model
-      // waits for the forward's output, while this stage has the whole transfer of the batch before
-      // it to finish in (benchmark workload: forward 0.36 -> 0.275 ms beside the other streams, this
-      // stage 2.1 -> 1.7 ms, step unchanged)
-      HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_fwd, 0));
+    } else {
+      // Training launched so far goes first: its kernels and this stage are all bound by HBM and slow each
+      // other down when they overlap, the model waits for training, and this stage has the whole transfer of
+      // the batch before it to finish in.  (Benchmark workload, this stage behind the last forward only, i.e.
+      // beside the backward: forward 0.27 ms, backward 0.78 ms, this stage 1.5 ms per step; behind both: see
+      // the design notes.  The step is bound by the host link either way.)
+      if (h->fwd_recorded) HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_fwd, 0));
+      if (h->last_trained >= 0) HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_trained[h->last_trained], 0));
     }
     // this buffer last served the batch three before: its backward read the buffer's arrays,
     // and the commit of the batch after it read its bypass list and overflow copies
@@ -675,25 +679,33 @@ static int backward_update_with(tbe_ctx *h, const float *d_grad_out, float lr, f
   if (!d_grad_out) return fail(h, TBE_EINVAL, "backward_update: null gradient");
   if (h->current < 0) return fail(h, TBE_EORDER, "backward_update: no forwarded batch");
   const int bi = h->current;
+  // The four kernels touch disjoint rows and run one after the other.  (The heavy rows' tile kernel and its
+  // combine on a stream of their own, beside the other two: the tile kernel's workgroups need a CU to
+  // themselves each and waited for the others' waves to drain -- 0.28 ms instead of 0.12 alone, the whole
+  // backward 0.51 ms instead of 0.48, and 0.72 instead of 0.65 ms beside the other streams' work.)
   {
-    StageTimer tm_(h, TBE_STAGE_BACKWARD_HEAVY, h->cs);
-    HIP_TRY(h, launch_backward_classes(kBwdHeavy, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
-  }
-  {
-    StageTimer tm_(h, TBE_STAGE_BACKWARD_COMBINE, h->cs);
-    HIP_TRY(h, launch_backward_classes(kBwdCombine, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
-  }
-  {
-    StageTimer tm_(h, TBE_STAGE_BACKWARD_SINGLE, h->cs);
-    HIP_TRY(h, launch_backward_single_classes(h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, lr, eps, h->cs));
-  }
-  {
-    StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
-    HIP_TRY(h, launch_backward_classes(kBwdShort, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+    StageTimer all_(h, TBE_STAGE_BACKWARD, h->cs);
+    {
+      StageTimer tm_(h, TBE_STAGE_BACKWARD_HEAVY, h->cs);
+      HIP_TRY(h, launch_backward_classes(kBwdHeavy, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+    }
+    {
+      StageTimer tm_(h, TBE_STAGE_BACKWARD_COMBINE, h->cs);
+      HIP_TRY(h, launch_backward_classes(kBwdCombine, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+    }
+    {
+      StageTimer tm_(h, TBE_STAGE_BACKWARD_SINGLE, h->cs);
+      HIP_TRY(h, launch_backward_single_classes(h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, lr, eps, h->cs));
+    }
+    {
+      StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
+      HIP_TRY(h, launch_backward_classes(kBwdShort, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+    }
   }
   h->current = -1;
   if (h->as != h->cs) {
     HIP_TRY(h, hipEventRecord(h->ev_trained[bi], h->cs));
+    h->last_trained = bi;
     // later commits overwrite lines this batch used (the prefetch stream only decides on
     // tags and timestamps, which training never reads, so it does not wait here)
     HIP_TRY(h, hipStreamWaitEvent(h->ls, h->ev_trained[bi], 0));

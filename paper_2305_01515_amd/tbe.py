@@ -27,7 +27,7 @@ EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "
            "tbe_set_prefetch_depth", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax", "tbe_backward_update_static", "tbe_import_cache_freq"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1, "max": 2}
-STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_combine": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_heavy": 7}
+STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_combine": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_heavy": 7, "backward": 8}
 
 
 class TableSpec(C.Structure):
