@@ -342,7 +342,8 @@ int tbe_get_stats(tbe_handle h, tbe_stats *out);
  * brackets the kernels of each stage with HIP timing events on the stream they are
  * launched on; tbe_get_stage_times returns the elapsed milliseconds of every bracket
  * recorded since profiling was switched on, in call order (at most 16384 per stage).
- * Both calls synchronise; tbe_set_profiling discards earlier records.
+ * enable = 2 leaves out the brackets of the backward's single kernels (3, 4, 6, 7), which lie inside bracket 8
+ * and lengthen it by their own events.  Both calls synchronise; tbe_set_profiling discards earlier records.
  * With h_ms NULL, tbe_get_stage_times returns the number of records.
  */
 #define TBE_STAGE_PREFETCH 0       /* key generation, sort, dedup, probe, compaction (aux stream) */

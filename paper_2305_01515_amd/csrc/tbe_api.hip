@@ -125,7 +125,7 @@ struct tbe_ctx {
   int sticky = 0;
   std::string err;
   // optional stage timing: (start, stop) event pairs per stage, in call order
-  bool profiling = false;
+  int profiling = 0;  // 0 off, 1 every bracket, 2 the whole-stage brackets only
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof[TBE_NUM_STAGES];
 };
 
@@ -155,7 +155,9 @@ struct StageTimer {
   hipStream_t s;
   hipEvent_t stop = nullptr;
   StageTimer(tbe_ctx *h_, int stage, hipStream_t s_) : h(h_), s(s_) {
-    if (!h->profiling || h->prof[stage].size() >= kMaxProfiledCalls) return;
+    const bool inner = stage == TBE_STAGE_BACKWARD_HEAVY || stage == TBE_STAGE_BACKWARD_COMBINE ||
+                       stage == TBE_STAGE_BACKWARD_SINGLE || stage == TBE_STAGE_BACKWARD_SHORT;
+    if (!h->profiling || (inner && h->profiling == 2) || h->prof[stage].size() >= kMaxProfiledCalls) return;
     hipEvent_t a = nullptr, b = nullptr;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { if (a) (void)hipEventDestroy(a); return; }
     (void)hipEventRecord(a, s);
@@ -535,6 +537,16 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   // per batch so that the pairs fit (heavy_ranges)
   h->huge_slots = std::max<size_t>(4 * ((size_t)max_lookups / (kLongRun + 1) + 1), 32768);
   h->g.partial_slots = (int64_t)h->huge_slots;
+  {
+    int dev = 0, cus = 256;
+    (void)hipGetDevice(&dev);
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    (void)hipGetLastError();
+    // the transfer kernel keeps kLinkCus CUs to itself while it runs, which is most of the time when the link has
+    // a stream of its own and rows miss (the same figure without such a stream: the split of the sums, and with
+    // it their rounding, must not depend on how the streams are arranged)
+    h->g.heavy_target = std::max(8, cus - kLinkCus);
+  }
   for (int i = 0; i < kBatchBufs; i++) {
     int rc = alloc_batchbuf(h, h->buf[i], max_lookups);
     if (rc) { g_create_error = h->err; return bail(rc); }
@@ -956,7 +968,7 @@ int tbe_set_profiling(tbe_handle h, int32_t enable) {
   int rc = sync_all(h);
   if (rc) return rc;
   drop_profile(h);
-  h->profiling = enable != 0;
+  h->profiling = enable == 2 ? 2 : (enable != 0 ? 1 : 0);
   return TBE_OK;
 }
 

@@ -350,7 +350,8 @@ __global__ __launch_bounds__(256) void worklist_emit_kernel(const int32_t *__res
 __global__ __launch_bounds__(256) void heavy_group_kernel(const TableMeta *__restrict__ tm, int T,
                                                           const int32_t *__restrict__ heavy_per_table,
                                                           int32_t *first_of_table, uint4 *hchunks,
-                                                          long long slot_capacity, BatchCounters *cnt) {
+                                                          long long slot_capacity, int target_items,
+                                                          BatchCounters *cnt) {
   __shared__ int s_rows[4], s_chunks[4];
   __shared__ int s_carry[2];
   if (cnt->err) return;
@@ -380,7 +381,7 @@ __global__ __launch_bounds__(256) void heavy_group_kernel(const TableMeta *__res
   }
   if (tid == 0) {
     cnt->n_hchunks = s_carry[1];
-    cnt->h_ranges = heavy_ranges(s_carry[1], cnt->n_heavy, slot_capacity);
+    cnt->h_ranges = heavy_ranges(s_carry[1], cnt->n_heavy, slot_capacity, target_items);
   }
 }
 
@@ -862,7 +863,7 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
                      b.heavy, b.heavy_sub, b.hg_count, b.cnt);
   if (!b.maxp) {  // the tile kernel's chunks and range starts (max pooling takes heavy rows a workgroup each)
     hipLaunchKernelGGL(heavy_group_kernel, dim3(1), dim3(256), 0, s, tm, g.T, b.hg_count, b.hg_count + g.T + 1, b.hchunks,
-                       (long long)g.partial_slots, b.cnt);
+                       (long long)g.partial_slots, g.heavy_target, b.cnt);
     hipLaunchKernelGGL(heavy_order_kernel, dim3(g.T), dim3(64), 0, s, b.hg_count, b.hg_count + g.T + 1, b.heavy,
                        b.heavy_sub, b.run_off, b.hperm, b.cnt);
     hipLaunchKernelGGL(heavy_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.heavy, b.uniq_tab, b.run_off,

@@ -29,13 +29,11 @@ constexpr int kHeavyMaxParts = 64;         // parts (at most this many), each ta
 #define TBE_HEAVY_TILE_BYTES 98304
 #endif
 constexpr int kHeavyTileBytes = TBE_HEAVY_TILE_BYTES;    // gradient tile in LDS (rows padded by 16 bytes against bank conflicts)
-// (chunk, bag range) work items the ranges are chosen for: one workgroup of 1024 threads per CU.  Measured on
-// the benchmark workload (32 chunks; tile kernel + combine, ms): 256 items 0.110 + 0.024, 512 items 0.124 + 0.039,
-// 1024 items 0.148 + 0.079 -- more ranges mean more partial sums to write and to add up.
-#ifndef TBE_HEAVY_TARGET_ITEMS
-#define TBE_HEAVY_TARGET_ITEMS 256
-#endif
-constexpr int kHeavyTargetItems = TBE_HEAVY_TARGET_ITEMS;    // (chunk, bag range) work items the ranges are chosen for
+// (chunk, bag range) work items the ranges are chosen for: one workgroup of 1024 threads per CU that is free for
+// them (Geometry::heavy_target: all CUs less those the transfer kernel keeps to itself).  Measured on the benchmark workload (32 chunks, 256 CUs; tile kernel + combine alone, ms): 256 items
+// 0.110 + 0.024, 512 items 0.124 + 0.039, 1024 items 0.148 + 0.079 -- more ranges mean more partial sums to write
+// and to add up; beside the transfer kernel, which holds 48 CUs: 256 items 0.20 (two rounds), 192 items 0.15.
+constexpr int kLinkCus = 48;              // workgroups of the transfer kernel: 1024 threads each, a CU each
 constexpr int kHeavyMaxRanges = 128;
 
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
@@ -220,6 +218,7 @@ struct Geometry {
   int32_t within_bits;  // bits left for the position inside the bag in a packed sort payload (0 = never packed)
   int32_t partial_stride;  // floats per partial-sum slot (widest row, padded to whole lanes)
   int64_t partial_slots;   // slots of the partial-sum buffer (heavy rows x bag ranges of a batch fit in)
+  int32_t heavy_target;    // (chunk, bag range) work items the heavy rows' tile kernel should have: the CUs free for it
   uint32_t ovf_stride;     // bytes per overflow / staging slot (widest row)
   uint32_t total_sets;
   int64_t total_slots;
@@ -289,12 +288,12 @@ hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassIn
 // ---- small device helpers ----
 
 // Bag ranges of the heavy-row backward for a batch with n_hchunks (table, row group) chunks and n_heavy
-// heavy rows: enough ranges for about kHeavyTargetItems work items, no more than the partial-sum buffer
+// heavy rows: enough ranges for about target_items work items, no more than the partial-sum buffer
 // (slot_capacity slots of one row each) holds.  A function of the batch alone, so the summation order is
 // reproducible.
-__host__ __device__ inline int heavy_ranges(int n_hchunks, int n_heavy, long long slot_capacity) {
+__host__ __device__ inline int heavy_ranges(int n_hchunks, int n_heavy, long long slot_capacity, int target_items) {
   if (n_hchunks < 1 || n_heavy < 1) return 1;
-  long long r = (kHeavyTargetItems + n_hchunks - 1) / n_hchunks;
+  long long r = target_items / n_hchunks;  // rounded down: one round of workgroups
   if (r > kHeavyMaxRanges) r = kHeavyMaxRanges;
   if (r > slot_capacity / n_heavy) r = slot_capacity / n_heavy;
   return r < 1 ? 1 : (int)r;

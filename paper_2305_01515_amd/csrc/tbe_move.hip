@@ -25,7 +25,6 @@ namespace tbe {
 typedef unsigned long long u64;
 constexpr int kMoveLanes = 16;
 constexpr int kLinkBlocks = 192;   // workgroups of the smaller kernels that write to the host link
-constexpr int kLinkCus = 48;       // workgroups of the transfer kernel: 1024 threads each, a CU each
 constexpr int kLinkThreads = 1024;
 
 // ---- deferred initialisation: counter-based normal numbers of (seed, table, row, element) ----

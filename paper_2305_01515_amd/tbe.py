@@ -236,8 +236,9 @@ class TBE:
         """ready=True: index/offset tensors given to prefetch() are complete when it is called"""
         self._check(lib().tbe_set_inputs_ready(self._h, 1 if ready else 0), "tbe_set_inputs_ready")
 
-    def set_profiling(self, enable: bool):
-        self._check(lib().tbe_set_profiling(self._h, 1 if enable else 0), "tbe_set_profiling")
+    def set_profiling(self, enable):
+        """False / True, or 2: whole-stage brackets only (none around the backward's single kernels)"""
+        self._check(lib().tbe_set_profiling(self._h, int(enable)), "tbe_set_profiling")
 
     def stage_times(self, stage: str) -> np.ndarray:
         """milliseconds of every recorded bracket of a stage (see STAGES)"""
