@@ -167,9 +167,15 @@ __global__ __launch_bounds__(256) void forward_kernel(const TableMeta *__restric
     for (int e = 0; e < EPL; e++) acc[e] *= sc;
   }
   if (active) {
+    // written once, read by the model: a non-temporal store, so that the pooled output does not push the
+    // tables' hot rows out of L2 (benchmark workload: 0.202 -> 0.197 ms alone, 0.267 -> 0.260 ms beside the other streams)
     float *o = out + (size_t)b * sum_dim + m.col + lig * EPL;
 #pragma unroll
-    for (int e = 0; e < EPL; e += 4) *(float4 *)(o + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+    for (int e = 0; e < EPL; e += 4) {
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+      f32x4 v = {acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+      __builtin_nontemporal_store(v, (f32x4 *)(o + e));
+    }
   }
 }
 
@@ -684,10 +690,17 @@ __global__ __launch_bounds__(256) void backward_long_kernel(const TableMeta *__r
 // the tile are a prefix of what is left of the window.
 struct HeavySlot {
   int bag;   // this lane's bag id of the window (0x7FFFFFFF outside the row's lookups of this range)
-  int next;  // ... of the entry's next window, requested at the end of the tile in which the one before was taken up
-  int used;  // ids of the window consumed so far (same in all lanes of the group)
-  int need;  // 1 = `next` has been taken up and not been requested again yet
+  int next;  // ... of the entry's next window, requested when the one before it is taken up
 };
+// Beside these, per row of a lane group: `used`, the ids of the window consumed so far (the same in all lanes
+// of the group; one byte per row of the group, packed to save vector registers).
+struct HeavyState {
+  uint64_t used;
+};
+__device__ inline int heavy_used(const HeavyState &st, int s) { return (int)((st.used >> (8 * s)) & 0xFFu); }
+__device__ inline void heavy_set_used(HeavyState &st, int s, int v) {
+  st.used = (st.used & ~(0xFFull << (8 * s))) | ((uint64_t)(uint32_t)v << (8 * s));
+}
 
 // this lane's bag id of the window that starts at sorted position `at`, for a row whose lookups of the
 // range are [lo, hi)
@@ -696,60 +709,111 @@ __device__ inline int heavy_window(const int32_t *__restrict__ sorted_bag, int a
   return (p >= lo && p < hi) ? sorted_bag[p] : 0x7FFFFFFF;
 }
 
-// win: in LDS, (sorted position of the window after `next`, end of the row's lookups inside this bag range,
-// distance between the entry's windows) -- touched once per G lookups, so they need not sit in registers
-// zero_row: index of a staged row of zeros, read in place of the lookups a quad does not have
-template <int DT, int G>
-__device__ inline void heavy_consume(HeavySlot &sl, int4 *win, float (&g)[Elems<DT>::n], const float *tile,
-                                     int row_stride, int zero_row, int base_bag, int end_bag,
-                                     const int32_t *__restrict__ sorted_bag, int lig, int gshift) {
+// N window positions P0 .. P0+N-1: every lane takes the byte offset of the staged gradient row from the lane
+// that holds the lookup and reads its own float4s of that row -- all reads are issued before the first is
+// added -- then the N rows are added in lookup order.  A lane's float4s are number lig, G + lig, ... of the
+// row, so the lanes of a group read consecutive 16-byte pieces (no two of them in one LDS bank).
+template <int DT, int G, int P0, int N, int X = 0>
+__device__ inline void heavy_issue(float4 (&v)[N][Elems<DT>::n / 4], const char *tile, uint32_t row_off,
+                                   uint32_t lane_off) {
+  if constexpr (X < N) {
+    const char *src = tile + (row_bcast<P0 + X>(row_off) + lane_off);
+#pragma unroll
+    for (int e = 0; e < Elems<DT>::n / 4; e++) v[X][e] = *(const float4 *)(src + e * G * 16);
+    heavy_issue<DT, G, P0, N, X + 1>(v, tile, row_off, lane_off);
+  }
+}
+template <int DT, int G, int P0, int N>
+__device__ inline void heavy_add(float (&g)[Elems<DT>::n], const char *tile, uint32_t row_off, uint32_t lane_off) {
   constexpr int EPL = Elems<DT>::n;
-  constexpr int Q = EPL == 8 ? 2 : 4;  // gradient rows read from LDS before they are added
-  while (true) {
-    uint64_t ok = __ballot(lig >= sl.used && sl.bag < end_bag) >> gshift;
-    if (G < 64) ok &= (1ull << G) - 1ull;
-    const int n_ok = __popcll(ok);  // lanes used .. used + n_ok - 1 hold lookups of this tile
-    if (n_ok == 0) break;
-    for (int q = 0; q < n_ok; q += Q) {
-      float4 v[Q][EPL / 4];
+  float4 v[N][EPL / 4];
+  heavy_issue<DT, G, P0, N>(v, tile, row_off, lane_off);
 #pragma unroll
-      for (int x = 0; x < Q; x++) {
-        const int bq = __shfl(sl.bag, (sl.used + q + x) & (G - 1), G);
-        const float *src = tile + (q + x < n_ok ? bq - base_bag : zero_row) * row_stride + lig * EPL;
+  for (int x = 0; x < N; x++)
 #pragma unroll
-        for (int e = 0; e < EPL / 4; e++) v[x][e] = *(const float4 *)(src + 4 * e);
+    for (int e = 0; e < EPL / 4; e++) {
+      g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
+    }
+}
+
+template <int DT, int G, int P0 = 0>
+__device__ inline void heavy_add_window(float (&g)[Elems<DT>::n], const char *tile, uint32_t row_off, uint32_t lane_off,
+                                        uint64_t positions) {
+  constexpr int N = Elems<DT>::n == 8 ? 2 : 4;  // gradient rows read from LDS before they are added
+  if constexpr (P0 < G) {
+    if (positions & ((uint64_t)((1 << N) - 1) << P0))  // the same for the whole wavefront
+      heavy_add<DT, G, P0, N>(g, tile, row_off, lane_off);
+    heavy_add_window<DT, G, P0 + N>(g, tile, row_off, lane_off, positions);
+  }
+}
+
+// win: in LDS, (sorted position of the window after `next`, end of the row's lookups inside this bag range,
+// distance between the entry's windows, the entry's position in the heavy list) -- touched once per G lookups,
+// so they need not sit in registers
+// zero_row: index of a staged row of zeros, read in place of the lookups a group does not have
+//
+// The lane that holds a lookup of this tile works out the offset of its staged gradient row once; the
+// window's positions are then visited in unrolled runs of four, and a run is skipped when no group of the
+// wavefront has a lookup of this tile there (a group without one at a position adds the row of zeros).
+// Per lookup this costs one DPP addition, the row's LDS reads and its additions (benchmark workload: 27 M vector
+// instructions per launch instead of 49 M with the offsets worked out per lookup after a shuffle of the bag id;
+// the kernel's time stayed at 0.14 ms: with the additions taken out altogether it takes 0.064 ms, with the
+// staging loads taken out 0.12 ms -- what is left is the 3 GB that the lookups read from LDS on the CUs in use).
+template <int DT, int G>
+__device__ inline uint64_t heavy_consume(HeavySlot &sl, HeavyState &st, int s, int4 *win, float (&g)[Elems<DT>::n], const float *tile,
+                                         int row_stride, int zero_row, int base_bag, int end_bag,
+                                         const int32_t *__restrict__ sorted_bag, int lig, int gshift) {
+  const uint32_t lane_off = (uint32_t)lig * 16u;
+  const int group_lane0_x4 = gshift * 4;
+  int used = heavy_used(st, s);
+  const bool in = lig >= used && sl.bag < end_bag;  // this lane's lookup belongs to the tile and is still to be added
+  const uint64_t any = __ballot(in);
+  if (any == 0) return 0;
+  const uint32_t row_off = (uint32_t)((in ? sl.bag - base_bag : zero_row) * row_stride) * 4u;
+  // positions at which some group of the wavefront has a lookup
+  uint64_t pos = any;
+  if (G <= 32) pos |= pos >> 32;
+  if (G <= 16) pos |= pos >> 16;
+  if (G <= 8) pos |= pos >> 8;
+  if (G <= 4) pos |= pos >> 4;
+  if (G < 64) pos &= (1ull << G) - 1ull;
+  if constexpr (G == 16) {
+    heavy_add_window<DT, G>(g, (const char *)tile, row_off, lane_off, pos);
+  } else {  // the same with the positions counted at run time and the offsets permuted through LDS
+    constexpr int EPL = Elems<DT>::n;
+    constexpr int N = EPL == 8 ? 2 : 4;
+#pragma unroll 1
+    for (int p = 0; p < G; p += N) {
+      if (!((pos >> p) & ((1u << N) - 1u))) continue;  // the same for the whole wavefront
+      float4 v[N][EPL / 4];
+#pragma unroll
+      for (int x = 0; x < N; x++) {
+        const uint32_t o = (uint32_t)__builtin_amdgcn_ds_bpermute(group_lane0_x4 + 4 * (p + x), (int)row_off);
+        const char *src = (const char *)tile + (o + lane_off);
+#pragma unroll
+        for (int e = 0; e < EPL / 4; e++) v[x][e] = *(const float4 *)(src + e * G * 16);
       }
 #pragma unroll
-      for (int x = 0; x < Q; x++)
+      for (int x = 0; x < N; x++)
 #pragma unroll
         for (int e = 0; e < EPL / 4; e++) {
           g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
         }
     }
-    sl.used += n_ok;
-    if (sl.used < G) break;  // what is left of the window lies behind this tile
-    sl.used = 0;             // window used up
-    if (!sl.need) {          // on to the one requested before; the one after it is requested when this tile is done,
-      sl.bag = sl.next;      // so that no wave waits for memory between two rows (heavy_refill)
-      sl.need = 1;
-    } else {                 // a second window inside one tile (a hot row's part): fetched on the spot
-      int4 w = *win;
-      sl.bag = heavy_window(sorted_bag, w.x, 0, w.y, lig);
-      w.x += w.z;
-      if (lig == 0) *win = w;
-    }
   }
-}
-
-// after a tile: request the next window of every row whose spare one has been taken up
-__device__ inline void heavy_refill(HeavySlot &sl, int4 *win, const int32_t *__restrict__ sorted_bag, int lig) {
-  if (sl.need) {
+  uint64_t mine = any >> gshift;
+  if (G < 64) mine &= (1ull << G) - 1ull;
+  used += __popcll(mine);  // the group's lanes used .. used + n - 1 held its lookups of this tile
+  if (used == G) {         // window used up (else what is left of it lies behind this tile): on to the one requested
+    used = 0;              // before, and the one after it is requested now -- it is needed when this one is used up,
+    sl.bag = sl.next;      // and the group's other rows are visited in between
     int4 w = *win;
     sl.next = heavy_window(sorted_bag, w.x, 0, w.y, lig);
-    sl.need = 0;
     w.x += w.z;
     if (lig == 0) *win = w;
   }
+  heavy_set_used(st, s, used);
+  return any;
 }
 
 template <int DT, int G>
@@ -797,6 +861,8 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
     const int bag0 = t * B;
     const int tile_lo = min(n_tiles, range * tiles_per_range), tile_hi = min(n_tiles, tile_lo + tiles_per_range);
     HeavySlot sl[RPG];
+    HeavyState st;
+    st.used = 0;
     float g[RPG][EPL];
 #pragma unroll
     for (int s = 0; s < RPG; s++) {
@@ -814,11 +880,10 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
       const int w0 = (lo - run0) / G;                               // window that holds position lo
       const int w = w0 + ((part - w0) % parts + parts) % parts;     // first window >= w0 of this part
       const int at = run0 + w * G, stride = parts * G;
-      if (lig == 0) s_win[s][grp] = make_int4(at + 2 * stride, hi, stride, 0);  // only this group reads it
-      sl[s].used = (w == w0 && lo > at) ? lo - at : 0;
+      if (lig == 0) s_win[s][grp] = make_int4(at + 2 * stride, hi, stride, has ? h : -1);  // only this group reads it
+      heavy_set_used(st, s, (w == w0 && lo > at) ? lo - at : 0);
       sl[s].bag = heavy_window(sorted_bag, at, lo, hi, lig);
       sl[s].next = heavy_window(sorted_bag, at + stride, lo, hi, lig);
-      sl[s].need = 0;
 #pragma unroll
       for (int e = 0; e < EPL; e++) g[s][e] = 0.f;
     }
@@ -851,21 +916,25 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
       }
       __syncthreads();
       const int base_bag = bag0 + b_first, end_bag = bag0 + min(B, b_first + TB);
+      // the group's rows are visited in turn, a window's lookups of this tile at a time, until none has any left
+      uint64_t busy;
+      do {
+        busy = 0;
 #pragma unroll
-      for (int s = 0; s < RPG; s++)
-        heavy_consume<DT, G>(sl[s], &s_win[s][grp], g[s], tile, STRIDE, TB, base_bag, end_bag, sorted_bag, lig, gshift);
-      // the rows' next windows are requested behind the tile's work, all together (a request in front of
-      // the work would make the first wait for a window hold up for the others as well)
-#pragma unroll
-      for (int s = 0; s < RPG; s++) heavy_refill(sl[s], &s_win[s][grp], sorted_bag, lig);
+        for (int s = 0; s < RPG; s++)
+          busy |= heavy_consume<DT, G>(sl[s], st, s, &s_win[s][grp], g[s], tile, STRIDE, TB, base_bag, end_bag, sorted_bag, lig, gshift);
+      } while (busy);
     }
+    // the sums go to the slots of the groups' heavy-list entries (kept in LDS since the set-up: a load from memory
+    // here would wait for the stores in front of it)
 #pragma unroll
     for (int s = 0; s < RPG; s++) {
-      const int j = s * NG + grp;
-      if (j < (int)ch.z) {
-        float *p = partials + ((size_t)hperm[(int)ch.y + j] * R + range) * pstride + lig * EPL;
+      const int h = s_win[s][grp].w;
+      if (h >= 0) {
+        // this lane's float4s are number lig, G + lig, ... of the row (see heavy_add)
+        float *p = partials + ((size_t)h * R + range) * pstride + lig * 4;
 #pragma unroll
-        for (int e = 0; e < EPL; e += 4) *(float4 *)(p + e) = make_float4(g[s][e], g[s][e + 1], g[s][e + 2], g[s][e + 3]);
+        for (int e = 0; e < EPL; e += 4) *(float4 *)(p + e * G) = make_float4(g[s][e], g[s][e + 1], g[s][e + 2], g[s][e + 3]);
       }
     }
   }
