@@ -50,8 +50,8 @@
  * Optional, each selected by one call before the first batch: LFU instead of LRU
  * (tbe_set_policy), mean or max instead of sum pooling (tbe_set_pooling), a second-level cache in
  * pinned host memory between the two tiers (tbe_enable_second_level), initial values made up on
- * first read instead of stored (tbe_enable_deferred_init), batches accepted several ahead of
- * training (tbe_set_prefetch_depth).
+ * first read instead of stored (tbe_enable_deferred_init), a queue of batches accepted further
+ * ahead of training than the one batch the pipeline runs ahead (tbe_set_prefetch_queue).
  */
 #ifndef TBE_H
 #define TBE_H
@@ -247,18 +247,18 @@ int tbe_export_argmax(tbe_handle h, int32_t *d_argmax);
 int tbe_set_policy(tbe_handle h, int32_t policy);
 
 /*
- * Prefetch depth (Section 5.7: the caches are accessed several batches in advance).  With depth
- * D > 1 tbe_prefetch accepts up to D batches ahead of training.  The pipeline itself stays one
- * batch deep -- the host link is its bottleneck and is busy at that depth, and no row needed
- * by a batch that has not trained is evicted because a batch's rows enter their cache lines
- * only after the batch before has trained -- so batches beyond the next one are queued and
- * their work is issued, in order, as soon as the batch before them has been forwarded.
- * Results are those of depth 1.  The index buffers of a queued batch must stay valid and
+ * Queue in front of tbe_prefetch.  With length D > 1 tbe_prefetch accepts up to D batches ahead of
+ * training.  This is NOT the multi-batch prefetch of Section 5.7 (cache accesses several batches
+ * in advance, with the rule that rows prefetched for a batch are not evicted before it trains):
+ * the pipeline itself stays one batch deep, no batch's rows are fetched more than one batch ahead
+ * and no lock over several batches exists.  Batches beyond the next one are only kept on the host
+ * and their work is issued, in order, as soon as the batch before them has been forwarded.
+ * Results are those of a caller that prefetches one batch ahead.  The index buffers of a queued batch must stay valid and
  * unchanged until its tbe_backward_update has completed.  tbe_get_stats and the tbe_export_*
  * calls describe the last batch whose work has been issued, not the last one accepted.
- * depth 1..64 (TBE_EINVAL); not while batches are queued (TBE_EORDER).  Default 1.
+ * length 1..64 (TBE_EINVAL); not while batches are queued (TBE_EORDER).  Default 1.
  */
-int tbe_set_prefetch_depth(tbe_handle h, int32_t depth);
+int tbe_set_prefetch_queue(tbe_handle h, int32_t length);
 
 /*
  * By default tbe_prefetch orders its work behind everything enqueued on the compute stream

@@ -99,6 +99,8 @@ struct tbe_ctx {
   hipStream_t cs = nullptr, as = nullptr;  // compute / prefetch streams (caller's)
   hipStream_t ls = nullptr;                // host-link stream: transfer and commit (own, unless cs == as)
   bool own_ls = false;
+  hipStream_t ws = nullptr;                // side stream of the prefetch stage: the backward's work lists (own; null if cs == as)
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
   hipEvent_t ev_fwd = nullptr;  // the last forward launched
   bool fwd_recorded = false;
@@ -116,7 +118,7 @@ struct tbe_ctx {
   // soon as the batch before has been forwarded
   struct Queued { const int64_t *d_indices, *d_offsets; int32_t batch; int64_t n; };
   std::deque<Queued> queued;
-  int depth = 1;                // batches tbe_prefetch may run ahead of training
+  int depth = 1;                // batches tbe_prefetch accepts ahead of training (those beyond the next one are queued)
   int n_pend = 0;
   int current = -1;
   int deferred = -1;
@@ -323,7 +325,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     int res = 0;
     HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
     HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->freq,
-                                  h->policy == TBE_POLICY_LFU, h->l2, h->as));
+                                  h->policy == TBE_POLICY_LFU, h->l2, h->as, h->ws, h->ev_fork, h->ev_join));
     // which of the rows to insert have a backing-tier copy that is still being written
     // (by the write-back of the previous batch's victims or by its backward), then move
     // the marks on from the previous batch to this one
@@ -376,6 +378,9 @@ int tbe_destroy(tbe_handle h) {
   (void)hipStreamSynchronize(h->ls);
   (void)hipStreamSynchronize(h->cs);
   if (h->own_ls) (void)hipStreamDestroy(h->ls);
+  if (h->ws) { (void)hipStreamSynchronize(h->ws); (void)hipStreamDestroy(h->ws); }
+  if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+  if (h->ev_join) (void)hipEventDestroy(h->ev_join);
   h->mem.release();
   if (h->lines2) (void)hipHostFree(h->lines2);
   drop_profile(h);
@@ -508,6 +513,9 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   if (h->as != h->cs) {
     CREATE_TRY(hipStreamCreateWithFlags(&h->ls, hipStreamNonBlocking));
     h->own_ls = true;
+    CREATE_TRY(hipStreamCreateWithFlags(&h->ws, hipStreamNonBlocking));
+    CREATE_TRY(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
+    CREATE_TRY(hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming));
   }
   CREATE_TRY(h->mem.get(&h->d_slot_m, 4 * slots));
   if (slots) CREATE_TRY(hipMemset(h->d_slot_m, 0, 4 * slots));
@@ -630,17 +638,17 @@ int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offset
   if (h->depth > 1 && (ahead > 1 || !h->queued.empty())) {  // beyond what runs now: keep it for later
     if (!d_offsets || batch < 0 || num_lookups < 0 || (num_lookups > 0 && !d_indices)) return fail(h, TBE_EINVAL, "prefetch: bad argument");
     if (batch > h->max_batch || num_lookups > h->max_lookups) return fail(h, TBE_ELIMIT, "prefetch: batch or lookups above the sizes given to tbe_create");
-    if (ahead > h->depth) return fail(h, TBE_EORDER, "prefetch: more batches ahead of training than the prefetch depth");
+    if (ahead > h->depth) return fail(h, TBE_EORDER, "prefetch: more batches ahead of training than the queue takes");
     h->queued.push_back({d_indices, d_offsets, batch, num_lookups});
     return TBE_OK;
   }
   return do_prefetch(h, d_indices, d_offsets, batch, num_lookups);
 }
 
-int tbe_set_prefetch_depth(tbe_handle h, int32_t depth) {
+int tbe_set_prefetch_queue(tbe_handle h, int32_t depth) {
   if (!h) return TBE_EINVAL;
-  if (depth < 1 || depth > 64) return fail(h, TBE_EINVAL, "set_prefetch_depth: depth must be 1..64");
-  if (!h->queued.empty()) return fail(h, TBE_EORDER, "set_prefetch_depth: batches are queued");
+  if (depth < 1 || depth > 64) return fail(h, TBE_EINVAL, "set_prefetch_queue: length must be 1..64");
+  if (!h->queued.empty()) return fail(h, TBE_EORDER, "set_prefetch_queue: batches are queued");
   h->depth = depth;
   return TBE_OK;
 }

@@ -42,8 +42,9 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
   const int t = (int)(bag / B);
   const TableMeta m = tm[t];
   const bool packed = cnt->packed != 0;
-  for (int64_t j = lo + sub; j < hi; j += kKeygenLanes) {
-    int64_t r = indices[j];
+  // two indices per lane and step, both requested before either is used (the loop is bound by the latency
+  // of these reads: a bag has a few dozen lookups, so a lane makes only a few steps)
+  auto emit = [&](int64_t j, int64_t r) {
     if (r < 0 || r >= m.rows) {
       atomicMax(&cnt->err, 2 /* -TBE_ERANGE */);
       r = 0;
@@ -55,6 +56,13 @@ __global__ __launch_bounds__(256) void keygen_kernel(const TableMeta *__restrict
       vals[j] = (uint32_t)j;
       bag_of_pos[j] = (int32_t)bag;
     }
+  };
+  for (int64_t j = lo + sub; j < hi; j += 2 * kKeygenLanes) {
+    const bool second = j + kKeygenLanes < hi;
+    const int64_t r0 = indices[j];
+    const int64_t r1 = second ? indices[j + kKeygenLanes] : 0;
+    emit(j, r0);
+    if (second) emit(j + kKeygenLanes, r1);
   }
 }
 

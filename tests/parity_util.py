@@ -399,10 +399,10 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             if s + 1 < steps:
                 gpu_prefetch(s + 1)
             g.backward_update(go, cfg.lr, cfg.eps)
-        elif order.startswith("deep"):  # deepN: N batches accepted ahead of training
+        elif order.startswith("deep"):  # deepN: a queue that accepts N batches ahead of training
             depth = int(order[4:])
             if s == 0:
-                g.set_prefetch_depth(depth)
+                g.set_prefetch_queue(depth)
             while pushed < min(steps, s + 1 + depth):
                 g.prefetch(*dev[pushed])
                 pushed += 1

@@ -231,9 +231,10 @@ def test_repeated_runs_are_reproducible():
 
 
 @pytest.mark.parametrize("depth", [2, 5])
-def test_prefetch_depth_queues_batches(depth):
-    """tbe_prefetch accepts `depth` batches ahead of training; results are those of depth 1 (the
-    oracle's), the queue refuses one batch too many, flush refuses while batches are queued."""
+def test_prefetch_queue_takes_batches_ahead(depth):
+    """With a queue of length `depth` tbe_prefetch accepts that many batches ahead of training; results are
+    those of prefetching one batch ahead (the oracle's), the queue refuses one batch too many, flush refuses
+    while batches are queued."""
     from paper_2305_01515_amd.tbe import TbeError
     from parity_util import run_parity
     from test_gpu_parity import small_cfg
@@ -242,7 +243,7 @@ def test_prefetch_depth_queues_batches(depth):
     g, _, _ = make(cfg, max_lookups=1 << 16)
     stream = synth.BatchStream(cfg, device="cuda")
     bs = [stream.next() for _ in range(depth + 2)]
-    g.set_prefetch_depth(depth)
+    g.set_prefetch_queue(depth)
     for b in bs[:depth + 1]:  # the batch about to train and `depth` batches after it
         g.prefetch(*b)
     with pytest.raises(TbeError) as e:
@@ -251,7 +252,7 @@ def test_prefetch_depth_queues_batches(depth):
     with pytest.raises(TbeError):
         g.flush()
     with pytest.raises(TbeError):
-        g.set_prefetch_depth(1)
+        g.set_prefetch_queue(1)
     for b in bs[:depth + 1]:
         g.forward(*b)
         g.backward_update(torch.zeros(cfg.batch, cfg.sum_dim, device="cuda"), 0.1, 1e-8)
@@ -326,7 +327,7 @@ def test_binding_keeps_queued_batches_alive_at_depth_four():
     runs = []
     for careless in (False, True):
         g, Wp, Mp = make(cfg)
-        g.set_prefetch_depth(4)
+        g.set_prefetch_queue(4)
         held, pushed, outs, junk = [], 0, [], []
         for s in range(len(batches)):
             while pushed < min(len(batches), s + 5):
