@@ -235,6 +235,8 @@ def main():
     ap.add_argument("--cache-frac", type=float, default=0.05, help="locality: cached fraction of the rows")
     ap.add_argument("--policy", default="lru", choices=["lru", "lfu"],
                     help="replacement policy; lru is the benchmark's, lfu for the comparison the paper makes")
+    ap.add_argument("--backing-throttle-ns", type=int, default=0,
+                    help="emulate a slower backing tier: the host-link kernel pauses this long per backing-tier row (0 = off)")
     ap.add_argument("--second-level", type=int, default=0,
                     help="factor of a second-level cache in pinned host memory (0 = none, the benchmark's)")
     ap.add_argument("--deferred-init", action="store_true",
@@ -304,7 +306,7 @@ def main():
                 f"{'uniform' if args.alpha <= 0 else 'Zipf %g' % args.alpha}, 64-way cache {args.cache_frac:.0%} of rows")
     if args.policy != "lru":
         desc = desc.replace("LRU ", "").replace("-way cache", "-way LFU cache")
-    if args.workload != "main" or args.policy != "lru" or args.pooling != "sum" or args.second_level or args.deferred_init:
+    if args.workload != "main" or args.policy != "lru" or args.pooling != "sum" or args.second_level or args.deferred_init or args.backing_throttle_ns:
         args.no_cpu_baseline = True
     T = cfg.num_tables
 
@@ -357,6 +359,8 @@ def main():
             g.forward(batches[s][0], batches[s][1], out)
             g.backward_update(grads[s % len(grads)], cfg.lr, cfg.eps)
 
+    if args.backing_throttle_ns:
+        g.set_backing_throttle(args.backing_throttle_ns)
     g.set_inputs_ready(not args.wait_for_compute)  # all index tensors were generated and synchronised above
     g.set_profiling(True)  # stage brackets from the first launch on, so that the means over all
     g.prefetch(*batches[0])  # launches can be compared with a rocprofv3 --stats run of this command
@@ -446,7 +450,8 @@ def main():
         "config": {"workload": desc,
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
                    "overlap": not args.no_overlap, "policy": args.policy, "pooling": args.pooling,
-                   "second_level_factor": args.second_level, "deferred_init": args.deferred_init},
+                   "second_level_factor": args.second_level, "deferred_init": args.deferred_init,
+                   "backing_throttle_ns": args.backing_throttle_ns},
         # The dominant kernel of a step: transfer_kernel (write-back of parked victims beside the fetch-ahead of the
         # missed rows), bound by the host link.  achieved = bytes of the busier direction per launch / mean launch time,
         # measured live in the timed, pipelined region with HIP events on the link stream; peak = PCIe Gen5 x16 per
@@ -520,7 +525,7 @@ def main():
         second_level = {k: (l2b[k] - l2a[k]) / npf for k in l2b}
         second_level["hit_rate_of_first_level_misses"] = (l2b["hits"] - l2a["hits"]) / max(1, tot["inserts"] + tot["bypasses"])
     g.close()
-    if args.workload == "main" and not args.second_level and not args.no_control and not args.deferred_init:
+    if args.workload == "main" and not args.second_level and not args.no_control and not args.deferred_init and not args.backing_throttle_ns:
         res["all_hit_control"] = all_hit_control(TBE, cfg, Wp, Mp, batches[Wm + K], grads, out, max_n, hit_b,
                                                  not args.no_overlap, not args.wait_for_compute)
     if args.second_level:

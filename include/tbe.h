@@ -253,12 +253,26 @@ int tbe_set_policy(tbe_handle h, int32_t policy);
  * the pipeline itself stays one batch deep, no batch's rows are fetched more than one batch ahead
  * and no lock over several batches exists.  Batches beyond the next one are only kept on the host
  * and their work is issued, in order, as soon as the batch before them has been forwarded.
- * Results are those of a caller that prefetches one batch ahead.  The index buffers of a queued batch must stay valid and
- * unchanged until its tbe_backward_update has completed.  tbe_get_stats and the tbe_export_*
+ * Results are those of a caller that prefetches one batch ahead.  The index buffers of a queued
+ * batch must stay valid and unchanged until its tbe_backward_update has completed.  tbe_get_stats and the tbe_export_*
  * calls describe the last batch whose work has been issued, not the last one accepted.
  * length 1..64 (TBE_EINVAL); not while batches are queued (TBE_EORDER).  Default 1.
  */
 int tbe_set_prefetch_queue(tbe_handle h, int32_t length);
+
+/*
+ * For measurements, not for production use: emulates a backing tier that is slower than pinned host
+ * memory (the paper's lowest tier is storage, Section 5.3).  After every row that the host-link kernel
+ * reads from or writes to the backing tier proper -- not the lines of a second-level cache, which stay
+ * as fast as they are -- the wavefront that moved it pauses for about ns_per_row nanoseconds (a fixed
+ * number of sleep instructions: no wait on memory, so the kernel always ends).  Results do not change,
+ * only the time the transfer takes: the backing tier then carries at most about
+ * (wavefronts of the kernel, 768) x row bytes / ns_per_row in both directions together.  0 switches it
+ * off (the default).
+ * Flush, and the write-back that follows a batch without a successor, are not slowed down.
+ * May be called at any time between batches; TBE_EINVAL outside 0 .. 1e8.
+ */
+int tbe_set_backing_throttle(tbe_handle h, int64_t ns_per_row);
 
 /*
  * By default tbe_prefetch orders its work behind everything enqueued on the compute stream

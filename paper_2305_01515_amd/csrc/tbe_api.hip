@@ -78,6 +78,7 @@ struct tbe_ctx {
   int policy = TBE_POLICY_LRU;
   int pooling = TBE_POOL_SUM;
   DeferredInit di;              // deferred initialisation on read (off unless enabled)
+  Throttle throttle;            // emulated slower backing tier (off unless tbe_set_backing_throttle was called)
   uint32_t *init_bits = nullptr;
   size_t huge_slots = 0;        // (huge row, bag range) pairs a batch can have
   Level2 l2;                    // second-level cache (off unless tbe_enable_second_level was called)
@@ -345,7 +346,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     // the host link; neither touches a cache line, so a batch in flight is not disturbed,
     // and the link stream lets the next batch's sort and probe run meanwhile
     StageTimer tm_(h, TBE_STAGE_FILL, h->ls);
-    HIP_TRY(h, launch_transfer(&b, h->st, h->l2, h->di, b.k, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
+    HIP_TRY(h, launch_transfer(&b, h->st, h->l2, h->di, h->throttle, b.k, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
   }
   b.prev_bi = h->prev_buf;
   h->prev_buf = bi;
@@ -785,7 +786,7 @@ int tbe_flush(tbe_handle h) {
     h->deferred = -1;
     h->queued.clear();
   }
-  HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, h->di, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
+  HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, h->di, h->throttle, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
   if (h->prev_buf >= 0) {
     // Every copy in the backing tier is current now, so the next batch must find no row marked
     // "still on its way".  Left in place, such a mark would make that batch ask the transfer to skip
@@ -813,6 +814,18 @@ int tbe_set_policy(tbe_handle h, int32_t policy) {
   return TBE_OK;
 }
 
+int tbe_set_backing_throttle(tbe_handle h, int64_t ns_per_row) {
+  if (!h) return TBE_EINVAL;
+  if (ns_per_row < 0 || ns_per_row > 100000000) return fail(h, TBE_EINVAL, "set_backing_throttle: 0 .. 1e8 ns per row");
+  int khz = 0;
+  if (hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, h->device) != hipSuccess || khz < 1) khz = 2400000;
+  (void)hipGetLastError();
+  // one pause is s_sleep 127: about 127 x 64 clocks
+  const double clocks = (double)ns_per_row * 1e-9 * (double)khz * 1e3;
+  h->throttle.pauses = ns_per_row == 0 ? 0 : std::max(1, (int)(clocks / (127.0 * 64.0) + 0.5));
+  return TBE_OK;
+}
+
 int tbe_enable_second_level(tbe_handle h, int32_t factor) {
   if (!h) return TBE_EINVAL;
   if (factor < 1 || factor > 1024) return fail(h, TBE_EINVAL, "enable_second_level: factor must be 1..1024");
@@ -828,6 +841,8 @@ int tbe_enable_second_level(tbe_handle h, int32_t factor) {
   }
   if (slots2 == 0) return fail(h, TBE_EINVAL, "enable_second_level: no table has a first-level cache");
   HIP_TRY(h, hipHostMalloc((void **)&h->lines2, bytes2, hipHostMallocDefault));
+  h->l2.lines_lo = h->lines2;
+  h->l2.lines_hi = h->lines2 + bytes2;
   Level2 &l2 = h->l2;
   const size_t M = (size_t)h->st.max_inserts;
   HIP_TRY(h, h->mem.get(&l2.tags2, 4 * (size_t)slots2));

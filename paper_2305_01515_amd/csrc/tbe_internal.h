@@ -209,6 +209,13 @@ struct Level2 {
   int32_t *tags2 = nullptr, *ts2 = nullptr;
   char *out2[2] = {nullptr, nullptr};  // [max_inserts * stride] each, by batch parity
   char **wb2_dst = nullptr;            // [max_inserts] lower-tier row of each staged second-level victim
+  const char *lines_lo = nullptr, *lines_hi = nullptr;  // address range of the second-level lines (pinned host memory)
+};
+
+// Emulation of a slower backing tier, for measurements only: the transfer kernel pauses after every row it
+// reads from or writes to the backing tier proper (not the second-level lines).  0 pauses = off.
+struct Throttle {
+  int32_t pauses = 0;  // s_sleep instructions of the longest kind per backing-tier row
 };
 
 struct Geometry {
@@ -256,8 +263,8 @@ struct DeferredInit {
   float std = 0.f;
 };
 
-hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, const DeferredInit &di, int k,
-                           const uint32_t *rb_of_table,
+hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, const DeferredInit &di,
+                           const Throttle &th, int k, const uint32_t *rb_of_table,
                            unsigned long long *bytes_h2d, unsigned long long *bytes_d2h, hipStream_t s);
 // look up, for the rows cur inserts or bypasses, whether their backing-tier copy is stale
 // and where the current value is; then remove prev's entries from the map and enter cur's

@@ -107,7 +107,8 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
                                                        u64 di_seed, float di_std,
                                                        const uint32_t *__restrict__ ins_key,
                                                        const uint32_t *__restrict__ byp_key, u64 *bytes_h2d,
-                                                       u64 *bytes_d2h) {
+                                                       u64 *bytes_d2h, const char *l2_lo, const char *l2_hi,
+                                                       int pauses) {
   // Waves that wait on the host link slow the memory accesses of every wave that shares their CU,
   // so this kernel keeps its CUs to itself: a workgroup of 16 wavefronts that claims 128 vector
   // registers per lane fills the register files of a CU's four SIMDs, and no wave of another
@@ -127,6 +128,9 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
   const int n_groups = n_blocks * blockDim.x / kMoveLanes;
   u64 in_b = 0, out_b = 0;
   const int wpar = st.wb_n[1] & 1;
+  // emulated slower tier: rows of this pass that the group moved to or from the backing tier proper
+  int slow_rows = 0;
+  auto in_backing = [&](const char *p) { return pauses > 0 && !(p >= l2_lo && p < l2_hi); };
   auto write_back = [&](int w) {
     if (w >= n_wb) return;
     char *dst = st.wb_dst[w];
@@ -139,6 +143,7 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
       const uint32_t wrb = st.wb_rb[w];
       copy_row_to_host(dst, st.out[wpar] + (size_t)w * st.stride, wrb, lig);
       if (lig == 0) out_b += wrb;
+      slow_rows += in_backing(dst);
     }
     if (wb2_dst) {  // second level: the row this victim pushed out of it goes to the lower tier
       char *dst2 = wb2_dst[w];
@@ -151,6 +156,7 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
         const uint32_t wrb = st.wb_rb[w];
         copy_row_to_host(dst2, (wpar ? out2_odd : out2_even) + (size_t)w * st.stride, wrb, lig);
         if (lig == 0) out_b += wrb;
+        slow_rows += in_backing(dst2);
       }
     }
   };
@@ -180,6 +186,7 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
         }
         if (!made_up) {
           const char *src = ins_src[i];
+          slow_rows += in_backing(src);
 #pragma unroll
           for (int q = 0; q < 4; q++) {
             const uint32_t c = lig * 16 + q * kMoveLanes * 16;
@@ -225,7 +232,14 @@ __global__ __launch_bounds__(kLinkThreads) void transfer_kernel(Staging st, cons
       if (!fresh_row) {
         copy_row(ovf + (size_t)i * st.stride, byp_src[i], brb, lig);
         if (lig == 0) in_b += brb;
+        slow_rows += in_backing(byp_src[i]);
       }
+    }
+    if (pauses > 0) {  // the wavefront pauses once per backing-tier row its groups moved (a bounded delay: no wait on memory)
+      int rows = 0;    // counted over the lanes still in the loop; a pass moves at most five rows per group
+      for (int q = 1; q <= 5; q++) rows += __popcll(__ballot(lig == 0 && slow_rows >= q));
+      for (int z = 0; z < rows * pauses; z++) __builtin_amdgcn_s_sleep(127);
+      slow_rows = 0;
     }
   }
   for (int d = 32; d >= 1; d >>= 1) {
@@ -242,8 +256,9 @@ __global__ void clear_wb_kernel(int32_t *wb_n) {
   if (threadIdx.x == 0) wb_n[0] = 0;
 }
 
-hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, const DeferredInit &di, int k,
-                           const uint32_t *rb_of_table, u64 *bytes_h2d, u64 *bytes_d2h, hipStream_t s) {
+hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l2, const DeferredInit &di,
+                           const Throttle &th, int k, const uint32_t *rb_of_table, u64 *bytes_h2d, u64 *bytes_d2h,
+                           hipStream_t s) {
   // How many waves wait on the host link, and where, decides how the link and the HBM-bound kernels
   // of the other streams slow each other.  Measured on the benchmark workload (step / transfer
   // kernel / prefetch stage / forward kernel while the transfer runs, ms; alone the forward takes
@@ -262,7 +277,8 @@ hipError_t launch_transfer(const BatchBuf *b, const Staging &st, const Level2 &l
                      b ? b->ins_where : nullptr, b ? b->byp_src : nullptr, b ? b->byp_tab : nullptr,
                      b ? b->byp_where : nullptr, b ? b->ovf : nullptr, (b && l2.on) ? b->l2v_src : nullptr,
                      l2.on ? l2.wb2_dst : nullptr, l2.out2[0], l2.out2[1], k, b ? di.tm : nullptr, di.seed, di.std,
-                     b ? b->ins_key : nullptr, b ? b->byp_key : nullptr, bytes_h2d, bytes_d2h);
+                     b ? b->ins_key : nullptr, b ? b->byp_key : nullptr, bytes_h2d, bytes_d2h, l2.lines_lo, l2.lines_hi,
+                     th.pauses);
   hipLaunchKernelGGL(clear_wb_kernel, dim3(1), dim3(64), 0, s, st.wb_n);
   return hipGetLastError();
 }

@@ -256,7 +256,8 @@ def compare_backing_touched(cfg, Wn, Mn, Wp, Mp, touched, ctx: str, tally: Tally
 def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, check_every: int = 1, device="cuda",
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
                pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None, deferred_init=None,
-               flush_every: int = 0, misuse: int = 0, vary_batch: int = 0, touched_only: bool = False):
+               flush_every: int = 0, misuse: int = 0, vary_batch: int = 0, touched_only: bool = False,
+               backing_throttle_ns: int = 0):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -269,6 +270,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     1..batch (the library is created for the full batch).
     flush_every = n ('serial' and 'inline' only, where no batch is in flight between steps): both sides
     flush after every n-th step, the backing tiers are compared, and training goes on.
+    backing_throttle_ns: the library's emulation of a slower backing tier (timing only: nothing may change).
     Cache state, counters and event sets are compared after every `check_every`-th
     prefetch (the library's snapshot is taken right after its prefetch call, the oracle,
     which is strictly sequential, is compared when it reaches that batch)."""
@@ -295,6 +297,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
         max_lookups = max(int(b[0].numel()) for b in batches) + 1
     g = TBE(Wp, Mp, slots, cfg.ways, max_batch or cfg.batch, max_lookups, overlap=overlap, policy=policy, pooling=pooling,
             second_level_factor=second_level_factor, deferred_init=deferred_init)
+    if backing_throttle_ns:
+        g.set_backing_throttle(backing_throttle_ns)
     dev = [(i.to(device), f.to(device)) for i, f in batches]
     snaps = {}
 

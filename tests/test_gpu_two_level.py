@@ -90,3 +90,24 @@ def test_main_config_full_size_two_level():
                     deferred_init=(7, cfg.init_std))
     l2 = st["second_level_total"]
     assert l2["demotions"] > 0 and l2["hits"] > 0 and st["total"]["bypasses"] > 0 and st["late_fetches"] > 0
+
+
+@pytest.mark.parametrize("factor", [0, 2])
+def test_emulated_slow_backing_tier_changes_nothing_but_time(factor):
+    """tbe_set_backing_throttle pauses the host-link kernel after every row it moves to or from the backing
+    tier proper (timing only): cache state, events and values stay those of the oracle, with and without a
+    second level, prefetch ahead and pipelined; values outside 0 .. 1e8 ns are refused."""
+    from paper_2305_01515_amd.tbe import TbeError
+    from test_gpu_parity import small_cfg
+    st = run_parity(small_cfg(synth.FP16, 8, seed=131), steps=8, order="ahead", second_level_factor=factor,
+                    backing_throttle_ns=20000)
+    assert st["total"]["evictions"] > 0
+    cfg = small_cfg(synth.FP32, 4, seed=132, batch=16)
+    from test_gpu_api import make
+    g, _, _ = make(cfg, max_lookups=1 << 16)
+    for bad in (-1, 10 ** 8 + 1):
+        with pytest.raises(TbeError) as e:
+            g.set_backing_throttle(bad)
+        assert e.value.code == -1
+    g.set_backing_throttle(0)
+    g.close()
