@@ -65,6 +65,7 @@ def lib():
         _lib.orc_set_pooling.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_set_second_level.argtypes = [C.c_void_p, C.c_void_p]
         _lib.orc_set_second_level_lock.argtypes = [C.c_void_p, C.c_int32]
+        _lib.orc_set_prefetch_lock.argtypes = [C.c_void_p, C.c_int32]
         _lib.orc_enable_deferred_init.argtypes = [C.c_void_p, C.c_uint64, C.c_double]
         _lib.orc_export_initialised.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.orc_init_sum.restype = C.c_int32
@@ -100,7 +101,8 @@ class Oracle:
 
     def __init__(self, weights: Sequence[np.ndarray], state: Sequence[np.ndarray], cache_slots: Sequence[int],
                  ways: int, threads: int = 1, policy: str = "lru", pooling: str = "sum",
-                 second_level_slots: Optional[Sequence[int]] = None, deferred_init=None, second_level_lock: int = 2):
+                 second_level_slots: Optional[Sequence[int]] = None, deferred_init=None, second_level_lock: int = 2,
+                 prefetch_lock: int = 0):
         self.weights = list(weights)
         self.state = list(state)
         self.ways = ways
@@ -125,6 +127,10 @@ class Oracle:
         rc = lib().orc_set_pooling(self.h, {"sum": 0, "mean": 1, "max": 2}[pooling])
         if rc:
             raise OracleError(rc, "set_pooling")
+        if prefetch_lock:  # batches before the current one whose ways are locked as well (Section 5.7 at that depth)
+            rc = lib().orc_set_prefetch_lock(self.h, prefetch_lock)
+            if rc:
+                raise OracleError(rc, "set_prefetch_lock")
         if second_level_slots is not None:
             s2 = np.ascontiguousarray(second_level_slots, dtype=np.int64)
             assert s2.shape == (T,)

@@ -26,6 +26,9 @@
  *     is the way with the smallest timestamp < k, the lowest way among equals;
  *   - when every way of the set already carries timestamp k the row is not inserted
  *     ("bypass"): it is read from and updated in the lower tier directly;
+ *   - prefetching D batches ahead [Section 5.7: rows fetched for a batch are not evicted before it
+ *     has trained]: optional; the ways stamped k-D .. k-1 are then locked like those stamped k (the
+ *     batches that would still be waiting for their training when batch k is fetched);
  *   - every evicted row is written back (rows are trained on after insertion, so all
  *     lines are dirty); flush writes back every valid line and keeps the tags;
  *   - row-wise Adagrad: m += mean_d(g_d^2); w_d -= lr * g_d / (sqrt(m) + eps), m starts
@@ -162,6 +165,9 @@ typedef struct {
   int64_t cap_arg;
   int forwarded, prefetched;
   int threads;
+  int32_t lock1;       /* first level: ways stamped within the last `lock1` batches before the current one are locked
+                          like the current batch's own (0 = only those; D = the rule of Section 5.7 for a pipeline
+                          that fetches D batches ahead: a row fetched for a batch stays until that batch has trained) */
   int32_t lock2;       /* second level: entries stamped within the last `lock2` batches (the current one included)
                           are not replaced.  2 = the reading the library follows (this batch and the one before);
                           1 = the plain reading of Section 5.7 (this batch only), kept for the comparison of the two */
@@ -237,7 +243,7 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
   if (!specs || T <= 0 || ways <= 0) return NULL;
   orc *h = (orc *)calloc(1, sizeof(orc));
   if (!h) return NULL;
-  h->T = T; h->ways = ways; h->threads = 1; h->lock2 = 2;
+  h->T = T; h->ways = ways; h->threads = 1; h->lock1 = 0; h->lock2 = 2;
   h->tab = (orc_table *)calloc((size_t)T, sizeof(orc_table));
   for (int t = 0; t < T; t++) {
     orc_table *tb = &h->tab[t];
@@ -266,6 +272,15 @@ void *orc_create(const orc_table_spec *specs, int32_t T, int32_t ways) {
 void orc_set_threads(void *hp, int n) { ((orc *)hp)->threads = n > 0 ? n : 1; }
 
 /* second-level cache of slots2[t] entries per table (whole sets of `ways`); only before the first batch */
+/* Batches before the current one whose first-level entries are locked as well (see orc.lock1); before the first batch. */
+int orc_set_prefetch_lock(void *hp, int32_t batches) {
+  orc *h = (orc *)hp;
+  if (!h || batches < 0 || batches > 64) return ORC_EINVAL;
+  if (h->k != 0) return ORC_EORDER;
+  h->lock1 = batches;
+  return ORC_OK;
+}
+
 /* Batches whose second-level entries are locked (see orc.lock2): 1 or 2, before the first batch. */
 int orc_set_second_level_lock(void *hp, int32_t batches) {
   orc *h = (orc *)hp;
@@ -562,7 +577,8 @@ static int prefetch_table(orc *h, int t) {
       s = r % tb->sets;
       for (int w = 0; w < W; w++) {
         int32_t tw = tb->ts[s * W + w], fw = tb->freq[s * W + w];
-        if (tw >= k) continue; /* used by this batch: locked */
+        if (tw >= 1 && tw >= k - h->lock1) continue; /* used by this batch (or one of the lock1 before it): locked;
+                                                         a free way (-1) never is */
         if (victim < 0) { victim = w; continue; }
         int32_t tv = tb->ts[s * W + victim], fv = tb->freq[s * W + victim];
         if (h->policy == ORC_LFU ? (fw < fv || (fw == fv && tw < tv)) : (tw < tv)) victim = w;

@@ -100,8 +100,6 @@ struct tbe_ctx {
   hipStream_t cs = nullptr, as = nullptr;  // compute / prefetch streams (caller's)
   hipStream_t ls = nullptr;                // host-link stream: transfer and commit (own, unless cs == as)
   bool own_ls = false;
-  hipStream_t ws = nullptr;                // side stream of the prefetch stage: the backward's work lists (own; null if cs == as)
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
   hipEvent_t ev_fwd = nullptr;  // the last forward launched
   bool fwd_recorded = false;
@@ -326,7 +324,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     int res = 0;
     HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
     HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->freq,
-                                  h->policy == TBE_POLICY_LFU, h->l2, h->as, h->ws, h->ev_fork, h->ev_join));
+                                  h->policy == TBE_POLICY_LFU, h->l2, h->as));
     // which of the rows to insert have a backing-tier copy that is still being written
     // (by the write-back of the previous batch's victims or by its backward), then move
     // the marks on from the previous batch to this one
@@ -379,9 +377,6 @@ int tbe_destroy(tbe_handle h) {
   (void)hipStreamSynchronize(h->ls);
   (void)hipStreamSynchronize(h->cs);
   if (h->own_ls) (void)hipStreamDestroy(h->ls);
-  if (h->ws) { (void)hipStreamSynchronize(h->ws); (void)hipStreamDestroy(h->ws); }
-  if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
-  if (h->ev_join) (void)hipEventDestroy(h->ev_join);
   h->mem.release();
   if (h->lines2) (void)hipHostFree(h->lines2);
   drop_profile(h);
@@ -514,9 +509,6 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
   if (h->as != h->cs) {
     CREATE_TRY(hipStreamCreateWithFlags(&h->ls, hipStreamNonBlocking));
     h->own_ls = true;
-    CREATE_TRY(hipStreamCreateWithFlags(&h->ws, hipStreamNonBlocking));
-    CREATE_TRY(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
-    CREATE_TRY(hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming));
   }
   CREATE_TRY(h->mem.get(&h->d_slot_m, 4 * slots));
   if (slots) CREATE_TRY(hipMemset(h->d_slot_m, 0, 4 * slots));

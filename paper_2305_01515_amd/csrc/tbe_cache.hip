@@ -849,41 +849,26 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__
 
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
-                              int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s, hipStream_t side,
-                              hipEvent_t ev_fork, hipEvent_t ev_join) {
+                              int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s) {
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
   DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.cnt, g.within_bits, b.d_offsets,
             b.maxp ? b.sorted_within : nullptr, b.uid_sorted, b.sorted_bag, b.uniq_key, b.run_off, b.uniq_sid,
             b.uniq_tab, nullptr};
   run_compaction(d, nullptr, n, n, ss.blk, b.cnt, s);
-  // The backward's work lists need the distinct rows and their runs only, the cache decisions need nothing of
-  // the lists: with a side stream the five small kernels of the lists run beside the probe and the passes after
-  // it (they are chains of short dependent launches, each waiting for the one before), and the stage waits for
-  // them at its end.
-  hipStream_t ws = side ? side : s;
-  if (side) {
-    hipError_t e = hipEventRecord(ev_fork, s);
-    if (e == hipSuccess) e = hipStreamWaitEvent(side, ev_fork, 0);
-    if (e != hipSuccess) return e;
-  }
-  hipLaunchKernelGGL(worklist_count_kernel, dim3(kWorklistBlocks), dim3(256), 0, ws, b.run_off, ss.wl, b.cnt);
-  hipLaunchKernelGGL(worklist_emit_kernel, dim3(kWorklistBlocks), dim3(256), 0, ws, b.run_off, b.uniq_tab, ss.wl, b.mid_idx,
-                     b.heavy, b.heavy_sub, b.hg_count, b.cnt);
-  if (!b.maxp) {  // the tile kernel's chunks and range starts (max pooling takes heavy rows a workgroup each)
-    hipLaunchKernelGGL(heavy_group_kernel, dim3(1), dim3(256), 0, ws, tm, g.T, b.hg_count, b.hg_count + g.T + 1, b.hchunks,
-                       (long long)g.partial_slots, g.heavy_target, b.cnt);
-    hipLaunchKernelGGL(heavy_order_kernel, dim3(g.T), dim3(64), 0, ws, b.hg_count, b.hg_count + g.T + 1, b.heavy,
-                       b.heavy_sub, b.run_off, b.hperm, b.cnt);
-    hipLaunchKernelGGL(heavy_starts_kernel, dim3(256), dim3(256), 0, ws, tm, b.batch, b.heavy, b.uniq_tab, b.run_off,
-                       b.sorted_bag, b.hstart, b.cnt);
-  }
-  if (side) {
-    hipError_t e = hipEventRecord(ev_join, side);
-    if (e != hipSuccess) return e;
-  }
   SetHeadOp h{b.uniq_sid, b.run_off, b.touched};
   run_compaction(h, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s);
+  hipLaunchKernelGGL(worklist_count_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, ss.wl, b.cnt);
+  hipLaunchKernelGGL(worklist_emit_kernel, dim3(kWorklistBlocks), dim3(256), 0, s, b.run_off, b.uniq_tab, ss.wl, b.mid_idx,
+                     b.heavy, b.heavy_sub, b.hg_count, b.cnt);
+  if (!b.maxp) {  // the tile kernel's chunks and range starts (max pooling takes heavy rows a workgroup each)
+    hipLaunchKernelGGL(heavy_group_kernel, dim3(1), dim3(256), 0, s, tm, g.T, b.hg_count, b.hg_count + g.T + 1, b.hchunks,
+                       (long long)g.partial_slots, g.heavy_target, b.cnt);
+    hipLaunchKernelGGL(heavy_order_kernel, dim3(g.T), dim3(64), 0, s, b.hg_count, b.hg_count + g.T + 1, b.heavy,
+                       b.heavy_sub, b.run_off, b.hperm, b.cnt);
+    hipLaunchKernelGGL(heavy_starts_kernel, dim3(256), dim3(256), 0, s, tm, b.batch, b.heavy, b.uniq_tab, b.run_off,
+                       b.sorted_bag, b.hstart, b.cnt);
+  }
   int64_t max_touched = (int64_t)g.total_sets + g.T;
   if (max_touched > n) max_touched = n;
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
@@ -901,10 +886,6 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   ss.tally_waves = run_compaction(st, &b.cnt->n_uniq, 0, n, ss.blk, b.cnt, s) * kScanWavesPerBlock;
   hipLaunchKernelGGL(finalize_kernel, dim3(TBE_FINALIZE_BLOCKS), dim3(256), 0, s, n, sorted_pos, b.uid_sorted, b.loc_u, b.run_off,
                      b.loc, b.d_offsets, g.within_bits, b.cnt);
-  if (side) {
-    hipError_t e = hipStreamWaitEvent(s, ev_join, 0);
-    if (e != hipSuccess) return e;
-  }
   return hipGetLastError();
 }
 

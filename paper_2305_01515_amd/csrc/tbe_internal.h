@@ -248,12 +248,9 @@ struct ClassInfo {
 hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf &b, uint32_t *keys, uint32_t *vals,
                          hipStream_t s);
 hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *result_buf, hipStream_t s);
-// side: a stream for the backward's work lists beside the cache decisions (null: everything on s); ev_fork / ev_join
-// order it behind the dedup pass and make s wait for it at the end
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
-                              int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s, hipStream_t side,
-                              hipEvent_t ev_fork, hipEvent_t ev_join);
+                              int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s);
 // write back the staged victims and (b != null) fetch ahead the rows b's batch inserts
 // Deferred initialisation on read (Section 5.4.2): a row of the backing tier has no value until it is
 // first fetched; the fetch then makes it up instead of reading it.
