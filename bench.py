@@ -235,6 +235,8 @@ def main():
     ap.add_argument("--cache-frac", type=float, default=0.05, help="locality: cached fraction of the rows")
     ap.add_argument("--policy", default="lru", choices=["lru", "lfu"],
                     help="replacement policy; lru is the benchmark's, lfu for the comparison the paper makes")
+    ap.add_argument("--prefetch-depth", type=int, default=1,
+                    help="pipeline this many batches deep (tbe_set_prefetch_depth; 1 = the benchmark's)")
     ap.add_argument("--backing-throttle-ns", type=int, default=0,
                     help="emulate a slower backing tier: the host-link kernel pauses this long per backing-tier row (0 = off)")
     ap.add_argument("--second-level", type=int, default=0,
@@ -352,18 +354,26 @@ def main():
             policy=args.policy, pooling=args.pooling, second_level_factor=args.second_level,
             deferred_init=(cfg.seed, cfg.init_std) if args.deferred_init else None)
 
+    D = args.prefetch_depth
+    pushed = [0]
+
     def run(lo, hi):
-        # next-batch prefetch is issued ahead of the current batch's training
+        # the next batch (the next D batches) are prefetched ahead of the current batch's training
         for s in range(lo, hi):
-            g.prefetch(*batches[s + 1])
+            while pushed[0] < min(s + 1 + D, hi + 1):
+                g.prefetch(*batches[pushed[0]])
+                pushed[0] += 1
             g.forward(batches[s][0], batches[s][1], out)
             g.backward_update(grads[s % len(grads)], cfg.lr, cfg.eps)
 
     if args.backing_throttle_ns:
         g.set_backing_throttle(args.backing_throttle_ns)
+    if D > 1:
+        g.set_prefetch_depth(D)
     g.set_inputs_ready(not args.wait_for_compute)  # all index tensors were generated and synchronised above
     g.set_profiling(True)  # stage brackets from the first launch on, so that the means over all
     g.prefetch(*batches[0])  # launches can be compared with a rocprofv3 --stats run of this command
+    pushed[0] = 1
     run(0, Wm)
     torch.cuda.synchronize()
     s0 = g.stats()
@@ -451,7 +461,7 @@ def main():
                    "tables": T, "batch": cfg.batch, "lookups_per_step": lookups / K,
                    "overlap": not args.no_overlap, "policy": args.policy, "pooling": args.pooling,
                    "second_level_factor": args.second_level, "deferred_init": args.deferred_init,
-                   "backing_throttle_ns": args.backing_throttle_ns},
+                   "backing_throttle_ns": args.backing_throttle_ns, "prefetch_depth": D},
         # The dominant kernel of a step: transfer_kernel (write-back of parked victims beside the fetch-ahead of the
         # missed rows), bound by the host link.  achieved = bytes of the busier direction per launch / mean launch time,
         # measured live in the timed, pipelined region with HIP events on the link stream; peak = PCIe Gen5 x16 per

@@ -50,8 +50,9 @@
  * Optional, each selected by one call before the first batch: LFU instead of LRU
  * (tbe_set_policy), mean or max instead of sum pooling (tbe_set_pooling), a second-level cache in
  * pinned host memory between the two tiers (tbe_enable_second_level), initial values made up on
- * first read instead of stored (tbe_enable_deferred_init), a queue of batches accepted further
- * ahead of training than the one batch the pipeline runs ahead (tbe_set_prefetch_queue).
+ * first read instead of stored (tbe_enable_deferred_init), a pipeline that fetches several batches
+ * ahead (tbe_set_prefetch_depth), a host-side queue of batches in front of tbe_prefetch
+ * (tbe_set_prefetch_queue), an emulated slower backing tier for measurements (tbe_set_backing_throttle).
  */
 #ifndef TBE_H
 #define TBE_H
@@ -245,6 +246,31 @@ int tbe_export_argmax(tbe_handle h, int32_t *d_argmax);
 #define TBE_POLICY_LRU 0
 #define TBE_POLICY_LFU 1
 int tbe_set_policy(tbe_handle h, int32_t policy);
+
+/*
+ * Prefetch depth (Section 5.7: the caches are accessed several batches in advance, and rows fetched for
+ * a batch are not evicted before that batch has trained).  With depth D >= 2 tbe_prefetch may be called
+ * for up to D batches beyond the one in training (or about to train), and each of them is fetched into
+ * its cache lines right away, beside the training of the batches before it.  The rule of Section 5.7 is a
+ * lock: when batch k is decided on, the ways stamped by the batches k - D .. k - 1 -- those that may
+ * still wait for their training -- are locked like the ways of batch k itself, so a miss takes the
+ * evictable way with the smallest timestamp below k - D (free ways first), and bypasses the cache when
+ * the set has none.  Everything else is as at depth 1; pooled outputs and trained values do not depend
+ * on the depth, hit, insert and bypass counts do (more rows bypass).  Rows that an earlier batch
+ * bypassed and has not written back yet are taken from its copies before the forward of the batch that
+ * wants them.  Depth 1 is the default: the next batch is decided on early, but its rows enter their
+ * cache lines only after the batch before it has trained, which needs no lock beyond a batch's own.
+ * Allocates 2 D - 2 more sets of per-batch buffers (TBE_ENOMEM / TBE_EHIP).  depth 1..7 (TBE_EINVAL);
+ * only before the first batch, once, and not together with a second level or a prefetch queue
+ * (TBE_EORDER); max_lookups must be below 2^26 (TBE_ELIMIT).  The index buffers of a prefetched batch
+ * must stay valid and unchanged until its tbe_backward_update has completed.
+ */
+int tbe_set_prefetch_depth(tbe_handle h, int32_t depth);
+/*
+ * The depth in use, and how many rows so far were taken, before a batch's forward, from the copy on which an
+ * earlier batch had trained them as bypassed rows (depth >= 2 only; 0 at depth 1).  Synchronises.
+ */
+int tbe_get_prefetch_depth(tbe_handle h, int32_t *depth, int64_t *rows_from_copies);
 
 /*
  * Queue in front of tbe_prefetch.  With length D > 1 tbe_prefetch accepts up to D batches ahead of

@@ -66,6 +66,9 @@ struct DevAlloc {  // everything hipMalloc'ed, freed together
 
 // Batch buffers rotate over three: the buffer of batch k is still read after k has trained
 // (its bypass list by the commit of batch k+1) while batch k+2 is already being prefetched.
+// A pipeline D batches deep (tbe_set_prefetch_depth) rotates over 2 D + 1: the overflow copies of batch k are
+// read before the forward of every batch up to k + D, and batch k + 2 D + 1 may be prefetched once batch k + D
+// has trained.
 constexpr int kBatchBufs = 3;
 
 struct tbe_ctx {
@@ -90,7 +93,12 @@ struct tbe_ctx {
   float *static_partials = nullptr;  // the same in the library's static scratch array on this handle's GPU
   int device = -1;                   // GPU the handle was created on
   char *lines = nullptr;
-  BatchBuf buf[kBatchBufs]{};
+  BatchBuf buf[kMaxBatchBufs]{};
+  int nbuf = kBatchBufs;        // batch buffers in use
+  int deep = 0;                 // 0: the one-deep pipeline; D >= 2: batches are fetched into the cache up to D ahead
+  hipEvent_t ev_home[kMaxBatchBufs] = {};   // deep pipeline: the write-back of the buffer's bypassed rows
+  bool home_pending[kMaxBatchBufs] = {};    // ... has been enqueued and the rows' marks are still in the map
+  bool home_recorded[kMaxBatchBufs] = {};
   SortScratch ss{};
   Staging st{};
   uint32_t *d_rb = nullptr;  // row bytes of every table
@@ -104,7 +112,7 @@ struct tbe_ctx {
   hipEvent_t ev_fwd = nullptr;  // the last forward launched
   bool fwd_recorded = false;
   int last_trained = -1;        // buffer of the batch whose backward was launched last
-  hipEvent_t ev_inputs = nullptr, ev_ready[kBatchBufs] = {}, ev_trained[kBatchBufs] = {}, ev_probed[kBatchBufs] = {};
+  hipEvent_t ev_inputs = nullptr, ev_ready[kMaxBatchBufs] = {}, ev_trained[kMaxBatchBufs] = {}, ev_probed[kMaxBatchBufs] = {};
   int64_t flush_state_bytes = 0;
   bool inputs_ready = false;  // caller guarantees index / offset buffers are complete when tbe_prefetch is called
   int32_t max_batch = 0;
@@ -112,7 +120,7 @@ struct tbe_ctx {
   int32_t k = 0;
   // pipeline: buffers prefetched and waiting for forward (oldest first), the buffer that
   // was forwarded and waits for its update, and a buffer whose copies wait for that update
-  int pend[2] = {-1, -1};
+  int pend[kMaxBatchBufs] = {-1, -1};
   // batches accepted by tbe_prefetch further ahead than the pipeline runs: their work is issued, in order, as
   // soon as the batch before has been forwarded
   struct Queued { const int64_t *d_indices, *d_offsets; int32_t batch; int64_t n; };
@@ -252,7 +260,7 @@ int device_error_code(int e) { return e == 0 ? 0 : e == 1 ? TBE_EINVAL : TBE_ERA
 
 // After a synchronisation: pick up errors the device recorded.
 int collect_device_errors(tbe_ctx *h) {
-  for (int i = 0; i < kBatchBufs; i++) {
+  for (int i = 0; i < h->nbuf; i++) {
     BatchCounters c;
     HIP_TRY(h, hipMemcpy(&c, h->buf[i].cnt, sizeof(c), hipMemcpyDeviceToHost));
     if (c.err && !h->sticky) {
@@ -279,7 +287,75 @@ int enqueue_commit(tbe_ctx *h, int bi, bool wb_prev) {
     StageTimer tm_(h, TBE_STAGE_COMMIT, h->ls);
     const int prev_mode = !wb_prev ? kPrevKeep : b.parks_prev ? kPrevPark : kPrevWrite;
     HIP_TRY(h, launch_commit(h->d_tm, b, b.prev_bi >= 0 ? &h->buf[b.prev_bi] : nullptr, prev_mode, h->st, h->l2, h->d_rb,
-                             h->d_bytes + 1, h->ls));
+                             h->d_bytes + 1, false, h->ls));
+  }
+  HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->ls));
+  return TBE_OK;
+}
+
+// Pipeline several batches deep (Section 5.7): the batch is fetched into the cache as soon as it is decided on.
+// The ways of the batches that may still wait for their training are locked (ts >= k - D), so its victims and
+// the lines it fills are used by none of them and nothing waits for a backward -- except the rows whose current
+// value is an overflow copy of such a batch: they are copied before this batch's forward (launch_fixup).
+int do_prefetch_deep(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch, int64_t n) {
+  if (h->n_pend + (h->current >= 0 ? 1 : 0) > h->deep)
+    return fail(h, TBE_EORDER, "prefetch: more batches would be ahead of training than the prefetch depth");
+  const int bi = h->k % h->nbuf;
+  BatchBuf &b = h->buf[bi];
+  b.d_indices = d_indices; b.d_offsets = d_offsets; b.batch = batch; b.n = n; b.k = ++h->k;
+  b.mean = h->pooling == TBE_POOL_MEAN;
+  b.maxp = h->pooling == TBE_POOL_MAX;
+  b.parks_prev = false;
+  h->total_lookups += n;
+  h->last_buf = bi;
+  if (h->as != h->cs) {
+    if (!h->inputs_ready) {
+      HIP_TRY(h, hipEventRecord(h->ev_inputs, h->cs));
+      HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_inputs, 0));
+    } else {
+      if (h->fwd_recorded) HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_fwd, 0));
+    }
+    // the buffer last served batch k - (2 D + 1): every batch that read its overflow copies (up to k - D - 1) has
+    // trained, and its bypassed rows have been written back
+    if (h->last_trained >= 0) HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_trained[h->last_trained], 0));
+    if (h->home_recorded[bi]) HIP_TRY(h, hipStreamWaitEvent(h->as, h->ev_home[bi], 0));
+  }
+  {
+    StageTimer tm_(h, TBE_STAGE_PREFETCH, h->as);
+    // batches whose bypassed rows are on their way home in front of this batch's transfer: their marks go
+    // (before this buffer's lists are overwritten, should it be one of them)
+    for (int x = 0; x < h->nbuf; x++)
+      if (h->home_pending[x]) {
+        HIP_TRY(h, launch_unmark_bypassed(h->buf[x], x, h->st, h->as));
+        h->home_pending[x] = false;
+      }
+    HIP_TRY(h, launch_keygen(h->d_tm, h->g, b, h->ss.keys[0], h->ss.vals[0], h->as));
+    int res = 0;
+    HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
+    HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->freq,
+                                  h->policy == TBE_POLICY_LFU, h->l2, h->deep, h->as));
+    const BatchBuf *prev = h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr;
+    HIP_TRY(h, launch_classify_mark_deep(h->d_tm, prev, b, bi, h->st, h->d_bytes + 5, h->as));
+    hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total, h->d_bytes + 2,
+                       (unsigned long long *)nullptr, h->ss.tally, n > 0 ? h->ss.tally_waves : 0);
+    HIP_TRY(h, hipGetLastError());
+  }
+  if (h->ls != h->as) {
+    HIP_TRY(h, hipEventRecord(h->ev_probed[bi], h->as));
+    HIP_TRY(h, hipStreamWaitEvent(h->ls, h->ev_probed[bi], 0));
+  }
+  {
+    StageTimer tm_(h, TBE_STAGE_FILL, h->ls);
+    HIP_TRY(h, launch_transfer(&b, h->st, h->l2, h->di, h->throttle, b.k, h->d_rb, h->d_bytes, h->d_bytes + 1, h->ls));
+  }
+  b.prev_bi = h->prev_buf;
+  h->prev_buf = bi;
+  h->pend[h->n_pend++] = bi;
+  {
+    // the link stream waits for every backward launched so far (tbe_backward_update sees to that), which covers the
+    // batches whose lines this commit may overwrite: they were stamped before k - D
+    StageTimer tm_(h, TBE_STAGE_COMMIT, h->ls);
+    HIP_TRY(h, launch_commit(h->d_tm, b, nullptr, kPrevKeep, h->st, h->l2, h->d_rb, h->d_bytes + 1, true, h->ls));
   }
   HIP_TRY(h, hipEventRecord(h->ev_ready[bi], h->ls));
   return TBE_OK;
@@ -288,6 +364,7 @@ int enqueue_commit(tbe_ctx *h, int bi, bool wb_prev) {
 int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, int32_t batch, int64_t n) {
   if (!d_offsets || batch < 0 || n < 0 || (n > 0 && !d_indices)) return fail(h, TBE_EINVAL, "prefetch: bad argument");
   if (batch > h->max_batch || n > h->max_lookups) return fail(h, TBE_ELIMIT, "prefetch: batch or lookups above the sizes given to tbe_create");
+  if (h->deep) return do_prefetch_deep(h, d_indices, d_offsets, batch, n);
   if (h->n_pend + (h->current >= 0 ? 1 : 0) > 1) return fail(h, TBE_EORDER, "prefetch: more than one batch would be ahead of training");
   const int bi = h->k % kBatchBufs;  // free: at most the batch before this one is still in use
   BatchBuf &b = h->buf[bi];
@@ -324,7 +401,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     int res = 0;
     HIP_TRY(h, launch_sort(h->g, h->ss, n, &res, h->as));
     HIP_TRY(h, launch_dedup_probe(h->d_tm, h->g, b, h->ss, h->ss.keys[res], h->ss.vals[res], h->tags, h->ts, h->freq,
-                                  h->policy == TBE_POLICY_LFU, h->l2, h->as));
+                                  h->policy == TBE_POLICY_LFU, h->l2, 0, h->as));
     // which of the rows to insert have a backing-tier copy that is still being written
     // (by the write-back of the previous batch's victims or by its backward), then move
     // the marks on from the previous batch to this one
@@ -382,10 +459,11 @@ int tbe_destroy(tbe_handle h) {
   drop_profile(h);
   if (h->ev_inputs) (void)hipEventDestroy(h->ev_inputs);
   if (h->ev_fwd) (void)hipEventDestroy(h->ev_fwd);
-  for (int i = 0; i < kBatchBufs; i++) {
+  for (int i = 0; i < kMaxBatchBufs; i++) {
     if (h->ev_ready[i]) (void)hipEventDestroy(h->ev_ready[i]);
     if (h->ev_trained[i]) (void)hipEventDestroy(h->ev_trained[i]);
     if (h->ev_probed[i]) (void)hipEventDestroy(h->ev_probed[i]);
+    if (h->ev_home[i]) (void)hipEventDestroy(h->ev_home[i]);
   }
   delete h;
   return TBE_OK;
@@ -638,8 +716,48 @@ int tbe_prefetch(tbe_handle h, const int64_t *d_indices, const int64_t *d_offset
   return do_prefetch(h, d_indices, d_offsets, batch, num_lookups);
 }
 
+int tbe_set_prefetch_depth(tbe_handle h, int32_t depth) {
+  if (!h) return TBE_EINVAL;
+  if (depth < 1 || 2 * depth + 1 > kMaxBatchBufs) return fail(h, TBE_EINVAL, "set_prefetch_depth: depth must be 1..7");
+  if (h->k != 0) return fail(h, TBE_EORDER, "set_prefetch_depth: batches have been prefetched already");
+  if (h->deep) return fail(h, TBE_EORDER, "set_prefetch_depth: already set");
+  if (depth == 1) return TBE_OK;  // the pipeline as it is
+  if (h->l2.on) return fail(h, TBE_EORDER, "set_prefetch_depth: not together with a second level");
+  if (h->depth != 1) return fail(h, TBE_EORDER, "set_prefetch_depth: not together with a prefetch queue");
+  if (h->max_lookups > (int64_t)kWhereBufIndex) return fail(h, TBE_ELIMIT, "set_prefetch_depth: max_lookups must be below 2^26");
+  const int want = 2 * depth + 1;
+  for (int i = h->nbuf; i < want; i++) {
+    int rc = alloc_batchbuf(h, h->buf[i], h->max_lookups);
+    if (rc) return rc;
+    if (h->pooling == TBE_POOL_MAX) {
+      HIP_TRY(h, h->mem.get(&h->buf[i].argpos, 4 * (size_t)h->max_batch * (size_t)h->g.sum_dim));
+      HIP_TRY(h, h->mem.get(&h->buf[i].sorted_within, 4 * (size_t)std::max<int64_t>(h->max_lookups, 1)));
+    }
+    HIP_TRY(h, hipEventCreateWithFlags(&h->ev_ready[i], hipEventDisableTiming));
+    HIP_TRY(h, hipEventCreateWithFlags(&h->ev_trained[i], hipEventDisableTiming));
+    HIP_TRY(h, hipEventCreateWithFlags(&h->ev_probed[i], hipEventDisableTiming));
+    h->nbuf = i + 1;
+  }
+  for (int i = 0; i < want; i++) HIP_TRY(h, hipEventCreateWithFlags(&h->ev_home[i], hipEventDisableTiming));
+  HIP_TRY(h, hipDeviceSynchronize());
+  h->deep = depth;
+  return TBE_OK;
+}
+
+int tbe_get_prefetch_depth(tbe_handle h, int32_t *depth, int64_t *rows_from_copies) {
+  if (!h || !depth || !rows_from_copies) return TBE_EINVAL;
+  int rc = sync_all(h);
+  if (rc) return rc;
+  unsigned long long n = 0;
+  HIP_TRY(h, hipMemcpy(&n, h->d_bytes + 6, sizeof(n), hipMemcpyDeviceToHost));
+  *depth = h->deep ? h->deep : 1;
+  *rows_from_copies = (int64_t)n;
+  return TBE_OK;
+}
+
 int tbe_set_prefetch_queue(tbe_handle h, int32_t depth) {
   if (!h) return TBE_EINVAL;
+  if (h->deep) return fail(h, TBE_EORDER, "set_prefetch_queue: not together with a prefetch depth above one");
   if (depth < 1 || depth > 64) return fail(h, TBE_EINVAL, "set_prefetch_queue: length must be 1..64");
   if (!h->queued.empty()) return fail(h, TBE_EORDER, "set_prefetch_queue: batches are queued");
   h->depth = depth;
@@ -665,7 +783,7 @@ int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets
   if (b.d_indices != d_indices || b.d_offsets != d_offsets || b.batch != batch || b.n != num_lookups)
     return fail(h, TBE_EMISMATCH, "forward: buffers differ from the pending prefetch");
   if (h->deferred == bi) return fail(h, TBE_EORDER, "forward: the batch before this one has not been updated");
-  h->pend[0] = h->pend[1];
+  for (int i = 1; i < h->n_pend; i++) h->pend[i - 1] = h->pend[i];
   h->n_pend--;
   if (h->as != h->cs) {
     HIP_TRY(h, hipStreamWaitEvent(h->cs, h->ev_ready[bi], 0));
@@ -673,6 +791,11 @@ int tbe_forward(tbe_handle h, const int64_t *d_indices, const int64_t *d_offsets
     // over (measured: the forward's bracket began 0.15 ms before the commit it waits for had ended).
     // A kernel is held back by the wait, so an empty one in front of the bracket pins its beginning.
     if (h->profiling) hipLaunchKernelGGL(stream_pin_kernel, dim3(1), dim3(64), 0, h->cs);
+  }
+  if (h->deep) {  // rows whose value was an overflow copy of a batch that had not trained when this one was fetched
+    OverflowCopies oc{};
+    for (int x = 0; x < h->nbuf; x++) oc.of_buf[x] = h->buf[x].ovf;
+    HIP_TRY(h, launch_fixup(h->d_tm, b, oc, h->st, h->d_rb, h->d_bytes + 6, h->cs));
   }
   {
     StageTimer tm_(h, TBE_STAGE_FORWARD, h->cs);
@@ -737,6 +860,11 @@ static int backward_update_with(tbe_ctx *h, const float *d_grad_out, float lr, f
     const BatchBuf &b = h->buf[bi];
     const BatchBuf *parked_prev = (b.parks_prev && b.prev_bi >= 0) ? &h->buf[b.prev_bi] : nullptr;
     HIP_TRY(h, launch_ovf_writeback(b, parked_prev, h->st, h->d_rb, h->d_bytes + 1, h->ls));
+    if (h->deep) {  // the marks of these rows go with the next prefetch; the buffer is free once they are home
+      HIP_TRY(h, hipEventRecord(h->ev_home[bi], h->ls));
+      h->home_recorded[bi] = true;
+      h->home_pending[bi] = true;
+    }
   }
   return pump_queue(h);
 }
@@ -778,6 +906,11 @@ int tbe_flush(tbe_handle h) {
     h->deferred = -1;
     h->queued.clear();
   }
+  for (int x = 0; x < h->nbuf; x++)  // deep pipeline: bypassed rows that went home after their backward
+    if (h->home_pending[x]) {
+      HIP_TRY(h, launch_unmark_bypassed(h->buf[x], x, h->st, h->cs));
+      h->home_pending[x] = false;
+    }
   HIP_TRY(h, launch_transfer(nullptr, h->st, h->l2, h->di, h->throttle, 0, h->d_rb, h->d_bytes, h->d_bytes + 1, h->cs));  // parked victims first
   if (h->prev_buf >= 0) {
     // Every copy in the backing tier is current now, so the next batch must find no row marked
@@ -823,6 +956,7 @@ int tbe_enable_second_level(tbe_handle h, int32_t factor) {
   if (factor < 1 || factor > 1024) return fail(h, TBE_EINVAL, "enable_second_level: factor must be 1..1024");
   if (h->k != 0) return fail(h, TBE_EORDER, "enable_second_level: batches have been prefetched already");
   if (h->l2.on) return fail(h, TBE_EORDER, "enable_second_level: already enabled");
+  if (h->deep) return fail(h, TBE_EORDER, "enable_second_level: not together with a prefetch depth above one");
   if (h->st.max_inserts >= (1ll << 29)) return fail(h, TBE_ELIMIT, "enable_second_level: too many possible inserts per batch");
   int64_t slots2 = 0;
   size_t bytes2 = 0;
@@ -851,7 +985,7 @@ int tbe_enable_second_level(tbe_handle h, int32_t factor) {
   HIP_TRY(h, hipMemset(l2.wb2_dst, 0, 8 * M ? 8 * M : 8));
   HIP_TRY(h, h->mem.get(&h->d_l2tot, 8 * 4));
   HIP_TRY(h, hipMemset(h->d_l2tot, 0, 8 * 4));
-  for (int i = 0; i < kBatchBufs; i++) {
+  for (int i = 0; i < h->nbuf; i++) {
     BatchBuf &b = h->buf[i];
     const size_t N = (size_t)std::max<int64_t>(h->max_lookups, 1);
     HIP_TRY(h, h->mem.get(&b.src2, 4 * N));
@@ -953,7 +1087,7 @@ int tbe_set_pooling(tbe_handle h, int32_t pooling) {
     return fail(h, TBE_EINVAL, "set_pooling: unknown pooling mode");
   if (h->k != 0) return fail(h, TBE_EORDER, "set_pooling: batches have been prefetched already");
   if (pooling == TBE_POOL_MAX && !h->buf[0].argpos) {  // who supplied each maximum, and the lookups' positions in their bags
-    for (int i = 0; i < kBatchBufs; i++) {
+    for (int i = 0; i < h->nbuf; i++) {
       HIP_TRY(h, h->mem.get(&h->buf[i].argpos, 4 * (size_t)h->max_batch * (size_t)h->g.sum_dim));
       HIP_TRY(h, h->mem.get(&h->buf[i].sorted_within, 4 * (size_t)std::max<int64_t>(h->max_lookups, 1)));
     }

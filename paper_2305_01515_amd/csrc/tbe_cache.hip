@@ -599,6 +599,7 @@ __device__ inline int32_t add_saturating(int32_t a, int32_t b) {  // a, b >= 0
 
 template <bool LFU, bool L2>
 __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restrict__ tm, int T, int W, int32_t k,
+                                                      int32_t evictable_below,
                                                       const uint32_t *__restrict__ uniq_key,
                                                       const int32_t *__restrict__ uniq_tab,
                                                       const uint2 *__restrict__ touched, int32_t *__restrict__ tags,
@@ -663,12 +664,14 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
     __syncthreads();
     // phase 2: rank the evictable ways
     const int32_t my_ts = l_ts[lane];
-    const bool cand = lane < W && my_ts < k;
+    // evictable: free ways (-1) and ways stamped before evictable_below = max(k - lock, 1): the ways of this batch
+    // and, in a pipeline `lock` batches deep, of the batches that may still be waiting for their training
+    const bool cand = lane < W && my_ts < evictable_below;
     const int32_t my_freq = l_freq[lane];
     int rank = 0;
     for (int w = 0; w < W; w++) {
       const int32_t tw = l_ts[w];
-      if (tw >= k) continue;
+      if (tw >= evictable_below) continue;
       bool first = tw < my_ts || (tw == my_ts && w < lane);
       if (LFU) {
         const int32_t fw = l_freq[w];
@@ -849,7 +852,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(int n, const uint32_t *__
 
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
-                              int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s) {
+                              int32_t *freq, bool lfu, const Level2 &l2, int lock, hipStream_t s) {
   const int n = (int)b.n;
   if (n == 0) return hipSuccess;
   DedupOp d{tm, g.T, sorted_keys, sorted_pos, b.bag_of_pos, b.cnt, g.within_bits, b.d_offsets,
@@ -874,7 +877,7 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
   auto probe = l2.on ? (lfu ? probe_kernel<true, true> : probe_kernel<false, true>)
                      : (lfu ? probe_kernel<true, false> : probe_kernel<false, false>);
-  hipLaunchKernelGGL(probe, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.uniq_key, b.uniq_tab, b.touched,
+  hipLaunchKernelGGL(probe, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.k - lock > 1 ? b.k - lock : 1, b.uniq_key, b.uniq_tab, b.touched,
                      tags, ts, freq, b.run_off, b.loc_u, b.status, b.old_tag, l2.tags2, l2.ts2, l2.factor,
                      l2.on ? b.src2 : nullptr, l2.on ? b.dst2 : nullptr, l2.on ? b.evict2 : nullptr, b.cnt);
   StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.uniq_tab, b.ins_idx, b.ins_tab, b.ins_slot,

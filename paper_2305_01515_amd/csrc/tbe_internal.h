@@ -39,6 +39,11 @@ constexpr int kHeavyMaxRanges = 128;
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
 constexpr uint32_t kWhereParked = 0x40000000u;    // among the victims the batch before parked
 constexpr uint32_t kWhereIndex = 0x3FFFFFFFu;
+// With a pipeline several batches deep the overflow copies of more than one batch are alive: the code of such a
+// copy also names its batch buffer (bits 26..29; the index is then 26 bits wide).  Zero in the one-deep pipeline.
+constexpr int kWhereBufShift = 26;
+constexpr uint32_t kWhereBufIndex = (1u << kWhereBufShift) - 1u;
+constexpr int kMaxBatchBufs = 16;
 
 // Per-lookup location word (BatchBuf::loc): where the lookup's row is while its batch trains.
 constexpr uint32_t kLocOverflow = 0x80000000u;  // index = overflow slot of a bypassed row, else global cache slot
@@ -248,9 +253,10 @@ struct ClassInfo {
 hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf &b, uint32_t *keys, uint32_t *vals,
                          hipStream_t s);
 hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *result_buf, hipStream_t s);
+// lock: batches before the current one whose ways are locked like the current batch's own (0 in the one-deep pipeline)
 hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const BatchBuf &b, SortScratch &ss,
                               const uint32_t *sorted_keys, const uint32_t *sorted_pos, int32_t *tags, int32_t *ts,
-                              int32_t *freq, bool lfu, const Level2 &l2, hipStream_t s);
+                              int32_t *freq, bool lfu, const Level2 &l2, int lock, hipStream_t s);
 // write back the staged victims and (b != null) fetch ahead the rows b's batch inserts
 // Deferred initialisation on read (Section 5.4.2): a row of the backing tier has no value until it is
 // first fetched; the fetch then makes it up instead of reading it.
@@ -271,8 +277,29 @@ hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *pp, const B
 // prev_mode: what becomes of prev's overflow copies: kPrevKeep (nothing), kPrevWrite (to the backing tier now),
 // kPrevPark (among this batch's parked victims: the next transfer writes them)
 constexpr int kPrevKeep = 0, kPrevWrite = 1, kPrevPark = 2;
+// deep: the pipeline is several batches deep -- rows whose current value is an overflow copy of a batch that may
+// not have trained yet are left to launch_fixup
 hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, int prev_mode, const Staging &st,
-                         const Level2 &l2, const uint32_t *rb_of_table, unsigned long long *bytes_d2h, hipStream_t s);
+                         const Level2 &l2, const uint32_t *rb_of_table, unsigned long long *bytes_d2h, bool deep,
+                         hipStream_t s);
+// ---- pipeline several batches deep (Section 5.7) ----
+// The overflow copies of every batch buffer, by buffer number.
+struct OverflowCopies {
+  const char *of_buf[kMaxBatchBufs];
+};
+// which of cur's rows are late (as launch_classify_mark), then: prev's victims are home with cur's transfer, prev's
+// bypassed rows keep their marks (they go home after prev's backward: launch_unmark_bypassed), cur's rows are
+// entered -- its bypassed rows with the number of its buffer
+hipError_t launch_classify_mark_deep(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, int cur_buf,
+                                     const Staging &st, unsigned long long *n_late, hipStream_t s);
+// the marks of b's bypassed rows go, unless a later batch has entered the row again (the write-back that follows
+// b's backward is on the link stream in front of every later transfer)
+hipError_t launch_unmark_bypassed(const BatchBuf &b, int buf, const Staging &st, hipStream_t s);
+// before b's forward, on the compute stream (every earlier batch has trained): the rows of b whose current value
+// was an overflow copy of an earlier batch when b's commit ran are copied from there to where b uses them, and
+// the accumulators of those it inserted are taken over again
+hipError_t launch_fixup(const TableMeta *tm, const BatchBuf &b, const OverflowCopies &oc, const Staging &st,
+                        const uint32_t *rb_of_table, unsigned long long *n_copied, hipStream_t s);
 // after the batch's backward: its bypassed rows go from their HBM copies to the backing tier
 // parked_prev: the batch whose overflow copies b's commit parked and no transfer has written yet (else null)
 hipError_t launch_ovf_writeback(const BatchBuf &b, const BatchBuf *parked_prev, const Staging &st,

@@ -299,9 +299,9 @@ __global__ __launch_bounds__(256) void mark_kernel(const TableMeta *__restrict__
                                                    char *const *__restrict__ l2v_src,
                                                    const uint32_t *__restrict__ l2v_key, uint32_t max_inserts,
                                                    uint32_t *where, int vic_mode, int byp_mode,
-                                                   const BatchCounters *next_cnt) {
+                                                   const BatchCounters *next_cnt, uint32_t overflow_code) {
   if (cnt->err) return;
-  const int n_ins = vic_mode == kMarkKeep ? 0 : cnt->n_ins, n_byp = cnt->n_byp;
+  const int n_ins = vic_mode == kMarkKeep ? 0 : cnt->n_ins, n_byp = byp_mode == kMarkKeep ? 0 : cnt->n_byp;
   const int set = vic_mode != kMarkClear;
   const uint32_t park_base = (byp_mode == kMarkParked && next_cnt) ? (uint32_t)next_cnt->n_ins : 0u;
   const int stride = gridDim.x * blockDim.x;
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(256) void mark_kernel(const TableMeta *__restrict__
       if (l2v_src && l2v_src[i]) where[l2v_key[i]] = set ? (kWhereParked | (max_inserts + (uint32_t)i)) : 0u;
     } else {
       const uint32_t j = (uint32_t)(i - n_ins);
-      where[byp_key[j]] = byp_mode == kMarkOverflow ? (kWhereOverflow | j) : byp_mode == kMarkParked ? (kWhereParked | (park_base + j)) : 0u;
+      where[byp_key[j]] = byp_mode == kMarkOverflow ? (overflow_code | j) : byp_mode == kMarkParked ? (kWhereParked | (park_base + j)) : 0u;
     }
   }
 }
@@ -356,14 +356,14 @@ hipError_t launch_classify_mark(const TableMeta *tm, const BatchBuf *pp, const B
   if (pp)
     hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, pp->cnt, pp->ins_tab, pp->ins_old, pp->byp_key,
                        (char *const *)nullptr, (const uint32_t *)nullptr, M, st.where, kMarkKeep, kMarkClear,
-                       (const BatchCounters *)nullptr);
+                       (const BatchCounters *)nullptr, kWhereOverflow);
   if (prev)
     hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, prev->cnt, prev->ins_tab, prev->ins_old, prev->byp_key,
                        l2.on ? prev->l2v_src : nullptr, prev->l2v_key, M, st.where, kMarkClear,
-                       cur.parks_prev ? kMarkParked : kMarkClear, cur.cnt);
+                       cur.parks_prev ? kMarkParked : kMarkClear, cur.cnt, kWhereOverflow);
   hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, cur.cnt, cur.ins_tab, cur.ins_old, cur.byp_key,
                      l2.on ? cur.l2v_src : nullptr, cur.l2v_key, M, st.where, kMarkOverflow, kMarkOverflow,
-                     (const BatchCounters *)nullptr);
+                     (const BatchCounters *)nullptr, kWhereOverflow);
   return hipGetLastError();
 }
 
@@ -374,10 +374,86 @@ hipError_t launch_unmark(const TableMeta *tm, const BatchBuf &last, const BatchB
   if (parked_prev)
     hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, parked_prev->cnt, parked_prev->ins_tab,
                        parked_prev->ins_old, parked_prev->byp_key, (char *const *)nullptr, (const uint32_t *)nullptr,
-                       (uint32_t)st.max_inserts, st.where, kMarkKeep, kMarkClear, (const BatchCounters *)nullptr);
+                       (uint32_t)st.max_inserts, st.where, kMarkKeep, kMarkClear, (const BatchCounters *)nullptr, kWhereOverflow);
   hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, last.cnt, last.ins_tab, last.ins_old, last.byp_key,
                      l2.on ? last.l2v_src : nullptr, last.l2v_key, (uint32_t)st.max_inserts, st.where, kMarkClear, kMarkClear,
-                     (const BatchCounters *)nullptr);
+                     (const BatchCounters *)nullptr, kWhereOverflow);
+  return hipGetLastError();
+}
+
+// ---- pipeline several batches deep ----
+hipError_t launch_classify_mark_deep(const TableMeta *tm, const BatchBuf *prev, const BatchBuf &cur, int cur_buf,
+                                     const Staging &st, u64 *n_late, hipStream_t s) {
+  const uint32_t M = (uint32_t)st.max_inserts;
+  hipLaunchKernelGGL(classify_kernel, dim3(512), dim3(256), 0, s, cur.cnt, cur.ins_key, cur.byp_key, st.where,
+                     cur.ins_where, cur.byp_where, st.wb_skip[(cur.k - 1) & 1], n_late);
+  if (prev)
+    hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, prev->cnt, prev->ins_tab, prev->ins_old, prev->byp_key,
+                       (char *const *)nullptr, (const uint32_t *)nullptr, M, st.where, kMarkClear, kMarkKeep,
+                       (const BatchCounters *)nullptr, kWhereOverflow);
+  hipLaunchKernelGGL(mark_kernel, dim3(512), dim3(256), 0, s, tm, cur.cnt, cur.ins_tab, cur.ins_old, cur.byp_key,
+                     (char *const *)nullptr, (const uint32_t *)nullptr, M, st.where, kMarkOverflow, kMarkOverflow,
+                     (const BatchCounters *)nullptr, kWhereOverflow | ((uint32_t)cur_buf << kWhereBufShift));
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void unmark_bypassed_kernel(const BatchCounters *cnt, const uint32_t *__restrict__ byp_key,
+                                                              uint32_t *where, uint32_t overflow_code) {
+  if (cnt->err) return;
+  const int n_byp = cnt->n_byp;
+  for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n_byp; j += gridDim.x * blockDim.x) {
+    uint32_t *w = where + byp_key[j];
+    if (*w == (overflow_code | (uint32_t)j)) *w = 0u;  // a later batch's entry for the same row stays
+  }
+}
+
+hipError_t launch_unmark_bypassed(const BatchBuf &b, int buf, const Staging &st, hipStream_t s) {
+  hipLaunchKernelGGL(unmark_bypassed_kernel, dim3(512), dim3(256), 0, s, b.cnt, b.byp_key, st.where,
+                     kWhereOverflow | ((uint32_t)buf << kWhereBufShift));
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fixup_kernel(const TableMeta *__restrict__ tm, const BatchCounters *cnt,
+                                                    const int32_t *__restrict__ ins_tab,
+                                                    const uint32_t *__restrict__ ins_where,
+                                                    const int32_t *__restrict__ ins_slot,
+                                                    const uint32_t *__restrict__ ins_key,
+                                                    const int32_t *__restrict__ byp_tab,
+                                                    const uint32_t *__restrict__ byp_where, char *__restrict__ ovf,
+                                                    OverflowCopies oc, uint32_t stride,
+                                                    const uint32_t *__restrict__ rb_of_table, u64 *n_copied) {
+  if (cnt->err) return;
+  const int n_ins = cnt->n_ins, n_byp = cnt->n_byp;
+  const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
+  const int lig = threadIdx.x % kMoveLanes;
+  const int n_groups = gridDim.x * blockDim.x / kMoveLanes;
+  unsigned int copied = 0;
+  for (int i = group; i < n_ins + n_byp; i += n_groups) {
+    const bool ins = i < n_ins;
+    const uint32_t code = ins ? ins_where[i] : byp_where[i - n_ins];
+    if (!(code & kWhereOverflow)) continue;
+    copied += lig == 0;
+    const char *src = oc.of_buf[(code >> kWhereBufShift) & (kMaxBatchBufs - 1)] + (size_t)(code & kWhereBufIndex) * stride;
+    if (ins) {
+      const TableMeta &m = tm[ins_tab[i]];
+      const int slot = ins_slot[i];
+      copy_row(m.lines + (size_t)(slot - m.slot_base) * m.row_bytes, src, m.row_bytes, lig);
+      // the row's accumulator was updated among those of all rows while it trained as a bypassed row
+      if (lig == 0) m.slot_m[slot - m.slot_base] = m.dev_m[row_of_key(m, ins_key[i])];
+    } else {
+      const int j = i - n_ins;
+      copy_row(ovf + (size_t)j * stride, src, rb_of_table[byp_tab[j]], lig);
+    }
+  }
+  for (int d = 32; d >= 1; d >>= 1) copied += __shfl_xor(copied, d);
+  if ((threadIdx.x & 63) == 0 && copied) atomicAdd(n_copied, (u64)copied);
+}
+
+hipError_t launch_fixup(const TableMeta *tm, const BatchBuf &b, const OverflowCopies &oc, const Staging &st,
+                        const uint32_t *rb_of_table, u64 *n_copied, hipStream_t s) {
+  if (b.n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fixup_kernel, dim3(1024), dim3(256), 0, s, tm, b.cnt, b.ins_tab, b.ins_where, b.ins_slot, b.ins_key,
+                     b.byp_tab, b.byp_where, b.ovf, oc, st.stride, rb_of_table, n_copied);
   return hipGetLastError();
 }
 
@@ -403,7 +479,7 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
                                                      char *const *__restrict__ l2v_dst, char **wb2_dst,
                                                      const char *__restrict__ out2_prev,
                                                      const uint32_t *__restrict__ rb_of_table,
-                                                     const uint32_t *__restrict__ ins_key, u64 *bytes_d2h) {
+                                                     const uint32_t *__restrict__ ins_key, u64 *bytes_d2h, int deep) {
   const uint32_t M = (uint32_t)st.max_inserts;  // map codes kWhereParked | (M + i): rows staged in out2
   const int n_prev = (prev_cnt && prev_cnt->err == 0) ? prev_cnt->n_byp : 0;
   const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
@@ -456,7 +532,9 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
     const uint32_t rb = m.row_bytes;
     char *line = m.lines + (size_t)(slot - m.slot_base) * rb;
     const uint32_t ix = code & kWhereIndex;
-    const char *src = code == 0             ? st.in + (size_t)i * st.stride
+    // (deep pipeline: an overflow copy may belong to a batch that has not trained yet -- the line gets the staging
+    //  slot's content for now and the value, with its accumulator, before this batch's forward: fixup_kernel)
+    const char *src = (code == 0 || (deep && (code & kWhereOverflow))) ? st.in + (size_t)i * st.stride
                       : (code & kWhereOverflow) ? prev_ovf + (size_t)ix * st.stride
                       : (out2_prev && ix >= M)  ? out2_prev + (size_t)(ix - M) * st.stride
                                                 : st.out[ppar] + (size_t)ix * st.stride;
@@ -485,7 +563,7 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
   }
   for (int j = group; j < n_byp; j += n_groups) {  // late bypassed rows
     const uint32_t code = byp_where[j];
-    if (code == 0) continue;
+    if (code == 0 || (deep && (code & kWhereOverflow))) continue;
     const uint32_t ix = code & kWhereIndex;
     const char *src = (code & kWhereOverflow) ? prev_ovf + (size_t)ix * st.stride
                       : (out2_prev && ix >= M) ? out2_prev + (size_t)(ix - M) * st.stride
@@ -556,13 +634,13 @@ hipError_t launch_ovf_writeback(const BatchBuf &b, const BatchBuf *parked_prev, 
 }
 
 hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, int prev_mode, const Staging &st,
-                         const Level2 &l2, const uint32_t *rb_of_table, u64 *bytes_d2h, hipStream_t s) {
+                         const Level2 &l2, const uint32_t *rb_of_table, u64 *bytes_d2h, bool deep, hipStream_t s) {
   hipLaunchKernelGGL(commit_kernel, dim3(4096), dim3(256), 0, s, tm, st, b.cnt, b.ins_tab, b.ins_where, b.ins_slot,
                      b.ins_old, b.byp_tab, b.byp_where, b.ovf, prev ? prev->cnt : nullptr,
                      prev ? prev->byp_src : nullptr, prev ? prev->byp_tab : nullptr, prev ? prev->ovf : nullptr,
                      prev ? prev_mode : kPrevKeep, b.k, l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr,
                      l2.on ? b.l2v_dst : nullptr, l2.on ? l2.wb2_dst : nullptr, l2.out2[(b.k & 1) ^ 1], rb_of_table,
-                     b.ins_key, bytes_d2h);
+                     b.ins_key, bytes_d2h, deep ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
            "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling",
-           "tbe_set_prefetch_queue", "tbe_set_backing_throttle", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax", "tbe_backward_update_static", "tbe_import_cache_freq"]
+           "tbe_set_prefetch_queue", "tbe_set_prefetch_depth", "tbe_get_prefetch_depth", "tbe_set_backing_throttle", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax", "tbe_backward_update_static", "tbe_import_cache_freq"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1, "max": 2}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_combine": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_heavy": 7, "backward": 8}
@@ -90,6 +90,8 @@ def lib() -> C.CDLL:
         l.tbe_export_argmax.argtypes = [vp, vp]
         l.tbe_enable_second_level.argtypes = [vp, i32]
         l.tbe_set_prefetch_queue.argtypes = [vp, i32]
+        l.tbe_set_prefetch_depth.argtypes = [vp, i32]
+        l.tbe_get_prefetch_depth.argtypes = [vp, C.POINTER(i32), C.POINTER(i64)]
         l.tbe_set_backing_throttle.argtypes = [vp, i64]
         l.tbe_enable_deferred_init.argtypes = [vp, C.c_uint64, C.c_float]
         l.tbe_export_initialised.argtypes = [vp, i32, vp]
@@ -286,6 +288,18 @@ class TBE:
     def set_prefetch_queue(self, length: int):
         self._check(lib().tbe_set_prefetch_queue(self._h, length), "tbe_set_prefetch_queue")
         self._depth = length  # tensors of queued batches are kept alive that much longer
+
+    def set_prefetch_depth(self, depth: int):
+        """pipeline `depth` batches deep (before the first batch): tbe_prefetch may run that many batches ahead"""
+        self._check(lib().tbe_set_prefetch_depth(self._h, depth), "tbe_set_prefetch_depth")
+        # the library's batch buffers then rotate over 2 depth + 1
+        self._trained = collections.deque(self._trained, maxlen=max(3, 2 * depth + 1))
+
+    def prefetch_depth(self):
+        """(depth, rows taken from an earlier batch's overflow copies before a forward)"""
+        d, n = C.c_int32(), C.c_int64()
+        self._check(lib().tbe_get_prefetch_depth(self._h, C.byref(d), C.byref(n)), "tbe_get_prefetch_depth")
+        return int(d.value), int(n.value)
 
     def set_backing_throttle(self, ns_per_row: int):
         self._check(lib().tbe_set_backing_throttle(self._h, ns_per_row), "tbe_set_backing_throttle")

@@ -262,6 +262,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
               'early'    prefetch(k+1) is issued before forward(k)
+              'pipeD'    pipeline D batches deep (tbe_set_prefetch_depth): the batches up to k+D are prefetched before
+                         forward(k); the oracle locks the ways of the D batches before the current one as well
     misuse = seed (0: off): between the regular calls, calls that the library must refuse -- an update with
     nothing forwarded, a second forward, a flush with a batch in flight, a forward whose buffers are not those
     of the pending prefetch, a batch above the sizes given at creation, a change of policy or pooling after
@@ -284,8 +286,9 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             wn.fill(np.nan)
     slots = [tc.cache_slots for tc in cfg.tables]
     slots2 = [second_level_factor * (s // cfg.ways) * cfg.ways for s in slots] if second_level_factor else None
+    pipe_depth = int(order[4:]) if order.startswith("pipe") else 0
     o = Oracle(Wn, Mn, slots, cfg.ways, threads=oracle_threads, policy=policy, pooling=pooling, second_level_slots=slots2,
-               deferred_init=deferred_init)
+               deferred_init=deferred_init, prefetch_lock=pipe_depth if pipe_depth >= 2 else 0)
     stream = synth.BatchStream(cfg, device="cpu")
     batches = [stream.next() for _ in range(steps)]
     sizes = [cfg.batch] * steps
@@ -299,6 +302,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             second_level_factor=second_level_factor, deferred_init=deferred_init)
     if backing_throttle_ns:
         g.set_backing_throttle(backing_throttle_ns)
+    if pipe_depth:
+        g.set_prefetch_depth(pipe_depth)
     dev = [(i.to(device), f.to(device)) for i, f in batches]
     snaps = {}
 
@@ -403,6 +408,13 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             if s + 1 < steps:
                 gpu_prefetch(s + 1)
             g.backward_update(go, cfg.lr, cfg.eps)
+        elif order.startswith("pipe"):  # pipeN: a pipeline N batches deep (the oracle locks N batches as well)
+            depth = int(order[4:])
+            while pushed < min(steps, s + 1 + depth):
+                gpu_prefetch(pushed)
+                pushed += 1
+            out = gpu_forward(idx, off)
+            g.backward_update(go, cfg.lr, cfg.eps)
         elif order.startswith("deep"):  # deepN: a queue that accepts N batches ahead of training
             depth = int(order[4:])
             if s == 0:
@@ -465,6 +477,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     st["parted_at"], st["parted_elements"] = parted["at"], parted["elements"]
     st["refused_calls"] = poked["n"]
     st["second_level_total"] = g.second_level_stats()[1]
+    st["prefetch_depth"], st["rows_from_copies"] = g.prefetch_depth()
     g.close()
     o.close()
     return st
