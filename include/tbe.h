@@ -144,6 +144,8 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
  * prefetched-or-forwarded and not yet updated (else TBE_EORDER).  When such a batch is
  * still in flight, the cache decisions of the new batch are taken as if it had
  * already trained, and the copies that would touch its rows wait for its update.
+ * (With tbe_set_prefetch_depth(D), D >= 2: while no more than D batches are prefetched-or-forwarded
+ * and not yet updated; the ways of those batches are locked instead, see there.)
  * Bad offsets / out-of-range indices are detected on the device: the batch then does
  * nothing and the error is reported by the next synchronising call (and by later calls).
  */
@@ -274,15 +276,15 @@ int tbe_get_prefetch_depth(tbe_handle h, int32_t *depth, int64_t *rows_from_copi
 
 /*
  * Queue in front of tbe_prefetch.  With length D > 1 tbe_prefetch accepts up to D batches ahead of
- * training.  This is NOT the multi-batch prefetch of Section 5.7 (cache accesses several batches
- * in advance, with the rule that rows prefetched for a batch are not evicted before it trains):
+ * training.  This is NOT the multi-batch prefetch of Section 5.7 (that is tbe_set_prefetch_depth):
  * the pipeline itself stays one batch deep, no batch's rows are fetched more than one batch ahead
  * and no lock over several batches exists.  Batches beyond the next one are only kept on the host
  * and their work is issued, in order, as soon as the batch before them has been forwarded.
  * Results are those of a caller that prefetches one batch ahead.  The index buffers of a queued
  * batch must stay valid and unchanged until its tbe_backward_update has completed.  tbe_get_stats and the tbe_export_*
  * calls describe the last batch whose work has been issued, not the last one accepted.
- * length 1..64 (TBE_EINVAL); not while batches are queued (TBE_EORDER).  Default 1.
+ * length 1..64 (TBE_EINVAL); not while batches are queued and not together with a prefetch depth
+ * above one (TBE_EORDER).  Default 1.
  */
 int tbe_set_prefetch_queue(tbe_handle h, int32_t length);
 
