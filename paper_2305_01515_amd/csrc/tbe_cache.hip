@@ -447,10 +447,7 @@ __global__ __launch_bounds__(256) void heavy_starts_kernel(const TableMeta *__re
     const int h = x / R, range = x % R;
     const int u = heavy[h];
     const int t = uniq_tab[u];
-    const int tb = heavy_tile_bags(tm[t].lanes, tm[t].dtype);
-    const int n_tiles = (B + tb - 1) / tb;
-    const int tiles_per_range = (n_tiles + R - 1) / R;
-    const long long first_bag = (long long)t * B + (long long)range * tiles_per_range * tb;
+    const long long first_bag = (long long)t * B + heavy_range_first(B, R, range);
     int lo = run_off[u], hi = run_off[u + 1];
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;

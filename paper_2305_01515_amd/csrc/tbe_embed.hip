@@ -847,8 +847,6 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
   const int n_work = cnt->n_hchunks * R;
   const int lig = threadIdx.x % G, grp = threadIdx.x / G;
   const int gshift = (threadIdx.x & 63) / G * G;
-  const int n_tiles = (B + TB - 1) / TB;
-  const int tiles_per_range = (n_tiles + R - 1) / R;
   int first, end, step;
   xcd_span(n_work, 1, first, end, step);  // work items are in table order
   for (int wk = first; wk < end; wk += step) {
@@ -859,7 +857,7 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
     const TableMeta &m = tm[t];
     const int dim = m.dim, col = m.col;
     const int bag0 = t * B;
-    const int tile_lo = min(n_tiles, range * tiles_per_range), tile_hi = min(n_tiles, tile_lo + tiles_per_range);
+    const int range_lo = heavy_range_first(B, R, range), range_hi = heavy_range_first(B, R, range + 1);
     HeavySlot sl[RPG];
     HeavyState st;
     st.used = 0;
@@ -887,10 +885,10 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
 #pragma unroll
       for (int e = 0; e < EPL; e++) g[s][e] = 0.f;
     }
-    for (int tl = tile_lo; tl < tile_hi; tl++) {
+    for (int b_first = range_lo; b_first < range_hi; b_first += TB) {  // the range's tiles, TB bags each
       // stage the tile: this thread's share is float4 number k * threads + tid of the tile's TB x ROWF floats,
       // all of them requested before the first is stored
-      const int b_first = tl * TB, n_f = (min(B, b_first + TB) - b_first) * ROWF;
+      const int n_f = (min(range_hi, b_first + TB) - b_first) * ROWF;
       __syncthreads();  // the previous tile is no longer read
 #pragma unroll
       for (int k0 = 0; k0 < PER; k0 += PH) {  // PH requests in flight, then their stores
@@ -915,7 +913,7 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
         }
       }
       __syncthreads();
-      const int base_bag = bag0 + b_first, end_bag = bag0 + min(B, b_first + TB);
+      const int base_bag = bag0 + b_first, end_bag = bag0 + min(range_hi, b_first + TB);
       // the group's rows are visited in turn, a window's lookups of this tile at a time, until none has any left
       uint64_t busy;
       do {

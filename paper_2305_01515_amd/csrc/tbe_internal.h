@@ -341,6 +341,9 @@ __host__ __device__ inline int heavy_parts(int len) {
   const int p = (len + kHeavySplit - 1) / kHeavySplit;
   return p < 1 ? 1 : (p > kHeavyMaxParts ? kHeavyMaxParts : p);
 }
+// first bag of bag range `range` of R over a batch of B bags per table (the ranges are equal to within one bag, so
+// that the workgroups of the tile kernel, one per (chunk, range), have equal shares of the lookups)
+__host__ __device__ inline int heavy_range_first(int B, int R, int range) { return (int)((long long)B * range / R); }
 __host__ __device__ inline int heavy_tile_bags(int lanes, int dtype) {
   return kHeavyTileBytes / (lanes * (dtype == 0 ? 4 : 8) * 4);
 }

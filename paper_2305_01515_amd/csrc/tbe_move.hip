@@ -463,6 +463,7 @@ hipError_t launch_fixup(const TableMeta *tm, const BatchBuf &b, const OverflowCo
 // parked behind this batch's victims for the next transfer to write them (kPrevPark): the link's
 // write direction then carries them beside that transfer's fetches, which costs the transfer a
 // hundredth of its time, instead of alone between two transfers.
+template <bool DEEP>
 __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict__ tm, Staging st,
                                                      const BatchCounters *cnt, const int32_t *__restrict__ ins_tab,
                                                      const uint32_t *__restrict__ ins_where,
@@ -479,7 +480,9 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
                                                      char *const *__restrict__ l2v_dst, char **wb2_dst,
                                                      const char *__restrict__ out2_prev,
                                                      const uint32_t *__restrict__ rb_of_table,
-                                                     const uint32_t *__restrict__ ins_key, u64 *bytes_d2h, int deep) {
+                                                     const uint32_t *__restrict__ ins_key, u64 *bytes_d2h) {
+  constexpr bool deep = DEEP;  // pipeline several batches deep (an instance of its own: the one-deep pipeline's commit
+                               // is on the critical path of every step and keeps its code as it was)
   const uint32_t M = (uint32_t)st.max_inserts;  // map codes kWhereParked | (M + i): rows staged in out2
   const int n_prev = (prev_cnt && prev_cnt->err == 0) ? prev_cnt->n_byp : 0;
   const int group = (blockIdx.x * blockDim.x + threadIdx.x) / kMoveLanes;
@@ -635,12 +638,13 @@ hipError_t launch_ovf_writeback(const BatchBuf &b, const BatchBuf *parked_prev, 
 
 hipError_t launch_commit(const TableMeta *tm, const BatchBuf &b, const BatchBuf *prev, int prev_mode, const Staging &st,
                          const Level2 &l2, const uint32_t *rb_of_table, u64 *bytes_d2h, bool deep, hipStream_t s) {
-  hipLaunchKernelGGL(commit_kernel, dim3(4096), dim3(256), 0, s, tm, st, b.cnt, b.ins_tab, b.ins_where, b.ins_slot,
+  auto kern = deep ? commit_kernel<true> : commit_kernel<false>;
+  hipLaunchKernelGGL(kern, dim3(4096), dim3(256), 0, s, tm, st, b.cnt, b.ins_tab, b.ins_where, b.ins_slot,
                      b.ins_old, b.byp_tab, b.byp_where, b.ovf, prev ? prev->cnt : nullptr,
                      prev ? prev->byp_src : nullptr, prev ? prev->byp_tab : nullptr, prev ? prev->ovf : nullptr,
                      prev ? prev_mode : kPrevKeep, b.k, l2.on ? b.ins_dst : nullptr, l2.on ? b.l2v_src : nullptr,
                      l2.on ? b.l2v_dst : nullptr, l2.on ? l2.wb2_dst : nullptr, l2.out2[(b.k & 1) ^ 1], rb_of_table,
-                     b.ins_key, bytes_d2h, deep ? 1 : 0);
+                     b.ins_key, bytes_d2h);
   return hipGetLastError();
 }
 
