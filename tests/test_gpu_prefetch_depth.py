@@ -101,3 +101,46 @@ def test_main_config_full_size_at_depth_2():
     st = run_parity(cfg, steps=6, order="pipe2", oracle_threads=16, init_device="cuda")
     assert st["total"]["bypasses"] > 0 and st["late_fetches"] > 0 and st["rows_from_copies"] > 0
     assert st["tolerance"]["vectors_on_peak_scale"] == 0
+
+
+def test_bad_batch_prefetched_two_ahead_loses_nothing():
+    """Two batches deep; the second batch beyond the one in training has an index out of range and is refused on
+    the device.  The batches in front of it train on; after the flush (which reports the error) the tables equal
+    the locked oracle's after the good batches -- bypassed rows, which train in copies outside the cache, included."""
+    from oracle import Oracle
+    from paper_2305_01515_amd.tbe import TbeError
+    from parity_util import compare_backing
+    from test_gpu_api import little, make
+    cfg = little()
+    g, Wp, Mp = make(cfg)
+    g.set_prefetch_depth(2)
+    Wn = [w.numpy().copy() for w in Wp]
+    Mn = [m.numpy().copy() for m in Mp]
+    o = Oracle(Wn, Mn, [t.cache_slots for t in cfg.tables], cfg.ways, prefetch_lock=2)
+    stream = synth.BatchStream(cfg)
+    good = [stream.next() for _ in range(4)]
+    bad_idx, bad_off = stream.next()
+    bad_idx = bad_idx.clone()
+    bad_idx[0] = cfg.tables[0].rows  # one past the end of table 0
+    dev = [tuple(x.cuda() for x in b) for b in good] + [(bad_idx.cuda(), bad_off.cuda())]
+    g.prefetch(*dev[0])
+    g.prefetch(*dev[1])
+    bypasses = 0
+    for s in range(4):
+        if s + 2 < len(dev):
+            g.prefetch(*dev[s + 2])  # the last one is the bad batch
+        g.forward(*dev[s])
+        go = synth.grad_out(cfg, s + 1)
+        g.backward_update(go.cuda(), cfg.lr, cfg.eps)
+        o.prefetch(good[s][0].numpy(), good[s][1].numpy())
+        o.forward()
+        o.backward_update(go.numpy(), cfg.lr, cfg.eps)
+        bypasses += o.stats()[0]["bypasses"]
+    assert bypasses > 0, "no good batch bypasses a row: the case is not exercised"
+    with pytest.raises(TbeError) as e:
+        g.flush()
+    assert e.value.code == -2
+    o.flush()
+    compare_backing(cfg, Wn, Mn, Wp, Mp, "after the refused batch")
+    g.close()
+    o.close()
