@@ -35,6 +35,10 @@ constexpr int kHeavyTileBytes = TBE_HEAVY_TILE_BYTES;    // gradient tile in LDS
 // and to add up; beside the transfer kernel, which holds 48 CUs: 256 items 0.20 (two rounds), 192 items 0.15.
 constexpr int kLinkCus = 48;              // workgroups of the transfer kernel: 1024 threads each, a CU each
 constexpr int kHeavyMaxRanges = 128;
+#ifndef TBE_HEAVY_ROUNDS
+#define TBE_HEAVY_ROUNDS 4
+#endif
+constexpr int kHeavyRounds = TBE_HEAVY_ROUNDS;  // rounds of (chunk, bag range) work items when one round would make them too long
 
 constexpr uint32_t kWhereOverflow = 0x80000000u;  // in the overflow copies of the batch before
 constexpr uint32_t kWhereParked = 0x40000000u;    // among the victims the batch before parked
@@ -328,6 +332,10 @@ hipError_t launch_backward_classes(int which, const TableMeta *tm, const ClassIn
 __host__ __device__ inline int heavy_ranges(int n_hchunks, int n_heavy, long long slot_capacity, int target_items) {
   if (n_hchunks < 1 || n_heavy < 1) return 1;
   long long r = target_items / n_hchunks;  // rounded down: one round of workgroups
+  // With many chunks (a model of many tables, or tables with thousands of heavy rows) one round would leave each
+  // workgroup a quarter of a batch or more to sweep alone: four rounds of shorter items then, which also evens out
+  // what the tables differ in (heterogeneous model: tile kernel 6.5 -> 1.7 ms).
+  if (r < kHeavyRounds) r = ((long long)kHeavyRounds * target_items + n_hchunks - 1) / n_hchunks;
   if (r > kHeavyMaxRanges) r = kHeavyMaxRanges;
   if (r > slot_capacity / n_heavy) r = slot_capacity / n_heavy;
   return r < 1 ? 1 : (int)r;
