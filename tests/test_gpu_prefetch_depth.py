@@ -144,3 +144,15 @@ def test_bad_batch_prefetched_two_ahead_loses_nothing():
     compare_backing(cfg, Wn, Mn, Wp, Mp, "after the refused batch")
     g.close()
     o.close()
+
+
+def test_heterogeneous_model_scaled_at_depth_3():
+    """100 tables of three widths (8, 16 and 32 lanes per row), pooling means 1..100, skews 0.9..1.3, rows 1/100 of
+    the configuration's and batch 2048, three batches deep: every backward class and table class under the lock."""
+    cfg = synth.config_hetero(max_rows=5e5, batch=2048, cache_bytes=160 << 20)
+    probe = synth.BatchStream(cfg)
+    _, off = probe.next()
+    lookups = [int(off[(t + 1) * cfg.batch] - off[t * cfg.batch]) for t in range(cfg.num_tables)]
+    synth.split_cache_budget(cfg, lookups, cfg.cache_bytes)
+    st = run_parity(cfg, steps=8, order="pipe3", oracle_threads=16, init_device="cuda")
+    assert st["total"]["hits"] > 0 and st["total"]["inserts"] > 0 and st["rows_from_copies"] > 0
