@@ -30,8 +30,10 @@ def algorithmic_bytes(cfg, lookups_per_table, uniques, batch):
     forward; rows read and written once per distinct row, accumulators and the output gradient once in the backward.
     Returns (forward, backward, gradient rows if counted per lookup, forward with every distinct row counted once)."""
     from paper_2305_01515_amd import synth
+    from paper_2305_01515_amd.accounting import eq3_bytes_per_lookup
     T = len(cfg.tables)
-    rows_fwd = sum(lookups_per_table[t] * cfg.tables[t].dim * (4 if cfg.tables[t].dtype == synth.FP32 else 2)
+    # Eq. 3 counts a row twice per lookup (forward and backward): the forward's half of it
+    rows_fwd = sum(lookups_per_table[t] * eq3_bytes_per_lookup(cfg.tables[t].dim, 4 if cfg.tables[t].dtype == synth.FP32 else 2) // 2
                    for t in range(T))
     rb_mean = sum(tc.dim * (4 if tc.dtype == synth.FP32 else 2) for tc in cfg.tables) / T
     grad_per_lookup = sum(lookups_per_table[t] * cfg.tables[t].dim * 4 for t in range(T))

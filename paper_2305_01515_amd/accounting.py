@@ -1,4 +1,4 @@
-"""The paper's own traffic accounting, used by the reports (host arithmetic only).
+"""The paper's own traffic accounting (host arithmetic only): bench.py takes the forward's Eq. 3 bytes from here.
 
   Eq. 3 (Section 2.1.2): an embedding lookup moves 2 * D * p bytes -- the row is consumed
       once by forward and once by backward.
