@@ -580,19 +580,32 @@ struct StatusOp {
 };
 
 // --------------------------------------------------------------------------------------
-// Probe + replacement: one wavefront per touched set; lane w holds way w.
-//   phase 1: every distinct row of the set that is found is a hit, its way is stamped k and
-//            its count grows by the row's lookups in the batch;
-//   phase 2: the ways still older than k are ranked by (timestamp, way) -- LRU -- or by
-//            (count, timestamp, way) -- LFU; the j-th miss in ascending row order takes the
-//            way of rank j (evicting what it held) and starts counting at its own lookups;
-//            misses beyond the number of such ways bypass the cache.
+// Probe + replacement.  A wavefront takes a window of consecutive touched sets -- as many as hold about a
+// wavefront's width of distinct rows, at most kProbeSets -- and keeps the ways of all of them in LDS.
+//   phase 1, a lane per distinct row over the whole window: a row that is found is a hit, its way is
+//            stamped k and its count grows by the row's lookups in the batch;
+//   phase 2, per set of the window that has a miss, lane w holding way w: the evictable ways are ranked by
+//            (timestamp, way) -- LRU -- or by (count, timestamp, way) -- LFU; the j-th miss in ascending
+//            row order takes the way of rank j (evicting what it held) and starts counting at its own
+//            lookups; misses beyond the number of such ways bypass the cache.
 // Rows of a set arrive in ascending order because the sort key is (set, row div S).
+// A set's chain of dependent reads (set head -> table -> ways -> rows) is several memory round trips; with a
+// cache as large as the tables a batch touches a million sets with two or three rows each, and one set per
+// wavefront left the kernel waiting on that chain (0.67 ms for the benchmark shapes with every row resident).
 // --------------------------------------------------------------------------------------
 __device__ inline int32_t add_saturating(int32_t a, int32_t b) {  // a, b >= 0
   const uint32_t v = (uint32_t)a + (uint32_t)b;
   return v > 0x7FFFFFFFu ? 0x7FFFFFFF : (int32_t)v;
 }
+
+#ifndef TBE_PROBE_SETS
+#define TBE_PROBE_SETS 8
+#endif
+constexpr int kProbeSets = TBE_PROBE_SETS;       // sets of one window, at most
+constexpr int kProbeWays = 32 * TBE_PROBE_SETS;  // ways of one window, at most (>= kWave, so that a window holds a set at least)
+#ifndef TBE_PROBE_ROWS
+#define TBE_PROBE_ROWS 64        // distinct rows a window aims for
+#endif
 
 template <bool LFU, bool L2>
 __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restrict__ tm, int T, int W, int32_t k,
@@ -607,188 +620,236 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
                                                       int32_t *__restrict__ ts2, int l2_factor,
                                                       int32_t *__restrict__ src2, int32_t *__restrict__ dst2,
                                                       int32_t *__restrict__ evict2, BatchCounters *cnt) {
-  __shared__ int32_t l_tag[kWave];
+  // ways of set i of the window at [i * (W + 1), i * (W + 1) + W): the odd stride keeps lanes that scan
+  // different sets on different banks
+  __shared__ int32_t w_tag[kProbeWays + kProbeSets], w_ts[kProbeWays + kProbeSets], w_freq[kProbeWays + kProbeSets];
+  __shared__ int32_t h_u0[kProbeSets + 1], h_tab[kProbeSets], h_slot0[kProbeSets];
+  __shared__ uint32_t h_key0[kProbeSets], h_sets[kProbeSets], h_set[kProbeSets];
+  __shared__ int32_t l_way[kWave];
   __shared__ int32_t l_tag2[L2 ? kWave : 1], l_ts2[L2 ? kWave : 1], l_way2[L2 ? kWave : 1];
   __shared__ int32_t v_row[L2 ? kWave : 1], v_u[L2 ? kWave : 1];
   int n_l2hit = 0, n_l2dem = 0, n_l2ev = 0, n_l2byp = 0;  // this lane's share of the second-level counters
-  __shared__ int32_t l_ts[kWave];
-  __shared__ int32_t l_freq[kWave];
-  __shared__ int32_t l_way[kWave];
   if (cnt->err) return;
   const int lane = threadIdx.x;
   const int n_touched = cnt->n_touched, n_uniq = cnt->n_uniq;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
-  for (int v = blockIdx.x; v < n_touched; v += gridDim.x) {
-    const uint2 head = touched[v];
-    const int u0 = (int)head.y;
-    const int u1 = (v + 1 < n_touched) ? (int)touched[v + 1].y : n_uniq;
-    if (head.x == kNoSet) {  // rows of tables without a cache
-      for (int u = u0 + lane; u < u1; u += kWave) {
-        loc_u[u] = -1;
-        status[u] = ST_BYPASS;
-        if (L2) src2[u] = dst2[u] = evict2[u] = -1;
-      }
-      continue;
-    }
-    const TableMeta &m = tm[uniq_tab[u0]];
-    const uint32_t set = head.x - m.set_base;
-    const int slot0 = (int)head.x * W;  // global slot id of way 0 (set_base * W == slot_base)
-    const uint32_t key0 = m.key_base + set * m.rows_per_set;
+  const int WP = W + 1;
+  int ns = n_uniq > 0 ? (int)(((long long)TBE_PROBE_ROWS * n_touched + n_uniq - 1) / n_uniq) : 1;
+  const int ns_max = kProbeWays / W < kProbeSets ? kProbeWays / W : kProbeSets;
+  ns = ns < 1 ? 1 : (ns > ns_max ? ns_max : ns);
+  for (long long v0 = (long long)blockIdx.x * ns; v0 < n_touched; v0 += (long long)gridDim.x * ns) {
+    const int nv = n_touched - v0 < ns ? (int)(n_touched - v0) : ns;
     __syncthreads();
-    l_tag[lane] = lane < W ? tags[slot0 + lane] : -2;
-    l_ts[lane] = lane < W ? ts[slot0 + lane] : 0x7FFFFFFF;
-    l_freq[lane] = lane < W ? freq[slot0 + lane] : 0;
-    __syncthreads();
-    // phase 1: hits
-    for (int c = u0; c < u1; c += kWave) {
-      const int u = c + lane;
-      const bool valid = u < u1;
-      const int32_t row = valid ? (int32_t)((uniq_key[u] - key0) * m.sets + set) : -3;
-      int hit = -1;
-      for (int w = 0; w < W; w++)
-        if (l_tag[w] == row) hit = w;
-      if (valid) {
-        if (hit >= 0) {
-          l_ts[hit] = k;
-          l_freq[hit] = add_saturating(l_freq[hit], run_off[u + 1] - run_off[u]);
-          loc_u[u] = slot0 + hit;
-          status[u] = ST_HIT;
+    if (lane <= nv) {
+      const long long v = v0 + lane;
+      uint2 head = make_uint2(kNoSet, (uint32_t)n_uniq);
+      if (v < n_touched) head = touched[v];
+      h_u0[lane] = (int)head.y;
+      if (lane < nv) {
+        if (head.x == kNoSet) {  // rows of tables without a cache
+          h_slot0[lane] = -1;
         } else {
-          status[u] = ST_MISS;
+          const int t = uniq_tab[head.y];
+          const TableMeta &m = tm[t];
+          const uint32_t set = head.x - m.set_base;
+          h_tab[lane] = t;
+          h_slot0[lane] = (int)head.x * W;  // global slot id of way 0 (set_base * W == slot_base)
+          h_set[lane] = set;
+          h_sets[lane] = m.sets;
+          h_key0[lane] = m.key_base + set * m.rows_per_set;
         }
       }
     }
     __syncthreads();
-    // phase 2: rank the evictable ways
-    const int32_t my_ts = l_ts[lane];
-    // evictable: free ways (-1) and ways stamped before evictable_below = max(k - lock, 1): the ways of this batch
-    // and, in a pipeline `lock` batches deep, of the batches that may still be waiting for their training
-    const bool cand = lane < W && my_ts < evictable_below;
-    const int32_t my_freq = l_freq[lane];
-    int rank = 0;
-    for (int w = 0; w < W; w++) {
-      const int32_t tw = l_ts[w];
-      if (tw >= evictable_below) continue;
-      bool first = tw < my_ts || (tw == my_ts && w < lane);
-      if (LFU) {
-        const int32_t fw = l_freq[w];
-        first = fw < my_freq || (fw == my_freq && first);
+    const int U0 = h_u0[0], U1 = h_u0[nv];
+    for (int e = lane; e < nv * W; e += kWave) {
+      const int si = e / W, w = e - si * W;
+      const int s0 = h_slot0[si];
+      if (s0 >= 0) {
+        w_tag[si * WP + w] = tags[s0 + w];
+        w_ts[si * WP + w] = ts[s0 + w];
+        w_freq[si * WP + w] = freq[s0 + w];
       }
-      if (first) rank++;
     }
-    const int n_cand = __popcll(__ballot(cand));
-    if (cand) l_way[rank] = lane;
     __syncthreads();
-    int before = 0;
-    for (int c = u0; c < u1; c += kWave) {
+    // phase 1: hits, a lane per distinct row of the window
+    uint32_t miss_sets = 0;
+    for (int c = U0; c < U1; c += kWave) {
       const int u = c + lane;
-      const bool miss = u < u1 && status[u] == ST_MISS;
-      const uint64_t mb = __ballot(miss);
-      if (miss) {
-        const int j = before + __popcll(mb & lt_mask);
-        if (j < n_cand) {
-          const int way = l_way[j];
-          old_tag[u] = l_tag[way];
-          l_tag[way] = (int32_t)((uniq_key[u] - key0) * m.sets + set);
-          l_ts[way] = k;
-          l_freq[way] = run_off[u + 1] - run_off[u];
-          loc_u[u] = slot0 + way;
-          status[u] = ST_INSERT;
-        } else {
+      if (u < U1) {
+        int si = 0;
+        for (int i = 1; i < nv; i++) si += h_u0[i] <= u ? 1 : 0;
+        const int s0 = h_slot0[si];
+        if (L2) src2[u] = dst2[u] = evict2[u] = -1;
+        if (s0 < 0) {
           loc_u[u] = -1;
           status[u] = ST_BYPASS;
+        } else {
+          const int32_t row = (int32_t)((uniq_key[u] - h_key0[si]) * h_sets[si] + h_set[si]);
+          const int base = si * WP;
+          int hit = -1;
+          for (int w = 0; w < W; w++)
+            if (w_tag[base + w] == row) hit = w;
+          if (hit >= 0) {
+            w_ts[base + hit] = k;
+            w_freq[base + hit] = add_saturating(w_freq[base + hit], run_off[u + 1] - run_off[u]);
+            loc_u[u] = s0 + hit;
+            status[u] = ST_HIT;
+          } else {
+            status[u] = ST_MISS;
+            miss_sets |= 1u << si;
+          }
         }
       }
-      before += __popcll(mb);
     }
+    for (int d = 32; d >= 1; d >>= 1) miss_sets |= __shfl_xor(miss_sets, d);
+    const uint32_t new_tags = miss_sets;  // only a miss changes a set's tags
     __syncthreads();
-    if (lane < W) {
-      tags[slot0 + lane] = l_tag[lane];
-      ts[slot0 + lane] = l_ts[lane];
-      freq[slot0 + lane] = l_freq[lane];
-    }
-    if (L2) {
-      // ---- second level (exclusive): the rows this set missed are looked up there, then the
-      // rows this set evicted move down.  sets2 = l2_factor * sets, so a row r of this set
-      // belongs to second-level set  set + sets * ((r div sets) mod l2_factor)  and no other
-      // first-level set shares it: this wavefront owns all of them.
-      int n_v = 0;  // the victims of this set: at most W, one per lane
+    while (miss_sets) {  // the same in every lane
+      const int si = __ffs(miss_sets) - 1;
+      miss_sets &= miss_sets - 1;
+      const int base = si * WP;
+      int32_t *l_tag = w_tag + base, *l_ts = w_ts + base, *l_freq = w_freq + base;
+      const int u0 = h_u0[si], u1 = h_u0[si + 1];
+      const int slot0 = h_slot0[si];
+      const TableMeta &m = tm[h_tab[si]];
+      const uint32_t set = h_set[si], key0 = h_key0[si];
+      // phase 2: rank the evictable ways
+      const int32_t my_ts = lane < W ? l_ts[lane] : 0x7FFFFFFF;
+      // evictable: free ways (-1) and ways stamped before evictable_below = max(k - lock, 1): the ways of this batch
+      // and, in a pipeline `lock` batches deep, of the batches that may still be waiting for their training
+      const bool cand = lane < W && my_ts < evictable_below;
+      const int32_t my_freq = lane < W ? l_freq[lane] : 0;
+      int rank = 0;
+      for (int w = 0; w < W; w++) {
+        const int32_t tw = l_ts[w];
+        if (tw >= evictable_below) continue;
+        bool first = tw < my_ts || (tw == my_ts && w < lane);
+        if (LFU) {
+          const int32_t fw = l_freq[w];
+          first = fw < my_freq || (fw == my_freq && first);
+        }
+        if (first) rank++;
+      }
+      const int n_cand = __popcll(__ballot(cand));
+      __syncthreads();
+      if (cand) l_way[rank] = lane;
+      __syncthreads();
+      int before = 0;
       for (int c = u0; c < u1; c += kWave) {
         const int u = c + lane;
-        const bool valid = u < u1;
-        if (valid) src2[u] = dst2[u] = evict2[u] = -1;
-        const bool isv = valid && status[u] == ST_INSERT && old_tag[u] >= 0;
-        const uint64_t vm = __ballot(isv);
-        if (isv) {
-          const int p = n_v + __popcll(vm & lt_mask);
-          v_row[p] = old_tag[u];
-          v_u[p] = u;
+        const bool miss = u < u1 && status[u] == ST_MISS;
+        const uint64_t mb = __ballot(miss);
+        if (miss) {
+          const int j = before + __popcll(mb & lt_mask);
+          if (j < n_cand) {
+            const int way = l_way[j];
+            old_tag[u] = l_tag[way];
+            l_tag[way] = (int32_t)((uniq_key[u] - key0) * m.sets + set);
+            l_ts[way] = k;
+            l_freq[way] = run_off[u + 1] - run_off[u];
+            loc_u[u] = slot0 + way;
+            status[u] = ST_INSERT;
+          } else {
+            loc_u[u] = -1;
+            status[u] = ST_BYPASS;
+          }
         }
-        n_v += __popcll(vm);
+        before += __popcll(mb);
       }
       __syncthreads();
-      const int32_t my_v = lane < n_v ? v_row[lane] : -1;
-      const int my_vset = my_v >= 0 ? (int)(((uint32_t)my_v / m.sets) % (uint32_t)l2_factor) : -1;
-      for (int j = 0; j < l2_factor; j++) {
-        const int slot20 = m.slot2_base + (int)(set + (uint32_t)j * m.sets) * W;
-        l_tag2[lane] = lane < W ? tags2[slot20 + lane] : -2;
-        l_ts2[lane] = lane < W ? ts2[slot20 + lane] : 0x7FFFFFFF;
-        __syncthreads();
-        // (A) missed rows of this second-level set: found and inserted above -> moves up, its entry
-        // becomes free; found but bypassed above -> stays, used in place, stamped k
+      if (L2) {
+        // ---- second level (exclusive): the rows this set missed are looked up there, then the
+        // rows this set evicted move down.  sets2 = l2_factor * sets, so a row r of this set
+        // belongs to second-level set  set + sets * ((r div sets) mod l2_factor)  and no other
+        // first-level set shares it: this wavefront owns all of them.
+        int n_v = 0;  // the victims of this set: at most W, one per lane
         for (int c = u0; c < u1; c += kWave) {
           const int u = c + lane;
-          const uint32_t q = u < u1 ? uniq_key[u] - key0 : 0u;  // row div sets
-          const bool mine = u < u1 && status[u] != ST_HIT && (int)(q % (uint32_t)l2_factor) == j;
-          const int32_t row = mine ? (int32_t)(q * m.sets + set) : -3;
-          int hw = -1;
-          for (int w = 0; w < W; w++)
-            if (l_tag2[w] == row) hw = w;
-          if (hw >= 0) {
-            src2[u] = slot20 + hw;
-            if (status[u] == ST_INSERT) { l_tag2[hw] = -1; l_ts2[hw] = -1; } else l_ts2[hw] = k;
-            n_l2hit++;
+          const bool valid = u < u1;
+          const bool isv = valid && status[u] == ST_INSERT && old_tag[u] >= 0;
+          const uint64_t vm = __ballot(isv);
+          if (isv) {
+            const int p = n_v + __popcll(vm & lt_mask);
+            v_row[p] = old_tag[u];
+            v_u[p] = u;
           }
+          n_v += __popcll(vm);
         }
         __syncthreads();
-        // (B) victims of this second-level set in ascending row order take the ways older than
-        // k - 1 in order of (timestamp, way); entries of this batch and the one before stay
-        const bool vmine = my_vset == j;
-        int vrank = 0;
-        for (int w = 0; w < n_v; w++) {
-          const int32_t o = v_row[w];
-          if ((int)(((uint32_t)o / m.sets) % (uint32_t)l2_factor) == j && o < my_v) vrank++;
-        }
-        const int32_t my_ts2 = l_ts2[lane];
-        const bool cand2 = lane < W && my_ts2 < k - 1;
-        int rank2 = 0;
-        for (int w = 0; w < W; w++) {
-          const int32_t tw = l_ts2[w];
-          if (tw < k - 1 && (tw < my_ts2 || (tw == my_ts2 && w < lane))) rank2++;
-        }
-        const int n_cand2 = __popcll(__ballot(cand2));
-        if (cand2) l_way2[rank2] = lane;
-        __syncthreads();
-        if (vmine) {
-          if (vrank < n_cand2) {
-            const int way = l_way2[vrank];
-            const int32_t held = l_tag2[way];
-            evict2[v_u[lane]] = held;
-            dst2[v_u[lane]] = slot20 + way;
-            l_tag2[way] = my_v;
-            l_ts2[way] = k;
-            n_l2dem++;
-            if (held >= 0) n_l2ev++;
-          } else {
-            n_l2byp++;  // no way to take: the victim goes to the lower tier
+        const int32_t my_v = lane < n_v ? v_row[lane] : -1;
+        const int my_vset = my_v >= 0 ? (int)(((uint32_t)my_v / m.sets) % (uint32_t)l2_factor) : -1;
+        for (int j = 0; j < l2_factor; j++) {
+          const int slot20 = m.slot2_base + (int)(set + (uint32_t)j * m.sets) * W;
+          l_tag2[lane] = lane < W ? tags2[slot20 + lane] : -2;
+          l_ts2[lane] = lane < W ? ts2[slot20 + lane] : 0x7FFFFFFF;
+          __syncthreads();
+          // (A) missed rows of this second-level set: found and inserted above -> moves up, its entry
+          // becomes free; found but bypassed above -> stays, used in place, stamped k
+          for (int c = u0; c < u1; c += kWave) {
+            const int u = c + lane;
+            const uint32_t q = u < u1 ? uniq_key[u] - key0 : 0u;  // row div sets
+            const bool mine = u < u1 && status[u] != ST_HIT && (int)(q % (uint32_t)l2_factor) == j;
+            const int32_t row = mine ? (int32_t)(q * m.sets + set) : -3;
+            int hw = -1;
+            for (int w = 0; w < W; w++)
+              if (l_tag2[w] == row) hw = w;
+            if (hw >= 0) {
+              src2[u] = slot20 + hw;
+              if (status[u] == ST_INSERT) { l_tag2[hw] = -1; l_ts2[hw] = -1; } else l_ts2[hw] = k;
+              n_l2hit++;
+            }
           }
+          __syncthreads();
+          // (B) victims of this second-level set in ascending row order take the ways older than
+          // k - 1 in order of (timestamp, way); entries of this batch and the one before stay
+          const bool vmine = my_vset == j;
+          int vrank = 0;
+          for (int w = 0; w < n_v; w++) {
+            const int32_t o = v_row[w];
+            if ((int)(((uint32_t)o / m.sets) % (uint32_t)l2_factor) == j && o < my_v) vrank++;
+          }
+          const int32_t my_ts2 = l_ts2[lane];
+          const bool cand2 = lane < W && my_ts2 < k - 1;
+          int rank2 = 0;
+          for (int w = 0; w < W; w++) {
+            const int32_t tw = l_ts2[w];
+            if (tw < k - 1 && (tw < my_ts2 || (tw == my_ts2 && w < lane))) rank2++;
+          }
+          const int n_cand2 = __popcll(__ballot(cand2));
+          if (cand2) l_way2[rank2] = lane;
+          __syncthreads();
+          if (vmine) {
+            if (vrank < n_cand2) {
+              const int way = l_way2[vrank];
+              const int32_t held = l_tag2[way];
+              evict2[v_u[lane]] = held;
+              dst2[v_u[lane]] = slot20 + way;
+              l_tag2[way] = my_v;
+              l_ts2[way] = k;
+              n_l2dem++;
+              if (held >= 0) n_l2ev++;
+            } else {
+              n_l2byp++;  // no way to take: the victim goes to the lower tier
+            }
+          }
+          __syncthreads();
+          if (lane < W) {
+            tags2[slot20 + lane] = l_tag2[lane];
+            ts2[slot20 + lane] = l_ts2[lane];
+          }
+          __syncthreads();
         }
-        __syncthreads();
-        if (lane < W) {
-          tags2[slot20 + lane] = l_tag2[lane];
-          ts2[slot20 + lane] = l_ts2[lane];
-        }
-        __syncthreads();
+      }
+    }
+    __syncthreads();
+    for (int e = lane; e < nv * W; e += kWave) {
+      const int si = e / W, w = e - si * W;
+      const int s0 = h_slot0[si];
+      if (s0 >= 0) {
+        if (new_tags >> si & 1u) tags[s0 + w] = w_tag[si * WP + w];
+        ts[s0 + w] = w_ts[si * WP + w];
+        freq[s0 + w] = w_freq[si * WP + w];
       }
     }
   }
