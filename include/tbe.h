@@ -303,6 +303,15 @@ int tbe_set_prefetch_queue(tbe_handle h, int32_t length);
 int tbe_set_backing_throttle(tbe_handle h, int64_t ns_per_row);
 
 /*
+ * Tuning of the probe of Section 5.5.1 (results never depend on it): a wavefront of the probe kernel
+ * takes several consecutive touched sets at a time when a batch leaves only a few distinct rows per
+ * set, but not while that would leave fewer than min_windows wavefronts' worth of work.  Default 4096;
+ * 1 groups whenever the rows per set allow it (how the tests reach the grouped path with small
+ * models), a huge value never groups.  Any time between batches; TBE_EINVAL outside 1 .. 2^30.
+ */
+int tbe_set_probe_grouping(tbe_handle h, int32_t min_windows);
+
+/*
  * By default tbe_prefetch orders its work behind everything enqueued on the compute stream
  * so far, because the index buffers may have been produced there.  With ready = 1 the
  * caller guarantees instead that the buffers passed to tbe_prefetch are complete in device

@@ -951,6 +951,13 @@ int tbe_set_backing_throttle(tbe_handle h, int64_t ns_per_row) {
   return TBE_OK;
 }
 
+int tbe_set_probe_grouping(tbe_handle h, int32_t min_windows) {
+  if (!h) return TBE_EINVAL;
+  if (min_windows < 1 || min_windows > (1 << 30)) return fail(h, TBE_EINVAL, "set_probe_grouping: 1 .. 2^30 windows");
+  h->g.probe_min_windows = min_windows;
+  return TBE_OK;
+}
+
 int tbe_enable_second_level(tbe_handle h, int32_t factor) {
   if (!h) return TBE_EINVAL;
   if (factor < 1 || factor > 1024) return fail(h, TBE_EINVAL, "enable_second_level: factor must be 1..1024");

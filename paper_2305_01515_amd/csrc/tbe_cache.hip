@@ -609,7 +609,7 @@ constexpr int kProbeWays = 32 * TBE_PROBE_SETS;  // ways of one window, at most 
 
 template <bool LFU, bool L2>
 __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restrict__ tm, int T, int W, int32_t k,
-                                                      int32_t evictable_below,
+                                                      int32_t evictable_below, int32_t min_windows,
                                                       const uint32_t *__restrict__ uniq_key,
                                                       const int32_t *__restrict__ uniq_tab,
                                                       const uint2 *__restrict__ touched, int32_t *__restrict__ tags,
@@ -635,8 +635,10 @@ __global__ __launch_bounds__(kWave) void probe_kernel(const TableMeta *__restric
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   const int WP = W + 1;
   int ns = n_uniq > 0 ? (int)(((long long)TBE_PROBE_ROWS * n_touched + n_uniq - 1) / n_uniq) : 1;
-  const int ns_max = kProbeWays / W < kProbeSets ? kProbeWays / W : kProbeSets;
-  ns = ns < 1 ? 1 : (ns > ns_max ? ns_max : ns);
+  int ns_max = kProbeWays / W < kProbeSets ? kProbeWays / W : kProbeSets;
+  if (ns_max > n_touched / min_windows) ns_max = n_touched / min_windows;  // few sets: a wavefront each
+  ns = ns > ns_max ? ns_max : ns;
+  ns = ns < 1 ? 1 : ns;
   for (long long v0 = (long long)blockIdx.x * ns; v0 < n_touched; v0 += (long long)gridDim.x * ns) {
     const int nv = n_touched - v0 < ns ? (int)(n_touched - v0) : ns;
     __syncthreads();
@@ -935,7 +937,7 @@ hipError_t launch_dedup_probe(const TableMeta *tm, const Geometry &g, const Batc
   const int probe_blocks = (int)(max_touched < 65536 ? max_touched : 65536);
   auto probe = l2.on ? (lfu ? probe_kernel<true, true> : probe_kernel<false, true>)
                      : (lfu ? probe_kernel<true, false> : probe_kernel<false, false>);
-  hipLaunchKernelGGL(probe, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.k - lock > 1 ? b.k - lock : 1, b.uniq_key, b.uniq_tab, b.touched,
+  hipLaunchKernelGGL(probe, dim3(probe_blocks), dim3(kWave), 0, s, tm, g.T, g.ways, b.k, b.k - lock > 1 ? b.k - lock : 1, g.probe_min_windows, b.uniq_key, b.uniq_tab, b.touched,
                      tags, ts, freq, b.run_off, b.loc_u, b.status, b.old_tag, l2.tags2, l2.ts2, l2.factor,
                      l2.on ? b.src2 : nullptr, l2.on ? b.dst2 : nullptr, l2.on ? b.evict2 : nullptr, b.cnt);
   StatusOp st{tm, g.T, b.status, b.run_off, b.old_tag, b.uniq_key, b.uniq_tab, b.ins_idx, b.ins_tab, b.ins_slot,

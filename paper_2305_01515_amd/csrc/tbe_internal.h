@@ -234,6 +234,7 @@ struct Geometry {
   int32_t within_bits;  // bits left for the position inside the bag in a packed sort payload (0 = never packed)
   int32_t partial_stride;  // floats per partial-sum slot (widest row, padded to whole lanes)
   int64_t partial_slots;   // slots of the partial-sum buffer (heavy rows x bag ranges of a batch fit in)
+  int32_t probe_min_windows = 4096;  // the probe does not group touched sets while that leaves fewer windows than this
   int32_t heavy_target;    // (chunk, bag range) work items the heavy rows' tile kernel should have: the CUs free for it
   uint32_t ovf_stride;     // bytes per overflow / staging slot (widest row)
   uint32_t total_sets;

@@ -24,7 +24,7 @@ EXPORTS = ["tbe_create", "tbe_prefetch", "tbe_forward", "tbe_backward_update", "
            "tbe_get_stats", "tbe_num_sets", "tbe_export_cache_state", "tbe_export_batch_events", "tbe_last_error",
            "tbe_host_alloc", "tbe_host_free", "tbe_set_profiling", "tbe_get_stage_times", "tbe_set_inputs_ready",
            "tbe_set_policy", "tbe_export_cache_freq", "tbe_plan_placement", "tbe_set_pooling",
-           "tbe_set_prefetch_queue", "tbe_set_prefetch_depth", "tbe_get_prefetch_depth", "tbe_set_backing_throttle", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax", "tbe_backward_update_static", "tbe_import_cache_freq"]
+           "tbe_set_prefetch_queue", "tbe_set_prefetch_depth", "tbe_get_prefetch_depth", "tbe_set_backing_throttle", "tbe_set_probe_grouping", "tbe_enable_deferred_init", "tbe_export_initialised", "tbe_enable_second_level", "tbe_num_sets2", "tbe_export_second_level_state", "tbe_get_second_level_stats", "tbe_export_argmax", "tbe_backward_update_static", "tbe_import_cache_freq"]
 POLICIES = {"lru": 0, "lfu": 1}
 POOLINGS = {"sum": 0, "mean": 1, "max": 2}
 STAGES = {"prefetch": 0, "fill": 1, "forward": 2, "backward_combine": 3, "backward_short": 4, "commit": 5, "backward_single": 6, "backward_heavy": 7, "backward": 8}
@@ -93,6 +93,7 @@ def lib() -> C.CDLL:
         l.tbe_set_prefetch_depth.argtypes = [vp, i32]
         l.tbe_get_prefetch_depth.argtypes = [vp, C.POINTER(i32), C.POINTER(i64)]
         l.tbe_set_backing_throttle.argtypes = [vp, i64]
+        l.tbe_set_probe_grouping.argtypes = [vp, i32]
         l.tbe_enable_deferred_init.argtypes = [vp, C.c_uint64, C.c_float]
         l.tbe_export_initialised.argtypes = [vp, i32, vp]
         l.tbe_num_sets2.argtypes = [vp, i32]
@@ -303,6 +304,9 @@ class TBE:
 
     def set_backing_throttle(self, ns_per_row: int):
         self._check(lib().tbe_set_backing_throttle(self._h, ns_per_row), "tbe_set_backing_throttle")
+
+    def set_probe_grouping(self, min_windows: int):
+        self._check(lib().tbe_set_probe_grouping(self._h, min_windows), "tbe_set_probe_grouping")
 
     def cache_freq(self, t: int) -> np.ndarray:
         f = np.empty(self.num_sets(t) * self.ways, dtype=np.int32)

@@ -257,7 +257,7 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
                oracle_threads: int = 8, max_lookups: int = None, init_device="cpu", policy: str = "lru",
                pooling: str = "sum", second_level_factor: int = 0, max_batch: int = None, deferred_init=None,
                flush_every: int = 0, misuse: int = 0, vary_batch: int = 0, touched_only: bool = False,
-               backing_throttle_ns: int = 0):
+               backing_throttle_ns: int = 0, probe_min_windows: int = 0):
     """order: 'serial'   prefetch(k) forward(k) backward(k)
               'inline'   forward(k) (prefetches itself) backward(k)
               'ahead'    prefetch(k+1) is issued between forward(k) and backward(k)
@@ -273,6 +273,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
     flush_every = n ('serial' and 'inline' only, where no batch is in flight between steps): both sides
     flush after every n-th step, the backing tiers are compared, and training goes on.
     backing_throttle_ns: the library's emulation of a slower backing tier (timing only: nothing may change).
+    probe_min_windows: tbe_set_probe_grouping (tuning only: nothing may change); 1 makes the probe group the sets of
+    small models, which it otherwise takes a wavefront each.
     Cache state, counters and event sets are compared after every `check_every`-th
     prefetch (the library's snapshot is taken right after its prefetch call, the oracle,
     which is strictly sequential, is compared when it reaches that batch)."""
@@ -302,6 +304,8 @@ def run_parity(cfg, steps: int, order: str = "serial", overlap: bool = True, che
             second_level_factor=second_level_factor, deferred_init=deferred_init)
     if backing_throttle_ns:
         g.set_backing_throttle(backing_throttle_ns)
+    if probe_min_windows:
+        g.set_probe_grouping(probe_min_windows)
     if pipe_depth:
         g.set_prefetch_depth(pipe_depth)
     dev = [(i.to(device), f.to(device)) for i, f in batches]

@@ -387,3 +387,17 @@ def test_bad_batch_prefetched_ahead_does_not_lose_the_last_good_batch():
     compare_backing(cfg, Wn, Mn, Wp, Mp, "after the refused batch")
     g.close()
     o.close()
+
+
+def test_probe_grouping_takes_1_to_2_pow_30():
+    """tbe_set_probe_grouping: a tuning value, refused outside its range"""
+    from paper_2305_01515_amd.tbe import TbeError
+    from test_gpu_parity import small_cfg
+    g, _, _ = make(small_cfg(synth.FP32, 4, seed=5, batch=16), max_lookups=1 << 16)
+    for bad in (0, -7, (1 << 30) + 1):
+        with pytest.raises(TbeError) as e:
+            g.set_probe_grouping(bad)
+        assert e.value.code == -1
+    g.set_probe_grouping(1)
+    g.set_probe_grouping(1 << 30)
+    g.close()

@@ -39,7 +39,8 @@ def draw(seed):
 @pytest.mark.parametrize("seed", range(24))
 def test_random_model(seed):
     cfg, order, overlap = draw(seed)
-    run_parity(cfg, steps=4, order=order, overlap=overlap)
+    # every other draw with the probe grouping touched sets as it does for large batches
+    run_parity(cfg, steps=4, order=order, overlap=overlap, probe_min_windows=seed % 2)
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -51,7 +52,8 @@ def test_random_model_two_level(seed):
         cfg.tables[0].cache_slots = cfg.ways
     g = np.random.default_rng(seed)
     run_parity(cfg, steps=7, order=order, overlap=overlap, second_level_factor=int(g.choice([1, 2, 5])),
-               policy=str(g.choice(["lru", "lfu"])), pooling=str(g.choice(["sum", "mean", "max"])))
+               policy=str(g.choice(["lru", "lfu"])), pooling=str(g.choice(["sum", "mean", "max"])),
+               probe_min_windows=(seed + 1) % 2)
 
 
 def draw_options(seed):

@@ -37,6 +37,17 @@ def test_small_mixed_model_call_orders(order, overlap):
     run_parity(small_cfg(synth.FP16, 16, seed=77), steps=7, order=order, overlap=overlap)
 
 
+@pytest.mark.parametrize("second_level_factor", [0, 3])
+@pytest.mark.parametrize("policy", ["lru", "lfu"])
+@pytest.mark.parametrize("ways", [1, 8, 32, 64])
+def test_small_mixed_model_with_grouped_probe(ways, policy, second_level_factor):
+    """the probe taking several touched sets per wavefront (as it does by itself only for batches that touch
+    thousands of sets): windows that cross tables, contain the rows of the table without cache, sets with
+    more misses than ways next to sets with hits only"""
+    run_parity(small_cfg(synth.FP16, ways, seed=21 + ways), steps=6, order="ahead", policy=policy,
+               second_level_factor=second_level_factor, probe_min_windows=1)
+
+
 def test_ragged_sizes_span_tiles():
     # more lookups than one sort tile per block and a ragged tail; batch not a multiple of anything
     cfg = small_cfg(synth.FP32, 32, seed=5, batch=1531)
@@ -78,6 +89,30 @@ def test_small_model_exercises_every_path():
     tot = st["total"]
     assert tot["hits"] > 0 and tot["evictions"] > 0 and tot["bypasses"] > 0 and tot["inserts"] > tot["evictions"]
     assert st["h2d_bytes"] > 0 and st["d2h_bytes"] > 0
+
+
+@pytest.mark.parametrize("second_level_factor", [0, 2])
+@pytest.mark.parametrize("ways", [4, 32, 64])
+def test_sparse_sets_in_caches_as_large_as_the_tables(ways, second_level_factor):
+    """Caches with a slot for every row: a batch touches tens of thousands of sets with one or two rows each, so the
+    windows of sets that a wavefront of the probe takes are as long as they get, cross table boundaries, and meet the
+    rows of a table without cache and the sets of a cache of two sets in between.  Six steps: free ways filled,
+    hits, evictions and bypasses in the small cache, and with a second level rows pushed down and found again."""
+    T = synth.TableCfg
+    rows = 400_000  # enough touched sets that the probe groups them at all
+    full = (rows // ways + 1) * ways
+    tabs = [
+        T(rows, 32, synth.FP16, 1.05, "poisson", 10, 0, 60, cache_slots=full),
+        T(rows, 64, synth.FP16, None, "fixed", 7, cache_slots=full),
+        T(5000, 16, synth.FP16, 1.0, "fixed", 3, cache_slots=0),
+        T(rows, 32, synth.FP32, 1.1, "poisson", 12, 1, 80, cache_slots=2 * ways),
+        T(rows, 128, synth.FP16, 0.9, "poisson", 10, 0, 60, cache_slots=full),
+        T(rows, 8, synth.FP32, 1.2, "fixed", 5, cache_slots=rows // 7 // ways * ways),
+    ]
+    cfg = synth.WorkloadCfg("sparse_sets", tabs, batch=2048, ways=ways, steps=6, seed=77, init_std=0.05, lr=0.05)
+    st = run_parity(cfg, steps=6, order="ahead", second_level_factor=second_level_factor)
+    tot = st["total"]
+    assert tot["hits"] > 0 and tot["evictions"] > 0 and tot["bypasses"] > 0 and tot["inserts"] > 3 * tot["evictions"]
 
 
 def test_main_config_full_size():
