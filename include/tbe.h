@@ -52,7 +52,8 @@
  * pinned host memory between the two tiers (tbe_enable_second_level), initial values made up on
  * first read instead of stored (tbe_enable_deferred_init), a pipeline that fetches several batches
  * ahead (tbe_set_prefetch_depth), a host-side queue of batches in front of tbe_prefetch
- * (tbe_set_prefetch_queue), an emulated slower backing tier for measurements (tbe_set_backing_throttle).
+ * (tbe_set_prefetch_queue), an emulated slower backing tier for measurements (tbe_set_backing_throttle),
+ * one tuning value of the probe (tbe_set_probe_grouping; any time).
  */
 #ifndef TBE_H
 #define TBE_H
