@@ -677,7 +677,7 @@ int tbe_create(tbe_handle *out, const tbe_table_spec *specs, int32_t num_tables,
     CREATE_TRY(static_scratch_of_current_device(&p, &h->device));
     h->static_partials = (float *)p;
   }
-  CREATE_TRY(h->mem.get(&h->ss.hist, 4 * (256 * 1024 + 256)));
+  CREATE_TRY(h->mem.get(&h->ss.hist, 4 * (512 * 1024 + 512)));  // sort: counts per digit value (<= 512) and block (<= 1024), digit totals
   CREATE_TRY(h->mem.get(&h->ss.blk, 8 * (8192 + 1)));
   CREATE_TRY(h->mem.get(&h->ss.tally, 8 * 2 * 8192));
   CREATE_TRY(h->mem.get(&h->ss.wl, 4 * 4 * (size_t)kWorklistBlocks));

@@ -102,15 +102,14 @@ hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf 
 //               its keys with ballot matching (stable), the tile is ordered by digit in
 //               LDS and written out so that neighbouring lanes hit neighbouring addresses
 // --------------------------------------------------------------------------------------
-constexpr int kSortThreads = 256;
-constexpr int kSortItems = 16;
-constexpr int kSortTile = kSortThreads * kSortItems;  // 4096 keys
-constexpr int kRadix = 256;
+constexpr int kSortTile = 4096;        // keys of a tile
+constexpr int kMaxRadix = 512;         // a pass sorts by a digit of up to 9 bits; one thread per digit value
 constexpr int kMaxSortBlocks = 1024;
 
-__global__ __launch_bounds__(kSortThreads) void sort_upsweep_kernel(const uint32_t *__restrict__ keys, int n, int shift,
-                                                                    uint32_t mask, int chunk,
-                                                                    uint32_t *__restrict__ hist) {
+template <int RB>
+__global__ __launch_bounds__(1 << RB) void sort_upsweep_kernel(const uint32_t *__restrict__ keys, int n, int shift,
+                                                               uint32_t mask, int chunk, uint32_t *__restrict__ hist) {
+  constexpr int kRadix = 1 << RB, kSortThreads = kRadix;
   __shared__ uint32_t h[kRadix];
   const int tid = threadIdx.x;
   h[tid] = 0;
@@ -179,16 +178,19 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(uint32_t *hist, int nb, 
   if (tid == 255) digit_total[blockIdx.x] = wb + incl;
 }
 
-__global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
+template <int RB>
+__global__ __launch_bounds__(1 << RB) void sort_downsweep_kernel(
     const uint32_t *__restrict__ keys_in, const uint32_t *__restrict__ vals_in, uint32_t *__restrict__ keys_out,
     uint32_t *__restrict__ vals_out, int n, int shift, uint32_t mask, int chunk, const uint32_t *__restrict__ hist,
     const uint32_t *__restrict__ digit_total) {
+  constexpr int kRadix = 1 << RB, kSortThreads = kRadix, kWaves = kSortThreads / kWave;
+  constexpr int kSortItems = kSortTile / kSortThreads;  // 16 keys per thread and tile, 8 for the 9-bit digit
   __shared__ uint32_t s_keys[kSortTile];
   __shared__ uint32_t s_vals[kSortTile];
-  __shared__ uint32_t s_cnt[4][kRadix];  // per wave and digit: count, later exclusive prefix over waves
-  __shared__ uint32_t s_dstart[kRadix];  // first tile-sorted position of each digit
-  __shared__ uint32_t s_gbase[kRadix];   // next global output position of each digit for this block
-  __shared__ uint32_t s_wtot[4];
+  __shared__ uint32_t s_cnt[kWaves][kRadix];  // per wave and digit: count, later exclusive prefix over waves
+  __shared__ uint32_t s_dstart[kRadix];       // first tile-sorted position of each digit
+  __shared__ uint32_t s_gbase[kRadix];        // next global output position of each digit for this block
+  __shared__ uint32_t s_wtot[kWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   const int block_base = blockIdx.x * chunk;
@@ -209,7 +211,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
   }
 
   for (int tile = block_base; tile < block_end; tile += kSortTile) {
-    for (int w = 0; w < 4; w++) s_cnt[w][tid] = 0;
+    for (int w = 0; w < kWaves; w++) s_cnt[w][tid] = 0;
     __syncthreads();
     uint32_t key[kSortItems], val[kSortItems], rank[kSortItems];
     const int seg = tile + wave * (kWave * kSortItems);
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
       const uint32_t d = (key[q] >> shift) & mask;
       uint64_t peers = __ballot(valid);
 #pragma unroll
-      for (int bit = 0; bit < 8; bit++) {
+      for (int bit = 0; bit < RB; bit++) {
         const bool on = (d >> bit) & 1u;
         const uint64_t bal = __ballot(on);
         peers &= on ? bal : ~bal;
@@ -241,9 +243,13 @@ __global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
     }
     __syncthreads();
     // thread tid owns digit tid: totals, prefix over waves, start of the digit in the tile
-    uint32_t c0 = s_cnt[0][tid], c1 = s_cnt[1][tid], c2 = s_cnt[2][tid], c3 = s_cnt[3][tid];
-    const uint32_t total = c0 + c1 + c2 + c3;
-    s_cnt[0][tid] = 0; s_cnt[1][tid] = c0; s_cnt[2][tid] = c0 + c1; s_cnt[3][tid] = c0 + c1 + c2;
+    uint32_t total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; w++) {
+      const uint32_t c = s_cnt[w][tid];
+      s_cnt[w][tid] = total;
+      total += c;
+    }
     uint32_t incl = total;
     for (int dd = 1; dd < 64; dd <<= 1) {
       uint32_t o = __shfl_up(incl, dd);
@@ -286,25 +292,34 @@ __global__ __launch_bounds__(kSortThreads) void sort_downsweep_kernel(
 hipError_t launch_sort(const Geometry &g, SortScratch &ss, int64_t n, int *result_buf, hipStream_t s) {
   *result_buf = 0;
   if (n <= 1) return hipSuccess;
-  const int passes = (g.key_bits + 7) / 8;
-  const int bits = (g.key_bits + passes - 1) / passes;  // balanced digit width <= 8
+  // 8-bit digits, except that keys of 25 to 27 bits (32 tables of a million rows make 25) take three passes, some of
+  // them by a 9-bit digit, instead of four
+  const int passes = (g.key_bits >= 25 && g.key_bits <= 27) ? 3 : (g.key_bits + 7) / 8;
   const int64_t tiles = (n + kSortTile - 1) / kSortTile;
   const int blocks = (int)(tiles < kMaxSortBlocks ? tiles : kMaxSortBlocks);
   const int64_t tiles_per_block = (tiles + blocks - 1) / blocks;
   const int chunk = (int)(tiles_per_block * kSortTile);
   const int used_blocks = (int)((n + chunk - 1) / chunk);
-  int cur = 0;
+  int cur = 0, shift = 0;
+  uint32_t *digit_total = ss.hist + kMaxRadix * kMaxSortBlocks;
   for (int p = 0; p < passes; p++) {
-    const int shift = p * bits;
-    const int w = (g.key_bits - shift) < bits ? (g.key_bits - shift) : bits;
+    const int left = g.key_bits - shift;
+    const int w = (left + (passes - p) - 1) / (passes - p);  // balanced digit widths, the wider ones first
     const uint32_t mask = (1u << w) - 1u;
-    hipLaunchKernelGGL(sort_upsweep_kernel, dim3(used_blocks), dim3(kSortThreads), 0, s, ss.keys[cur], (int)n, shift,
-                       mask, chunk, ss.hist);
-    hipLaunchKernelGGL(sort_scan_kernel, dim3(kRadix), dim3(256), 0, s, ss.hist, used_blocks,
-                       ss.hist + kRadix * kMaxSortBlocks);
-    hipLaunchKernelGGL(sort_downsweep_kernel, dim3(used_blocks), dim3(kSortThreads), 0, s, ss.keys[cur], ss.vals[cur],
-                       ss.keys[cur ^ 1], ss.vals[cur ^ 1], (int)n, shift, mask, chunk, ss.hist,
-                       ss.hist + kRadix * kMaxSortBlocks);
+    if (w > 8) {
+      hipLaunchKernelGGL(sort_upsweep_kernel<9>, dim3(used_blocks), dim3(512), 0, s, ss.keys[cur], (int)n, shift, mask,
+                         chunk, ss.hist);
+      hipLaunchKernelGGL(sort_scan_kernel, dim3(512), dim3(256), 0, s, ss.hist, used_blocks, digit_total);
+      hipLaunchKernelGGL(sort_downsweep_kernel<9>, dim3(used_blocks), dim3(512), 0, s, ss.keys[cur], ss.vals[cur],
+                         ss.keys[cur ^ 1], ss.vals[cur ^ 1], (int)n, shift, mask, chunk, ss.hist, digit_total);
+    } else {
+      hipLaunchKernelGGL(sort_upsweep_kernel<8>, dim3(used_blocks), dim3(256), 0, s, ss.keys[cur], (int)n, shift, mask,
+                         chunk, ss.hist);
+      hipLaunchKernelGGL(sort_scan_kernel, dim3(256), dim3(256), 0, s, ss.hist, used_blocks, digit_total);
+      hipLaunchKernelGGL(sort_downsweep_kernel<8>, dim3(used_blocks), dim3(256), 0, s, ss.keys[cur], ss.vals[cur],
+                         ss.keys[cur ^ 1], ss.vals[cur ^ 1], (int)n, shift, mask, chunk, ss.hist, digit_total);
+    }
+    shift += w;
     cur ^= 1;
   }
   *result_buf = cur;

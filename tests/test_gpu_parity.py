@@ -137,6 +137,23 @@ def test_sort_payload_with_and_without_the_bag(max_batch):
     run_parity(small_cfg(synth.FP16, 8, seed=91), steps=4, order="ahead", max_batch=max_batch)
 
 
+@pytest.mark.parametrize("big_rows,key_bits", [(17_000_000, 25), (40_000_000, 26), (100_000_000, 27), (9_000_000, 24)])
+def test_sort_digit_widths_on_small_ragged_batches(big_rows, key_bits):
+    """The sort key has as many bits as the keys of all tables need; 25 to 27 bits are sorted in three passes with
+    9-bit digits among them, everything else by digits of up to 8 bits.  One table of narrow rows sets the key width
+    (its rows are spread over the whole range by uniform indices, so every digit value occurs), small ragged
+    batches: tiles that are not full, workgroups without keys."""
+    T = synth.TableCfg
+    tabs = [
+        T(big_rows, 4, synth.FP32, None, "poisson", 9, 0, 50, cache_slots=64 * 8),
+        T(3001, 64, synth.FP16, 1.2, "poisson", 20, 1, 100, cache_slots=13 * 8),
+        T(777, 128, synth.FP16, None, "fixed", 3, cache_slots=0),
+    ]
+    assert (sum(t.rows for t in tabs) - 1).bit_length() <= key_bits
+    cfg = synth.WorkloadCfg("wide_keys", tabs, batch=611, ways=8, steps=3, seed=300 + key_bits, init_std=0.05, lr=0.05)
+    run_parity(cfg, steps=3, order="ahead", init_device="cuda", touched_only=True)
+
+
 @pytest.mark.parametrize("second_level_factor", [0, 2, 5])
 @pytest.mark.parametrize("pooling", ["sum", "max"])
 def test_flush_between_steps_then_train_on(second_level_factor, pooling):
