@@ -190,14 +190,22 @@ __global__ void stream_pin_kernel() {}
 // Running totals of a batch's counters: tot (hits, evictions, lookups that hit), t64 ([0] distinct
 // rows, [1] inserts, [2] bypasses) and, with a second level, l2 (its four counters).
 // Also completes the batch's own counters: evictions and lookups that hit from the per-wavefront sums of the
-// status pass, hits as what is left of the distinct rows.  One wavefront.
-__global__ void add_totals_kernel(BatchCounters *c, BatchCounters *tot, unsigned long long *t64,
-                                  unsigned long long *l2, const unsigned long long *tally, int tally_waves) {
+// status pass (tens of thousands of them at the benchmark's batch: a single wavefront took 27 us to add them up),
+// hits as what is left of the distinct rows.  One workgroup of kTotalsThreads.
+constexpr int kTotalsThreads = 256;
+__global__ __launch_bounds__(kTotalsThreads) void add_totals_kernel(BatchCounters *c, BatchCounters *tot,
+                                                                    unsigned long long *t64, unsigned long long *l2,
+                                                                    const unsigned long long *tally, int tally_waves) {
   if (c->err != 0) return;
+  __shared__ unsigned long long s_e[kTotalsThreads / 64], s_l[kTotalsThreads / 64];
   unsigned long long e = 0, l = 0;
-  for (int w = threadIdx.x; w < tally_waves; w += 64) { e += tally[2 * w]; l += tally[2 * w + 1]; }
+  for (int w = threadIdx.x; w < tally_waves; w += kTotalsThreads) { e += tally[2 * w]; l += tally[2 * w + 1]; }
   for (int d = 32; d >= 1; d >>= 1) { e += __shfl_xor(e, d); l += __shfl_xor(l, d); }
+  if ((threadIdx.x & 63) == 0) { s_e[threadIdx.x >> 6] = e; s_l[threadIdx.x >> 6] = l; }
+  __syncthreads();
   if (threadIdx.x != 0) return;
+  e = l = 0;
+  for (int w = 0; w < kTotalsThreads / 64; w++) { e += s_e[w]; l += s_l[w]; }
   c->hits = (unsigned long long)(c->n_uniq - c->n_ins - c->n_byp);
   c->evictions = e;
   c->hit_lookups = l;
@@ -336,7 +344,7 @@ int do_prefetch_deep(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offs
                                   h->policy == TBE_POLICY_LFU, h->l2, h->deep, h->as));
     const BatchBuf *prev = h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr;
     HIP_TRY(h, launch_classify_mark_deep(h->d_tm, prev, b, bi, h->st, h->d_bytes + 5, h->as));
-    hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total, h->d_bytes + 2,
+    hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(kTotalsThreads), 0, h->as, b.cnt, h->d_total, h->d_bytes + 2,
                        (unsigned long long *)nullptr, h->ss.tally, n > 0 ? h->ss.tally_waves : 0);
     HIP_TRY(h, hipGetLastError());
   }
@@ -408,7 +416,7 @@ int do_prefetch(tbe_ctx *h, const int64_t *d_indices, const int64_t *d_offsets, 
     const BatchBuf *prev = h->prev_buf >= 0 ? &h->buf[h->prev_buf] : nullptr;
     const BatchBuf *pp = (prev && prev->parks_prev && prev->prev_bi >= 0) ? &h->buf[prev->prev_bi] : nullptr;
     HIP_TRY(h, launch_classify_mark(h->d_tm, pp, prev, b, h->st, h->l2, h->d_bytes + 5, h->as));
-    hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(64), 0, h->as, b.cnt, h->d_total, h->d_bytes + 2,
+    hipLaunchKernelGGL(add_totals_kernel, dim3(1), dim3(kTotalsThreads), 0, h->as, b.cnt, h->d_total, h->d_bytes + 2,
                        h->l2.on ? h->d_l2tot : nullptr, h->ss.tally, n > 0 ? h->ss.tally_waves : 0);
     HIP_TRY(h, hipGetLastError());
   }

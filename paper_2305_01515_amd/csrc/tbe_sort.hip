@@ -95,7 +95,7 @@ hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf 
 }
 
 // --------------------------------------------------------------------------------------
-// LSD radix sort, 8-bit digits, three kernels per pass:
+// LSD radix sort, digits of up to 8 bits (9 where that saves a pass), three kernels per pass:
 //   upsweep   : per-block digit histogram of the block's contiguous chunk
 //   scan      : per digit, exclusive scan of its counts over the blocks, and digit totals
 //   downsweep : the block walks its chunk tile by tile; inside a tile every wave ranks
@@ -105,6 +105,7 @@ hipError_t launch_keygen(const TableMeta *tm, const Geometry &g, const BatchBuf 
 constexpr int kSortTile = 4096;        // keys of a tile
 constexpr int kMaxRadix = 512;         // a pass sorts by a digit of up to 9 bits; one thread per digit value
 constexpr int kMaxSortBlocks = 1024;
+constexpr int kUpsweepKeys = 4;  // keys a thread of the counting pass has in flight (8 and 16: no faster)
 
 template <int RB>
 __global__ __launch_bounds__(1 << RB) void sort_upsweep_kernel(const uint32_t *__restrict__ keys, int n, int shift,
@@ -116,18 +117,18 @@ __global__ __launch_bounds__(1 << RB) void sort_upsweep_kernel(const uint32_t *_
   __syncthreads();
   const int base = blockIdx.x * chunk;
   const int end = min(n, base + chunk);
-  // Four keys per thread and step, their loads in flight together.  After the first pass equal keys lie side
+  // Several keys per thread and step, their loads in flight together.  After the first pass equal keys lie side
   // by side, and a power-law batch has keys with thousands of copies: a wavefront whose 64 keys share one digit
   // adds them with one atomic instead of 64 to the same LDS word.
-  for (int i0 = base; i0 < end; i0 += 4 * kSortThreads) {
-    uint32_t k[4];
+  for (int i0 = base; i0 < end; i0 += kUpsweepKeys * kSortThreads) {
+    uint32_t k[kUpsweepKeys];
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
+    for (int q = 0; q < kUpsweepKeys; q++) {
       const int i = i0 + q * kSortThreads + tid;
       k[q] = i < end ? keys[i] : 0u;
     }
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
+    for (int q = 0; q < kUpsweepKeys; q++) {
       const bool valid = i0 + q * kSortThreads + tid < end;
       const uint32_t d = valid ? (k[q] >> shift) & mask : 0xFFFFFFFFu;
       const uint32_t d0 = __shfl(d, 0, 64);
