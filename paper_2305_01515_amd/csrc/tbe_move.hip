@@ -552,9 +552,12 @@ __global__ __launch_bounds__(256) void commit_kernel(const TableMeta *__restrict
       m_fresh = m.dev_m[row_of_key(m, ins_key[i])];
     }
     for (uint32_t c = lig * 16; c < rb; c += kMoveLanes * 16) {
-      const uint4 fresh = *(const uint4 *)(src + c);
-      if (old >= 0) *(uint4 *)(park + c) = *(const uint4 *)(line + c);
-      *(uint4 *)(line + c) = fresh;
+      // The staged row and the parked victim pass through once: read and written around the caches, so that
+      // the forward that follows does not start behind half a gigabyte of dirty lines (commit 0.274 -> 0.253 ms,
+      // the forward after it 0.198 -> 0.186 ms).  The line itself is about to be read: it is stored as usual.
+      const mv_u32x4 fresh = __builtin_nontemporal_load((const mv_u32x4 *)(src + c));
+      if (old >= 0) __builtin_nontemporal_store(*(const mv_u32x4 *)(line + c), (mv_u32x4 *)(park + c));
+      *(mv_u32x4 *)(line + c) = fresh;
     }
     if (lig == 0) {
       st.wb_dst[i] = old < 0 ? nullptr : ins_dst ? ins_dst[i] : m.host_w + (size_t)old * rb;
