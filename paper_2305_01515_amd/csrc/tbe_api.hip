@@ -829,22 +829,30 @@ static int backward_update_with(tbe_ctx *h, const float *d_grad_out, float lr, f
   // backward 0.51 ms instead of 0.48, and 0.72 instead of 0.65 ms beside the other streams' work.)
   {
     StageTimer all_(h, TBE_STAGE_BACKWARD, h->cs);
-    {
-      StageTimer tm_(h, TBE_STAGE_BACKWARD_HEAVY, h->cs);
-      HIP_TRY(h, launch_backward_classes(kBwdHeavy, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
-    }
-    {
+    auto heavy = [&]() -> int {
+      {
+        StageTimer tm_(h, TBE_STAGE_BACKWARD_HEAVY, h->cs);
+        HIP_TRY(h, launch_backward_classes(kBwdHeavy, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
+      }
       StageTimer tm_(h, TBE_STAGE_BACKWARD_COMBINE, h->cs);
       HIP_TRY(h, launch_backward_classes(kBwdCombine, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
-    }
-    {
+      return TBE_OK;
+    };
+    auto single = [&]() -> int {
       StageTimer tm_(h, TBE_STAGE_BACKWARD_SINGLE, h->cs);
       HIP_TRY(h, launch_backward_single_classes(h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, lr, eps, h->cs));
-    }
-    {
+      return TBE_OK;
+    };
+    auto shortk = [&]() -> int {
       StageTimer tm_(h, TBE_STAGE_BACKWARD_SHORT, h->cs);
       HIP_TRY(h, launch_backward_classes(kBwdShort, h->d_tm, h->ci, h->g, h->buf[bi], d_grad_out, partials, lr, eps, h->cs));
-    }
+      return TBE_OK;
+    };
+    // single-lookup rows first, the heavy rows' tile kernel last: 0.471 ms alone against 0.479 with the tile kernel
+    // first (it takes 0.124 instead of 0.134 ms when it does not follow the forward), 0.627 against 0.635 ms beside
+    // the other streams; the other orders lie between
+    int rc;
+    if ((rc = single()) || (rc = shortk()) || (rc = heavy())) return rc;
   }
   h->current = -1;
   if (h->as != h->cs) {
