@@ -602,6 +602,7 @@ __device__ inline int32_t add_saturating(int32_t a, int32_t b) {  // a, b >= 0
 #define TBE_PROBE_SETS 8
 #endif
 constexpr int kProbeSets = TBE_PROBE_SETS;       // sets of one window, at most
+static_assert(TBE_PROBE_SETS >= 2 && TBE_PROBE_SETS <= 32, "a window's sets with a miss are a 32-bit mask; 32 ways per set of room make a set of 64 ways fit");
 constexpr int kProbeWays = 32 * TBE_PROBE_SETS;  // ways of one window, at most (>= kWave, so that a window holds a set at least)
 #ifndef TBE_PROBE_ROWS
 #define TBE_PROBE_ROWS 64        // distinct rows a window aims for
