@@ -17,8 +17,10 @@ namespace tbe {
 // --------------------------------------------------------------------------------------
 constexpr int kScanThreads = 256;
 constexpr int kScanWavesPerBlock = kScanThreads / kWave;
-constexpr int kScanItems = 4;                    // consecutive elements per lane and step
-constexpr int kScanStep = kWave * kScanItems;    // elements per wavefront and step
+// Consecutive elements per lane and step: Op::kItems.  With several, the lanes of one store instruction write
+// compacted entries that lie apart (the entries of a lane's other elements fall between them), and the emit pass
+// that flags a third of its elements and writes seven arrays wrote 121 MB for 32 MB of lists (49 us; 38 MB and
+// 34 us with one element per lane); the passes that flag nearly every element or nearly none are faster with four.
 #ifndef TBE_SCAN_BLOCKS
 #define TBE_SCAN_BLOCKS 1024
 #endif
@@ -40,10 +42,10 @@ __device__ inline u64 wave_total(u64 v) {
 }
 
 // elements per wavefront: n spread over all wavefronts of the grid, in whole steps
-__device__ inline int scan_chunk(int n, int nblocks) {
+__device__ inline int scan_chunk(int n, int nblocks, int step) {
   const int waves = nblocks * kScanWavesPerBlock;
-  const int steps = (n + kScanStep - 1) / kScanStep;
-  return (steps + waves - 1) / waves * kScanStep;
+  const int steps = (n + step - 1) / step;
+  return (steps + waves - 1) / waves * step;
 }
 
 // blk: [0, nblocks) sums per workgroup; [nblocks, nblocks * 5) sums per wavefront
@@ -52,8 +54,9 @@ __global__ __launch_bounds__(kScanThreads) void compact_count_kernel(Op op, cons
                                                                      u64 *blk, const BatchCounters *cnt) {
   __shared__ u64 wsum[kScanWavesPerBlock];
   if (cnt->err) return;
+  constexpr int kScanItems = Op::kItems, kScanStep = kWave * kScanItems;
   const int n = n_ptr ? *n_ptr : n_fixed;
-  const int chunk = scan_chunk(n, gridDim.x);
+  const int chunk = scan_chunk(n, gridDim.x, kScanStep);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int w = blockIdx.x * kScanWavesPerBlock + wave;
   const int64_t base64 = (int64_t)w * chunk;
@@ -104,8 +107,9 @@ __global__ __launch_bounds__(kScanThreads) void compact_emit_kernel(Op op, const
   __shared__ TableLut s_lut;
   if (cnt->err) return;
   if (op.prepare(s_lut)) __syncthreads();
+  constexpr int kScanItems = Op::kItems, kScanStep = kWave * kScanItems;
   const int n = n_ptr ? *n_ptr : n_fixed;
-  const int chunk = scan_chunk(n, gridDim.x);
+  const int chunk = scan_chunk(n, gridDim.x, kScanStep);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int w = blockIdx.x * kScanWavesPerBlock + wave;
   const int64_t base64 = (int64_t)w * chunk;
@@ -145,7 +149,7 @@ __global__ __launch_bounds__(kScanThreads) void compact_emit_kernel(Op op, const
 template <class Op>
 static int run_compaction(Op op, const int32_t *n_ptr, int n_fixed, int n_bound, u64 *blk, BatchCounters *cnt,
                            hipStream_t s) {
-  int nb = (n_bound + kScanThreads * kScanItems - 1) / (kScanThreads * kScanItems);
+  int nb = (n_bound + kScanThreads * Op::kItems - 1) / (kScanThreads * Op::kItems);
   if (nb > kScanBlocks) nb = kScanBlocks;
   if (nb < 1) nb = 1;
   hipLaunchKernelGGL(compact_count_kernel<Op>, dim3(nb), dim3(kScanThreads), 0, s, op, n_ptr, n_fixed, blk, cnt);
@@ -155,6 +159,7 @@ static int run_compaction(Op op, const int32_t *n_ptr, int n_fixed, int n_bound,
 
 // ---- pass 1 over the N sorted lookups: distinct rows, run starts, set ids ----
 struct DedupOp {
+  static constexpr int kItems = 2;
   const TableMeta *tm;
   int T;
   const uint32_t *key;      // sorted
@@ -214,6 +219,7 @@ struct DedupOp {
 
 // ---- pass 2 over the distinct rows: first row of every touched set; long runs ----
 struct SetHeadOp {
+  static constexpr int kItems = 4;
   const uint32_t *uniq_sid;
   const int32_t *run_off;
   uint2 *touched;
@@ -459,6 +465,7 @@ __global__ __launch_bounds__(256) void heavy_starts_kernel(const TableMeta *__re
 
 // ---- pass 3 over the distinct rows after the probe: insert and bypass lists, counters ----
 struct StatusOp {
+  static constexpr int kItems = 1;
   const TableMeta *tm;
   int T;
   const uint8_t *status;
