@@ -254,6 +254,8 @@ int alloc_batchbuf(tbe_ctx *h, BatchBuf &b, int64_t n) {
   HIP_TRY(h, h->mem.get(&b.mid_idx, 4 * (N / 2 + 1)));
   HIP_TRY(h, h->mem.get(&b.heavy, 4 * (N / 32 + 1)));  // rows: N / 65 at most; extra parts: N / kHeavySplit at most
   HIP_TRY(h, h->mem.get(&b.heavy_sub, 4 * (N / 32 + 1)));
+  HIP_TRY(h, h->mem.get(&b.harrive, 4 * (N / 32 + 1)));
+  HIP_TRY(h, hipMemset(b.harrive, 0, 4 * (N / 32 + 1)));
   HIP_TRY(h, h->mem.get(&b.hchunks, 16 * (N / 32 + (size_t)h->g.T + 1)));
   HIP_TRY(h, h->mem.get(&b.hg_count, 4 * 2 * ((size_t)h->g.T + 1)));
   HIP_TRY(h, hipMemset(b.hg_count, 0, 4 * 2 * ((size_t)h->g.T + 1)));

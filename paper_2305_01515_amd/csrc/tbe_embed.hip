@@ -941,14 +941,18 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
 // Heavy rows: add the partial sums, then update the row.  One lane group per row; the sums of a row's
 // parts and bag ranges lie one behind the other and are added in that order (a fixed order, so the result
 // is reproducible), four loads in flight.
+// sums of one row from which its parts are added up side by side (128: the hot rows of a heterogeneous model pay
+// for the fences beside the other streams, its backward 4.6 -> 5.0 ms; 2048: a chain of 2047 sums takes 0.2 ms)
+constexpr int kCombineChain = 512;
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int cls,
                                                                const int32_t *__restrict__ heavy,
                                                                const int32_t *__restrict__ heavy_sub,
+                                                               int32_t *harrive,
                                                                const uint32_t *__restrict__ uniq_key,
                                                                const int32_t *__restrict__ uniq_tab,
                                                                const int32_t *__restrict__ loc_u,
-                                                               const float *__restrict__ partials, int pstride,
+                                                               float *partials, int pstride,
                                                                float lr, float eps, char *__restrict__ ovf,
                                                                uint32_t ovf_stride,
                                                                const int32_t *__restrict__ table_class,
@@ -962,9 +966,20 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
   int first, end, step;
   xcd_span(n_heavy, NG, first, end, step);  // the list is in table order
   for (int h = first + grp; h < end; h += step) {
+    // A row entered once, or a few times, is added up by the lane group of its first entry: parts x R sums in
+    // the slots h * R onwards.  For a row with a third of a million lookups that is a chain of 170 parts x 208
+    // ranges in one lane group (half a millisecond), so from kCombineChain sums on the work is shared: every part
+    // adds up its own R sums, leaves the result in its first slot and counts itself in, and the lane group that
+    // finds all the others in adds the parts' sums -- in the order of the parts, whoever it is -- and updates the
+    // row.  (The fences this takes write back an XCD's whole L2 each: with them on every row entered twice the
+    // benchmark workload's combine took 0.052 instead of 0.019 ms alone and 0.15 instead of 0.03 ms beside the
+    // other streams' kernels.  One table, Zipf 1.4, a million lookups: combine 0.53 -> 0.06 ms.)
     const int sub = heavy_sub[h];
-    if (sub & 0xFFFF) continue;  // the entries of a row's parts follow its first one: their sums are added here
-    const int n_sums = (sub >> 16) * R;  // (part, range) pairs in order: slot (h + part) * R + range = h * R + r
+    const int part = sub & 0xFFFF, parts = sub >> 16;
+    const bool shared = parts > 1 && parts * R >= kCombineChain;
+    if (part && !shared) continue;
+    const int hf = h - part;
+    const int n_sums = shared ? R : parts * R;
     const int u = heavy[h];
     const int t = uniq_tab[u];
     if (table_class[t] != cls) continue;
@@ -973,7 +988,7 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
     float g[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
-    const float *p0 = partials + (size_t)h * R * pstride + lig * EPL;
+    float *p0 = partials + (size_t)h * R * pstride + lig * EPL;
     for (int r = 0; r < n_sums; r += 4) {
       float4 v[4][EPL / 4];
 #pragma unroll
@@ -986,6 +1001,26 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
 #pragma unroll
         for (int e = 0; e < EPL / 4; e++) {
           g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
+        }
+    }
+    if (shared) {
+#pragma unroll
+      for (int e = 0; e < EPL / 4; e++) *(float4 *)(p0 + 4 * e) = make_float4(g[4 * e], g[4 * e + 1], g[4 * e + 2], g[4 * e + 3]);
+      __threadfence();  // the sum is out before this part is counted in
+      int before = 0;
+      if (lig == 0) before = atomicAdd(harrive + hf, 1);
+      before = __shfl(before, 0, G);
+      if (before != parts - 1) continue;
+      if (lig == 0) harrive[hf] = 0;  // as the next batch expects it
+      __threadfence();  // the other parts' sums are read after the count was seen
+#pragma unroll
+      for (int e = 0; e < EPL; e++) g[e] = 0.f;
+      const float *q0 = partials + (size_t)hf * R * pstride + lig * EPL;
+      for (int q = 0; q < parts; q++)
+#pragma unroll
+        for (int e = 0; e < EPL / 4; e++) {
+          const float4 v = *(const float4 *)(q0 + (size_t)q * R * pstride + 4 * e);
+          g[4 * e] += v.x; g[4 * e + 1] += v.y; g[4 * e + 2] += v.z; g[4 * e + 3] += v.w;
         }
     }
     update_row<DT, G>(m, uniq_key[u], loc_u[u], ovf, ovf_stride, g, lr, eps, lig, active);
@@ -1028,8 +1063,9 @@ static void bwd_one(int which, const TableMeta *tm, int cls, const int32_t *tabl
                        b.mean ? b.inv_len : nullptr, b.argpos, b.sorted_within, b.cnt);
   } else if (which == kBwdCombine) {
     if (tiled)
-      hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(2048), dim3(256), 0, s, tm, cls, b.heavy, b.heavy_sub, b.uniq_key,
-                         b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class, b.cnt);
+      hipLaunchKernelGGL((backward_combine_kernel<DT, G>), dim3(2048), dim3(256), 0, s, tm, cls, b.heavy, b.heavy_sub, b.harrive,
+                         b.uniq_key, b.uniq_tab, b.loc_u, partials, g.partial_stride, lr, eps, b.ovf, g.ovf_stride, table_class,
+                         b.cnt);
   } else {
     auto kern = b.maxp ? backward_short_kernel<DT, G, kMax>
                 : b.mean ? backward_short_kernel<DT, G, kMean> : backward_short_kernel<DT, G, kSum>;

@@ -160,6 +160,7 @@ struct BatchBuf {
   int32_t *mid_idx;     // [N/2 + 1] rows with 2..kLongRun lookups, in the order of the distinct rows (table order)
   int32_t *heavy;       // [N/32 + 1] rows with more lookups, same order, one entry per part of a row (heavy_parts)
   int32_t *heavy_sub;   // [N/32 + 1] per entry: part number | parts << 16
+  int32_t *harrive;     // [N/32 + 1] per entry list position of a row's first part: parts whose sums are in (0 between batches)
   uint4 *hchunks;       // [N/kLongRun + T + 1] (table, first position in `heavy`, count, -)
   int32_t *hg_count;    // [2 * (T + 1)] heavy-list entries per table, then the position of each table's first entry
   int32_t *hperm;       // [N/32 + 1] the heavy list's positions, every table's entries ordered by lookups per entry
