@@ -115,6 +115,23 @@ def test_sparse_sets_in_caches_as_large_as_the_tables(ways, second_level_factor)
     assert tot["hits"] > 0 and tot["evictions"] > 0 and tot["bypasses"] > 0 and tot["inserts"] > 3 * tot["evictions"]
 
 
+@pytest.mark.parametrize("dtype,dim", [(synth.FP32, 128), (synth.FP16, 64), (synth.FP16, 256)])
+@pytest.mark.parametrize("pooling", ["sum", "mean"])
+def test_rows_with_a_large_share_of_all_lookups(dtype, dim, pooling):
+    """Zipf 1.4 over a single table: one row takes a third of the batch's quarter of a million lookups and a dozen
+    more take thousands each.  Such rows enter the heavy rows' kernel in parts of 2048 lookups, and from 512 partial
+    sums on their parts are added up side by side, the last part in finishing the row (arrival counters, which must
+    be back at zero for the next batch: six steps); a second, ordinary table runs along."""
+    T = synth.TableCfg
+    tabs = [
+        T(200_000, dim, dtype, 1.4, "fixed", 64, cache_slots=32 * 400),
+        T(3001, 64, synth.FP16, 1.2, "poisson", 20, 1, 100, cache_slots=32 * 13),
+    ]
+    cfg = synth.WorkloadCfg("hot_rows", tabs, batch=4096, ways=32, steps=6, seed=500 + dim, init_std=0.05, lr=0.05)
+    st = run_parity(cfg, steps=6, order="ahead", pooling=pooling)
+    assert st["total"]["hits"] > 0 and st["total"]["inserts"] > 0
+
+
 def test_main_config_full_size():
     """The benchmark's workload at full size (32 tables x 1M rows x dim 128 fp16, batch
     8192), prefetch issued ahead as bench.py does; 12 steps, every pooled output compared, the cache
