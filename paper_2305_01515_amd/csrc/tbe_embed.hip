@@ -944,6 +944,7 @@ __global__ __launch_bounds__(kHeavyThreads) void backward_heavy_kernel(const Tab
 // sums of one row from which its parts are added up side by side (128: the hot rows of a heterogeneous model pay
 // for the fences beside the other streams, its backward 4.6 -> 5.0 ms; 2048: a chain of 2047 sums takes 0.2 ms)
 constexpr int kCombineChain = 512;
+constexpr int kCombineLoads = 8;  // partial sums a lane group has in flight (4: a chain of 500 sums 0.059 ms, 8: 0.049 ms)
 template <int DT, int G>
 __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *__restrict__ tm, int cls,
                                                                const int32_t *__restrict__ heavy,
@@ -989,15 +990,15 @@ __global__ __launch_bounds__(256) void backward_combine_kernel(const TableMeta *
 #pragma unroll
     for (int e = 0; e < EPL; e++) g[e] = 0.f;
     float *p0 = partials + (size_t)h * R * pstride + lig * EPL;
-    for (int r = 0; r < n_sums; r += 4) {
-      float4 v[4][EPL / 4];
+    for (int r = 0; r < n_sums; r += kCombineLoads) {
+      float4 v[kCombineLoads][EPL / 4];
 #pragma unroll
-      for (int x = 0; x < 4; x++)
+      for (int x = 0; x < kCombineLoads; x++)
 #pragma unroll
         for (int e = 0; e < EPL / 4; e++)
           v[x][e] = r + x < n_sums ? *(const float4 *)(p0 + (size_t)(r + x) * pstride + 4 * e) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int x = 0; x < 4; x++)
+      for (int x = 0; x < kCombineLoads; x++)
 #pragma unroll
         for (int e = 0; e < EPL / 4; e++) {
           g[4 * e] += v[x][e].x; g[4 * e + 1] += v[x][e].y; g[4 * e + 2] += v[x][e].z; g[4 * e + 3] += v[x][e].w;
